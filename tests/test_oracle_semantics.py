@@ -1,0 +1,305 @@
+"""Pins of what the oracle decides: 'token allowed' == 'text stays a prefix of a sentence',
+'EOS allowed' == 'text is a sentence' (paper Sec. 1 mask semantics; App. A.2 parse loop)."""
+import itertools
+import json
+import random
+import re
+
+import numpy as np
+import pytest
+
+from cfg_brute import languages
+from oracle import Oracle, apply_mask
+from workloads import grammars as G
+from workloads.vocab import BASE_SEED, Vocab, arithmetic_vocab, bf16_logits, bpe_like_vocab
+
+N = 8
+
+
+def _stack_after(o, text):
+    rc, st = o.advance(o.initial_stack(), text.encode()) if text else (0, o.initial_stack())
+    return rc, st
+
+
+@pytest.mark.parametrize("name,alphabet,max_tok", [
+    ("ARITHMETIC", "a+*()b", 3), ("DYCK", "()x", 3), ("ANBN", "abx", 3),
+    ("RIGHT_LIST", "x,y", 3), ("EPSILON_MIX", "abcx", 3), ("RIGHT_LINEAR", "abcd", 3),
+    ("DRAGON_CC", "cdx", 3),
+])
+def test_brute_force_all_strings_up_to_8(name, alphabet, max_tok):
+    """Every string of length <= 8 over the grammar's alphabet plus one foreign byte: the set of
+    sentences and the set of viable prefixes come from an LR-free set-of-strings fixpoint on
+    the raw productions.  For every viable prefix p and every token t with |p.t| <= 8 the
+    oracle must allow t exactly when p.t is again a viable prefix, and must allow EOS exactly
+    when p is a sentence."""
+    text = getattr(G, name)
+    o = Oracle(text)
+    sentences, viable = languages(text, N)
+    assert len(sentences) > 3
+    tokens = ["".join(t) for k in range(1, max_tok + 1) for t in itertools.product(alphabet, repeat=k)]
+    n_checked = 0
+    for p in sorted(viable):
+        rc, st = _stack_after(o, p)
+        assert rc == 0, p
+        assert o.eos_allowed(st) == (p in sentences), p
+        for t in tokens:
+            if len(p) + len(t) > N:
+                continue
+            assert o.allowed(st, t.encode()) == ((p + t) in viable), (p, t)
+            n_checked += 1
+    assert n_checked > 200
+    # strings that are not viable cannot be advanced by at all
+    for k in range(1, 5):
+        for w in itertools.product(alphabet, repeat=k):
+            w = "".join(w)
+            assert (_stack_after(o, w)[0] == 0) == (w in viable), w
+
+
+def test_dyck_equals_counter():
+    o = Oracle(G.DYCK)
+    rnd = random.Random(1)
+    for _ in range(3000):
+        n = rnd.randint(0, 40)
+        w = "".join(rnd.choice("()") if rnd.random() < 0.97 else "x" for _ in range(n))
+        depth, viable = 0, True
+        for ch in w:
+            depth += {"(": 1, ")": -1}.get(ch, -10 ** 6)
+            if depth < 0:
+                viable = False
+                break
+        rc, st = _stack_after(o, w)
+        assert (rc == 0) == viable, w
+        if viable:
+            assert o.eos_allowed(st) == (depth == 0), w
+            # S -> eps | S ( S ): every open level holds the two states of "S (" above s0; a
+            # text ending in ')' still carries the unreduced "S ( S )" of the last group
+            # (reductions wait for the next lookahead)
+            expect = 1 if not w else (1 + 2 * depth if w[-1] == "(" else 5 + 2 * depth)
+            assert len(st) == expect, w
+
+
+def test_right_linear_equals_regex():
+    o = Oracle(G.RIGHT_LINEAR)
+    full, pre = re.compile(r"(ab|c)*d"), re.compile(r"(ab|c)*(a|d|ab|)")
+    for k in range(0, 9):
+        for w in itertools.product("abcd", repeat=k):
+            w = "".join(w)
+            rc, st = _stack_after(o, w)
+            is_prefix = bool(re.fullmatch(r"(ab|c)*(a|d)?", w))
+            assert (rc == 0) == is_prefix, w
+            if rc == 0:
+                assert o.eos_allowed(st) == bool(full.fullmatch(w)), w
+
+
+# ---------------------------------------------------------------- JSON vs the json module
+
+def _random_json(rnd, depth=0):
+    r = rnd.random()
+    if depth > 3 or r < 0.35:
+        k = rnd.randrange(7)
+        if k == 0:
+            return rnd.randint(-10 ** 6, 10 ** 6)
+        if k == 1:
+            return rnd.choice([0.5, -1.25e-7, 3e20, 1.0, -0.0, 12345.678])
+        if k == 2:
+            return rnd.choice([True, False, None])
+        return "".join(rnd.choice('ab z"\\/\b\f\n\r\t{}[]:,0eé中\x7f') for _ in range(rnd.randint(0, 8)))
+    if r < 0.7:
+        return [_random_json(rnd, depth + 1) for _ in range(rnd.randint(0, 4))]
+    return {"k%d" % i + rnd.choice(["", '"', "\\"]): _random_json(rnd, depth + 1) for i in range(rnd.randint(0, 4))}
+
+
+def _json_ok(data: bytes) -> bool:
+    def refuse(_):
+        raise ValueError("non-standard constant")
+    try:
+        json.loads(data.decode("ascii"), parse_constant=refuse)
+        return True
+    except (ValueError, RecursionError):
+        return False
+
+
+def test_json_grammar_equals_json_module(json_oracle):
+    """Membership in the byte-level JSON grammar == json.loads succeeds, on documents written
+    by json.dumps in several layouts and on random one-byte corruptions of them (ASCII only,
+    non-standard constants refused)."""
+    o, rnd = json_oracle, random.Random(7)
+    n_bad = n_good = 0
+    for i in range(400):
+        doc = _random_json(rnd)
+        style = i % 4
+        text = json.dumps(doc, ensure_ascii=True,
+                          indent=[None, 1, None, "\t"][style],
+                          separators=[(",", ":"), (", ", ": "), (" , ", " : "), None][style])
+        data = text.encode("ascii")
+        if i % 5 == 0:
+            data = b" \n" + data + b"\r\n\t "
+        assert _json_ok(data)
+        assert o.accepts(data), data
+        for _ in range(12):
+            pos = rnd.randrange(len(data))
+            kind = rnd.randrange(3)
+            if kind == 0:
+                mut = data[:pos] + bytes([rnd.choice(b'"\\{}[]:,0123456789.eE+-tfn u\n\x01\x7fax')]) + data[pos + 1:]
+            elif kind == 1:
+                mut = data[:pos] + data[pos + 1:]
+            else:
+                mut = data[:pos] + bytes([rnd.choice(b'"\\{}[]:,01.e-t ')]) + data[pos:]
+            expect = _json_ok(mut)
+            assert o.accepts(mut) == expect, mut
+            n_good += expect
+            n_bad += not expect
+    assert n_good > 300 and n_bad > 1500
+
+
+@pytest.mark.parametrize("text,ok", [
+    (b"0", True), (b"-0", True), (b"01", False), (b"-", False), (b"1.", False), (b".5", False),
+    (b"1e5", True), (b"1E+5", True), (b"1e", False), (b"1.5e-3", True), (b"--1", False),
+    (b'"\\u12aF"', True), (b'"\\u12G4"', False), (b'"\\x"', False), (b'"\t"', False),
+    (b'"\x7f\x80\xff"', True), (b"[]", True), (b"[,]", False), (b"[1,]", False), (b"{}", True),
+    (b'{"a"}', False), (b'{"a":1,}', False), (b'{1:2}', False), (b"tru", False), (b"true", True),
+    (b"nullx", False), (b"", False), (b"  ", False), (b"1 2", False), (b"[1 2]", False),
+    (b'{"a":{"b":[{},[[]],""]}}', True), (b"[" * 40 + b"]" * 40, True), (b"[" * 5 + b"]" * 4, False),
+])
+def test_json_special_cases(json_oracle, text, ok):
+    assert json_oracle.accepts(text) == ok
+
+
+# ------------------------------------------------------------------------ invariants
+
+@pytest.fixture(scope="module")
+def json_vocab():
+    return bpe_like_vocab(4000, 12, BASE_SEED + 99)
+
+
+def _bits(row, n):
+    return ((row[np.arange(n) >> 5] >> (np.arange(n) & 31)) & 1).astype(bool)
+
+
+def test_invariants_on_json_walks(json_oracle, json_vocab):
+    """I1 prefix closure, I2 concatenation, I3 EOS == sentence, I4 liveness, I5 token advance ==
+    byte-by-byte advance, I6 stack shape - along seeded random walks."""
+    o, v, rnd = json_oracle, json_vocab, random.Random(3)
+    by_text = {}
+    for t, tok in enumerate(v.tokens):
+        by_text.setdefault(tok, []).append(t)
+    for walk in range(12):
+        st, text = o.initial_stack(), b""
+        for step in range(40):
+            row = o.mask_row(st, v)
+            bits = _bits(row, v.n_tokens)
+            assert not (row[-1] >> (v.n_tokens & 31 or 32)) if v.n_tokens & 31 else True   # padding is 0
+            assert bits[v.eos_id] == o.eos_allowed(st) == o.accepts(text)               # I3
+            assert bits[:256].any()                                                     # I4
+            allowed = np.flatnonzero(bits)
+            allowed = allowed[allowed != v.eos_id]
+            # equal strings get equal bits; I1: every prefix that is itself a token is allowed
+            for t in rnd.sample(list(allowed), min(25, len(allowed))):
+                tok = v.tokens[t]
+                assert all(bits[u] for u in by_text[tok])
+                for k in range(1, len(tok)):
+                    for u in by_text.get(tok[:k], []):
+                        assert bits[u], (tok, tok[:k])
+            t = int(rnd.choice(list(allowed)))
+            tok = v.tokens[t]
+            rc, new = o.advance(st, tok)
+            assert rc == 0
+            step_st = st                                                                # I5
+            for c in tok:
+                rc1, step_st = o.advance(step_st, bytes([c]))
+                assert rc1 == 0
+            assert step_st == new
+            assert new[0] == o.initial_state() and all(0 <= s < o.n_states() for s in new)  # I6
+            # I2: after advancing by u, v is allowed iff u.v was viable from the old stack
+            new_bits = _bits(o.mask_row(new, v), v.n_tokens)
+            for u in rnd.sample(range(v.n_tokens - 1), 60):
+                assert new_bits[u] == o.allowed(st, tok + v.tokens[u]), (tok, v.tokens[u])
+            st, text = new, text + tok
+            if len(st) > 60:
+                break
+    # a token that is not allowed cannot be advanced by, and leaves the stack unchanged
+    st = o.initial_stack()
+    rc, same = o.advance(st, b"}")
+    assert rc == 1 and same == st
+    # empty byte strings are never allowed
+    assert not o.allowed(st, b"")
+
+
+def test_advance_overflow_leaves_stack_unchanged(json_oracle):
+    o = json_oracle
+    st = o.initial_stack()
+    rc, deep = o.advance(st, b"[[[[")
+    assert rc == 0
+    rc2, same = o.advance(deep, b"[[[[[[[[", cap=len(deep) + 3)
+    assert rc2 == 2 and same == deep
+    assert o.allowed(deep, b"[[[[[[[[")          # 'allowed' itself has no capacity
+
+
+def test_batched_calls_match_single_calls(json_oracle, json_vocab):
+    o, v = json_oracle, json_vocab
+    prefixes = [b"", b'{"a', b"[1", b'{"k": [tr', b"[[[[", b'"x\\', b"12.5e", b" 7 "]
+    B, cap = len(prefixes) + 1, 64
+    data = np.zeros((B, cap), dtype=np.int32)
+    length = np.ones(B, dtype=np.int32)
+    states = np.zeros(B, dtype=np.int32)
+    for b, p in enumerate(prefixes):
+        rc, st = (0, o.initial_stack()) if not p else o.advance(o.initial_stack(), p)
+        assert rc == 0
+        data[b, : len(st)] = st
+        length[b] = len(st)
+        states[b] = st[-1]
+    data[B - 1, 0] = o.initial_state()
+    states[B - 1] = -1                                             # a finished sequence
+    m = o.fill_mask(states, data, length, v)
+    for b in range(B - 1):
+        assert (m[b] == o.mask_row(data[b, : length[b]], v)).all()
+    only_eos = np.zeros(v.words, dtype=np.uint32)
+    only_eos[v.eos_id >> 5] = 1 << (v.eos_id & 31)
+    assert (m[B - 1] == only_eos).all()
+    # advance_batch: ok, skip, disallowed, EOS where allowed / not allowed, finished, overflow
+    tok_of = {tok: t for t, tok in enumerate(v.tokens) if t != v.eos_id}
+    tokens = np.array([tok_of[b"{"], -1, tok_of[b"}"], v.eos_id, tok_of[b"["], tok_of[b"n"],
+                       tok_of[b"1"], v.eos_id, tok_of[b"1"]], dtype=np.int32)
+    s2, d2, l2 = states.copy(), data.copy(), length.copy()
+    d2[4, :] = data[4, :]
+    err = o.advance_batch(s2, d2, l2, tokens, v)
+    assert err.tolist() == [0, 0, 1, 1, 0, 0, 0, 0, 1]
+    assert s2[7] == -1 and (d2[7] == data[7]).all() and l2[7] == length[7]       # EOS: stack untouched
+    assert (d2[2] == data[2]).all() and l2[2] == length[2] and s2[2] == states[2]
+    assert l2[1] == length[1] and s2[1] == states[1]
+    rc, st0 = o.advance(o.initial_stack(), b"{")
+    assert d2[0, : l2[0]].tolist() == st0 and s2[0] == st0[-1]
+    # overflow: the row has no room for the push; the sequence is left unchanged
+    n4 = int(length[4])
+    tight = np.ascontiguousarray(data[4:5, :n4])
+    s3, l3 = states[4:5].copy(), length[4:5].copy()
+    before = tight.copy()
+    err3 = o.advance_batch(s3, tight, l3, np.array([tok_of[b"["]], dtype=np.int32), v)
+    assert err3.tolist() == [2] and (tight == before).all() and l3[0] == n4 and s3[0] == states[4]
+
+
+def test_apply_mask_is_a_bf16_select():
+    rng = np.random.default_rng(5)
+    B, V = 5, 1000 + 17
+    logits = bf16_logits(rng, B, V)
+    logits[0, :6] = [0x7FC0, 0xFFC1, 0x7F80, 0xFF80, 0x0000, 0x8000]      # NaNs, infs, zeros
+    W = (V + 31) // 32
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[1] = 0
+    mask[2] = 0xFFFFFFFF
+    bits = ((mask[:, np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1).astype(bool)
+    expect = np.where(bits, logits, np.uint16(0xFF80))
+    got = logits.copy()
+    apply_mask(got, mask, V)
+    assert (got == expect).all()
+    # strided rows: only the first V entries of each row are touched
+    wide = np.full((B, V + 9), 0x1234, dtype=np.uint16)
+    wide[:, :V] = logits
+    apply_mask(wide, mask, V)
+    assert (wide[:, :V] == expect).all() and (wide[:, V:] == 0x1234).all()
+
+
+def test_arithmetic_workload_vocab_has_the_terminals():
+    v = arithmetic_vocab(BASE_SEED + 1)
+    assert v.n_tokens == 513 and v.eos_id == 512
+    assert all(bytes([c]) in v.tokens for c in b"a+*()")
