@@ -1,0 +1,171 @@
+/*
+ * pre3.h -- C ABI of the MI355X (gfx950) batched token-mask path of Pre^3
+ * (arXiv 2506.03887: constrained LLM decoding with a deterministic pushdown automaton
+ * built from a canonical LR(1) grammar).
+ *
+ * Per decode step, for every (sequence, vocabulary token) pair the token's bytes are
+ * walked through the DPDA from the sequence's stack; the verdicts are packed into a
+ * vocabulary bitmask, the bitmask is applied to the logits, and each sequence's stack is
+ * advanced by its sampled token.  All per-step work runs in HIP kernels; the host only
+ * compiles the grammar once.
+ *
+ * Conventions
+ *   - "host" / "device" says where a pointer must live.  Device pointers are plain
+ *     hipMalloc-style addresses (e.g. torch tensor data_ptr()); the library never frees
+ *     or reallocates caller memory.
+ *   - Every function returns PRE3_OK (0) or a negative pre3_status.  Nothing throws.
+ *   - Device calls only enqueue work on `stream` (a hipStream_t, NULL = default stream)
+ *     and return; they do not synchronise and do not allocate.
+ *   - Terminals are single bytes; a parse stack holds LR(1) state ids only, bottom first
+ *     (Sec. 3.2.2: an acceptance edge pushes the target node's state).
+ *   - State ids: canonical LR(1) item sets (App. A.2) numbered in breadth-first discovery
+ *     order from the initial set, trying terminals in ascending byte order and then
+ *     nonterminals in order of first appearance on a left-hand side; with several
+ *     grammars, the ids of grammar g are shifted by the number of states of grammars
+ *     0..g-1 (disjoint union), so a stack identifies its grammar by itself.
+ */
+#ifndef PRE3_H
+#define PRE3_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PRE3_OK = 0,
+    PRE3_E_BADARG = -1,          /* null pointer, bad size, misaligned buffer, wrong handle kind */
+    PRE3_E_PARSE = -2,           /* malformed grammar text, undefined or useless nonterminal     */
+    PRE3_E_NOT_LR1 = -3,         /* shift/reduce or reduce/reduce conflict in the canonical table */
+    PRE3_E_TOKEN_TOO_LONG = -4,  /* a vocabulary token exceeds options.max_token_len             */
+    PRE3_E_NOMEM = -5,
+    PRE3_E_HIP = -6,             /* a HIP runtime call failed; text in pre3_last_error           */
+    PRE3_E_LIMIT = -7            /* grammar exceeds an internal table limit                      */
+} pre3_status;
+
+/* per-sequence error codes written by pre3_advance into err[b] */
+#define PRE3_SEQ_OK 0
+#define PRE3_SEQ_NOT_ALLOWED 1   /* token not allowed (also: any token on a finished sequence)  */
+#define PRE3_SEQ_OVERFLOW 2      /* the stack would exceed `cap` entries during the walk         */
+
+#define PRE3_STATE_DONE (-1)     /* states[b] of a sequence that has taken the EOS token         */
+
+#define PRE3_FLAG_HOST_ONLY 1    /* build the tables but upload nothing (no GPU needed);         */
+                                 /* device calls on such a handle return PRE3_E_BADARG           */
+
+typedef struct pre3_handle pre3_handle;     /* opaque; owns host and device tables */
+typedef void *pre3_stream;                  /* hipStream_t */
+
+/* Vocabulary, host memory, borrowed for the duration of pre3_compile only.
+ * Token t is bytes[offsets[t] .. offsets[t+1]).  The bytes of eos_id are ignored.
+ * Tokens of length 0 are never allowed.  Equal byte strings get equal mask bits. */
+typedef struct {
+    const uint8_t *bytes;
+    const int64_t *offsets;      /* [n_tokens + 1], non-decreasing, offsets[0] >= 0 */
+    int32_t n_tokens;
+    int32_t eos_id;              /* in [0, n_tokens) */
+} pre3_vocab;
+
+typedef struct {
+    int32_t max_token_len;       /* 0 = default 64; longer tokens -> PRE3_E_TOKEN_TOO_LONG */
+    int32_t stack_cap;           /* 0 = default 1024; largest `cap` accepted in pre3_stacks */
+    int32_t flags;               /* PRE3_FLAG_* */
+} pre3_options;
+
+/* Parse stacks of a batch, device memory, caller-owned.
+ * Row b is data[b*cap .. b*cap + len[b]); data[b*cap] is the initial state of the
+ * sequence's grammar and data[b*cap + len[b] - 1] its current top.  len[b] >= 1. */
+typedef struct {
+    int32_t *data;               /* device [batch, cap] row-major */
+    int32_t *len;                /* device [batch] */
+    int32_t cap;
+    int32_t batch;
+} pre3_stacks;
+
+/* Builds, on the host, the canonical LR(1) automaton of each grammar (App. A.2) and from
+ * it the DPDA edge tables of Sec. 3.1-3.3: acceptance edges (shift: push the target state),
+ * reduction edges keyed by the exposed stack state (the stack-matching condition), byte
+ * classes that aggregate bytes with identical edges (Sec. 3.3, edge aggregation), and the
+ * byte-sorted vocabulary layout; then uploads them to the current HIP device.
+ *
+ * grammars: host array of n_grammars NUL-terminated texts (n_grammars >= 1).  Format:
+ *     Name ::= alt | alt ...      a following line starting with '|' continues the rule
+ *     alt  = sequence of Names and "quoted byte strings" ("" = empty string)
+ *          | [class]              a byte class must be a whole alternative (sugar for one
+ *                                 production per byte; '^' negates, a-b is a range)
+ *     escapes: \n \r \t \\ \" \] \- \^ \[ \xHH ; '#' starts a comment; first rule = start.
+ * opt: host, may be NULL (defaults).
+ * out: receives the handle; on error *out is still a valid handle holding only the error
+ *      text (free it with pre3_free) or NULL if even that allocation failed.
+ * Errors: BADARG, PARSE, NOT_LR1, TOKEN_TOO_LONG, LIMIT, NOMEM, HIP. */
+int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_vocab *vocab,
+                 const pre3_options *opt, pre3_handle **out);
+
+/* Releases host and device tables.  NULL is allowed.  The caller must have synchronised
+ * every stream that still runs work of this handle. */
+int pre3_free(pre3_handle *h);
+
+/* Host text of the last error recorded on this handle ("" if none).  Never NULL. */
+const char *pre3_last_error(const pre3_handle *h);
+
+/* Initial LR(1) state of grammar g (the value to put in data[b*cap] with len[b] = 1 and
+ * states[b]), or PRE3_E_BADARG. */
+int32_t pre3_initial_state(const pre3_handle *h, int32_t grammar_idx);
+
+/* Binds the per-sequence buffers that pre3_advance mutates (all device memory, caller-owned,
+ * must outlive the binding): states [batch] (top state of each stack, or PRE3_STATE_DONE),
+ * the stacks, and err [batch].  Rebinding replaces the previous binding. */
+int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t *err);
+
+/* Token mask of one decode step (Sec. 1: every token whose bytes leave the language of
+ * viable prefixes is excluded; Sec. 3.1-3.2: the walk follows acceptance and reduction
+ * edges, each selected by input byte and stack-matching condition, never backtracking).
+ * For each sequence b and token t: bit (t mod 32), least significant first, of word
+ * bitmask[b*W + t/32], W = ceil(n_tokens/32), is 1 iff t is allowed after b's stack; the
+ * EOS bit is 1 iff the text so far is a sentence; padding bits are 0.  A sequence with
+ * states[b] == PRE3_STATE_DONE gets only the EOS bit.  Reads states/stacks (which may be
+ * the bound buffers or any snapshot of the same shape), writes all batch*W words.
+ * states, stacks.*, bitmask: device.  Errors: BADARG (null, cap > stack_cap, batch < 0). */
+int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
+                   pre3_stream stream);
+
+/* Applies a token mask to bf16 logits in place (Sec. 1: the mask removes the sampling
+ * probability of excluded tokens): logits[b*row_stride + t] becomes -inf (bit pattern
+ * 0xFF80) where the token's bit is 0 and is left untouched, bit for bit, where it is 1.
+ * logits_bf16: device, [batch, >= vocab] with row_stride elements between rows;
+ * bitmask: device [batch, ceil(vocab/32)].  Needs no handle.  Errors: BADARG. */
+int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batch, int32_t vocab,
+                    int64_t row_stride, pre3_stream stream);
+
+/* Advances every bound sequence by its sampled token (Sec. 3.2.2: acceptance edges push,
+ * reduction edges match, pop and push).  tokens: device [batch]; tokens[b] < 0 skips b.
+ * The EOS token, where allowed, sets states[b] = PRE3_STATE_DONE and leaves the stack
+ * untouched.  A token that is not allowed, any token on a finished sequence, or an id
+ * >= n_tokens sets err[b] = PRE3_SEQ_NOT_ALLOWED; a walk that would grow the stack
+ * beyond cap sets err[b] = PRE3_SEQ_OVERFLOW; in both cases the sequence is left
+ * unchanged.  Otherwise err[b] = 0, the stack holds the LR(1) stack after the token's
+ * last byte (reductions that wait for the next byte are not applied) and states[b] its
+ * top.  Errors: BADARG (nothing bound, null tokens). */
+int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream);
+
+/* ---- host-side introspection of the compiled tables (used by tests and tools) ---- */
+
+int32_t pre3_n_grammars(const pre3_handle *h);
+int32_t pre3_n_states(const pre3_handle *h);            /* total over all grammars */
+int32_t pre3_n_byte_classes(const pre3_handle *h);      /* aggregated input symbols, without '$' */
+int32_t pre3_byte_class(const pre3_handle *h, int32_t byte);
+/* Edge leaving global state `state` on input `symbol` (0..255 a byte, 256 = end of input):
+ * returns 0 none, 1 acceptance edge (*arg0 = target state), 2 reduction step (*arg0 = number
+ * of states popped, *arg1 = nonterminal index local to the state's grammar), 3 accept. */
+int32_t pre3_edge(const pre3_handle *h, int32_t state, int32_t symbol, int32_t *arg0, int32_t *arg1);
+/* Target of the reduction step that exposes `state` and pushes nonterminal `nt` (the
+ * stack-matching condition of a reduction edge), or -1. */
+int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt);
+/* Largest number of private stack entries a walk of one token can need. */
+int32_t pre3_walk_depth_bound(const pre3_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRE3_H */

@@ -1,0 +1,188 @@
+"""Thin ctypes binding of libpre3.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  Device buffers are torch tensors
+(PyTorch is used for device memory and streams only); their data_ptr() and the current
+stream's handle are passed through the C ABI declared in include/pre3.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpre3.so")
+
+PRE3_OK = 0
+E_BADARG, E_PARSE, E_NOT_LR1, E_TOKEN_TOO_LONG, E_NOMEM, E_HIP, E_LIMIT = -1, -2, -3, -4, -5, -6, -7
+FLAG_HOST_ONLY = 1
+STATE_DONE = -1
+
+EXPORTS = [
+    "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
+    "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
+]
+
+
+class Pre3Error(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"pre3 status {status}: {text}")
+        self.status = status
+
+
+class _Vocab(ctypes.Structure):
+    _fields_ = [("bytes", ctypes.c_void_p), ("offsets", ctypes.c_void_p),
+                ("n_tokens", ctypes.c_int32), ("eos_id", ctypes.c_int32)]
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("max_token_len", ctypes.c_int32), ("stack_cap", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class _Stacks(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("len", ctypes.c_void_p),
+                ("cap", ctypes.c_int32), ("batch", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with paper_2506_03887_amd.build.build()")
+    lib = ctypes.CDLL(LIB_PATH)
+    c, vp, i32 = ctypes, ctypes.c_void_p, ctypes.c_int32
+    lib.pre3_compile.argtypes = [c.POINTER(c.c_char_p), i32, c.POINTER(_Vocab), c.POINTER(_Options), c.POINTER(vp)]
+    lib.pre3_free.argtypes = [vp]
+    lib.pre3_last_error.argtypes = [vp]
+    lib.pre3_last_error.restype = c.c_char_p
+    lib.pre3_initial_state.argtypes = [vp, i32]
+    lib.pre3_bind_state.argtypes = [vp, vp, _Stacks, vp]
+    lib.pre3_fill_mask.argtypes = [vp, vp, _Stacks, vp, vp]
+    lib.pre3_apply_mask.argtypes = [vp, vp, i32, i32, c.c_int64, vp]
+    lib.pre3_advance.argtypes = [vp, vp, vp]
+    for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
+        getattr(lib, name).argtypes = [vp]
+    lib.pre3_byte_class.argtypes = [vp, i32]
+    lib.pre3_edge.argtypes = [vp, i32, i32, c.POINTER(i32), c.POINTER(i32)]
+    lib.pre3_goto_target.argtypes = [vp, i32, i32]
+    for name in EXPORTS:
+        if name != "pre3_last_error":
+            getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t, dtype_name):
+    """Device pointer of a contiguous torch tensor of the expected dtype."""
+    import torch
+    want = {"i32": torch.int32, "u16": (torch.bfloat16, torch.uint16, torch.int16), "u32": (torch.int32, torch.uint32)}[dtype_name]
+    ok = t.dtype in want if isinstance(want, tuple) else t.dtype == want
+    if not (t.is_cuda and ok):
+        raise TypeError(f"expected a CUDA tensor of kind {dtype_name}, got {t.dtype} on {t.device}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Pre3:
+    """Compiled grammar(s) + vocabulary.  Mirrors the C entry points one to one."""
+
+    def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
+                 max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False):
+        lib = load()
+        if isinstance(grammars, str):
+            grammars = [grammars]
+        texts = (ctypes.c_char_p * len(grammars))(*[g.encode("latin-1") for g in grammars])
+        vb = np.ascontiguousarray(vocab_bytes, dtype=np.uint8)
+        vo = np.ascontiguousarray(vocab_offsets, dtype=np.int64)
+        voc = _Vocab(vb.ctypes.data, vo.ctypes.data, len(vo) - 1, eos_id)
+        opt = _Options(max_token_len, stack_cap, FLAG_HOST_ONLY if host_only else 0)
+        h = ctypes.c_void_p()
+        rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
+        self._lib, self._h = lib, h
+        if rc != PRE3_OK:
+            text = lib.pre3_last_error(h).decode() if h else "allocation failed"
+            lib.pre3_free(h)
+            self._h = None
+            raise Pre3Error(rc, text)
+        self.n_tokens = len(vo) - 1
+        self.words = (self.n_tokens + 31) // 32
+        self.eos_id = eos_id
+        self._bound = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.pre3_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def _check(self, rc):
+        if rc != PRE3_OK:
+            raise Pre3Error(rc, self._lib.pre3_last_error(self._h).decode())
+
+    # ---- host queries
+    def initial_state(self, g=0):
+        s = self._lib.pre3_initial_state(self._h, g)
+        if s < 0:
+            raise Pre3Error(s, "bad grammar index")
+        return s
+
+    n_grammars = property(lambda self: self._lib.pre3_n_grammars(self._h))
+    n_states = property(lambda self: self._lib.pre3_n_states(self._h))
+    n_byte_classes = property(lambda self: self._lib.pre3_n_byte_classes(self._h))
+    walk_depth_bound = property(lambda self: self._lib.pre3_walk_depth_bound(self._h))
+
+    def byte_class(self, byte):
+        return self._lib.pre3_byte_class(self._h, byte)
+
+    def edge(self, state, symbol):
+        a0, a1 = ctypes.c_int32(), ctypes.c_int32()
+        kind = self._lib.pre3_edge(self._h, state, symbol, ctypes.byref(a0), ctypes.byref(a1))
+        return kind, a0.value, a1.value
+
+    def goto_target(self, state, nt):
+        return self._lib.pre3_goto_target(self._h, state, nt)
+
+    # ---- device calls (torch tensors in, nothing out: all results are written in place)
+    @staticmethod
+    def _stacks(data, length):
+        batch, cap = data.shape
+        assert data.is_contiguous() and length.is_contiguous() and length.numel() == batch
+        return _Stacks(_dev(data, "i32"), _dev(length, "i32"), cap, batch)
+
+    def bind_state(self, states, data, length, err):
+        self._check(self._lib.pre3_bind_state(self._h, _dev(states, "i32"), self._stacks(data, length), _dev(err, "i32")))
+        self._bound = (states, data, length, err)          # keep the tensors alive
+
+    def fill_mask(self, states, data, length, bitmask, stream=None):
+        assert bitmask.is_contiguous() and tuple(bitmask.shape) == (data.shape[0], self.words)
+        self._check(self._lib.pre3_fill_mask(self._h, _dev(states, "i32"), self._stacks(data, length),
+                                             _dev(bitmask, "u32"), _stream_ptr(stream)))
+
+    def advance(self, tokens, stream=None):
+        assert tokens.is_contiguous()
+        self._check(self._lib.pre3_advance(self._h, _dev(tokens, "i32"), _stream_ptr(stream)))
+
+
+def apply_mask(logits, bitmask, vocab: int, stream=None):
+    """In place on a [B, >=vocab] bf16 tensor whose rows may be strided."""
+    lib = load()
+    assert logits.dim() == 2 and logits.stride(1) == 1 and bitmask.is_contiguous()
+    rc = lib.pre3_apply_mask(_dev(logits, "u16"), _dev(bitmask, "u32"), logits.shape[0], vocab,
+                             logits.stride(0), _stream_ptr(stream))
+    if rc != PRE3_OK:
+        raise Pre3Error(rc, "apply_mask: bad argument or launch failure")

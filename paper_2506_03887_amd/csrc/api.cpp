@@ -1,0 +1,264 @@
+// C ABI of the library (declared in include/pre3.h): argument checks, table upload, launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pre3.h"
+#include "device_tables.hpp"
+#include "grammar.hpp"
+#include "launch.hpp"
+#include "tables.hpp"
+
+using namespace pre3;
+
+struct pre3_handle {
+    std::string error;
+    bool compiled = false;
+    bool host_only = false;
+    int stack_cap = 1024;
+    EdgeTables T;
+    VocabLayout V;
+    int max_depth = 0;
+
+    std::vector<void *> allocations;     // device memory owned by the handle
+    DevTables dev{};
+    int grid_blocks = 0;
+    int32_t *spill = nullptr;
+
+    // binding used by pre3_advance
+    int32_t *b_states = nullptr, *b_err = nullptr;
+    pre3_stacks b_stacks{};
+    int32_t *adv_scratch = nullptr;
+    size_t adv_scratch_entries = 0;
+};
+
+namespace {
+
+int fail(pre3_handle *h, int status, const std::string &text) {
+    if (h) h->error = text;
+    return status;
+}
+
+int hip_fail(pre3_handle *h, hipError_t e, const char *what) {
+    return fail(h, PRE3_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+template <typename T>
+hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
+    void *p = nullptr;
+    size_t bytes = src.size() * sizeof(T);
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+    if (e != hipSuccess) return e;
+    h->allocations.push_back(p);
+    if (bytes) {
+        e = hipMemcpy(p, src.data(), bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    *dst = static_cast<const T *>(p);
+    return hipSuccess;
+}
+
+hipError_t device_alloc(pre3_handle *h, size_t bytes, void **out, bool zero) {
+    hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+    if (e != hipSuccess) return e;
+    h->allocations.push_back(*out);
+    if (zero) e = hipMemset(*out, 0, bytes ? bytes : 16);
+    return e;
+}
+
+int upload_tables(pre3_handle *h) {
+    hipError_t e;
+    DevTables &D = h->dev;
+#define PRE3_UP(vec, field)                                               \
+    if ((e = upload(h, vec, &D.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
+    std::vector<int32_t> byte_info(256);
+    for (int b = 0; b < 256; ++b) byte_info[b] = (int32_t)h->T.byte_class[b] | (h->T.byte_delta[b] * 256);
+    PRE3_UP(byte_info, byte_info);
+    PRE3_UP(h->T.edge, edge);
+    PRE3_UP(h->T.goto_row, goto_row);
+    PRE3_UP(h->T.goto_flat, goto_flat);
+    PRE3_UP(h->V.tok_len, tok_len);
+    PRE3_UP(h->V.tok_bit, tok_bit);
+    PRE3_UP(h->V.tok_words, tok_words);
+    PRE3_UP(h->V.bytes, vbytes);
+    PRE3_UP(h->V.offsets, voffsets);
+#undef PRE3_UP
+    D.n_states = h->T.n_states;
+    D.ncol = h->T.n_classes + 1;
+    D.end_col = h->T.n_classes;
+    D.n_padded = h->V.n_padded;
+    D.n_chunks = h->V.n_chunks;
+    D.n_words = h->V.n_words;
+    D.n_tokens = h->V.n_tokens;
+    D.eos_id = h->V.eos_id;
+    D.max_depth = h->max_depth;
+
+    int device = 0;
+    hipDeviceProp_t prop;
+    if ((e = hipGetDevice(&device)) != hipSuccess) return hip_fail(h, e, "hipGetDevice");
+    if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return hip_fail(h, e, "hipGetDeviceProperties");
+    h->grid_blocks = walk_grid_blocks(prop.multiProcessorCount);
+    void *p = nullptr;
+    if ((e = device_alloc(h, walk_spill_entries(h->grid_blocks, h->max_depth) * sizeof(int32_t), &p, false)) != hipSuccess)
+        return hip_fail(h, e, "allocate walk spill area");
+    h->spill = static_cast<int32_t *>(p);
+    if ((e = device_alloc(h, sizeof(int32_t), &p, true)) != hipSuccess) return hip_fail(h, e, "allocate fault counter");
+    D.fault = static_cast<int32_t *>(p);
+    return PRE3_OK;
+}
+
+bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
+
+// (grammar, local state) of a global state id
+bool locate(const pre3_handle *h, int state, int *g, int *local) {
+    if (!h || !h->compiled || state < 0 || state >= h->T.n_states) return false;
+    for (int i = 0; i < h->T.n_grammars; ++i)
+        if (state < h->T.state_offset[i + 1]) { *g = i; *local = state - h->T.state_offset[i]; return true; }
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_vocab *vocab, const pre3_options *opt,
+                 pre3_handle **out) {
+    if (!out) return PRE3_E_BADARG;
+    *out = nullptr;
+    pre3_handle *h = new (std::nothrow) pre3_handle();
+    if (!h) return PRE3_E_NOMEM;
+    *out = h;
+    if (!grammars || n_grammars < 1 || !vocab) return fail(h, PRE3_E_BADARG, "null or empty argument");
+    if (!vocab->bytes || !vocab->offsets || vocab->n_tokens < 1 || vocab->eos_id < 0 ||
+        vocab->eos_id >= vocab->n_tokens)
+        return fail(h, PRE3_E_BADARG, "bad vocabulary");
+    int max_token_len = opt && opt->max_token_len ? opt->max_token_len : 64;
+    h->stack_cap = opt && opt->stack_cap ? opt->stack_cap : 1024;
+    h->host_only = opt && (opt->flags & PRE3_FLAG_HOST_ONLY);
+    if (max_token_len < 1 || max_token_len > 254 || h->stack_cap < 1)
+        return fail(h, PRE3_E_BADARG, "max_token_len must be in 1..254 and stack_cap positive");
+    try {
+        std::vector<Grammar> gs;
+        for (int i = 0; i < n_grammars; ++i) {
+            if (!grammars[i]) return fail(h, PRE3_E_BADARG, "null grammar text");
+            try {
+                gs.push_back(parse_grammar(grammars[i]));
+            } catch (CompileError &e) {
+                if (n_grammars > 1) e.text = "grammar " + std::to_string(i) + ": " + e.text;
+                throw;
+            }
+        }
+        h->T = build_edge_tables(gs);
+        h->V = build_vocab_layout(vocab->bytes, vocab->offsets, vocab->n_tokens, vocab->eos_id, max_token_len);
+        // every input symbol adds at most height_per_byte - 1 private entries (see tables.cpp)
+        h->max_depth = std::max(1, h->V.max_len) * (h->T.height_per_byte - 1) + 1;
+    } catch (const CompileError &e) {
+        return fail(h, e.status, e.text);
+    } catch (const std::bad_alloc &) {
+        return fail(h, PRE3_E_NOMEM, "out of host memory");
+    }
+    h->compiled = true;
+    if (!h->host_only) {
+        int rc = upload_tables(h);
+        if (rc != PRE3_OK) { h->compiled = false; return rc; }
+    }
+    return PRE3_OK;
+}
+
+int pre3_free(pre3_handle *h) {
+    if (!h) return PRE3_OK;
+    for (void *p : h->allocations) (void)hipFree(p);
+    delete h;
+    return PRE3_OK;
+}
+
+const char *pre3_last_error(const pre3_handle *h) { return h ? h->error.c_str() : "null handle"; }
+
+int32_t pre3_initial_state(const pre3_handle *h, int32_t g) {
+    if (!h || !h->compiled || g < 0 || g >= h->T.n_grammars) return PRE3_E_BADARG;
+    return h->T.state_offset[g];
+}
+
+int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t *err) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (!states || !err || !stacks.data || !stacks.len || stacks.batch < 0 || stacks.cap < 1 ||
+        stacks.cap > h->stack_cap)
+        return fail(h, PRE3_E_BADARG, "bind_state: null buffer, negative batch or cap outside 1..stack_cap");
+    size_t need = advance_scratch_entries(stacks.batch, h->max_depth);
+    if (need > h->adv_scratch_entries) {
+        void *p = nullptr;
+        hipError_t e = device_alloc(h, need * sizeof(int32_t), &p, false);
+        if (e != hipSuccess) return hip_fail(h, e, "allocate advance scratch");
+        h->adv_scratch = static_cast<int32_t *>(p);
+        h->adv_scratch_entries = need;
+    }
+    h->b_states = states;
+    h->b_stacks = stacks;
+    h->b_err = err;
+    return PRE3_OK;
+}
+
+int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (!states || !stacks.data || !stacks.len || !bitmask || stacks.batch < 0 || stacks.cap < 1 ||
+        stacks.cap > h->stack_cap)
+        return fail(h, PRE3_E_BADARG, "fill_mask: null buffer, negative batch or cap outside 1..stack_cap");
+    hipError_t e = launch_fill_mask_walk(h->dev, states, stacks.data, stacks.len, stacks.cap, stacks.batch, bitmask,
+                                         h->spill, h->grid_blocks, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_mask");
+}
+
+int pre3_apply_mask(uint16_t *logits, const uint32_t *bitmask, int32_t batch, int32_t vocab, int64_t row_stride,
+                    pre3_stream stream) {
+    if (!logits || !bitmask || batch < 0 || vocab < 0 || row_stride < vocab) return PRE3_E_BADARG;
+    if (reinterpret_cast<uintptr_t>(logits) % 2 != 0 || reinterpret_cast<uintptr_t>(bitmask) % 4 != 0)
+        return PRE3_E_BADARG;
+    hipError_t e = launch_apply_mask(logits, bitmask, batch, vocab, row_stride, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : PRE3_E_HIP;
+}
+
+int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance: no state bound");
+    if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
+    hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
+                                  h->b_stacks.batch, h->b_err, h->adv_scratch, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance");
+}
+
+int32_t pre3_n_grammars(const pre3_handle *h) { return h && h->compiled ? h->T.n_grammars : PRE3_E_BADARG; }
+int32_t pre3_n_states(const pre3_handle *h) { return h && h->compiled ? h->T.n_states : PRE3_E_BADARG; }
+int32_t pre3_n_byte_classes(const pre3_handle *h) { return h && h->compiled ? h->T.n_classes : PRE3_E_BADARG; }
+int32_t pre3_byte_class(const pre3_handle *h, int32_t byte) {
+    if (!h || !h->compiled || byte < 0 || byte > 255) return PRE3_E_BADARG;
+    return h->T.byte_class[byte];
+}
+
+int32_t pre3_edge(const pre3_handle *h, int32_t state, int32_t symbol, int32_t *arg0, int32_t *arg1) {
+    int g, local;
+    if (!locate(h, state, &g, &local) || symbol < 0 || symbol > 256 || !arg0 || !arg1) return PRE3_E_BADARG;
+    int col = symbol == 256 ? h->T.n_classes : h->T.byte_class[symbol];
+    uint32_t e = h->T.edge[(size_t)state * (h->T.n_classes + 1) + col];
+    *arg0 = *arg1 = 0;
+    switch (e & kKindMask) {
+        case kShift: *arg0 = (int32_t)(e >> 2) + (symbol < 256 ? h->T.byte_delta[symbol] : 0); return 1;
+        case kReduce: *arg0 = (int32_t)((e >> 2) & kMaxPop); *arg1 = (int32_t)(e >> kNtShift); return 2;
+        case kAccept: return 3;
+        default: return 0;
+    }
+}
+
+int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt) {
+    int g, local;
+    if (!locate(h, state, &g, &local) || nt < 0 || nt >= h->T.automata[g].n_nt) return PRE3_E_BADARG;
+    int row = h->T.goto_row[state];
+    return row < 0 ? -1 : h->T.goto_flat[row + nt];
+}
+
+int32_t pre3_walk_depth_bound(const pre3_handle *h) { return h && h->compiled ? h->max_depth : PRE3_E_BADARG; }
+
+}  // extern "C"

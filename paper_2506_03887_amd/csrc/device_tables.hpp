@@ -1,0 +1,26 @@
+// Plain-pointer view of the uploaded tables, passed to kernels by value.
+#pragma once
+#include <cstdint>
+
+namespace pre3 {
+
+struct DevTables {
+    // DPDA edges
+    const int32_t *byte_info;      // [256] byte class | (acceptance-target offset << 8)
+    const uint32_t *edge;          // [n_states * ncol], packed as in tables.hpp
+    const int32_t *goto_row;       // [n_states]
+    const int32_t *goto_flat;
+    int n_states, ncol, end_col;   // end_col = column of '$'
+    // vocabulary, chunk-sorted order
+    const uint8_t *tok_len;        // [n_padded]
+    const uint16_t *tok_bit;       // [n_padded]
+    const uint32_t *tok_words;     // [words_per_token * n_padded]
+    int n_padded, n_chunks, n_words, n_tokens, eos_id;
+    // vocabulary, id order
+    const uint8_t *vbytes;
+    const int32_t *voffsets;       // [n_tokens + 1]
+    int max_depth;                 // private stack entries a walk can need
+    int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
+};
+
+}  // namespace pre3

@@ -1,0 +1,24 @@
+// Host-callable launchers of the kernels (defined in kernels.hip).
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "device_tables.hpp"
+
+namespace pre3 {
+
+int walk_grid_blocks(int n_compute_units);
+size_t walk_spill_entries(int grid_blocks, int max_depth);          // int32 entries
+size_t advance_scratch_entries(int batch, int max_depth);           // int32 entries
+
+hipError_t launch_fill_mask_walk(const DevTables &T, const int32_t *states, const int32_t *data, const int32_t *len,
+                                 int cap, int batch, uint32_t *bitmask, int32_t *spill, int grid_blocks,
+                                 hipStream_t stream);
+hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
+                             hipStream_t stream);
+hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
+                          int cap, int batch, int32_t *err, int32_t *scratch, hipStream_t stream);
+
+}  // namespace pre3

@@ -1,0 +1,96 @@
+"""Replays a seeded trajectory through the GPU library and the CPU oracle side by side."""
+import time
+
+import numpy as np
+
+from oracle import Oracle, apply_mask as oracle_apply_mask
+from workloads import configs, trajectory
+from workloads.vocab import bf16_logits
+
+
+def make_library(cfg):
+    from paper_2506_03887_amd import Pre3
+    v = cfg.vocab
+    return Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cfg.cap)
+
+
+def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, log=print):
+    """Runs `steps` decode steps of config `cfg_idx` on the GPU through the C ABI and checks,
+    against the oracle on the same inputs:
+      - states, len, live stack entries and err of every sequence after every advance;
+      - the whole bitmask (all B*W words) and the masked bf16 logits (all B*V raw patterns)
+        on the steps in `full_mask_steps` (None = every step);
+      - the full mask rows of `rows_per_step` seeded random sequences on every other step.
+    Returns a dict of counters."""
+    import torch
+    from paper_2506_03887_amd import apply_mask
+
+    cfg = configs.get(cfg_idx)
+    v = cfg.vocab
+    steps = cfg.steps if steps is None else steps
+    o = Oracle(cfg.grammars)
+    gi, depths = configs.sequence_setup(cfg)
+    t0 = time.time()
+    traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
+                               cfg.json_strings, depths)
+    log(f"[cfg {cfg_idx}] trajectory of {steps} steps in {time.time() - t0:.1f}s; "
+        f"{int(traj.reset.sum())} resets, {int((traj.tokens == v.eos_id).sum())} EOS", flush=True)
+    lib = make_library(cfg)
+    dev = torch.device("cuda:0")
+    B, cap, W, V = cfg.batch, cfg.cap, v.words, v.n_tokens
+
+    data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
+    states_h = data_h[np.arange(B), len_h - 1].copy()
+    data_d = torch.from_numpy(data_h).to(dev)
+    len_d = torch.from_numpy(len_h).to(dev)
+    states_d = torch.from_numpy(states_h).to(dev)
+    err_d = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
+    rng = np.random.default_rng(cfg.seed + 1)
+    full = set(range(steps)) if full_mask_steps is None else set(full_mask_steps)
+    n_full = n_rows = 0
+
+    for s in range(steps):
+        rs = np.flatnonzero(traj.reset[s])
+        if len(rs):                      # slot reuse: finished sequences start afresh
+            data_h[rs, 0], len_h[rs], states_h[rs] = s0[rs], 1, s0[rs]
+            idx = torch.from_numpy(rs).to(dev)
+            data_d[idx, 0] = torch.from_numpy(s0[rs]).to(dev)
+            len_d[idx] = 1
+            states_d[idx] = torch.from_numpy(s0[rs]).to(dev)
+        mask_d.fill_(0x5A5A5A5A)
+        lib.fill_mask(states_d, data_d, len_d, mask_d)
+        got = mask_d.cpu().numpy().view(np.uint32)
+        if s in full:
+            want = o.fill_mask(states_h, data_h, len_h, v)
+            bad = np.argwhere(got != want)
+            assert len(bad) == 0, f"cfg {cfg_idx} step {s}: {len(bad)} mask words differ, first (row, word) {bad[0]}"
+            n_full += 1
+            if check_apply:
+                logits = bf16_logits(rng, B, V)
+                logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
+                apply_mask(logits_d, mask_d, V)
+                oracle_apply_mask(logits, want, V)
+                out = logits_d.cpu().numpy().view(np.uint16)
+                assert (out == logits).all(), f"cfg {cfg_idx} step {s}: masked logits differ"
+        else:
+            for b in rng.integers(0, B, size=rows_per_step):
+                want = o.mask_row(data_h[b, : len_h[b]], v, done=states_h[b] < 0)
+                assert (got[b] == want).all(), f"cfg {cfg_idx} step {s} row {b}: mask row differs"
+                n_rows += 1
+        tok = traj.tokens[s]
+        lib.advance(torch.from_numpy(tok).to(dev))
+        err_h = o.advance_batch(states_h, data_h, len_h, tok, v)
+        assert (err_d.cpu().numpy() == err_h).all() and not err_h.any(), f"cfg {cfg_idx} step {s}: err differs"
+        assert (states_d.cpu().numpy() == states_h).all(), f"cfg {cfg_idx} step {s}: states differ"
+        len_g = len_d.cpu().numpy()
+        assert (len_g == len_h).all(), f"cfg {cfg_idx} step {s}: len differs"
+        live = np.arange(cap)[None, :] < len_h[:, None]
+        data_g = data_d.cpu().numpy()
+        assert (data_g[live] == data_h[live]).all(), f"cfg {cfg_idx} step {s}: stack entries differ"
+        if s % 32 == 31 or s == steps - 1:
+            log(f"[cfg {cfg_idx}] step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
+    torch.cuda.synchronize()
+    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, depth_hist=traj.depth_hist)

@@ -1,0 +1,36 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the five
+seeded workload configurations.  Integer/bit work: everything must be bit-exact."""
+import numpy as np
+import pytest
+
+from replay import replay
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg1_arithmetic_all_steps():
+    r = replay(1)
+    assert r["full_masks"] == 32
+
+
+def test_cfg2_json_all_steps():
+    r = replay(2)
+    assert r["full_masks"] == 128
+
+
+def test_cfg3_json_full_size():
+    """B=256, V=128256, 256 steps: states/stacks on every step, the whole bitmask and masked
+    logits on 6 steps spread over the run, two full mask rows on every other step."""
+    r = replay(3, full_mask_steps=[0, 1, 50, 100, 200, 255])
+    assert r["full_masks"] == 6 and r["sampled_rows"] == 500
+
+
+def test_cfg4_schema_full_size():
+    r = replay(4, full_mask_steps=[0, 40, 128, 255])
+    assert r["full_masks"] == 4
+
+
+def test_cfg5_mixed_grammars_deep_stacks():
+    r = replay(5, full_mask_steps=[0, 1, 64, 256, 511])
+    assert r["full_masks"] == 5
+    assert max(r["depth_hist"]) >= 60 and len(r["depth_hist"]) > 40

@@ -1,0 +1,127 @@
+"""Host logic of the library, checked on the CPU: the compiled DPDA edge tables against the
+oracle's ACTION/GOTO tables, byte-class aggregation, error statuses, exported symbols."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import A_ACCEPT, A_ERROR, A_REDUCE, A_SHIFT, Oracle
+from paper_2506_03887_amd import binding
+from paper_2506_03887_amd.binding import Pre3, Pre3Error
+from workloads import grammars as G
+from workloads.vocab import BASE_SEED, bpe_like_vocab
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def vocab():
+    return bpe_like_vocab(2000, 12, BASE_SEED + 50)
+
+
+def host_compile(grammars, vocab, **kw):
+    return Pre3(grammars, vocab.bytes, vocab.offsets, vocab.eos_id, host_only=True, **kw)
+
+
+def test_header_symbols_are_exported():
+    header = open(os.path.join(ROOT, "include", "pre3.h")).read()
+    declared = set(re.findall(r"\b(pre3_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("texts", [
+    [G.ARITHMETIC], [G.JSON], [G.EPSILON_MIX, G.DYCK, G.ARITHMETIC],
+    [G.schema_grammar(11, 6, 2, 4).text, G.JSON],
+])
+def test_edge_tables_equal_oracle_tables(texts, vocab):
+    """Same canonical collection, same state numbering, same actions: every (state, symbol)
+    cell and every goto of the library equals the oracle's."""
+    o = Oracle(texts)
+    p = host_compile(texts, vocab)
+    assert p.n_grammars == len(texts) and p.n_states == o.n_states_total()
+    for g in range(len(texts)):
+        off = o.initial_state(g)
+        assert p.initial_state(g) == off
+        names = [o.production(q, g)[0] for q in range(o.n_productions(g))]
+        lhs_index = {n: o.nonterminal_index(n, g) for n in set(names)}
+        for s in range(o.n_states(g)):
+            for a in range(257):
+                kind, arg = o.action(s, a, g)
+                got = p.edge(off + s, a)
+                if kind == A_ERROR:
+                    assert got[0] == 0
+                elif kind == A_SHIFT:
+                    assert got[:2] == (1, arg + off), (g, s, a)
+                elif kind == A_REDUCE:
+                    name, n = o.production(arg, g)
+                    assert got == (2, n, lhs_index[name]), (g, s, a)
+                else:
+                    assert kind == A_ACCEPT and got[0] == 3 and a == 256
+            for A in range(o.n_nonterminals(g)):
+                t = o.goto(s, A, g)
+                assert p.goto_target(off + s, A) == (t + off if t >= 0 else -1)
+
+
+def test_byte_classes_aggregate_digits_and_plain_characters(vocab):
+    """Sec. 3.3 edge aggregation: bytes with identical edges share a class - the digits 0-9 of
+    a number grammar collapse into one class, and so do the plain string characters."""
+    p = host_compile(G.JSON, vocab)
+    assert len({p.byte_class(c) for c in b"0123456789"}) == 1
+    plain = [c for c in range(0x20, 0x100) if c not in b'"\\/bfnrtu0123456789abcdefABCDEF+-.eE{}[]:, truefalsn']
+    assert len({p.byte_class(c) for c in plain}) == 1
+    assert len({p.byte_class(c) for c in b"\t\n\r"}) == 1                         # white space only
+    assert p.byte_class(ord(" ")) not in (p.byte_class(9), p.byte_class(ord("x")))  # also a string character
+    assert len({p.byte_class(c) for c in range(0x20) if c not in b"\t\n\r"}) == 1  # control bytes: no edges
+    assert p.n_byte_classes < 40
+    a = host_compile(G.ARITHMETIC, vocab)
+    # '(' and 'a' can start a factor in exactly the same states and their target states were
+    # numbered consecutively there, so they share a class: + * ) {(,a} and "everything else"
+    assert a.n_byte_classes == 5 and a.byte_class(ord("(")) == a.byte_class(ord("a"))
+
+
+@pytest.mark.parametrize("text,status", [
+    (G.AMBIGUOUS, binding.E_NOT_LR1), (G.PALINDROME, binding.E_NOT_LR1),
+    ('S ::= "a" | S B\nB ::= B "b"\n', binding.E_PARSE), ('S ::= "a"\nB ::= "b"\n', binding.E_PARSE),
+    ('S ::= "a" C\n', binding.E_PARSE), ('S ::= "a" [bc]\n', binding.E_PARSE),
+    ('S ::= "a\n', binding.E_PARSE), ('S ::= \n', binding.E_PARSE), ("", binding.E_PARSE),
+    ('S ::= "\\q"\n', binding.E_PARSE),
+])
+def test_compile_errors(text, status, vocab):
+    with pytest.raises(Pre3Error) as e:
+        host_compile(text, vocab)
+    assert e.value.status == status and len(str(e.value)) > 20
+
+
+def test_argument_errors(vocab):
+    with pytest.raises(Pre3Error) as e:
+        host_compile(G.JSON, vocab, max_token_len=4)
+    assert e.value.status == binding.E_TOKEN_TOO_LONG
+    with pytest.raises(Pre3Error) as e:
+        Pre3(G.JSON, vocab.bytes, vocab.offsets, vocab.n_tokens, host_only=True)       # eos out of range
+    assert e.value.status == binding.E_BADARG
+    p = host_compile(G.JSON, vocab)
+    lib = binding.load()
+    # device calls on a host-only handle are refused, as are null pointers
+    st = binding._Stacks(1, 1, 8, 1)
+    assert lib.pre3_fill_mask(p._h, 1, st, 1, None) == binding.E_BADARG
+    assert lib.pre3_advance(p._h, 1, None) == binding.E_BADARG
+    assert lib.pre3_bind_state(p._h, 1, st, 1) == binding.E_BADARG
+    assert lib.pre3_apply_mask(None, None, 1, 1, 1, None) == binding.E_BADARG
+    assert lib.pre3_apply_mask(16, 16, 1, 8, 4, None) == binding.E_BADARG               # stride < vocab
+    assert lib.pre3_initial_state(p._h, 1) == binding.E_BADARG
+    assert lib.pre3_free(None) == 0
+    assert lib.pre3_last_error(None) == b"null handle"
+
+
+def test_walk_depth_bound_covers_deep_tokens(vocab):
+    """The private-stack bound must cover the deepest walk: '[' pushes two states ('[' and the
+    empty white space), so k brackets need 2k entries."""
+    o = Oracle(G.JSON)
+    p = host_compile(G.JSON, vocab, max_token_len=12)
+    rc, st = o.advance(o.initial_stack(), b"[" * vocab.max_len)
+    assert rc == 0 and p.walk_depth_bound >= len(st) - 1
