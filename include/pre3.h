@@ -53,6 +53,8 @@ typedef enum {
 
 #define PRE3_FLAG_HOST_ONLY 1    /* build the tables but upload nothing (no GPU needed);         */
                                  /* device calls on such a handle return PRE3_E_BADARG           */
+#define PRE3_FLAG_NO_TOKEN_EDGES 2 /* do not precompute token-level edges: pre3_fill_mask then     */
+                                 /* walks every (sequence, token) pair byte by byte              */
 
 typedef struct pre3_handle pre3_handle;     /* opaque; owns host and device tables */
 typedef void *pre3_stream;                  /* hipStream_t */
@@ -71,6 +73,9 @@ typedef struct {
     int32_t max_token_len;       /* 0 = default 64; longer tokens -> PRE3_E_TOKEN_TOO_LONG */
     int32_t stack_cap;           /* 0 = default 1024; largest `cap` accepted in pre3_stacks */
     int32_t flags;               /* PRE3_FLAG_* */
+    int32_t max_condition_depth; /* 0 = default 48: deepest stack entry (below the top) that the    */
+                                 /* stack-matching condition of a token-level edge may test; tokens */
+                                 /* that would need more are walked byte by byte at run time        */
 } pre3_options;
 
 /* Parse stacks of a batch, device memory, caller-owned.
@@ -164,6 +169,19 @@ int32_t pre3_edge(const pre3_handle *h, int32_t state, int32_t symbol, int32_t *
 int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt);
 /* Largest number of private stack entries a walk of one token can need. */
 int32_t pre3_walk_depth_bound(const pre3_handle *h);
+/* Sizes of the token-level prefix-conditioned edge tables (Sec. 3.3, edge merging along the
+ * bytes of each token): out[0] built?, [1] distinct root conditions, [2] condition-tree nodes,
+ * [3] dense rows, [4] token ids in delta lists, [5] token ids in walk lists, [6] deepest stack
+ * entry tested, [7] bytes of device memory they take. */
+int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]);
+/* Table lookup only, on the host: evaluates the condition tree for one stack (host memory,
+ * global state ids, bottom first).  row (ceil(n_tokens/32) words) receives the tokens whose
+ * merged edge matches the stack; walk[0..*n_walk) the token ids the tables leave to a
+ * byte-by-byte walk; info (may be NULL) 4 ints: condition-tree nodes on the path, index of the
+ * node whose dense row is used, delta ids ORed, deepest stack entry tested.  Returns 1, or 0 if the tables hold no answer for this stack (then the
+ * kernels walk every token), or PRE3_E_BADARG (also when walk_cap is too small). */
+int pre3_debug_resolve_row(const pre3_handle *h, const int32_t *stack, int32_t len, uint32_t *row,
+                           int32_t *walk, int32_t walk_cap, int32_t *n_walk, int32_t *info);
 
 #ifdef __cplusplus
 }

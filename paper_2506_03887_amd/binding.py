@@ -17,12 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libpre3.so")
 PRE3_OK = 0
 E_BADARG, E_PARSE, E_NOT_LR1, E_TOKEN_TOO_LONG, E_NOMEM, E_HIP, E_LIMIT = -1, -2, -3, -4, -5, -6, -7
 FLAG_HOST_ONLY = 1
+FLAG_NO_TOKEN_EDGES = 2
 STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
     "pre3_fill_mask", "pre3_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
+    "pre3_token_edge_stats", "pre3_debug_resolve_row",
 ]
 
 
@@ -38,7 +40,8 @@ class _Vocab(ctypes.Structure):
 
 
 class _Options(ctypes.Structure):
-    _fields_ = [("max_token_len", ctypes.c_int32), ("stack_cap", ctypes.c_int32), ("flags", ctypes.c_int32)]
+    _fields_ = [("max_token_len", ctypes.c_int32), ("stack_cap", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("max_condition_depth", ctypes.c_int32)]
 
 
 class _Stacks(ctypes.Structure):
@@ -72,6 +75,8 @@ def load():
     lib.pre3_byte_class.argtypes = [vp, i32]
     lib.pre3_edge.argtypes = [vp, i32, i32, c.POINTER(i32), c.POINTER(i32)]
     lib.pre3_goto_target.argtypes = [vp, i32, i32]
+    lib.pre3_token_edge_stats.argtypes = [vp, vp]
+    lib.pre3_debug_resolve_row.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp]
     for name in EXPORTS:
         if name != "pre3_last_error":
             getattr(lib, name).restype = i32
@@ -100,7 +105,8 @@ class Pre3:
     """Compiled grammar(s) + vocabulary.  Mirrors the C entry points one to one."""
 
     def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
-                 max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False):
+                 max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False,
+                 token_edges: bool = True, max_condition_depth: int = 0):
         lib = load()
         if isinstance(grammars, str):
             grammars = [grammars]
@@ -108,7 +114,9 @@ class Pre3:
         vb = np.ascontiguousarray(vocab_bytes, dtype=np.uint8)
         vo = np.ascontiguousarray(vocab_offsets, dtype=np.int64)
         voc = _Vocab(vb.ctypes.data, vo.ctypes.data, len(vo) - 1, eos_id)
-        opt = _Options(max_token_len, stack_cap, FLAG_HOST_ONLY if host_only else 0)
+        opt = _Options(max_token_len, stack_cap,
+                       (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES),
+                       max_condition_depth)
         h = ctypes.c_void_p()
         rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
         self._lib, self._h = lib, h
@@ -156,6 +164,26 @@ class Pre3:
 
     def goto_target(self, state, nt):
         return self._lib.pre3_goto_target(self._h, state, nt)
+
+    def token_edge_stats(self):
+        out = (ctypes.c_int64 * 8)()
+        self._check(self._lib.pre3_token_edge_stats(self._h, out))
+        keys = ["built", "roots", "nodes", "dense_rows", "delta_ids", "walk_ids", "max_known", "device_bytes"]
+        return dict(zip(keys, list(out)))
+
+    def debug_resolve_row(self, stack):
+        """(resolved?, row bits uint32[W], walk token ids) from the host copy of the tables."""
+        st = np.ascontiguousarray(stack, dtype=np.int32)
+        row = np.zeros(self.words, dtype=np.uint32)
+        walk = np.zeros(self.n_tokens, dtype=np.int32)
+        n = ctypes.c_int32()
+        info = np.zeros(4, dtype=np.int32)
+        rc = self._lib.pre3_debug_resolve_row(self._h, st.ctypes.data, len(st), row.ctypes.data,
+                                              walk.ctypes.data, len(walk), ctypes.byref(n), info.ctypes.data)
+        self.last_resolve_info = dict(zip(["path_nodes", "dense_index", "delta_ids", "deepest_entry"], info.tolist()))
+        if rc < 0:
+            raise Pre3Error(rc, "debug_resolve_row")
+        return bool(rc), row, walk[: n.value].copy()
 
     # ---- device calls (torch tensors in, nothing out: all results are written in place)
     @staticmethod

@@ -5,6 +5,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/pre3.h"
@@ -12,6 +13,7 @@
 #include "grammar.hpp"
 #include "launch.hpp"
 #include "tables.hpp"
+#include "token_edges.hpp"
 
 using namespace pre3;
 
@@ -22,12 +24,17 @@ struct pre3_handle {
     int stack_cap = 1024;
     EdgeTables T;
     VocabLayout V;
+    TokenEdges E;
     int max_depth = 0;
 
     std::vector<void *> allocations;     // device memory owned by the handle
     DevTables dev{};
     int grid_blocks = 0;
     int32_t *spill = nullptr;
+    DevTokenEdges dev_edges{};
+    bool use_edges = false;
+    int edge_blocks = 0;
+    int32_t *edge_spill = nullptr;
 
     // binding used by pre3_advance
     int32_t *b_states = nullptr, *b_err = nullptr;
@@ -108,6 +115,30 @@ int upload_tables(pre3_handle *h) {
     h->spill = static_cast<int32_t *>(p);
     if ((e = device_alloc(h, sizeof(int32_t), &p, true)) != hipSuccess) return hip_fail(h, e, "allocate fault counter");
     D.fault = static_cast<int32_t *>(p);
+
+    // token-level edges; a vocabulary whose mask row does not fit the kernel's LDS bitmap keeps
+    // the byte-by-byte path
+    if (h->E.enabled && (size_t)h->V.n_words <= edge_kernel_max_lds_words()) {
+        static_assert(sizeof(DevConditionNode) == sizeof(ConditionNode), "node layouts must agree");
+        DevTokenEdges &X = h->dev_edges;
+        std::vector<DevConditionNode> nodes(h->E.nodes.size());
+        std::memcpy(nodes.data(), h->E.nodes.data(), nodes.size() * sizeof(DevConditionNode));
+#define PRE3_UPE(vec, field)                                              \
+    if ((e = upload(h, vec, &X.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
+        PRE3_UPE(h->E.root_of_state, root_of_state);
+        PRE3_UPE(nodes, nodes);
+        PRE3_UPE(h->E.child_state, child_state);
+        PRE3_UPE(h->E.child_node, child_node);
+        PRE3_UPE(h->E.dense_rows, dense_rows);
+        PRE3_UPE(h->E.delta_ids, delta_ids);
+        PRE3_UPE(h->E.walk_ids, walk_ids);
+#undef PRE3_UPE
+        h->edge_blocks = edge_grid_blocks(prop.multiProcessorCount);
+        if ((e = device_alloc(h, edge_spill_entries(h->edge_blocks, h->max_depth) * sizeof(int32_t), &p, false)) != hipSuccess)
+            return hip_fail(h, e, "allocate edge-kernel spill area");
+        h->edge_spill = static_cast<int32_t *>(p);
+        h->use_edges = true;
+    }
     return PRE3_OK;
 }
 
@@ -156,6 +187,12 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
         h->V = build_vocab_layout(vocab->bytes, vocab->offsets, vocab->n_tokens, vocab->eos_id, max_token_len);
         // every input symbol adds at most height_per_byte - 1 private entries (see tables.cpp)
         h->max_depth = std::max(1, h->V.max_len) * (h->T.height_per_byte - 1) + 1;
+        if (!(opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EDGES))) {
+            TokenEdgeLimits lim;
+            if (opt && opt->max_condition_depth > 0) lim.max_known = opt->max_condition_depth;
+            lim.n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+            h->E = build_token_edges(h->T, h->V, lim);
+        }
     } catch (const CompileError &e) {
         return fail(h, e.status, e.text);
     } catch (const std::bad_alloc &) {
@@ -207,8 +244,12 @@ int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, ui
     if (!states || !stacks.data || !stacks.len || !bitmask || stacks.batch < 0 || stacks.cap < 1 ||
         stacks.cap > h->stack_cap)
         return fail(h, PRE3_E_BADARG, "fill_mask: null buffer, negative batch or cap outside 1..stack_cap");
-    hipError_t e = launch_fill_mask_walk(h->dev, states, stacks.data, stacks.len, stacks.cap, stacks.batch, bitmask,
-                                         h->spill, h->grid_blocks, static_cast<hipStream_t>(stream));
+    hipError_t e =
+        h->use_edges
+            ? launch_fill_mask_edges(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap, stacks.batch,
+                                     bitmask, h->edge_spill, h->edge_blocks, static_cast<hipStream_t>(stream))
+            : launch_fill_mask_walk(h->dev, states, stacks.data, stacks.len, stacks.cap, stacks.batch, bitmask,
+                                    h->spill, h->grid_blocks, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_mask");
 }
 
@@ -260,5 +301,33 @@ int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt) {
 }
 
 int32_t pre3_walk_depth_bound(const pre3_handle *h) { return h && h->compiled ? h->max_depth : PRE3_E_BADARG; }
+
+int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]) {
+    if (!h || !h->compiled || !out) return PRE3_E_BADARG;
+    const TokenEdges &E = h->E;
+    out[0] = E.enabled;
+    out[1] = E.n_roots;
+    out[2] = (int64_t)E.nodes.size();
+    out[3] = E.n_dense;
+    out[4] = (int64_t)E.delta_ids.size();
+    out[5] = (int64_t)E.walk_ids.size();
+    out[6] = E.max_known;
+    out[7] = (int64_t)(E.dense_rows.size() * 4 + (E.delta_ids.size() + E.walk_ids.size() + E.child_state.size() * 2 +
+                                                   E.root_of_state.size()) * 4 + E.nodes.size() * sizeof(ConditionNode));
+    return PRE3_OK;
+}
+
+int pre3_debug_resolve_row(const pre3_handle *h, const int32_t *stack, int32_t len, uint32_t *row, int32_t *walk,
+                           int32_t walk_cap, int32_t *n_walk, int32_t *info) {
+    if (!h || !h->compiled || !h->E.enabled || !stack || !row || !walk || !n_walk) return PRE3_E_BADARG;
+    std::vector<int32_t> w;
+    std::memset(row, 0, sizeof(uint32_t) * h->V.n_words);
+    bool ok = resolve_row(h->E, stack, len, row, w, info);
+    *n_walk = (int32_t)w.size();
+    if (!ok) return 0;
+    if ((int32_t)w.size() > walk_cap) return PRE3_E_BADARG;
+    std::copy(w.begin(), w.end(), walk);
+    return 1;
+}
 
 }  // extern "C"

@@ -23,4 +23,17 @@ struct DevTables {
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
 };
 
+// Condition tree of the token-level prefix-conditioned edges (layout in token_edges.hpp).
+struct DevConditionNode {
+    int32_t known, child_begin, child_count, dense_row, delta_begin, delta_count, walk_begin, walk_count;
+};
+
+struct DevTokenEdges {
+    const int32_t *root_of_state;          // [n_states]
+    const DevConditionNode *nodes;
+    const int32_t *child_state, *child_node;
+    const uint32_t *dense_rows;            // [n_dense * n_words]
+    const int32_t *delta_ids, *walk_ids;
+};
+
 }  // namespace pre3

@@ -154,6 +154,128 @@ __global__ __launch_bounds__(kBlock) void fill_mask_walk_kernel(DevTables T, con
     }
 }
 
+
+// Walks token id `t` (bytes in id order) from the stack row[0..len).
+__device__ __forceinline__ bool walk_token_id(const DevTables &T, PrivateStack &priv, int t,
+                                              const int32_t *__restrict__ row, int len, int top0) {
+    if (t == T.eos_id) return walk_end(T, priv, row, len, top0);
+    int base = len, d = 0, top = top0;
+    const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
+    if (hi <= lo) return false;
+    for (int i = lo; i < hi; ++i)
+        if (feed<false>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, row, 0) != kFed) return false;
+    return true;
+}
+
+constexpr int kEdgeBlock = 1024;       // threads per block of the token-edge kernel (one row per block)
+constexpr int kWalkLanes = 256;        // lanes of a block that may walk tokens byte by byte
+constexpr int kMaxPath = 64;           // condition-tree nodes on one descent
+constexpr int kStackWindow = 64;       // top-of-stack entries staged in LDS
+
+// Token mask from the precomputed token-level edges.  One block owns one sequence:
+//   1. the top of the sequence's stack is staged in LDS and wave 0 descends the condition tree,
+//      comparing the stack entry each node asks for with all of the node's condition states
+//      at once (one lane per child, wave ballot);
+//   2. the dense row of the deepest dense node on the path is copied into an LDS bitmap;
+//   3. the delta lists of the nodes after it are ORed in, one lane per token id;
+//   4. tokens the tree leaves undetermined (rare) are walked byte by byte by up to 256 lanes;
+//   5. the bitmap is stored with coalesced writes.
+// A stack the tree has no answer for falls back to walking every token.
+__global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
+    DevTables T, DevTokenEdges E, const int32_t *__restrict__ states, const int32_t *__restrict__ data,
+    const int32_t *__restrict__ len, int cap, int batch, uint32_t *__restrict__ bitmask, int32_t *spill,
+    size_t spill_stride) {
+    extern __shared__ uint32_t bits[];                 // n_words
+    __shared__ int32_t s_stack[kStackWindow];
+    __shared__ int32_t s_path[kMaxPath];
+    __shared__ int32_t s_npath, s_start, s_mode;
+    __shared__ int32_t lds_stack[kLdsDepth * kWalkLanes];
+    const int tid = threadIdx.x;
+    PrivateStack priv;
+    priv.lds = lds_stack + (tid & (kWalkLanes - 1));
+    priv.lds_stride = kWalkLanes;
+    priv.spill = spill + (size_t)blockIdx.x * kWalkLanes + (tid & (kWalkLanes - 1));
+    priv.spill_stride = spill_stride;
+    enum { kFast = 0, kWalkAll = 1, kEmpty = 2 };
+
+    for (int b = blockIdx.x; b < batch; b += gridDim.x) {
+        const int32_t *row = data + (size_t)b * cap;
+        const int n = len[b];
+        const bool done = states[b] < 0;
+        const bool valid = !done && n >= 1 && n <= cap;
+        if (tid < kStackWindow) s_stack[tid] = (valid && n - 1 - tid >= 0) ? row[n - 1 - tid] : -1;
+        __syncthreads();
+        if (tid < 64) {                                // wave 0: descent, uniform across lanes
+            int mode = kFast, npath = 0, start = 0;
+            const int top = s_stack[0];
+            if (!valid || (unsigned)top >= (unsigned)T.n_states) {
+                mode = kEmpty;
+            } else {
+                int node = E.root_of_state[top];
+                for (;;) {
+                    const DevConditionNode nd = E.nodes[node];
+                    if (tid == 0) s_path[npath] = node;
+                    if (nd.dense_row >= 0) start = npath;
+                    ++npath;
+                    if (nd.child_count == 0) {
+                        if (nd.walk_count < 0) mode = kWalkAll;
+                        break;
+                    }
+                    if (nd.known >= n || npath >= kMaxPath) { mode = kWalkAll; break; }
+                    const int x = nd.known < kStackWindow ? s_stack[nd.known] : row[n - 1 - nd.known];
+                    int next = -1;
+                    for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
+                        const int i = c0 + tid;
+                        const bool hit = i < nd.child_count && E.child_state[nd.child_begin + i] == x;
+                        const unsigned long long m = __ballot(hit);
+                        if (m) { next = E.child_node[nd.child_begin + c0 + __ffsll((long long)m) - 1]; break; }
+                    }
+                    if (next < 0) { mode = kWalkAll; break; }
+                    node = next;
+                }
+            }
+            if (tid == 0) { s_npath = npath; s_start = start; s_mode = mode; }
+        }
+        __syncthreads();
+        const int mode = s_mode, npath = s_npath, start = s_start;
+        int dense = -1;
+        if (mode == kFast) dense = E.nodes[s_path[start]].dense_row;
+        if (dense >= 0) {
+            const uint32_t *src = E.dense_rows + (size_t)dense * T.n_words;
+            for (int w = tid; w < T.n_words; w += kEdgeBlock) bits[w] = src[w];
+        } else {
+            for (int w = tid; w < T.n_words; w += kEdgeBlock) bits[w] = 0;
+        }
+        __syncthreads();
+        const int top0 = s_stack[0];
+        if (mode == kFast) {
+            for (int i = start; i < npath; ++i) {
+                const DevConditionNode nd = E.nodes[s_path[i]];
+                for (int k = tid; k < nd.delta_count; k += kEdgeBlock) {
+                    const int t = E.delta_ids[nd.delta_begin + k];
+                    atomicOr(&bits[t >> 5], 1u << (t & 31));
+                }
+            }
+            const DevConditionNode last = E.nodes[s_path[npath - 1]];
+            if (tid < kWalkLanes)
+                for (int k = tid; k < last.walk_count; k += kWalkLanes) {
+                    const int t = E.walk_ids[last.walk_begin + k];
+                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+                }
+        } else if (mode == kWalkAll) {
+            if (tid < kWalkLanes)
+                for (int t = tid; t < T.n_tokens; t += kWalkLanes)
+                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+        } else if (done && tid == 0) {
+            bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
+        }
+        __syncthreads();
+        uint32_t *dst = bitmask + (size_t)b * T.n_words;
+        for (int w = tid; w < T.n_words; w += kEdgeBlock) dst[w] = bits[w];
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------- apply
 
 constexpr uint32_t kNegInfPair = 0xFF80FF80u;
@@ -249,6 +371,22 @@ __global__ __launch_bounds__(64) void advance_kernel(DevTables T, const int32_t 
 }  // namespace
 
 int walk_grid_blocks(int n_compute_units) { return 4 * n_compute_units; }
+int edge_grid_blocks(int n_compute_units) { return 2 * n_compute_units; }
+size_t edge_spill_entries(int grid_blocks, int max_depth) {
+    const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
+    return (size_t)grid_blocks * kWalkLanes * (size_t)deep;
+}
+size_t edge_kernel_max_lds_words() { return (size_t)(64 * 1024 - 24 * 1024) / 4; }
+
+hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, const int32_t *states,
+                                  const int32_t *data, const int32_t *len, int cap, int batch, uint32_t *bitmask,
+                                  int32_t *spill, int grid_blocks, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    const int grid = batch < grid_blocks ? batch : grid_blocks;
+    hipLaunchKernelGGL(fill_mask_edges_kernel, dim3(grid), dim3(kEdgeBlock), (size_t)T.n_words * sizeof(uint32_t),
+                       stream, T, E, states, data, len, cap, batch, bitmask, spill, (size_t)grid_blocks * kWalkLanes);
+    return hipGetLastError();
+}
 size_t walk_spill_entries(int grid_blocks, int max_depth) {
     const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
     return (size_t)grid_blocks * kBlock * (size_t)deep;

@@ -1,0 +1,406 @@
+// Builds the condition tree of token-level prefix-conditioned edges (see token_edges.hpp).
+#include "token_edges.hpp"
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <numeric>
+#include <thread>
+
+namespace pre3 {
+
+namespace {
+
+// ------------------------------------------------------------------ vocabulary trie
+struct Trie {
+    struct Node {
+        int32_t first_child = 0, n_children = 0;
+        int32_t tok_begin = 0, tok_count = 0;   // token ids that end here
+        int32_t col = 0, delta = 0;             // byte class column and target offset of the edge label
+        int32_t sub_tokens = 0;                 // tokens in the whole subtree
+    };
+    std::vector<Node> nodes;                    // nodes[0] = root; nodes[1] = the end-of-input pseudo token
+    std::vector<int32_t> tok_ids;
+};
+
+struct TrieBuilder {
+    const EdgeTables &T;
+    const VocabLayout &V;
+    Trie trie;
+    std::vector<int32_t> order;                 // token ids sorted by byte string
+
+    const uint8_t *str(int t) const { return V.bytes.data() + V.offsets[t]; }
+    int len(int t) const { return V.offsets[t + 1] - V.offsets[t]; }
+
+    TrieBuilder(const EdgeTables &t, const VocabLayout &v) : T(t), V(v) {
+        for (int t2 = 0; t2 < V.n_tokens; ++t2)
+            if (t2 != V.eos_id && len(t2) > 0) order.push_back(t2);
+        std::sort(order.begin(), order.end(), [&](int a, int b) {
+            int la = len(a), lb = len(b);
+            int r = std::memcmp(str(a), str(b), std::min(la, lb));
+            if (r != 0) return r < 0;
+            if (la != lb) return la < lb;
+            return a < b;
+        });
+        trie.nodes.resize(2);
+        // pseudo token: the single symbol '$', carried by the end-of-sequence token id
+        trie.nodes[1].col = T.n_classes;
+        trie.nodes[1].tok_begin = 0;
+        trie.nodes[1].tok_count = 1;
+        trie.nodes[1].sub_tokens = 1;
+        trie.tok_ids.push_back(V.eos_id);
+        build(0, 0, (int)order.size(), 0);
+    }
+
+    // tokens order[lo..hi) share their first `depth` bytes and belong below `node`
+    void build(int node, int lo, int hi, int depth) {
+        int p = lo;
+        trie.nodes[node].tok_begin = (int)trie.tok_ids.size();
+        while (p < hi && len(order[p]) == depth) trie.tok_ids.push_back(order[p++]);
+        trie.nodes[node].tok_count = p - lo;
+        trie.nodes[node].sub_tokens = hi - lo;
+        std::vector<std::pair<int, int>> groups;        // [begin, end) per next byte
+        while (p < hi) {
+            int b = str(order[p])[depth], q = p;
+            while (q < hi && str(order[q])[depth] == b) ++q;
+            groups.push_back({p, q});
+            p = q;
+        }
+        int first = (int)trie.nodes.size();
+        trie.nodes[node].first_child = first;
+        trie.nodes[node].n_children = (int)groups.size();
+        trie.nodes.resize(first + groups.size());
+        for (size_t i = 0; i < groups.size(); ++i) {
+            int b = str(order[groups[i].first])[depth];
+            trie.nodes[first + i].col = T.byte_class[b];
+            trie.nodes[first + i].delta = T.byte_delta[b];
+        }
+        for (size_t i = 0; i < groups.size(); ++i) build(first + (int)i, groups[i].first, groups[i].second, depth + 1);
+    }
+};
+
+// ------------------------------------------------------------- walking on a known suffix
+enum FeedKind { kFedH, kRejectedH, kAcceptedH, kUnderflowH };
+struct FeedOut {
+    FeedKind kind;
+    int need;       // kUnderflowH: the exposed state lies `need` entries below the deepest known one
+    int nt;         // ... and this nonterminal is pushed from it
+};
+
+struct Pending {    // a trie subtree whose verdict depends on stack entries not known yet
+    int32_t trie_node;
+    int32_t need;
+    int32_t nt;
+};
+
+struct BuildNode {
+    int known = 1;
+    int floor = 0;                              // deepest known state
+    std::vector<int32_t> accepted;              // token ids allowed under this node's condition
+    std::vector<Pending> pend;
+    std::vector<std::pair<int32_t, std::unique_ptr<BuildNode>>> children;
+};
+
+struct Walker {
+    const EdgeTables &T;
+    const Trie &trie;
+    const std::vector<std::vector<int32_t>> &pred;
+    const TokenEdgeLimits &lim;
+    std::atomic<int> &node_budget;
+    const int ncol;
+    std::vector<std::vector<int32_t>> pool;     // one scratch stack per trie depth
+
+    Walker(const EdgeTables &t, const Trie &tr, const std::vector<std::vector<int32_t>> &p,
+           const TokenEdgeLimits &l, std::atomic<int> &budget)
+        : T(t), trie(tr), pred(p), lim(l), node_budget(budget), ncol(t.n_classes + 1), pool(300) {}
+
+    int goto_of(int state, int nt) const {
+        int row = T.goto_row[state];
+        return row < 0 ? -1 : T.goto_flat[row + nt];
+    }
+
+    // st[0] is the deepest known state; consumes one symbol
+    FeedOut feed(std::vector<int32_t> &st, int col, int delta) const {
+        for (;;) {
+            uint32_t e = T.edge[(size_t)st.back() * ncol + col];
+            switch (e & kKindMask) {
+                case kError: return {kRejectedH, 0, 0};
+                case kAccept: return {kAcceptedH, 0, 0};
+                case kShift: st.push_back((int32_t)(e >> 2) + delta); return {kFedH, 0, 0};
+                default: break;
+            }
+            int n = (int)((e >> 2) & kMaxPop), nt = (int)(e >> kNtShift);
+            if (n > (int)st.size() - 1) return {kUnderflowH, n - ((int)st.size() - 1), nt};
+            st.resize(st.size() - n);
+            int t = goto_of(st.back(), nt);
+            if (t < 0) return {kRejectedH, 0, 0};
+            st.push_back(t);
+        }
+    }
+
+    // The edge into trie node `c` is fed from `st`; on success the subtree below is explored.
+    void enter(int c, std::vector<int32_t> &st, int depth, BuildNode &out) {
+        const Trie::Node &N = trie.nodes[c];
+        FeedOut r = feed(st, N.col, N.delta);
+        if (r.kind == kUnderflowH) { out.pend.push_back({c, r.need, r.nt}); return; }
+        if (r.kind == kRejectedH) return;
+        // shifted (or, for the end-of-input pseudo token, accepted)
+        for (int i = 0; i < N.tok_count; ++i) out.accepted.push_back(trie.tok_ids[N.tok_begin + i]);
+        if (r.kind == kAcceptedH) return;
+        for (int i = 0; i < N.n_children; ++i) {
+            std::vector<int32_t> &st2 = pool[depth + 1];
+            st2 = st;
+            enter(N.first_child + i, st2, depth + 1, out);
+        }
+    }
+
+    void walk_root(int state, BuildNode &out) {
+        out.known = 1;
+        out.floor = state;
+        const Trie::Node &R = trie.nodes[0];
+        std::vector<int32_t> &st = pool[0];
+        st.assign(1, state);
+        enter(1, st, 0, out);                                   // '$'
+        for (int i = 0; i < R.n_children; ++i) {
+            st.assign(1, state);
+            enter(R.first_child + i, st, 0, out);
+        }
+    }
+
+    // One more stack entry X becomes known below the node that owned `in`.
+    void resolve(int X, const std::vector<Pending> &in, BuildNode &out) {
+        for (const Pending &u : in) {
+            if (u.need > 1) { out.pend.push_back({u.trie_node, u.need - 1, u.nt}); continue; }
+            int t = goto_of(X, u.nt);
+            if (t < 0) continue;
+            std::vector<int32_t> &st = pool[0];
+            st.clear();
+            st.push_back(X);
+            st.push_back(t);
+            enter(u.trie_node, st, 0, out);
+        }
+    }
+
+    void expand(BuildNode &nd) {
+        while (!nd.pend.empty()) {
+            const std::vector<int32_t> &ps = pred[nd.floor];
+            if (ps.empty()) { nd.pend.clear(); return; }        // the bottom of a stack is never popped
+            if (nd.known >= lim.max_known) return;              // left to the run-time walk
+            if (ps.size() == 1) {                               // only one stack can lie below: no test needed
+                std::vector<Pending> in;
+                in.swap(nd.pend);
+                resolve(ps[0], in, nd);
+                nd.floor = ps[0];
+                nd.known++;
+                continue;
+            }
+            if (node_budget.fetch_sub((int)ps.size()) < (int)ps.size()) return;
+            for (int X : ps) {
+                std::unique_ptr<BuildNode> ch(new BuildNode());
+                ch->known = nd.known + 1;
+                ch->floor = X;
+                resolve(X, nd.pend, *ch);
+                expand(*ch);
+                nd.children.emplace_back(X, std::move(ch));
+            }
+            nd.pend.clear();
+            return;
+        }
+    }
+};
+
+// ----------------------------------------------------------------------- flattening
+struct Flattener {
+    const Trie &trie;
+    const TokenEdgeLimits &lim;
+    TokenEdges &E;
+    int dense_threshold;
+
+    void subtree_tokens(int c, std::vector<int32_t> &out) const {
+        const Trie::Node &N = trie.nodes[c];
+        for (int i = 0; i < N.tok_count; ++i) out.push_back(trie.tok_ids[N.tok_begin + i]);
+        for (int i = 0; i < N.n_children; ++i) subtree_tokens(N.first_child + i, out);
+    }
+
+    // `base` = dense row of the nearest dense ancestor (or null), `since` = ids accepted after it
+    int flatten(const BuildNode &b, const uint32_t *base, std::vector<int32_t> &since) {
+        int idx = (int)E.nodes.size();
+        E.nodes.push_back(ConditionNode{});
+        ConditionNode n{};
+        n.known = b.known;
+        n.dense_row = -1;
+        E.max_known = std::max<int64_t>(E.max_known, b.known);
+        size_t since_mark = since.size();
+        std::vector<uint32_t> own_row;
+        const bool dense = (int)b.accepted.size() >= dense_threshold &&
+                           (int64_t)E.dense_rows.size() + E.n_words <= lim.max_dense_words;
+        if (dense) {
+            n.dense_row = (int)(E.dense_rows.size() / E.n_words);
+            own_row.assign(E.n_words, 0);
+            if (base) std::memcpy(own_row.data(), base, sizeof(uint32_t) * E.n_words);
+            for (int32_t t : since) own_row[t >> 5] |= 1u << (t & 31);
+            for (int32_t t : b.accepted) own_row[t >> 5] |= 1u << (t & 31);
+            E.dense_rows.insert(E.dense_rows.end(), own_row.begin(), own_row.end());
+            E.n_dense++;
+            n.delta_begin = (int)E.delta_ids.size();
+            n.delta_count = 0;
+        } else {
+            n.delta_begin = (int)E.delta_ids.size();
+            n.delta_count = (int)b.accepted.size();
+            E.delta_ids.insert(E.delta_ids.end(), b.accepted.begin(), b.accepted.end());
+            since.insert(since.end(), b.accepted.begin(), b.accepted.end());
+        }
+        // tokens left undetermined when the tree ends here
+        n.walk_begin = (int)E.walk_ids.size();
+        n.walk_count = 0;
+        if (b.children.empty() && !b.pend.empty()) {
+            int64_t total = 0;
+            for (const Pending &u : b.pend) total += trie.nodes[u.trie_node].sub_tokens;
+            if (total > lim.max_walk) {
+                n.walk_count = -1;
+            } else {
+                std::vector<int32_t> ids;
+                for (const Pending &u : b.pend) subtree_tokens(u.trie_node, ids);
+                n.walk_count = (int)ids.size();
+                E.walk_ids.insert(E.walk_ids.end(), ids.begin(), ids.end());
+            }
+        }
+        // children, sorted by condition state; their records are laid out after all of them exist
+        std::vector<std::pair<int32_t, int32_t>> kids;
+        {
+            std::vector<int32_t> empty_since;
+            for (const auto &ch : b.children) {
+                int ci = dense ? flatten(*ch.second, own_row.data(), empty_since) : flatten(*ch.second, base, since);
+                empty_since.clear();
+                kids.push_back({ch.first, ci});
+            }
+        }
+        std::sort(kids.begin(), kids.end());
+        n.child_begin = (int)E.child_state.size();
+        n.child_count = (int)kids.size();
+        for (auto &k : kids) { E.child_state.push_back(k.first); E.child_node.push_back(k.second); }
+        since.resize(since_mark);
+        E.nodes[idx] = n;
+        return idx;
+    }
+};
+
+}  // namespace
+
+TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const TokenEdgeLimits &lim) {
+    TokenEdges E;
+    E.enabled = true;
+    E.n_words = V.n_words;
+    TrieBuilder tb(T, V);
+    const Trie &trie = tb.trie;
+    const int ncol = T.n_classes + 1;
+
+    // predecessors: every p with a transition (acceptance edge or goto) into s
+    std::vector<std::vector<int32_t>> pred(T.n_states);
+    for (int g = 0; g < T.n_grammars; ++g) {
+        const Lr1Automaton &A = T.automata[g];
+        const int off = T.state_offset[g];
+        for (int s = 0; s < A.n_states; ++s) {
+            for (int a = 0; a < 256; ++a) {
+                uint32_t act = A.action[(size_t)s * kNumTerminals + a];
+                if ((act & 3u) == kShift) pred[off + (act >> 2)].push_back(off + s);
+            }
+            for (int nt = 0; nt < A.n_nt; ++nt) {
+                int t = A.go[(size_t)s * A.n_nt + nt];
+                if (t >= 0) pred[off + t].push_back(off + s);
+            }
+        }
+    }
+    for (auto &p : pred) {
+        std::sort(p.begin(), p.end());
+        p.erase(std::unique(p.begin(), p.end()), p.end());
+    }
+
+    // states with identical edges, goto row and predecessors share one root
+    std::map<std::tuple<std::vector<uint32_t>, int32_t, std::vector<int32_t>>, int> root_ids;
+    std::vector<int> root_state;
+    std::vector<int> root_index(T.n_states);
+    for (int s = 0; s < T.n_states; ++s) {
+        std::vector<uint32_t> row(T.edge.begin() + (size_t)s * ncol, T.edge.begin() + (size_t)(s + 1) * ncol);
+        auto ins = root_ids.emplace(std::make_tuple(std::move(row), T.goto_row[s], pred[s]), (int)root_state.size());
+        if (ins.second) root_state.push_back(s);
+        root_index[s] = ins.first->second;
+    }
+    E.n_roots = (int64_t)root_state.size();
+
+    std::vector<std::unique_ptr<BuildNode>> roots(root_state.size());
+    std::atomic<int> node_budget(lim.max_nodes);
+    std::atomic<size_t> next(0);
+    auto worker = [&]() {
+        Walker w(T, trie, pred, lim, node_budget);
+        for (;;) {
+            size_t i = next.fetch_add(1);
+            if (i >= roots.size()) return;
+            roots[i].reset(new BuildNode());
+            w.walk_root(root_state[i], *roots[i]);
+            w.expand(*roots[i]);
+        }
+    };
+    int n_threads = std::max(1, std::min<int>(lim.n_threads, (int)roots.size()));
+    std::vector<std::thread> pool;
+    for (int i = 1; i < n_threads; ++i) pool.emplace_back(worker);
+    worker();
+    for (auto &t : pool) t.join();
+
+    Flattener F{trie, lim, E, std::max(64, V.n_words)};
+    std::vector<int> root_node(roots.size());
+    for (size_t i = 0; i < roots.size(); ++i) {
+        std::vector<int32_t> since;
+        root_node[i] = F.flatten(*roots[i], nullptr, since);
+        roots[i].reset();
+    }
+    E.root_of_state.resize(T.n_states);
+    for (int s = 0; s < T.n_states; ++s) E.root_of_state[s] = root_node[root_index[s]];
+    return E;
+}
+
+bool resolve_row(const TokenEdges &E, const int32_t *stack, int len, uint32_t *row, std::vector<int32_t> &walk,
+                 int32_t *info) {
+    if (len < 1 || stack[len - 1] < 0 || stack[len - 1] >= (int)E.root_of_state.size()) return false;
+    int node = E.root_of_state[stack[len - 1]];
+    std::vector<int> path;
+    for (;;) {
+        path.push_back(node);
+        const ConditionNode &n = E.nodes[node];
+        if (n.child_count == 0) break;
+        if (n.known >= len) return false;
+        int x = stack[len - 1 - n.known], next = -1;
+        for (int i = 0; i < n.child_count; ++i)
+            if (E.child_state[n.child_begin + i] == x) next = E.child_node[n.child_begin + i];
+        if (next < 0) return false;
+        node = next;
+    }
+    int start = 0;
+    for (int i = (int)path.size() - 1; i >= 0; --i)
+        if (E.nodes[path[i]].dense_row >= 0) { start = i; break; }
+    const ConditionNode &first = E.nodes[path[start]];
+    if (first.dense_row >= 0)
+        for (int w = 0; w < E.n_words; ++w) row[w] |= E.dense_rows[(size_t)first.dense_row * E.n_words + w];
+    for (size_t i = start; i < path.size(); ++i) {
+        const ConditionNode &n = E.nodes[path[i]];
+        for (int k = 0; k < n.delta_count; ++k) {
+            int t = E.delta_ids[n.delta_begin + k];
+            row[t >> 5] |= 1u << (t & 31);
+        }
+    }
+    const ConditionNode &last = E.nodes[path.back()];
+    if (info) {
+        info[0] = (int32_t)path.size();
+        info[1] = start;
+        info[2] = 0;
+        for (size_t i = start; i < path.size(); ++i) info[2] += E.nodes[path[i]].delta_count;
+        info[3] = last.known;
+    }
+    if (last.walk_count < 0) return false;
+    for (int k = 0; k < last.walk_count; ++k) walk.push_back(E.walk_ids[last.walk_begin + k]);
+    return true;
+}
+
+}  // namespace pre3

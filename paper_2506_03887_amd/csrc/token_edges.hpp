@@ -1,0 +1,73 @@
+// Token-level prefix-conditioned edges (paper Sec. 3.1 and Sec. 3.3 "edge merging").
+//
+// Along the bytes of one vocabulary token the per-byte edges of the DPDA are merged into a
+// single multi-byte "jump" edge.  Its stack-matching condition is the sequence of states that
+// the walk would read from the sequence's stack: the top state, then deeper entries as
+// reductions expose them.  Because every edge is known when the grammar is compiled, all
+// feasible conditions can be enumerated ahead of time by following the automaton's
+// transitions backwards from a state (Sec. 3.2.2: a reduction edge backtracks along the path
+// it was reached by).  The result is a condition tree:
+//
+//   root  = a top state (states with identical edges and predecessors share a root)
+//   child = one more known stack entry below the ones already known, chosen among the
+//           predecessors of the deepest known state
+//   node  = the tokens whose merged edge exists (token allowed) for EVERY stack that matches
+//           the node's condition and that were still undetermined at the parent ("delta"),
+//           and, where the tree was not expanded further, the tokens that are still
+//           undetermined ("walk" list: the kernel walks those byte by byte).
+//
+// A token rejected for every matching stack simply appears nowhere.  At run time a sequence
+// descends the tree by comparing its stack entries with the children's condition states, ORs
+// the deltas on its path and walks the few tokens left.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "tables.hpp"
+
+namespace pre3 {
+
+struct ConditionNode {
+    int32_t known;          // stack entries (from the top) fixed by this node's condition
+    int32_t child_begin;    // children in child_state/child_node[child_begin .. +child_count)
+    int32_t child_count;    // they are told apart by the state at depth `known` below the top
+    int32_t dense_row;      // >= 0: dense_rows[dense_row * n_words ..] holds every token allowed at
+                            // this node or at an ancestor; -1: none
+    int32_t delta_begin;    // token ids allowed here and not at an ancestor
+    int32_t delta_count;
+    int32_t walk_begin;     // token ids left undetermined if the descent ends here;
+    int32_t walk_count;     // -1: too many, walk the whole vocabulary
+};
+
+struct TokenEdges {
+    bool enabled = false;
+    int n_words = 0;
+    std::vector<int32_t> root_of_state;       // [n_states]
+    std::vector<ConditionNode> nodes;
+    std::vector<int32_t> child_state, child_node;
+    std::vector<uint32_t> dense_rows;
+    std::vector<int32_t> delta_ids, walk_ids;
+    // statistics
+    int64_t n_roots = 0, max_known = 0, n_dense = 0;
+};
+
+struct TokenEdgeLimits {
+    int max_nodes = 1 << 18;          // condition-tree nodes
+    int max_known = 48;               // deepest stack entry a condition may test
+    int max_walk = 2048;              // longest walk list kept per node (longer: whole vocabulary)
+    int64_t max_dense_words = (int64_t)1 << 28;   // 1 GiB of dense rows
+    int n_threads = 8;
+};
+
+TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const TokenEdgeLimits &lim);
+
+// Host-side evaluation of the condition tree for one stack (tests and tools): ORs into `row`
+// (n_words words) every token the tree determines as allowed and appends to `walk` the tokens
+// it leaves undetermined.  Returns false if the tree has no answer for this stack (the kernel
+// then walks the whole vocabulary).
+// info (optional, 4 ints): nodes on the path, index of the dense node used, delta ids ORed, deepest
+// stack entry tested.
+bool resolve_row(const TokenEdges &E, const int32_t *stack, int len, uint32_t *row, std::vector<int32_t> &walk,
+                 int32_t *info = nullptr);
+
+}  // namespace pre3

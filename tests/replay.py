@@ -8,13 +8,13 @@ from workloads import configs, trajectory
 from workloads.vocab import bf16_logits
 
 
-def make_library(cfg):
+def make_library(cfg, **kw):
     from paper_2506_03887_amd import Pre3
     v = cfg.vocab
-    return Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cfg.cap)
+    return Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cfg.cap, **kw)
 
 
-def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, log=print):
+def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, log=print, **lib_options):
     """Runs `steps` decode steps of config `cfg_idx` on the GPU through the C ABI and checks,
     against the oracle on the same inputs:
       - states, len, live stack entries and err of every sequence after every advance;
@@ -35,7 +35,8 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
                                cfg.json_strings, depths)
     log(f"[cfg {cfg_idx}] trajectory of {steps} steps in {time.time() - t0:.1f}s; "
         f"{int(traj.reset.sum())} resets, {int((traj.tokens == v.eos_id).sum())} EOS", flush=True)
-    lib = make_library(cfg)
+    lib = make_library(cfg, **lib_options)
+    log(f"[cfg {cfg_idx}] token edges: {lib.token_edge_stats()}", flush=True)
     dev = torch.device("cuda:0")
     B, cap, W, V = cfg.batch, cfg.cap, v.words, v.n_tokens
 

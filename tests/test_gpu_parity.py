@@ -18,6 +18,22 @@ def test_cfg2_json_all_steps():
     assert r["full_masks"] == 128
 
 
+def test_cfg1_byte_by_byte_path():
+    """Same workload with the token-level edges switched off: every pair is walked."""
+    assert replay(1, token_edges=False)["full_masks"] == 32
+
+
+def test_cfg2_byte_by_byte_path():
+    assert replay(2, steps=24, token_edges=False)["full_masks"] == 24
+
+
+@pytest.mark.parametrize("depth", [1, 2, 4])
+def test_cfg2_shallow_conditions_leave_tokens_to_the_walk(depth):
+    """Conditions limited to a few stack entries: the tree leaves walk lists (and, at depth 1,
+    whole rows) to the byte-by-byte walk inside the edge kernel."""
+    assert replay(2, steps=16, max_condition_depth=depth)["full_masks"] == 16
+
+
 def test_cfg3_json_full_size():
     """B=256, V=128256, 256 steps: states/stacks on every step, the whole bitmask and masked
     logits on 6 steps spread over the run, two full mask rows on every other step."""
