@@ -143,6 +143,15 @@ int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, ui
 int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batch, int32_t vocab,
                     int64_t row_stride, pre3_stream stream);
 
+/* pre3_fill_mask followed by pre3_apply_mask on the same rows, as one call: the mask of each
+ * row segment is applied to the logits while it is still on chip, so the bitmask is not read
+ * back from memory (Sec. 1: mask computation and masking belong to the same decode step).
+ * Results are exactly those of the two calls in sequence: bitmask as pre3_fill_mask writes it,
+ * logits (device, [batch, >= n_tokens], row_stride elements between rows) as pre3_apply_mask
+ * leaves them.  Errors: BADARG. */
+int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
+                         uint16_t *logits_bf16, int64_t row_stride, pre3_stream stream);
+
 /* Advances every bound sequence by its sampled token (Sec. 3.2.2: acceptance edges push,
  * reduction edges match, pop and push).  tokens: device [batch]; tokens[b] < 0 skips b.
  * The EOS token, where allowed, sets states[b] = PRE3_STATE_DONE and leaves the stack

@@ -22,7 +22,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row",
 ]
@@ -69,6 +69,7 @@ def load():
     lib.pre3_bind_state.argtypes = [vp, vp, _Stacks, vp]
     lib.pre3_fill_mask.argtypes = [vp, vp, _Stacks, vp, vp]
     lib.pre3_apply_mask.argtypes = [vp, vp, i32, i32, c.c_int64, vp]
+    lib.pre3_fill_apply_mask.argtypes = [vp, vp, _Stacks, vp, vp, c.c_int64, vp]
     lib.pre3_advance.argtypes = [vp, vp, vp]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
         getattr(lib, name).argtypes = [vp]
@@ -200,6 +201,13 @@ class Pre3:
         assert bitmask.is_contiguous() and tuple(bitmask.shape) == (data.shape[0], self.words)
         self._check(self._lib.pre3_fill_mask(self._h, _dev(states, "i32"), self._stacks(data, length),
                                              _dev(bitmask, "u32"), _stream_ptr(stream)))
+
+    def fill_apply_mask(self, states, data, length, bitmask, logits, stream=None):
+        assert bitmask.is_contiguous() and tuple(bitmask.shape) == (data.shape[0], self.words)
+        assert logits.dim() == 2 and logits.stride(1) == 1 and logits.shape[0] == data.shape[0]
+        self._check(self._lib.pre3_fill_apply_mask(self._h, _dev(states, "i32"), self._stacks(data, length),
+                                                   _dev(bitmask, "u32"), _dev(logits, "u16"), logits.stride(0),
+                                                   _stream_ptr(stream)))
 
     def advance(self, tokens, stream=None):
         assert tokens.is_contiguous()

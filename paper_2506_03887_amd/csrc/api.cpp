@@ -125,11 +125,19 @@ int upload_tables(pre3_handle *h) {
         std::memcpy(nodes.data(), h->E.nodes.data(), nodes.size() * sizeof(DevConditionNode));
 #define PRE3_UPE(vec, field)                                              \
     if ((e = upload(h, vec, &X.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
-        PRE3_UPE(h->E.root_of_state, root_of_state);
+        std::vector<DevConditionNode> roots(h->E.root_of_state.size());
+        for (size_t i = 0; i < roots.size(); ++i) roots[i] = nodes[h->E.root_of_state[i]];
+        std::vector<int2> pairs(h->E.child_state.size());
+        for (size_t i = 0; i < pairs.size(); ++i) pairs[i] = make_int2(h->E.child_state[i], h->E.child_node[i]);
+        const int stride = edge_row_stride_words(h->V.n_words);
+        std::vector<uint32_t> dense((size_t)h->E.n_dense * stride, 0);
+        for (int64_t r = 0; r < h->E.n_dense; ++r)
+            std::memcpy(&dense[(size_t)r * stride], &h->E.dense_rows[(size_t)r * h->V.n_words],
+                        sizeof(uint32_t) * h->V.n_words);
+        PRE3_UPE(roots, root_nodes);
         PRE3_UPE(nodes, nodes);
-        PRE3_UPE(h->E.child_state, child_state);
-        PRE3_UPE(h->E.child_node, child_node);
-        PRE3_UPE(h->E.dense_rows, dense_rows);
+        PRE3_UPE(pairs, child_pairs);
+        PRE3_UPE(dense, dense_rows);
         PRE3_UPE(h->E.delta_ids, delta_ids);
         PRE3_UPE(h->E.walk_ids, walk_ids);
 #undef PRE3_UPE
@@ -247,10 +255,30 @@ int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, ui
     hipError_t e =
         h->use_edges
             ? launch_fill_mask_edges(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap, stacks.batch,
-                                     bitmask, h->edge_spill, h->edge_blocks, static_cast<hipStream_t>(stream))
+                                     bitmask, nullptr, 0, h->edge_spill, h->edge_blocks,
+                                     static_cast<hipStream_t>(stream))
             : launch_fill_mask_walk(h->dev, states, stacks.data, stacks.len, stacks.cap, stacks.batch, bitmask,
                                     h->spill, h->grid_blocks, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_mask");
+}
+
+int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
+                         uint16_t *logits, int64_t row_stride, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (!states || !stacks.data || !stacks.len || !bitmask || !logits || stacks.batch < 0 || stacks.cap < 1 ||
+        stacks.cap > h->stack_cap || row_stride < h->V.n_tokens)
+        return fail(h, PRE3_E_BADARG, "fill_apply_mask: null buffer, negative batch, bad cap or row_stride < vocabulary");
+    if (reinterpret_cast<uintptr_t>(logits) % 2 != 0) return fail(h, PRE3_E_BADARG, "fill_apply_mask: misaligned logits");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool fused = h->use_edges && reinterpret_cast<uintptr_t>(logits) % 16 == 0 && row_stride % 8 == 0;
+    if (fused) {
+        hipError_t e = launch_fill_mask_edges(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap,
+                                              stacks.batch, bitmask, logits, row_stride, h->edge_spill, h->edge_blocks, s);
+        return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_apply_mask");
+    }
+    int rc = pre3_fill_mask(h, states, stacks, bitmask, stream);
+    if (rc != PRE3_OK) return rc;
+    return pre3_apply_mask(logits, bitmask, stacks.batch, h->V.n_tokens, row_stride, stream);
 }
 
 int pre3_apply_mask(uint16_t *logits, const uint32_t *bitmask, int32_t batch, int32_t vocab, int64_t row_stride,

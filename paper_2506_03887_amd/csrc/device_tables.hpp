@@ -1,5 +1,7 @@
 // Plain-pointer view of the uploaded tables, passed to kernels by value.
 #pragma once
+#include <hip/hip_runtime_api.h>
+
 #include <cstdint>
 
 namespace pre3 {
@@ -29,10 +31,10 @@ struct DevConditionNode {
 };
 
 struct DevTokenEdges {
-    const int32_t *root_of_state;          // [n_states]
+    const DevConditionNode *root_nodes;    // [n_states] copy of each state's root record
     const DevConditionNode *nodes;
-    const int32_t *child_state, *child_node;
-    const uint32_t *dense_rows;            // [n_dense * n_words]
+    const int2 *child_pairs;               // (condition state, child node), sorted by state per node
+    const uint32_t *dense_rows;            // [n_dense * stride], stride = n_words rounded up to 4
     const int32_t *delta_ids, *walk_ids;
 };
 

@@ -167,28 +167,38 @@ __device__ __forceinline__ bool walk_token_id(const DevTables &T, PrivateStack &
     return true;
 }
 
-constexpr int kEdgeBlock = 1024;       // threads per block of the token-edge kernel (one row per block)
-constexpr int kWalkLanes = 256;        // lanes of a block that may walk tokens byte by byte
-constexpr int kMaxPath = 64;           // condition-tree nodes on one descent
-constexpr int kStackWindow = 64;       // top-of-stack entries staged in LDS
+constexpr int kEdgeBlock = 256;        // threads per block of the token-edge kernel
+constexpr int kWalkLanes = 64;         // lanes of a block that may walk tokens byte by byte
+constexpr int kMaxPath = 64;           // delta lists ORed on one descent
+constexpr uint32_t kNegInfPair = 0xFF80FF80u;
 
-// Token mask from the precomputed token-level edges.  One block owns one sequence:
-//   1. the top of the sequence's stack is staged in LDS and wave 0 descends the condition tree,
-//      comparing the stack entry each node asks for with all of the node's condition states
-//      at once (one lane per child, wave ballot);
-//   2. the dense row of the deepest dense node on the path is copied into an LDS bitmap;
+// Token mask from the precomputed token-level edges, optionally fused with the masking of the
+// logits.  A work item is one segment (a run of mask words) of one sequence's row; blocks loop
+// over items.  Per item:
+//   1. wave 0 descends the condition tree.  Lane j holds the stack entry j below the top; each
+//      node names the entry it tests, and all of the node's condition states are compared
+//      with it at once (one lane per child, wave ballot).  The root is fetched from states[b]
+//      while the stack is still loading and re-fetched if the stack's top disagrees;
+//   2. the segment of the dense row of the deepest dense node on the path is copied into an
+//      LDS bitmap;
 //   3. the delta lists of the nodes after it are ORed in, one lane per token id;
-//   4. tokens the tree leaves undetermined (rare) are walked byte by byte by up to 256 lanes;
-//   5. the bitmap is stored with coalesced writes.
-// A stack the tree has no answer for falls back to walking every token.
+//   4. tokens the tree leaves undetermined (rare) are walked byte by byte by one wave;
+//   5. the bitmap segment is stored with coalesced writes and, when fused, applied to the
+//      segment's logits straight from LDS (allowed groups untouched, masked groups
+//      overwritten unread, mixed groups read, patched and written back).
+// A stack the tree has no answer for falls back to walking every token of the segment.
+// Items are numbered so that the segments of one row run on the same XCD (blocks are dealt
+// round-robin to the 8 XCDs) and share that XCD's L2 for the row's table reads.
+template <bool kApply>
 __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
     DevTables T, DevTokenEdges E, const int32_t *__restrict__ states, const int32_t *__restrict__ data,
-    const int32_t *__restrict__ len, int cap, int batch, uint32_t *__restrict__ bitmask, int32_t *spill,
+    const int32_t *__restrict__ len, int cap, int batch, uint32_t *__restrict__ bitmask,
+    uint16_t *__restrict__ logits, int64_t row_stride, int n_seg, int seg_vec, int32_t *spill,
     size_t spill_stride) {
-    extern __shared__ uint32_t bits[];                 // n_words
-    __shared__ int32_t s_stack[kStackWindow];
-    __shared__ int32_t s_path[kMaxPath];
-    __shared__ int32_t s_npath, s_start, s_mode;
+    extern __shared__ uint4 bits4[];                   // seg_vec
+    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
+    __shared__ int32_t s_seg_begin[kMaxPath], s_seg_count[kMaxPath];
+    __shared__ int32_t s_nseg, s_dense, s_mode, s_walk_begin, s_walk_count, s_top, s_len;
     __shared__ int32_t lds_stack[kLdsDepth * kWalkLanes];
     const int tid = threadIdx.x;
     PrivateStack priv;
@@ -196,120 +206,216 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
     priv.lds_stride = kWalkLanes;
     priv.spill = spill + (size_t)blockIdx.x * kWalkLanes + (tid & (kWalkLanes - 1));
     priv.spill_stride = spill_stride;
-    enum { kFast = 0, kWalkAll = 1, kEmpty = 2 };
+    enum { kFast = 0, kWalkAll = 1, kEmpty = 2, kDone = 3 };
+    const int n_vec = (T.n_words + 3) >> 2;
+    const int rows_padded = (batch + 7) & ~7;
+    const int n_items = rows_padded * n_seg;
 
-    for (int b = blockIdx.x; b < batch; b += gridDim.x) {
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        // blocks i, i+8, i+16, ... share an XCD: give them the segments of the same rows
+        const int xcd = item & 7, slot = item >> 3;
+        const int seg = slot % n_seg, b = (slot / n_seg) * 8 + xcd;
+        if (b >= batch) continue;                      // uniform for the block
         const int32_t *row = data + (size_t)b * cap;
-        const int n = len[b];
-        const bool done = states[b] < 0;
-        const bool valid = !done && n >= 1 && n <= cap;
-        if (tid < kStackWindow) s_stack[tid] = (valid && n - 1 - tid >= 0) ? row[n - 1 - tid] : -1;
-        __syncthreads();
         if (tid < 64) {                                // wave 0: descent, uniform across lanes
-            int mode = kFast, npath = 0, start = 0;
-            const int top = s_stack[0];
-            if (!valid || (unsigned)top >= (unsigned)T.n_states) {
+            const int st = states[b];
+            const int n = len[b];
+            int mode = kFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0, top = -1;
+            if (st < 0) {
+                mode = kDone;
+            } else if (n < 1 || n > cap) {
                 mode = kEmpty;
             } else {
-                int node = E.root_of_state[top];
-                for (;;) {
-                    const DevConditionNode nd = E.nodes[node];
-                    if (tid == 0) s_path[npath] = node;
-                    if (nd.dense_row >= 0) start = npath;
-                    ++npath;
-                    if (nd.child_count == 0) {
-                        if (nd.walk_count < 0) mode = kWalkAll;
-                        break;
+                DevConditionNode nd{};
+                const bool guess = (unsigned)st < (unsigned)T.n_states;
+                if (guess) nd = E.root_nodes[st];      // overlaps the stack load below
+                const int xj = n - 1 - tid >= 0 ? row[n - 1 - tid] : -1;
+                top = __shfl(xj, 0);
+                if ((unsigned)top >= (unsigned)T.n_states) {
+                    mode = kEmpty;
+                } else {
+                    if (!guess || top != st) nd = E.root_nodes[top];
+                    for (;;) {
+                        if (nd.dense_row >= 0) {       // holds everything allowed so far on this path
+                            dense = nd.dense_row;
+                            nseg = 0;
+                        } else if (nd.delta_count > 0) {
+                            if (tid == 0) { s_seg_begin[nseg] = nd.delta_begin; s_seg_count[nseg] = nd.delta_count; }
+                            ++nseg;
+                        }
+                        if (nd.child_count == 0) {
+                            walk_begin = nd.walk_begin;
+                            walk_count = nd.walk_count;
+                            if (walk_count < 0) mode = kWalkAll;
+                            break;
+                        }
+                        if (nd.known >= n || nseg >= kMaxPath) { mode = kWalkAll; break; }
+                        const int x = nd.known < 64 ? __shfl(xj, nd.known) : row[n - 1 - nd.known];
+                        int next = -1;
+                        for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
+                            const int i = c0 + tid;
+                            int2 pr = make_int2(-2, -1);
+                            if (i < nd.child_count) pr = E.child_pairs[nd.child_begin + i];
+                            const unsigned long long m = __ballot(pr.x == x);
+                            if (m) { next = __shfl(pr.y, __ffsll((long long)m) - 1); break; }
+                        }
+                        if (next < 0) { mode = kWalkAll; break; }
+                        nd = E.nodes[next];
                     }
-                    if (nd.known >= n || npath >= kMaxPath) { mode = kWalkAll; break; }
-                    const int x = nd.known < kStackWindow ? s_stack[nd.known] : row[n - 1 - nd.known];
-                    int next = -1;
-                    for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
-                        const int i = c0 + tid;
-                        const bool hit = i < nd.child_count && E.child_state[nd.child_begin + i] == x;
-                        const unsigned long long m = __ballot(hit);
-                        if (m) { next = E.child_node[nd.child_begin + c0 + __ffsll((long long)m) - 1]; break; }
-                    }
-                    if (next < 0) { mode = kWalkAll; break; }
-                    node = next;
                 }
             }
-            if (tid == 0) { s_npath = npath; s_start = start; s_mode = mode; }
+            if (tid == 0) {
+                s_nseg = nseg; s_dense = dense; s_mode = mode; s_top = top; s_len = n;
+                s_walk_begin = walk_begin; s_walk_count = walk_count;
+            }
         }
         __syncthreads();
-        const int mode = s_mode, npath = s_npath, start = s_start;
-        int dense = -1;
-        if (mode == kFast) dense = E.nodes[s_path[start]].dense_row;
-        if (dense >= 0) {
-            const uint32_t *src = E.dense_rows + (size_t)dense * T.n_words;
-            for (int w = tid; w < T.n_words; w += kEdgeBlock) bits[w] = src[w];
+        const int mode = s_mode;
+        const int v_lo = seg * seg_vec;                                    // first uint4 of the segment
+        const int v_cnt = min(seg_vec, n_vec - v_lo);                      // may be <= 0 for a trailing segment
+        const int w_lo = v_lo * 4, w_hi = w_lo + max(v_cnt, 0) * 4;        // mask words [w_lo, w_hi)
+        if (mode == kFast && s_dense >= 0) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)s_dense * n_vec + v_lo;
+            for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = src[w];
         } else {
-            for (int w = tid; w < T.n_words; w += kEdgeBlock) bits[w] = 0;
+            for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = make_uint4(0, 0, 0, 0);
         }
         __syncthreads();
-        const int top0 = s_stack[0];
         if (mode == kFast) {
-            for (int i = start; i < npath; ++i) {
-                const DevConditionNode nd = E.nodes[s_path[i]];
-                for (int k = tid; k < nd.delta_count; k += kEdgeBlock) {
-                    const int t = E.delta_ids[nd.delta_begin + k];
-                    atomicOr(&bits[t >> 5], 1u << (t & 31));
+            const int nseg = s_nseg;
+            for (int i = 0; i < nseg; ++i) {
+                const int32_t *ids = E.delta_ids + s_seg_begin[i];
+                const int cnt = s_seg_count[i];
+                for (int k = tid; k < cnt; k += kEdgeBlock) {
+                    const int t = ids[k], w = t >> 5;
+                    if (w >= w_lo && w < w_hi) atomicOr(&bits[w - w_lo], 1u << (t & 31));
                 }
             }
-            const DevConditionNode last = E.nodes[s_path[npath - 1]];
-            if (tid < kWalkLanes)
-                for (int k = tid; k < last.walk_count; k += kWalkLanes) {
-                    const int t = E.walk_ids[last.walk_begin + k];
-                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+            const int wc = s_walk_count;
+            if (wc > 0 && tid < kWalkLanes) {
+                const int n = s_len, top0 = s_top;
+                for (int k = tid; k < wc; k += kWalkLanes) {
+                    const int t = E.walk_ids[s_walk_begin + k], w = t >> 5;
+                    if (w >= w_lo && w < w_hi && walk_token_id(T, priv, t, row, n, top0))
+                        atomicOr(&bits[w - w_lo], 1u << (t & 31));
                 }
+            }
         } else if (mode == kWalkAll) {
-            if (tid < kWalkLanes)
-                for (int t = tid; t < T.n_tokens; t += kWalkLanes)
-                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
-        } else if (done && tid == 0) {
-            bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
+            if (tid < kWalkLanes) {
+                const int n = s_len, top0 = s_top;
+                const int t_hi = min(T.n_tokens, w_hi * 32);
+                for (int t = w_lo * 32 + tid; t < t_hi; t += kWalkLanes)
+                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[(t >> 5) - w_lo], 1u << (t & 31));
+            }
+        } else if (mode == kDone && tid == 0) {
+            const int w = T.eos_id >> 5;
+            if (w >= w_lo && w < w_hi) bits[w - w_lo] = 1u << (T.eos_id & 31);
         }
         __syncthreads();
         uint32_t *dst = bitmask + (size_t)b * T.n_words;
-        for (int w = tid; w < T.n_words; w += kEdgeBlock) dst[w] = bits[w];
+        if ((T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0) {
+            uint4 *dst4 = reinterpret_cast<uint4 *>(dst) + v_lo;
+            for (int w = tid; w < v_cnt; w += kEdgeBlock) dst4[w] = bits4[w];
+        } else {
+            for (int w = w_lo + tid; w < min(w_hi, T.n_words); w += kEdgeBlock) dst[w] = bits[w - w_lo];
+        }
+        if (kApply) {
+            // group g = 8 logits = one byte of the LDS bitmap (little endian)
+            const uint8_t *mbytes = reinterpret_cast<const uint8_t *>(bits);
+            uint16_t *lrow = logits + (size_t)b * row_stride;
+            const int g_lo = w_lo * 4, g_cnt = max(v_cnt, 0) * 16;
+            for (int g0 = tid; g0 < g_cnt; g0 += kEdgeBlock * 4) {
+                uint32_t m[4];
+                uint4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int gl = g0 + u * kEdgeBlock;
+                    m[u] = gl < g_cnt ? mbytes[gl] : 0xFFu;
+                    const int t0 = (g_lo + gl) * 8;
+                    if (t0 >= T.n_tokens) m[u] = 0xFFu;                   // padding beyond the vocabulary
+                    if (m[u] != 0xFFu && m[u] != 0u && t0 + 8 <= T.n_tokens)
+                        v[u] = *reinterpret_cast<const uint4 *>(lrow + t0);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t mu = m[u];
+                    if (mu == 0xFFu) continue;
+                    const int t0 = (g_lo + g0 + u * kEdgeBlock) * 8;
+                    uint16_t *p = lrow + t0;
+                    if (t0 + 8 <= T.n_tokens) {
+                        if (mu == 0u) {
+                            *reinterpret_cast<uint4 *>(p) = make_uint4(kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair);
+                        } else {
+                            uint32_t *x = reinterpret_cast<uint32_t *>(&v[u]);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                if (!((mu >> (2 * k)) & 1u)) x[k] = (x[k] & 0xFFFF0000u) | 0xFF80u;
+                                if (!((mu >> (2 * k + 1)) & 1u)) x[k] = (x[k] & 0x0000FFFFu) | 0xFF800000u;
+                            }
+                            *reinterpret_cast<uint4 *>(p) = v[u];
+                        }
+                    } else {
+                        for (int k = 0; t0 + k < T.n_tokens; ++k)
+                            if (!((mu >> k) & 1u)) p[k] = 0xFF80;
+                    }
+                }
+            }
+        }
         __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------------------- apply
 
-constexpr uint32_t kNegInfPair = 0xFF80FF80u;
+constexpr int kApplyBlock = 256;
+constexpr int kApplyUnroll = 4;        // 16-byte groups per lane
+constexpr int kApplySpan = kApplyBlock * kApplyUnroll * 8;   // logits per block
 
-// One lane per 8 consecutive logits (16 bytes) of one row: fully allowed groups are not
-// touched, fully masked groups are overwritten without being read, mixed groups are patched.
-__global__ __launch_bounds__(256) void apply_mask_vec8_kernel(uint16_t *__restrict__ logits,
-                                                               const uint32_t *__restrict__ bitmask, int batch,
-                                                               int vocab, int64_t row_stride, int n_words) {
+// blockIdx.y = row, blockIdx.x = span of kApplySpan logits.  A lane owns kApplyUnroll groups of 8
+// consecutive logits (16 bytes), one per pass, so that every pass of a wave is one contiguous
+// 1 KiB access.  Fully allowed groups are not touched, fully masked groups are overwritten
+// without being read, mixed groups are read, patched and written back.
+__global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *__restrict__ logits,
+                                                                     const uint32_t *__restrict__ bitmask,
+                                                                     int vocab, int64_t row_stride, int n_words) {
+    const int b = blockIdx.y;
     const int groups = (vocab + 7) >> 3;
-    const int64_t total = (int64_t)batch * groups;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int b = (int)(i / groups), g = (int)(i - (int64_t)b * groups);
-        const uint32_t m = (bitmask[(size_t)b * n_words + (g >> 2)] >> ((g & 3) * 8)) & 0xFFu;
-        if (m == 0xFFu) continue;
-        uint16_t *p = logits + (size_t)b * row_stride + (size_t)g * 8;
+    const int g0 = blockIdx.x * (kApplyBlock * kApplyUnroll) + threadIdx.x;
+    const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
+    uint16_t *lrow = logits + (size_t)b * row_stride;
+    uint32_t m[kApplyUnroll];
+    uint4 v[kApplyUnroll];
+#pragma unroll
+    for (int u = 0; u < kApplyUnroll; ++u) {
+        const int g = g0 + u * kApplyBlock;
+        m[u] = g < groups ? mrow[g] : 0xFFu;            // little endian: byte g of the row = bits of group g
+    }
+#pragma unroll
+    for (int u = 0; u < kApplyUnroll; ++u) {                // all loads of the lane are in flight together
+        const int g = g0 + u * kApplyBlock;
+        if (m[u] != 0xFFu && m[u] != 0u && g * 8 + 8 <= vocab) v[u] = *reinterpret_cast<const uint4 *>(lrow + (size_t)g * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < kApplyUnroll; ++u) {
+        const int g = g0 + u * kApplyBlock;
+        const uint32_t mu = m[u];
+        if (mu == 0xFFu) continue;
+        uint16_t *p = lrow + (size_t)g * 8;
         if (g * 8 + 8 <= vocab) {
-            uint4 *q = reinterpret_cast<uint4 *>(p);
-            if (m == 0) {
-                *q = make_uint4(kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair);
+            if (mu == 0u) {
+                *reinterpret_cast<uint4 *>(p) = make_uint4(kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair);
             } else {
-                uint4 v = *q;
-                uint32_t *x = reinterpret_cast<uint32_t *>(&v);
+                uint32_t *x = reinterpret_cast<uint32_t *>(&v[u]);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    if (!((m >> (2 * k)) & 1u)) x[k] = (x[k] & 0xFFFF0000u) | 0xFF80u;
-                    if (!((m >> (2 * k + 1)) & 1u)) x[k] = (x[k] & 0x0000FFFFu) | 0xFF800000u;
+                    if (!((mu >> (2 * k)) & 1u)) x[k] = (x[k] & 0xFFFF0000u) | 0xFF80u;
+                    if (!((mu >> (2 * k + 1)) & 1u)) x[k] = (x[k] & 0x0000FFFFu) | 0xFF800000u;
                 }
-                *q = v;
+                *reinterpret_cast<uint4 *>(p) = v[u];
             }
         } else {
             for (int k = 0; g * 8 + k < vocab; ++k)
-                if (!((m >> k) & 1u)) p[k] = 0xFF80;
+                if (!((mu >> k) & 1u)) p[k] = 0xFF80;
         }
     }
 }
@@ -371,22 +477,42 @@ __global__ __launch_bounds__(64) void advance_kernel(DevTables T, const int32_t 
 }  // namespace
 
 int walk_grid_blocks(int n_compute_units) { return 4 * n_compute_units; }
-int edge_grid_blocks(int n_compute_units) { return 2 * n_compute_units; }
+int edge_grid_blocks(int n_compute_units) { return 4 * n_compute_units; }
 size_t edge_spill_entries(int grid_blocks, int max_depth) {
     const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
     return (size_t)grid_blocks * kWalkLanes * (size_t)deep;
 }
-size_t edge_kernel_max_lds_words() { return (size_t)(64 * 1024 - 24 * 1024) / 4; }
+size_t edge_kernel_max_lds_words() { return (size_t)(64 * 1024 - 8 * 1024) / 4; }
+int edge_row_stride_words(int n_words) { return (n_words + 3) & ~3; }
 
 hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, const int32_t *states,
                                   const int32_t *data, const int32_t *len, int cap, int batch, uint32_t *bitmask,
-                                  int32_t *spill, int grid_blocks, hipStream_t stream) {
+                                  uint16_t *logits, int64_t row_stride, int32_t *spill, int grid_blocks,
+                                  hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    const int grid = batch < grid_blocks ? batch : grid_blocks;
-    hipLaunchKernelGGL(fill_mask_edges_kernel, dim3(grid), dim3(kEdgeBlock), (size_t)T.n_words * sizeof(uint32_t),
-                       stream, T, E, states, data, len, cap, batch, bitmask, spill, (size_t)grid_blocks * kWalkLanes);
+    // Segments per row: enough items to give every block of the grid one (two when only the
+    // mask is wanted: the items are short), but segments of at least 64 uint4 (8 KiB of mask
+    // = 16 Ki logits) so that the redundant descents stay cheap next to the streaming.
+    const int n_vec = (T.n_words + 3) / 4;
+    const int rows_padded = (batch + 7) & ~7;
+    int want = (grid_blocks * (logits ? 1 : 1) + rows_padded - 1) / rows_padded;
+    int max_seg = (n_vec + 63) / 64;
+    int n_seg = want < 1 ? 1 : (want > max_seg ? max_seg : want);
+    int seg_vec = (n_vec + n_seg - 1) / n_seg;
+    n_seg = (n_vec + seg_vec - 1) / seg_vec;
+    const long long n_items = (long long)rows_padded * n_seg;
+    const int grid = (int)(n_items < grid_blocks ? n_items : grid_blocks);
+    const size_t lds = (size_t)seg_vec * sizeof(uint4);
+    const size_t stride = (size_t)grid_blocks * kWalkLanes;
+    if (logits)
+        hipLaunchKernelGGL(fill_mask_edges_kernel<true>, dim3(grid), dim3(kEdgeBlock), lds, stream, T, E, states, data,
+                           len, cap, batch, bitmask, logits, row_stride, n_seg, seg_vec, spill, stride);
+    else
+        hipLaunchKernelGGL(fill_mask_edges_kernel<false>, dim3(grid), dim3(kEdgeBlock), lds, stream, T, E, states, data,
+                           len, cap, batch, bitmask, logits, row_stride, n_seg, seg_vec, spill, stride);
     return hipGetLastError();
 }
+
 size_t walk_spill_entries(int grid_blocks, int max_depth) {
     const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
     return (size_t)grid_blocks * kBlock * (size_t)deep;
@@ -412,12 +538,10 @@ hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batc
     if (batch == 0 || vocab == 0) return hipSuccess;
     const int n_words = (vocab + 31) / 32;
     const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
-    if (aligned) {
-        const int64_t total = (int64_t)batch * ((vocab + 7) / 8);
-        const int64_t want = (total + 255) / 256;
-        const int grid = (int)(want < 65536 ? want : 65536);
-        hipLaunchKernelGGL(apply_mask_vec8_kernel, dim3(grid), dim3(256), 0, stream, logits, bitmask, batch, vocab,
-                           row_stride, n_words);
+    if (aligned && batch <= 65535) {
+        const dim3 grid((vocab + kApplySpan - 1) / kApplySpan, batch);
+        hipLaunchKernelGGL(apply_mask_vec8_kernel, grid, dim3(kApplyBlock), 0, stream, logits, bitmask, vocab, row_stride,
+                           n_words);
     } else {
         const int64_t total = (int64_t)batch * vocab;
         const int64_t want = (total + 255) / 256;

@@ -18,10 +18,12 @@ hipError_t launch_fill_mask_walk(const DevTables &T, const int32_t *states, cons
                                  hipStream_t stream);
 int edge_grid_blocks(int n_compute_units);
 size_t edge_spill_entries(int grid_blocks, int max_depth);          // int32 entries
+int edge_row_stride_words(int n_words);                             // stride of dense rows on the device
 size_t edge_kernel_max_lds_words();                                 // largest bitmap row the kernel can hold
 hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, const int32_t *states,
                                   const int32_t *data, const int32_t *len, int cap, int batch, uint32_t *bitmask,
-                                  int32_t *spill, int grid_blocks, hipStream_t stream);
+                                  uint16_t *logits /* null: mask only */, int64_t row_stride, int32_t *spill,
+                                  int grid_blocks, hipStream_t stream);
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream);
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,

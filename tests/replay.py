@@ -72,10 +72,18 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
             if check_apply:
                 logits = bf16_logits(rng, B, V)
                 logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
+                fused_logits_d = logits_d.clone()
                 apply_mask(logits_d, mask_d, V)
                 oracle_apply_mask(logits, want, V)
                 out = logits_d.cpu().numpy().view(np.uint16)
                 assert (out == logits).all(), f"cfg {cfg_idx} step {s}: masked logits differ"
+                # the fused entry point must leave exactly the same bitmask and logits
+                fused_mask_d = torch.full_like(mask_d, 0x3C3C3C3C)
+                lib.fill_apply_mask(states_d, data_d, len_d, fused_mask_d, fused_logits_d)
+                assert (fused_mask_d.cpu().numpy().view(np.uint32) == want).all(), \
+                    f"cfg {cfg_idx} step {s}: fused bitmask differs"
+                assert (fused_logits_d.cpu().numpy().view(np.uint16) == logits).all(), \
+                    f"cfg {cfg_idx} step {s}: fused masked logits differ"
         else:
             for b in rng.integers(0, B, size=rows_per_step):
                 want = o.mask_row(data_h[b, : len_h[b]], v, done=states_h[b] < 0)
