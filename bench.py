@@ -1,8 +1,14 @@
 """Benchmark of the batched token-mask path on one MI355X.
 
-One step = fill_mask -> apply_mask -> advance over one batch (B=256 sequences, V=128,256
-tokens, byte-level JSON grammar: workload "json-B256-V128256"), replaying a seeded
-trajectory; all inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+One step = token mask + logits masking + stack advance over one batch (B=256 sequences,
+V=128,256 tokens, byte-level JSON grammar: workload "json-B256-V128256"), replaying a seeded
+trajectory; all inputs are resident in HBM before the timed region.  The K timed steps are
+captured into one HIP graph (kernel launches only) and replayed between two HIP events, so
+the GPU runs the kernels back to back as a serving loop would: that replay gives `value`.
+Per-kernel durations are measured in a second, eager pass over the same K steps with a HIP
+event before and after every launch (each bracket carries a few microseconds of event
+overhead; the rocprofv3 summaries under profiles/ hold the pure durations).  Prints ONE
+JSON line.
 """
 import argparse
 import json
@@ -24,6 +30,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload timed on the CPU oracle")
+    ap.add_argument("--repeats", type=int, default=3, help="replays of each graph (the fastest is reported)")
+    ap.add_argument("--step", choices=["two-call", "fused"], default="two-call",
+                    help="mask+apply as pre3_fill_mask + pre3_apply_mask, or as pre3_fill_apply_mask")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on one GPU (sequences are independent; see DESIGN.md on sharding); use --gpus 1")
@@ -49,7 +58,9 @@ def main():
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
 
     dev = torch.device("cuda:0")
+    t_compile = time.perf_counter()
     lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap)
+    t_compile = time.perf_counter() - t_compile
     data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
     states_h = data_h[np.arange(B), len_h - 1].copy()
     data_d = torch.from_numpy(data_h).to(dev)
@@ -69,36 +80,78 @@ def main():
     logits = [torch.randn((B, V), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
               for _ in range(n_pool)]
 
-    def step(s, ev=None):
+    def resets(s):
         if any_reset[s]:          # slot reuse: a finished sequence restarts (bottom of its stack is kept)
             torch.where(reset_d[s], one_d, len_d, out=len_d)
             torch.where(reset_d[s], s0_d, states_d, out=states_d)
-        if ev:
-            ev[0].record()
-        lib.fill_mask(states_d, data_d, len_d, mask_d)
-        if ev:
-            ev[1].record()
-        apply_mask(logits[s % n_pool], mask_d, V)
-        if ev:
-            ev[2].record()
-        lib.advance(tokens_d[s])
-        if ev:
-            ev[3].record()
+
+    def step(s, kind):
+        resets(s)
+        if kind == "fused":
+            lib.fill_apply_mask(states_d, data_d, len_d, mask_d, logits[s % n_pool])
+        if kind in ("fill", "fill+apply"):
+            lib.fill_mask(states_d, data_d, len_d, mask_d)
+        if kind == "fill+apply":
+            apply_mask(logits[s % n_pool], mask_d, V)
+        if kind != "resets":
+            lib.advance(tokens_d[s])
 
     for s in range(Wm):
-        step(s)
+        step(s, "fused" if s % 2 else "fill+apply")
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(K):
-        step(Wm + s, events[s])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    snap = (data_d.clone(), len_d.clone(), states_d.clone())
 
-    fill_us = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e3
-    apply_us = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e3
-    adv_us = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e3
+    def restore():
+        data_d.copy_(snap[0]); len_d.copy_(snap[1]); states_d.copy_(snap[2])
+
+    def timed_graph(kind):
+        """Captures the K timed steps with the given kernels and returns the fastest replay (ms)."""
+        restore()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(K):
+                step(Wm + s, kind)
+        best = float("inf")
+        for _ in range(max(1, args.repeats) + 1):          # the first replay also warms the graph
+            restore()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+
+    step_kind = "fill+apply" if args.step == "two-call" else "fused"
+    other_kind = "fused" if args.step == "two-call" else "fill+apply"
+    t_other = timed_graph(other_kind)
+    t_adv = timed_graph("advance")
+    t_step = timed_graph(step_kind)
+
+    # ---- eager pass over the same steps: one event pair per launch
+    restore()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    for s in range(K):
+        resets(Wm + s)
+        ev[s][0].record()
+        if step_kind == "fused":
+            lib.fill_apply_mask(states_d, data_d, len_d, mask_d, logits[(Wm + s) % n_pool])
+            ev[s][1].record()
+        else:
+            lib.fill_mask(states_d, data_d, len_d, mask_d)
+            ev[s][1].record()
+            apply_mask(logits[(Wm + s) % n_pool], mask_d, V)
+        ev[s][2].record()
+        lib.advance(tokens_d[Wm + s])
+        ev[s][3].record()
+    torch.cuda.synchronize()
+    first_us = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3       # fill (or the fused kernel)
+    second_us = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3      # apply (0 when fused)
+    adv_us = np.array([e[2].elapsed_time(e[3]) for e in ev]) * 1e3
+    # after this pass the device holds the state after all K timed steps
 
     # ---- the timed run must have done the real work: final state == oracle's replay
     for s in range(total):
@@ -109,6 +162,21 @@ def main():
     assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), \
         "device state after the timed run differs from the oracle's replay"
     assert int(err_d.abs().sum().item()) == 0
+    # and the last mask on the device is the oracle's mask of the last timed step's input state
+    restore()
+    for s in range(K - 1):
+        step(Wm + s, "advance")
+    resets(total - 1)
+    lib.fill_mask(states_d, data_d, len_d, mask_d)
+    d_c, l_c = traj.init_data.copy(), traj.init_len.copy()
+    s_c = d_c[np.arange(B), l_c - 1].copy()
+    for s in range(total - 1):
+        rs = np.flatnonzero(traj.reset[s])
+        d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
+        o.advance_batch(s_c, d_c, l_c, traj.tokens[s], v)
+    rs = np.flatnonzero(traj.reset[total - 1])
+    d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
+    assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_c, d_c, l_c, v)).all(), "final mask differs"
 
     # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
     n_cpu = max(1, args.cpu_steps)
@@ -128,36 +196,46 @@ def main():
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
 
     pairs = float(B) * V
-    mask_apply_us = float(np.mean(fill_us + apply_us))
-    dominant = "fill_mask" if fill_us.mean() >= apply_us.mean() else "apply_mask"
-    achieved = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9
+    stat = lambda x: {"mean": float(x.mean()), "p50": float(np.median(x)), "p99": float(np.percentile(x, 99))}
+    mask_apply_us = float((first_us + second_us).mean())
+    if step_kind == "fused":
+        kernels = {"fill_apply_mask": stat(first_us), "advance": stat(adv_us)}
+        dom_name, dom_us, dom_bytes = "fill_mask_edges_kernel<true> (token mask + logits masking)", float(first_us.mean()), BYTES_PER_PAIR * pairs
+    else:
+        kernels = {"fill_mask": stat(first_us), "apply_mask": stat(second_us), "advance": stat(adv_us)}
+        # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
+        dom_name, dom_us, dom_bytes = "apply_mask_vec8_kernel", float(second_us.mean()), (4.0 + 0.125) * pairs
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    step_achieved = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9
     out = {
         "metric": "masked (seq x vocab) tokens/sec",
-        "value": pairs * K / elapsed,
+        "value": pairs * K / (t_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": elapsed / K * 1e3,
+        "ms_per_step": t_step / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 bitmask / bf16 logits / i32 states",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": "byte-level JSON, canonical LR(1)",
-                   "stack_cap": cap, "resets_in_timed_steps": int(traj.reset[Wm:].sum())},
+                   "stack_cap": cap, "resets_in_timed_steps": int(traj.reset[Wm:].sum()),
+                   "step": ("pre3_fill_mask + pre3_apply_mask" if step_kind != "fused" else "pre3_fill_apply_mask")
+                           + " + pre3_advance (+ slot-reuse resets), K steps in one HIP graph"},
         "mask_apply_us_per_step": mask_apply_us,
-        "kernels_us": {"fill_mask": {"mean": float(fill_us.mean()), "p50": float(np.median(fill_us)),
-                                     "p99": float(np.percentile(fill_us, 99))},
-                       "apply_mask": {"mean": float(apply_us.mean()), "p50": float(np.median(apply_us)),
-                                      "p99": float(np.percentile(apply_us, 99))},
-                       "advance": {"mean": float(adv_us.mean()), "p50": float(np.median(adv_us)),
-                                   "p99": float(np.percentile(adv_us, 99))}},
         "mask_apply_tokens_per_s": pairs / (mask_apply_us * 1e-6),
+        "mask_apply_frac_of_hbm_peak": step_achieved / HBM_PEAK_GBS,
+        "kernels_us": kernels,
+        "graph_ms_per_step": {"this step": t_step / K, "with the other mask+apply variant": t_other / K,
+                              "advance and resets only": t_adv / K},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "fill_mask + apply_mask (one step)", "dominant": dominant,
-                     "algorithmic_bytes_per_step": BYTES_PER_PAIR * pairs},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": dom_name,
+                     "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
+                     "timing": "HIP events around every launch of the eager pass over the timed steps"},
         "cpu_baseline": {"value": pairs * n_cpu / cpu_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                          "sample": f"fill_mask+apply_mask of the first {n_cpu} steps of the same workload "
                                    f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",
                          "us_per_step": cpu_t / n_cpu * 1e6},
+        "compile_s": t_compile,
+        "token_edges": lib.token_edge_stats(),
     }
     print(json.dumps(out))
 

@@ -57,6 +57,9 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime: it must be in the process before libpre3.so is
+    # loaded, so that both resolve to the same runtime (two runtimes cannot share the GPU).
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with paper_2506_03887_amd.build.build()")
     lib = ctypes.CDLL(LIB_PATH)

@@ -40,6 +40,7 @@ struct pre3_handle {
     int32_t *b_states = nullptr, *b_err = nullptr;
     pre3_stacks b_stacks{};
     int32_t *adv_scratch = nullptr;
+    bool bound_empty = false;
     size_t adv_scratch_entries = 0;
 };
 
@@ -230,6 +231,11 @@ int32_t pre3_initial_state(const pre3_handle *h, int32_t g) {
 
 int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t *err) {
     if (!usable(h)) return PRE3_E_BADARG;
+    if (stacks.batch == 0) {                 // an empty batch has no buffers to point at
+        h->b_states = nullptr; h->b_err = nullptr; h->b_stacks = stacks; h->bound_empty = true;
+        return PRE3_OK;
+    }
+    h->bound_empty = false;
     if (!states || !err || !stacks.data || !stacks.len || stacks.batch < 0 || stacks.cap < 1 ||
         stacks.cap > h->stack_cap)
         return fail(h, PRE3_E_BADARG, "bind_state: null buffer, negative batch or cap outside 1..stack_cap");
@@ -249,6 +255,7 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
 
 int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask, pre3_stream stream) {
     if (!usable(h)) return PRE3_E_BADARG;
+    if (stacks.batch == 0) return PRE3_OK;
     if (!states || !stacks.data || !stacks.len || !bitmask || stacks.batch < 0 || stacks.cap < 1 ||
         stacks.cap > h->stack_cap)
         return fail(h, PRE3_E_BADARG, "fill_mask: null buffer, negative batch or cap outside 1..stack_cap");
@@ -265,6 +272,7 @@ int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, ui
 int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
                          uint16_t *logits, int64_t row_stride, pre3_stream stream) {
     if (!usable(h)) return PRE3_E_BADARG;
+    if (stacks.batch == 0) return PRE3_OK;
     if (!states || !stacks.data || !stacks.len || !bitmask || !logits || stacks.batch < 0 || stacks.cap < 1 ||
         stacks.cap > h->stack_cap || row_stride < h->V.n_tokens)
         return fail(h, PRE3_E_BADARG, "fill_apply_mask: null buffer, negative batch, bad cap or row_stride < vocabulary");
@@ -283,6 +291,7 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
 
 int pre3_apply_mask(uint16_t *logits, const uint32_t *bitmask, int32_t batch, int32_t vocab, int64_t row_stride,
                     pre3_stream stream) {
+    if (batch == 0 || vocab == 0) return PRE3_OK;
     if (!logits || !bitmask || batch < 0 || vocab < 0 || row_stride < vocab) return PRE3_E_BADARG;
     if (reinterpret_cast<uintptr_t>(logits) % 2 != 0 || reinterpret_cast<uintptr_t>(bitmask) % 4 != 0)
         return PRE3_E_BADARG;
@@ -292,6 +301,7 @@ int pre3_apply_mask(uint16_t *logits, const uint32_t *bitmask, int32_t batch, in
 
 int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
     if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
     if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance: no state bound");
     if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
     hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,

@@ -435,43 +435,72 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(uint16_t *__rest
 
 // -------------------------------------------------------------------------- advance
 
-// One lane per sequence.  The token is walked on a private overlay exactly like in the mask
-// kernel; only a walk that succeeds is committed to the sequence's stack.
-__global__ __launch_bounds__(64) void advance_kernel(DevTables T, const int32_t *__restrict__ tokens,
-                                                     int32_t *__restrict__ states, int32_t *__restrict__ data,
-                                                     int32_t *__restrict__ len, int cap, int batch,
-                                                     int32_t *__restrict__ err, int32_t *scratch) {
-    __shared__ int32_t lds_stack[kLdsDepth * 64];
-    const int b = blockIdx.x * 64 + threadIdx.x;
+// One wave per sequence: the walk of a single token is a chain of dependent table look-ups, so
+// giving every sequence its own wave keeps control flow uniform (lanes of a shared wave would
+// serialise each other's reduction chains) and lets the chip overlap the chains of all
+// sequences.  Lane 0 walks the token on a private overlay exactly like in the mask kernels;
+// only a walk that succeeds is committed, by all lanes, to the sequence's stack.
+constexpr int kAdvSeqPerBlock = 4;
+__global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
+    DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
+    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch) {
+    __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
+    __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * kAdvSeqPerBlock + wave;
     if (b >= batch) return;
-    const int t = tokens[b];
-    if (t < 0) { err[b] = 0; return; }
     int32_t *row = data + (size_t)b * cap;
-    const int n = len[b];
-    int top = -1;
-    if (states[b] >= 0 && n >= 1 && n <= cap) top = row[n - 1];
-    if (t >= T.n_tokens || (unsigned)top >= (unsigned)T.n_states) { err[b] = 1; return; }
-
     PrivateStack priv;
-    priv.lds = lds_stack + threadIdx.x;
-    priv.lds_stride = 64;
+    priv.lds = lds_stack + wave;
+    priv.lds_stride = kAdvSeqPerBlock;
     priv.spill = scratch + b;
     priv.spill_stride = (size_t)batch;
-    int base = n, d = 0;
-    if (t == T.eos_id) {
-        if (feed<false>(T, priv, T.end_col, base, d, top, row, 0) == kAccepted) { states[b] = -1; err[b] = 0; }
-        else err[b] = 1;
-        return;
+    if (lane == 0) {
+        int commit = -1;                                  // private entries to copy, or -1
+        const int t = tokens[b];
+        const int n = len[b];
+        int top = -1;
+        if (t < 0) {
+            err[b] = 0;
+        } else {
+            if (states[b] >= 0 && n >= 1 && n <= cap) top = row[n - 1];
+            if (t >= T.n_tokens || (unsigned)top >= (unsigned)T.n_states) {
+                err[b] = 1;
+            } else {
+                int base = n, d = 0;
+                if (t == T.eos_id) {
+                    if (feed<false>(T, priv, T.end_col, base, d, top, row, 0) == kAccepted) { states[b] = -1; err[b] = 0; }
+                    else err[b] = 1;
+                } else {
+                    const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
+                    int rc = hi > lo ? kFed : kRejected;
+                    for (int i = lo; i < hi && rc == kFed; ++i)
+                        rc = feed<true>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, row, cap);
+                    if (rc != kFed) {
+                        err[b] = rc == kOverflow ? 2 : 1;
+                    } else {
+                        commit = d;
+                        s_base[wave] = base;
+                        len[b] = base + d;
+                        states[b] = top;
+                        err[b] = 0;
+                    }
+                }
+            }
+        }
+        s_depth[wave] = commit;
     }
-    const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
-    int rc = hi > lo ? kFed : kRejected;
-    for (int i = lo; i < hi && rc == kFed; ++i)
-        rc = feed<true>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, row, cap);
-    if (rc != kFed) { err[b] = rc == kOverflow ? 2 : 1; return; }
-    for (int i = 0; i < d; ++i) row[base + i] = priv.get(i);
-    len[b] = base + d;
-    states[b] = top;
-    err[b] = 0;
+    __builtin_amdgcn_wave_barrier();
+    // LDS operations of one wave complete in order, so every lane sees lane 0's LDS writes;
+    // entries that spilled to global memory are copied by lane 0 itself
+    const int d = s_depth[wave];
+    if (d > 0) {
+        const int base = s_base[wave];
+        const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+        if (lane < in_lds) row[base + lane] = priv.get(lane);
+        if (lane == 0)
+            for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
+    }
 }
 
 }  // namespace
@@ -555,8 +584,8 @@ hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batc
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
                           int cap, int batch, int32_t *err, int32_t *scratch, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    hipLaunchKernelGGL(advance_kernel, dim3((batch + 63) / 64), dim3(64), 0, stream, T, tokens, states, data, len,
-                       cap, batch, err, scratch);
+    hipLaunchKernelGGL(advance_kernel, dim3((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), dim3(64 * kAdvSeqPerBlock),
+                       0, stream, T, tokens, states, data, len, cap, batch, err, scratch);
     return hipGetLastError();
 }
 

@@ -1,0 +1,262 @@
+"""GPU edge cases through the C ABI, each checked against the CPU oracle: empty batch, ragged
+vocabulary sizes, strided / unaligned logits, every per-sequence error of advance, finished
+rows, tokens deep enough to spill the private stack, snapshots, HIP-graph replay."""
+import numpy as np
+import pytest
+
+from oracle import Oracle, apply_mask as oracle_apply_mask
+from workloads import grammars as G
+from workloads.vocab import BASE_SEED, Vocab, bf16_logits, bpe_like_vocab
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch, torch.device("cuda:0")
+
+
+def _lib(grammars, vocab, **kw):
+    from paper_2506_03887_amd import Pre3
+    return Pre3(grammars, vocab.bytes, vocab.offsets, vocab.eos_id, max_token_len=max(1, vocab.max_len), **kw)
+
+
+def _stacks(o, prefixes, cap, grammar=0):
+    B = len(prefixes)
+    data = np.zeros((B, cap), dtype=np.int32)
+    length = np.ones(B, dtype=np.int32)
+    for b, p in enumerate(prefixes):
+        rc, st = (0, o.initial_stack(grammar)) if not p else o.advance(o.initial_stack(grammar), p)
+        assert rc == 0, p
+        data[b, : len(st)] = st
+        length[b] = len(st)
+    states = data[np.arange(B), length - 1].copy()
+    return states, data, length
+
+
+def _gpu_mask(lib, states, data, length, words):
+    torch, dev = _torch()
+    m = torch.full((len(states), words), 0x77777777, dtype=torch.int32, device=dev)
+    lib.fill_mask(torch.from_numpy(states).to(dev), torch.from_numpy(data).to(dev), torch.from_numpy(length).to(dev), m)
+    return m.cpu().numpy().view(np.uint32)
+
+
+@pytest.fixture(scope="module")
+def deep_vocab():
+    """JSON vocabulary with tokens that nest up to 32 levels in one token (private stacks of the
+    walk spill from LDS to global memory), empty tokens, duplicates and a ragged size."""
+    base = bpe_like_vocab(3000, 16, BASE_SEED + 77).tokens[:-1]
+    extra = [b"[" * 32, b"[" * 17 + b"1", b"[[[[[[[[[[[[[[[[[[[[{\"a\":[[", b"{\"k\":" * 6, b"[" * 9 + b"]" * 9,
+             b"", b"", b"[" * 32, b"]" * 20, b"\"" + b"x" * 30 + b"\"", b"[1," * 10, b"]]]]]]]],"]
+    toks = base + extra + [b""]                  # EOS last
+    assert len(toks) % 32 != 0 and len(toks) % 8 != 0
+    return Vocab(toks, len(toks) - 1)
+
+
+@pytest.mark.parametrize("token_edges", [True, False])
+def test_deep_tokens_spill_the_private_stack(deep_vocab, token_edges):
+    o = Oracle(G.JSON)
+    v = deep_vocab
+    lib = _lib(G.JSON, v, token_edges=token_edges, max_condition_depth=3 if token_edges else 0)
+    assert lib.walk_depth_bound > 16
+    prefixes = [b"", b"[", b"[[[[[[[[[", b'{"a":', b'{"a":[[[[[[[[[[[[[[[[[[[[', b'"abc', b"[1", b"[[[[[[[[[1" + b"]" * 3, b"12"]
+    states, data, length = _stacks(o, prefixes, 256)
+    got = _gpu_mask(lib, states, data, length, v.words)
+    want = o.fill_mask(states, data, length, v)
+    assert (got == want).all()
+    # the deep tokens really are allowed somewhere, and equal strings get equal bits
+    t_deep = [t for t, tok in enumerate(v.tokens) if tok == b"[" * 32]
+    assert len(t_deep) == 2
+    for b in range(len(prefixes)):
+        bits = [(want[b, t >> 5] >> (t & 31)) & 1 for t in t_deep]
+        assert bits[0] == bits[1]
+    assert (want[0, t_deep[0] >> 5] >> (t_deep[0] & 31)) & 1
+    # advance by the deep tokens, token by token, against the oracle
+    torch, dev = _torch()
+    toks = np.array([t_deep[0], t_deep[1], v.tokens.index(b"]]]]]]]],"), v.tokens.index(b"[" * 17 + b"1"),
+                     v.tokens.index(b"]" * 20), -1, v.tokens.index(b"[1," * 10), v.tokens.index(b"]]]]]]]],"),
+                     v.eos_id], dtype=np.int32)
+    s_d, d_d, l_d = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+    e_d = torch.full((len(toks),), -5, dtype=torch.int32, device=dev)
+    lib.bind_state(s_d, d_d, l_d, e_d)
+    lib.advance(torch.from_numpy(toks).to(dev))
+    s_h, d_h, l_h = states.copy(), data.copy(), length.copy()
+    err = o.advance_batch(s_h, d_h, l_h, toks, v)
+    assert (e_d.cpu().numpy() == err).all() and set(err.tolist()) >= {0, 1}
+    assert (s_d.cpu().numpy() == s_h).all() and (l_d.cpu().numpy() == l_h).all()
+    live = np.arange(256)[None, :] < l_h[:, None]
+    assert (d_d.cpu().numpy()[live] == d_h[live]).all()
+    assert l_h.max() > 60                                        # a 32-bracket token was committed
+
+
+def test_advance_error_codes_and_overflow(deep_vocab):
+    o = Oracle(G.JSON)
+    v = deep_vocab
+    lib = _lib(G.JSON, v)
+    torch, dev = _torch()
+    cap = 24
+    prefixes = [b"[[[[[[[[[[", b"[[[[[[[[[[", b"[1", b"[1", b"12", b"12", b"[1", b"{"]
+    states, data, length = _stacks(o, prefixes, cap)
+    states[5] = -1                                               # a finished sequence
+    tok = {t: i for i, t in reversed(list(enumerate(v.tokens))) if i != v.eos_id}
+    toks = np.array([tok[b"[" * 9 + b"]" * 9],                    # transient overflow of cap -> 2
+                     tok[b"]"],                                    # fine
+                     tok[b"}"],                                    # not allowed -> 1
+                     v.eos_id,                                     # EOS where the text is no sentence -> 1
+                     v.eos_id,                                     # EOS allowed -> DONE
+                     tok[b"1"],                                    # any token on a finished sequence -> 1
+                     v.n_tokens + 5,                               # id out of range -> 1
+                     [t for t, s in enumerate(v.tokens) if s == b"" and t != v.eos_id][0]],   # empty token -> 1
+                    dtype=np.int32)
+    s_d, d_d, l_d = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+    e_d = torch.full((len(toks),), -5, dtype=torch.int32, device=dev)
+    lib.bind_state(s_d, d_d, l_d, e_d)
+    lib.advance(torch.from_numpy(toks).to(dev))
+    s_h, d_h, l_h = states.copy(), data.copy(), length.copy()
+    err = o.advance_batch(s_h, d_h, l_h, toks, v)
+    assert err.tolist() == [2, 0, 1, 1, 0, 1, 1, 1]
+    assert (e_d.cpu().numpy() == err).all()
+    assert (s_d.cpu().numpy() == s_h).all() and (l_d.cpu().numpy() == l_h).all() and s_h[4] == -1
+    live = np.arange(cap)[None, :] < l_h[:, None]
+    assert (d_d.cpu().numpy()[live] == d_h[live]).all()
+    # failing sequences are untouched, including the part of the row above len
+    for b in (0, 2, 3, 5, 6, 7):
+        assert (d_d.cpu().numpy()[b] == data[b]).all() and l_h[b] == length[b]
+    # a finished row gets only the EOS bit; fill_mask reads snapshots that need not be the bound buffers
+    got = _gpu_mask(lib, s_h, d_h, l_h, v.words)
+    assert (got == o.fill_mask(s_h, d_h, l_h, v)).all()
+    only_eos = np.zeros(v.words, dtype=np.uint32)
+    only_eos[v.eos_id >> 5] = 1 << (v.eos_id & 31)
+    assert (got[4] == only_eos).all() and (got[5] == only_eos).all()
+
+
+def test_empty_batch_and_single_row(deep_vocab):
+    torch, dev = _torch()
+    from paper_2506_03887_amd import apply_mask
+    o = Oracle(G.JSON)
+    v = deep_vocab
+    lib = _lib(G.JSON, v)
+    z32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=dev)
+    lib.fill_mask(z32(0), z32(0, 8), z32(0), z32(0, v.words))
+    lib.fill_apply_mask(z32(0), z32(0, 8), z32(0), z32(0, v.words), torch.zeros((0, v.n_tokens), dtype=torch.bfloat16, device=dev))
+    apply_mask(torch.zeros((0, v.n_tokens), dtype=torch.bfloat16, device=dev), z32(0, v.words), v.n_tokens)
+    lib.bind_state(z32(0), z32(0, 8), z32(0), z32(0))
+    lib.advance(z32(0))
+    torch.cuda.synchronize()
+    states, data, length = _stacks(o, [b'{"a": [1, '], 64)
+    assert (_gpu_mask(lib, states, data, length, v.words) == o.fill_mask(states, data, length, v)).all()
+
+
+@pytest.mark.parametrize("V,stride,offset", [(513, 513, 0), (1000, 1000, 0), (1000, 1008, 0), (1003, 1016, 0),
+                                             (1000, 1001, 0), (264, 264, 3), (40000, 40008, 8)])
+def test_apply_mask_layouts(V, stride, offset):
+    """Ragged vocabulary sizes, padded rows, rows that are not 16-byte aligned (scalar path),
+    NaN / inf payloads: the result is a pure select on raw bf16 patterns."""
+    torch, dev = _torch()
+    from paper_2506_03887_amd import apply_mask
+    rng = np.random.default_rng(V + stride)
+    B, W = 7, (V + 31) // 32
+    host = np.full((B, stride), 0x1234, dtype=np.uint16)
+    host[:, :V] = bf16_logits(rng, B, V)
+    host[0, :6] = [0x7FC1, 0xFFC0, 0x7F80, 0xFF80, 0x0000, 0x8000]
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[1], mask[2] = 0, 0xFFFFFFFF
+    mask[3, ::2], mask[4, 1::2] = 0, 0xFFFFFFFF
+    flat = torch.zeros(B * stride + offset + 16, dtype=torch.int16, device=dev)
+    view = flat[offset: offset + B * stride].view(B, stride)
+    view.copy_(torch.from_numpy(host.view(np.int16)).to(dev))
+    apply_mask(view[:, :V] if stride == V else view, torch.from_numpy(mask.view(np.int32)).to(dev), V)
+    want = host.copy()
+    oracle_apply_mask(want, mask, V)
+    assert (view.cpu().numpy().view(np.uint16) == want).all()
+    assert int(flat[:offset].abs().sum()) == 0 and int(flat[offset + B * stride:].abs().sum()) == 0
+
+
+@pytest.mark.parametrize("stride_pad,offset", [(0, 0), (8, 0), (3, 0), (0, 4)])
+def test_fused_call_equals_two_calls_on_any_layout(deep_vocab, stride_pad, offset):
+    torch, dev = _torch()
+    from paper_2506_03887_amd import apply_mask
+    o = Oracle(G.JSON)
+    v = deep_vocab
+    lib = _lib(G.JSON, v)
+    prefixes = [b"", b'{"a', b"[1", b'{"k": [tr', b"[[[[", b'"x\\', b"12.5e", b" 7 ", b'{"a":{"b":[{},[[]],"']
+    states, data, length = _stacks(o, prefixes, 64)
+    states[7] = -1
+    B, V, stride = len(prefixes), v.n_tokens, v.n_tokens + stride_pad
+    host = np.full((B, stride), 0x4321, dtype=np.uint16)
+    host[:, :V] = bf16_logits(np.random.default_rng(5), B, V)
+    flat = torch.zeros(B * stride + offset + 8, dtype=torch.int16, device=dev)
+    view = flat[offset: offset + B * stride].view(B, stride)
+    view.copy_(torch.from_numpy(host.view(np.int16)).to(dev))
+    s_d, d_d, l_d = (torch.from_numpy(x).to(dev) for x in (states, data, length))
+    m = torch.full((B, v.words), 0x11111111, dtype=torch.int32, device=dev)
+    lib.fill_apply_mask(s_d, d_d, l_d, m, view)
+    want_mask = o.fill_mask(states, data, length, v)
+    want = host.copy()
+    oracle_apply_mask(want, want_mask, V)
+    assert (m.cpu().numpy().view(np.uint32) == want_mask).all()
+    assert (view.cpu().numpy().view(np.uint16) == want).all()
+
+
+def test_hip_graph_replays_match_eager():
+    """A captured step (fill -> apply -> advance, kernels only) is replayed several times with
+    eager work between the replays (token upload, fresh logits, slot-reuse resets); every
+    replay must leave what the eager calls leave."""
+    torch, dev = _torch()
+    from paper_2506_03887_amd import apply_mask
+    from workloads import configs, trajectory
+    cfg = configs.get(2)
+    v = cfg.vocab
+    o = Oracle(cfg.grammars)
+    steps = 8
+    traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed + 3, None, cfg.nest_cap, None, True, None)
+    lib = _lib(cfg.grammars, v)
+    B, V = cfg.batch, v.n_tokens
+    init_data, init_len = torch.from_numpy(traj.init_data).to(dev), torch.from_numpy(traj.init_len).to(dev)
+    data, length = init_data.clone(), init_len.clone()
+    states = data[:, 0].clone()
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states, data, length, err)
+    mask = torch.zeros((B, v.words), dtype=torch.int32, device=dev)
+    logits0 = torch.from_numpy(bf16_logits(np.random.default_rng(1), B, V).view(np.int16)).to(dev)
+    logits = logits0.clone()
+    tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    toks = torch.from_numpy(traj.tokens).to(dev)
+    reset = torch.from_numpy(traj.reset).to(dev)
+    s0 = o.initial_state()
+
+    def start():
+        data.copy_(init_data); length.copy_(init_len); states.copy_(init_data[:, 0])
+
+    def eager_inputs(s):
+        tok.copy_(toks[s]); logits.copy_(logits0)
+        length.masked_fill_(reset[s], 1); states.masked_fill_(reset[s], s0)
+
+    def one_step():
+        lib.fill_mask(states, data, length, mask)
+        apply_mask(logits, mask, V)
+        lib.advance(tok)
+
+    start(); eager_inputs(0); one_step()             # warm up outside capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    start()
+    with torch.cuda.graph(g):
+        one_step()
+    ref = []
+    start()
+    for s in range(steps):
+        eager_inputs(s)
+        one_step()
+        torch.cuda.synchronize()
+        ref.append((mask.clone(), logits.clone(), states.clone(), length.clone(), data.clone()))
+    assert traj.reset.any()                           # the run includes slot reuse
+    start()
+    for s in range(steps):
+        eager_inputs(s)                               # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((mask, logits, states, length, data), ref[s]):
+            assert torch.equal(got, want), f"replay {s} differs from the eager step"
+    assert int(err.abs().sum()) == 0

@@ -112,6 +112,7 @@ def test_argument_errors(vocab):
     assert lib.pre3_advance(p._h, 1, None) == binding.E_BADARG
     assert lib.pre3_bind_state(p._h, 1, st, 1) == binding.E_BADARG
     assert lib.pre3_apply_mask(None, None, 1, 1, 1, None) == binding.E_BADARG
+    assert lib.pre3_apply_mask(None, None, 0, 1, 1, None) == 0                          # empty batch: nothing to do
     assert lib.pre3_apply_mask(16, 16, 1, 8, 4, None) == binding.E_BADARG               # stride < vocab
     assert lib.pre3_initial_state(p._h, 1) == binding.E_BADARG
     assert lib.pre3_free(None) == 0
