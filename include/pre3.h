@@ -53,6 +53,8 @@ typedef enum {
 
 #define PRE3_FLAG_HOST_ONLY 1    /* build the tables but upload nothing (no GPU needed);         */
                                  /* device calls on such a handle return PRE3_E_BADARG           */
+#define PRE3_FLAG_STEPWISE_REDUCTIONS 4 /* do not merge reduction chains into single reduction   */
+                                 /* edges: walks follow one reduction step at a time             */
 #define PRE3_FLAG_NO_TOKEN_EDGES 2 /* do not precompute token-level edges: pre3_fill_mask then     */
                                  /* walks every (sequence, token) pair byte by byte              */
 
@@ -183,6 +185,16 @@ int32_t pre3_walk_depth_bound(const pre3_handle *h);
  * [3] dense rows, [4] token ids in delta lists, [5] token ids in walk lists, [6] deepest stack
  * entry tested, [7] bytes of device memory they take. */
 int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]);
+/* Sizes of the merged reduction edges (Sec. 3.2.2; Alg. 1 step 3): out[0] built?, [1] condition
+ * nodes, [2] deepest stack entry tested, [3] bytes of device memory. */
+int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]);
+/* Host mirror of one sequence's advance, for checking the compiled edge tables without a GPU
+ * (tests and tools; never used by the device calls): walks bytes[0..n_bytes) (n_bytes < 0: the
+ * end-of-input symbol) on stack[0..*len) (host memory, capacity cap) with the merged reduction
+ * edges (use_merged != 0) or one reduction step at a time.  Returns 0 (stack and *len updated;
+ * for end of input: accepted, stack untouched), 1 not allowed, 2 overflow, or PRE3_E_BADARG. */
+int pre3_debug_advance(const pre3_handle *h, int32_t *stack, int32_t *len, int32_t cap, const uint8_t *bytes,
+                       int32_t n_bytes, int32_t use_merged);
 /* Table lookup only, on the host: evaluates the condition tree for one stack (host memory,
  * global state ids, bottom first).  row (ceil(n_tokens/32) words) receives the tokens whose
  * merged edge matches the stack; walk[0..*n_walk) the token ids the tables leave to a

@@ -18,13 +18,14 @@ PRE3_OK = 0
 E_BADARG, E_PARSE, E_NOT_LR1, E_TOKEN_TOO_LONG, E_NOMEM, E_HIP, E_LIMIT = -1, -2, -3, -4, -5, -6, -7
 FLAG_HOST_ONLY = 1
 FLAG_NO_TOKEN_EDGES = 2
+FLAG_STEPWISE_REDUCTIONS = 4
 STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
-    "pre3_token_edge_stats", "pre3_debug_resolve_row",
+    "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance",
 ]
 
 
@@ -80,6 +81,8 @@ def load():
     lib.pre3_edge.argtypes = [vp, i32, i32, c.POINTER(i32), c.POINTER(i32)]
     lib.pre3_goto_target.argtypes = [vp, i32, i32]
     lib.pre3_token_edge_stats.argtypes = [vp, vp]
+    lib.pre3_symbol_edge_stats.argtypes = [vp, vp]
+    lib.pre3_debug_advance.argtypes = [vp, vp, vp, i32, vp, i32, i32]
     lib.pre3_debug_resolve_row.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp]
     for name in EXPORTS:
         if name != "pre3_last_error":
@@ -110,7 +113,7 @@ class Pre3:
 
     def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
                  max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False,
-                 token_edges: bool = True, max_condition_depth: int = 0):
+                 token_edges: bool = True, max_condition_depth: int = 0, merged_reductions: bool = True):
         lib = load()
         if isinstance(grammars, str):
             grammars = [grammars]
@@ -119,7 +122,8 @@ class Pre3:
         vo = np.ascontiguousarray(vocab_offsets, dtype=np.int64)
         voc = _Vocab(vb.ctypes.data, vo.ctypes.data, len(vo) - 1, eos_id)
         opt = _Options(max_token_len, stack_cap,
-                       (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES),
+                       (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES)
+                       | (0 if merged_reductions else FLAG_STEPWISE_REDUCTIONS),
                        max_condition_depth)
         h = ctypes.c_void_p()
         rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
@@ -174,6 +178,25 @@ class Pre3:
         self._check(self._lib.pre3_token_edge_stats(self._h, out))
         keys = ["built", "roots", "nodes", "dense_rows", "delta_ids", "walk_ids", "max_known", "device_bytes"]
         return dict(zip(keys, list(out)))
+
+    def symbol_edge_stats(self):
+        out = (ctypes.c_int64 * 4)()
+        self._check(self._lib.pre3_symbol_edge_stats(self._h, out))
+        return dict(zip(["built", "nodes", "max_known", "device_bytes"], list(out)))
+
+    def debug_advance(self, stack, data: bytes, cap: int = 1 << 20, merged: bool = True, end: bool = False):
+        """Host mirror of advance on one stack: (rc, new stack list)."""
+        n = len(stack)
+        cap = int(min(cap, n + 8 * len(data) + 64))
+        st = np.zeros(cap, dtype=np.int32)
+        st[:n] = stack
+        ln = ctypes.c_int32(n)
+        buf = np.frombuffer(bytes(data) + b"\0", dtype=np.uint8)
+        rc = self._lib.pre3_debug_advance(self._h, st.ctypes.data, ctypes.byref(ln), cap, buf.ctypes.data,
+                                          -1 if end else len(data), int(merged))
+        if rc < 0:
+            raise Pre3Error(rc, "debug_advance")
+        return rc, st[: ln.value].tolist()
 
     def debug_resolve_row(self, stack):
         """(resolved?, row bits uint32[W], walk token ids) from the host copy of the tables."""

@@ -12,6 +12,7 @@
 #include "device_tables.hpp"
 #include "grammar.hpp"
 #include "launch.hpp"
+#include "symbol_edges.hpp"
 #include "tables.hpp"
 #include "token_edges.hpp"
 
@@ -25,6 +26,7 @@ struct pre3_handle {
     EdgeTables T;
     VocabLayout V;
     TokenEdges E;
+    SymbolEdges S;
     int max_depth = 0;
 
     std::vector<void *> allocations;     // device memory owned by the handle
@@ -95,6 +97,19 @@ int upload_tables(pre3_handle *h) {
     PRE3_UP(h->V.bytes, vbytes);
     PRE3_UP(h->V.offsets, voffsets);
 #undef PRE3_UP
+    D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_eff = nullptr; D.sym_pool = nullptr;
+    if (h->S.enabled) {
+        std::vector<int4> sn(h->S.nodes.size());
+        for (size_t i = 0; i < sn.size(); ++i)
+            sn[i] = make_int4(h->S.nodes[i].known, h->S.nodes[i].child_begin, h->S.nodes[i].child_count,
+                              h->S.nodes[i].first_child);
+        std::vector<int2> sp(h->S.child_state.size());
+        for (size_t i = 0; i < sp.size(); ++i) sp[i] = make_int2(h->S.child_state[i], h->S.child_node[i]);
+        if ((e = upload(h, sn, &D.sym_nodes)) != hipSuccess) return hip_fail(h, e, "upload sym_nodes");
+        if ((e = upload(h, sp, &D.sym_pairs)) != hipSuccess) return hip_fail(h, e, "upload sym_pairs");
+        if ((e = upload(h, h->S.eff, &D.sym_eff)) != hipSuccess) return hip_fail(h, e, "upload sym_eff");
+        if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
+    }
     D.n_states = h->T.n_states;
     D.ncol = h->T.n_classes + 1;
     D.end_col = h->T.n_classes;
@@ -196,6 +211,7 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
         h->V = build_vocab_layout(vocab->bytes, vocab->offsets, vocab->n_tokens, vocab->eos_id, max_token_len);
         // every input symbol adds at most height_per_byte - 1 private entries (see tables.cpp)
         h->max_depth = std::max(1, h->V.max_len) * (h->T.height_per_byte - 1) + 1;
+        if (!(opt && (opt->flags & PRE3_FLAG_STEPWISE_REDUCTIONS))) h->S = build_symbol_edges(h->T);
         if (!(opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EDGES))) {
             TokenEdgeLimits lim;
             if (opt && opt->max_condition_depth > 0) lim.max_known = opt->max_condition_depth;
@@ -353,6 +369,34 @@ int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]) {
     out[7] = (int64_t)(E.dense_rows.size() * 4 + (E.delta_ids.size() + E.walk_ids.size() + E.child_state.size() * 2 +
                                                    E.root_of_state.size()) * 4 + E.nodes.size() * sizeof(ConditionNode));
     return PRE3_OK;
+}
+
+int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]) {
+    if (!h || !h->compiled || !out) return PRE3_E_BADARG;
+    out[0] = h->S.enabled;
+    out[1] = (int64_t)h->S.nodes.size();
+    out[2] = h->S.max_known;
+    out[3] = (int64_t)(h->S.nodes.size() * sizeof(SymbolNode) + (h->S.eff.size() + h->S.pool.size() +
+                                                                 h->S.child_state.size() * 2) * 4);
+    return PRE3_OK;
+}
+
+int pre3_debug_advance(const pre3_handle *h, int32_t *stack, int32_t *len, int32_t cap, const uint8_t *bytes,
+                       int32_t n_bytes, int32_t use_merged) {
+    if (!h || !h->compiled || !stack || !len || *len < 1 || *len > cap || (n_bytes > 0 && !bytes)) return PRE3_E_BADARG;
+    if (use_merged && !h->S.enabled) return PRE3_E_BADARG;
+    if (stack[*len - 1] < 0 || stack[*len - 1] >= h->T.n_states) return PRE3_E_BADARG;
+    std::vector<int32_t> st(stack, stack + *len);
+    if (n_bytes < 0)                                            // end of input
+        return host_feed(h->T, h->S, st, h->T.n_classes, 0, 1 << 30, use_merged != 0) == kHostAccepted ? 0 : 1;
+    if (n_bytes == 0) return 1;
+    for (int i = 0; i < n_bytes; ++i) {
+        int r = host_feed(h->T, h->S, st, h->T.byte_class[bytes[i]], h->T.byte_delta[bytes[i]], cap, use_merged != 0);
+        if (r != kHostFed) return r == kHostOverflow ? 2 : 1;
+    }
+    std::copy(st.begin(), st.end(), stack);
+    *len = (int32_t)st.size();
+    return 0;
 }
 
 int pre3_debug_resolve_row(const pre3_handle *h, const int32_t *stack, int32_t len, uint32_t *row, int32_t *walk,

@@ -13,6 +13,11 @@ struct DevTables {
     const int32_t *goto_row;       // [n_states]
     const int32_t *goto_flat;
     int n_states, ncol, end_col;   // end_col = column of '$'
+    // merged reduction edges with stack-matching conditions (symbol_edges.hpp); null = not built
+    const int4 *sym_nodes;         // (known, child_begin, child_count, first_child)
+    const int2 *sym_pairs;         // (condition state, child node)
+    const int32_t *sym_eff;        // [nodes * ncol]
+    const int32_t *sym_pool;       // effect records, 16-byte aligned
     // vocabulary, chunk-sorted order
     const uint8_t *tok_len;        // [n_padded]
     const uint16_t *tok_bit;       // [n_padded]

@@ -4,6 +4,7 @@
 
 #include "device_tables.hpp"
 #include "launch.hpp"
+#include "symbol_edges.hpp"
 #include "tables.hpp"
 
 namespace pre3 {
@@ -34,20 +35,154 @@ struct PrivateStack {
 
 enum FeedResult { kFed = 0, kRejected = 1, kOverflow = 2, kAccepted = 3 };
 
+// Table look-ups.  In a wave that runs ONE walk (advance), every index is the same in all lanes:
+// the index is moved to a scalar register and the read-only table is addressed through the
+// constant address space, which lets the compiler use scalar loads served by the scalar cache
+// (a chain of dependent look-ups then costs a fraction of the vector-memory latency).  The
+// tables are never written by a kernel, so the scalar cache cannot hold stale data.
+template <typename V>
+using ConstPtr = const __attribute__((address_space(4))) V *;
+
+typedef int NativeInt2 __attribute__((ext_vector_type(2)));
+typedef int NativeInt4 __attribute__((ext_vector_type(4)));
+
+template <bool kUniform, typename V>
+__device__ __forceinline__ V table(const V *p, int i) {
+    if (kUniform) return ((ConstPtr<V>)p)[__builtin_amdgcn_readfirstlane(i)];
+    return p[i];
+}
+template <bool kUniform>
+__device__ __forceinline__ int2 table(const int2 *p, int i) {
+    if (kUniform) {
+        const NativeInt2 v = ((ConstPtr<NativeInt2>)p)[__builtin_amdgcn_readfirstlane(i)];
+        return make_int2(v.x, v.y);
+    }
+    return p[i];
+}
+template <bool kUniform>
+__device__ __forceinline__ int4 table(const int4 *p, int i) {
+    if (kUniform) {
+        const NativeInt4 v = ((ConstPtr<NativeInt4>)p)[__builtin_amdgcn_readfirstlane(i)];
+        return make_int4(v.x, v.y, v.z, v.w);
+    }
+    return p[i];
+}
+template <bool kUniform>
+__device__ __forceinline__ int uni(int v) {
+    return kUniform ? __builtin_amdgcn_readfirstlane(v) : v;
+}
+
+// The sequence's stack as the walk sees it: row[0..n), optionally with its top `kWindow` entries
+// staged in LDS (win[k] = entry k below the top).
+constexpr int kWindow = 64;
+struct StackView {
+    const int32_t *row;
+    const int32_t *win;
+    int n;
+    __device__ int32_t at(int idx) const {
+        const int k = n - 1 - idx;
+        return (win && k < kWindow) ? win[k] : row[idx];
+    }
+};
+
 // Consumes one input symbol (`info` = byte class column | target offset << 8) from the configuration
-//   row[0 .. base) ++ priv[0 .. d),  top = last entry,
-// following reduction steps until an acceptance edge shifts the symbol.  Each reduction step
-// pops, reads the exposed state (its stack-matching condition) and pushes the goto target.
+//   row[0 .. base) ++ priv[0 .. d),  top = last entry.
+// First the merged reduction edge is looked up: starting at the top state's condition node, the
+// stack entry each node names is matched against the node's condition states until a node holds
+// the symbol's effect (truncate, push list ending in the acceptance edge's target).  Where no
+// merged edge was precomputed the per-step edges are followed: each reduction step pops, reads
+// the exposed state (its stack-matching condition) and pushes the goto target, until an
+// acceptance edge shifts the symbol.
 // With kCheckCap the walk reports kOverflow exactly when a push would exceed `cap` entries.
-template <bool kCheckCap>
+template <bool kCheckCap, bool kUniform = false>
 __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int info, int &base, int &d,
-                                    int &top, const int32_t *__restrict__ row, int cap) {
+                                    int &top, const StackView &row, int cap) {
     const int col = info & 0xFF, delta = info >> 8;    // byte class and per-byte target offset
+    if (T.sym_eff) {
+        int node = top;
+        int4 nd = table<kUniform>(T.sym_nodes, node);
+        int code = table<kUniform>(T.sym_eff, node * T.ncol + col);
+        for (int level = 0; level < 64; ++level) {
+            if (code >= 0) {
+                // known, peak, n_push, push[0]; push[1..4] ride along in the same access
+                const int4 hdr = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), code >> 2);
+                int4 more = make_int4(0, 0, 0, 0);
+                if (kUniform) more = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), (code >> 2) + 1);
+                const int pops = hdr.x - 1, np = hdr.z;
+                if (kCheckCap && base + d + hdr.y >= cap) return kOverflow;
+                if (pops <= d) {
+                    d -= pops;
+                } else {
+                    base -= pops - d;
+                    d = 0;
+                    if (base < 1) return kRejected;              // only with a corrupted stack
+                }
+                if (d + np > T.max_depth) { if (!kUniform || (threadIdx.x & 63) == 0) atomicAdd(T.fault, 1); return kRejected; }
+                for (int i = 0; i < np; ++i) {
+                    int v;
+                    if (i == 0) v = hdr.w;
+                    else if (kUniform && i <= 4) v = i == 1 ? more.x : i == 2 ? more.y : i == 3 ? more.z : more.w;
+                    else v = table<kUniform>(T.sym_pool, code + 3 + i);
+                    if (i == np - 1) v += delta;
+                    priv.set(d++, v);
+                    top = v;
+                }
+                return kFed;
+            }
+            if (code == kEffNone) return kRejected;
+            if (code == kEffAccept) return kAccepted;
+            if (code == kEffStepwise) break;
+            int x;                                             // the entry nd.x below the top
+            if (nd.x < d) {
+                x = priv.get(d - 1 - nd.x);
+            } else {
+                const int idx = base - 1 - (nd.x - d);
+                if (idx < 0) break;
+                x = row.at(idx);
+            }
+            x = uni<kUniform>(x);
+            int next = -1;
+            if (kUniform) {
+                // all lanes run this walk: lane j fetches condition j together with child j's node
+                // record and effect code, so one round of loads both picks the child and enters it
+                const int lane = threadIdx.x & 63;
+                int4 cnd = make_int4(0, 0, 0, 0);
+                int ccode = kEffStepwise, cstate = -2;
+                for (int c0 = 0; c0 < nd.z && next < 0; c0 += 64) {
+                    const int j = c0 + lane;
+                    if (j < nd.z) {
+                        cstate = T.sym_pairs[nd.y + j].x;
+                        cnd = T.sym_nodes[nd.w + j];
+                        ccode = T.sym_eff[(nd.w + j) * T.ncol + col];
+                    }
+                    const unsigned long long m = __ballot(j < nd.z && cstate == x);
+                    if (m) {
+                        const int src = __ffsll((long long)m) - 1;
+                        next = nd.w + c0 + src;
+                        nd = make_int4(__shfl(cnd.x, src), __shfl(cnd.y, src), __shfl(cnd.z, src), __shfl(cnd.w, src));
+                        nd = make_int4(uni<true>(nd.x), uni<true>(nd.y), uni<true>(nd.z), uni<true>(nd.w));
+                        code = uni<true>(__shfl(ccode, src));
+                    }
+                }
+                if (next < 0) break;
+                node = next;
+            } else {
+                for (int i = 0; i < nd.z; ++i) {
+                    const int2 pr = T.sym_pairs[nd.y + i];
+                    if (pr.x == x) next = pr.y;
+                }
+                if (next < 0) break;
+                node = next;
+                nd = T.sym_nodes[node];
+                code = T.sym_eff[node * T.ncol + col];
+            }
+        }
+    }
     // A chain of reduction steps on one symbol is finite for LR(1) tables; the counter only
     // guarantees that a lane also terminates on tables or stacks that are not.
     for (int guard = 0;; ++guard) {
         if (guard > kMaxChain) { atomicAdd(T.fault, 1); return kRejected; }
-        const uint32_t e = T.edge[(size_t)top * T.ncol + col];
+        const uint32_t e = table<kUniform>(T.edge, top * T.ncol + col);
         const uint32_t kind = e & kKindMask;
         if (kind == kError) return kRejected;
         if (kind == kAccept) return kAccepted;
@@ -71,14 +206,15 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
             if (d > 0) {
                 exposed = priv.get(d - 1);
             } else {
-                exposed = row[base - 1];
+                exposed = row.at(base - 1);
                 if ((unsigned)exposed >= (unsigned)T.n_states) return kRejected;
             }
+            exposed = uni<kUniform>(exposed);
         }
         if (kCheckCap && base + d >= cap) return kOverflow;
-        const int r = T.goto_row[exposed];
+        const int r = table<kUniform>(T.goto_row, exposed);
         if (r < 0) return kRejected;
-        const int t = T.goto_flat[r + nt];
+        const int t = table<kUniform>(T.goto_flat, r + nt);
         if (t < 0) return kRejected;
         if (d >= T.max_depth) { atomicAdd(T.fault, 1); return kRejected; }
         top = t;
@@ -95,7 +231,7 @@ __device__ __forceinline__ bool walk_token(const DevTables &T, PrivateStack &pri
         if ((i & 3) == 0) w = T.tok_words[(size_t)(i >> 2) * T.n_padded + pos];
         const int info = T.byte_info[w & 0xFF];
         w >>= 8;
-        if (feed<false>(T, priv, info, base, d, top, row, 0) != kFed) return false;
+        if (feed<false>(T, priv, info, base, d, top, StackView{row, nullptr, len}, 0) != kFed) return false;
     }
     return true;
 }
@@ -103,7 +239,7 @@ __device__ __forceinline__ bool walk_token(const DevTables &T, PrivateStack &pri
 __device__ __forceinline__ bool walk_end(const DevTables &T, PrivateStack &priv, const int32_t *__restrict__ row,
                                          int len, int top0) {
     int base = len, d = 0, top = top0;
-    return feed<false>(T, priv, T.end_col, base, d, top, row, 0) == kAccepted;
+    return feed<false>(T, priv, T.end_col, base, d, top, StackView{row, nullptr, len}, 0) == kAccepted;
 }
 
 // One block per (sequence, vocabulary chunk) work item, grid-strided.  Every lane walks the
@@ -163,7 +299,7 @@ __device__ __forceinline__ bool walk_token_id(const DevTables &T, PrivateStack &
     const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
     if (hi <= lo) return false;
     for (int i = lo; i < hi; ++i)
-        if (feed<false>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, row, 0) != kFed) return false;
+        if (feed<false>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, StackView{row, nullptr, len}, 0) != kFed) return false;
     return true;
 }
 
@@ -445,6 +581,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
     int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch) {
     __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
+    __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
     __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int b = blockIdx.x * kAdvSeqPerBlock + wave;
@@ -455,44 +592,62 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     priv.lds_stride = kAdvSeqPerBlock;
     priv.spill = scratch + b;
     priv.spill_stride = (size_t)batch;
-    if (lane == 0) {
-        int commit = -1;                                  // private entries to copy, or -1
-        const int t = tokens[b];
-        const int n = len[b];
-        int top = -1;
-        if (t < 0) {
-            err[b] = 0;
+    // every lane: the sequence's inputs, then (in parallel across lanes) the top of the stack and
+    // the byte classes of the token, so that lane 0's walk finds them in LDS
+    const int t = tokens[b];
+    const int n = len[b];
+    const int st = states[b];
+    const bool live = t >= 0 && t < T.n_tokens && st >= 0 && n >= 1 && n <= cap;
+    int lo = 0, hi = 0;
+    if (live) {
+        s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
+        if (t != T.eos_id) {
+            lo = T.voffsets[t];
+            hi = T.voffsets[t + 1];
+            if (lo + lane < hi) s_info[wave][lane] = T.byte_info[T.vbytes[lo + lane]];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    // The walk itself runs on all 64 lanes with identical values (scalar table loads, LDS
+    // broadcast reads); lane 0 alone writes the results.
+    int commit = -1, out_err = 0, out_state = st, out_len = n;
+    if (t >= 0) {
+        int top = live ? __builtin_amdgcn_readfirstlane(s_win[wave][0]) : -1;
+        if (!live || (unsigned)top >= (unsigned)T.n_states) {
+            out_err = 1;
         } else {
-            if (states[b] >= 0 && n >= 1 && n <= cap) top = row[n - 1];
-            if (t >= T.n_tokens || (unsigned)top >= (unsigned)T.n_states) {
-                err[b] = 1;
+            const StackView view{row, s_win[wave], n};
+            int base = n, d = 0;
+            if (t == T.eos_id) {
+                if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) out_state = -1;
+                else out_err = 1;
             } else {
-                int base = n, d = 0;
-                if (t == T.eos_id) {
-                    if (feed<false>(T, priv, T.end_col, base, d, top, row, 0) == kAccepted) { states[b] = -1; err[b] = 0; }
-                    else err[b] = 1;
+                int rc = hi > lo ? kFed : kRejected;
+                for (int i = 0; i < hi - lo && rc == kFed; ++i) {
+                    const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[wave][i] : T.byte_info[T.vbytes[lo + i]]);
+                    rc = feed<true, true>(T, priv, info, base, d, top, view, cap);
+                }
+                if (rc != kFed) {
+                    out_err = rc == kOverflow ? 2 : 1;
                 } else {
-                    const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
-                    int rc = hi > lo ? kFed : kRejected;
-                    for (int i = lo; i < hi && rc == kFed; ++i)
-                        rc = feed<true>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, row, cap);
-                    if (rc != kFed) {
-                        err[b] = rc == kOverflow ? 2 : 1;
-                    } else {
-                        commit = d;
-                        s_base[wave] = base;
-                        len[b] = base + d;
-                        states[b] = top;
-                        err[b] = 0;
-                    }
+                    commit = d;
+                    out_len = base + d;
+                    out_state = top;
+                    s_base[wave] = base;
                 }
             }
         }
-        s_depth[wave] = commit;
+        if (lane == 0) {
+            err[b] = out_err;
+            if (out_err == 0) { states[b] = out_state; len[b] = out_len; }
+        }
+    } else if (lane == 0) {
+        err[b] = 0;
     }
+    s_depth[wave] = commit;
     __builtin_amdgcn_wave_barrier();
-    // LDS operations of one wave complete in order, so every lane sees lane 0's LDS writes;
-    // entries that spilled to global memory are copied by lane 0 itself
+    // LDS operations of one wave complete in order; entries that spilled to global memory are
+    // copied by lane 0
     const int d = s_depth[wave];
     if (d > 0) {
         const int base = s_base[wave];

@@ -53,6 +53,8 @@ struct VocabLayout {
 };
 
 EdgeTables build_edge_tables(const std::vector<Grammar> &grammars);
+// pred[s] = every state with a transition (acceptance edge or goto) into s, sorted
+std::vector<std::vector<int32_t>> predecessors(const EdgeTables &T);
 VocabLayout build_vocab_layout(const uint8_t *bytes, const int64_t *offsets, int n_tokens, int eos_id,
                                int max_token_len);
 

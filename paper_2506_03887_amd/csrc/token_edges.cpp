@@ -297,26 +297,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     const Trie &trie = tb.trie;
     const int ncol = T.n_classes + 1;
 
-    // predecessors: every p with a transition (acceptance edge or goto) into s
-    std::vector<std::vector<int32_t>> pred(T.n_states);
-    for (int g = 0; g < T.n_grammars; ++g) {
-        const Lr1Automaton &A = T.automata[g];
-        const int off = T.state_offset[g];
-        for (int s = 0; s < A.n_states; ++s) {
-            for (int a = 0; a < 256; ++a) {
-                uint32_t act = A.action[(size_t)s * kNumTerminals + a];
-                if ((act & 3u) == kShift) pred[off + (act >> 2)].push_back(off + s);
-            }
-            for (int nt = 0; nt < A.n_nt; ++nt) {
-                int t = A.go[(size_t)s * A.n_nt + nt];
-                if (t >= 0) pred[off + t].push_back(off + s);
-            }
-        }
-    }
-    for (auto &p : pred) {
-        std::sort(p.begin(), p.end());
-        p.erase(std::unique(p.begin(), p.end()), p.end());
-    }
+    const std::vector<std::vector<int32_t>> pred = predecessors(T);
 
     // states with identical edges, goto row and predecessors share one root
     std::map<std::tuple<std::vector<uint32_t>, int32_t, std::vector<int32_t>>, int> root_ids;

@@ -27,6 +27,12 @@ def test_cfg2_byte_by_byte_path():
     assert replay(2, steps=24, token_edges=False)["full_masks"] == 24
 
 
+def test_cfg2_one_reduction_step_at_a_time():
+    """Merged reduction edges switched off: walks and advance follow single reduction steps."""
+    assert replay(2, steps=24, token_edges=False, merged_reductions=False)["full_masks"] == 24
+    assert replay(1, merged_reductions=False)["full_masks"] == 32
+
+
 @pytest.mark.parametrize("depth", [1, 2, 4])
 def test_cfg2_shallow_conditions_leave_tokens_to_the_walk(depth):
     """Conditions limited to a few stack entries: the tree leaves walk lists (and, at depth 1,

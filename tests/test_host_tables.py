@@ -126,3 +126,36 @@ def test_walk_depth_bound_covers_deep_tokens(vocab):
     p = host_compile(G.JSON, vocab, max_token_len=12)
     rc, st = o.advance(o.initial_stack(), b"[" * vocab.max_len)
     assert rc == 0 and p.walk_depth_bound >= len(st) - 1
+
+
+@pytest.mark.parametrize("texts,prefixes", [
+    ([G.JSON], [b"", b'{"a', b"[1", b'{"k": [tr', b"[[[[", b'"x\\', b"12.5e", b" 7 ", b'{"a":{"b":[{},[[]],"', b"[[1,2],[3"]),
+    ([G.ARITHMETIC, G.DYCK], [b"", b"(a+a", b"((a*(a", b"a+a*a"]),
+])
+def test_merged_reduction_edges_equal_oracle_advance(texts, prefixes, vocab):
+    """Alg. 1 step 3: every reduction chain collapsed into one edge with a stack-matching
+    condition.  The host mirror of the device walk, with merged edges and with one reduction
+    step at a time, must reproduce the oracle's advance (result code and stack) and its EOS test."""
+    import random
+    o = Oracle(texts)
+    p = host_compile(texts, vocab)
+    stats = p.symbol_edge_stats()
+    assert stats["built"] == 1 and stats["nodes"] >= p.n_states
+    rnd = random.Random(4)
+    n_ok = 0
+    for prefix in prefixes:
+        rc, st = (0, o.initial_stack()) if not prefix else o.advance(o.initial_stack(), prefix)
+        assert rc == 0
+        assert (p.debug_advance(st, b"", end=True)[0] == 0) == o.eos_allowed(st)
+        toks = [vocab.tokens[rnd.randrange(vocab.n_tokens - 1)] for _ in range(300)]
+        toks += [b"]", b"}", b"]]", b'"', b'",', b"1", b",", b" ", b"]]]]", b"[" * 12, b")", b"))", b"+a", b""]
+        for tok in toks:
+            for cap in (len(st) + 3, len(st) + 64):
+                want = o.advance(st, tok, cap=cap) if tok else (1, st)
+                for merged in (True, False):
+                    got = p.debug_advance(st, tok, cap=cap, merged=merged)
+                    assert got[0] == want[0], (prefix, tok, cap, merged)
+                    if want[0] == 0:
+                        assert got[1] == want[1], (prefix, tok, cap, merged)
+                        n_ok += 1
+    assert n_ok > 30
