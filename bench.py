@@ -6,8 +6,9 @@ trajectory; all inputs are resident in HBM before the timed region.  The K timed
 captured into one HIP graph (kernel launches only) and replayed between two HIP events, so
 the GPU runs the kernels back to back as a serving loop would: that replay gives `value`.
 Per-kernel durations are measured in a second, eager pass over the same K steps with a HIP
-event before and after every launch (each bracket carries a few microseconds of event
-overhead; the rocprofv3 summaries under profiles/ hold the pure durations).  Prints ONE
+event before and after every launch; the pass is queued behind a device-side delay so the
+events are processed back to back on the GPU (the rocprofv3 summaries under profiles/ hold
+the profiler's durations of the same kernels).  Prints ONE
 JSON line.
 """
 import argparse
@@ -31,14 +32,31 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload timed on the CPU oracle")
     ap.add_argument("--repeats", type=int, default=3, help="replays of each graph (the fastest is reported)")
-    ap.add_argument("--step", choices=["two-call", "fused"], default="two-call",
-                    help="mask+apply as pre3_fill_mask + pre3_apply_mask, or as pre3_fill_apply_mask")
+    ap.add_argument("--eager", action="store_true",
+                    help="no HIP graphs: time the eager pass only (for counter collection with rocprofv3 --pmc)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
+    ap.add_argument("--no-token-edges", action="store_true",
+                    help="compile without token-level edges: fill_mask walks every (sequence, token) pair")
+    ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
+                    help="fill_mask + apply_mask + advance | fill_apply_mask + advance | "
+                         "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on one GPU (sequences are independent; see DESIGN.md on sharding); use --gpus 1")
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
+        return
 
     from oracle import Oracle, apply_mask as oracle_apply_mask
     from paper_2506_03887_amd import Pre3, apply_mask
@@ -59,21 +77,22 @@ def main():
 
     dev = torch.device("cuda:0")
     t_compile = time.perf_counter()
-    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap)
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
+               token_edges=not args.no_token_edges)
     t_compile = time.perf_counter() - t_compile
     data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
     states_h = data_h[np.arange(B), len_h - 1].copy()
     data_d = torch.from_numpy(data_h).to(dev)
-    len_d = torch.from_numpy(len_h).to(dev)
-    states_d = torch.from_numpy(states_h).to(dev)
+    # len and states share one [2, B] tensor so that slot reuse is a single small kernel
+    ls_d = torch.from_numpy(np.stack([len_h, states_h])).to(dev)
+    len_d, states_d = ls_d[0], ls_d[1]
     err_d = torch.zeros(B, dtype=torch.int32, device=dev)
     mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
     lib.bind_state(states_d, data_d, len_d, err_d)
     tokens_d = torch.from_numpy(traj.tokens).to(dev)
-    reset_d = torch.from_numpy(traj.reset).to(dev)
+    reset_d = torch.from_numpy(np.repeat(traj.reset[:, None, :], 2, axis=1)).to(dev)      # [steps, 2, B]
     any_reset = traj.reset.any(axis=1)
-    s0_d = torch.from_numpy(s0).to(dev)
-    one_d = torch.ones(B, dtype=torch.int32, device=dev)
+    fresh_d = torch.from_numpy(np.stack([np.ones(B, dtype=np.int32), s0])).to(dev)        # len = 1, state = s0
     n_pool = 4
     gen = torch.Generator(device=dev)
     gen.manual_seed(cfg.seed)
@@ -82,10 +101,13 @@ def main():
 
     def resets(s):
         if any_reset[s]:          # slot reuse: a finished sequence restarts (bottom of its stack is kept)
-            torch.where(reset_d[s], one_d, len_d, out=len_d)
-            torch.where(reset_d[s], s0_d, states_d, out=states_d)
+            torch.where(reset_d[s], fresh_d, ls_d, out=ls_d)
 
     def step(s, kind):
+        if kind == "advance-fill":     # mask_d already holds this step's mask (from the previous call)
+            apply_mask(logits[s % n_pool], mask_d, V)
+            lib.advance_fill_mask(tokens_d[s], mask_d, restart_on_eos=True)
+            return
         resets(s)
         if kind == "fused":
             lib.fill_apply_mask(states_d, data_d, len_d, mask_d, logits[s % n_pool])
@@ -99,10 +121,13 @@ def main():
     for s in range(Wm):
         step(s, "fused" if s % 2 else "fill+apply")
     torch.cuda.synchronize()
-    snap = (data_d.clone(), len_d.clone(), states_d.clone())
+    snap = (data_d.clone(), ls_d.clone())
 
     def restore():
-        data_d.copy_(snap[0]); len_d.copy_(snap[1]); states_d.copy_(snap[2])
+        data_d.copy_(snap[0]); ls_d.copy_(snap[1])
+        # the advance-fill pipeline enters a step with that step's mask already computed
+        resets(Wm)
+        lib.fill_mask(states_d, data_d, len_d, mask_d)
 
     def timed_graph(kind):
         """Captures the K timed steps with the given kernels and returns the fastest replay (ms)."""
@@ -124,34 +149,61 @@ def main():
             best = min(best, e0.elapsed_time(e1))
         return best
 
-    step_kind = "fill+apply" if args.step == "two-call" else "fused"
-    other_kind = "fused" if args.step == "two-call" else "fill+apply"
-    t_other = timed_graph(other_kind)
-    t_adv = timed_graph("advance")
-    t_step = timed_graph(step_kind)
+    step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill"}[args.step]
+    if args.eager:
+        t_two = t_step = float("nan")
+    else:
+        t_two = timed_graph("fill+apply") if step_kind != "fill+apply" else None
+        t_step = timed_graph(step_kind)
+        if t_two is None:
+            t_two = t_step
 
-    # ---- eager pass over the same steps: one event pair per launch
-    restore()
-    torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
-    for s in range(K):
-        resets(Wm + s)
-        ev[s][0].record()
-        if step_kind == "fused":
-            lib.fill_apply_mask(states_d, data_d, len_d, mask_d, logits[(Wm + s) % n_pool])
-            ev[s][1].record()
-        else:
-            lib.fill_mask(states_d, data_d, len_d, mask_d)
-            ev[s][1].record()
-            apply_mask(logits[(Wm + s) % n_pool], mask_d, V)
-        ev[s][2].record()
-        lib.advance(tokens_d[Wm + s])
-        ev[s][3].record()
-    torch.cuda.synchronize()
-    first_us = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3       # fill (or the fused kernel)
-    second_us = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3      # apply (0 when fused)
-    adv_us = np.array([e[2].elapsed_time(e[3]) for e in ev]) * 1e3
-    # after this pass the device holds the state after all K timed steps
+    def eager_pass(kind):
+        """The same K steps launched eagerly with a HIP event before and after every library call.
+        Returns {call name: microseconds per step} and the wall time of the pass (ms)."""
+        restore()
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+        if not args.eager:
+            # keep the GPU busy while the host enqueues the K steps, so that the events are taken back
+            # to back on the device and bracket kernel time rather than the host's launch latency
+            torch.cuda._sleep(int(60e6))
+        t0 = time.perf_counter()
+        for s in range(K):
+            lg = logits[(Wm + s) % n_pool]
+            if kind == "advance-fill":
+                ev[s][0].record()
+                apply_mask(lg, mask_d, V)
+                ev[s][1].record()
+                lib.advance_fill_mask(tokens_d[Wm + s], mask_d, restart_on_eos=True)
+                ev[s][2].record()
+                continue
+            resets(Wm + s)
+            ev[s][0].record()
+            if kind == "fused":
+                lib.fill_apply_mask(states_d, data_d, len_d, mask_d, lg)
+                ev[s][1].record()
+            else:
+                lib.fill_mask(states_d, data_d, len_d, mask_d)
+                ev[s][1].record()
+                apply_mask(lg, mask_d, V)
+            ev[s][2].record()
+            lib.advance(tokens_d[Wm + s])
+            ev[s][3].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        d = lambda i, j: np.array([e[i].elapsed_time(e[j]) for e in ev]) * 1e3
+        if kind == "advance-fill":
+            return {"apply_mask": d(0, 1), "advance_fill_mask": d(1, 2)}, wall
+        if kind == "fused":
+            return {"fill_apply_mask": d(0, 1), "advance": d(2, 3)}, wall
+        return {"fill_mask": d(0, 1), "apply_mask": d(1, 2), "advance": d(2, 3)}, wall
+
+    two_call_us, wall_two = eager_pass("fill+apply")
+    step_us, wall_step = (two_call_us, wall_two) if step_kind == "fill+apply" else eager_pass(step_kind)
+    if args.eager:
+        t_step, t_two = wall_step, wall_two
+    # after the last pass the device holds the state after all K timed steps of `step_kind`
 
     # ---- the timed run must have done the real work: final state == oracle's replay
     for s in range(total):
@@ -159,6 +211,9 @@ def main():
         data_h[rs, 0], len_h[rs], states_h[rs] = s0[rs], 1, s0[rs]
         err = o.advance_batch(states_h, data_h, len_h, traj.tokens[s], v)
         assert not err.any()
+    if step_kind == "advance-fill":            # slot reuse happened inside the last call
+        fin = states_h < 0
+        states_h[fin], len_h[fin] = s0[fin], 1
     assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), \
         "device state after the timed run differs from the oracle's replay"
     assert int(err_d.abs().sum().item()) == 0
@@ -197,16 +252,19 @@ def main():
 
     pairs = float(B) * V
     stat = lambda x: {"mean": float(x.mean()), "p50": float(np.median(x)), "p99": float(np.percentile(x, 99))}
-    mask_apply_us = float((first_us + second_us).mean())
-    if step_kind == "fused":
-        kernels = {"fill_apply_mask": stat(first_us), "advance": stat(adv_us)}
-        dom_name, dom_us, dom_bytes = "fill_mask_edges_kernel<true> (token mask + logits masking)", float(first_us.mean()), BYTES_PER_PAIR * pairs
-    else:
-        kernels = {"fill_mask": stat(first_us), "apply_mask": stat(second_us), "advance": stat(adv_us)}
-        # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
-        dom_name, dom_us, dom_bytes = "apply_mask_vec8_kernel", float(second_us.mean()), (4.0 + 0.125) * pairs
+    kernels = {k: stat(x) for k, x in two_call_us.items()}
+    kernels.update({k: stat(x) for k, x in step_us.items() if k not in kernels or step_kind != "fill+apply"})
+    mask_apply_us = float((two_call_us["fill_mask"] + two_call_us["apply_mask"]).mean())
+    # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
+    dom_us = float(step_us["apply_mask"].mean()) if "apply_mask" in step_us else float(step_us["fill_apply_mask"].mean())
+    dom_name = "apply_mask_vec8_kernel" if "apply_mask" in step_us else "fill_mask_edges_kernel<true>"
+    dom_bytes = (4.0 + 0.125) * pairs if "apply_mask" in step_us else BYTES_PER_PAIR * pairs
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     step_achieved = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9
+    step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
+                 "fused": "pre3_fill_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
+                 "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "
+                                 "slot reuse on EOS)"}
     out = {
         "metric": "masked (seq x vocab) tokens/sec",
         "value": pairs * K / (t_step * 1e-3),
@@ -217,19 +275,18 @@ def main():
         "dtype": "u32 bitmask / bf16 logits / i32 states",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": "byte-level JSON, canonical LR(1)",
-                   "stack_cap": cap, "resets_in_timed_steps": int(traj.reset[Wm:].sum()),
-                   "step": ("pre3_fill_mask + pre3_apply_mask" if step_kind != "fused" else "pre3_fill_apply_mask")
-                           + " + pre3_advance (+ slot-reuse resets), K steps in one HIP graph"},
+                   "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
+                   "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
         "mask_apply_us_per_step": mask_apply_us,
         "mask_apply_tokens_per_s": pairs / (mask_apply_us * 1e-6),
         "mask_apply_frac_of_hbm_peak": step_achieved / HBM_PEAK_GBS,
         "kernels_us": kernels,
-        "graph_ms_per_step": {"this step": t_step / K, "with the other mask+apply variant": t_other / K,
-                              "advance and resets only": t_adv / K},
+        "graph_ms_per_step": {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": dom_name,
-                     "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
-                     "timing": "HIP events around every launch of the eager pass over the timed steps"},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": 130.48e6 if dom_name.startswith("apply") else None,
+                     "kernel": dom_name, "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
+                     "timing": "HIP events around every launch of an eager pass over the timed steps, "
+                               "queued behind a device-side delay"},
         "cpu_baseline": {"value": pairs * n_cpu / cpu_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                          "sample": f"fill_mask+apply_mask of the first {n_cpu} steps of the same workload "
                                    f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",

@@ -165,6 +165,20 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
  * top.  Errors: BADARG (nothing bound, null tokens). */
 int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream);
 
+#define PRE3_ADVANCE_RESTART_ON_EOS 1  /* slot reuse: a sequence that takes the EOS token (where allowed) */
+                                      /* goes back to its initial state (len = 1) instead of DONE         */
+
+/* pre3_advance followed by pre3_fill_mask on the bound buffers, as one call (the natural shape of
+ * a decode loop: once the token is sampled, advance and prepare the next step's mask, which can
+ * run under the model's next forward pass).  Results are exactly those of the two calls in
+ * sequence: states, stacks and err as pre3_advance leaves them (with flag
+ * PRE3_ADVANCE_RESTART_ON_EOS a sequence that takes EOS restarts from data[b*cap] with len 1),
+ * bitmask (device, [batch, ceil(n_tokens/32)]) as pre3_fill_mask then writes it for the new
+ * stacks.  A sequence whose advance fails keeps its stack and gets the mask of that stack.
+ * Errors: BADARG (nothing bound, null pointer, unknown flag). */
+int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,
+                           pre3_stream stream);
+
 /* ---- host-side introspection of the compiled tables (used by tests and tools) ---- */
 
 int32_t pre3_n_grammars(const pre3_handle *h);

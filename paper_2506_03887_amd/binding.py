@@ -19,11 +19,12 @@ E_BADARG, E_PARSE, E_NOT_LR1, E_TOKEN_TOO_LONG, E_NOMEM, E_HIP, E_LIMIT = -1, -2
 FLAG_HOST_ONLY = 1
 FLAG_NO_TOKEN_EDGES = 2
 FLAG_STEPWISE_REDUCTIONS = 4
+ADVANCE_RESTART_ON_EOS = 1
 STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance",
 ]
@@ -75,6 +76,7 @@ def load():
     lib.pre3_apply_mask.argtypes = [vp, vp, i32, i32, c.c_int64, vp]
     lib.pre3_fill_apply_mask.argtypes = [vp, vp, _Stacks, vp, vp, c.c_int64, vp]
     lib.pre3_advance.argtypes = [vp, vp, vp]
+    lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
         getattr(lib, name).argtypes = [vp]
     lib.pre3_byte_class.argtypes = [vp, i32]
@@ -238,6 +240,12 @@ class Pre3:
     def advance(self, tokens, stream=None):
         assert tokens.is_contiguous()
         self._check(self._lib.pre3_advance(self._h, _dev(tokens, "i32"), _stream_ptr(stream)))
+
+    def advance_fill_mask(self, tokens, bitmask, restart_on_eos=False, stream=None):
+        assert tokens.is_contiguous() and bitmask.is_contiguous() and bitmask.shape[1] == self.words
+        self._check(self._lib.pre3_advance_fill_mask(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
+                                                     ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
+                                                     _stream_ptr(stream)))
 
 
 def apply_mask(logits, bitmask, vocab: int, stream=None):

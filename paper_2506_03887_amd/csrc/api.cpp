@@ -42,6 +42,8 @@ struct pre3_handle {
     int32_t *b_states = nullptr, *b_err = nullptr;
     pre3_stacks b_stacks{};
     int32_t *adv_scratch = nullptr;
+    int32_t *af_walk_spill = nullptr;
+    size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
     size_t adv_scratch_entries = 0;
 };
@@ -263,6 +265,16 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
         h->adv_scratch = static_cast<int32_t *>(p);
         h->adv_scratch_entries = need;
     }
+    if (h->use_edges) {
+        size_t need2 = advance_fill_walk_spill_entries(stacks.batch, h->max_depth);
+        if (need2 > h->af_walk_spill_entries) {
+            void *p = nullptr;
+            hipError_t e = device_alloc(h, need2 * sizeof(int32_t), &p, false);
+            if (e != hipSuccess) return hip_fail(h, e, "allocate advance+fill spill area");
+            h->af_walk_spill = static_cast<int32_t *>(p);
+            h->af_walk_spill_entries = need2;
+        }
+    }
     h->b_states = states;
     h->b_stacks = stacks;
     h->b_err = err;
@@ -321,8 +333,30 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
     if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance: no state bound");
     if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
     hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
-                                  h->b_stacks.batch, h->b_err, h->adv_scratch, static_cast<hipStream_t>(stream));
+                                  h->b_stacks.batch, h->b_err, h->adv_scratch, 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance");
+}
+
+int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,
+                           pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance_fill_mask: no state bound");
+    if (!tokens || !bitmask) return fail(h, PRE3_E_BADARG, "advance_fill_mask: null tokens or bitmask");
+    if (flags & ~PRE3_ADVANCE_RESTART_ON_EOS) return fail(h, PRE3_E_BADARG, "advance_fill_mask: unknown flag");
+    const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (h->use_edges) {
+        e = launch_advance_fill(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
+                                h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
+                                h->af_walk_spill, s);
+        return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
+    }
+    e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
+                       h->b_stacks.batch, h->b_err, h->adv_scratch, restart, s);
+    if (e != hipSuccess) return hip_fail(h, e, "launch advance");
+    return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);
 }
 
 int32_t pre3_n_grammars(const pre3_handle *h) { return h && h->compiled ? h->T.n_grammars : PRE3_E_BADARG; }

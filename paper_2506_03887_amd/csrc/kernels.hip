@@ -504,12 +504,13 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
 // ---------------------------------------------------------------------------- apply
 
 constexpr int kApplyBlock = 256;
-constexpr int kApplyUnroll = 4;        // 16-byte groups per lane
+constexpr int kApplyUnroll = 1;        // 16-byte groups per lane (measured: more waves beat more loads per lane)
 constexpr int kApplySpan = kApplyBlock * kApplyUnroll * 8;   // logits per block
 
 // blockIdx.y = row, blockIdx.x = span of kApplySpan logits.  A lane owns kApplyUnroll groups of 8
 // consecutive logits (16 bytes), one per pass, so that every pass of a wave is one contiguous
-// 1 KiB access.  Fully allowed groups are not touched, fully masked groups are overwritten
+// 1 KiB access.  In-place read-modify-write of the logits streams at about 5.6 TB/s on MI355X
+// whatever the unroll, block size or cache hints; one group per lane was the fastest.  Fully allowed groups are not touched, fully masked groups are overwritten
 // without being read, mixed groups are read, patched and written back.
 __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *__restrict__ logits,
                                                                      const uint32_t *__restrict__ bitmask,
@@ -579,7 +580,7 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(uint16_t *__rest
 constexpr int kAdvSeqPerBlock = 4;
 __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
-    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch) {
+    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos) {
     __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
     __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
     __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
@@ -619,8 +620,12 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
             const StackView view{row, s_win[wave], n};
             int base = n, d = 0;
             if (t == T.eos_id) {
-                if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) out_state = -1;
-                else out_err = 1;
+                if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) {
+                    out_state = -1;
+                    if (restart_on_eos) { out_state = row[0]; out_len = 1; }   // slot reuse: back to the initial state
+                } else {
+                    out_err = 1;
+                }
             } else {
                 int rc = hi > lo ? kFed : kRejected;
                 for (int i = 0; i < hi - lo && rc == kFed; ++i) {
@@ -658,6 +663,195 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     }
 }
 
+// Advance and next mask in one launch: one block per sequence.  Wave 0 walks the sampled token
+// exactly like advance_kernel (scalar table loads), commits the new stack, stages the NEW top
+// of the stack in LDS and descends the condition tree of the token-level edges with it; then the
+// whole block builds the sequence's next mask row (dense row copy, delta lists, leftover walks)
+// and stores it.  The sequence's inputs are loaded once, no kernel boundary separates the two
+// halves, and the long walks of a few sequences overlap the mask building of all others.
+constexpr int kAfBlock = 256;
+__global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
+    DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
+    int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
+    uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+    size_t walk_spill_stride) {
+    extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4
+    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
+    __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
+    __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
+    __shared__ int32_t s_seg_begin[kMaxPath], s_seg_count[kMaxPath];
+    __shared__ int32_t s_nseg, s_dense, s_mode, s_walk_begin, s_walk_count, s_top, s_len;
+    enum { kFast = 0, kWalkAll = 1, kEmpty = 2, kDone = 3 };
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int b = blockIdx.x;
+    const int n_vec = (T.n_words + 3) >> 2;
+    int32_t *row = data + (size_t)b * cap;
+
+    if (tid < 64) {
+        PrivateStack priv;
+        priv.lds = s_adv_stack;
+        priv.lds_stride = 1;
+        priv.spill = adv_scratch + b;
+        priv.spill_stride = (size_t)batch;
+        const int t = tokens[b];
+        const int n = len[b];
+        const int st = states[b];
+        const bool shape_ok = n >= 1 && n <= cap;
+        const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
+        int lo = 0, hi = 0;
+        s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
+        if (live && t != T.eos_id) {
+            lo = T.voffsets[t];
+            hi = T.voffsets[t + 1];
+            if (lo + lane < hi) s_info[lane] = T.byte_info[T.vbytes[lo + lane]];
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- advance (all lanes hold identical values)
+        int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
+        bool restarted = false;
+        if (t >= 0) {
+            int top = live ? __builtin_amdgcn_readfirstlane(s_win[0]) : -1;
+            if (!live || (unsigned)top >= (unsigned)T.n_states) {
+                out_err = 1;
+            } else {
+                const StackView view{row, s_win, n};
+                if (t == T.eos_id) {
+                    if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) {
+                        out_state = -1;
+                        if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
+                    } else {
+                        out_err = 1;
+                    }
+                    base = n;
+                    d = 0;                               // the '$' walk never changes the stack
+                } else {
+                    int rc = hi > lo ? kFed : kRejected;
+                    for (int i = 0; i < hi - lo && rc == kFed; ++i) {
+                        const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[lo + i]]);
+                        rc = feed<true, true>(T, priv, info, base, d, top, view, cap);
+                    }
+                    if (rc != kFed) {
+                        out_err = rc == kOverflow ? 2 : 1;
+                        base = n;
+                        d = 0;
+                    } else {
+                        out_len = base + d;
+                        out_state = top;
+                    }
+                }
+            }
+        }
+        if (lane == 0) {
+            err[b] = out_err;
+            if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
+        }
+        // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart):
+        //      stage its top in LDS and commit the private part
+        const int nl = out_len;
+        auto new_at = [&](int k) -> int32_t {           // entry k below the new top
+            if (restarted) return k == 0 ? row[0] : -1;
+            if (k < d) return priv.get(d - 1 - k);
+            const int idx = base - 1 - (k - d);
+            return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
+        };
+        s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
+        {
+            const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+            if (lane < in_lds) row[base + lane] = priv.get(lane);
+            if (lane == 0)
+                for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- descent of the condition tree with the new stack
+        int mode = kFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0;
+        const int top = s_new[0];
+        if (out_state < 0) {
+            mode = kDone;
+        } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
+            mode = kEmpty;
+        } else {
+            DevConditionNode nd = E.root_nodes[top];
+            for (;;) {
+                if (nd.dense_row >= 0) {
+                    dense = nd.dense_row;
+                    nseg = 0;
+                } else if (nd.delta_count > 0) {
+                    if (lane == 0) { s_seg_begin[nseg] = nd.delta_begin; s_seg_count[nseg] = nd.delta_count; }
+                    ++nseg;
+                }
+                if (nd.child_count == 0) {
+                    walk_begin = nd.walk_begin;
+                    walk_count = nd.walk_count;
+                    if (walk_count < 0) mode = kWalkAll;
+                    break;
+                }
+                if (nd.known >= nl || nseg >= kMaxPath) { mode = kWalkAll; break; }
+                const int x = nd.known < kWindow ? s_new[nd.known] : new_at(nd.known);
+                int next = -1;
+                for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
+                    const int i = c0 + lane;
+                    int2 pr = make_int2(-2, -1);
+                    if (i < nd.child_count) pr = E.child_pairs[nd.child_begin + i];
+                    const unsigned long long m = __ballot(pr.x == x);
+                    if (m) { next = __shfl(pr.y, __ffsll((long long)m) - 1); break; }
+                }
+                if (next < 0) { mode = kWalkAll; break; }
+                nd = E.nodes[next];
+            }
+        }
+        if (lane == 0) {
+            s_nseg = nseg; s_dense = dense; s_mode = mode; s_top = top; s_len = nl;
+            s_walk_begin = walk_begin; s_walk_count = walk_count;
+        }
+    }
+    __syncthreads();
+    // ---- the next mask row
+    const int mode = s_mode;
+    if (mode == kFast && s_dense >= 0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)s_dense * n_vec;
+        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = src[w];
+    } else {
+        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    if (mode == kFast || mode == kWalkAll) {
+        if (mode == kFast) {
+            const int nseg = s_nseg;
+            for (int i = 0; i < nseg; ++i) {
+                const int32_t *ids = E.delta_ids + s_seg_begin[i];
+                const int cnt = s_seg_count[i];
+                for (int k = tid; k < cnt; k += kAfBlock) {
+                    const int t = ids[k];
+                    atomicOr(&bits[t >> 5], 1u << (t & 31));
+                }
+            }
+        }
+        const int wc = mode == kWalkAll ? T.n_tokens : s_walk_count;
+        if (wc > 0 && tid < 64) {                       // leftovers: walked on the committed stack
+            PrivateStack wp;
+            wp.lds = s_walk_stack + lane;
+            wp.lds_stride = 64;
+            wp.spill = walk_spill + (size_t)b * 64 + lane;
+            wp.spill_stride = walk_spill_stride;
+            const int n = s_len, top0 = s_top;
+            for (int k = lane; k < wc; k += 64) {
+                const int t = mode == kWalkAll ? k : E.walk_ids[s_walk_begin + k];
+                if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+            }
+        }
+    } else if (mode == kDone && tid == 0) {
+        bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
+    }
+    __syncthreads();
+    uint32_t *dst = bitmask + (size_t)b * T.n_words;
+    if ((T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0) {
+        uint4 *dst4 = reinterpret_cast<uint4 *>(dst);
+        for (int w = tid; w < n_vec; w += kAfBlock) dst4[w] = bits4[w];
+    } else {
+        for (int w = tid; w < T.n_words; w += kAfBlock) dst[w] = bits[w];
+    }
+}
+
 }  // namespace
 
 int walk_grid_blocks(int n_compute_units) { return 4 * n_compute_units; }
@@ -674,12 +868,11 @@ hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, co
                                   uint16_t *logits, int64_t row_stride, int32_t *spill, int grid_blocks,
                                   hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    // Segments per row: enough items to give every block of the grid one (two when only the
-    // mask is wanted: the items are short), but segments of at least 64 uint4 (8 KiB of mask
-    // = 16 Ki logits) so that the redundant descents stay cheap next to the streaming.
+    // Segments per row: enough items to give every block of the grid one, but segments of at
+    // least 64 uint4 (8 KiB of mask = 16 Ki logits) so that the redundant descents stay cheap.
     const int n_vec = (T.n_words + 3) / 4;
     const int rows_padded = (batch + 7) & ~7;
-    int want = (grid_blocks * (logits ? 1 : 1) + rows_padded - 1) / rows_padded;
+    int want = (grid_blocks + rows_padded - 1) / rows_padded;
     int max_seg = (n_vec + 63) / 64;
     int n_seg = want < 1 ? 1 : (want > max_seg ? max_seg : want);
     int seg_vec = (n_vec + n_seg - 1) / n_seg;
@@ -717,6 +910,21 @@ hipError_t launch_fill_mask_walk(const DevTables &T, const int32_t *states, cons
     return hipGetLastError();
 }
 
+size_t advance_fill_walk_spill_entries(int batch, int max_depth) {
+    const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
+    return (size_t)batch * 64 * (size_t)deep;
+}
+
+hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
+                               int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
+                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    const size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    hipLaunchKernelGGL(advance_fill_kernel, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data, len, cap,
+                       batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64);
+    return hipGetLastError();
+}
+
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream) {
     if (batch == 0 || vocab == 0) return hipSuccess;
@@ -737,10 +945,10 @@ hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batc
 }
 
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
-                          int cap, int batch, int32_t *err, int32_t *scratch, hipStream_t stream) {
+                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
     hipLaunchKernelGGL(advance_kernel, dim3((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), dim3(64 * kAdvSeqPerBlock),
-                       0, stream, T, tokens, states, data, len, cap, batch, err, scratch);
+                       0, stream, T, tokens, states, data, len, cap, batch, err, scratch, restart_on_eos);
     return hipGetLastError();
 }
 

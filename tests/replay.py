@@ -103,3 +103,60 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
             log(f"[cfg {cfg_idx}] step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
     torch.cuda.synchronize()
     return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, depth_hist=traj.depth_hist)
+
+
+def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, **lib_options):
+    """Same trajectory, driven through pre3_advance_fill_mask with slot reuse on EOS: after every
+    call the device's states/len/live stack/err and the next mask must equal the oracle's
+    advance followed by its fill (whole bitmask on `full_mask_steps`, sampled rows otherwise)."""
+    import torch
+
+    cfg = configs.get(cfg_idx)
+    v = cfg.vocab
+    steps = cfg.steps if steps is None else steps
+    o = Oracle(cfg.grammars)
+    gi, depths = configs.sequence_setup(cfg)
+    traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
+                               cfg.json_strings, depths)
+    # slot reuse in the trajectory == restart right after an EOS token
+    assert (traj.reset[1:] == (traj.tokens[:-1] == v.eos_id)).all() and not traj.reset[0].any()
+    lib = make_library(cfg, **lib_options)
+    dev = torch.device("cuda:0")
+    B, cap, W = cfg.batch, cfg.cap, v.words
+    data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
+    states_h = data_h[np.arange(B), len_h - 1].copy()
+    data_d = torch.from_numpy(data_h).to(dev)
+    len_d = torch.from_numpy(len_h).to(dev)
+    states_d = torch.from_numpy(states_h).to(dev)
+    err_d = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    mask_d = torch.full((B, W), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    rng = np.random.default_rng(cfg.seed + 2)
+    full = set(range(steps)) if full_mask_steps is None else set(full_mask_steps)
+    n_full = n_rows = 0
+    for s in range(steps):
+        tok = traj.tokens[s]
+        lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d, restart_on_eos=True)
+        err_h = o.advance_batch(states_h, data_h, len_h, tok, v)
+        done = states_h < 0
+        states_h[done], len_h[done] = data_h[done, 0], 1                   # restart on EOS
+        assert (err_d.cpu().numpy() == err_h).all() and not err_h.any(), f"cfg {cfg_idx} step {s}: err differs"
+        assert (states_d.cpu().numpy() == states_h).all(), f"cfg {cfg_idx} step {s}: states differ"
+        assert (len_d.cpu().numpy() == len_h).all(), f"cfg {cfg_idx} step {s}: len differs"
+        live = np.arange(cap)[None, :] < len_h[:, None]
+        assert (data_d.cpu().numpy()[live] == data_h[live]).all(), f"cfg {cfg_idx} step {s}: stack entries differ"
+        got = mask_d.cpu().numpy().view(np.uint32)
+        if s in full:
+            want = o.fill_mask(states_h, data_h, len_h, v)
+            bad = np.argwhere(got != want)
+            assert len(bad) == 0, f"cfg {cfg_idx} step {s}: {len(bad)} mask words differ, first (row, word) {bad[0]}"
+            n_full += 1
+        else:
+            for b in rng.integers(0, B, size=rows_per_step):
+                want = o.mask_row(data_h[b, : len_h[b]], v, done=states_h[b] < 0)
+                assert (got[b] == want).all(), f"cfg {cfg_idx} step {s} row {b}: mask row differs"
+                n_rows += 1
+        if s % 32 == 31 or s == steps - 1:
+            log(f"[cfg {cfg_idx}] advance+fill step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
+    torch.cuda.synchronize()
+    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows)

@@ -3,7 +3,7 @@ seeded workload configurations.  Integer/bit work: everything must be bit-exact.
 import numpy as np
 import pytest
 
-from replay import replay
+from replay import replay, replay_advance_fill
 
 pytestmark = pytest.mark.gpu
 
@@ -56,3 +56,16 @@ def test_cfg5_mixed_grammars_deep_stacks():
     r = replay(5, full_mask_steps=[0, 1, 64, 256, 511])
     assert r["full_masks"] == 5
     assert max(r["depth_hist"]) >= 60 and len(r["depth_hist"]) > 40
+
+
+def test_advance_fill_mask_all_configs():
+    """pre3_advance_fill_mask (advance + next mask in one launch, slot reuse on EOS) on every
+    configuration; config 2 also with shallow conditions (leftover walks inside the fused kernel)
+    and without token-level edges (two-launch fallback)."""
+    assert replay_advance_fill(1)["full_masks"] == 32
+    assert replay_advance_fill(2, steps=64)["full_masks"] == 64
+    assert replay_advance_fill(2, steps=12, max_condition_depth=2)["full_masks"] == 12
+    assert replay_advance_fill(2, steps=12, token_edges=False)["full_masks"] == 12
+    assert replay_advance_fill(3, steps=96, full_mask_steps=[0, 40, 95])["full_masks"] == 3
+    assert replay_advance_fill(4, steps=64, full_mask_steps=[0, 63])["full_masks"] == 2
+    assert replay_advance_fill(5, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
