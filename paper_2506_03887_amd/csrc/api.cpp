@@ -99,7 +99,7 @@ int upload_tables(pre3_handle *h) {
     PRE3_UP(h->V.bytes, vbytes);
     PRE3_UP(h->V.offsets, voffsets);
 #undef PRE3_UP
-    D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_eff = nullptr; D.sym_pool = nullptr;
+    D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_eff = nullptr; D.sym_pool = nullptr; D.state_kind = nullptr;
     if (h->S.enabled) {
         std::vector<int4> sn(h->S.nodes.size());
         for (size_t i = 0; i < sn.size(); ++i)
@@ -111,6 +111,7 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, sp, &D.sym_pairs)) != hipSuccess) return hip_fail(h, e, "upload sym_pairs");
         if ((e = upload(h, h->S.eff, &D.sym_eff)) != hipSuccess) return hip_fail(h, e, "upload sym_eff");
         if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
+        if ((e = upload(h, h->T.state_kind, &D.state_kind)) != hipSuccess) return hip_fail(h, e, "upload state_kind");
     }
     D.n_states = h->T.n_states;
     D.ncol = h->T.n_classes + 1;

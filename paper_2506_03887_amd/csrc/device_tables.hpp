@@ -18,6 +18,7 @@ struct DevTables {
     const int2 *sym_pairs;         // (condition state, child node)
     const int32_t *sym_eff;        // [nodes * ncol]
     const int32_t *sym_pool;       // effect records, 16-byte aligned
+    const int32_t *state_kind;     // [n_states] root node of each state's condition tree
     // vocabulary, chunk-sorted order
     const uint8_t *tok_len;        // [n_padded]
     const uint16_t *tok_bit;       // [n_padded]

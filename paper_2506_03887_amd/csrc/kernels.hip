@@ -96,19 +96,20 @@ struct StackView {
 // With kCheckCap the walk reports kOverflow exactly when a push would exceed `cap` entries.
 template <bool kCheckCap, bool kUniform = false>
 __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int info, int &base, int &d,
-                                    int &top, const StackView &row, int cap) {
+                                    int &top, int &tree, const StackView &row, int cap, int *run_node = nullptr) {
     const int col = info & 0xFF, delta = info >> 8;    // byte class and per-byte target offset
+    // `tree` names the condition tree of the top state (states that behave alike share one, and all
+    // bytes of a class shift to states of one kind, so the kind after an edge is stored with it)
     if (T.sym_eff) {
-        int node = top;
+        int node = tree;
         int4 nd = table<kUniform>(T.sym_nodes, node);
         int code = table<kUniform>(T.sym_eff, node * T.ncol + col);
         for (int level = 0; level < 64; ++level) {
             if (code >= 0) {
-                // known, peak, n_push, push[0]; push[1..4] ride along in the same access
+                // known, peak, n_push, kind after the edge; push[0..3] ride along in the same access
                 const int4 hdr = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), code >> 2);
-                int4 more = make_int4(0, 0, 0, 0);
-                if (kUniform) more = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), (code >> 2) + 1);
-                const int pops = hdr.x - 1, np = hdr.z;
+                const int4 more = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), (code >> 2) + 1);
+                const int pops = hdr.x - 1, np = hdr.z & kEffPushMask;
                 if (kCheckCap && base + d + hdr.y >= cap) return kOverflow;
                 if (pops <= d) {
                     d -= pops;
@@ -120,13 +121,14 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
                 if (d + np > T.max_depth) { if (!kUniform || (threadIdx.x & 63) == 0) atomicAdd(T.fault, 1); return kRejected; }
                 for (int i = 0; i < np; ++i) {
                     int v;
-                    if (i == 0) v = hdr.w;
-                    else if (kUniform && i <= 4) v = i == 1 ? more.x : i == 2 ? more.y : i == 3 ? more.z : more.w;
-                    else v = table<kUniform>(T.sym_pool, code + 3 + i);
+                    if (i < 4) v = i == 0 ? more.x : i == 1 ? more.y : i == 2 ? more.z : more.w;
+                    else v = table<kUniform>(T.sym_pool, code + 4 + i);
                     if (i == np - 1) v += delta;
                     priv.set(d++, v);
                     top = v;
                 }
+                if (run_node) *run_node = ((hdr.z & kEffSameShape) && hdr.w == tree) ? node : -1;
+                tree = hdr.w;
                 return kFed;
             }
             if (code == kEffNone) return kRejected;
@@ -191,6 +193,7 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
             if (d >= T.max_depth) { atomicAdd(T.fault, 1); return kRejected; }
             top = (int)(e >> 2) + delta;
             priv.set(d++, top);
+            if (T.state_kind) tree = table<kUniform>(T.state_kind, top);
             return kFed;
         }
         const int n = (int)((e >> 2) & kMaxPop), nt = (int)(e >> kNtShift);
@@ -222,24 +225,54 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
     }
 }
 
+// After a self-similar edge found at condition node `node` (the stack kept its shape and the kind
+// of its top), every following symbol whose edge at the same node is again self-similar merely
+// replaces the top of the stack.  Each of the 64 lanes examines one upcoming byte
+// (infos[first + lane], staged in LDS); the run ends at the first byte that is not such an edge.
+// Returns the number of bytes consumed; the last one's target becomes the new top.
+template <bool kCheckCap>
+__device__ __forceinline__ int apply_run(const DevTables &T, PrivateStack &priv, const int32_t *infos, int first,
+                                         int n_bytes, int node, int tree, int base, int d, int &top, int cap) {
+    const int i = first + (threadIdx.x & 63);
+    bool ok = i < n_bytes && i < 64;
+    int new_top = 0;
+    if (ok) {
+        const int info = infos[i];
+        const int code = T.sym_eff[node * T.ncol + (info & 0xFF)];
+        ok = code >= 0;
+        if (ok) {
+            const int4 hdr = *reinterpret_cast<const int4 *>(T.sym_pool + code);
+            ok = (hdr.z & kEffSameShape) && hdr.w == tree && (!kCheckCap || base + d + hdr.y < cap);
+            if (ok) new_top = T.sym_pool[code + 4 + (hdr.z & kEffPushMask) - 1] + (info >> 8);
+        }
+    }
+    const unsigned long long bad = __ballot(!ok);
+    const int run = bad ? __ffsll((long long)bad) - 1 : 64;
+    if (run > 0) {
+        top = __builtin_amdgcn_readfirstlane(__shfl(new_top, run - 1));
+        priv.set(d - 1, top);
+    }
+    return run;
+}
+
 // Walks the token at chunk-sorted position `pos` from the stack row[0..len).
 __device__ __forceinline__ bool walk_token(const DevTables &T, PrivateStack &priv, int pos, int n_bytes,
                                            const int32_t *__restrict__ row, int len, int top0) {
-    int base = len, d = 0, top = top0;
+    int base = len, d = 0, top = top0, kind = T.state_kind ? T.state_kind[top0] : 0;
     uint32_t w = 0;
     for (int i = 0; i < n_bytes; ++i) {
         if ((i & 3) == 0) w = T.tok_words[(size_t)(i >> 2) * T.n_padded + pos];
         const int info = T.byte_info[w & 0xFF];
         w >>= 8;
-        if (feed<false>(T, priv, info, base, d, top, StackView{row, nullptr, len}, 0) != kFed) return false;
+        if (feed<false>(T, priv, info, base, d, top, kind, StackView{row, nullptr, len}, 0) != kFed) return false;
     }
     return true;
 }
 
 __device__ __forceinline__ bool walk_end(const DevTables &T, PrivateStack &priv, const int32_t *__restrict__ row,
                                          int len, int top0) {
-    int base = len, d = 0, top = top0;
-    return feed<false>(T, priv, T.end_col, base, d, top, StackView{row, nullptr, len}, 0) == kAccepted;
+    int base = len, d = 0, top = top0, kind = T.state_kind ? T.state_kind[top0] : 0;
+    return feed<false>(T, priv, T.end_col, base, d, top, kind, StackView{row, nullptr, len}, 0) == kAccepted;
 }
 
 // One block per (sequence, vocabulary chunk) work item, grid-strided.  Every lane walks the
@@ -295,11 +328,11 @@ __global__ __launch_bounds__(kBlock) void fill_mask_walk_kernel(DevTables T, con
 __device__ __forceinline__ bool walk_token_id(const DevTables &T, PrivateStack &priv, int t,
                                               const int32_t *__restrict__ row, int len, int top0) {
     if (t == T.eos_id) return walk_end(T, priv, row, len, top0);
-    int base = len, d = 0, top = top0;
+    int base = len, d = 0, top = top0, kind = T.state_kind ? T.state_kind[top0] : 0;
     const int lo = T.voffsets[t], hi = T.voffsets[t + 1];
     if (hi <= lo) return false;
     for (int i = lo; i < hi; ++i)
-        if (feed<false>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, StackView{row, nullptr, len}, 0) != kFed) return false;
+        if (feed<false>(T, priv, T.byte_info[T.vbytes[i]], base, d, top, kind, StackView{row, nullptr, len}, 0) != kFed) return false;
     return true;
 }
 
@@ -619,8 +652,9 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
         } else {
             const StackView view{row, s_win[wave], n};
             int base = n, d = 0;
+            int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
             if (t == T.eos_id) {
-                if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) {
+                if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
                     out_state = -1;
                     if (restart_on_eos) { out_state = row[0]; out_len = 1; }   // slot reuse: back to the initial state
                 } else {
@@ -630,7 +664,10 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
                 int rc = hi > lo ? kFed : kRejected;
                 for (int i = 0; i < hi - lo && rc == kFed; ++i) {
                     const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[wave][i] : T.byte_info[T.vbytes[lo + i]]);
-                    rc = feed<true, true>(T, priv, info, base, d, top, view, cap);
+                    int run_node = -1;
+                    rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+                    if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
+                        i += apply_run<true>(T, priv, s_info[wave], i + 1, hi - lo, run_node, kind, base, d, top, cap);
                 }
                 if (rc != kFed) {
                     out_err = rc == kOverflow ? 2 : 1;
@@ -715,8 +752,9 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                 out_err = 1;
             } else {
                 const StackView view{row, s_win, n};
+                int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
                 if (t == T.eos_id) {
-                    if (feed<false, true>(T, priv, T.end_col, base, d, top, view, 0) == kAccepted) {
+                    if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
                         out_state = -1;
                         if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
                     } else {
@@ -728,7 +766,10 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                     int rc = hi > lo ? kFed : kRejected;
                     for (int i = 0; i < hi - lo && rc == kFed; ++i) {
                         const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[lo + i]]);
-                        rc = feed<true, true>(T, priv, info, base, d, top, view, cap);
+                        int run_node = -1;
+                        rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+                        if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
+                            i += apply_run<true>(T, priv, s_info, i + 1, hi - lo, run_node, kind, base, d, top, cap);
                     }
                     if (rc != kFed) {
                         out_err = rc == kOverflow ? 2 : 1;

@@ -19,6 +19,7 @@ struct Pending {        // a symbol whose chain reached below the known stack en
 struct BuildNode {
     int known = 1;
     int floor = 0;
+    std::vector<int32_t> suffix;                // the known entries, deepest first (suffix.back() = top state)
     std::vector<int32_t> eff;                   // per column: code or offset into the pool
     std::vector<Pending> pend;
     std::vector<std::pair<int32_t, std::unique_ptr<BuildNode>>> children;
@@ -53,9 +54,16 @@ struct Builder {
                 st.push_back((int32_t)(e >> 2));
                 while (pool.size() & 3) pool.push_back(0);          // records start on 16-byte boundaries
                 nd.eff[col] = (int32_t)pool.size();
+                // Self-similar edge: the stack keeps its height and all known entries except the top,
+                // and the new top is of the same kind as the old one.  The next symbol then meets the
+                // same condition node, which lets a run of such symbols be applied in one go.
+                bool same_shape = st.size() == nd.suffix.size() &&
+                                  T.state_kind[st.back()] == T.state_kind[nd.suffix.back()];
+                for (size_t i = 1; same_shape && i + 1 < st.size(); ++i) same_shape = st[i] == nd.suffix[i];
                 pool.push_back(nd.known);
                 pool.push_back(peak);
-                pool.push_back((int32_t)st.size() - 1);
+                pool.push_back(((int32_t)st.size() - 1) | (same_shape ? kEffSameShape : 0));
+                pool.push_back(T.state_kind[st.back()]);
                 pool.insert(pool.end(), st.begin() + 1, st.end());
                 deepest = std::max<int64_t>(deepest, nd.known);
                 return;
@@ -111,6 +119,7 @@ struct Builder {
                 in.swap(nd.pend);
                 nd.floor = ps[0];
                 nd.known++;
+                nd.suffix.insert(nd.suffix.begin(), ps[0]);
                 resolve(ps[0], in, nd);
                 continue;
             }
@@ -120,6 +129,8 @@ struct Builder {
                 std::unique_ptr<BuildNode> ch(new BuildNode());
                 ch->known = nd.known + 1;
                 ch->floor = X;
+                ch->suffix = nd.suffix;
+                ch->suffix.insert(ch->suffix.begin(), X);
                 ch->eff.assign(ncol, kEffNone);
                 resolve(X, nd.pend, *ch);
                 expand(*ch);
@@ -182,13 +193,18 @@ SymbolEdges build_symbol_edges(const EdgeTables &T, int max_known, int max_nodes
     S.ncol = T.n_classes + 1;
     Builder B(T, max_known, 0);
     int remaining = max_nodes;
-    S.nodes.assign(T.n_states, SymbolNode{});
-    S.eff.assign((size_t)T.n_states * S.ncol, kEffNone);
+    S.nodes.assign(T.n_kinds, SymbolNode{});
+    S.eff.assign((size_t)T.n_kinds * S.ncol, kEffNone);
     std::vector<int32_t> st;
+    std::vector<char> done(T.n_kinds, 0);
     for (int s = 0; s < T.n_states; ++s) {
+        const int kind = T.state_kind[s];
+        if (done[kind]) continue;                               // one tree per kind, built from its first state
+        done[kind] = 1;
         BuildNode root;
         root.known = 1;
         root.floor = s;
+        root.suffix.assign(1, s);
         root.eff.assign(S.ncol, kEffNone);
         for (int col = 0; col < S.ncol; ++col) {
             st.assign(1, s);
@@ -198,10 +214,10 @@ SymbolEdges build_symbol_edges(const EdgeTables &T, int max_known, int max_nodes
         const int granted = B.node_budget;
         B.expand(root);
         remaining -= granted - B.node_budget;
-        flatten(root, s, S, S.ncol);
+        flatten(root, kind, S, S.ncol);
     }
     while (B.pool.size() & 3) B.pool.push_back(0);
-    B.pool.insert(B.pool.end(), 4, 0);                          // a record is read as two 16-byte halves
+    B.pool.insert(B.pool.end(), 8, 0);                          // a record is read as two 16-byte halves
     S.pool.swap(B.pool);
     S.max_known = B.deepest;
     return S;
@@ -210,7 +226,7 @@ SymbolEdges build_symbol_edges(const EdgeTables &T, int max_known, int max_nodes
 int host_feed(const EdgeTables &T, const SymbolEdges &S, std::vector<int32_t> &st, int col, int delta, int cap,
               bool use_merged) {
     const int ncol = T.n_classes + 1;
-    int node = st.back();
+    int node = T.state_kind[st.back()];
     while (use_merged) {
         int code = S.eff[(size_t)node * ncol + col];
         if (code == kEffNone) return kHostRejected;
@@ -218,10 +234,10 @@ int host_feed(const EdgeTables &T, const SymbolEdges &S, std::vector<int32_t> &s
         if (code == kEffStepwise) break;
         if (code >= 0) {
             const int32_t *rec = &S.pool[code];
-            int known = rec[0], peak = rec[1], np = rec[2];
+            int known = rec[0], peak = rec[1], np = rec[2] & kEffPushMask;
             if ((int)st.size() + peak >= cap) return kHostOverflow;
             st.resize(st.size() - (known - 1));
-            for (int i = 0; i < np; ++i) st.push_back(rec[3 + i] + (i == np - 1 ? delta : 0));
+            for (int i = 0; i < np; ++i) st.push_back(rec[4 + i] + (i == np - 1 ? delta : 0));
             return kHostFed;
         }
         const SymbolNode &nd = S.nodes[node];

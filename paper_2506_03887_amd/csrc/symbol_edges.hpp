@@ -25,6 +25,10 @@ enum SymbolEffectCode : int32_t {
     kEffStepwise = -4     // not precomputed (limits reached): follow the per-step edges
 };
 
+// n_push field of an effect record: low bits = number of pushes, flag = self-similar edge
+constexpr int32_t kEffPushMask = 0xFFFF;
+constexpr int32_t kEffSameShape = 1 << 16;
+
 struct SymbolNode {
     int32_t known;        // stack entries (from the top) fixed by this node
     int32_t child_begin;  // children in child_state/child_node[child_begin .. +child_count)
@@ -35,10 +39,11 @@ struct SymbolNode {
 struct SymbolEdges {
     bool enabled = false;
     int ncol = 0;
-    std::vector<SymbolNode> nodes;              // nodes[s] is the root of state s
+    std::vector<SymbolNode> nodes;              // nodes[k] is the root shared by the states of kind k
     std::vector<int32_t> child_state, child_node;
     std::vector<int32_t> eff;                   // [nodes * ncol]: SymbolEffectCode or offset into pool
-    // effect record at pool[o]: known, peak, n_push, push[0..n_push)
+    // effect record at pool[o] (16-byte aligned): known, peak, n_push, kind of the last pushed state,
+    // push[0..n_push)
     //   peak = largest (stack height just before a push) - (height before the symbol), so that
     //   "a push would exceed cap" can be decided without replaying the chain
     std::vector<int32_t> pool;

@@ -92,6 +92,28 @@ EdgeTables build_edge_tables(const std::vector<Grammar> &grammars) {
             }
         }
     }
+    // state kinds: identical per-byte edges (targets included), '$' edge, goto targets and predecessors
+    {
+        const std::vector<std::vector<int32_t>> pred = predecessors(T);
+        std::map<std::vector<int64_t>, int> kinds;
+        T.state_kind.resize(T.n_states);
+        std::vector<int64_t> key;
+        for (int g = 0; g < T.n_grammars; ++g) {
+            const Lr1Automaton &A = T.automata[g];
+            const int off = T.state_offset[g];
+            for (int s = 0; s < A.n_states; ++s) {
+                key.clear();
+                key.push_back(g);
+                for (int b = 0; b < 256; ++b) key.push_back(column[b][off + s]);
+                key.push_back(pack_edge(A, off, A.action[(size_t)s * kNumTerminals + kEnd]));
+                for (int nt = 0; nt < A.n_nt; ++nt) key.push_back(A.go[(size_t)s * A.n_nt + nt]);
+                key.push_back(-7);
+                for (int32_t p : pred[off + s]) key.push_back(p);
+                T.state_kind[off + s] = kinds.emplace(key, (int)kinds.size()).first->second;
+            }
+        }
+        T.n_kinds = (int)kinds.size();
+    }
     std::map<std::vector<int64_t>, int> class_of_signature;
     T.byte_class.resize(256);
     T.byte_delta.assign(256, 0);
@@ -99,9 +121,14 @@ EdgeTables build_edge_tables(const std::vector<Grammar> &grammars) {
     std::vector<int64_t> sig;
     for (int b = 0; b < 256; ++b) {
         sig.clear();
-        for (uint32_t e : column[b])
-            sig.push_back((e & kKindMask) == kShift ? (((int64_t)(e >> 2) - first_target[b]) << 2) | kShift
-                                                    : (int64_t)e);
+        for (uint32_t e : column[b]) {
+            if ((e & kKindMask) == kShift) {        // same target offset and same kind of target state
+                sig.push_back((((int64_t)(e >> 2) - first_target[b]) << 2) | kShift);
+                sig.push_back(T.state_kind[e >> 2]);
+            } else {
+                sig.push_back((int64_t)e);
+            }
+        }
         auto ins = class_of_signature.emplace(sig, (int)representative.size());
         if (ins.second) representative.push_back(b);
         T.byte_class[b] = (uint8_t)ins.first->second;

@@ -34,6 +34,10 @@ struct EdgeTables {
     std::vector<uint32_t> edge;            // [n_states * (n_classes + 1)]
     std::vector<int32_t> goto_row;         // [n_states] offset into goto_flat, -1 = no row
     std::vector<int32_t> goto_flat;        // deduplicated rows of targets (global ids), -1 = none
+    // States that behave identically as the top of a stack (same edges for every byte and '$', same
+    // goto row, same predecessors) share a kind; bytes of one class shift to states of one kind.
+    std::vector<int32_t> state_kind;       // [n_states]
+    int n_kinds = 0;
     int height_per_byte = 1;               // H: most private entries one input symbol can add, plus 1
 };
 
