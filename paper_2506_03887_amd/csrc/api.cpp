@@ -29,7 +29,9 @@ struct pre3_handle {
     SymbolEdges S;
     int max_depth = 0;
 
-    std::vector<void *> allocations;     // device memory owned by the handle
+    std::vector<void *> allocations;     // device memory owned by the handle (arena chunks)
+    char *arena = nullptr;               // current chunk: tables are packed into few large
+    size_t arena_left = 0;               // allocations so that they share address translations
     DevTables dev{};
     int grid_blocks = 0;
     int32_t *spill = nullptr;
@@ -59,13 +61,34 @@ int hip_fail(pre3_handle *h, hipError_t e, const char *what) {
     return fail(h, PRE3_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+// Sub-allocates from large chunks (256-byte aligned): the many small tables of a handle end up
+// next to each other instead of each in its own mapping.
+hipError_t arena_alloc(pre3_handle *h, size_t bytes, void **out) {
+    const size_t kChunk = (size_t)64 << 20;
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (bytes == 0) bytes = 256;
+    if (bytes > h->arena_left) {
+        const size_t chunk = bytes > kChunk ? bytes : kChunk;
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, chunk);
+        if (e != hipSuccess) return e;
+        h->allocations.push_back(p);
+        if (bytes >= kChunk) { *out = p; return hipSuccess; }   // a chunk of its own; keep the current one
+        h->arena = static_cast<char *>(p);
+        h->arena_left = chunk;
+    }
+    *out = h->arena;
+    h->arena += bytes;
+    h->arena_left -= bytes;
+    return hipSuccess;
+}
+
 template <typename T>
 hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
     void *p = nullptr;
     size_t bytes = src.size() * sizeof(T);
-    hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+    hipError_t e = arena_alloc(h, bytes, &p);
     if (e != hipSuccess) return e;
-    h->allocations.push_back(p);
     if (bytes) {
         e = hipMemcpy(p, src.data(), bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) return e;
@@ -75,9 +98,8 @@ hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
 }
 
 hipError_t device_alloc(pre3_handle *h, size_t bytes, void **out, bool zero) {
-    hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+    hipError_t e = arena_alloc(h, bytes, out);
     if (e != hipSuccess) return e;
-    h->allocations.push_back(*out);
     if (zero) e = hipMemset(*out, 0, bytes ? bytes : 16);
     return e;
 }
@@ -138,16 +160,29 @@ int upload_tables(pre3_handle *h) {
     // token-level edges; a vocabulary whose mask row does not fit the kernel's LDS bitmap keeps
     // the byte-by-byte path
     if (h->E.enabled && (size_t)h->V.n_words <= edge_kernel_max_lds_words()) {
-        static_assert(sizeof(DevConditionNode) == sizeof(ConditionNode), "node layouts must agree");
         DevTokenEdges &X = h->dev_edges;
         std::vector<DevConditionNode> nodes(h->E.nodes.size());
-        std::memcpy(nodes.data(), h->E.nodes.data(), nodes.size() * sizeof(DevConditionNode));
+        for (size_t i = 0; i < nodes.size(); ++i) {
+            const ConditionNode &n = h->E.nodes[i];
+            DevConditionNode d{};
+            d.known = n.known;
+            d.child_count = n.child_count;
+            if (n.child_count > 0) {
+                d.a = n.child_begin;
+                d.b = h->E.child_node[n.child_begin];            // first child; the others follow it
+            } else {
+                d.a = n.walk_begin;
+                d.b = n.walk_count;
+            }
+            d.dense_row = n.dense_row;
+            d.delta_begin = n.delta_begin;
+            d.delta_count = n.delta_count;
+            nodes[i] = d;
+        }
 #define PRE3_UPE(vec, field)                                              \
     if ((e = upload(h, vec, &X.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
         std::vector<DevConditionNode> roots(h->E.root_of_state.size());
         for (size_t i = 0; i < roots.size(); ++i) roots[i] = nodes[h->E.root_of_state[i]];
-        std::vector<int2> pairs(h->E.child_state.size());
-        for (size_t i = 0; i < pairs.size(); ++i) pairs[i] = make_int2(h->E.child_state[i], h->E.child_node[i]);
         const int stride = edge_row_stride_words(h->V.n_words);
         std::vector<uint32_t> dense((size_t)h->E.n_dense * stride, 0);
         for (int64_t r = 0; r < h->E.n_dense; ++r)
@@ -155,7 +190,7 @@ int upload_tables(pre3_handle *h) {
                         sizeof(uint32_t) * h->V.n_words);
         PRE3_UPE(roots, root_nodes);
         PRE3_UPE(nodes, nodes);
-        PRE3_UPE(pairs, child_pairs);
+        PRE3_UPE(h->E.child_state, child_state);
         PRE3_UPE(dense, dense_rows);
         PRE3_UPE(h->E.delta_ids, delta_ids);
         PRE3_UPE(h->E.walk_ids, walk_ids);

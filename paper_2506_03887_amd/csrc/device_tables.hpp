@@ -31,15 +31,18 @@ struct DevTables {
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
 };
 
-// Condition tree of the token-level prefix-conditioned edges (layout in token_edges.hpp).
+// Condition tree of the token-level prefix-conditioned edges (see token_edges.hpp), device form.
+// An inner node (child_count > 0) names its children: their condition states are
+// child_state[a .. a + child_count), their records nodes[b .. b + child_count).
+// A leaf names the tokens still undetermined there: walk_ids[a .. a + b), b = -1: all tokens.
 struct DevConditionNode {
-    int32_t known, child_begin, child_count, dense_row, delta_begin, delta_count, walk_begin, walk_count;
+    int32_t known, child_count, a, b, dense_row, delta_begin, delta_count, pad;
 };
 
 struct DevTokenEdges {
     const DevConditionNode *root_nodes;    // [n_states] copy of each state's root record
     const DevConditionNode *nodes;
-    const int2 *child_pairs;               // (condition state, child node), sorted by state per node
+    const int32_t *child_state;            // condition states, sorted per node
     const uint32_t *dense_rows;            // [n_dense * stride], stride = n_words rounded up to 4
     const int32_t *delta_ids, *walk_ids;
 };

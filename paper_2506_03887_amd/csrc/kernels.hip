@@ -336,9 +336,80 @@ __device__ __forceinline__ bool walk_token_id(const DevTables &T, PrivateStack &
     return true;
 }
 
+constexpr int kMaxPath = 64;           // delta lists ORed on one descent
+enum RowMode { kRowFast = 0, kRowWalkAll = 1, kRowEmpty = 2, kRowDone = 3 };
+
+// How one sequence's mask row is assembled; lives in LDS, written by the wave that descends.
+struct RowPlan {
+    int32_t seg_begin[kMaxPath], seg_count[kMaxPath];   // delta lists to OR in
+    int32_t nseg;
+    int32_t dense;            // dense row to start from, or -1 (start from zero)
+    int32_t mode;             // RowMode
+    int32_t walk_begin, walk_count;                     // tokens left to the byte-by-byte walk
+    int32_t top, len;         // the stack the row belongs to
+};
+
+// Descent of the condition tree of the token-level edges, run by all 64 lanes of one wave with
+// identical values.  `win[k]` (LDS) is the stack entry k below the top for k < kWindow, deeper(k)
+// any entry below that; `n` the stack length; `nd` the root record of the top state.  Each node
+// names the entry it tests; lane j fetches condition state j TOGETHER with child j's record
+// (children are stored consecutively), so one round of loads both verifies all of the node's
+// stack-matching conditions at once (wave ballot) and enters the matching child.
+template <typename Deeper>
+__device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNode nd, const int32_t *win, int n,
+                                         Deeper deeper, RowPlan *plan, int lane) {
+    int mode = kRowFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0;
+    for (;;) {
+        if (nd.dense_row >= 0) {               // holds everything allowed so far on this path
+            dense = nd.dense_row;
+            nseg = 0;
+        } else if (nd.delta_count > 0) {
+            if (lane == 0) { plan->seg_begin[nseg] = nd.delta_begin; plan->seg_count[nseg] = nd.delta_count; }
+            ++nseg;
+        }
+        if (nd.child_count == 0) {
+            walk_begin = nd.a;
+            walk_count = nd.b;
+            if (walk_count < 0) mode = kRowWalkAll;
+            break;
+        }
+        if (nd.known >= n || nseg >= kMaxPath) { mode = kRowWalkAll; break; }
+        const int x = nd.known < kWindow ? win[nd.known] : deeper(nd.known);
+        bool found = false;
+        for (int c0 = 0; c0 < nd.child_count && !found; c0 += 64) {
+            const int j = c0 + lane;
+            int cstate = -2;
+            DevConditionNode c{};
+            if (j < nd.child_count) {
+                cstate = E.child_state[nd.a + j];
+                c = E.nodes[nd.b + j];
+            }
+            const unsigned long long m = __ballot(cstate == x);
+            if (m) {
+                const int src = __ffsll((long long)m) - 1;
+                nd.known = __shfl(c.known, src);
+                nd.child_count = __shfl(c.child_count, src);
+                nd.a = __shfl(c.a, src);
+                nd.b = __shfl(c.b, src);
+                nd.dense_row = __shfl(c.dense_row, src);
+                nd.delta_begin = __shfl(c.delta_begin, src);
+                nd.delta_count = __shfl(c.delta_count, src);
+                found = true;
+            }
+        }
+        if (!found) { mode = kRowWalkAll; break; }
+    }
+    if (lane == 0) {
+        plan->nseg = nseg;
+        plan->dense = dense;
+        plan->mode = mode;
+        plan->walk_begin = walk_begin;
+        plan->walk_count = walk_count;
+    }
+}
+
 constexpr int kEdgeBlock = 256;        // threads per block of the token-edge kernel
 constexpr int kWalkLanes = 64;         // lanes of a block that may walk tokens byte by byte
-constexpr int kMaxPath = 64;           // delta lists ORed on one descent
 constexpr uint32_t kNegInfPair = 0xFF80FF80u;
 
 // Token mask from the precomputed token-level edges, optionally fused with the masking of the
@@ -366,8 +437,8 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
     size_t spill_stride) {
     extern __shared__ uint4 bits4[];                   // seg_vec
     uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
-    __shared__ int32_t s_seg_begin[kMaxPath], s_seg_count[kMaxPath];
-    __shared__ int32_t s_nseg, s_dense, s_mode, s_walk_begin, s_walk_count, s_top, s_len;
+    __shared__ RowPlan plan;
+    __shared__ int32_t s_win[kWindow];
     __shared__ int32_t lds_stack[kLdsDepth * kWalkLanes];
     const int tid = threadIdx.x;
     PrivateStack priv;
@@ -375,7 +446,6 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
     priv.lds_stride = kWalkLanes;
     priv.spill = spill + (size_t)blockIdx.x * kWalkLanes + (tid & (kWalkLanes - 1));
     priv.spill_stride = spill_stride;
-    enum { kFast = 0, kWalkAll = 1, kEmpty = 2, kDone = 3 };
     const int n_vec = (T.n_words + 3) >> 2;
     const int rows_padded = (batch + 7) & ~7;
     const int n_items = rows_padded * n_seg;
@@ -389,94 +459,66 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
         if (tid < 64) {                                // wave 0: descent, uniform across lanes
             const int st = states[b];
             const int n = len[b];
-            int mode = kFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0, top = -1;
+            int top = -1;
             if (st < 0) {
-                mode = kDone;
+                if (tid == 0) plan.mode = kRowDone;
             } else if (n < 1 || n > cap) {
-                mode = kEmpty;
+                if (tid == 0) plan.mode = kRowEmpty;
             } else {
                 DevConditionNode nd{};
                 const bool guess = (unsigned)st < (unsigned)T.n_states;
                 if (guess) nd = E.root_nodes[st];      // overlaps the stack load below
                 const int xj = n - 1 - tid >= 0 ? row[n - 1 - tid] : -1;
+                s_win[tid] = xj;
                 top = __shfl(xj, 0);
                 if ((unsigned)top >= (unsigned)T.n_states) {
-                    mode = kEmpty;
+                    if (tid == 0) plan.mode = kRowEmpty;
                 } else {
                     if (!guess || top != st) nd = E.root_nodes[top];
-                    for (;;) {
-                        if (nd.dense_row >= 0) {       // holds everything allowed so far on this path
-                            dense = nd.dense_row;
-                            nseg = 0;
-                        } else if (nd.delta_count > 0) {
-                            if (tid == 0) { s_seg_begin[nseg] = nd.delta_begin; s_seg_count[nseg] = nd.delta_count; }
-                            ++nseg;
-                        }
-                        if (nd.child_count == 0) {
-                            walk_begin = nd.walk_begin;
-                            walk_count = nd.walk_count;
-                            if (walk_count < 0) mode = kWalkAll;
-                            break;
-                        }
-                        if (nd.known >= n || nseg >= kMaxPath) { mode = kWalkAll; break; }
-                        const int x = nd.known < 64 ? __shfl(xj, nd.known) : row[n - 1 - nd.known];
-                        int next = -1;
-                        for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
-                            const int i = c0 + tid;
-                            int2 pr = make_int2(-2, -1);
-                            if (i < nd.child_count) pr = E.child_pairs[nd.child_begin + i];
-                            const unsigned long long m = __ballot(pr.x == x);
-                            if (m) { next = __shfl(pr.y, __ffsll((long long)m) - 1); break; }
-                        }
-                        if (next < 0) { mode = kWalkAll; break; }
-                        nd = E.nodes[next];
-                    }
+                    plan_row(E, nd, s_win, n, [&](int k) { return row[n - 1 - k]; }, &plan, tid);
                 }
             }
-            if (tid == 0) {
-                s_nseg = nseg; s_dense = dense; s_mode = mode; s_top = top; s_len = n;
-                s_walk_begin = walk_begin; s_walk_count = walk_count;
-            }
+            if (tid == 0) { plan.top = top; plan.len = n; }
         }
         __syncthreads();
-        const int mode = s_mode;
+        const int mode = plan.mode;
         const int v_lo = seg * seg_vec;                                    // first uint4 of the segment
         const int v_cnt = min(seg_vec, n_vec - v_lo);                      // may be <= 0 for a trailing segment
         const int w_lo = v_lo * 4, w_hi = w_lo + max(v_cnt, 0) * 4;        // mask words [w_lo, w_hi)
-        if (mode == kFast && s_dense >= 0) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)s_dense * n_vec + v_lo;
+        if (mode == kRowFast && plan.dense >= 0) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
             for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = src[w];
         } else {
             for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = make_uint4(0, 0, 0, 0);
         }
         __syncthreads();
-        if (mode == kFast) {
-            const int nseg = s_nseg;
+        if (mode == kRowFast) {
+            const int nseg = plan.nseg;
             for (int i = 0; i < nseg; ++i) {
-                const int32_t *ids = E.delta_ids + s_seg_begin[i];
-                const int cnt = s_seg_count[i];
+                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
+                const int cnt = plan.seg_count[i];
                 for (int k = tid; k < cnt; k += kEdgeBlock) {
                     const int t = ids[k], w = t >> 5;
                     if (w >= w_lo && w < w_hi) atomicOr(&bits[w - w_lo], 1u << (t & 31));
                 }
             }
-            const int wc = s_walk_count;
+            const int wc = plan.walk_count;
             if (wc > 0 && tid < kWalkLanes) {
-                const int n = s_len, top0 = s_top;
+                const int n = plan.len, top0 = plan.top;
                 for (int k = tid; k < wc; k += kWalkLanes) {
-                    const int t = E.walk_ids[s_walk_begin + k], w = t >> 5;
+                    const int t = E.walk_ids[plan.walk_begin + k], w = t >> 5;
                     if (w >= w_lo && w < w_hi && walk_token_id(T, priv, t, row, n, top0))
                         atomicOr(&bits[w - w_lo], 1u << (t & 31));
                 }
             }
-        } else if (mode == kWalkAll) {
+        } else if (mode == kRowWalkAll) {
             if (tid < kWalkLanes) {
-                const int n = s_len, top0 = s_top;
+                const int n = plan.len, top0 = plan.top;
                 const int t_hi = min(T.n_tokens, w_hi * 32);
                 for (int t = w_lo * 32 + tid; t < t_hi; t += kWalkLanes)
                     if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[(t >> 5) - w_lo], 1u << (t & 31));
             }
-        } else if (mode == kDone && tid == 0) {
+        } else if (mode == kRowDone && tid == 0) {
             const int w = T.eos_id >> 5;
             if (w >= w_lo && w < w_hi) bits[w - w_lo] = 1u << (T.eos_id & 31);
         }
@@ -716,9 +758,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
     __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
     __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
-    __shared__ int32_t s_seg_begin[kMaxPath], s_seg_count[kMaxPath];
-    __shared__ int32_t s_nseg, s_dense, s_mode, s_walk_begin, s_walk_count, s_top, s_len;
-    enum { kFast = 0, kWalkAll = 1, kEmpty = 2, kDone = 3 };
+    __shared__ RowPlan plan;
     const int tid = threadIdx.x, lane = tid & 63;
     const int b = blockIdx.x;
     const int n_vec = (T.n_words + 3) >> 2;
@@ -804,83 +844,52 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         }
         __builtin_amdgcn_wave_barrier();
         // ---- descent of the condition tree with the new stack
-        int mode = kFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0;
         const int top = s_new[0];
         if (out_state < 0) {
-            mode = kDone;
+            if (lane == 0) plan.mode = kRowDone;
         } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
-            mode = kEmpty;
+            if (lane == 0) plan.mode = kRowEmpty;
         } else {
-            DevConditionNode nd = E.root_nodes[top];
-            for (;;) {
-                if (nd.dense_row >= 0) {
-                    dense = nd.dense_row;
-                    nseg = 0;
-                } else if (nd.delta_count > 0) {
-                    if (lane == 0) { s_seg_begin[nseg] = nd.delta_begin; s_seg_count[nseg] = nd.delta_count; }
-                    ++nseg;
-                }
-                if (nd.child_count == 0) {
-                    walk_begin = nd.walk_begin;
-                    walk_count = nd.walk_count;
-                    if (walk_count < 0) mode = kWalkAll;
-                    break;
-                }
-                if (nd.known >= nl || nseg >= kMaxPath) { mode = kWalkAll; break; }
-                const int x = nd.known < kWindow ? s_new[nd.known] : new_at(nd.known);
-                int next = -1;
-                for (int c0 = 0; c0 < nd.child_count; c0 += 64) {
-                    const int i = c0 + lane;
-                    int2 pr = make_int2(-2, -1);
-                    if (i < nd.child_count) pr = E.child_pairs[nd.child_begin + i];
-                    const unsigned long long m = __ballot(pr.x == x);
-                    if (m) { next = __shfl(pr.y, __ffsll((long long)m) - 1); break; }
-                }
-                if (next < 0) { mode = kWalkAll; break; }
-                nd = E.nodes[next];
-            }
+            plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
         }
-        if (lane == 0) {
-            s_nseg = nseg; s_dense = dense; s_mode = mode; s_top = top; s_len = nl;
-            s_walk_begin = walk_begin; s_walk_count = walk_count;
-        }
+        if (lane == 0) { plan.top = top; plan.len = nl; }
     }
     __syncthreads();
     // ---- the next mask row
-    const int mode = s_mode;
-    if (mode == kFast && s_dense >= 0) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)s_dense * n_vec;
+    const int mode = plan.mode;
+    if (mode == kRowFast && plan.dense >= 0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec;
         for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = src[w];
     } else {
         for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
-    if (mode == kFast || mode == kWalkAll) {
-        if (mode == kFast) {
-            const int nseg = s_nseg;
+    if (mode == kRowFast || mode == kRowWalkAll) {
+        if (mode == kRowFast) {
+            const int nseg = plan.nseg;
             for (int i = 0; i < nseg; ++i) {
-                const int32_t *ids = E.delta_ids + s_seg_begin[i];
-                const int cnt = s_seg_count[i];
+                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
+                const int cnt = plan.seg_count[i];
                 for (int k = tid; k < cnt; k += kAfBlock) {
                     const int t = ids[k];
                     atomicOr(&bits[t >> 5], 1u << (t & 31));
                 }
             }
         }
-        const int wc = mode == kWalkAll ? T.n_tokens : s_walk_count;
+        const int wc = mode == kRowWalkAll ? T.n_tokens : plan.walk_count;
         if (wc > 0 && tid < 64) {                       // leftovers: walked on the committed stack
             PrivateStack wp;
             wp.lds = s_walk_stack + lane;
             wp.lds_stride = 64;
             wp.spill = walk_spill + (size_t)b * 64 + lane;
             wp.spill_stride = walk_spill_stride;
-            const int n = s_len, top0 = s_top;
+            const int n = plan.len, top0 = plan.top;
             for (int k = lane; k < wc; k += 64) {
-                const int t = mode == kWalkAll ? k : E.walk_ids[s_walk_begin + k];
+                const int t = mode == kRowWalkAll ? k : E.walk_ids[plan.walk_begin + k];
                 if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
             }
         }
-    } else if (mode == kDone && tid == 0) {
+    } else if (mode == kRowDone && tid == 0) {
         bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
     }
     __syncthreads();

@@ -225,9 +225,9 @@ struct Flattener {
     }
 
     // `base` = dense row of the nearest dense ancestor (or null), `since` = ids accepted after it
-    int flatten(const BuildNode &b, const uint32_t *base, std::vector<int32_t> &since) {
-        int idx = (int)E.nodes.size();
-        E.nodes.push_back(ConditionNode{});
+    // The node is written to E.nodes[idx]; its children get consecutive indices, in the order of
+    // their condition states, so that child j is node first_child + j.
+    void flatten(const BuildNode &b, int idx, const uint32_t *base, std::vector<int32_t> &since) {
         ConditionNode n{};
         n.known = b.known;
         n.dense_row = -1;
@@ -267,23 +267,28 @@ struct Flattener {
                 E.walk_ids.insert(E.walk_ids.end(), ids.begin(), ids.end());
             }
         }
-        // children, sorted by condition state; their records are laid out after all of them exist
-        std::vector<std::pair<int32_t, int32_t>> kids;
-        {
-            std::vector<int32_t> empty_since;
-            for (const auto &ch : b.children) {
-                int ci = dense ? flatten(*ch.second, own_row.data(), empty_since) : flatten(*ch.second, base, since);
-                empty_since.clear();
-                kids.push_back({ch.first, ci});
-            }
-        }
-        std::sort(kids.begin(), kids.end());
+        std::vector<std::pair<int32_t, const BuildNode *>> kids;
+        for (const auto &ch : b.children) kids.push_back({ch.first, ch.second.get()});
+        std::sort(kids.begin(), kids.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
+        const int first = (int)E.nodes.size();
         n.child_begin = (int)E.child_state.size();
         n.child_count = (int)kids.size();
-        for (auto &k : kids) { E.child_state.push_back(k.first); E.child_node.push_back(k.second); }
-        since.resize(since_mark);
+        E.nodes.resize(E.nodes.size() + kids.size());
+        for (size_t j = 0; j < kids.size(); ++j) {
+            E.child_state.push_back(kids[j].first);
+            E.child_node.push_back(first + (int)j);
+        }
         E.nodes[idx] = n;
-        return idx;
+        std::vector<int32_t> empty_since;
+        for (size_t j = 0; j < kids.size(); ++j) {
+            if (dense) {
+                empty_since.clear();
+                flatten(*kids[j].second, first + (int)j, own_row.data(), empty_since);
+            } else {
+                flatten(*kids[j].second, first + (int)j, base, since);
+            }
+        }
+        since.resize(since_mark);
     }
 };
 
@@ -334,7 +339,9 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;
-        root_node[i] = F.flatten(*roots[i], nullptr, since);
+        root_node[i] = (int)E.nodes.size();
+        E.nodes.push_back(ConditionNode{});
+        F.flatten(*roots[i], root_node[i], nullptr, since);
         roots[i].reset();
     }
     E.root_of_state.resize(T.n_states);

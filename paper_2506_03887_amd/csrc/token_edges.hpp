@@ -29,7 +29,8 @@ namespace pre3 {
 
 struct ConditionNode {
     int32_t known;          // stack entries (from the top) fixed by this node's condition
-    int32_t child_begin;    // children in child_state/child_node[child_begin .. +child_count)
+    int32_t child_begin;    // children in child_state/child_node[child_begin .. +child_count); their nodes
+                            // have consecutive indices in the order of their condition states
     int32_t child_count;    // they are told apart by the state at depth `known` below the top
     int32_t dense_row;      // >= 0: dense_rows[dense_row * n_words ..] holds every token allowed at
                             // this node or at an ancestor; -1: none
