@@ -234,7 +234,9 @@ struct Flattener {
         E.max_known = std::max<int64_t>(E.max_known, b.known);
         size_t since_mark = since.size();
         std::vector<uint32_t> own_row;
-        const bool dense = (int)b.accepted.size() >= dense_threshold &&
+        // a row is materialised where the ids ORed in since the last materialised row reach the
+        // threshold, so that no descent ever collects more than `dense_threshold` ids
+        const bool dense = (int64_t)(since.size() + b.accepted.size()) >= dense_threshold &&
                            (int64_t)E.dense_rows.size() + E.n_words <= lim.max_dense_words;
         if (dense) {
             n.dense_row = (int)(E.dense_rows.size() / E.n_words);
@@ -335,7 +337,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     worker();
     for (auto &t : pool) t.join();
 
-    Flattener F{trie, lim, E, std::max(64, V.n_words)};
+    Flattener F{trie, lim, E, std::min(lim.max_path_ids, std::max(64, V.n_words))};
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;
