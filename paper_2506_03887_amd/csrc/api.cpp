@@ -104,6 +104,8 @@ hipError_t device_alloc(pre3_handle *h, size_t bytes, void **out, bool zero) {
     return e;
 }
 
+constexpr ptrdiff_t kHotBytesMax = 2 << 20;   // half of one XCD's L2
+
 int upload_tables(pre3_handle *h) {
     hipError_t e;
     DevTables &D = h->dev;
@@ -111,16 +113,9 @@ int upload_tables(pre3_handle *h) {
     if ((e = upload(h, vec, &D.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
     std::vector<int32_t> byte_info(256);
     for (int b = 0; b < 256; ++b) byte_info[b] = (int32_t)h->T.byte_class[b] | (h->T.byte_delta[b] * 256);
+    // first the tables a walk of one token touches, so that they form one contiguous region
     PRE3_UP(byte_info, byte_info);
-    PRE3_UP(h->T.edge, edge);
-    PRE3_UP(h->T.goto_row, goto_row);
-    PRE3_UP(h->T.goto_flat, goto_flat);
-    PRE3_UP(h->V.tok_len, tok_len);
-    PRE3_UP(h->V.tok_bit, tok_bit);
-    PRE3_UP(h->V.tok_words, tok_words);
-    PRE3_UP(h->V.bytes, vbytes);
-    PRE3_UP(h->V.offsets, voffsets);
-#undef PRE3_UP
+    const size_t chunks_before = h->allocations.size();
     D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_eff = nullptr; D.sym_pool = nullptr; D.state_kind = nullptr;
     if (h->S.enabled) {
         std::vector<int4> sn(h->S.nodes.size());
@@ -135,6 +130,21 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
         if ((e = upload(h, h->T.state_kind, &D.state_kind)) != hipSuccess) return hip_fail(h, e, "upload state_kind");
     }
+    {
+        const ptrdiff_t span = h->arena - reinterpret_cast<const char *>(D.byte_info);
+        const bool one_chunk = h->allocations.size() == chunks_before;
+        D.hot_begin = reinterpret_cast<const char *>(D.byte_info);
+        D.hot_bytes = one_chunk && span > 0 ? (int32_t)std::min<ptrdiff_t>(span, kHotBytesMax) : 0;
+    }
+    PRE3_UP(h->T.edge, edge);
+    PRE3_UP(h->T.goto_row, goto_row);
+    PRE3_UP(h->T.goto_flat, goto_flat);
+    PRE3_UP(h->V.tok_len, tok_len);
+    PRE3_UP(h->V.tok_bit, tok_bit);
+    PRE3_UP(h->V.tok_words, tok_words);
+    PRE3_UP(h->V.bytes, vbytes);
+    PRE3_UP(h->V.offsets, voffsets);
+#undef PRE3_UP
     D.n_states = h->T.n_states;
     D.ncol = h->T.n_classes + 1;
     D.end_col = h->T.n_classes;

@@ -29,6 +29,9 @@ struct DevTables {
     const int32_t *voffsets;       // [n_tokens + 1]
     int max_depth;                 // private stack entries a walk can need
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
+    // the small tables every advance touches lie next to each other: idle waves pull them into L2
+    const char *hot_begin;
+    int32_t hot_bytes;             // 0 = no such region
 };
 
 // Condition tree of the token-level prefix-conditioned edges (see token_edges.hpp), device form.

@@ -578,6 +578,18 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
 
 // ---------------------------------------------------------------------------- apply
 
+// 16-byte accesses marked non-temporal: the logits pass through once, and lines marked this way
+// are the first to leave L2, so the automaton's tables survive the pass for the next kernel.
+typedef unsigned int NativeUint4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load(const uint16_t *p) {
+    const NativeUint4 x = __builtin_nontemporal_load(reinterpret_cast<const NativeUint4 *>(p));
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ void stream_store(uint4 v, uint16_t *p) {
+    const NativeUint4 x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<NativeUint4 *>(p));
+}
+
 constexpr int kApplyBlock = 256;
 constexpr int kApplyUnroll = 1;        // 16-byte groups per lane (measured: more waves beat more loads per lane)
 constexpr int kApplySpan = kApplyBlock * kApplyUnroll * 8;   // logits per block
@@ -605,7 +617,7 @@ __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *
 #pragma unroll
     for (int u = 0; u < kApplyUnroll; ++u) {                // all loads of the lane are in flight together
         const int g = g0 + u * kApplyBlock;
-        if (m[u] != 0xFFu && m[u] != 0u && g * 8 + 8 <= vocab) v[u] = *reinterpret_cast<const uint4 *>(lrow + (size_t)g * 8);
+        if (m[u] != 0xFFu && m[u] != 0u && g * 8 + 8 <= vocab) v[u] = stream_load(lrow + (size_t)g * 8);
     }
 #pragma unroll
     for (int u = 0; u < kApplyUnroll; ++u) {
@@ -615,7 +627,7 @@ __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *
         uint16_t *p = lrow + (size_t)g * 8;
         if (g * 8 + 8 <= vocab) {
             if (mu == 0u) {
-                *reinterpret_cast<uint4 *>(p) = make_uint4(kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair);
+                stream_store(make_uint4(kNegInfPair, kNegInfPair, kNegInfPair, kNegInfPair), p);
             } else {
                 uint32_t *x = reinterpret_cast<uint32_t *>(&v[u]);
 #pragma unroll
@@ -623,7 +635,7 @@ __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *
                     if (!((mu >> (2 * k)) & 1u)) x[k] = (x[k] & 0xFFFF0000u) | 0xFF80u;
                     if (!((mu >> (2 * k + 1)) & 1u)) x[k] = (x[k] & 0x0000FFFFu) | 0xFF800000u;
                 }
-                *reinterpret_cast<uint4 *>(p) = v[u];
+                stream_store(v[u], p);
             }
         } else {
             for (int k = 0; g * 8 + k < vocab; ++k)
@@ -764,6 +776,16 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     const int n_vec = (T.n_words + 3) >> 2;
     int32_t *row = data + (size_t)b * cap;
 
+    if (tid >= 64) {
+        // The waves that wait for the walk pull the small tables it reads into this XCD's L2 (a
+        // streaming kernel that ran in between has evicted them): one 128-byte line per lane,
+        // the lines dealt out over the blocks of the XCD (blocks go round-robin to the 8 XCDs).
+        const int per_xcd = (gridDim.x + 7) >> 3, idle = kAfBlock - 64;
+        int acc = 0;
+        for (int off = ((blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
+            acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
+        if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
+    }
     if (tid < 64) {
         PrivateStack priv;
         priv.lds = s_adv_stack;
