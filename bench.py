@@ -1,15 +1,17 @@
 """Benchmark of the batched token-mask path on one MI355X.
 
-One step = token mask + logits masking + stack advance over one batch (B=256 sequences,
-V=128,256 tokens, byte-level JSON grammar: workload "json-B256-V128256"), replaying a seeded
-trajectory; all inputs are resident in HBM before the timed region.  The K timed steps are
-captured into one HIP graph (kernel launches only) and replayed between two HIP events, so
+One step = logits masking + stack advance + token mask of the next step over one batch (B=256
+sequences, V=128,256 tokens, byte-level JSON grammar: workload "json-B256-V128256"), replaying
+a seeded trajectory; all inputs are resident in HBM before the timed region.  The K timed steps
+are captured into one HIP graph (kernel launches only) and replayed between two HIP events, so
 the GPU runs the kernels back to back as a serving loop would: that replay gives `value`.
-Per-kernel durations are measured in a second, eager pass over the same K steps with a HIP
-event before and after every launch; the pass is queued behind a device-side delay so the
-events are processed back to back on the GPU (the rocprofv3 summaries under profiles/ hold
-the profiler's durations of the same kernels).  Prints ONE
-JSON line.
+Per-call durations (`kernels_us`) come from a second, eager pass over the same K steps with a
+HIP event before and after every launch; the pass is queued behind a device-side delay so the
+events are processed back to back on the GPU.  The launch duration behind `roofline` is taken
+without a bracket around every launch (K launches of the kernel in one graph between two
+events); the rocprofv3 summaries under profiles/ hold the profiler's durations of the same
+kernels.  After the timed runs the device state and the last mask are checked against the CPU
+oracle's replay.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -22,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 BYTES_PER_PAIR = 4.25          # algorithmic HBM bytes per (sequence, token) pair of mask+apply
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of apply_mask_vec8_kernel on the default workload, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE scaled by what the counters read on a plain device copy
+# (profiles/apply_mask_vec8_kernel__json-B256-V128256.txt); other workloads report null
+APPLY_TRAFFIC_BYTES = {3: 130.38e6}
 
 
 def main():
@@ -30,7 +36,7 @@ def main():
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--cpu-steps", type=int, default=2, help="steps of the workload timed on the CPU oracle")
+    ap.add_argument("--cpu-steps", type=int, default=96, help="steps of the workload timed on the CPU oracle")
     ap.add_argument("--repeats", type=int, default=3, help="replays of each graph (the fastest is reported)")
     ap.add_argument("--eager", action="store_true",
                     help="no HIP graphs: time the eager pass only (for counter collection with rocprofv3 --pmc)")
@@ -199,6 +205,27 @@ def main():
             return {"fill_apply_mask": d(0, 1), "advance": d(2, 3)}, wall
         return {"fill_mask": d(0, 1), "apply_mask": d(1, 2), "advance": d(2, 3)}, wall
 
+    def apply_launch_us():
+        """Average duration of one apply_mask launch: K launches (rotating logits buffers, so every
+        launch streams from HBM) replayed as one graph between two HIP events."""
+        restore()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(K):
+                apply_mask(logits[s % n_pool], mask_d, V)
+        best = float("inf")
+        for _ in range(max(1, args.repeats) + 1):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best * 1e3 / K
+
+    apply_us = float("nan") if args.eager else apply_launch_us()
     two_call_us, wall_two = eager_pass("fill+apply")
     step_us, wall_step = (two_call_us, wall_two) if step_kind == "fill+apply" else eager_pass(step_kind)
     if args.eager:
@@ -256,9 +283,18 @@ def main():
     kernels.update({k: stat(x) for k, x in step_us.items() if k not in kernels or step_kind != "fill+apply"})
     mask_apply_us = float((two_call_us["fill_mask"] + two_call_us["apply_mask"]).mean())
     # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
-    dom_us = float(step_us["apply_mask"].mean()) if "apply_mask" in step_us else float(step_us["fill_apply_mask"].mean())
-    dom_name = "apply_mask_vec8_kernel" if "apply_mask" in step_us else "fill_mask_edges_kernel<true>"
-    dom_bytes = (4.0 + 0.125) * pairs if "apply_mask" in step_us else BYTES_PER_PAIR * pairs
+    if "apply_mask" in step_us:
+        dom_name, dom_bytes = "apply_mask_vec8_kernel", (4.0 + 0.125) * pairs
+        dom_us = float(step_us["apply_mask"].mean()) if args.eager else apply_us
+        dom_timing = ("K launches on rotating logits buffers replayed as one HIP graph between two HIP events, "
+                      "divided by K (a pair of events around every single launch reads "
+                      f"{float(step_us['apply_mask'].mean()):.1f} us: the brackets add a few us)")
+        traffic = APPLY_TRAFFIC_BYTES.get(args.config)
+    else:
+        dom_name, dom_bytes = "fill_mask_edges_kernel<true>", BYTES_PER_PAIR * pairs
+        dom_us = float(step_us["fill_apply_mask"].mean())
+        dom_timing = "HIP events around every launch of an eager pass over the timed steps"
+        traffic = None
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     step_achieved = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9
     step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
@@ -283,10 +319,9 @@ def main():
         "kernels_us": kernels,
         "graph_ms_per_step": {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": 130.48e6 if dom_name.startswith("apply") else None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": dom_name, "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
-                     "timing": "HIP events around every launch of an eager pass over the timed steps, "
-                               "queued behind a device-side delay"},
+                     "timing": dom_timing},
         "cpu_baseline": {"value": pairs * n_cpu / cpu_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                          "sample": f"fill_mask+apply_mask of the first {n_cpu} steps of the same workload "
                                    f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",

@@ -116,7 +116,7 @@ int upload_tables(pre3_handle *h) {
     // first the tables a walk of one token touches, so that they form one contiguous region
     PRE3_UP(byte_info, byte_info);
     const size_t chunks_before = h->allocations.size();
-    D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_eff = nullptr; D.sym_pool = nullptr; D.state_kind = nullptr;
+    D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_cell = nullptr; D.sym_pool = nullptr; D.state_kind = nullptr;
     if (h->S.enabled) {
         std::vector<int4> sn(h->S.nodes.size());
         for (size_t i = 0; i < sn.size(); ++i)
@@ -126,7 +126,23 @@ int upload_tables(pre3_handle *h) {
         for (size_t i = 0; i < sp.size(); ++i) sp[i] = make_int2(h->S.child_state[i], h->S.child_node[i]);
         if ((e = upload(h, sn, &D.sym_nodes)) != hipSuccess) return hip_fail(h, e, "upload sym_nodes");
         if ((e = upload(h, sp, &D.sym_pairs)) != hipSuccess) return hip_fail(h, e, "upload sym_pairs");
-        if ((e = upload(h, h->S.eff, &D.sym_eff)) != hipSuccess) return hip_fail(h, e, "upload sym_eff");
+        // edges with at most two pushes travel inside their cell: one look-up per input symbol
+        if (h->S.pool.size() >= (size_t)kCellInline) return fail(h, PRE3_E_LIMIT, "reduction-edge records exceed 2^30 words");
+        std::vector<int4> cells(h->S.eff.size());
+        for (size_t i = 0; i < cells.size(); ++i) {
+            const int32_t code = h->S.eff[i];
+            int4 c = make_int4(code, 0, 0, 0);
+            if (code >= 0) {
+                const int32_t *r = &h->S.pool[code];
+                const int32_t known = r[0], peak = r[1], np = r[2] & kEffPushMask;
+                if (known < 256 && peak >= -128 && peak < 128 && np >= 1 && np <= 2)
+                    c = make_int4(kCellInline | known | ((peak + 128) << 8) | (np << 16) |
+                                      ((r[2] & kEffSameShape) ? kCellSameShape : 0),
+                                  r[3], r[4], np == 2 ? r[5] : 0);
+            }
+            cells[i] = c;
+        }
+        if ((e = upload(h, cells, &D.sym_cell)) != hipSuccess) return hip_fail(h, e, "upload sym_cell");
         if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
         if ((e = upload(h, h->T.state_kind, &D.state_kind)) != hipSuccess) return hip_fail(h, e, "upload state_kind");
     }
@@ -456,8 +472,9 @@ int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]) {
     out[0] = h->S.enabled;
     out[1] = (int64_t)h->S.nodes.size();
     out[2] = h->S.max_known;
-    out[3] = (int64_t)(h->S.nodes.size() * sizeof(SymbolNode) + (h->S.eff.size() + h->S.pool.size() +
-                                                                 h->S.child_state.size() * 2) * 4);
+    // device form: 16-byte node records, 16-byte cells, records pool, (condition state, child) pairs
+    out[3] = (int64_t)(h->S.nodes.size() * 16 + h->S.eff.size() * 16 + h->S.pool.size() * 4 +
+                       h->S.child_state.size() * 8);
     return PRE3_OK;
 }
 

@@ -6,6 +6,9 @@
 
 namespace pre3 {
 
+constexpr int32_t kCellInline = 1 << 30;
+constexpr int32_t kCellSameShape = 1 << 18;
+
 struct DevTables {
     // DPDA edges
     const int32_t *byte_info;      // [256] byte class | (acceptance-target offset << 8)
@@ -16,7 +19,11 @@ struct DevTables {
     // merged reduction edges with stack-matching conditions (symbol_edges.hpp); null = not built
     const int4 *sym_nodes;         // (known, child_begin, child_count, first_child)
     const int2 *sym_pairs;         // (condition state, child node)
-    const int32_t *sym_eff;        // [nodes * ncol]
+    // [nodes * ncol] one 16-byte cell per (condition node, symbol column).  x < 0: SymbolEffectCode;
+    // x with kCellInline: the whole edge (x = known | (peak + 128) << 8 | n_push << 16 | same-shape
+    // flag, y = kind after the edge, z and w = the one or two states pushed); otherwise x is the
+    // offset of the edge's record in sym_pool
+    const int4 *sym_cell;
     const int32_t *sym_pool;       // effect records, 16-byte aligned
     const int32_t *state_kind;     // [n_states] root node of each state's condition tree
     // vocabulary, chunk-sorted order

@@ -100,17 +100,36 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
     const int col = info & 0xFF, delta = info >> 8;    // byte class and per-byte target offset
     // `tree` names the condition tree of the top state (states that behave alike share one, and all
     // bytes of a class shift to states of one kind, so the kind after an edge is stored with it)
-    if (T.sym_eff) {
+    if (T.sym_cell) {
         int node = tree;
         int4 nd = table<kUniform>(T.sym_nodes, node);
-        int code = table<kUniform>(T.sym_eff, node * T.ncol + col);
+        int4 cell = table<kUniform>(T.sym_cell, node * T.ncol + col);
         for (int level = 0; level < 64; ++level) {
+            const int code = cell.x;
             if (code >= 0) {
-                // known, peak, n_push, kind after the edge; push[0..3] ride along in the same access
-                const int4 hdr = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), code >> 2);
-                const int4 more = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), (code >> 2) + 1);
-                const int pops = hdr.x - 1, np = hdr.z & kEffPushMask;
-                if (kCheckCap && base + d + hdr.y >= cap) return kOverflow;
+                // the edge: truncate to (len - known + 1) entries, push np states (the last one is the
+                // acceptance edge's target); `peak` bounds the height reached on the way
+                int known, peak, np, same, after;
+                int4 push4;
+                if (code & kCellInline) {
+                    known = code & 0xFF;
+                    peak = ((code >> 8) & 0xFF) - 128;
+                    np = (code >> 16) & 3;
+                    same = code & kCellSameShape;
+                    after = cell.y;
+                    push4 = make_int4(cell.z, cell.w, 0, 0);
+                } else {
+                    // record in the pool: known, peak, n_push, kind after; push[0..3] ride along
+                    const int4 hdr = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), code >> 2);
+                    push4 = table<kUniform>(reinterpret_cast<const int4 *>(T.sym_pool), (code >> 2) + 1);
+                    known = hdr.x;
+                    peak = hdr.y;
+                    np = hdr.z & kEffPushMask;
+                    same = hdr.z & kEffSameShape;
+                    after = hdr.w;
+                }
+                const int pops = known - 1;
+                if (kCheckCap && base + d + peak >= cap) return kOverflow;
                 if (pops <= d) {
                     d -= pops;
                 } else {
@@ -121,14 +140,14 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
                 if (d + np > T.max_depth) { if (!kUniform || (threadIdx.x & 63) == 0) atomicAdd(T.fault, 1); return kRejected; }
                 for (int i = 0; i < np; ++i) {
                     int v;
-                    if (i < 4) v = i == 0 ? more.x : i == 1 ? more.y : i == 2 ? more.z : more.w;
+                    if (i < 4) v = i == 0 ? push4.x : i == 1 ? push4.y : i == 2 ? push4.z : push4.w;
                     else v = table<kUniform>(T.sym_pool, code + 4 + i);
                     if (i == np - 1) v += delta;
                     priv.set(d++, v);
                     top = v;
                 }
-                if (run_node) *run_node = ((hdr.z & kEffSameShape) && hdr.w == tree) ? node : -1;
-                tree = hdr.w;
+                if (run_node) *run_node = (same && after == tree) ? node : -1;
+                tree = after;
                 return kFed;
             }
             if (code == kEffNone) return kRejected;
@@ -146,24 +165,25 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
             int next = -1;
             if (kUniform) {
                 // all lanes run this walk: lane j fetches condition j together with child j's node
-                // record and effect code, so one round of loads both picks the child and enters it
+                // record and cell, so one round of loads both picks the child and enters it
                 const int lane = threadIdx.x & 63;
-                int4 cnd = make_int4(0, 0, 0, 0);
-                int ccode = kEffStepwise, cstate = -2;
+                int4 cnd = make_int4(0, 0, 0, 0), ccell = make_int4(kEffStepwise, 0, 0, 0);
+                int cstate = -2;
                 for (int c0 = 0; c0 < nd.z && next < 0; c0 += 64) {
                     const int j = c0 + lane;
                     if (j < nd.z) {
                         cstate = T.sym_pairs[nd.y + j].x;
                         cnd = T.sym_nodes[nd.w + j];
-                        ccode = T.sym_eff[(nd.w + j) * T.ncol + col];
+                        ccell = T.sym_cell[(nd.w + j) * T.ncol + col];
                     }
                     const unsigned long long m = __ballot(j < nd.z && cstate == x);
                     if (m) {
                         const int src = __ffsll((long long)m) - 1;
                         next = nd.w + c0 + src;
-                        nd = make_int4(__shfl(cnd.x, src), __shfl(cnd.y, src), __shfl(cnd.z, src), __shfl(cnd.w, src));
-                        nd = make_int4(uni<true>(nd.x), uni<true>(nd.y), uni<true>(nd.z), uni<true>(nd.w));
-                        code = uni<true>(__shfl(ccode, src));
+                        nd = make_int4(uni<true>(__shfl(cnd.x, src)), uni<true>(__shfl(cnd.y, src)),
+                                       uni<true>(__shfl(cnd.z, src)), uni<true>(__shfl(cnd.w, src)));
+                        cell = make_int4(uni<true>(__shfl(ccell.x, src)), uni<true>(__shfl(ccell.y, src)),
+                                         uni<true>(__shfl(ccell.z, src)), uni<true>(__shfl(ccell.w, src)));
                     }
                 }
                 if (next < 0) break;
@@ -176,7 +196,7 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
                 if (next < 0) break;
                 node = next;
                 nd = T.sym_nodes[node];
-                code = T.sym_eff[node * T.ncol + col];
+                cell = T.sym_cell[node * T.ncol + col];
             }
         }
     }
@@ -238,9 +258,13 @@ __device__ __forceinline__ int apply_run(const DevTables &T, PrivateStack &priv,
     int new_top = 0;
     if (ok) {
         const int info = infos[i];
-        const int code = T.sym_eff[node * T.ncol + (info & 0xFF)];
+        const int4 cell = T.sym_cell[node * T.ncol + (info & 0xFF)];
+        const int code = cell.x;
         ok = code >= 0;
-        if (ok) {
+        if (ok && (code & kCellInline)) {
+            ok = (code & kCellSameShape) && cell.y == tree && (!kCheckCap || base + d + ((code >> 8) & 0xFF) - 128 < cap);
+            new_top = (((code >> 16) & 3) == 1 ? cell.z : cell.w) + (info >> 8);
+        } else if (ok) {
             const int4 hdr = *reinterpret_cast<const int4 *>(T.sym_pool + code);
             ok = (hdr.z & kEffSameShape) && hdr.w == tree && (!kCheckCap || base + d + hdr.y < cap);
             if (ok) new_top = T.sym_pool[code + 4 + (hdr.z & kEffPushMask) - 1] + (info >> 8);
