@@ -160,6 +160,16 @@ int upload_tables(pre3_handle *h) {
     PRE3_UP(h->V.tok_words, tok_words);
     PRE3_UP(h->V.bytes, vbytes);
     PRE3_UP(h->V.offsets, voffsets);
+    {
+        std::vector<int32_t> info((size_t)h->V.n_tokens * 32, 0);
+        for (int t = 0; t < h->V.n_tokens; ++t) {
+            const int lo = h->V.offsets[t], n = h->V.offsets[t + 1] - lo;
+            int32_t *rec = &info[(size_t)t * 32];
+            rec[0] = n <= kTokInfoBytes ? n : -1;
+            for (int i = 0; i < n && i < kTokInfoBytes; ++i) rec[1 + i] = byte_info[h->V.bytes[lo + i]];
+        }
+        PRE3_UP(info, tok_info);
+    }
 #undef PRE3_UP
     D.n_states = h->T.n_states;
     D.ncol = h->T.n_classes + 1;

@@ -9,6 +9,8 @@ namespace pre3 {
 constexpr int32_t kCellInline = 1 << 30;
 constexpr int32_t kCellSameShape = 1 << 18;
 
+constexpr int kTokInfoBytes = 31;
+
 struct DevTables {
     // DPDA edges
     const int32_t *byte_info;      // [256] byte class | (acceptance-target offset << 8)
@@ -34,6 +36,9 @@ struct DevTables {
     // vocabulary, id order
     const uint8_t *vbytes;
     const int32_t *voffsets;       // [n_tokens + 1]
+    // one 128-byte line per token: [0] = length in bytes (-1: longer than kTokInfoBytes, use vbytes),
+    // [1 + i] = byte_info of byte i -- everything a walk needs to know about the token in one access
+    const int32_t *tok_info;       // [n_tokens * 32]
     int max_depth;                 // private stack entries a walk can need
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
     // the small tables every advance touches lie next to each other: idle waves pull them into L2

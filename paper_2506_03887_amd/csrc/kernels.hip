@@ -714,9 +714,16 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     if (live) {
         s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
         if (t != T.eos_id) {
-            lo = T.voffsets[t];
-            hi = T.voffsets[t + 1];
-            if (lo + lane < hi) s_info[wave][lane] = T.byte_info[T.vbytes[lo + lane]];
+            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
+            const int n_bytes = rec[0];
+            if (n_bytes >= 0) {
+                hi = n_bytes;
+                if (lane < n_bytes) s_info[wave][lane] = rec[1 + lane];
+            } else {
+                lo = T.voffsets[t];
+                hi = T.voffsets[t + 1];
+                if (lo + lane < hi) s_info[wave][lane] = T.byte_info[T.vbytes[lo + lane]];
+            }
         }
     }
     __builtin_amdgcn_wave_barrier();
@@ -824,9 +831,16 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         int lo = 0, hi = 0;
         s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
         if (live && t != T.eos_id) {
-            lo = T.voffsets[t];
-            hi = T.voffsets[t + 1];
-            if (lo + lane < hi) s_info[lane] = T.byte_info[T.vbytes[lo + lane]];
+            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
+            const int n_bytes = rec[0];
+            if (n_bytes >= 0) {
+                hi = n_bytes;
+                if (lane < n_bytes) s_info[lane] = rec[1 + lane];
+            } else {
+                lo = T.voffsets[t];
+                hi = T.voffsets[t + 1];
+                if (lo + lane < hi) s_info[lane] = T.byte_info[T.vbytes[lo + lane]];
+            }
         }
         __builtin_amdgcn_wave_barrier();
         // ---- advance (all lanes hold identical values)
