@@ -69,6 +69,8 @@ def _load():
     lib.pre3o_allowed_many.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp]
     lib.pre3o_apply_mask.restype = None
     lib.pre3o_apply_mask.argtypes = [vp, vp, i32, i32, i64]
+    lib.pre3o_masked_argmax.restype = None
+    lib.pre3o_masked_argmax.argtypes = [vp, vp, i32, i32, i64, vp]
     lib.pre3o_advance_batch.restype = None
     lib.pre3o_advance_batch.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp]
     _lib = lib
@@ -219,3 +221,12 @@ def apply_mask(logits_u16: np.ndarray, bitmask: np.ndarray, n_tokens: int) -> No
     assert logits_u16.dtype == np.uint16 and logits_u16.flags.c_contiguous and logits_u16.ndim == 2
     bm = np.ascontiguousarray(bitmask, dtype=np.uint32)
     _load().pre3o_apply_mask(_ptr(logits_u16), _ptr(bm), bm.shape[0], int(n_tokens), logits_u16.shape[1])
+
+
+def masked_argmax(logits_u16: np.ndarray, bitmask: np.ndarray, n_tokens: int) -> np.ndarray:
+    """Greedy choice per row: id of the largest allowed, non-NaN bf16 logit (first of equals), -1 if none."""
+    assert logits_u16.dtype == np.uint16 and logits_u16.flags.c_contiguous and logits_u16.ndim == 2
+    bm = np.ascontiguousarray(bitmask, dtype=np.uint32)
+    out = np.empty(bm.shape[0], dtype=np.int32)
+    _load().pre3o_masked_argmax(_ptr(logits_u16), _ptr(bm), bm.shape[0], int(n_tokens), logits_u16.shape[1], _ptr(out))
+    return out

@@ -838,6 +838,29 @@ void pre3o_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int 
                 logits[(size_t)b * (size_t)row_stride + (size_t)t] = 0xFF80;
 }
 
+/* Greedy choice among the allowed tokens (Sec. 1: the mask removes the invalid tokens before
+ * a token is sampled; the greedy sampler takes the most probable of what is left):
+ * out[b] = the allowed token whose bf16 logit is largest as a number; among equal values
+ * (+0 and -0 are equal) the smallest id; NaN logits are never chosen; -1 if no token is both
+ * allowed and not NaN.  The logits are not modified. */
+void pre3o_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int n_tokens,
+                         int64_t row_stride, int32_t *out) {
+    int W = (n_tokens + 31) / 32;
+    for (int b = 0; b < batch; b++) {
+        int best = -1;
+        float best_value = 0.0f;
+        for (int t = 0; t < n_tokens; t++) {
+            if (!((bitmask[(size_t)b * W + (t >> 5)] >> (t & 31)) & 1u)) continue;
+            uint32_t bits = (uint32_t)logits[(size_t)b * (size_t)row_stride + (size_t)t] << 16;
+            float value;                      /* a bf16 number is the upper half of a binary32 */
+            memcpy(&value, &bits, sizeof value);
+            if (value != value) continue;     /* NaN */
+            if (best < 0 || value > best_value) { best = t; best_value = value; }
+        }
+        out[b] = best;
+    }
+}
+
 /* Batched advance mirroring the device call: tokens[b] < 0 skips the sequence;
  * the end-of-sequence token marks it finished (states[b] = -1, stack untouched);
  * err[b] = 1 for a token that is not allowed (also any token on a finished

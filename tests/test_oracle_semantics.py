@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from cfg_brute import languages
-from oracle import Oracle, apply_mask
+from oracle import Oracle, apply_mask, masked_argmax
 from workloads import grammars as G
 from workloads.vocab import BASE_SEED, Vocab, arithmetic_vocab, bf16_logits, bpe_like_vocab
 
@@ -297,6 +297,72 @@ def test_apply_mask_is_a_bf16_select():
     wide[:, :V] = logits
     apply_mask(wide, mask, V)
     assert (wide[:, :V] == expect).all() and (wide[:, V:] == 0x1234).all()
+
+
+def _bits_of(mask, V):
+    return ((mask[:, np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1).astype(bool)
+
+
+def test_masked_argmax_is_numpy_argmax_over_the_candidates():
+    # pinned to a library routine: numpy's argmax (first occurrence of the maximum) over the
+    # float32 values of the allowed, non-NaN entries
+    rng = np.random.default_rng(11)
+    B, V = 9, 2000 + 13
+    logits = bf16_logits(rng, B, V)
+    # coarse values in some rows so that equal maxima occur
+    logits[3] = (np.round(rng.normal(size=V) * 2).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    logits[4] = logits[3]
+    logits[5, ::7] = 0x7FC0                                   # NaNs sprinkled in
+    logits[5, 3::11] = 0xFFC0
+    logits[6, 100] = 0x7F80                                   # +inf wins when allowed
+    W = (V + 31) // 32
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[7] = 0                                               # nothing allowed
+    mask[8] = 0
+    mask[8, 5] = 1 << 9                                       # exactly one token allowed
+    bits = _bits_of(mask, V)
+    values = (logits.astype(np.uint32) << 16).view(np.float32)
+    expect = np.full(B, -1, dtype=np.int32)
+    for b in range(B):
+        cand = np.flatnonzero(bits[b] & ~np.isnan(values[b]))
+        if len(cand):
+            expect[b] = cand[np.argmax(values[b, cand])]
+    got = masked_argmax(logits, mask, V)
+    assert got.tolist() == expect.tolist()
+    assert expect[7] == -1 and expect[8] == 5 * 32 + 9
+    # the choice is what a sampler would see after apply_mask: the masked logits' own maximum
+    masked = logits.copy()
+    apply_mask(masked, mask, V)
+    mv = (masked.astype(np.uint32) << 16).view(np.float32)
+    for b in range(B):
+        if expect[b] >= 0:
+            assert mv[b, expect[b]] == np.nanmax(mv[b])
+
+
+def test_masked_argmax_hand_cases():
+    V = 40
+    W = 2
+    def run(values_u16, allowed):
+        logits = np.full((1, V), 0xC000, dtype=np.uint16)     # -2.0 everywhere
+        for t, x in values_u16.items():
+            logits[0, t] = x
+        mask = np.zeros((1, W), dtype=np.uint32)
+        for t in allowed:
+            mask[0, t >> 5] |= np.uint32(1 << (t & 31))
+        return int(masked_argmax(logits, mask, V)[0])
+    one, two, neg0, pos0, nan, ninf, pinf = 0x3F80, 0x4000, 0x8000, 0x0000, 0x7FC1, 0xFF80, 0x7F80
+    assert run({3: two, 9: one}, [3, 9, 12]) == 3
+    assert run({3: two, 9: two}, [9, 3]) == 3                 # equal values: smallest id
+    assert run({3: two, 9: one}, [9, 12]) == 9                # the larger one is masked
+    assert run({35: two}, [35, 1]) == 35                      # second mask word
+    assert run({4: neg0, 7: pos0}, [4, 7]) == 4               # -0 == +0: first wins
+    assert run({4: pos0, 7: neg0}, [4, 7]) == 4
+    assert run({2: nan, 5: one}, [2, 5]) == 5                 # NaN is never chosen
+    assert run({2: nan}, [2]) == -1
+    assert run({2: ninf, 6: ninf}, [6, 2]) == 2               # -inf is a value like any other
+    assert run({2: ninf, 6: nan}, [6, 2]) == 2
+    assert run({2: pinf, 6: two}, [6, 2]) == 2
+    assert run({}, []) == -1
 
 
 def test_arithmetic_workload_vocab_has_the_terminals():
