@@ -64,7 +64,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
         return
 
-    from oracle import Oracle, apply_mask as oracle_apply_mask
+    from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax
     from paper_2506_03887_amd import Pre3, apply_mask
     from workloads import configs, trajectory
     from workloads.vocab import bf16_logits
@@ -260,6 +260,65 @@ def main():
     d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
     assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_c, d_c, l_c, v)).all(), "final mask differs"
 
+    # ---- greedy decoding: the sampler fused behind the mask (pre3_apply_mask_argmax reads the logits once
+    #      and writes nothing back), tokens fed straight to pre3_advance_fill_mask
+    def greedy_leg():
+        tok_d = torch.empty(B, dtype=torch.int32, device=dev)
+        for x in logits:                          # fresh logits: the timed passes above have masked these in place
+            x.copy_(torch.randn((B, V), generator=gen, device=dev, dtype=torch.float32))
+        restore()
+        torch.cuda.synchronize()
+        d_g, ls_g = data_d.cpu().numpy().copy(), ls_d.cpu().numpy().copy()
+        l_g, s_g = ls_g[0].copy(), ls_g[1].copy()
+        host_logits = [x.view(torch.int16).cpu().numpy().view(np.uint16) for x in logits]
+        n_check = 6
+        for s in range(n_check):                  # both sides choose their own tokens and must agree
+            want = oracle_masked_argmax(host_logits[s % n_pool], o.fill_mask(s_g, d_g, l_g, v), V)
+            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
+            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
+            assert (tok_d.cpu().numpy() == want).all(), "greedy tokens differ from the oracle's"
+            e = o.advance_batch(s_g, d_g, l_g, want, v)
+            fin = s_g < 0
+            s_g[fin], l_g[fin] = s0[fin], 1
+            assert (err_d.cpu().numpy() == e).all()
+        assert (states_d.cpu().numpy() == s_g).all() and (len_d.cpu().numpy() == l_g).all()
+
+        def graph_us(fn):
+            restore()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in range(K):
+                    fn(s)
+            best = float("inf")
+            for _ in range(max(1, args.repeats) + 1):
+                restore()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            return best * 1e3 / K
+
+        def greedy_step(s):
+            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
+            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
+
+        argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
+        step_us_g = graph_us(greedy_step)
+        nbytes = 2.0 * pairs_ + 4.0 * B * W
+        return {"step": "pre3_apply_mask_argmax + pre3_advance_fill_mask, K steps in one HIP graph, tokens chosen on the device",
+                "us_per_step": step_us_g, "tokens_per_s": pairs_ / (step_us_g * 1e-6),
+                "argmax_launch_us": argmax_us, "argmax_algorithmic_bytes": nbytes,
+                "argmax_achieved_GBs": nbytes / (argmax_us * 1e-6) / 1e9,
+                "argmax_frac_of_hbm_peak": nbytes / (argmax_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "checked_steps_against_oracle": n_check}
+
+    pairs_ = float(B) * V
+    greedy = None if args.eager else greedy_leg()
+
     # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
     n_cpu = max(1, args.cpu_steps)
     data_c, len_c = traj.init_data.copy(), traj.init_len.copy()
@@ -326,6 +385,7 @@ def main():
                          "sample": f"fill_mask+apply_mask of the first {n_cpu} steps of the same workload "
                                    f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",
                          "us_per_step": cpu_t / n_cpu * 1e6},
+        "greedy": greedy,
         "compile_s": t_compile,
         "token_edges": lib.token_edge_stats(),
     }

@@ -179,6 +179,22 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream);
 int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,
                            pre3_stream stream);
 
+/* Greedy sampling fused behind the mask (Sec. 1: invalid tokens are excluded, then a token is
+ * sampled; here the sampler is the arg max).  For every bound sequence b:
+ *   out_tokens[b] = the token t with bit t of bitmask row b set whose bf16 logit is the largest
+ *   number; among equal values (+0 and -0 are equal) the smallest id; NaN logits are never
+ *   chosen; -1 if no token is both allowed and not NaN.
+ * This is the arg max of what pre3_apply_mask would leave in the row, but the logits are only
+ * read (groups of 8 masked tokens are not even read) and nothing is written back.
+ * logits_bf16: device, [batch, row_stride] bf16 bit patterns, row_stride >= n_tokens (16-byte
+ * aligned rows take the vector path, any other layout a slower one); bitmask: device, [batch,
+ * ceil(n_tokens/32)] as pre3_fill_mask writes it; out_tokens: device [batch], ready to be
+ * passed to pre3_advance.  batch is that of the bound buffers (pre3_bind_state), which also
+ * sized the call's workspace inside the handle: calls on one handle must not overlap.
+ * Errors: BADARG (nothing bound, null pointer, row_stride < n_tokens). */
+int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
+                           int32_t *out_tokens, pre3_stream stream);
+
 /* ---- host-side introspection of the compiled tables (used by tests and tools) ---- */
 
 int32_t pre3_n_grammars(const pre3_handle *h);

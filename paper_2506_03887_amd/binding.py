@@ -24,7 +24,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance",
 ]
@@ -77,6 +77,7 @@ def load():
     lib.pre3_fill_apply_mask.argtypes = [vp, vp, _Stacks, vp, vp, c.c_int64, vp]
     lib.pre3_advance.argtypes = [vp, vp, vp]
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
+    lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
         getattr(lib, name).argtypes = [vp]
     lib.pre3_byte_class.argtypes = [vp, i32]
@@ -246,6 +247,13 @@ class Pre3:
         self._check(self._lib.pre3_advance_fill_mask(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
                                                      ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
                                                      _stream_ptr(stream)))
+
+    def apply_mask_argmax(self, logits, bitmask, out_tokens, stream=None):
+        """out_tokens[b] = id of the largest allowed logit of row b (bound batch); the logits are only read."""
+        assert logits.dim() == 2 and logits.stride(1) == 1 and bitmask.is_contiguous() and out_tokens.is_contiguous()
+        assert bitmask.shape[1] == self.words and out_tokens.numel() == logits.shape[0] == bitmask.shape[0]
+        self._check(self._lib.pre3_apply_mask_argmax(self._h, _dev(logits, "u16"), logits.stride(0), _dev(bitmask, "u32"),
+                                                     _dev(out_tokens, "i32"), _stream_ptr(stream)))
 
 
 def apply_mask(logits, bitmask, vocab: int, stream=None):

@@ -45,6 +45,9 @@ struct pre3_handle {
     pre3_stacks b_stacks{};
     int32_t *adv_scratch = nullptr;
     int32_t *af_walk_spill = nullptr;
+    unsigned long long *argmax_best = nullptr;   // per-segment partial results of pre3_apply_mask_argmax
+    size_t argmax_bytes = 0;
+    int n_compute_units = 0;
     size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
     size_t adv_scratch_entries = 0;
@@ -185,6 +188,7 @@ int upload_tables(pre3_handle *h) {
     hipDeviceProp_t prop;
     if ((e = hipGetDevice(&device)) != hipSuccess) return hip_fail(h, e, "hipGetDevice");
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return hip_fail(h, e, "hipGetDeviceProperties");
+    h->n_compute_units = prop.multiProcessorCount;
     h->grid_blocks = walk_grid_blocks(prop.multiProcessorCount);
     void *p = nullptr;
     if ((e = device_alloc(h, walk_spill_entries(h->grid_blocks, h->max_depth) * sizeof(int32_t), &p, false)) != hipSuccess)
@@ -337,6 +341,14 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
         h->adv_scratch = static_cast<int32_t *>(p);
         h->adv_scratch_entries = need;
     }
+    const size_t need_arg = masked_argmax_workspace_bytes(stacks.batch, h->V.n_tokens, h->n_compute_units);
+    if (need_arg > h->argmax_bytes) {
+        void *p = nullptr;
+        hipError_t e = device_alloc(h, need_arg, &p, false);
+        if (e != hipSuccess) return hip_fail(h, e, "allocate argmax workspace");
+        h->argmax_best = static_cast<unsigned long long *>(p);
+        h->argmax_bytes = need_arg;
+    }
     if (h->use_edges) {
         size_t need2 = advance_fill_walk_spill_entries(stacks.batch, h->max_depth);
         if (need2 > h->af_walk_spill_entries) {
@@ -429,6 +441,19 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
                        h->b_stacks.batch, h->b_err, h->adv_scratch, restart, s);
     if (e != hipSuccess) return hip_fail(h, e, "launch advance");
     return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);
+}
+
+int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
+                           int32_t *out_tokens, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "apply_mask_argmax: no state bound");
+    if (!logits_bf16 || !bitmask || !out_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_argmax: null pointer");
+    if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_argmax: row stride below vocabulary size");
+    hipError_t e = launch_masked_argmax(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride,
+                                        h->n_compute_units, h->argmax_best, out_tokens,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask_argmax");
 }
 
 int32_t pre3_n_grammars(const pre3_handle *h) { return h && h->compiled ? h->T.n_grammars : PRE3_E_BADARG; }

@@ -28,6 +28,9 @@ hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batc
                              hipStream_t stream);
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
                           int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos, hipStream_t stream);
+hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
+                                int n_compute_units, unsigned long long *workspace, int32_t *out, hipStream_t stream);
+size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);   // per-segment partial results
 size_t advance_fill_walk_spill_entries(int batch, int max_depth);   // int32 entries
 hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
