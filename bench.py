@@ -283,6 +283,9 @@ def main():
             assert (err_d.cpu().numpy() == e).all()
         assert (states_d.cpu().numpy() == s_g).all() and (len_d.cpu().numpy() == l_g).all()
 
+        if args.eager:                            # counter collection: the checked eager steps are enough
+            return {"checked_steps_against_oracle": n_check}
+
         def graph_us(fn):
             restore()
             torch.cuda.synchronize()
@@ -317,7 +320,7 @@ def main():
                 "checked_steps_against_oracle": n_check}
 
     pairs_ = float(B) * V
-    greedy = None if args.eager else greedy_leg()
+    greedy = greedy_leg()
 
     # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
     n_cpu = max(1, args.cpu_steps)
