@@ -375,6 +375,7 @@ def main():
         "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": "byte-level JSON, canonical LR(1)",
                    "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
                    "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
+        "fill_mask_tokens_per_s": pairs / (float(two_call_us["fill_mask"].mean()) * 1e-6),
         "mask_apply_us_per_step": mask_apply_us,
         "mask_apply_tokens_per_s": pairs / (mask_apply_us * 1e-6),
         "mask_apply_frac_of_hbm_peak": step_achieved / HBM_PEAK_GBS,
