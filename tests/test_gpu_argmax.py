@@ -141,3 +141,50 @@ def test_greedy_decode_in_lockstep_with_the_oracle(cfg_idx, steps, fused_advance
         assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all()
         live = np.arange(cap)[None, :] < len_h[:, None]
         assert (data_d.cpu().numpy()[live] == data_h[live]).all()
+
+
+def test_greedy_decode_emits_documents_the_json_module_accepts():
+    """No oracle in the loop: the device decodes greedily from seeded logits (EOS favoured a little
+    so that documents end), and every finished sequence's text must parse with Python's json."""
+    import json
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    cfg = configs.get(2)
+    v = cfg.vocab
+    B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap)
+    s0 = lib.initial_state(0)
+    data_d = torch.zeros((B, cap), dtype=torch.int32, device=dev)
+    data_d[:, 0] = s0
+    len_d = torch.ones(B, dtype=torch.int32, device=dev)
+    states_d = torch.full((B,), s0, dtype=torch.int32, device=dev)
+    err_d = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
+    tok_d = torch.empty(B, dtype=torch.int32, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed + 9)
+    lib.fill_mask(states_d, data_d, len_d, mask_d)
+    texts = [bytearray() for _ in range(B)]
+    finished = [None] * B
+    for _ in range(160):
+        logits = torch.randn((B, V), generator=gen, device=dev, dtype=torch.float32)
+        logits[:, v.eos_id] += 2.5
+        lib.apply_mask_argmax(logits.to(torch.bfloat16), mask_d, tok_d)
+        live = (states_d >= 0)
+        toks = torch.where(live, tok_d, torch.full_like(tok_d, -1))      # finished sequences stay finished
+        lib.advance_fill_mask(toks, mask_d)
+        t_h, e_h, s_h = toks.cpu().numpy(), err_d.cpu().numpy(), states_d.cpu().numpy()
+        for b in range(B):
+            if t_h[b] < 0 or e_h[b] != 0:
+                continue
+            if t_h[b] == v.eos_id:
+                assert s_h[b] < 0
+                finished[b] = bytes(texts[b])
+            else:
+                texts[b] += v.tokens[t_h[b]]
+    done = [t for t in finished if t is not None]
+    assert len(done) >= B // 2, f"only {len(done)} of {B} sequences ended"
+    for t in done:
+        json.loads(t.decode("latin-1"))                          # raises on anything that is not JSON
+    assert len({bytes(t) for t in done}) > 5
