@@ -15,7 +15,11 @@
  *     or reallocates caller memory.
  *   - Every function returns PRE3_OK (0) or a negative pre3_status.  Nothing throws.
  *   - Device calls only enqueue work on `stream` (a hipStream_t, NULL = default stream)
- *     and return; they do not synchronise and do not allocate.
+ *     and return; they do not synchronise and do not allocate.  pre3_compile and
+ *     pre3_bind_state are the calls that allocate device memory (tables; scratch sized by
+ *     the bound batch).  Device calls that take the handle share that scratch: enqueue
+ *     them so that calls on one handle do not run concurrently (one stream, or ordered
+ *     by events); different handles are independent.
  *   - Terminals are single bytes; a parse stack holds LR(1) state ids only, bottom first
  *     (Sec. 3.2.2: an acceptance edge pushes the target node's state).
  *   - State ids: canonical LR(1) item sets (App. A.2) numbered in breadth-first discovery

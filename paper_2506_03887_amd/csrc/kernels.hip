@@ -620,9 +620,10 @@ constexpr int kApplySpan = kApplyBlock * kApplyUnroll * 8;   // logits per block
 
 // blockIdx.y = row, blockIdx.x = span of kApplySpan logits.  A lane owns kApplyUnroll groups of 8
 // consecutive logits (16 bytes), one per pass, so that every pass of a wave is one contiguous
-// 1 KiB access.  In-place read-modify-write of the logits streams at about 5.6 TB/s on MI355X
-// whatever the unroll, block size or cache hints; one group per lane was the fastest.  Fully allowed groups are not touched, fully masked groups are overwritten
-// without being read, mixed groups are read, patched and written back.
+// 1 KiB access.  Fully allowed groups are not touched, fully masked groups are overwritten
+// without being read, mixed groups are read, patched and written back.  In-place
+// read-modify-write of the logits streams at about 5.4 TB/s on MI355X whatever the unroll or
+// block size; one group per lane was the fastest.
 __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *__restrict__ logits,
                                                                      const uint32_t *__restrict__ bitmask,
                                                                      int vocab, int64_t row_stride, int n_words) {
