@@ -707,8 +707,8 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 }
 
 // Greedy choice among the allowed tokens without writing the masked logits back: a row's logits
-// are read once (groups of 8 whose mask byte is zero are not read at all).  blockIdx.y = row,
-// blockIdx.x = segment of the row.  A lane keeps the largest value it has seen among allowed
+// are read once (groups of 8 whose mask byte is zero are not read at all).  blockIdx.x = row,
+// blockIdx.y = segment of the row.  A lane keeps the largest value it has seen among allowed
 // entries and its id (ids ascend within a lane, so `>` keeps the first of equal values; a NaN
 // never compares greater; an allowed -inf, which can only win if nothing else is allowed, is
 // remembered separately by lanes that have seen nothing larger); lanes and waves are then
@@ -726,9 +726,9 @@ __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int groups_per_seg, int vec_ok, unsigned long long *__restrict__ partial, int32_t *__restrict__ out) {
     __shared__ unsigned long long s_part[kArgBlock / 64];
-    const int b = blockIdx.y, tid = threadIdx.x;
+    const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x;
     const int groups = (vocab + 7) >> 3;
-    const int g_lo = blockIdx.x * groups_per_seg, g_hi = min(groups, g_lo + groups_per_seg);
+    const int g_lo = seg * groups_per_seg, g_hi = min(groups, g_lo + groups_per_seg);
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     float best_v = -INFINITY;
@@ -796,8 +796,8 @@ __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
     }
     __syncthreads();
     mine = s_part[0];
-    if (gridDim.x > 1) {
-        if (tid == 0) partial[(size_t)b * gridDim.x + blockIdx.x] = mine;
+    if (n_seg > 1) {
+        if (tid == 0) partial[(size_t)b * n_seg + seg] = mine;
         return;
     }
     if (tid == 0) out[b] = mine != 0ull ? (int32_t)(0xFFFFFFFFu - (uint32_t)mine) : -1;
@@ -1208,12 +1208,11 @@ size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units) 
 hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                                 int n_compute_units, unsigned long long *workspace, int32_t *out, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    if (batch > 65535) return hipErrorInvalidValue;
     const int n_words = (vocab + 31) / 32, groups = (vocab + 7) / 8;
     const int n_seg = masked_argmax_segments(batch, vocab, n_compute_units);
     const int groups_per_seg = (groups + n_seg - 1) / n_seg;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
-    hipLaunchKernelGGL(masked_argmax_kernel, dim3(n_seg, batch), dim3(kArgBlock), 0, stream, logits, bitmask, vocab,
+    hipLaunchKernelGGL(masked_argmax_kernel, dim3(batch, n_seg), dim3(kArgBlock), 0, stream, logits, bitmask, vocab,
                        row_stride, n_words, groups_per_seg, vec_ok, workspace, out);
     if (n_seg > 1)
         hipLaunchKernelGGL(masked_argmax_finish_kernel, dim3((batch + kArgFinishRows - 1) / kArgFinishRows),
