@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpre3.so")
-SOURCES = ["grammar.cpp", "lr1.cpp", "tables.cpp", "token_edges.cpp", "symbol_edges.cpp", "api.cpp", "kernels.hip"]
+SOURCES = ["grammar.cpp", "lr1.cpp", "tables.cpp", "token_edges.cpp", "symbol_edges.cpp", "api.cpp",
+           "mask_kernels.hip", "logits_kernels.hip", "advance_kernels.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-pthread",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -1,0 +1,323 @@
+// gfx950 kernels of the stack advance: one sampled token per sequence walked on the sequence's
+// own stack, alone or followed by the next step's mask row in the same launch.
+#include <hip/hip_runtime.h>
+
+#include "launch.hpp"
+#include "row_plan.hpp"
+
+namespace pre3 {
+
+namespace {
+
+// -------------------------------------------------------------------------- advance
+
+// One wave per sequence: the walk of a single token is a chain of dependent table look-ups, so
+// giving every sequence its own wave keeps control flow uniform (lanes of a shared wave would
+// serialise each other's reduction chains) and lets the chip overlap the chains of all
+// sequences.  Lane 0 walks the token on a private overlay exactly like in the mask kernels;
+// only a walk that succeeds is committed, by all lanes, to the sequence's stack.
+constexpr int kAdvSeqPerBlock = 4;
+__global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
+    DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
+    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos) {
+    __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
+    __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
+    __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * kAdvSeqPerBlock + wave;
+    if (b >= batch) return;
+    int32_t *row = data + (size_t)b * cap;
+    PrivateStack priv;
+    priv.lds = lds_stack + wave;
+    priv.lds_stride = kAdvSeqPerBlock;
+    priv.spill = scratch + b;
+    priv.spill_stride = (size_t)batch;
+    // every lane: the sequence's inputs, then (in parallel across lanes) the top of the stack and
+    // the byte classes of the token, so that lane 0's walk finds them in LDS
+    const int t = tokens[b];
+    const int n = len[b];
+    const int st = states[b];
+    const bool live = t >= 0 && t < T.n_tokens && st >= 0 && n >= 1 && n <= cap;
+    int lo = 0, hi = 0;
+    if (live) {
+        s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
+        if (t != T.eos_id) {
+            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
+            const int n_bytes = rec[0];
+            if (n_bytes >= 0) {
+                hi = n_bytes;
+                if (lane < n_bytes) s_info[wave][lane] = rec[1 + lane];
+            } else {
+                lo = T.voffsets[t];
+                hi = T.voffsets[t + 1];
+                if (lo + lane < hi) s_info[wave][lane] = T.byte_info[T.vbytes[lo + lane]];
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    // The walk itself runs on all 64 lanes with identical values (scalar table loads, LDS
+    // broadcast reads); lane 0 alone writes the results.
+    int commit = -1, out_err = 0, out_state = st, out_len = n;
+    if (t >= 0) {
+        int top = live ? __builtin_amdgcn_readfirstlane(s_win[wave][0]) : -1;
+        if (!live || (unsigned)top >= (unsigned)T.n_states) {
+            out_err = 1;
+        } else {
+            const StackView view{row, s_win[wave], n};
+            int base = n, d = 0;
+            int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
+            if (t == T.eos_id) {
+                if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
+                    out_state = -1;
+                    if (restart_on_eos) { out_state = row[0]; out_len = 1; }   // slot reuse: back to the initial state
+                } else {
+                    out_err = 1;
+                }
+            } else {
+                int rc = hi > lo ? kFed : kRejected;
+                for (int i = 0; i < hi - lo && rc == kFed; ++i) {
+                    const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[wave][i] : T.byte_info[T.vbytes[lo + i]]);
+                    int run_node = -1;
+                    rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+                    if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
+                        i += apply_run<true>(T, priv, s_info[wave], i + 1, hi - lo, run_node, kind, base, d, top, cap);
+                }
+                if (rc != kFed) {
+                    out_err = rc == kOverflow ? 2 : 1;
+                } else {
+                    commit = d;
+                    out_len = base + d;
+                    out_state = top;
+                    s_base[wave] = base;
+                }
+            }
+        }
+        if (lane == 0) {
+            err[b] = out_err;
+            if (out_err == 0) { states[b] = out_state; len[b] = out_len; }
+        }
+    } else if (lane == 0) {
+        err[b] = 0;
+    }
+    s_depth[wave] = commit;
+    __builtin_amdgcn_wave_barrier();
+    // LDS operations of one wave complete in order; entries that spilled to global memory are
+    // copied by lane 0
+    const int d = s_depth[wave];
+    if (d > 0) {
+        const int base = s_base[wave];
+        const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+        if (lane < in_lds) row[base + lane] = priv.get(lane);
+        if (lane == 0)
+            for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
+    }
+}
+
+// Advance and next mask in one launch: one block per sequence.  Wave 0 walks the sampled token
+// exactly like advance_kernel (scalar table loads), commits the new stack, stages the NEW top
+// of the stack in LDS and descends the condition tree of the token-level edges with it; then the
+// whole block builds the sequence's next mask row (dense row copy, delta lists, leftover walks)
+// and stores it.  The sequence's inputs are loaded once, no kernel boundary separates the two
+// halves, and the long walks of a few sequences overlap the mask building of all others.
+constexpr int kAfBlock = 256;
+__global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
+    DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
+    int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
+    uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+    size_t walk_spill_stride) {
+    extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4
+    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
+    __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
+    __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
+    __shared__ RowPlan plan;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int b = blockIdx.x;
+    const int n_vec = (T.n_words + 3) >> 2;
+    int32_t *row = data + (size_t)b * cap;
+
+    if (tid >= 64) {
+        // The waves that wait for the walk pull the small tables it reads into this XCD's L2 (a
+        // streaming kernel that ran in between has evicted them): one 128-byte line per lane,
+        // the lines dealt out over the blocks of the XCD (blocks go round-robin to the 8 XCDs).
+        const int per_xcd = (gridDim.x + 7) >> 3, idle = kAfBlock - 64;
+        int acc = 0;
+        for (int off = ((blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
+            acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
+        if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
+    }
+    if (tid < 64) {
+        PrivateStack priv;
+        priv.lds = s_adv_stack;
+        priv.lds_stride = 1;
+        priv.spill = adv_scratch + b;
+        priv.spill_stride = (size_t)batch;
+        const int t = tokens[b];
+        const int n = len[b];
+        const int st = states[b];
+        const bool shape_ok = n >= 1 && n <= cap;
+        const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
+        int lo = 0, hi = 0;
+        s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
+        if (live && t != T.eos_id) {
+            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
+            const int n_bytes = rec[0];
+            if (n_bytes >= 0) {
+                hi = n_bytes;
+                if (lane < n_bytes) s_info[lane] = rec[1 + lane];
+            } else {
+                lo = T.voffsets[t];
+                hi = T.voffsets[t + 1];
+                if (lo + lane < hi) s_info[lane] = T.byte_info[T.vbytes[lo + lane]];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- advance (all lanes hold identical values)
+        int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
+        bool restarted = false;
+        if (t >= 0) {
+            int top = live ? __builtin_amdgcn_readfirstlane(s_win[0]) : -1;
+            if (!live || (unsigned)top >= (unsigned)T.n_states) {
+                out_err = 1;
+            } else {
+                const StackView view{row, s_win, n};
+                int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
+                if (t == T.eos_id) {
+                    if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
+                        out_state = -1;
+                        if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
+                    } else {
+                        out_err = 1;
+                    }
+                    base = n;
+                    d = 0;                               // the '$' walk never changes the stack
+                } else {
+                    int rc = hi > lo ? kFed : kRejected;
+                    for (int i = 0; i < hi - lo && rc == kFed; ++i) {
+                        const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[lo + i]]);
+                        int run_node = -1;
+                        rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+                        if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
+                            i += apply_run<true>(T, priv, s_info, i + 1, hi - lo, run_node, kind, base, d, top, cap);
+                    }
+                    if (rc != kFed) {
+                        out_err = rc == kOverflow ? 2 : 1;
+                        base = n;
+                        d = 0;
+                    } else {
+                        out_len = base + d;
+                        out_state = top;
+                    }
+                }
+            }
+        }
+        if (lane == 0) {
+            err[b] = out_err;
+            if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
+        }
+        // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart):
+        //      stage its top in LDS and commit the private part
+        const int nl = out_len;
+        auto new_at = [&](int k) -> int32_t {           // entry k below the new top
+            if (restarted) return k == 0 ? row[0] : -1;
+            if (k < d) return priv.get(d - 1 - k);
+            const int idx = base - 1 - (k - d);
+            return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
+        };
+        s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
+        {
+            const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+            if (lane < in_lds) row[base + lane] = priv.get(lane);
+            if (lane == 0)
+                for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // ---- descent of the condition tree with the new stack
+        const int top = s_new[0];
+        if (out_state < 0) {
+            if (lane == 0) plan.mode = kRowDone;
+        } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
+            if (lane == 0) plan.mode = kRowEmpty;
+        } else {
+            plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+        }
+        if (lane == 0) { plan.top = top; plan.len = nl; }
+    }
+    __syncthreads();
+    // ---- the next mask row
+    const int mode = plan.mode;
+    if (mode == kRowFast && plan.dense >= 0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec;
+        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = src[w];
+    } else {
+        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    if (mode == kRowFast || mode == kRowWalkAll) {
+        if (mode == kRowFast) {
+            const int nseg = plan.nseg;
+            for (int i = 0; i < nseg; ++i) {
+                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
+                const int cnt = plan.seg_count[i];
+                for (int k = tid; k < cnt; k += kAfBlock) {
+                    const int t = ids[k];
+                    atomicOr(&bits[t >> 5], 1u << (t & 31));
+                }
+            }
+        }
+        const int wc = mode == kRowWalkAll ? T.n_tokens : plan.walk_count;
+        if (wc > 0 && tid < 64) {                       // leftovers: walked on the committed stack
+            PrivateStack wp;
+            wp.lds = s_walk_stack + lane;
+            wp.lds_stride = 64;
+            wp.spill = walk_spill + (size_t)b * 64 + lane;
+            wp.spill_stride = walk_spill_stride;
+            const int n = plan.len, top0 = plan.top;
+            for (int k = lane; k < wc; k += 64) {
+                const int t = mode == kRowWalkAll ? k : E.walk_ids[plan.walk_begin + k];
+                if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+            }
+        }
+    } else if (mode == kRowDone && tid == 0) {
+        bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
+    }
+    __syncthreads();
+    uint32_t *dst = bitmask + (size_t)b * T.n_words;
+    if ((T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0) {
+        uint4 *dst4 = reinterpret_cast<uint4 *>(dst);
+        for (int w = tid; w < n_vec; w += kAfBlock) dst4[w] = bits4[w];
+    } else {
+        for (int w = tid; w < T.n_words; w += kAfBlock) dst[w] = bits[w];
+    }
+}
+
+}  // namespace
+
+size_t advance_scratch_entries(int batch, int max_depth) {
+    const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
+    return (size_t)batch * (size_t)deep;
+}
+
+size_t advance_fill_walk_spill_entries(int batch, int max_depth) {
+    const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;
+    return (size_t)batch * 64 * (size_t)deep;
+}
+
+hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
+                               int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
+                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    const size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    hipLaunchKernelGGL(advance_fill_kernel, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data, len, cap,
+                       batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64);
+    return hipGetLastError();
+}
+
+hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
+                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(advance_kernel, dim3((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), dim3(64 * kAdvSeqPerBlock),
+                       0, stream, T, tokens, states, data, len, cap, batch, err, scratch, restart_on_eos);
+    return hipGetLastError();
+}
+
+}  // namespace pre3

@@ -1,4 +1,5 @@
-// Host-callable launchers of the kernels (defined in kernels.hip).
+// Host-callable launchers of the kernels (defined in mask_kernels.hip, logits_kernels.hip and
+// advance_kernels.hip) and the sizes of the scratch areas they need.
 #pragma once
 #include <hip/hip_runtime_api.h>
 
