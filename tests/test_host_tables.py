@@ -160,3 +160,19 @@ def test_merged_reduction_edges_equal_oracle_advance(texts, prefixes, vocab):
                         assert got[1] == want[1], (prefix, tok, cap, merged)
                         n_ok += 1
     assert n_ok > 30
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, vocab):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "paper_2506_03887_amd", "no_such_libpre3.so"))
+    with pytest.raises(ImportError):
+        Pre3([G.ARITHMETIC], vocab.bytes, vocab.offsets, vocab.eos_id, host_only=True)
+
+
+def test_device_calls_refuse_a_host_only_handle(vocab):
+    p = host_compile([G.ARITHMETIC], vocab)
+    lib = binding.load()
+    null = ctypes.c_void_p(0)
+    assert lib.pre3_advance(p._h, null, null) == binding.E_BADARG
+    assert lib.pre3_advance_fill_mask(p._h, null, null, 0, null) == binding.E_BADARG
+    assert lib.pre3_apply_mask_argmax(p._h, null, 0, null, null, null) == binding.E_BADARG
