@@ -290,7 +290,9 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
         // every input symbol adds at most height_per_byte - 1 private entries (see tables.cpp)
         h->max_depth = std::max(1, h->V.max_len) * (h->T.height_per_byte - 1) + 1;
         if (!(opt && (opt->flags & PRE3_FLAG_STEPWISE_REDUCTIONS))) h->S = build_symbol_edges(h->T);
-        if (!(opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EDGES))) {
+        // token-level edges serve the kernels that keep a whole mask row in LDS: a vocabulary
+        // beyond that size keeps the byte-by-byte path and needs no such tables
+        if (!(opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EDGES)) && (size_t)h->V.n_words <= edge_kernel_max_lds_words()) {
             TokenEdgeLimits lim;
             if (opt && opt->max_condition_depth > 0) lim.max_known = opt->max_condition_depth;
             lim.n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));

@@ -260,3 +260,43 @@ def test_hip_graph_replays_match_eager():
         for got, want in zip((mask, logits, states, length, data), ref[s]):
             assert torch.equal(got, want), f"replay {s} differs from the eager step"
     assert int(err.abs().sum()) == 0
+
+
+def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
+    """A mask row of more than 56 KiB does not fit the token-edge kernels' LDS bitmap: every call
+    must then give the same results through the byte-by-byte kernel."""
+    torch, dev = _torch()
+    rng = np.random.default_rng(BASE_SEED + 91)
+    V = 14336 * 32 + 2000 + 5                                  # beyond the bitmap, ragged tail
+    alphabet = np.frombuffer(b"a+*()b- ", dtype=np.uint8)
+    lens = rng.integers(1, 5, size=V - 1)
+    flat = alphabet[rng.integers(0, len(alphabet), size=int(lens.sum()))].tobytes()
+    offs = np.concatenate([[0], np.cumsum(lens)])
+    toks = [flat[offs[i]: offs[i + 1]] for i in range(V - 1)] + [b""]
+    v = Vocab(toks, V - 1)
+    o = Oracle(G.ARITHMETIC)
+    lib = _lib(G.ARITHMETIC, v, stack_cap=64)
+    assert lib.token_edge_stats()["built"] == 0               # no token-level edges for such a vocabulary
+    prefixes = [b"", b"(a+", b"a*(a", b"((a)"]
+    states, data, length = _stacks(o, prefixes, 64)
+    B, W = len(prefixes), v.words
+    want = o.fill_mask(states, data, length, v)
+    assert (_gpu_mask(lib, states, data, length, W) == want).all()
+    # fused mask + apply, then advance + next mask, all through the fallback
+    logits = bf16_logits(rng, B, V)
+    lg = torch.from_numpy(logits.view(np.int16)).to(dev)
+    st, da, ln = torch.from_numpy(states).to(dev), torch.from_numpy(data).to(dev), torch.from_numpy(length).to(dev)
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    m = torch.zeros((B, W), dtype=torch.int32, device=dev)
+    lib.fill_apply_mask(st, da, ln, m, lg.view(torch.bfloat16))
+    expect = logits.copy()
+    oracle_apply_mask(expect, want, V)
+    assert (m.cpu().numpy().view(np.uint32) == want).all()
+    assert (lg.cpu().numpy().view(np.uint16) == expect).all()
+    lib.bind_state(st, da, ln, err)
+    picks = np.array([int(np.flatnonzero(((want[b][np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1))[7])
+                      for b in range(B)], dtype=np.int32)
+    e_h = o.advance_batch(states, data, length, picks, v)
+    lib.advance_fill_mask(torch.from_numpy(picks).to(dev), m)
+    assert (err.cpu().numpy() == e_h).all() and (st.cpu().numpy() == states).all() and (ln.cpu().numpy() == length).all()
+    assert (m.cpu().numpy().view(np.uint32) == o.fill_mask(states, data, length, v)).all()
