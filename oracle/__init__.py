@@ -71,6 +71,10 @@ def _load():
     lib.pre3o_apply_mask.argtypes = [vp, vp, i32, i32, i64]
     lib.pre3o_masked_argmax.restype = None
     lib.pre3o_masked_argmax.argtypes = [vp, vp, i32, i32, i64, vp]
+    lib.pre3o_jump_forward.restype = i32
+    lib.pre3o_jump_forward.argtypes = [vp, vp, vp, i32, i32, vp]
+    lib.pre3o_jump_forward_batch.restype = None
+    lib.pre3o_jump_forward_batch.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
     lib.pre3o_advance_batch.restype = None
     lib.pre3o_advance_batch.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp]
     _lib = lib
@@ -166,6 +170,27 @@ class Oracle:
         buf = np.frombuffer(bytes(data) + b"\0", dtype=np.uint8)
         rc = self._lib.pre3o_advance(self._h, _ptr(st), _ptr(ln), cap, _ptr(buf), len(data))
         return rc, st[: ln[0]].tolist()
+
+    def jump_forward(self, stack, max_bytes: int = 64, cap: int = 1 << 20):
+        """(forced bytes, advanced stack): the bytes every continuation must start with."""
+        n = len(stack)
+        cap = int(min(cap, n + 8 * max_bytes + 64))
+        st = np.zeros(cap, dtype=np.int32)
+        st[:n] = stack
+        ln = np.array([n], dtype=np.int32)
+        out = np.zeros(max(1, max_bytes), dtype=np.uint8)
+        k = self._lib.pre3o_jump_forward(self._h, _ptr(st), _ptr(ln), cap, int(max_bytes), _ptr(out))
+        return out[:k].tobytes(), st[: ln[0]].tolist()
+
+    def jump_forward_batch(self, states, data, length, max_bytes: int):
+        """In place on states/data/length (as advance_batch); returns (bytes [B, max_bytes] u8, counts [B])."""
+        B, cap = data.shape
+        assert data.flags.c_contiguous and data.dtype == np.int32 and length.dtype == np.int32 and states.dtype == np.int32
+        out = np.zeros((B, max(1, max_bytes)), dtype=np.uint8)
+        cnt = np.zeros(B, dtype=np.int32)
+        self._lib.pre3o_jump_forward_batch(self._h, _ptr(states), _ptr(data), _ptr(length), cap, B, int(max_bytes),
+                                           _ptr(out), _ptr(cnt))
+        return out[:, :max_bytes], cnt
 
     def accepts(self, text: bytes, g=0) -> bool:
         """Is `text` a sentence of grammar g?"""

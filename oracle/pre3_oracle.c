@@ -861,6 +861,43 @@ void pre3o_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int ba
     }
 }
 
+/* Jump-forward (Sec. 3.3: runs of edges with a single successor can be merged into one jump):
+ * the bytes every continuation of the text must start with.  While the text is not a sentence
+ * (the end-of-sequence token is not allowed) and exactly ONE of the 256 bytes keeps it a viable
+ * prefix, that byte is forced: it is appended to out[] and the stack is advanced by it.  Stops
+ * at the first position with no or several viable bytes, where EOS is allowed, after max_bytes
+ * bytes, or before a byte whose walk would exceed cap.  Returns the number of forced bytes;
+ * stack / *len hold the advanced stack. */
+int pre3o_jump_forward(const oracle_t *O, int32_t *stack, int32_t *len, int cap, int max_bytes, uint8_t *out) {
+    int n = 0;
+    while (n < max_bytes) {
+        if (pre3o_eos_allowed(O, stack, *len)) break;
+        int viable = 0, which = -1;
+        for (int c = 0; c < 256 && viable < 2; c++) {
+            uint8_t byte = (uint8_t)c;
+            if (pre3o_allowed(O, stack, *len, &byte, 1)) { viable++; which = c; }
+        }
+        if (viable != 1) break;
+        uint8_t byte = (uint8_t)which;
+        if (pre3o_advance(O, stack, len, cap, &byte, 1) != 0) break;
+        out[n++] = byte;
+    }
+    return n;
+}
+
+/* The same for a batch, mirroring the device call: finished sequences (states[b] < 0) get no
+ * bytes; states[b] follows the top of the advanced stack. */
+void pre3o_jump_forward_batch(const oracle_t *O, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
+                              int max_bytes, uint8_t *out_bytes, int32_t *out_len) {
+    for (int b = 0; b < batch; b++) {
+        out_len[b] = 0;
+        if (states[b] < 0) continue;
+        int32_t *stack = data + (size_t)b * cap;
+        out_len[b] = pre3o_jump_forward(O, stack, &len[b], cap, max_bytes, out_bytes + (size_t)b * max_bytes);
+        states[b] = stack[len[b] - 1];
+    }
+}
+
 /* Batched advance mirroring the device call: tokens[b] < 0 skips the sequence;
  * the end-of-sequence token marks it finished (states[b] = -1, stack untouched);
  * err[b] = 1 for a token that is not allowed (also any token on a finished

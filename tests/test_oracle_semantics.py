@@ -369,3 +369,79 @@ def test_arithmetic_workload_vocab_has_the_terminals():
     v = arithmetic_vocab(BASE_SEED + 1)
     assert v.n_tokens == 513 and v.eos_id == 512
     assert all(bytes([c]) in v.tokens for c in b"a+*()")
+
+
+@pytest.mark.parametrize("name,alphabet", [
+    ("ARITHMETIC", "a+*()b"), ("DYCK", "()x"), ("ANBN", "abx"), ("RIGHT_LIST", "x,y"),
+    ("EPSILON_MIX", "abcx"), ("RIGHT_LINEAR", "abcd"), ("DRAGON_CC", "cdx"),
+])
+def test_jump_forward_equals_brute_force(name, alphabet):
+    """Forced bytes from the LR-free sets of sentences and viable prefixes: while the text is not
+    a sentence and exactly one byte keeps it viable, that byte is forced."""
+    text = getattr(G, name)
+    o = Oracle(text)
+    sentences, viable = languages(text, N)
+    n_forced = 0
+    for p in sorted(viable):
+        if len(p) > 4:
+            continue
+        horizon = N - 1 - len(p)                 # every p.w.c looked up below has length <= N
+        w = ""
+        while len(w) < horizon and (p + w) not in sentences:
+            nxt = [c for c in alphabet if (p + w + c) in viable]
+            if len(nxt) != 1:
+                break
+            w += nxt[0]
+        rc, st = _stack_after(o, p)
+        got, new_stack = o.jump_forward(st, max_bytes=horizon)
+        assert got == w.encode(), (p, w, got)
+        assert new_stack == _stack_after(o, p + w)[1]
+        n_forced += len(w)
+    if name == "ANBN":                           # a^n b^k: the remaining b's are forced
+        assert n_forced >= 4
+
+
+def test_jump_forward_hand_cases_and_batch():
+    o = Oracle('S ::= "hello" | "help" A\nA ::= "!" | A "?"')
+    s0 = o.initial_stack()
+    assert o.jump_forward(s0)[0] == b"hel"
+    assert o.jump_forward(o.advance(s0, b"hell")[1])[0] == b"o"
+    assert o.jump_forward(o.advance(s0, b"help")[1])[0] == b"!"
+    assert o.jump_forward(o.advance(s0, b"help!")[1])[0] == b""          # a sentence: EOS is allowed, nothing is forced
+    assert o.jump_forward(s0, max_bytes=2)[0] == b"he"
+    j = Oracle(G.JSON)
+    j0 = j.initial_stack()
+    for prefix, forced in [(b"t", b"rue"), (b"[tru", b"e"), (b"n", b"ull"), (b"fa", b"lse"), (b'"', b""), (b"[", b""),
+                           (b'{"a"', b""), (b"[1,", b""), (b'"\\u12', b"")]:
+        assert j.jump_forward(j.advance(j0, prefix)[1])[0] == forced, prefix
+    # a schema grammar forces its key text
+    sch = G.schema_grammar(5, 3, 1, 2)
+    so = Oracle(sch.text)
+    forced, _ = so.jump_forward(so.advance(so.initial_stack(), b"{")[1])
+    assert forced == b"" or forced.startswith(b'"')
+    forced, _ = so.jump_forward(so.advance(so.initial_stack(), b'{"')[1])
+    assert len(forced) >= 3 and forced.endswith(b'"') or b'"' in forced
+    # batch form: same bytes, finished rows untouched, a tight cap stops before the overflowing byte
+    cap = 16
+    prefixes = [b"t", b"[tru", b'"', b"n"]
+    data = np.zeros((5, cap), dtype=np.int32)
+    length = np.ones(5, dtype=np.int32)
+    for b, p in enumerate(prefixes):
+        st = j.advance(j0, p)[1]
+        data[b, : len(st)], length[b] = st, len(st)
+    data[4, 0] = j0[0]
+    states = data[np.arange(5), length - 1].copy()
+    states[4] = -1
+    out, cnt = j.jump_forward_batch(states, data, length, 8)
+    assert [out[b, : cnt[b]].tobytes() for b in range(5)] == [b"rue", b"e", b"", b"ull", b""]
+    assert states[4] == -1 and length[4] == 1
+    for b, (p, f) in enumerate(zip(prefixes, [b"rue", b"e", b"", b"ull"])):
+        st = j.advance(j0, p + f)[1]
+        assert data[b, : length[b]].tolist() == st and states[b] == st[-1]
+    deep = j.advance(j0, b"[" * 10 + b"t")[1]
+    tight = np.zeros((1, len(deep) + 1), dtype=np.int32)
+    tight[0, : len(deep)] = deep
+    l1, s1 = np.array([len(deep)], dtype=np.int32), np.array([deep[-1]], dtype=np.int32)
+    out, cnt = j.jump_forward_batch(s1, tight, l1, 8)
+    full = j.jump_forward(deep, 8)[0]
+    assert full == b"rue" and out[0, : cnt[0]].tobytes() == full[: cnt[0]] and l1[0] <= tight.shape[1]
