@@ -415,12 +415,11 @@ def test_jump_forward_hand_cases_and_batch():
                            (b'{"a"', b""), (b"[1,", b""), (b'"\\u12', b"")]:
         assert j.jump_forward(j.advance(j0, prefix)[1])[0] == forced, prefix
     # a schema grammar forces its key text
-    sch = G.schema_grammar(5, 3, 1, 2)
+    sch = G.schema_grammar(11, 6, 2, 4)
     so = Oracle(sch.text)
-    forced, _ = so.jump_forward(so.advance(so.initial_stack(), b"{")[1])
-    assert forced == b"" or forced.startswith(b'"')
-    forced, _ = so.jump_forward(so.advance(so.initial_stack(), b'{"')[1])
-    assert len(forced) >= 3 and forced.endswith(b'"') or b'"' in forced
+    forced, st = so.jump_forward(so.advance(so.initial_stack(), b'{"')[1])
+    assert len(forced) >= 4 and b'"' in forced                       # the first key's text and its closing quote
+    assert so.advance(so.initial_stack(), b'{"' + forced)[1] == st
     # batch form: same bytes, finished rows untouched, a tight cap stops before the overflowing byte
     cap = 16
     prefixes = [b"t", b"[tru", b'"', b"n"]
