@@ -225,18 +225,59 @@ def main():
             best = min(best, e0.elapsed_time(e1))
         return best * 1e3 / K
 
+    _snaps = []
+
+    def recorded_stacks():
+        """(len/states, stack data) of the batch at each of the K timed steps of the trajectory."""
+        if not _snaps:
+            restore()
+            for s in range(K):
+                resets(Wm + s)
+                _snaps.append((ls_d.clone(), data_d.clone()))
+                lib.advance(tokens_d[Wm + s])
+            torch.cuda.synchronize()
+        return _snaps
+
+    def jump_forward_leg(n_calls=32, max_bytes=32):
+        """pre3_jump_forward on the recorded stacks of the first steps (on copies: it advances the
+        stacks), one call per step with a HIP event on either side; checked against the oracle."""
+        snaps = recorded_stacks()
+        n_calls = min(n_calls, K)
+        ls2, da2 = snaps[0][0].clone(), snaps[0][1].clone()
+        err2 = torch.zeros(B, dtype=torch.int32, device=dev)
+        out_b = torch.zeros((B, max_bytes), dtype=torch.uint8, device=dev)
+        out_n = torch.zeros(B, dtype=torch.int32, device=dev)
+        lib.bind_state(ls2[1], da2, ls2[0], err2)
+        times, forced = [], 0
+        for s in range(n_calls):
+            ls2.copy_(snaps[s][0]); da2.copy_(snaps[s][1])
+            if s == 0:                                            # check one call against the oracle
+                l_h, s_h = (x.copy() for x in ls2.cpu().numpy())
+                d_h = da2.cpu().numpy().copy()
+                wb, wn = o.jump_forward_batch(s_h, d_h, l_h, max_bytes)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lib.jump_forward(out_b, out_n)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3)
+            forced += int(out_n.sum().item())
+            if s == 0:
+                assert (out_n.cpu().numpy() == wn).all() and (ls2[0].cpu().numpy() == l_h).all(), "jump_forward differs from the oracle"
+                gb = out_b.cpu().numpy()
+                assert all(gb[b, : wn[b]].tobytes() == wb[b, : wn[b]].tobytes() for b in range(B))
+        lib.bind_state(states_d, data_d, len_d, err_d)
+        return {"us_per_call": float(np.mean(times[1:])), "calls": n_calls - 1, "max_bytes": max_bytes,
+                "forced_bytes_per_call": forced / n_calls,
+                "timing": "one eager call per recorded step between two HIP events (the bracket adds a few us)"}
+
     def mask_apply_graph_us():
         """fill_mask + apply_mask alone, K steps in one graph: the stacks of the K timed steps are
         recorded first (fill_mask reads a snapshot, the bound buffers stay untouched), so every
         step computes a different batch of rows, as in the real loop, but no advance or reset
         kernel and no event bracket sits between the two calls that are timed."""
-        restore()
-        snaps = []
-        for s in range(K):
-            resets(Wm + s)
-            snaps.append((ls_d.clone(), data_d.clone()))
-            lib.advance(tokens_d[Wm + s])
-        torch.cuda.synchronize()
+        snaps = recorded_stacks()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for s in range(K):
@@ -424,6 +465,7 @@ def main():
                                    f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",
                          "us_per_step": cpu_t / n_cpu * 1e6},
         "greedy": greedy,
+        "jump_forward": None if args.eager else jump_forward_leg(),
         "compile_s": t_compile,
         "token_edges": lib.token_edge_stats(),
     }

@@ -199,6 +199,20 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
                            int32_t *out_tokens, pre3_stream stream);
 
+/* Jump-forward (Sec. 3.3: runs of edges with a single successor merge into one jump): for every
+ * bound, unfinished sequence, the bytes that every continuation of its text must start with.
+ * While the end-of-sequence token is not allowed and exactly one of the 256 bytes keeps the text
+ * a viable prefix, that byte is forced: it is stored in out_bytes[b * max_bytes + i] and the
+ * sequence's stack is advanced by it (states, len and the stack entries change as under
+ * pre3_advance; err is not touched).  A sequence stops at the first position with no or several
+ * viable bytes, where EOS is allowed, after max_bytes bytes, or before a byte whose walk would
+ * grow the stack beyond cap.  out_len[b] = number of forced bytes (0 for a finished sequence).
+ * A server appends the bytes to the output (re-tokenising them as it likes) without running the
+ * model, then asks for the next mask.  out_bytes: device [batch, max_bytes] (may be null when
+ * max_bytes is 0); out_len: device [batch].  Errors: BADARG (nothing bound, null pointer,
+ * negative max_bytes). */
+int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int32_t max_bytes, pre3_stream stream);
+
 /* ---- host-side introspection of the compiled tables (used by tests and tools) ---- */
 
 int32_t pre3_n_grammars(const pre3_handle *h);

@@ -24,7 +24,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance",
 ]
@@ -78,6 +78,7 @@ def load():
     lib.pre3_advance.argtypes = [vp, vp, vp]
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
+    lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
         getattr(lib, name).argtypes = [vp]
     lib.pre3_byte_class.argtypes = [vp, i32]
@@ -104,7 +105,8 @@ def _stream_ptr(stream):
 def _dev(t, dtype_name):
     """Device pointer of a contiguous torch tensor of the expected dtype."""
     import torch
-    want = {"i32": torch.int32, "u16": (torch.bfloat16, torch.uint16, torch.int16), "u32": (torch.int32, torch.uint32)}[dtype_name]
+    want = {"i32": torch.int32, "u16": (torch.bfloat16, torch.uint16, torch.int16), "u32": (torch.int32, torch.uint32),
+            "u8": torch.uint8}[dtype_name]
     ok = t.dtype in want if isinstance(want, tuple) else t.dtype == want
     if not (t.is_cuda and ok):
         raise TypeError(f"expected a CUDA tensor of kind {dtype_name}, got {t.dtype} on {t.device}")
@@ -254,6 +256,14 @@ class Pre3:
         assert bitmask.shape[1] == self.words and out_tokens.numel() == logits.shape[0] == bitmask.shape[0]
         self._check(self._lib.pre3_apply_mask_argmax(self._h, _dev(logits, "u16"), logits.stride(0), _dev(bitmask, "u32"),
                                                      _dev(out_tokens, "i32"), _stream_ptr(stream)))
+
+    def jump_forward(self, out_bytes, out_len, stream=None):
+        """Forced bytes of every bound sequence into out_bytes [B, max_bytes] (uint8), their counts into
+        out_len [B]; the stacks are advanced by them."""
+        assert out_bytes.dim() == 2 and out_bytes.is_contiguous() and out_len.is_contiguous()
+        assert out_bytes.shape[0] == out_len.numel()
+        self._check(self._lib.pre3_jump_forward(self._h, _dev(out_bytes, "u8"), _dev(out_len, "i32"), out_bytes.shape[1],
+                                                _stream_ptr(stream)))
 
 
 def apply_mask(logits, bitmask, vocab: int, stream=None):

@@ -290,6 +290,104 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     }
 }
 
+// Jump-forward: while a sequence's text is not a sentence and exactly one byte keeps it a viable
+// prefix, that byte is forced; it is emitted and the stack is advanced by it.  One wave per
+// sequence.  At every position lane c tries byte class c (and one lane the end-of-input symbol)
+// from the current stack on a private overlay of its own -- the walk of a one-byte token --, the
+// wave adds up the BYTES of the viable classes, and if that is one (and '$' is not accepted) the
+// forced byte is walked on the real stack by all lanes together, exactly like in advance_kernel.
+constexpr int kJfSeqPerBlock = 4;
+__global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
+    DevTables T, int32_t *__restrict__ states, int32_t *__restrict__ data, int32_t *__restrict__ len, int cap,
+    int batch, uint8_t *__restrict__ out_bytes, int32_t *__restrict__ out_len, int max_bytes, int32_t *adv_scratch,
+    int32_t *lane_spill, size_t lane_spill_stride) {
+    __shared__ int32_t s_trial[kJfSeqPerBlock][kLdsDepth * 64];
+    __shared__ int32_t s_adv[kJfSeqPerBlock][kLdsDepth];
+    __shared__ int32_t s_win[kJfSeqPerBlock][kWindow], s_new[kJfSeqPerBlock][kWindow];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * kJfSeqPerBlock + wave;
+    if (b >= batch) return;
+    int32_t *row = data + (size_t)b * cap;
+    int n = len[b];
+    const int st = states[b];
+    int count = 0;
+    if (st >= 0 && n >= 1 && n <= cap && max_bytes > 0) {
+        s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
+        __builtin_amdgcn_wave_barrier();
+        int top = __builtin_amdgcn_readfirstlane(s_win[wave][0]);
+        if ((unsigned)top < (unsigned)T.n_states) {
+            int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
+            PrivateStack trial;                        // one column per lane
+            trial.lds = s_trial[wave] + lane;
+            trial.lds_stride = 64;
+            trial.spill = lane_spill + (size_t)b * 64 + lane;
+            trial.spill_stride = lane_spill_stride;
+            PrivateStack adv;                          // the wave's own walk of a forced byte
+            adv.lds = s_adv[wave];
+            adv.lds_stride = 1;
+            adv.spill = adv_scratch + b;
+            adv.spill_stride = (size_t)batch;
+            int new_top = top;
+            while (count < max_bytes) {
+                const StackView view{row, s_win[wave], n};
+                int viable_bytes = 0, only = -1;
+                bool at_end = false;
+                for (int c0 = 0; c0 < T.ncol; c0 += 64) {
+                    const int c = c0 + lane;
+                    int res = kRejected;
+                    if (c < T.ncol) {
+                        int base = n, d = 0, tp = top, tr = kind;
+                        res = feed<false, false>(T, trial, c, base, d, tp, tr, view, 0);
+                    }
+                    if (__ballot(c == T.end_col && res == kAccepted)) at_end = true;
+                    int bytes_here = (c < T.end_col && res == kFed) ? (T.class_info[c] & 0xFFFF) : 0;
+                    const unsigned long long m = __ballot(bytes_here > 0);
+                    if (m) only = c0 + __ffsll((long long)m) - 1;
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) bytes_here += __shfl_xor(bytes_here, off);
+                    viable_bytes += bytes_here;
+                }
+                if (at_end || viable_bytes != 1) break;
+                const int byte = __builtin_amdgcn_readfirstlane(T.class_info[only] >> 16);
+                const int info = __builtin_amdgcn_readfirstlane(T.byte_info[byte]);
+                int base = n, d = 0;
+                new_top = top;
+                int new_kind = kind;
+                if (feed<true, true>(T, adv, info, base, d, new_top, new_kind, view, cap) != kFed) break;   // would exceed cap
+                // commit: stage the new top of the stack, then write the pushed entries
+                int entry = -1;
+                if (lane < base + d) {
+                    if (lane < d) {
+                        entry = adv.get(d - 1 - lane);
+                    } else {
+                        const int idx = base - 1 - (lane - d);
+                        entry = idx >= 0 ? view.at(idx) : -1;
+                    }
+                }
+                s_new[wave][lane] = entry;
+                const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+                if (lane < in_lds) row[base + lane] = adv.get(lane);
+                if (lane == 0) {
+                    for (int i = kLdsDepth; i < d; ++i) row[base + i] = adv.get(i);
+                    out_bytes[(size_t)b * max_bytes + count] = (uint8_t)byte;
+                }
+                __builtin_amdgcn_wave_barrier();
+                s_win[wave][lane] = s_new[wave][lane];
+                __builtin_amdgcn_wave_barrier();
+                n = base + d;
+                top = new_top;
+                kind = new_kind;
+                ++count;
+            }
+            if (lane == 0 && count > 0) {
+                len[b] = n;
+                states[b] = top;
+            }
+        }
+    }
+    if (lane == 0) out_len[b] = count;
+}
+
 }  // namespace
 
 size_t advance_scratch_entries(int batch, int max_depth) {
@@ -317,6 +415,16 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
     if (batch == 0) return hipSuccess;
     hipLaunchKernelGGL(advance_kernel, dim3((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), dim3(64 * kAdvSeqPerBlock),
                        0, stream, T, tokens, states, data, len, cap, batch, err, scratch, restart_on_eos);
+    return hipGetLastError();
+}
+
+hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
+                               uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
+                               int32_t *lane_spill, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(jump_forward_kernel, dim3((batch + kJfSeqPerBlock - 1) / kJfSeqPerBlock), dim3(64 * kJfSeqPerBlock),
+                       0, stream, T, states, data, len, cap, batch, out_bytes, out_len, max_bytes, adv_scratch, lane_spill,
+                       (size_t)batch * 64);
     return hipGetLastError();
 }
 

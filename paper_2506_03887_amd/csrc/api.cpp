@@ -119,6 +119,14 @@ int upload_tables(pre3_handle *h) {
     // first the tables a walk of one token touches, so that they form one contiguous region
     PRE3_UP(byte_info, byte_info);
     const size_t chunks_before = h->allocations.size();
+    {
+        std::vector<int32_t> class_info(h->T.n_classes + 1, 0);
+        for (int b = 255; b >= 0; --b) {
+            int32_t &ci = class_info[h->T.byte_class[b]];
+            ci = ((ci & 0xFFFF) + 1) | (b << 16);
+        }
+        PRE3_UP(class_info, class_info);
+    }
     D.sym_nodes = nullptr; D.sym_pairs = nullptr; D.sym_cell = nullptr; D.sym_pool = nullptr; D.state_kind = nullptr;
     if (h->S.enabled) {
         std::vector<int4> sn(h->S.nodes.size());
@@ -351,7 +359,7 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
         h->argmax_best = static_cast<unsigned long long *>(p);
         h->argmax_bytes = need_arg;
     }
-    if (h->use_edges) {
+    {   // private stacks of per-lane walks beside an advance (leftover tokens, jump-forward trials)
         size_t need2 = advance_fill_walk_spill_entries(stacks.batch, h->max_depth);
         if (need2 > h->af_walk_spill_entries) {
             void *p = nullptr;
@@ -456,6 +464,18 @@ int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t 
                                         h->n_compute_units, h->argmax_best, out_tokens,
                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask_argmax");
+}
+
+int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int32_t max_bytes, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "jump_forward: no state bound");
+    if (!out_len || max_bytes < 0 || (max_bytes > 0 && !out_bytes))
+        return fail(h, PRE3_E_BADARG, "jump_forward: null pointer or negative max_bytes");
+    hipError_t e = launch_jump_forward(h->dev, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
+                                       h->b_stacks.batch, out_bytes, out_len, max_bytes, h->adv_scratch,
+                                       h->af_walk_spill, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch jump_forward");
 }
 
 int32_t pre3_n_grammars(const pre3_handle *h) { return h && h->compiled ? h->T.n_grammars : PRE3_E_BADARG; }

@@ -28,6 +28,7 @@ struct DevTables {
     const int4 *sym_cell;
     const int32_t *sym_pool;       // effect records, 16-byte aligned
     const int32_t *state_kind;     // [n_states] root node of each state's condition tree
+    const int32_t *class_info;     // [ncol] bytes in the class | (smallest byte of the class << 16)
     // vocabulary, chunk-sorted order
     const uint8_t *tok_len;        // [n_padded]
     const uint16_t *tok_bit;       // [n_padded]

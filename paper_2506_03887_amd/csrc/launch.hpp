@@ -36,5 +36,8 @@ size_t advance_fill_walk_spill_entries(int batch, int max_depth);   // int32 ent
 hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
                                int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill, hipStream_t stream);
+hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
+                               uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
+                               int32_t *lane_spill, hipStream_t stream);
 
 }  // namespace pre3
