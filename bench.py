@@ -280,6 +280,31 @@ def main():
                 "forced_bytes_per_call": forced / n_calls,
                 "timing": "one eager call per recorded step between two HIP events (the bracket adds a few us)"}
 
+    def byte_by_byte_leg(n_calls=6):
+        """The same masks without token-level edges: every (sequence, token) pair walked byte by byte
+        (the path the token-level edges replace), on the recorded stacks of the first steps."""
+        snaps = recorded_stacks()
+        plain = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
+                     token_edges=False)
+        m2 = torch.empty_like(mask_d)
+        times = []
+        for s in range(min(n_calls, K)):
+            ls, da = snaps[s]
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            plain.fill_mask(ls[1], da, ls[0], m2)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3)
+            if s == 0:
+                lib.fill_mask(ls[1], da, ls[0], mask_d)
+                assert torch.equal(m2, mask_d), "byte-by-byte mask differs from the token-edge mask"
+        t = float(np.mean(times[1:])) if len(times) > 1 else float(times[0])
+        return {"us_per_launch": t, "tokens_per_s": pairs_ / (t * 1e-6),
+                "vocab_bytes_times_batch_per_s": float(B) * float(v.offsets[-1]) / (t * 1e-6),
+                "note": "fill_mask_walk_kernel; a walk stops at its first rejected byte, so the byte rate is an upper bound on byte steps"}
+
     def mask_apply_graph_us():
         """fill_mask + apply_mask alone, K steps in one graph: the stacks of the K timed steps are
         recorded first (fill_mask reads a snapshot, the bound buffers stay untouched), so every
@@ -474,6 +499,7 @@ def main():
                          "us_per_step": cpu_t / n_cpu * 1e6},
         "greedy": greedy,
         "jump_forward": None if args.eager else jump_forward_leg(),
+        "fill_mask_byte_by_byte": None if (args.eager or args.no_token_edges) else byte_by_byte_leg(),
         "compile_s": t_compile,
         "token_edges": lib.token_edge_stats(),
     }
