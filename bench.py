@@ -49,7 +49,7 @@ def main():
                          "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this path runs on one GPU (sequences are independent; see DESIGN.md on sharding); use --gpus 1")
+        sys.exit("bench.py: this path runs on one GPU (sequences are independent: shard the batch across processes, one handle each); use --gpus 1")
 
     import numpy as np
     import torch
