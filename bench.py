@@ -58,10 +58,18 @@ def main():
         n = args.calibrate_copy << 20
         src = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(20):
             dst.copy_(src)
+        e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
+        us = e0.elapsed_time(e1) * 1e3 / 20
+        # buffers beyond the 256 MB Infinity Cache give the chip's practical read+write HBM rate
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 21,
+                          "us_per_copy": us, "read_plus_write_GBs": 2.0 * n / (us * 1e-6) / 1e9}))
         return
 
     from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax
