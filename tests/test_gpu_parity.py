@@ -69,3 +69,70 @@ def test_advance_fill_mask_all_configs():
     assert replay_advance_fill(3, steps=96, full_mask_steps=[0, 40, 95])["full_masks"] == 3
     assert replay_advance_fill(4, steps=64, full_mask_steps=[0, 63])["full_masks"] == 2
     assert replay_advance_fill(5, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
+    """Sequences of config 2 fed, per step and sequence, one of: an allowed token, an arbitrary
+    token (mostly not allowed), EOS (allowed or not), or no token; finished sequences keep
+    receiving tokens.  err, states, stacks and the next masks must follow the oracle exactly."""
+    import torch
+    from oracle import Oracle
+    from paper_2506_03887_amd import Pre3
+    from workloads import configs
+    dev = torch.device("cuda:0")
+    cfg = configs.get(2)
+    v = cfg.vocab
+    B, V, W, cap = cfg.batch, v.n_tokens, v.words, 20            # a small capacity: overflows do happen
+    o = Oracle(cfg.grammars)
+    s0 = o.initial_state(0)
+    data = np.zeros((B, cap), dtype=np.int32)
+    data[:, 0] = s0
+    length = np.ones(B, dtype=np.int32)
+    states = np.full(B, s0, dtype=np.int32)
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=cap)
+    st, da, ln = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    mask = torch.empty((B, W), dtype=torch.int32, device=dev)
+    lib.bind_state(st, da, ln, err)
+    lib.fill_mask(st, da, ln, mask)
+    rng = np.random.default_rng(cfg.seed + 31)
+    seen = {0: 0, 1: 0, 2: 0}
+    opening = [t for t in range(V - 1) if v.tokens[t] and set(v.tokens[t]) <= set(b"[{")]
+    for step in range(80):
+        m_h = o.fill_mask(states, data, length, v)
+        assert (mask.cpu().numpy().view(np.uint32) == m_h).all(), step
+        toks = np.full(B, -1, dtype=np.int32)
+        kind = rng.random(B)
+        for b in range(B):
+            if kind[b] < 0.55 and states[b] >= 0:
+                allowed = np.flatnonzero((m_h[b][np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1)
+                deepen = [t for t in opening if (m_h[b][t >> 5] >> (t & 31)) & 1]
+                toks[b] = rng.choice(deepen) if deepen and rng.random() < 0.7 else rng.choice(allowed)
+            elif kind[b] < 0.75:
+                toks[b] = rng.integers(0, V)
+            elif kind[b] < 0.85:
+                toks[b] = v.eos_id
+            elif kind[b] < 0.88:
+                toks[b] = V + int(rng.integers(0, 5))            # an id beyond the vocabulary
+        e_h = o.advance_batch(states, data, length, toks, v)
+        for code in (0, 1, 2):
+            seen[code] += int((e_h == code).sum())
+        t_d = torch.from_numpy(toks).to(dev)
+        if fused:
+            lib.advance_fill_mask(t_d, mask)
+        else:
+            lib.advance(t_d)
+            lib.fill_mask(st, da, ln, mask)
+        assert (err.cpu().numpy() == e_h).all(), step
+        assert (st.cpu().numpy() == states).all() and (ln.cpu().numpy() == length).all(), step
+        live = np.arange(cap)[None, :] < length[:, None]
+        assert (da.cpu().numpy()[live] == data[live]).all(), step
+        # a few finished sequences start over so that the stream stays lively
+        again = (states < 0) & (rng.random(B) < 0.3)
+        if again.any():
+            states[again], length[again] = s0, 1
+            st[torch.from_numpy(again).to(dev)] = s0
+            ln[torch.from_numpy(again).to(dev)] = 1
+            lib.fill_mask(st, da, ln, mask)
+    assert seen[0] > 1000 and seen[1] > 300 and seen[2] > 0, seen
