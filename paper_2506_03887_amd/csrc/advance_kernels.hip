@@ -11,11 +11,60 @@ namespace {
 
 // -------------------------------------------------------------------------- advance
 
+// The bytes of a sampled token as the walk needs them: hi - lo bytes; the class/offset word of
+// byte i < 64 is staged in LDS, later ones are read through the id-ordered vocabulary at lo + i.
+struct StagedToken {
+    int lo, hi;
+};
+
+// All 64 lanes of the wave call this with the same token id: lane i fetches byte i.
+__device__ __forceinline__ StagedToken stage_token(const DevTables &T, int t, int lane, int32_t *s_info) {
+    StagedToken tok{0, 0};
+    const int32_t *rec = T.tok_info + (size_t)t * 32;           // the token's line: length and byte infos
+    const int n_bytes = rec[0];
+    if (n_bytes >= 0) {
+        tok.hi = n_bytes;
+        if (lane < n_bytes) s_info[lane] = rec[1 + lane];
+    } else {
+        tok.lo = T.voffsets[t];
+        tok.hi = T.voffsets[t + 1];
+        if (tok.lo + lane < tok.hi) s_info[lane] = T.byte_info[T.vbytes[tok.lo + lane]];
+    }
+    return tok;
+}
+
+// Walks a staged token from the configuration  view ++ priv[0..d)  with capacity checks.  Runs on
+// all 64 lanes with identical values (scalar table loads, LDS broadcast reads); a run of
+// self-similar edges is applied in one step.  Returns kFed, kRejected or kOverflow.
+__device__ __forceinline__ int walk_staged_token(const DevTables &T, PrivateStack &priv, const int32_t *s_info,
+                                                 StagedToken tok, const StackView &view, int cap, int &base, int &d,
+                                                 int &top, int &kind) {
+    const int n_bytes = tok.hi - tok.lo;
+    int rc = n_bytes > 0 ? kFed : kRejected;
+    for (int i = 0; i < n_bytes && rc == kFed; ++i) {
+        const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[tok.lo + i]]);
+        int run_node = -1;
+        rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+        if (rc == kFed && run_node >= 0 && i + 1 < n_bytes)
+            i += apply_run<true>(T, priv, s_info, i + 1, n_bytes, run_node, kind, base, d, top, cap);
+    }
+    return rc;
+}
+
+// Writes the d private entries of a finished walk above row[0..base): the first kLdsDepth by one
+// lane each, entries that spilled to global memory by lane 0.
+__device__ __forceinline__ void commit_overlay(int32_t *row, const PrivateStack &priv, int base, int d, int lane) {
+    const int in_lds = d < kLdsDepth ? d : kLdsDepth;
+    if (lane < in_lds) row[base + lane] = priv.get(lane);
+    if (lane == 0)
+        for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
+}
+
 // One wave per sequence: the walk of a single token is a chain of dependent table look-ups, so
 // giving every sequence its own wave keeps control flow uniform (lanes of a shared wave would
 // serialise each other's reduction chains) and lets the chip overlap the chains of all
-// sequences.  Lane 0 walks the token on a private overlay exactly like in the mask kernels;
-// only a walk that succeeds is committed, by all lanes, to the sequence's stack.
+// sequences.  The walk runs on a private overlay exactly like in the mask kernels; only a walk
+// that succeeds is committed to the sequence's stack.
 constexpr int kAdvSeqPerBlock = 4;
 __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
@@ -33,30 +82,18 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     priv.spill = scratch + b;
     priv.spill_stride = (size_t)batch;
     // every lane: the sequence's inputs, then (in parallel across lanes) the top of the stack and
-    // the byte classes of the token, so that lane 0's walk finds them in LDS
+    // the byte classes of the token, so that the walk finds them in LDS
     const int t = tokens[b];
     const int n = len[b];
     const int st = states[b];
     const bool live = t >= 0 && t < T.n_tokens && st >= 0 && n >= 1 && n <= cap;
-    int lo = 0, hi = 0;
+    StagedToken tok{0, 0};
     if (live) {
         s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
-        if (t != T.eos_id) {
-            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
-            const int n_bytes = rec[0];
-            if (n_bytes >= 0) {
-                hi = n_bytes;
-                if (lane < n_bytes) s_info[wave][lane] = rec[1 + lane];
-            } else {
-                lo = T.voffsets[t];
-                hi = T.voffsets[t + 1];
-                if (lo + lane < hi) s_info[wave][lane] = T.byte_info[T.vbytes[lo + lane]];
-            }
-        }
+        if (t != T.eos_id) tok = stage_token(T, t, lane, s_info[wave]);
     }
     __builtin_amdgcn_wave_barrier();
-    // The walk itself runs on all 64 lanes with identical values (scalar table loads, LDS
-    // broadcast reads); lane 0 alone writes the results.
+    // all lanes hold identical values from here on; lane 0 alone writes the results
     int commit = -1, out_err = 0, out_state = st, out_len = n;
     if (t >= 0) {
         int top = live ? __builtin_amdgcn_readfirstlane(s_win[wave][0]) : -1;
@@ -74,14 +111,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
                     out_err = 1;
                 }
             } else {
-                int rc = hi > lo ? kFed : kRejected;
-                for (int i = 0; i < hi - lo && rc == kFed; ++i) {
-                    const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[wave][i] : T.byte_info[T.vbytes[lo + i]]);
-                    int run_node = -1;
-                    rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
-                    if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
-                        i += apply_run<true>(T, priv, s_info[wave], i + 1, hi - lo, run_node, kind, base, d, top, cap);
-                }
+                const int rc = walk_staged_token(T, priv, s_info[wave], tok, view, cap, base, d, top, kind);
                 if (rc != kFed) {
                     out_err = rc == kOverflow ? 2 : 1;
                 } else {
@@ -101,16 +131,8 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     }
     s_depth[wave] = commit;
     __builtin_amdgcn_wave_barrier();
-    // LDS operations of one wave complete in order; entries that spilled to global memory are
-    // copied by lane 0
     const int d = s_depth[wave];
-    if (d > 0) {
-        const int base = s_base[wave];
-        const int in_lds = d < kLdsDepth ? d : kLdsDepth;
-        if (lane < in_lds) row[base + lane] = priv.get(lane);
-        if (lane == 0)
-            for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
-    }
+    if (d > 0) commit_overlay(row, priv, s_base[wave], d, lane);
 }
 
 // Advance and next mask in one launch: one block per sequence.  Wave 0 walks the sampled token
@@ -156,20 +178,9 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         const int st = states[b];
         const bool shape_ok = n >= 1 && n <= cap;
         const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
-        int lo = 0, hi = 0;
+        StagedToken tok{0, 0};
         s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
-        if (live && t != T.eos_id) {
-            const int32_t *rec = T.tok_info + (size_t)t * 32;       // the token's line: length and byte infos
-            const int n_bytes = rec[0];
-            if (n_bytes >= 0) {
-                hi = n_bytes;
-                if (lane < n_bytes) s_info[lane] = rec[1 + lane];
-            } else {
-                lo = T.voffsets[t];
-                hi = T.voffsets[t + 1];
-                if (lo + lane < hi) s_info[lane] = T.byte_info[T.vbytes[lo + lane]];
-            }
-        }
+        if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
         __builtin_amdgcn_wave_barrier();
         // ---- advance (all lanes hold identical values)
         int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
@@ -191,14 +202,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                     base = n;
                     d = 0;                               // the '$' walk never changes the stack
                 } else {
-                    int rc = hi > lo ? kFed : kRejected;
-                    for (int i = 0; i < hi - lo && rc == kFed; ++i) {
-                        const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[lo + i]]);
-                        int run_node = -1;
-                        rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
-                        if (rc == kFed && run_node >= 0 && i + 1 < hi - lo)
-                            i += apply_run<true>(T, priv, s_info, i + 1, hi - lo, run_node, kind, base, d, top, cap);
-                    }
+                    const int rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
                     if (rc != kFed) {
                         out_err = rc == kOverflow ? 2 : 1;
                         base = n;
@@ -224,12 +228,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
             return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
         };
         s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
-        {
-            const int in_lds = d < kLdsDepth ? d : kLdsDepth;
-            if (lane < in_lds) row[base + lane] = priv.get(lane);
-            if (lane == 0)
-                for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
-        }
+        commit_overlay(row, priv, base, d, lane);
         __builtin_amdgcn_wave_barrier();
         // ---- descent of the condition tree with the new stack
         const int top = s_new[0];
@@ -365,12 +364,8 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
                     }
                 }
                 s_new[wave][lane] = entry;
-                const int in_lds = d < kLdsDepth ? d : kLdsDepth;
-                if (lane < in_lds) row[base + lane] = adv.get(lane);
-                if (lane == 0) {
-                    for (int i = kLdsDepth; i < d; ++i) row[base + i] = adv.get(i);
-                    out_bytes[(size_t)b * max_bytes + count] = (uint8_t)byte;
-                }
+                commit_overlay(row, adv, base, d, lane);
+                if (lane == 0) out_bytes[(size_t)b * max_bytes + count] = (uint8_t)byte;
                 __builtin_amdgcn_wave_barrier();
                 s_win[wave][lane] = s_new[wave][lane];
                 __builtin_amdgcn_wave_barrier();
