@@ -148,7 +148,6 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
     size_t walk_spill_stride) {
     extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4
-    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
     __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
     __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
     __shared__ RowPlan plan;
@@ -242,51 +241,14 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         if (lane == 0) { plan.top = top; plan.len = nl; }
     }
     __syncthreads();
-    // ---- the next mask row
-    const int mode = plan.mode;
-    if (mode == kRowFast && plan.dense >= 0) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec;
-        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = src[w];
-    } else {
-        for (int w = tid; w < n_vec; w += kAfBlock) bits4[w] = make_uint4(0, 0, 0, 0);
-    }
-    __syncthreads();
-    if (mode == kRowFast || mode == kRowWalkAll) {
-        if (mode == kRowFast) {
-            const int nseg = plan.nseg;
-            for (int i = 0; i < nseg; ++i) {
-                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
-                const int cnt = plan.seg_count[i];
-                for (int k = tid; k < cnt; k += kAfBlock) {
-                    const int t = ids[k];
-                    atomicOr(&bits[t >> 5], 1u << (t & 31));
-                }
-            }
-        }
-        const int wc = mode == kRowWalkAll ? T.n_tokens : plan.walk_count;
-        if (wc > 0 && tid < 64) {                       // leftovers: walked on the committed stack
-            PrivateStack wp;
-            wp.lds = s_walk_stack + lane;
-            wp.lds_stride = 64;
-            wp.spill = walk_spill + (size_t)b * 64 + lane;
-            wp.spill_stride = walk_spill_stride;
-            const int n = plan.len, top0 = plan.top;
-            for (int k = lane; k < wc; k += 64) {
-                const int t = mode == kRowWalkAll ? k : E.walk_ids[plan.walk_begin + k];
-                if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
-            }
-        }
-    } else if (mode == kRowDone && tid == 0) {
-        bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
-    }
-    __syncthreads();
-    uint32_t *dst = bitmask + (size_t)b * T.n_words;
-    if ((T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0) {
-        uint4 *dst4 = reinterpret_cast<uint4 *>(dst);
-        for (int w = tid; w < n_vec; w += kAfBlock) dst4[w] = bits4[w];
-    } else {
-        for (int w = tid; w < T.n_words; w += kAfBlock) dst[w] = bits[w];
-    }
+    // ---- the next mask row, by the whole block
+    PrivateStack wp;                                    // leftovers are walked on the committed stack
+    wp.lds = s_walk_stack + lane;
+    wp.lds_stride = 64;
+    wp.spill = walk_spill + (size_t)b * 64 + lane;
+    wp.spill_stride = walk_spill_stride;
+    const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
+    build_and_store_row<kAfBlock, true>(T, E, plan, bits4, 0, n_vec, row, wp, bitmask + (size_t)b * T.n_words, vector_ok, tid);
 }
 
 // Jump-forward: while a sequence's text is not a sentence and exactly one byte keeps it a viable

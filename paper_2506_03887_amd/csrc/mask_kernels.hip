@@ -130,55 +130,12 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
             if (tid == 0) { plan.top = top; plan.len = n; }
         }
         __syncthreads();
-        const int mode = plan.mode;
         const int v_lo = seg * seg_vec;                                    // first uint4 of the segment
         const int v_cnt = min(seg_vec, n_vec - v_lo);                      // may be <= 0 for a trailing segment
-        const int w_lo = v_lo * 4, w_hi = w_lo + max(v_cnt, 0) * 4;        // mask words [w_lo, w_hi)
-        if (mode == kRowFast && plan.dense >= 0) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
-            for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = src[w];
-        } else {
-            for (int w = tid; w < v_cnt; w += kEdgeBlock) bits4[w] = make_uint4(0, 0, 0, 0);
-        }
-        __syncthreads();
-        if (mode == kRowFast) {
-            const int nseg = plan.nseg;
-            for (int i = 0; i < nseg; ++i) {
-                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
-                const int cnt = plan.seg_count[i];
-                for (int k = tid; k < cnt; k += kEdgeBlock) {
-                    const int t = ids[k], w = t >> 5;
-                    if (w >= w_lo && w < w_hi) atomicOr(&bits[w - w_lo], 1u << (t & 31));
-                }
-            }
-            const int wc = plan.walk_count;
-            if (wc > 0 && tid < kWalkLanes) {
-                const int n = plan.len, top0 = plan.top;
-                for (int k = tid; k < wc; k += kWalkLanes) {
-                    const int t = E.walk_ids[plan.walk_begin + k], w = t >> 5;
-                    if (w >= w_lo && w < w_hi && walk_token_id(T, priv, t, row, n, top0))
-                        atomicOr(&bits[w - w_lo], 1u << (t & 31));
-                }
-            }
-        } else if (mode == kRowWalkAll) {
-            if (tid < kWalkLanes) {
-                const int n = plan.len, top0 = plan.top;
-                const int t_hi = min(T.n_tokens, w_hi * 32);
-                for (int t = w_lo * 32 + tid; t < t_hi; t += kWalkLanes)
-                    if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[(t >> 5) - w_lo], 1u << (t & 31));
-            }
-        } else if (mode == kRowDone && tid == 0) {
-            const int w = T.eos_id >> 5;
-            if (w >= w_lo && w < w_hi) bits[w - w_lo] = 1u << (T.eos_id & 31);
-        }
-        __syncthreads();
-        uint32_t *dst = bitmask + (size_t)b * T.n_words;
-        if ((T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0) {
-            uint4 *dst4 = reinterpret_cast<uint4 *>(dst) + v_lo;
-            for (int w = tid; w < v_cnt; w += kEdgeBlock) dst4[w] = bits4[w];
-        } else {
-            for (int w = w_lo + tid; w < min(w_hi, T.n_words); w += kEdgeBlock) dst[w] = bits[w - w_lo];
-        }
+        const int w_lo = v_lo * 4;
+        const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
+        build_and_store_row<kEdgeBlock>(T, E, plan, bits4, v_lo, v_cnt, row, priv, bitmask + (size_t)b * T.n_words,
+                                        vector_ok, tid);
         if (kApply) {
             // group g = 8 logits = one byte of the LDS bitmap (little endian)
             const uint8_t *mbytes = reinterpret_cast<const uint8_t *>(bits);

@@ -1,5 +1,5 @@
-// Descent of the condition tree of the token-level edges: how one sequence's mask row is
-// assembled.  Shared by the mask kernel and the advance+mask kernel.
+// Descent of the condition tree of the token-level edges and the assembly of one sequence's mask
+// row from what the descent found.  Shared by the mask kernel and the advance+mask kernel.
 #pragma once
 #include "walk.hpp"
 
@@ -76,6 +76,70 @@ __device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNod
         plan->mode = mode;
         plan->walk_begin = walk_begin;
         plan->walk_count = walk_count;
+    }
+}
+
+// Assembles mask words [4 * v_lo, 4 * (v_lo + v_cnt)) of the row that `plan` describes in the LDS
+// bitmap bits4[0 .. v_cnt) and stores them to dst_row (the row's first word in the bitmask):
+//   1. the segment of the materialised row the descent ended on (or zeros);
+//   2. the token ids collected after it, ORed in one lane per id (LDS atomics);
+//   3. tokens the tree leaves undetermined, walked byte by byte on `row` by the first 64 threads
+//      (each with its own private stack `priv`); a stack the tree has no answer for walks every
+//      token of the segment; a finished sequence gets the EOS bit only.
+// Called by all kThreads threads of the block after a barrier that made `plan` visible; contains
+// two block barriers; on return the bitmap still holds the segment.  kWholeRow: the segment is the
+// whole row (v_lo = 0), so no id needs a range test.
+template <int kThreads, bool kWholeRow = false>
+__device__ __forceinline__ void build_and_store_row(const DevTables &T, const DevTokenEdges &E, const RowPlan &plan,
+                                                    uint4 *bits4, int v_lo, int v_cnt, const int32_t *row,
+                                                    PrivateStack &priv, uint32_t *dst_row, bool dst_vector_ok, int tid) {
+    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
+    const int n_vec = (T.n_words + 3) >> 2;
+    const int mode = plan.mode;
+    const int w_lo = v_lo * 4, w_hi = w_lo + max(v_cnt, 0) * 4;
+    if (mode == kRowFast && plan.dense >= 0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
+        for (int w = tid; w < v_cnt; w += kThreads) bits4[w] = src[w];
+    } else {
+        for (int w = tid; w < v_cnt; w += kThreads) bits4[w] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+    if (mode == kRowFast) {
+        const int nseg = plan.nseg;
+        for (int i = 0; i < nseg; ++i) {
+            const int32_t *ids = E.delta_ids + plan.seg_begin[i];
+            const int cnt = plan.seg_count[i];
+            for (int k = tid; k < cnt; k += kThreads) {
+                const int t = ids[k], w = t >> 5;
+                if (kWholeRow || (w >= w_lo && w < w_hi)) atomicOr(&bits[w - w_lo], 1u << (t & 31));
+            }
+        }
+        const int wc = plan.walk_count;
+        if (wc > 0 && tid < 64) {
+            const int n = plan.len, top0 = plan.top;
+            for (int k = tid; k < wc; k += 64) {
+                const int t = E.walk_ids[plan.walk_begin + k], w = t >> 5;
+                if (w >= w_lo && w < w_hi && walk_token_id(T, priv, t, row, n, top0))
+                    atomicOr(&bits[w - w_lo], 1u << (t & 31));
+            }
+        }
+    } else if (mode == kRowWalkAll) {
+        if (tid < 64) {
+            const int n = plan.len, top0 = plan.top;
+            const int t_hi = min(T.n_tokens, w_hi * 32);
+            for (int t = w_lo * 32 + tid; t < t_hi; t += 64)
+                if (walk_token_id(T, priv, t, row, n, top0)) atomicOr(&bits[(t >> 5) - w_lo], 1u << (t & 31));
+        }
+    } else if (mode == kRowDone && tid == 0) {
+        const int w = T.eos_id >> 5;
+        if (w >= w_lo && w < w_hi) bits[w - w_lo] = 1u << (T.eos_id & 31);
+    }
+    __syncthreads();
+    if (dst_vector_ok) {
+        uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row) + v_lo;
+        for (int w = tid; w < v_cnt; w += kThreads) dst4[w] = bits4[w];
+    } else {
+        for (int w = w_lo + tid; w < min(w_hi, T.n_words); w += kThreads) dst_row[w] = bits[w - w_lo];
     }
 }
 
