@@ -157,6 +157,34 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
         if ((e = upload(h, h->T.state_kind, &D.state_kind)) != hipSuccess) return hip_fail(h, e, "upload state_kind");
     }
+    // the entry points of the token-level condition trees belong to the same hot region
+    const bool with_token_edges = h->E.enabled && (size_t)h->V.n_words <= edge_kernel_max_lds_words();
+    std::vector<DevConditionNode> nodes;
+    if (with_token_edges) {
+        nodes.resize(h->E.nodes.size());
+        for (size_t i = 0; i < nodes.size(); ++i) {
+            const ConditionNode &n = h->E.nodes[i];
+            DevConditionNode d{};
+            d.known = n.known;
+            d.child_count = n.child_count;
+            if (n.child_count > 0) {
+                d.a = n.child_begin;
+                d.b = h->E.child_node[n.child_begin];            // first child; the others follow it
+            } else {
+                d.a = n.walk_begin;
+                d.b = n.walk_count;
+            }
+            d.dense_row = n.dense_row;
+            d.delta_begin = n.delta_begin;
+            d.delta_count = n.delta_count;
+            nodes[i] = d;
+        }
+        std::vector<DevConditionNode> roots(h->E.root_of_state.size());
+        for (size_t i = 0; i < roots.size(); ++i) roots[i] = nodes[h->E.root_of_state[i]];
+        if ((e = upload(h, roots, &h->dev_edges.root_nodes)) != hipSuccess) return hip_fail(h, e, "upload root_nodes");
+        if ((e = upload(h, h->E.child_state, &h->dev_edges.child_state)) != hipSuccess)
+            return hip_fail(h, e, "upload child_state");
+    }
     {
         const ptrdiff_t span = h->arena - reinterpret_cast<const char *>(D.byte_info);
         const bool one_chunk = h->allocations.size() == chunks_before;
@@ -207,38 +235,16 @@ int upload_tables(pre3_handle *h) {
 
     // token-level edges; a vocabulary whose mask row does not fit the kernel's LDS bitmap keeps
     // the byte-by-byte path
-    if (h->E.enabled && (size_t)h->V.n_words <= edge_kernel_max_lds_words()) {
+    if (with_token_edges) {
         DevTokenEdges &X = h->dev_edges;
-        std::vector<DevConditionNode> nodes(h->E.nodes.size());
-        for (size_t i = 0; i < nodes.size(); ++i) {
-            const ConditionNode &n = h->E.nodes[i];
-            DevConditionNode d{};
-            d.known = n.known;
-            d.child_count = n.child_count;
-            if (n.child_count > 0) {
-                d.a = n.child_begin;
-                d.b = h->E.child_node[n.child_begin];            // first child; the others follow it
-            } else {
-                d.a = n.walk_begin;
-                d.b = n.walk_count;
-            }
-            d.dense_row = n.dense_row;
-            d.delta_begin = n.delta_begin;
-            d.delta_count = n.delta_count;
-            nodes[i] = d;
-        }
 #define PRE3_UPE(vec, field)                                              \
     if ((e = upload(h, vec, &X.field)) != hipSuccess) return hip_fail(h, e, "upload " #field)
-        std::vector<DevConditionNode> roots(h->E.root_of_state.size());
-        for (size_t i = 0; i < roots.size(); ++i) roots[i] = nodes[h->E.root_of_state[i]];
         const int stride = edge_row_stride_words(h->V.n_words);
         std::vector<uint32_t> dense((size_t)h->E.n_dense * stride, 0);
         for (int64_t r = 0; r < h->E.n_dense; ++r)
             std::memcpy(&dense[(size_t)r * stride], &h->E.dense_rows[(size_t)r * h->V.n_words],
                         sizeof(uint32_t) * h->V.n_words);
-        PRE3_UPE(roots, root_nodes);
         PRE3_UPE(nodes, nodes);
-        PRE3_UPE(h->E.child_state, child_state);
         PRE3_UPE(dense, dense_rows);
         PRE3_UPE(h->E.delta_ids, delta_ids);
         PRE3_UPE(h->E.walk_ids, walk_ids);
