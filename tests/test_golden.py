@@ -3,7 +3,6 @@ with its citation), checked against the oracle and, where they concern the compi
 against the library's host tables."""
 import os
 
-import numpy as np
 import pytest
 
 from oracle import A_ACCEPT, T_END, GrammarError, Oracle

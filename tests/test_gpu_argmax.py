@@ -7,7 +7,7 @@ import pytest
 from oracle import Oracle, masked_argmax as oracle_masked_argmax
 from workloads import configs
 from workloads import grammars as G
-from workloads.vocab import BASE_SEED, Vocab, bf16_logits, bpe_like_vocab
+from workloads.vocab import BASE_SEED, Vocab, bf16_logits
 
 pytestmark = pytest.mark.gpu
 

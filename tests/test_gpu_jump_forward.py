@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import Oracle, masked_argmax as oracle_masked_argmax
-from workloads import configs, trajectory
+from workloads import trajectory
 from workloads import grammars as G
 from workloads.vocab import BASE_SEED, bf16_logits, bpe_like_vocab
 

@@ -4,7 +4,6 @@ import ctypes
 import os
 import re
 
-import numpy as np
 import pytest
 
 from oracle import A_ACCEPT, A_ERROR, A_REDUCE, A_SHIFT, Oracle

@@ -11,7 +11,7 @@ import pytest
 from cfg_brute import languages
 from oracle import Oracle, apply_mask, masked_argmax
 from workloads import grammars as G
-from workloads.vocab import BASE_SEED, Vocab, arithmetic_vocab, bf16_logits, bpe_like_vocab
+from workloads.vocab import BASE_SEED, arithmetic_vocab, bf16_logits, bpe_like_vocab
 
 N = 8
 

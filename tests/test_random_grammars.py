@@ -7,7 +7,6 @@ import itertools
 import random
 
 import numpy as np
-import pytest
 
 from cfg_brute import languages
 from oracle import GrammarError, Oracle
