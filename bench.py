@@ -44,6 +44,8 @@ def main():
                     help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
     ap.add_argument("--no-token-edges", action="store_true",
                     help="compile without token-level edges: fill_mask walks every (sequence, token) pair")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
                     help="fill_mask + apply_mask + advance | fill_apply_mask + advance | "
                          "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS)")
@@ -78,6 +80,10 @@ def main():
     from workloads.vocab import bf16_logits
 
     cfg = configs.get(args.config)
+    if args.batch > 0 and args.batch != cfg.batch:
+        import dataclasses
+        import re
+        cfg = dataclasses.replace(cfg, batch=args.batch, name=re.sub(r"-B\d+-", f"-B{args.batch}-", cfg.name))
     v = cfg.vocab
     B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
     K, Wm = args.steps, args.warmup
@@ -464,7 +470,7 @@ def main():
         dom_timing = ("K launches on rotating logits buffers replayed as one HIP graph between two HIP events, "
                       "divided by K (a pair of events around every single launch reads "
                       f"{float(step_us['apply_mask'].mean()):.1f} us: the brackets add a few us)")
-        traffic = APPLY_TRAFFIC_BYTES.get(args.config)
+        traffic = APPLY_TRAFFIC_BYTES.get(args.config) if args.batch in (0, configs.get(args.config).batch) else None
     else:
         dom_name, dom_bytes = "fill_mask_edges_kernel<true>", BYTES_PER_PAIR * pairs
         dom_us = float(step_us["fill_apply_mask"].mean())
