@@ -236,6 +236,11 @@ int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]);
 /* Sizes of the merged reduction edges (Sec. 3.2.2; Alg. 1 step 3): out[0] built?, [1] condition
  * nodes, [2] deepest stack entry tested, [3] bytes of device memory. */
 int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]);
+/* Consistency check of the compiled tables on the host (tests and tools): every index that a
+ * kernel follows (edge targets, goto rows, condition children, record offsets, token ids, dense
+ * rows, vocabulary offsets) must stay inside its table.  Returns the number of violations (0 for
+ * a handle that pre3_compile built), or PRE3_E_BADARG. */
+int pre3_debug_validate_tables(const pre3_handle *h);
 /* Host mirror of one sequence's advance, for checking the compiled edge tables without a GPU
  * (tests and tools; never used by the device calls): walks bytes[0..n_bytes) (n_bytes < 0: the
  * end-of-input symbol) on stack[0..*len) (host memory, capacity cap) with the merged reduction

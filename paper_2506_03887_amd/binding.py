@@ -26,7 +26,7 @@ EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
-    "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance",
+    "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
 ]
 
 
@@ -82,6 +82,7 @@ def load():
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
         getattr(lib, name).argtypes = [vp]
     lib.pre3_byte_class.argtypes = [vp, i32]
+    lib.pre3_debug_validate_tables.argtypes = [vp]
     lib.pre3_edge.argtypes = [vp, i32, i32, c.POINTER(i32), c.POINTER(i32)]
     lib.pre3_goto_target.argtypes = [vp, i32, i32]
     lib.pre3_token_edge_stats.argtypes = [vp, vp]
@@ -202,6 +203,13 @@ class Pre3:
         if rc < 0:
             raise Pre3Error(rc, "debug_advance")
         return rc, st[: ln.value].tolist()
+
+    def validate_tables(self) -> int:
+        """Number of out-of-range indices in the compiled tables (0 expected)."""
+        rc = self._lib.pre3_debug_validate_tables(self._h)
+        if rc < 0:
+            raise Pre3Error(rc, "validate_tables")
+        return rc
 
     def debug_resolve_row(self, stack):
         """(resolved?, row bits uint32[W], walk token ids) from the host copy of the tables."""

@@ -541,6 +541,88 @@ int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]) {
     return PRE3_OK;
 }
 
+// Every index a kernel follows in the compiled tables must stay inside its table: the kernels
+// themselves do not range-check table contents.  Returns the number of violations found.
+int pre3_debug_validate_tables(const pre3_handle *h) {
+    if (!h || !h->compiled) return PRE3_E_BADARG;
+    int64_t bad = 0;
+    auto need = [&](bool ok) { if (!ok) ++bad; };
+    const EdgeTables &T = h->T;
+    const int ncol = T.n_classes + 1;
+    need((int)T.state_kind.size() == T.n_states && (int)T.goto_row.size() == T.n_states);
+    need((int64_t)T.edge.size() == (int64_t)T.n_states * ncol);
+    for (int b = 0; b < 256; ++b) need(T.byte_class[b] < T.n_classes);
+    for (int s = 0; s < T.n_states && bad == 0; ++s) {
+        need(T.state_kind[s] >= 0 && T.state_kind[s] < T.n_kinds);
+        for (int c = 0; c < ncol; ++c) {
+            const uint32_t e = T.edge[(size_t)s * ncol + c];
+            if ((e & kKindMask) == kShift) {
+                // the per-byte offsets of the class must keep the target inside the state range
+                for (int b = 0; b < 256; ++b)
+                    if (T.byte_class[b] == c) need((int64_t)(e >> 2) + T.byte_delta[b] >= 0 && (int64_t)(e >> 2) + T.byte_delta[b] < T.n_states);
+            }
+        }
+        const int r = T.goto_row[s];
+        need(r < (int)T.goto_flat.size());
+    }
+    for (int32_t t : T.goto_flat) need(t < T.n_states);
+    // merged reduction edges
+    const SymbolEdges &S = h->S;
+    if (S.enabled) {
+        need((int)S.nodes.size() >= T.n_kinds && (int64_t)S.eff.size() == (int64_t)S.nodes.size() * ncol);
+        need(S.child_state.size() == S.child_node.size());
+        for (size_t i = 0; i < S.nodes.size(); ++i) {
+            const SymbolNode &n = S.nodes[i];
+            need(n.known >= 1 && n.child_count >= 0 && n.child_begin >= 0 &&
+                 (size_t)n.child_begin + n.child_count <= S.child_state.size());
+            for (int j = 0; j < n.child_count; ++j) {
+                need(S.child_node[n.child_begin + j] == n.first_child + j);          // children are consecutive
+                need(S.child_state[n.child_begin + j] >= 0 && S.child_state[n.child_begin + j] < T.n_states);
+            }
+            need(n.child_count == 0 || (n.first_child > (int)i && (size_t)n.first_child + n.child_count <= S.nodes.size()));
+        }
+        for (int32_t code : S.eff) {
+            if (code < 0) { need(code >= kEffStepwise); continue; }
+            need((code & 3) == 0 && (size_t)code + 4 <= S.pool.size());
+            if ((size_t)code + 4 > S.pool.size()) continue;
+            const int32_t *r = &S.pool[code];
+            const int np = r[2] & kEffPushMask;
+            need(r[0] >= 1 && np >= 1 && (size_t)code + 4 + np <= S.pool.size() && r[3] >= 0 && r[3] < T.n_kinds);
+            if ((size_t)code + 4 + np <= S.pool.size())
+                for (int k = 0; k < np; ++k) need(r[4 + k] >= 0 && r[4 + k] < T.n_states);
+        }
+    }
+    // token-level edges
+    const TokenEdges &E = h->E;
+    if (E.enabled) {
+        const int64_t n_dense = E.n_words ? (int64_t)E.dense_rows.size() / E.n_words : 0;
+        need((int)E.root_of_state.size() == T.n_states && E.n_words == h->V.n_words);
+        for (int32_t r : E.root_of_state) need(r >= 0 && r < (int)E.nodes.size());
+        need(E.child_state.size() == E.child_node.size());
+        for (size_t i = 0; i < E.nodes.size(); ++i) {
+            const ConditionNode &n = E.nodes[i];
+            need(n.known >= 1 && n.child_count >= 0 && n.child_begin >= 0 &&
+                 (size_t)n.child_begin + n.child_count <= E.child_state.size());
+            for (int j = 0; j < n.child_count; ++j) {
+                const int32_t c = E.child_node[n.child_begin + j];
+                need(c == E.child_node[n.child_begin] + j && c > (int)i && c < (int)E.nodes.size());
+                need(j == 0 || E.child_state[n.child_begin + j] > E.child_state[n.child_begin + j - 1]);
+            }
+            need(n.dense_row >= -1 && n.dense_row < n_dense);
+            need(n.delta_count >= 0 && n.delta_begin >= 0 && (size_t)n.delta_begin + n.delta_count <= E.delta_ids.size());
+            need(n.walk_count >= -1 && n.walk_begin >= 0 &&
+                 (n.walk_count < 0 || (size_t)n.walk_begin + n.walk_count <= E.walk_ids.size()));
+        }
+        for (int32_t t : E.delta_ids) need(t >= 0 && t < h->V.n_tokens);
+        for (int32_t t : E.walk_ids) need(t >= 0 && t < h->V.n_tokens);
+    }
+    // vocabulary
+    need((int)h->V.offsets.size() == h->V.n_tokens + 1);
+    for (int t = 0; t < h->V.n_tokens; ++t) need(h->V.offsets[t] <= h->V.offsets[t + 1]);
+    need(h->V.offsets.empty() || (size_t)h->V.offsets.back() + 4 <= h->V.bytes.size());
+    return (int)std::min<int64_t>(bad, 1 << 30);
+}
+
 int pre3_debug_advance(const pre3_handle *h, int32_t *stack, int32_t *len, int32_t cap, const uint8_t *bytes,
                        int32_t n_bytes, int32_t use_merged) {
     if (!h || !h->compiled || !stack || !len || *len < 1 || *len > cap || (n_bytes > 0 && !bytes)) return PRE3_E_BADARG;

@@ -73,6 +73,7 @@ def test_random_grammars_three_ways():
             continue
         accepted += 1
         assert lib.n_states == o.n_states(0), text
+        assert lib.validate_tables() == 0, text
         for p in sorted(viable):
             rc, st = (0, o.initial_stack()) if not p else o.advance(o.initial_stack(), p.encode())
             assert rc == 0, (text, p)
