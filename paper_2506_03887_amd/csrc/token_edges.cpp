@@ -8,6 +8,7 @@
 #include <memory>
 #include <numeric>
 #include <thread>
+#include <unordered_map>
 
 namespace pre3 {
 
@@ -217,6 +218,7 @@ struct Flattener {
     const TokenEdgeLimits &lim;
     TokenEdges &E;
     int dense_threshold;
+    std::unordered_multimap<uint64_t, int> row_index;     // hash of a materialised row -> its index
 
     void subtree_tokens(int c, std::vector<int32_t> &out) const {
         const Trie::Node &N = trie.nodes[c];
@@ -244,8 +246,21 @@ struct Flattener {
             if (base) std::memcpy(own_row.data(), base, sizeof(uint32_t) * E.n_words);
             for (int32_t t : since) own_row[t >> 5] |= 1u << (t & 31);
             for (int32_t t : b.accepted) own_row[t >> 5] |= 1u << (t & 31);
-            E.dense_rows.insert(E.dense_rows.end(), own_row.begin(), own_row.end());
-            E.n_dense++;
+            // identical rows (the same set of tokens reached under different conditions) are stored once
+            uint64_t hsh = 1469598103934665603ull;
+            for (uint32_t w : own_row) hsh = (hsh ^ w) * 1099511628211ull;
+            int found = -1;
+            auto range = row_index.equal_range(hsh);
+            for (auto it = range.first; it != range.second && found < 0; ++it)
+                if (std::memcmp(&E.dense_rows[(size_t)it->second * E.n_words], own_row.data(), sizeof(uint32_t) * E.n_words) == 0)
+                    found = it->second;
+            if (found >= 0) {
+                n.dense_row = found;
+            } else {
+                row_index.emplace(hsh, n.dense_row);
+                E.dense_rows.insert(E.dense_rows.end(), own_row.begin(), own_row.end());
+                E.n_dense++;
+            }
             n.delta_begin = (int)E.delta_ids.size();
             n.delta_count = 0;
         } else {
