@@ -82,6 +82,11 @@ typedef struct {
     int32_t max_condition_depth; /* 0 = default 48: deepest stack entry (below the top) that the    */
                                  /* stack-matching condition of a token-level edge may test; tokens */
                                  /* that would need more are walked byte by byte at run time        */
+    int32_t row_threshold;       /* 0 = default 1: a node of a token-level condition tree holds a whole   */
+                                 /* mask row once this many token ids have been allowed since the last   */
+                                 /* such row on its path (identical rows are stored once); below the     */
+                                 /* threshold the node lists the ids and the kernel ORs them in.  Larger */
+                                 /* values trade table size for work at run time                         */
 } pre3_options;
 
 /* Parse stacks of a batch, device memory, caller-owned.

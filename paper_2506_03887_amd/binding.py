@@ -43,7 +43,7 @@ class _Vocab(ctypes.Structure):
 
 class _Options(ctypes.Structure):
     _fields_ = [("max_token_len", ctypes.c_int32), ("stack_cap", ctypes.c_int32), ("flags", ctypes.c_int32),
-                ("max_condition_depth", ctypes.c_int32)]
+                ("max_condition_depth", ctypes.c_int32), ("row_threshold", ctypes.c_int32)]
 
 
 class _Stacks(ctypes.Structure):
@@ -119,7 +119,8 @@ class Pre3:
 
     def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
                  max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False,
-                 token_edges: bool = True, max_condition_depth: int = 0, merged_reductions: bool = True):
+                 token_edges: bool = True, max_condition_depth: int = 0, merged_reductions: bool = True,
+                 row_threshold: int = 0):
         lib = load()
         if isinstance(grammars, str):
             grammars = [grammars]
@@ -130,7 +131,7 @@ class Pre3:
         opt = _Options(max_token_len, stack_cap,
                        (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES)
                        | (0 if merged_reductions else FLAG_STEPWISE_REDUCTIONS),
-                       max_condition_depth)
+                       max_condition_depth, row_threshold)
         h = ctypes.c_void_p()
         rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
         self._lib, self._h = lib, h

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     wp.spill = walk_spill + (size_t)b * 64 + lane;
     wp.spill_stride = walk_spill_stride;
     const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
-    build_and_store_row<kAfBlock, true>(T, E, plan, bits4, 0, n_vec, row, wp, bitmask + (size_t)b * T.n_words, vector_ok, tid);
+    build_and_store_row<kAfBlock, true, true>(T, E, plan, bits4, 0, n_vec, row, wp, bitmask + (size_t)b * T.n_words, vector_ok, tid);
 }
 
 // Jump-forward: while a sequence's text is not a sentence and exactly one byte keeps it a viable

@@ -309,6 +309,7 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
         if (!(opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EDGES)) && (size_t)h->V.n_words <= edge_kernel_max_lds_words()) {
             TokenEdgeLimits lim;
             if (opt && opt->max_condition_depth > 0) lim.max_known = opt->max_condition_depth;
+            if (opt && opt->row_threshold > 0) lim.max_path_ids = opt->row_threshold;
             lim.n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
             h->E = build_token_edges(h->T, h->V, lim);
         }

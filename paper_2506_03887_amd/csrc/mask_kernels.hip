@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
         const int v_cnt = min(seg_vec, n_vec - v_lo);                      // may be <= 0 for a trailing segment
         const int w_lo = v_lo * 4;
         const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
-        build_and_store_row<kEdgeBlock>(T, E, plan, bits4, v_lo, v_cnt, row, priv, bitmask + (size_t)b * T.n_words,
+        build_and_store_row<kEdgeBlock, false, !kApply>(T, E, plan, bits4, v_lo, v_cnt, row, priv, bitmask + (size_t)b * T.n_words,
                                         vector_ok, tid);
         if (kApply) {
             // group g = 8 logits = one byte of the LDS bitmap (little endian)

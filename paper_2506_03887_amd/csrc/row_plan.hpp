@@ -89,7 +89,7 @@ __device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNod
 // Called by all kThreads threads of the block after a barrier that made `plan` visible; contains
 // two block barriers; on return the bitmap still holds the segment.  kWholeRow: the segment is the
 // whole row (v_lo = 0), so no id needs a range test.
-template <int kThreads, bool kWholeRow = false>
+template <int kThreads, bool kWholeRow = false, bool kDirect = false>
 __device__ __forceinline__ void build_and_store_row(const DevTables &T, const DevTokenEdges &E, const RowPlan &plan,
                                                     uint4 *bits4, int v_lo, int v_cnt, const int32_t *row,
                                                     PrivateStack &priv, uint32_t *dst_row, bool dst_vector_ok, int tid) {
@@ -97,6 +97,13 @@ __device__ __forceinline__ void build_and_store_row(const DevTables &T, const De
     const int n_vec = (T.n_words + 3) >> 2;
     const int mode = plan.mode;
     const int w_lo = v_lo * 4, w_hi = w_lo + max(v_cnt, 0) * 4;
+    if (kDirect && mode == kRowFast && plan.dense >= 0 && plan.nseg == 0 && plan.walk_count == 0 && dst_vector_ok) {
+        // the row is exactly a materialised row: copy it without staging it in LDS
+        const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
+        uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row) + v_lo;
+        for (int w = tid; w < v_cnt; w += kThreads) dst4[w] = src[w];
+        return;
+    }
     if (mode == kRowFast && plan.dense >= 0) {
         const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
         for (int w = tid; w < v_cnt; w += kThreads) bits4[w] = src[w];

@@ -236,8 +236,9 @@ struct Flattener {
         E.max_known = std::max<int64_t>(E.max_known, b.known);
         size_t since_mark = since.size();
         std::vector<uint32_t> own_row;
-        // a row is materialised where the ids ORed in since the last materialised row reach the
-        // threshold, so that no descent ever collects more than `dense_threshold` ids
+        // a row is materialised where the ids allowed since the last materialised row reach the
+        // threshold (1 by default: wherever a node allows a token of its own), so that a descent
+        // collects fewer than `dense_threshold` ids to OR in
         const bool dense = (int64_t)(since.size() + b.accepted.size()) >= dense_threshold &&
                            (int64_t)E.dense_rows.size() + E.n_words <= lim.max_dense_words;
         if (dense) {
@@ -352,7 +353,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     worker();
     for (auto &t : pool) t.join();
 
-    Flattener F{trie, lim, E, std::min(lim.max_path_ids, std::max(64, V.n_words))};
+    Flattener F{trie, lim, E, std::max(1, lim.max_path_ids)};
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;

@@ -55,7 +55,10 @@ struct TokenEdges {
 struct TokenEdgeLimits {
     int max_nodes = 1 << 18;          // condition-tree nodes
     int max_known = 48;               // deepest stack entry a condition may test
-    int max_path_ids = 256;           // token ids a descent may collect before a row is materialised
+    int max_path_ids = 1;             // token ids a descent may collect before a row is materialised
+                                      // (1: every node that allows a token of its own has a row; rows
+                                      // are shared, so this costs little; delta lists then only appear
+                                      // once max_dense_words is exhausted)
     int max_walk = 2048;              // longest walk list kept per node (longer: whole vocabulary)
     int64_t max_dense_words = (int64_t)1 << 28;   // 1 GiB of dense rows
     int n_threads = 8;

@@ -61,7 +61,7 @@ int main(int argc, char **argv) {
 
     pre3_handle *h = NULL;
     pre3_vocab vocab = {vbytes, offsets, V, eos};
-    pre3_options opt = {64, cap, 0, 0};
+    pre3_options opt = {64, cap, 0, 0, 0};
     const char *texts[1] = {grammar};
     CHECK_PRE3(pre3_compile(texts, 1, &vocab, &opt, &h));
 

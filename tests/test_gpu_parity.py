@@ -40,6 +40,14 @@ def test_cfg2_shallow_conditions_leave_tokens_to_the_walk(depth):
     assert replay(2, steps=16, max_condition_depth=depth)["full_masks"] == 16
 
 
+@pytest.mark.parametrize("threshold", [64, 4008])
+def test_cfg2_rows_assembled_from_id_lists(threshold):
+    """A larger row threshold leaves token ids in per-node lists that the kernels OR into the row."""
+    r = replay(2, steps=40, row_threshold=threshold)
+    assert r["full_masks"] == 40
+    assert replay_advance_fill(2, steps=40, row_threshold=threshold)["steps"] == 40
+
+
 def test_cfg3_json_full_size():
     """B=256, V=128256, 256 steps: states/stacks on every step, the whole bitmask and masked
     logits on 6 steps spread over the run, two full mask rows on every other step."""

@@ -66,6 +66,13 @@ def test_json_rows_equal_oracle_rows(depth_limit):
         assert undecided > 0 or unresolved > 0           # shallow limits leave work to the byte-by-byte walk
 
 
+@pytest.mark.parametrize("threshold", [1, 16, 3000])
+def test_json_rows_with_id_lists(threshold):
+    v = bpe_like_vocab(3000, 12, BASE_SEED + 61)
+    resolved, undecided, unresolved, _ = _check_along_trajectory([G.JSON], v, 20, 6, 9, 6, row_threshold=threshold)
+    assert resolved > 80 and unresolved == 0 and undecided == 0
+
+
 def test_rows_of_several_grammars_in_one_handle():
     texts = [G.schema_grammar(21, 5, 2, 3).text, G.JSON, G.DYCK]
     v = bpe_like_vocab(2500, 12, BASE_SEED + 62)
