@@ -157,7 +157,7 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, h->S.pool, &D.sym_pool)) != hipSuccess) return hip_fail(h, e, "upload sym_pool");
         if ((e = upload(h, h->T.state_kind, &D.state_kind)) != hipSuccess) return hip_fail(h, e, "upload state_kind");
     }
-    // the entry points of the token-level condition trees belong to the same hot region
+    // the condition trees of the token-level edges (shared subtrees make them small) belong to the same hot region
     const bool with_token_edges = h->E.enabled && (size_t)h->V.n_words <= edge_kernel_max_lds_words();
     std::vector<DevConditionNode> nodes;
     if (with_token_edges) {
@@ -184,6 +184,7 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, roots, &h->dev_edges.root_nodes)) != hipSuccess) return hip_fail(h, e, "upload root_nodes");
         if ((e = upload(h, h->E.child_state, &h->dev_edges.child_state)) != hipSuccess)
             return hip_fail(h, e, "upload child_state");
+        if ((e = upload(h, nodes, &h->dev_edges.nodes)) != hipSuccess) return hip_fail(h, e, "upload nodes");
     }
     {
         const ptrdiff_t span = h->arena - reinterpret_cast<const char *>(D.byte_info);
@@ -244,7 +245,6 @@ int upload_tables(pre3_handle *h) {
         for (int64_t r = 0; r < h->E.n_dense; ++r)
             std::memcpy(&dense[(size_t)r * stride], &h->E.dense_rows[(size_t)r * h->V.n_words],
                         sizeof(uint32_t) * h->V.n_words);
-        PRE3_UPE(nodes, nodes);
         PRE3_UPE(dense, dense_rows);
         PRE3_UPE(h->E.delta_ids, delta_ids);
         PRE3_UPE(h->E.walk_ids, walk_ids);
@@ -606,7 +606,7 @@ int pre3_debug_validate_tables(const pre3_handle *h) {
                  (size_t)n.child_begin + n.child_count <= E.child_state.size());
             for (int j = 0; j < n.child_count; ++j) {
                 const int32_t c = E.child_node[n.child_begin + j];
-                need(c == E.child_node[n.child_begin] + j && c > (int)i && c < (int)E.nodes.size());
+                need(c == E.child_node[n.child_begin] + j && c >= 0 && c < (int)i);   // children are stored before their parents
                 need(j == 0 || E.child_state[n.child_begin + j] > E.child_state[n.child_begin + j - 1]);
             }
             need(n.dense_row >= -1 && n.dense_row < n_dense);

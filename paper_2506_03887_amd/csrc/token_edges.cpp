@@ -226,10 +226,60 @@ struct Flattener {
         for (int i = 0; i < N.n_children; ++i) subtree_tokens(N.first_child + i, out);
     }
 
-    // `base` = dense row of the nearest dense ancestor (or null), `since` = ids accepted after it
-    // The node is written to E.nodes[idx]; its children get consecutive indices, in the order of
-    // their condition states, so that child j is node first_child + j.
-    void flatten(const BuildNode &b, int idx, const uint32_t *base, std::vector<int32_t> &since) {
+    static uint64_t fnv(const void *data, size_t bytes, uint64_t h = 1469598103934665603ull) {
+        const unsigned char *p = static_cast<const unsigned char *>(data);
+        for (size_t i = 0; i < bytes; ++i) h = (h ^ p[i]) * 1099511628211ull;
+        return h;
+    }
+
+    // Appends `ids` to `pool` unless the same list is already there; returns where it starts.
+    static int32_t intern_list(std::vector<int32_t> &pool, std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> &index,
+                               const std::vector<int32_t> &ids) {
+        if (ids.empty()) return 0;
+        const uint64_t h = fnv(ids.data(), ids.size() * sizeof(int32_t));
+        auto range = index.equal_range(h);
+        for (auto it = range.first; it != range.second; ++it)
+            if (it->second.second == (int32_t)ids.size() &&
+                std::memcmp(&pool[it->second.first], ids.data(), ids.size() * sizeof(int32_t)) == 0)
+                return it->second.first;
+        const int32_t begin = (int32_t)pool.size();
+        pool.insert(pool.end(), ids.begin(), ids.end());
+        index.emplace(h, std::make_pair(begin, (int32_t)ids.size()));
+        return begin;
+    }
+
+    std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> delta_index, walk_index;
+    // hash of a group of sibling records (with their condition states) -> (child_begin, count)
+    std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> group_index;
+
+    // Stores a group of sibling nodes (records `recs`, told apart by `states`, ascending) unless an
+    // identical group exists: equal subtrees under different parents share one copy, which turns the
+    // trees into a DAG.  Returns the group's start in child_state / child_node; its nodes are
+    // consecutive, beginning at child_node[start].
+    int32_t intern_group(const std::vector<int32_t> &states, const std::vector<ConditionNode> &recs) {
+        uint64_t h = fnv(states.data(), states.size() * sizeof(int32_t));
+        h = fnv(recs.data(), recs.size() * sizeof(ConditionNode), h);
+        auto range = group_index.equal_range(h);
+        for (auto it = range.first; it != range.second; ++it) {
+            const int32_t begin = it->second.first;
+            if (it->second.second != (int32_t)states.size()) continue;
+            if (std::memcmp(&E.child_state[begin], states.data(), states.size() * sizeof(int32_t)) != 0) continue;
+            if (std::memcmp(&E.nodes[E.child_node[begin]], recs.data(), recs.size() * sizeof(ConditionNode)) == 0) return begin;
+        }
+        const int32_t begin = (int32_t)E.child_state.size(), first = (int32_t)E.nodes.size();
+        for (size_t j = 0; j < states.size(); ++j) {
+            E.child_state.push_back(states[j]);
+            E.child_node.push_back(first + (int32_t)j);
+        }
+        E.nodes.insert(E.nodes.end(), recs.begin(), recs.end());
+        group_index.emplace(h, std::make_pair(begin, (int32_t)states.size()));
+        return begin;
+    }
+
+    // `base` = dense row of the nearest dense ancestor (or null), `since` = ids accepted after it.
+    // Returns the node's record; its children (and theirs) have been stored by then, consecutively
+    // and in the order of their condition states, so that child j is node first_child + j.
+    ConditionNode flatten(const BuildNode &b, const uint32_t *base, std::vector<int32_t> &since) {
         ConditionNode n{};
         n.known = b.known;
         n.dense_row = -1;
@@ -248,8 +298,7 @@ struct Flattener {
             for (int32_t t : since) own_row[t >> 5] |= 1u << (t & 31);
             for (int32_t t : b.accepted) own_row[t >> 5] |= 1u << (t & 31);
             // identical rows (the same set of tokens reached under different conditions) are stored once
-            uint64_t hsh = 1469598103934665603ull;
-            for (uint32_t w : own_row) hsh = (hsh ^ w) * 1099511628211ull;
+            const uint64_t hsh = fnv(own_row.data(), own_row.size() * sizeof(uint32_t));
             int found = -1;
             auto range = row_index.equal_range(hsh);
             for (auto it = range.first; it != range.second && found < 0; ++it)
@@ -262,17 +311,12 @@ struct Flattener {
                 E.dense_rows.insert(E.dense_rows.end(), own_row.begin(), own_row.end());
                 E.n_dense++;
             }
-            n.delta_begin = (int)E.delta_ids.size();
-            n.delta_count = 0;
         } else {
-            n.delta_begin = (int)E.delta_ids.size();
             n.delta_count = (int)b.accepted.size();
-            E.delta_ids.insert(E.delta_ids.end(), b.accepted.begin(), b.accepted.end());
+            n.delta_begin = intern_list(E.delta_ids, delta_index, b.accepted);
             since.insert(since.end(), b.accepted.begin(), b.accepted.end());
         }
         // tokens left undetermined when the tree ends here
-        n.walk_begin = (int)E.walk_ids.size();
-        n.walk_count = 0;
         if (b.children.empty() && !b.pend.empty()) {
             int64_t total = 0;
             for (const Pending &u : b.pend) total += trie.nodes[u.trie_node].sub_tokens;
@@ -282,31 +326,28 @@ struct Flattener {
                 std::vector<int32_t> ids;
                 for (const Pending &u : b.pend) subtree_tokens(u.trie_node, ids);
                 n.walk_count = (int)ids.size();
-                E.walk_ids.insert(E.walk_ids.end(), ids.begin(), ids.end());
+                n.walk_begin = intern_list(E.walk_ids, walk_index, ids);
             }
         }
         std::vector<std::pair<int32_t, const BuildNode *>> kids;
         for (const auto &ch : b.children) kids.push_back({ch.first, ch.second.get()});
         std::sort(kids.begin(), kids.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
-        const int first = (int)E.nodes.size();
-        n.child_begin = (int)E.child_state.size();
-        n.child_count = (int)kids.size();
-        E.nodes.resize(E.nodes.size() + kids.size());
-        for (size_t j = 0; j < kids.size(); ++j) {
-            E.child_state.push_back(kids[j].first);
-            E.child_node.push_back(first + (int)j);
-        }
-        E.nodes[idx] = n;
+        std::vector<int32_t> states;
+        std::vector<ConditionNode> recs;
         std::vector<int32_t> empty_since;
-        for (size_t j = 0; j < kids.size(); ++j) {
+        for (const auto &kid : kids) {
+            states.push_back(kid.first);
             if (dense) {
                 empty_since.clear();
-                flatten(*kids[j].second, first + (int)j, own_row.data(), empty_since);
+                recs.push_back(flatten(*kid.second, own_row.data(), empty_since));
             } else {
-                flatten(*kids[j].second, first + (int)j, base, since);
+                recs.push_back(flatten(*kid.second, base, since));
             }
         }
+        n.child_count = (int)kids.size();
+        n.child_begin = kids.empty() ? 0 : intern_group(states, recs);
         since.resize(since_mark);
+        return n;
     }
 };
 
@@ -357,9 +398,9 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;
-        root_node[i] = (int)E.nodes.size();
-        E.nodes.push_back(ConditionNode{});
-        F.flatten(*roots[i], root_node[i], nullptr, since);
+        const ConditionNode rec = F.flatten(*roots[i], nullptr, since);
+        root_node[i] = (int)E.nodes.size();                  // a root is stored after its subtree
+        E.nodes.push_back(rec);
         roots[i].reset();
     }
     E.root_of_state.resize(T.n_states);
