@@ -218,7 +218,6 @@ struct Flattener {
     const TokenEdgeLimits &lim;
     TokenEdges &E;
     int dense_threshold;
-    std::unordered_multimap<uint64_t, int> row_index;     // hash of a materialised row -> its index
 
     void subtree_tokens(int c, std::vector<int32_t> &out) const {
         const Trie::Node &N = trie.nodes[c];
@@ -226,9 +225,80 @@ struct Flattener {
         for (int i = 0; i < N.n_children; ++i) subtree_tokens(N.first_child + i, out);
     }
 
+    // ---- materialised rows, each stored once.  A row is the base row plus tokens that are not in
+    // it (a node only lists tokens no ancestor allows), so its content hash -- the sum of a mixed
+    // value per token -- and its population follow from the base's in O(new tokens); a candidate with
+    // the same hash is then verified exactly: same population, every new token present, and a
+    // superset of the base (that last test is memoised per pair of rows).
+    std::vector<uint64_t> row_hash;
+    std::vector<int64_t> row_pop;
+    std::unordered_multimap<uint64_t, int> row_index;
+    std::unordered_map<uint64_t, bool> superset_memo;
+    std::vector<uint32_t> seen;              // scratch bitmap, all zero between calls
+    std::vector<int32_t> fresh_scratch;
+
+    static uint64_t mix(uint64_t x) {
+        x += 0x9E3779B97F4A7C15ull;
+        x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+        x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+        return x ^ (x >> 31);
+    }
+
+    bool is_superset(int cand, int base) {
+        if (base < 0) return true;
+        const uint64_t key = ((uint64_t)(uint32_t)cand << 32) | (uint32_t)base;
+        auto it = superset_memo.find(key);
+        if (it != superset_memo.end()) return it->second;
+        const uint32_t *c = &E.dense_rows[(size_t)cand * E.n_words], *b = &E.dense_rows[(size_t)base * E.n_words];
+        bool ok = true;
+        for (int w = 0; w < E.n_words && ok; ++w) ok = (c[w] & b[w]) == b[w];
+        superset_memo.emplace(key, ok);
+        return ok;
+    }
+
+    // Index of the row  base + ids_a + ids_b.
+    int row_of(int base, const std::vector<int32_t> &ids_a, const std::vector<int32_t> &ids_b) {
+        auto has = [&](int row, int32_t t) { return (E.dense_rows[(size_t)row * E.n_words + (t >> 5)] >> (t & 31)) & 1u; };
+        // the tokens that are really new (by construction all of them; made exact here because the
+        // verification below counts on it)
+        std::vector<int32_t> &fresh = fresh_scratch;
+        fresh.clear();
+        if (seen.empty()) seen.assign(E.n_words, 0);
+        for (const std::vector<int32_t> *ids : {&ids_a, &ids_b})
+            for (int32_t t : *ids) {
+                if ((base >= 0 && has(base, t)) || ((seen[t >> 5] >> (t & 31)) & 1u)) continue;
+                seen[t >> 5] |= 1u << (t & 31);
+                fresh.push_back(t);
+            }
+        for (int32_t t : fresh) seen[t >> 5] = 0;
+        if (fresh.empty() && base >= 0) return base;
+        uint64_t h = base >= 0 ? row_hash[base] : 0;
+        for (int32_t t : fresh) h += mix((uint64_t)t);
+        const int64_t pop = (base >= 0 ? row_pop[base] : 0) + (int64_t)fresh.size();
+        auto range = row_index.equal_range(h);
+        for (auto it = range.first; it != range.second; ++it) {
+            const int cand = it->second;
+            if (row_pop[cand] != pop) continue;           // same size, contains base and the new tokens: equal
+            bool ok = true;
+            for (size_t i = 0; i < fresh.size() && ok; ++i) ok = has(cand, fresh[i]);
+            if (ok && is_superset(cand, base)) return cand;
+        }
+        const int row = (int)(E.dense_rows.size() / E.n_words);
+        E.dense_rows.resize(E.dense_rows.size() + E.n_words, 0);          // may move the rows: take pointers after it
+        uint32_t *dst = &E.dense_rows[(size_t)row * E.n_words];
+        if (base >= 0) std::memcpy(dst, &E.dense_rows[(size_t)base * E.n_words], sizeof(uint32_t) * E.n_words);
+        for (int32_t t : fresh) dst[t >> 5] |= 1u << (t & 31);
+        row_hash.push_back(h);
+        row_pop.push_back(pop);
+        row_index.emplace(h, row);
+        E.n_dense++;
+        return row;
+    }
+
+    // multiplicative hash over 4-byte words (every hashed object here is an array of int32/uint32)
     static uint64_t fnv(const void *data, size_t bytes, uint64_t h = 1469598103934665603ull) {
-        const unsigned char *p = static_cast<const unsigned char *>(data);
-        for (size_t i = 0; i < bytes; ++i) h = (h ^ p[i]) * 1099511628211ull;
+        const uint32_t *p = static_cast<const uint32_t *>(data);
+        for (size_t i = 0; i < bytes / 4; ++i) h = (h ^ p[i]) * 1099511628211ull;
         return h;
     }
 
@@ -276,41 +346,24 @@ struct Flattener {
         return begin;
     }
 
-    // `base` = dense row of the nearest dense ancestor (or null), `since` = ids accepted after it.
+    // `base` = dense row of the nearest dense ancestor (or -1), `since` = ids accepted after it.
     // Returns the node's record; its children (and theirs) have been stored by then, consecutively
     // and in the order of their condition states, so that child j is node first_child + j.
-    ConditionNode flatten(const BuildNode &b, const uint32_t *base, std::vector<int32_t> &since) {
+    ConditionNode flatten(const BuildNode &b, int base, std::vector<int32_t> &since) {
         ConditionNode n{};
         n.known = b.known;
         n.dense_row = -1;
         E.max_known = std::max<int64_t>(E.max_known, b.known);
         size_t since_mark = since.size();
-        std::vector<uint32_t> own_row;
         // a row is materialised where the ids allowed since the last materialised row reach the
         // threshold (1 by default: wherever a node allows a token of its own), so that a descent
         // collects fewer than `dense_threshold` ids to OR in
         const bool dense = (int64_t)(since.size() + b.accepted.size()) >= dense_threshold &&
                            (int64_t)E.dense_rows.size() + E.n_words <= lim.max_dense_words;
+        int own_row = base;
         if (dense) {
-            n.dense_row = (int)(E.dense_rows.size() / E.n_words);
-            own_row.assign(E.n_words, 0);
-            if (base) std::memcpy(own_row.data(), base, sizeof(uint32_t) * E.n_words);
-            for (int32_t t : since) own_row[t >> 5] |= 1u << (t & 31);
-            for (int32_t t : b.accepted) own_row[t >> 5] |= 1u << (t & 31);
-            // identical rows (the same set of tokens reached under different conditions) are stored once
-            const uint64_t hsh = fnv(own_row.data(), own_row.size() * sizeof(uint32_t));
-            int found = -1;
-            auto range = row_index.equal_range(hsh);
-            for (auto it = range.first; it != range.second && found < 0; ++it)
-                if (std::memcmp(&E.dense_rows[(size_t)it->second * E.n_words], own_row.data(), sizeof(uint32_t) * E.n_words) == 0)
-                    found = it->second;
-            if (found >= 0) {
-                n.dense_row = found;
-            } else {
-                row_index.emplace(hsh, n.dense_row);
-                E.dense_rows.insert(E.dense_rows.end(), own_row.begin(), own_row.end());
-                E.n_dense++;
-            }
+            own_row = row_of(base, since, b.accepted);
+            n.dense_row = own_row;
         } else {
             n.delta_count = (int)b.accepted.size();
             n.delta_begin = intern_list(E.delta_ids, delta_index, b.accepted);
@@ -339,7 +392,7 @@ struct Flattener {
             states.push_back(kid.first);
             if (dense) {
                 empty_since.clear();
-                recs.push_back(flatten(*kid.second, own_row.data(), empty_since));
+                recs.push_back(flatten(*kid.second, own_row, empty_since));
             } else {
                 recs.push_back(flatten(*kid.second, base, since));
             }
@@ -398,7 +451,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;
-        const ConditionNode rec = F.flatten(*roots[i], nullptr, since);
+        const ConditionNode rec = F.flatten(*roots[i], -1, since);
         root_node[i] = (int)E.nodes.size();                  // a root is stored after its subtree
         E.nodes.push_back(rec);
         roots[i].reset();
