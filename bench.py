@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of apply_mask_vec8_kernel on the default workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by what the counters read on a plain device copy
 # (profiles/apply_mask_vec8_kernel__json-B256-V128256.txt); other workloads report null
-APPLY_TRAFFIC_BYTES = {3: 130.38e6}
+APPLY_TRAFFIC_BYTES = {3: 130.63e6}
 
 
 def main():
