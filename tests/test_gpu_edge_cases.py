@@ -262,6 +262,64 @@ def test_hip_graph_replays_match_eager():
     assert int(err.abs().sum()) == 0
 
 
+def test_hip_graph_of_the_greedy_loop_replays_like_eager():
+    """argmax -> advance+mask -> jump-forward -> mask, captured as one step and replayed: each
+    replay (with fresh logits uploaded eagerly in between) must leave what eager calls leave."""
+    torch, dev = _torch()
+    from workloads import configs
+    cfg = configs.get(2)
+    v = cfg.vocab
+    sch = G.schema_grammar(11, 6, 2, 4).text                  # forced key text gives jump-forward work
+    lib = _lib([sch], v, stack_cap=256)
+    B, V, W, cap, steps = 32, v.n_tokens, v.words, 256, 10
+    s0 = lib.initial_state(0)
+    data = torch.zeros((B, cap), dtype=torch.int32, device=dev)
+    length = torch.ones(B, dtype=torch.int32, device=dev)
+    states = torch.full((B,), s0, dtype=torch.int32, device=dev)
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states, data, length, err)
+    mask = torch.zeros((B, W), dtype=torch.int32, device=dev)
+    tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    jb = torch.zeros((B, 16), dtype=torch.uint8, device=dev)
+    jn = torch.zeros(B, dtype=torch.int32, device=dev)
+    rng = np.random.default_rng(8)
+    all_logits = [torch.from_numpy(bf16_logits(rng, B, V).view(np.int16)).to(dev) for _ in range(steps)]
+    logits = all_logits[0].clone()
+
+    def start():
+        data.zero_(); data[:, 0] = s0; length.fill_(1); states.fill_(s0)
+        lib.fill_mask(states, data, length, mask)
+
+    def one_step():
+        lib.apply_mask_argmax(logits.view(torch.bfloat16), mask, tok)
+        lib.advance_fill_mask(tok, mask)
+        lib.jump_forward(jb, jn)
+        lib.fill_mask(states, data, length, mask)
+
+    start(); one_step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    start()
+    with torch.cuda.graph(g):
+        one_step()
+    ref = []
+    start()
+    for s in range(steps):
+        logits.copy_(all_logits[s])
+        one_step()
+        torch.cuda.synchronize()
+        ref.append(tuple(x.clone() for x in (tok, mask, states, length, data, jn, err)))
+    assert sum(int(r[5].sum()) for r in ref) > 0              # bytes were forced along the way
+    start()
+    for s in range(steps):
+        logits.copy_(all_logits[s])                           # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((tok, mask, states, length, data, jn, err), ref[s]):
+            assert torch.equal(got, want), f"replay {s} differs from the eager step"
+
+
 def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
     """A mask row of more than 56 KiB does not fit the token-edge kernels' LDS bitmap: every call
     must then give the same results through the byte-by-byte kernel."""
