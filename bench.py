@@ -495,6 +495,8 @@ def main():
                    "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
                    "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
         "fill_mask_tokens_per_s": pairs / (float(two_call_us["fill_mask"].mean()) * 1e-6),
+        "initial_stack_depths": ({"min": int(traj.init_len.min() - 1), "mean": float(traj.init_len.mean() - 1),
+                                  "max": int(traj.init_len.max() - 1)} if cfg.mixed else None),
         "mask_apply_us_per_step": mask_apply_us,
         "mask_apply_timing": "pre3_fill_mask + pre3_apply_mask on the recorded stacks of the K timed steps, one HIP graph "
                              "between two HIP events, divided by K; with a pair of events around every launch the two "
