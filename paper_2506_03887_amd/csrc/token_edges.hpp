@@ -17,8 +17,16 @@
 //           undetermined ("walk" list: the kernel walks those byte by byte).
 //
 // A token rejected for every matching stack simply appears nowhere.  At run time a sequence
-// descends the tree by comparing its stack entries with the children's condition states, ORs
-// the deltas on its path and walks the few tokens left.
+// descends the tree by comparing its stack entries with the children's condition states,
+// takes the materialised row of the deepest node that has one (a "dense" row holds everything
+// allowed on the path so far), ORs the deltas of the nodes after it and walks the few tokens
+// left.
+//
+// Storage: by default every node that allows a token of its own has a dense row, and identical
+// rows are stored once; equal groups of sibling nodes (equal subtrees under different parents),
+// equal delta lists and equal walk lists are stored once as well, so the trees form a DAG.
+// Children of a node are consecutive records, sorted by condition state, and are stored before
+// their parent.
 #pragma once
 #include <cstdint>
 #include <vector>
