@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
 // whole block builds the sequence's next mask row (dense row copy, delta lists, leftover walks)
 // and stores it.  The sequence's inputs are loaded once, no kernel boundary separates the two
 // halves, and the long walks of a few sequences overlap the mask building of all others.
-constexpr int kAfBlock = 256;
+constexpr int kAfBlock = 512;
 __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
     int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
