@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <string>
 #include <thread>
@@ -317,6 +318,10 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
         return fail(h, e.status, e.text);
     } catch (const std::bad_alloc &) {
         return fail(h, PRE3_E_NOMEM, "out of host memory");
+    } catch (const std::exception &e) {            // nothing may cross the C boundary
+        return fail(h, PRE3_E_LIMIT, std::string("internal error: ") + e.what());
+    } catch (...) {
+        return fail(h, PRE3_E_LIMIT, "internal error");
     }
     h->compiled = true;
     if (!h->host_only) {

@@ -5,7 +5,9 @@
 #include <atomic>
 #include <cstring>
 #include <map>
+#include <exception>
 #include <memory>
+#include <mutex>
 #include <numeric>
 #include <thread>
 #include <unordered_map>
@@ -431,14 +433,22 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     std::vector<std::unique_ptr<BuildNode>> roots(root_state.size());
     std::atomic<int> node_budget(lim.max_nodes);
     std::atomic<size_t> next(0);
+    std::exception_ptr failure;                      // first exception of a worker, rethrown on the caller's thread
+    std::mutex failure_lock;
     auto worker = [&]() {
-        Walker w(T, trie, pred, lim, node_budget);
-        for (;;) {
-            size_t i = next.fetch_add(1);
-            if (i >= roots.size()) return;
-            roots[i].reset(new BuildNode());
-            w.walk_root(root_state[i], *roots[i]);
-            w.expand(*roots[i]);
+        try {
+            Walker w(T, trie, pred, lim, node_budget);
+            for (;;) {
+                size_t i = next.fetch_add(1);
+                if (i >= roots.size()) return;
+                roots[i].reset(new BuildNode());
+                w.walk_root(root_state[i], *roots[i]);
+                w.expand(*roots[i]);
+            }
+        } catch (...) {
+            std::lock_guard<std::mutex> g(failure_lock);
+            if (!failure) failure = std::current_exception();
+            next.store(roots.size());                // the other workers stop at their next root
         }
     };
     int n_threads = std::max(1, std::min<int>(lim.n_threads, (int)roots.size()));
@@ -446,6 +456,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     for (int i = 1; i < n_threads; ++i) pool.emplace_back(worker);
     worker();
     for (auto &t : pool) t.join();
+    if (failure) std::rethrow_exception(failure);
 
     Flattener F{trie, lim, E, std::max(1, lim.max_path_ids)};
     std::vector<int> root_node(roots.size());
