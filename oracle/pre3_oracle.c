@@ -38,7 +38,13 @@
  * textbook grammars, conflict detection, brute-force enumeration of all strings
  * up to length 8 with an independent (non-LR) recogniser, Dyck == counter,
  * right-linear grammar == DFA, JSON grammar == the json module of the Python
- * standard library, and the prefix/concatenation/EOS invariants.
+ * standard library, and the prefix/concatenation/EOS invariants; the greedy choice
+ * (masked arg max) against numpy's argmax over the candidates and hand cases; the
+ * jump-forward bytes against the forced bytes read off the brute-force sets of
+ * viable prefixes; seeded random grammars against the brute-force recogniser
+ * (tests/test_random_grammars.py); the statements of the paper that can be checked
+ * mechanically (tests/golden/paper_statements.txt, tests/test_golden.py).  No
+ * function here is unpinned.
  */
 #include <stdint.h>
 #include <stdio.h>
