@@ -27,6 +27,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of apply_mask_vec8_kernel on the default workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by what the counters read on a plain device copy
 # (profiles/apply_mask_vec8_kernel__json-B256-V128256.txt); other workloads report null
+GRAMMAR_LABEL = {1: "arithmetic expressions", 2: "byte-level JSON", 3: "byte-level JSON",
+                 4: "schema JSON (12 typed keys)", 5: "8 schema-JSON grammars, mixed",
+                 6: "free text, then byte-level JSON"}
 APPLY_TRAFFIC_BYTES = {3: 130.63e6}
 
 
@@ -92,7 +95,7 @@ def main():
     # ---- inputs: oracle-driven seeded trajectory (host), then everything uploaded
     o = Oracle(cfg.grammars)
     gi, depths = configs.sequence_setup(cfg)
-    traj = trajectory.generate(o, v, B, total, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths)
+    traj = trajectory.generate(o, v, B, total, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
 
     dev = torch.device("cuda:0")
@@ -491,7 +494,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 bitmask / bf16 logits / i32 states",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": "byte-level JSON, canonical LR(1)",
+        "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": GRAMMAR_LABEL.get(cfg.idx, cfg.name) + ", canonical LR(1)",
                    "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
                    "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
         "fill_mask_tokens_per_s": pairs / (float(two_call_us["fill_mask"].mean()) * 1e-6),

@@ -32,7 +32,7 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
     gi, depths = configs.sequence_setup(cfg)
     t0 = time.time()
     traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
-                               cfg.json_strings, depths)
+                               cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
     log(f"[cfg {cfg_idx}] trajectory of {steps} steps in {time.time() - t0:.1f}s; "
         f"{int(traj.reset.sum())} resets, {int((traj.tokens == v.eos_id).sum())} EOS", flush=True)
     lib = make_library(cfg, **lib_options)
@@ -117,7 +117,7 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
     o = Oracle(cfg.grammars)
     gi, depths = configs.sequence_setup(cfg)
     traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
-                               cfg.json_strings, depths)
+                               cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
     # slot reuse in the trajectory == restart right after an EOS token
     assert (traj.reset[1:] == (traj.tokens[:-1] == v.eos_id)).all() and not traj.reset[0].any()
     lib = make_library(cfg, **lib_options)

@@ -66,6 +66,13 @@ def test_cfg5_mixed_grammars_deep_stacks():
     assert max(r["depth_hist"]) >= 60 and len(r["depth_hist"]) > 40
 
 
+def test_cfg6_free_text_then_json_full_size():
+    """The second workload: documents that open with unconstrained text (dense masks) and end in
+    a JSON answer, B=256, V=128256."""
+    r = replay(6, steps=160, full_mask_steps=[0, 1, 30, 80, 159])
+    assert r["full_masks"] == 5 and r["sampled_rows"] == 310
+
+
 def test_advance_fill_mask_all_configs():
     """pre3_advance_fill_mask (advance + next mask in one launch, slot reuse on EOS) on every
     configuration; config 2 also with shallow conditions (leftover walks inside the fused kernel)
@@ -77,6 +84,7 @@ def test_advance_fill_mask_all_configs():
     assert replay_advance_fill(3, steps=96, full_mask_steps=[0, 40, 95])["full_masks"] == 3
     assert replay_advance_fill(4, steps=64, full_mask_steps=[0, 63])["full_masks"] == 2
     assert replay_advance_fill(5, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
+    assert replay_advance_fill(6, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
 
 
 @pytest.mark.parametrize("fused", [False, True])

@@ -177,7 +177,7 @@ def test_device_calls_refuse_a_host_only_handle(vocab):
     assert lib.pre3_apply_mask_argmax(p._h, null, 0, null, null, null) == binding.E_BADARG
 
 
-@pytest.mark.parametrize("cfg_idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg_idx", [1, 2, 3, 4, 5, 6])
 def test_compiled_tables_are_internally_consistent(cfg_idx):
     """The kernels follow table contents without range checks: every index in the tables of the
     five workload configurations must stay inside its table (with each merging level on and off)."""

@@ -152,6 +152,56 @@ def test_json_grammar_equals_json_module(json_oracle):
     assert n_good > 300 and n_bad > 1500
 
 
+def _thought_then_json_ok(data: bytes) -> bool:
+    """The free-text-then-JSON documents, recognised without a grammar: a fixed opening, one to
+    three lines (a space, one or more bytes from 0x20 up, a line feed), a fixed label, then a
+    JSON value that starts right after the label (the json module decides that part)."""
+    if not data.startswith(b"Thought:"):
+        return False
+    rest, n_lines = data[len(b"Thought:"):], 0
+    while rest.startswith(b" "):
+        end = rest.find(b"\n")
+        if end < 2 or min(rest[:end]) < 0x20:
+            return False
+        rest, n_lines = rest[end + 1:], n_lines + 1
+    if not 1 <= n_lines <= 3 or not rest.startswith(b"Answer: "):
+        return False
+    rest = rest[len(b"Answer: "):]
+    return len(rest) > 0 and rest[0] not in b" \t\r\n" and _json_ok(rest)
+
+
+def test_thought_then_json_grammar_equals_a_direct_recogniser():
+    o, rnd = Oracle([G.THOUGHT_THEN_JSON]), random.Random(11)
+    n_good = n_bad = 0
+    for i in range(150):
+        lines = [" " + "".join(rnd.choice('ab {}[]":,\\A\x7f') for _ in range(rnd.randint(1, 9))) + "\n"
+                 for _ in range(rnd.randint(1, 3))]
+        doc = json.dumps(_random_json(rnd), ensure_ascii=True, indent=[None, 1][i % 2])
+        data = ("Thought:" + "".join(lines) + "Answer: " + doc).encode("ascii") + [b"", b" \n"][i % 3 == 0]
+        assert _thought_then_json_ok(data) and o.accepts(data), data
+        for _ in range(16):
+            pos = rnd.randrange(len(data))
+            kind = rnd.randrange(4)
+            if kind == 0:
+                mut = data[:pos] + bytes([rnd.choice(b' \nA"{}[]:,0a\x01\x1f\x20\x7f')]) + data[pos + 1:]
+            elif kind == 1:
+                mut = data[:pos] + data[pos + 1:]
+            elif kind == 2:
+                mut = data[:pos] + bytes([rnd.choice(b' \nA"{[:,0a')]) + data[pos:]
+            else:                                   # one more or one fewer line
+                mut = data.replace(b"\nAnswer", rnd.choice([b"\n x\nAnswer", b"\n \nAnswer", b"Answer"]), 1)
+            expect = _thought_then_json_ok(mut)
+            assert o.accepts(mut) == expect, mut
+            n_good += expect
+            n_bad += not expect
+    assert n_good > 300 and n_bad > 600
+    for text, ok in [(b"Thought: a\nAnswer: 1", True), (b"Thought:\nAnswer: 1", False), (b"Thought: \nAnswer: 1", False),
+                     (b"Thought: a\n b\n c\nAnswer: []", True), (b"Thought: a\n b\n c\n d\nAnswer: []", False),
+                     (b"Thought: a\nAnswer:  1", False), (b"Thought: a\nAnswer: ", False),
+                     (b"Thought: a\n Answer: 1\nAnswer: 2 ", True), (b"Thought: \xff\x20\nAnswer: null", True)]:
+        assert _thought_then_json_ok(text) == ok and o.accepts(text) == ok, text
+
+
 @pytest.mark.parametrize("text,ok", [
     (b"0", True), (b"-0", True), (b"01", False), (b"-", False), (b"1.", False), (b".5", False),
     (b"1e5", True), (b"1E+5", True), (b"1e", False), (b"1.5e-3", True), (b"--1", False),

@@ -1,4 +1,4 @@
-"""The five seeded synthetic workload configurations (inputs only)."""
+"""The seeded synthetic workload configurations (inputs only)."""
 from __future__ import annotations
 
 from dataclasses import dataclass
@@ -26,6 +26,8 @@ class Config:
     mixed: bool = False       # sequences on different grammars with deep seeded stacks
     seed: int = 0
     notes: dict = None
+    marker: bytes = b""       # container nesting is counted only after these bytes (free text first)
+    p_line_feed: float = 0.0  # chance that a draw prefers the tokens that hold a line feed
 
 
 # (n_keys, depth, n_enum, extra_objects) of the eight schema grammars of config 5, chosen so the
@@ -55,6 +57,9 @@ def get(idx: int) -> Config:
         return Config(5, "mixed8-B256-V128256", [s.text for s in sgs],
                       bpe_like_vocab(128256, 32, seed), 256, 512, nest_cap=10, mixed=True, seed=seed,
                       notes=dict(alternatives=[s.n_alternatives for s in sgs]))
+    if idx == 6:
+        return Config(6, "thought-json-B256-V128256", [G.THOUGHT_THEN_JSON], bpe_like_vocab(128256, 32, seed),
+                      256, 256, nest_cap=10, seed=seed, marker=G.THOUGHT_THEN_JSON_MARKER, p_line_feed=0.125)
     raise KeyError(idx)
 
 

@@ -60,6 +60,23 @@ value    ::= object ws | array ws | string ws | number ws | "true" ws | "false" 
     + _JSON_LEXICAL_RULES
 )
 
+# Free text, then JSON: one to three lines of unconstrained text (any byte from 0x20 up), each
+# opened by a space and closed by a line feed, then the answer as a JSON value.  After a line
+# feed one byte decides: a space opens another line, "A" opens the answer.
+THOUGHT_THEN_JSON = (
+    r'''
+doc      ::= "Thought:" lines "Answer: " value
+lines    ::= line | line line | line line line
+line     ::= " " text "\n"
+text     ::= tchar | text tchar
+tchar    ::= [^\x00-\x1f]
+value    ::= object ws | array ws | string ws | number ws | "true" ws | "false" ws | "null" ws
+'''
+    + _JSON_VALUE_RULES
+    + _JSON_LEXICAL_RULES
+)
+THOUGHT_THEN_JSON_MARKER = b"\nA"      # the first bytes that cannot belong to the free text
+
 # Small grammars used by the oracle's pins.
 DRAGON_CC = r'''
 S ::= C C

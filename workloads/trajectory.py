@@ -12,7 +12,9 @@ Rules of the recipe:
   * tokens that would raise container nesting (unclosed { or [ outside strings, or
     unclosed parentheses) above `nest_cap`, or the stack above `len_cap` entries, are
     not drawn;
-  * the draw is uniform over the remaining allowed tokens: candidates are the tokens whose
+  * a workload of line-structured text sets `p_line_feed`: with that probability the draw is
+    first tried among the allowed tokens that contain a line feed (uniformly), so that lines end;
+  * otherwise the draw is uniform over the remaining allowed tokens: candidates are the tokens whose
     first byte is viable (found by asking the checker about the one-byte tokens), sampled
     by rejection, then by enumeration if rejection keeps failing.
 """
@@ -35,24 +37,33 @@ class Trajectory:
 
 
 class _Lexer:
-    """Tracks container nesting of the emitted text: { [ ( outside JSON strings."""
+    """Tracks container nesting of the emitted text: { [ ( outside JSON strings.  With a
+    `marker`, nothing counts until the text has contained the marker's bytes (a workload whose
+    documents open with free text that must not be read as containers)."""
 
-    __slots__ = ("in_string", "escape", "depth")
+    __slots__ = ("in_string", "escape", "depth", "marker", "matched")
 
-    def __init__(self):
+    def __init__(self, marker: bytes = b""):
         self.in_string = False
         self.escape = False
         self.depth = 0
+        self.marker = marker
+        self.matched = 0              # bytes of the marker seen so far; len(marker) = counting
 
     def copy(self):
-        c = _Lexer()
-        c.in_string, c.escape, c.depth = self.in_string, self.escape, self.depth
+        c = _Lexer(self.marker)
+        c.in_string, c.escape, c.depth, c.matched = self.in_string, self.escape, self.depth, self.matched
         return c
 
     def feed(self, data: bytes, strings: bool):
         """Returns the maximum depth reached while reading `data`."""
         peak = self.depth
         for c in data:
+            if self.matched < len(self.marker):
+                # the markers in use start with a byte that occurs nowhere else in them, so a
+                # mismatch can only restart the match at that first byte
+                self.matched = self.matched + 1 if c == self.marker[self.matched] else int(c == self.marker[0])
+                continue
             if self.in_string:
                 if self.escape:
                     self.escape = False
@@ -80,20 +91,23 @@ def _first_byte_buckets(vocab):
 
 class Driver:
     def __init__(self, checker, vocab, batch, cap, seed, grammar_idx=None, nest_cap=10,
-                 len_cap=None, json_strings=True, p_eos=0.5):
+                 len_cap=None, json_strings=True, p_eos=0.5, marker=b"", p_line_feed=0.0):
         self.ck, self.vocab, self.B, self.cap = checker, vocab, batch, cap
         self.rng = np.random.default_rng(seed)
         self.grammar_idx = (np.zeros(batch, dtype=np.int32) if grammar_idx is None
                             else np.asarray(grammar_idx, dtype=np.int32))
         self.nest_cap, self.len_cap = nest_cap, (cap if len_cap is None else len_cap)
-        self.json_strings, self.p_eos = json_strings, p_eos
+        self.json_strings, self.p_eos, self.marker = json_strings, p_eos, marker
         self.buckets = _first_byte_buckets(vocab)
+        self.p_line_feed = p_line_feed
+        self.line_feed_tokens = (np.array([t for t, tok in enumerate(vocab.tokens) if b"\n" in tok and t != vocab.eos_id],
+                                          dtype=np.int32) if p_line_feed > 0 else None)
         # does the vocabulary hold every single byte as ids 0..255 (byte fallback)?
         self.byte_fallback = vocab.n_tokens > 256 and all(vocab.tokens[b] == bytes([b]) for b in range(256))
         self.states = np.zeros(batch, dtype=np.int32)
         self.data = np.zeros((batch, cap), dtype=np.int32)
         self.len = np.ones(batch, dtype=np.int32)
-        self.lex = [_Lexer() for _ in range(batch)]
+        self.lex = [_Lexer(marker) for _ in range(batch)]
         for b in range(batch):
             self._reset(b)
 
@@ -102,7 +116,7 @@ class Driver:
         self.data[b, 0] = s0
         self.len[b] = 1
         self.states[b] = s0
-        self.lex[b] = _Lexer()
+        self.lex[b] = _Lexer(self.marker)
 
     def _fits(self, b, t):
         tok = self.vocab.tokens[t]
@@ -116,6 +130,11 @@ class Driver:
         stack = self.data[b, : self.len[b]]
         if self.ck.eos_allowed(stack) and (last_step or self.rng.random() < self.p_eos):
             return self.vocab.eos_id
+        if self.p_line_feed > 0 and self.rng.random() < self.p_line_feed:
+            ok = self.line_feed_tokens[self.ck.allowed_many(stack, self.vocab, self.line_feed_tokens)]
+            for t in self.rng.permutation(ok):
+                if self._fits(b, int(t)):
+                    return int(t)
         if self.byte_fallback:
             viable = np.flatnonzero(self.ck.allowed_many(stack, self.vocab, np.arange(256, dtype=np.int32)))
             cand = np.concatenate([self.buckets[c] for c in viable]) if len(viable) else np.zeros(0, np.int32)
@@ -185,8 +204,10 @@ class Driver:
 
 
 def generate(checker, vocab, batch, steps, cap, seed, grammar_idx=None, nest_cap=10, len_cap=None,
-             json_strings=True, target_depths=None, progress=None) -> Trajectory:
-    drv = Driver(checker, vocab, batch, cap, seed, grammar_idx, nest_cap, len_cap, json_strings)
+             json_strings=True, target_depths=None, progress=None, marker=b"",
+             p_line_feed=0.0) -> Trajectory:
+    drv = Driver(checker, vocab, batch, cap, seed, grammar_idx, nest_cap, len_cap, json_strings, marker=marker,
+                 p_line_feed=p_line_feed)
     if target_depths is not None:
         drv.warm_to_depths(target_depths)
     init_data, init_len = drv.data.copy(), drv.len.copy()
