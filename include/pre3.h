@@ -61,6 +61,11 @@ typedef enum {
                                  /* edges: walks follow one reduction step at a time             */
 #define PRE3_FLAG_NO_TOKEN_EDGES 2 /* do not precompute token-level edges: pre3_fill_mask then     */
                                  /* walks every (sequence, token) pair byte by byte              */
+#define PRE3_FLAG_COMPACT_CYCLES 8 /* cycle-aware stacks (Sec. 3.2.3; Alg. 1 step 1): every call that */
+                                 /* changes the bound stacks (pre3_advance, pre3_advance_fill_mask,  */
+                                 /* pre3_jump_forward) afterwards takes complete traversals of       */
+                                 /* reduction cycles out of them, see pre3_n_reduction_cycles.       */
+                                 /* Needs stack_cap <= 4096                                          */
 
 typedef struct pre3_handle pre3_handle;     /* opaque; owns host and device tables */
 typedef void *pre3_stream;                  /* hipStream_t */
@@ -219,6 +224,32 @@ int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t 
 int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int32_t max_bytes, pre3_stream stream);
 
 /* ---- host-side introspection of the compiled tables (used by tests and tools) ---- */
+
+/* Reduction cycles (Sec. 3.2.3: cycles with the reduction problem; Alg. 1 step 1).  A cycle is
+ * registered for a right-recursive production  A -> X1..Xn A  (1 <= n <= 64) and states
+ * v1 = GOTO(vn, X1), v2 = GOTO(v1, X2), .., vn = GOTO(v(n-1), Xn) when
+ *   - every kernel item of v1 is an item of A with the dot after its first symbol,
+ *   - the kernel of r = GOTO(vn, A) holds only the finished item  A -> X1..Xn A . , and
+ *   - r reduces on every lookahead that a kernel item of v1 carries.
+ * Then a stack  .. v1 .. vn v1 rest  accepts exactly the continuations of  .. v1 rest : whatever
+ * looks below the upper v1 goes to r, pops the traversal and repeats one traversal lower before
+ * the next byte is consumed.  With PRE3_FLAG_COMPACT_CYCLES the stacks are kept in the normal
+ * form that results from rebuilding them bottom-up and, after each entry v1, dropping the n
+ * entries below it while they equal v1..vn of a cycle headed by v1 (cycles of one head tried
+ * shortest first, then in ascending order of their states, from the first again after a match).
+ * Masks, err and DONE are those of the uncompacted stacks; len and the entries differ, and a
+ * right-recursive list of any length keeps a bounded stack.  (The paper pops the traversal on the
+ * cycle's back-edge; for cycles that are not of this shape, such as nesting, dropping a traversal
+ * would forget the depth, so none is registered.)
+ * pre3_n_reduction_cycles: number of registered cycles over all grammars.
+ * pre3_reduction_cycle: writes the states v1..vn (global ids) of cycle `index` (ordered by v1,
+ * then as tried) to out_states[0..out_cap) and returns n; BADARG if n > out_cap. */
+int32_t pre3_n_reduction_cycles(const pre3_handle *h);
+int32_t pre3_reduction_cycle(const pre3_handle *h, int32_t index, int32_t *out_states, int32_t out_cap);
+/* Host evaluation of the normal form on the uploaded cycle tables: compacts stack[0..len) in place
+ * and returns the new length (tests check the tables with it; the device path is the kernel). */
+int32_t pre3_debug_compact(const pre3_handle *h, int32_t *stack, int32_t len);
+
 
 int32_t pre3_n_grammars(const pre3_handle *h);
 int32_t pre3_n_states(const pre3_handle *h);            /* total over all grammars */

@@ -56,6 +56,9 @@ def _load():
         ("pre3o_allowed", [vp, vp, i32, vp, i32]),
         ("pre3o_eos_allowed", [vp, vp, i32]),
         ("pre3o_advance", [vp, vp, vp, i32, vp, i32]),
+        ("pre3o_n_cycles", [vp, i32]),
+        ("pre3o_cycle", [vp, i32, i32, vp]),
+        ("pre3o_compact", [vp, vp, i32]),
     ]:
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = args
@@ -75,6 +78,8 @@ def _load():
     lib.pre3o_jump_forward.argtypes = [vp, vp, vp, i32, i32, vp]
     lib.pre3o_jump_forward_batch.restype = None
     lib.pre3o_jump_forward_batch.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.pre3o_compact_batch.restype = None
+    lib.pre3o_compact_batch.argtypes = [vp, vp, vp, i32, i32]
     lib.pre3o_advance_batch.restype = None
     lib.pre3o_advance_batch.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, vp]
     _lib = lib
@@ -92,9 +97,12 @@ def _ptr(a: np.ndarray):
 class Oracle:
     """Canonical LR(1) tables of one or several grammars (disjoint union of state ids)."""
 
-    def __init__(self, grammars):
+    def __init__(self, grammars, compact_cycles: bool = False):
+        """compact_cycles: every advance (single, batched, jump-forward) is followed by the
+        compaction of Sec. 3.2.3 (`compact`), as a library compiled with that option does."""
         if isinstance(grammars, str):
             grammars = [grammars]
+        self.compact_cycles = bool(compact_cycles)
         lib = _load()
         arr = (ctypes.c_char_p * len(grammars))(*[g.encode("latin-1") for g in grammars])
         err = ctypes.create_string_buffer(512)
@@ -169,6 +177,8 @@ class Oracle:
         ln = np.array([n], dtype=np.int32)
         buf = np.frombuffer(bytes(data) + b"\0", dtype=np.uint8)
         rc = self._lib.pre3o_advance(self._h, _ptr(st), _ptr(ln), cap, _ptr(buf), len(data))
+        if rc == 0 and self.compact_cycles:
+            ln[0] = self._lib.pre3o_compact(self._h, _ptr(st), int(ln[0]))
         return rc, st[: ln[0]].tolist()
 
     def jump_forward(self, stack, max_bytes: int = 64, cap: int = 1 << 20):
@@ -180,6 +190,8 @@ class Oracle:
         ln = np.array([n], dtype=np.int32)
         out = np.zeros(max(1, max_bytes), dtype=np.uint8)
         k = self._lib.pre3o_jump_forward(self._h, _ptr(st), _ptr(ln), cap, int(max_bytes), _ptr(out))
+        if self.compact_cycles:
+            ln[0] = self._lib.pre3o_compact(self._h, _ptr(st), int(ln[0]))
         return out[:k].tobytes(), st[: ln[0]].tolist()
 
     def jump_forward_batch(self, states, data, length, max_bytes: int):
@@ -190,7 +202,30 @@ class Oracle:
         cnt = np.zeros(B, dtype=np.int32)
         self._lib.pre3o_jump_forward_batch(self._h, _ptr(states), _ptr(data), _ptr(length), cap, B, int(max_bytes),
                                            _ptr(out), _ptr(cnt))
+        if self.compact_cycles:
+            self.compact_batch(data, length)
         return out[:, :max_bytes], cnt
+
+    def cycles(self, g=0):
+        """Reduction cycles of grammar g (Sec. 3.2.3), each a list of GLOBAL state ids v1..vn."""
+        out, buf = [], np.zeros(64, dtype=np.int32)
+        off = self.initial_state(g)
+        for k in range(self._lib.pre3o_n_cycles(self._h, g)):
+            n = self._lib.pre3o_cycle(self._h, g, k, _ptr(buf))
+            out.append((buf[:n] + off).tolist())
+        return out
+
+    def compact(self, stack):
+        """The stack without the complete cycle traversals it need not keep (Alg. 1 step 1)."""
+        st = np.array(stack, dtype=np.int32)
+        n = self._lib.pre3o_compact(self._h, _ptr(st), len(st))
+        return st[:n].tolist()
+
+    def compact_batch(self, data, length):
+        """In place on data/length: every stack of the batch in normal form."""
+        B, cap = data.shape
+        assert data.flags.c_contiguous and data.dtype == np.int32 and length.dtype == np.int32
+        self._lib.pre3o_compact_batch(self._h, _ptr(data), _ptr(length), cap, B)
 
     def accepts(self, text: bytes, g=0) -> bool:
         """Is `text` a sentence of grammar g?"""
@@ -238,6 +273,8 @@ class Oracle:
         self._lib.pre3o_advance_batch(self._h, _ptr(states), _ptr(data), _ptr(length), cap, batch,
                                       _ptr(tokens), _ptr(vocab.bytes), _ptr(vocab.offsets),
                                       vocab.n_tokens, vocab.eos_id, _ptr(err))
+        if self.compact_cycles:
+            self.compact_batch(data, length)
         return err
 
 

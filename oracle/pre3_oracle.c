@@ -76,6 +76,10 @@ typedef struct {
     int *act_arg;           /* [n_states][N_TERM]: shift target or production */
     int *go;                /* [n_states][n_nt], -1 = none */
     int *n_items;           /* [n_states] size of each closed item set */
+    /* reduction cycles (Sec. 3.2.3): cycle k has cyc_len[k] states cyc_state[cyc_off[k] ..],
+     * local ids, ordered by (first state, length, states) */
+    int n_cycles;
+    int *cyc_len, *cyc_off, *cyc_state;
 } grammar_t;
 
 typedef struct {
@@ -531,6 +535,94 @@ static int set_action(grammar_t *G, int s, int a, int kind, int arg, char *err, 
 
 /* Canonical collection (App. A.2 "Construction Algorithm") and the ACTION / GOTO
  * tables (App. A.2 "Parsing with the Canonical LR(1) Automaton"). */
+/* ---------------------------------------------------------- reduction cycles */
+
+/* Sec. 3.2.3 and Alg. 1 step 1 pop a complete traversal of a cycle "with the reduction
+ * problem" that "corresponds to recursive reduction of a nonterminal A".  The reading taken
+ * here (the paper does not define the terms): a production  A -> X1 .. Xn A  and item sets
+ * v1 .. vn with  GOTO(vn, X1) = v1, GOTO(v1, X2) = v2, .., GOTO(v(n-1), Xn) = vn,  such that
+ *   (a) every kernel item (dot not at the left end) of v1 is [A -> Y . delta, a]: an item of A
+ *       with the dot after one symbol;
+ *   (b) every kernel item of r = GOTO(vn, A) is [A -> X1 .. Xn A ., a];
+ *   (c) for every kernel item [.., a] of v1 the item [A -> X1 .. Xn A ., a] is in r.
+ * Why a stack  .. v1 .. vn v1 rest  then accepts the same continuations as  .. v1 rest : the
+ * parser looks below the upper v1 only by finishing a kernel item of it, which by (a) pops
+ * down to the entry under v1 and goes to A from there: from vn that is r, where by (b) and
+ * (c) the same lookahead reduces A -> X1..Xn A, pops r and the traversal v1..vn and goes to A
+ * again from the entry below -- the very configuration the shorter stack reached directly. */
+static int set_has(const itemset_t *S, int prod, int dot, int la) {
+    for (int k = 0; k < S->n; k++)
+        if (S->it[k].prod == prod && S->it[k].dot == dot && S->it[k].la == la) return 1;
+    return 0;
+}
+
+static int cycle_cmp(const int *a, int na, const int *b, int nb) {
+    if (a[0] != b[0]) return a[0] < b[0] ? -1 : 1;
+    if (na != nb) return na < nb ? -1 : 1;
+    for (int i = 0; i < na; i++)
+        if (a[i] != b[i]) return a[i] < b[i] ? -1 : 1;
+    return 0;
+}
+
+#define MAX_CYCLE_STATES 64      /* longer cycles are not registered */
+
+static void find_cycles(grammar_t *G, const itemset_t *states, int n_states, const int *delta, int n_sym) {
+    int cap = 16, total = 0;
+    G->n_cycles = 0;
+    G->cyc_len = (int *)malloc(sizeof(int) * (size_t)cap);
+    G->cyc_off = (int *)malloc(sizeof(int) * (size_t)cap);
+    G->cyc_state = (int *)malloc(sizeof(int) * (size_t)cap * MAX_CYCLE_STATES);
+    for (int p = 1; p < G->n_prod; p++) {
+        const prod_t *P = &G->prod[p];
+        int n = P->len - 1;
+        if (n < 1 || n > MAX_CYCLE_STATES || P->rhs[n] != NT_BASE + P->lhs) continue;
+        for (int vn = 0; vn < n_states; vn++) {
+            int found = 0;
+            for (int k = 0; k < states[vn].n && !found; k++)
+                found = states[vn].it[k].prod == p && states[vn].it[k].dot == n;
+            if (!found) continue;
+            int path[MAX_CYCLE_STATES], v = vn;
+            for (int i = 0; i < n && v >= 0; i++) { v = delta[(size_t)v * n_sym + P->rhs[i]]; path[i] = v; }
+            if (v != vn) continue;
+            const itemset_t *V1 = &states[path[0]];
+            int r = delta[(size_t)vn * n_sym + NT_BASE + P->lhs];
+            if (r < 0) continue;
+            const itemset_t *R = &states[r];
+            int ok = 1;
+            for (int k = 0; k < V1->n && ok; k++) {
+                item_t x = V1->it[k];
+                if (x.dot == 0) continue;                              /* closure item */
+                ok = G->prod[x.prod].lhs == P->lhs && x.dot == 1       /* (a) */
+                     && set_has(R, p, n + 1, x.la);                    /* (c) */
+            }
+            for (int k = 0; k < R->n && ok; k++)
+                if (R->it[k].dot > 0) ok = R->it[k].prod == p && R->it[k].dot == n + 1;   /* (b) */
+            if (!ok) continue;
+            /* insert in order, skipping a duplicate */
+            int at = 0, dup = 0;
+            while (at < G->n_cycles) {
+                int c = cycle_cmp(G->cyc_state + G->cyc_off[at], G->cyc_len[at], path, n);
+                if (c == 0) dup = 1;
+                if (c >= 0) break;
+                at++;
+            }
+            if (dup) continue;
+            if (G->n_cycles == cap) {
+                cap *= 2;
+                G->cyc_len = (int *)realloc(G->cyc_len, sizeof(int) * (size_t)cap);
+                G->cyc_off = (int *)realloc(G->cyc_off, sizeof(int) * (size_t)cap);
+                G->cyc_state = (int *)realloc(G->cyc_state, sizeof(int) * (size_t)cap * MAX_CYCLE_STATES);
+            }
+            for (int k = G->n_cycles; k > at; k--) { G->cyc_len[k] = G->cyc_len[k - 1]; G->cyc_off[k] = G->cyc_off[k - 1]; }
+            G->cyc_len[at] = n;
+            G->cyc_off[at] = total;
+            memcpy(G->cyc_state + total, path, sizeof(int) * (size_t)n);
+            total += n;
+            G->n_cycles++;
+        }
+    }
+}
+
 static int build_tables(grammar_t *G, char *err, int errlen) {
     first_t F;
     compute_first(G, &F);
@@ -615,6 +707,7 @@ static int build_tables(grammar_t *G, char *err, int errlen) {
         }
     }
 
+    if (rc == 0) find_cycles(G, states, n, delta, n_sym);
     for (int i = 0; i < cap; i++) free(states[i].it);
     free(states); free(hashes); free(delta); free(J.it); free(after_dot);
     free(C.prod_off); free(C.seen); free(F.nullable); free(F.first);
@@ -628,6 +721,7 @@ static void free_grammar(grammar_t *G) {
     for (int p = 0; p < G->n_prod; p++) free(G->prod[p].rhs);
     free(G->prod);
     free(G->act_kind); free(G->act_arg); free(G->go); free(G->n_items);
+    free(G->cyc_len); free(G->cyc_off); free(G->cyc_state);
     free(G);
 }
 
@@ -928,4 +1022,48 @@ void pre3o_advance_batch(const oracle_t *O, int32_t *states, int32_t *data, int3
         if (r != 0) { err[b] = r; continue; }
         states[b] = stack[len[b] - 1];
     }
+}
+
+/* ----------------------------------------------------- cycle-aware stacks */
+
+int pre3o_n_cycles(const oracle_t *O, int g) { return O->g[g]->n_cycles; }
+
+/* Copies the states (local ids) of cycle k of grammar g to out; returns their number. */
+int pre3o_cycle(const oracle_t *O, int g, int k, int32_t *out) {
+    const grammar_t *G = O->g[g];
+    for (int i = 0; i < G->cyc_len[k]; i++) out[i] = G->cyc_state[G->cyc_off[k] + i];
+    return G->cyc_len[k];
+}
+
+/* The stack in normal form (Sec. 3.2.3: the stack never keeps a complete traversal of a
+ * cycle under the state that starts the next one).  The stack is rebuilt from the bottom, one
+ * push at a time; after a push of v1, while the entries under it spell v1 .. vn of a cycle that
+ * starts with v1 (cycles tried in their stored order, from the first again after a match), those
+ * n entries are popped and v1 pushed back -- the modified back-edge of Alg. 1 step 1.
+ * Returns the new length. */
+int pre3o_compact(const oracle_t *O, int32_t *stack, int len) {
+    if (len < 1) return len;
+    int g = grammar_of(O, stack[0]);
+    if (g < 0) return len;
+    const grammar_t *G = O->g[g];
+    int off = O->offset[g], w = 0;
+    for (int r = 0; r < len; r++) {
+        int32_t x = stack[r];
+        stack[w++] = x;                                  /* push */
+        int k = 0;
+        while (k < G->n_cycles) {
+            const int *c = G->cyc_state + G->cyc_off[k];
+            int n = G->cyc_len[k], match = c[0] + off == x && w - 1 - n >= 0;
+            for (int i = 0; match && i < n; i++) match = stack[w - 1 - n + i] == c[i] + off;
+            if (match) { w -= n; k = 0; }                /* pop v1..vn and the top, push v1 */
+            else k++;
+        }
+    }
+    return w;
+}
+
+/* Normal form of every stack of a batch (finished sequences included: their stacks are kept). */
+void pre3o_compact_batch(const oracle_t *O, int32_t *data, int32_t *len, int cap, int batch) {
+    for (int b = 0; b < batch; b++)
+        if (len[b] >= 1 && len[b] <= cap) len[b] = pre3o_compact(O, data + (size_t)b * cap, len[b]);
 }

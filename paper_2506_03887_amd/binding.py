@@ -19,6 +19,7 @@ E_BADARG, E_PARSE, E_NOT_LR1, E_TOKEN_TOO_LONG, E_NOMEM, E_HIP, E_LIMIT = -1, -2
 FLAG_HOST_ONLY = 1
 FLAG_NO_TOKEN_EDGES = 2
 FLAG_STEPWISE_REDUCTIONS = 4
+FLAG_COMPACT_CYCLES = 8
 ADVANCE_RESTART_ON_EOS = 1
 STATE_DONE = -1
 
@@ -27,6 +28,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
+    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact",
 ]
 
 
@@ -79,7 +81,10 @@ def load():
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
     lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
-    for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound"):
+    lib.pre3_reduction_cycle.argtypes = [vp, i32, vp, i32]
+    lib.pre3_debug_compact.argtypes = [vp, vp, i32]
+    for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound",
+                 "pre3_n_reduction_cycles"):
         getattr(lib, name).argtypes = [vp]
     lib.pre3_byte_class.argtypes = [vp, i32]
     lib.pre3_debug_validate_tables.argtypes = [vp]
@@ -120,7 +125,7 @@ class Pre3:
     def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
                  max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False,
                  token_edges: bool = True, max_condition_depth: int = 0, merged_reductions: bool = True,
-                 row_threshold: int = 0):
+                 row_threshold: int = 0, compact_cycles: bool = False):
         lib = load()
         if isinstance(grammars, str):
             grammars = [grammars]
@@ -130,7 +135,8 @@ class Pre3:
         voc = _Vocab(vb.ctypes.data, vo.ctypes.data, len(vo) - 1, eos_id)
         opt = _Options(max_token_len, stack_cap,
                        (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES)
-                       | (0 if merged_reductions else FLAG_STEPWISE_REDUCTIONS),
+                       | (0 if merged_reductions else FLAG_STEPWISE_REDUCTIONS)
+                       | (FLAG_COMPACT_CYCLES if compact_cycles else 0),
                        max_condition_depth, row_threshold)
         h = ctypes.c_void_p()
         rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
@@ -204,6 +210,25 @@ class Pre3:
         if rc < 0:
             raise Pre3Error(rc, "debug_advance")
         return rc, st[: ln.value].tolist()
+
+    def reduction_cycles(self):
+        """The registered reduction cycles, each a list of global state ids v1..vn."""
+        out = []
+        buf = np.zeros(64, dtype=np.int32)
+        for i in range(self._lib.pre3_n_reduction_cycles(self._h)):
+            n = self._lib.pre3_reduction_cycle(self._h, i, buf.ctypes.data, len(buf))
+            if n < 0:
+                raise Pre3Error(n, "reduction_cycle")
+            out.append(buf[:n].tolist())
+        return out
+
+    def debug_compact(self, stack):
+        """Host evaluation of the compaction normal form on the compiled cycle tables."""
+        st = np.array(stack, dtype=np.int32)
+        n = self._lib.pre3_debug_compact(self._h, st.ctypes.data, len(st))
+        if n < 0:
+            raise Pre3Error(n, "debug_compact")
+        return st[:n].tolist()
 
     def validate_tables(self) -> int:
         """Number of out-of-range indices in the compiled tables (0 expected)."""

@@ -345,6 +345,77 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
     if (lane == 0) out_len[b] = count;
 }
 
+
+// Cycle-aware stack compaction (Sec. 3.2.3; Alg. 1 step 1): a complete traversal v1..vn of a
+// registered reduction cycle that lies right below another v1 carries no information and is taken
+// out.  The stack is rebuilt entry by entry from the bottom; after each entry that is the head of a
+// cycle, the n entries under it are compared with the cycle's states and dropped on a match (then
+// the check repeats).  One wave per sequence, the stack staged in LDS; control flow is uniform over
+// the wave, lanes share the comparisons and the block moves.  A stack without any cycle head, the
+// usual case, costs one pass over its entries and writes nothing.
+__global__ __launch_bounds__(64) void compact_stacks_kernel(const int32_t *__restrict__ cycle_head,
+                                                            const int32_t *__restrict__ cycle_pool, int n_states,
+                                                            int32_t *__restrict__ data, int32_t *__restrict__ len,
+                                                            int cap, int batch) {
+    __shared__ int32_t s[kCompactMaxLen];
+    const int lane = threadIdx.x, b = blockIdx.x;
+    if (b >= batch) return;
+    const int n = len[b];
+    if (n < 2 || n > cap || n > kCompactMaxLen) return;
+    int32_t *row = data + (size_t)b * cap;
+    bool any = false;
+    for (int i = lane; i < n; i += 64) {
+        const int x = row[i];
+        s[i] = x;
+        any |= (unsigned)x < (unsigned)n_states && cycle_head[x] >= 0;
+    }
+    if (!__any(any)) return;
+    __builtin_amdgcn_wave_barrier();
+    int w = 0;                                          // entries of the rebuilt stack so far
+    for (int r0 = 0; r0 < n; r0 += 64) {
+        const int cnt = n - r0 < 64 ? n - r0 : 64;
+        const int x = lane < cnt ? s[r0 + lane] : -1;
+        const int hd = (unsigned)x < (unsigned)n_states ? cycle_head[x] : -1;
+        unsigned long long heads = __ballot(hd >= 0);
+        if (heads == 0 && w == r0) { w += cnt; continue; }
+        int prev = 0;                                   // entries of this chunk already moved
+        for (;;) {
+            const int j = heads ? __ffsll((long long)heads) - 1 : cnt - 1;   // the segment prev..j ends at a head or at the chunk's end
+            const int seg = j - prev + 1;
+            if (seg > 0) {
+                if (w != r0 + prev) {                   // all lanes read, then all lanes write: the ranges may overlap
+                    const int v = lane < seg ? s[r0 + prev + lane] : 0;
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane < seg) s[w + lane] = v;
+                    __builtin_amdgcn_wave_barrier();
+                }
+                w += seg;
+            }
+            if (!heads) break;
+            heads &= heads - 1;
+            prev = j + 1;
+            const int first = __shfl(hd, j);            // s[w - 1] is the head of these cycles
+            int h = first;
+            while (h >= 0) {
+                const int k = __builtin_amdgcn_readfirstlane(cycle_pool[h]);
+                const int next = __builtin_amdgcn_readfirstlane(cycle_pool[h + 1]);
+                bool match = false;
+                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == cycle_pool[h + 2 + lane]);
+                if (match) {
+                    w -= k;                             // the top stays: s[w - 1] held the same state
+                    h = first;
+                } else {
+                    h = next;
+                }
+            }
+        }
+    }
+    if (w != n) {
+        for (int i = lane; i < w; i += 64) row[i] = s[i];
+        if (lane == 0) len[b] = w;
+    }
+}
+
 }  // namespace
 
 size_t advance_scratch_entries(int batch, int max_depth) {
@@ -382,6 +453,14 @@ hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *dat
     hipLaunchKernelGGL(jump_forward_kernel, dim3((batch + kJfSeqPerBlock - 1) / kJfSeqPerBlock), dim3(64 * kJfSeqPerBlock),
                        0, stream, T, states, data, len, cap, batch, out_bytes, out_len, max_bytes, adv_scratch, lane_spill,
                        (size_t)batch * 64);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int n_states, int32_t *data,
+                                 int32_t *len, int cap, int batch, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(compact_stacks_kernel, dim3(batch), dim3(64), 0, stream, cycle_head, cycle_pool, n_states, data, len,
+                       cap, batch);
     return hipGetLastError();
 }
 

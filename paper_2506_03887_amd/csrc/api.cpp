@@ -52,6 +52,9 @@ struct pre3_handle {
     size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
     size_t adv_scratch_entries = 0;
+    // stack compaction over reduction cycles (PRE3_FLAG_COMPACT_CYCLES)
+    bool compact = false;
+    const int32_t *cycle_head = nullptr, *cycle_pool = nullptr;
 };
 
 namespace {
@@ -256,10 +259,24 @@ int upload_tables(pre3_handle *h) {
         h->edge_spill = static_cast<int32_t *>(p);
         h->use_edges = true;
     }
+    if (h->compact) {
+        if ((e = upload(h, h->T.cycle_head, &h->cycle_head)) != hipSuccess) return hip_fail(h, e, "upload cycle_head");
+        std::vector<int32_t> pool = h->T.cycle_pool;
+        if (pool.empty()) pool.push_back(0);
+        if ((e = upload(h, pool, &h->cycle_pool)) != hipSuccess) return hip_fail(h, e, "upload cycle_pool");
+    }
     return PRE3_OK;
 }
 
 bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
+
+// After a call that changed the bound stacks: take complete traversals of reduction cycles out
+// again (only with PRE3_FLAG_COMPACT_CYCLES and a grammar that has such cycles).
+hipError_t compact_bound_stacks(pre3_handle *h, hipStream_t s) {
+    if (!h->compact || h->T.n_cycles == 0) return hipSuccess;
+    return launch_compact_stacks(h->cycle_head, h->cycle_pool, h->T.n_states, h->b_stacks.data, h->b_stacks.len,
+                                 h->b_stacks.cap, h->b_stacks.batch, s);
+}
 
 // (grammar, local state) of a global state id
 bool locate(const pre3_handle *h, int state, int *g, int *local) {
@@ -287,6 +304,13 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
     int max_token_len = opt && opt->max_token_len ? opt->max_token_len : 64;
     h->stack_cap = opt && opt->stack_cap ? opt->stack_cap : 1024;
     h->host_only = opt && (opt->flags & PRE3_FLAG_HOST_ONLY);
+    h->compact = opt && (opt->flags & PRE3_FLAG_COMPACT_CYCLES);
+    if (opt && (opt->flags & ~(PRE3_FLAG_HOST_ONLY | PRE3_FLAG_NO_TOKEN_EDGES | PRE3_FLAG_STEPWISE_REDUCTIONS |
+                               PRE3_FLAG_COMPACT_CYCLES)))
+        return fail(h, PRE3_E_BADARG, "unknown flag in options");
+    if (h->compact && h->stack_cap > kCompactMaxLen)
+        return fail(h, PRE3_E_BADARG, "stack compaction handles stacks of at most " + std::to_string(kCompactMaxLen) +
+                                          " entries: lower stack_cap");
     if (max_token_len < 1 || max_token_len > 254 || h->stack_cap < 1)
         return fail(h, PRE3_E_BADARG, "max_token_len must be in 1..254 and stack_cap positive");
     try {
@@ -440,6 +464,7 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
     if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
     hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                                   h->b_stacks.batch, h->b_err, h->adv_scratch, 0, static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance");
 }
 
@@ -457,10 +482,12 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
         e = launch_advance_fill(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                 h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
                                 h->af_walk_spill, s);
+        if (e == hipSuccess) e = compact_bound_stacks(h, s);       // equivalent stacks: the mask just built stays right
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
     }
     e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                        h->b_stacks.batch, h->b_err, h->adv_scratch, restart, s);
+    if (e == hipSuccess) e = compact_bound_stacks(h, s);
     if (e != hipSuccess) return hip_fail(h, e, "launch advance");
     return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);
 }
@@ -487,6 +514,7 @@ int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int3
     hipError_t e = launch_jump_forward(h->dev, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                                        h->b_stacks.batch, out_bytes, out_len, max_bytes, h->adv_scratch,
                                        h->af_walk_spill, static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch jump_forward");
 }
 
@@ -517,6 +545,40 @@ int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt) {
     if (!locate(h, state, &g, &local) || nt < 0 || nt >= h->T.automata[g].n_nt) return PRE3_E_BADARG;
     int row = h->T.goto_row[state];
     return row < 0 ? -1 : h->T.goto_flat[row + nt];
+}
+
+int32_t pre3_n_reduction_cycles(const pre3_handle *h) { return h && h->compiled ? h->T.n_cycles : PRE3_E_BADARG; }
+
+int32_t pre3_reduction_cycle(const pre3_handle *h, int32_t index, int32_t *out_states, int32_t out_cap) {
+    if (!h || !h->compiled || index < 0 || index >= h->T.n_cycles || !out_states) return PRE3_E_BADARG;
+    int i = 0;                                  // records in head order, each chain shortest first
+    for (int head = 0; head < h->T.n_states; ++head)
+        for (int at = h->T.cycle_head[head]; at >= 0; at = h->T.cycle_pool[at + 1], ++i)
+            if (i == index) {
+                const int n = h->T.cycle_pool[at];
+                if (n > out_cap) return PRE3_E_BADARG;
+                for (int k = 0; k < n; ++k) out_states[k] = h->T.cycle_pool[at + 2 + k];
+                return n;
+            }
+    return PRE3_E_BADARG;
+}
+
+int32_t pre3_debug_compact(const pre3_handle *h, int32_t *stack, int32_t len) {
+    if (!h || !h->compiled || !stack || len < 1) return PRE3_E_BADARG;
+    int w = 0;
+    for (int r = 0; r < len; ++r) {
+        const int x = stack[r];
+        stack[w++] = x;
+        if (x < 0 || x >= h->T.n_states) continue;
+        for (int at = h->T.cycle_head[x]; at >= 0;) {
+            const int n = h->T.cycle_pool[at];
+            bool match = w - 1 - n >= 0;
+            for (int k = 0; match && k < n; ++k) match = stack[w - 1 - n + k] == h->T.cycle_pool[at + 2 + k];
+            if (match) { w -= n; at = h->T.cycle_head[x]; }
+            else at = h->T.cycle_pool[at + 1];
+        }
+    }
+    return w;
 }
 
 int32_t pre3_walk_depth_bound(const pre3_handle *h) { return h && h->compiled ? h->max_depth : PRE3_E_BADARG; }

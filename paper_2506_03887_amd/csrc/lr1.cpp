@@ -113,6 +113,64 @@ std::string kernel_key(const std::vector<KernelItem> &k) {
     return s;
 }
 
+// Cycles with the reduction problem (Sec. 3.2.3): a production  A -> X1..Xn A  whose states
+// v1 = GOTO(vn, X1), .., vn = GOTO(v(n-1), Xn) close a cycle.  Each traversal leaves v1..vn on the
+// stack and all of them are popped, one traversal per reduction by that production, when the
+// list ends.  Dropping one traversal from under a top v1 is sound when
+//   (1) every kernel item of v1 is an A-item with the dot after its first symbol, so the only
+//       reductions that look below v1 expose exactly the entry under it and then go to A;
+//   (2) from vn that goto leads to a state r whose kernel is only the finished  A -> X1..Xn A . ,
+//       so the next move pops the whole traversal and repeats the goto one traversal lower;
+//   (3) r reduces on every lookahead a kernel item of v1 carries (the reduction that brought the
+//       parser to r was made on such a lookahead).
+// Then both stacks reach the same configuration before the next byte is consumed.
+void find_reduction_cycles(const Grammar &g, const Builder &B, const std::vector<std::vector<KernelItem>> &kernels,
+                           Lr1Automaton &out) {
+    const int n_nt = g.n_nt();
+    auto step = [&](int s, int x) -> int {
+        if (x >= kNtBase) return out.go[(size_t)s * n_nt + (x - kNtBase)];
+        const uint32_t a = out.action[(size_t)s * kNumTerminals + x];
+        return (a & 3u) == kShift ? (int)(a >> 2) : -1;
+    };
+    for (size_t p = 1; p < g.prods.size(); ++p) {
+        const auto &rhs = g.prods[p].rhs;
+        const int n = (int)rhs.size() - 1, A = g.prods[p].lhs;
+        if (n < 1 || n > kMaxCycleStates || rhs[n] != kNtBase + A) continue;
+        const int64_t before_tail = B.core_of[p] + n;
+        for (int u = 0; u < out.n_states; ++u) {
+            bool has = false;
+            for (const KernelItem &it : kernels[u]) has |= it.core == before_tail;
+            if (!has) continue;
+            std::vector<int32_t> path;
+            int v = u;
+            for (int i = 0; i < n && v >= 0; ++i) {
+                v = step(v, rhs[i]);
+                path.push_back(v);
+            }
+            if (v != u) continue;
+            bool ok = true;
+            for (const KernelItem &it : kernels[path[0]])
+                ok &= B.core_dot[it.core] == 1 && g.prods[B.core_prod[it.core]].lhs == A;
+            const int r = step(u, kNtBase + A);
+            if (!ok || r < 0) continue;
+            TermSet reduces;
+            for (const KernelItem &it : kernels[r]) {
+                ok &= it.core == before_tail + 1;
+                reduces.add_all(it.la);
+            }
+            for (const KernelItem &it : kernels[path[0]]) {
+                TermSet both = reduces;
+                ok &= !both.add_all(it.la);           // nothing new: it.la is a subset
+            }
+            if (ok) out.cycles.push_back(path);
+        }
+    }
+    std::sort(out.cycles.begin(), out.cycles.end(), [](const std::vector<int32_t> &a, const std::vector<int32_t> &b) {
+        return a.size() != b.size() ? a.size() < b.size() : a < b;
+    });
+    out.cycles.erase(std::unique(out.cycles.begin(), out.cycles.end()), out.cycles.end());
+}
+
 }  // namespace
 
 Lr1Automaton build_lr1(const Grammar &g) {
@@ -220,6 +278,7 @@ Lr1Automaton build_lr1(const Grammar &g) {
         }
     }
     out.n_states = (int)kernels.size();
+    find_reduction_cycles(g, B, kernels, out);
     return out;
 }
 

@@ -17,7 +17,13 @@ struct Lr1Automaton {
     // go[s * n_nt + A] = target state or -1
     std::vector<int32_t> go;
     std::vector<int32_t> prod_lhs, prod_len;
+    // Cycles of right-recursive reductions (Sec. 3.2.3, Alg. 1 step 1): each entry lists the
+    // states v1..vn of one cycle; a stack whose top is v1 with v1..vn right below it behaves
+    // like the stack without those n entries.  Sorted by (length, states).
+    std::vector<std::vector<int32_t>> cycles;
 };
+
+constexpr int kMaxCycleStates = 64;     // longer cycles are not registered
 
 // States are numbered in breadth-first discovery order from the initial item set, trying
 // terminals in ascending byte order and then nonterminals by index.  Throws CompileError

@@ -173,6 +173,19 @@ EdgeTables build_edge_tables(const std::vector<Grammar> &grammars) {
     T.goto_flat.insert(T.goto_flat.end(), (size_t)max_nt + 1, -1);
 
     T.height_per_byte = height_per_symbol(T);
+    T.cycle_head.assign(T.n_states, -1);
+    for (int g = 0; g < T.n_grammars; ++g) {
+        const auto &cycles = T.automata[g].cycles;      // sorted by (length, states)
+        for (size_t k = cycles.size(); k-- > 0;) {      // prepend, so that chains run shortest first
+            const int head = T.state_offset[g] + cycles[k][0];
+            const int at = (int)T.cycle_pool.size();
+            T.cycle_pool.push_back((int32_t)cycles[k].size());
+            T.cycle_pool.push_back(T.cycle_head[head]);
+            for (int32_t v : cycles[k]) T.cycle_pool.push_back(T.state_offset[g] + v);
+            T.cycle_head[head] = at;
+            ++T.n_cycles;
+        }
+    }
     return T;
 }
 

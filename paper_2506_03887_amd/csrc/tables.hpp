@@ -39,6 +39,12 @@ struct EdgeTables {
     std::vector<int32_t> state_kind;       // [n_states]
     int n_kinds = 0;
     int height_per_byte = 1;               // H: most private entries one input symbol can add, plus 1
+    // Reduction cycles of all grammars (global state ids).  cycle_head[v1] = offset of the first
+    // record whose cycle starts with v1, or -1; a record is  n, offset of the next record with the
+    // same head (or -1), v1..vn.  Records of one head are chained shortest first.
+    std::vector<int32_t> cycle_head;       // [n_states]
+    std::vector<int32_t> cycle_pool;
+    int n_cycles = 0;
 };
 
 struct VocabLayout {

@@ -11,7 +11,8 @@ from workloads.vocab import bf16_logits
 def make_library(cfg, **kw):
     from paper_2506_03887_amd import Pre3
     v = cfg.vocab
-    return Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cfg.cap, **kw)
+    return Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cfg.cap,
+                compact_cycles=cfg.compact, **kw)
 
 
 def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, log=print, **lib_options):
@@ -28,7 +29,7 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
     cfg = configs.get(cfg_idx)
     v = cfg.vocab
     steps = cfg.steps if steps is None else steps
-    o = Oracle(cfg.grammars)
+    o = Oracle(cfg.grammars, compact_cycles=cfg.compact)
     gi, depths = configs.sequence_setup(cfg)
     t0 = time.time()
     traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
@@ -114,7 +115,7 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
     cfg = configs.get(cfg_idx)
     v = cfg.vocab
     steps = cfg.steps if steps is None else steps
-    o = Oracle(cfg.grammars)
+    o = Oracle(cfg.grammars, compact_cycles=cfg.compact)
     gi, depths = configs.sequence_setup(cfg)
     traj = trajectory.generate(o, v, cfg.batch, steps, cfg.cap, cfg.seed, gi, cfg.nest_cap, None,
                                cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)

@@ -28,6 +28,7 @@ class Config:
     notes: dict = None
     marker: bytes = b""       # container nesting is counted only after these bytes (free text first)
     p_line_feed: float = 0.0  # chance that a draw prefers the tokens that hold a line feed
+    compact: bool = False     # stacks are kept without complete traversals of reduction cycles
 
 
 # (n_keys, depth, n_enum, extra_objects) of the eight schema grammars of config 5, chosen so the
@@ -60,6 +61,9 @@ def get(idx: int) -> Config:
     if idx == 6:
         return Config(6, "thought-json-B256-V128256", [G.THOUGHT_THEN_JSON], bpe_like_vocab(128256, 32, seed),
                       256, 256, nest_cap=10, seed=seed, marker=G.THOUGHT_THEN_JSON_MARKER, p_line_feed=0.125)
+    if idx == 7:
+        return Config(7, "json-right-recursive-B256-V128256", [G.JSON_RIGHT_RECURSIVE],
+                      bpe_like_vocab(128256, 32, seed), 256, 256, nest_cap=10, seed=seed, compact=True)
     raise KeyError(idx)
 
 

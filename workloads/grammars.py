@@ -77,6 +77,38 @@ value    ::= object ws | array ws | string ws | number ws | "true" ws | "false" 
 )
 THOUGHT_THEN_JSON_MARKER = b"\nA"      # the first bytes that cannot belong to the free text
 
+# The same JSON language with every list written right-recursively (members, elements, string
+# characters, digits, white space): the LR stack then grows with the length of each list until
+# the list ends -- the shape that the cycle-aware stacks of Sec. 3.2.3 are for.
+JSON_RIGHT_RECURSIVE = r'''
+json     ::= ws value
+value    ::= object ws | array ws | string ws | number ws | "true" ws | "false" ws | "null" ws
+object   ::= "{" ws "}" | "{" ws members "}"
+members  ::= member | member "," ws members
+member   ::= string ws ":" ws value
+array    ::= "[" ws "]" | "[" ws elements "]"
+elements ::= value | value "," ws elements
+string   ::= "\"" chars "\""
+chars    ::= "" | char chars
+char     ::= plain | "\\" escape
+plain    ::= [^"\\\x00-\x1f]
+escape   ::= simple | "u" hex hex hex hex
+simple   ::= ["\\/bfnrt]
+hex      ::= [0-9a-fA-F]
+number   ::= sign int frac exp
+sign     ::= "" | "-"
+int      ::= "0" | onenine | onenine digits
+digits   ::= digit | digit digits
+digit    ::= [0-9]
+onenine  ::= [1-9]
+frac     ::= "" | "." digits
+exp      ::= "" | e esign digits
+e        ::= [eE]
+esign    ::= "" | [+\-]
+ws       ::= "" | wsc ws
+wsc      ::= [ \t\n\r]
+'''
+
 # Small grammars used by the oracle's pins.
 DRAGON_CC = r'''
 S ::= C C
