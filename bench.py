@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of apply_mask_vec8_kernel on the default workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE scaled by what the counters read on a plain device copy
 # (profiles/apply_mask_vec8_kernel__json-B256-V128256.txt); other workloads report null
-GRAMMAR_LABEL = {1: "arithmetic expressions", 2: "byte-level JSON", 3: "byte-level JSON",
+GRAMMAR_LABEL = {7: "byte-level JSON, every list right-recursive", 1: "arithmetic expressions", 2: "byte-level JSON", 3: "byte-level JSON",
                  4: "schema JSON (12 typed keys)", 5: "8 schema-JSON grammars, mixed",
                  6: "free text, then byte-level JSON"}
 APPLY_TRAFFIC_BYTES = {3: 130.63e6}
@@ -47,6 +47,8 @@ def main():
                     help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
     ap.add_argument("--no-token-edges", action="store_true",
                     help="compile without token-level edges: fill_mask walks every (sequence, token) pair")
+    ap.add_argument("--no-compact", action="store_true",
+                    help="a workload that keeps cycle-aware stacks is run without them (stacks then grow with every list)")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
@@ -93,7 +95,8 @@ def main():
     total = K + Wm
 
     # ---- inputs: oracle-driven seeded trajectory (host), then everything uploaded
-    o = Oracle(cfg.grammars)
+    compact = cfg.compact and not args.no_compact
+    o = Oracle(cfg.grammars, compact_cycles=compact)
     gi, depths = configs.sequence_setup(cfg)
     traj = trajectory.generate(o, v, B, total, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
@@ -101,7 +104,7 @@ def main():
     dev = torch.device("cuda:0")
     t_compile = time.perf_counter()
     lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
-               token_edges=not args.no_token_edges)
+               token_edges=not args.no_token_edges, compact_cycles=compact)
     t_compile = time.perf_counter() - t_compile
     data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
     states_h = data_h[np.arange(B), len_h - 1].copy()
@@ -302,7 +305,7 @@ def main():
         (the path the token-level edges replace), on the recorded stacks of the first steps."""
         snaps = recorded_stacks()
         plain = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
-                     token_edges=False)
+                     token_edges=False, compact_cycles=compact)
         m2 = torch.empty_like(mask_d)
         times = []
         for s in range(min(n_calls, K)):
@@ -365,6 +368,7 @@ def main():
     assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), \
         "device state after the timed run differs from the oracle's replay"
     assert int(err_d.abs().sum().item()) == 0
+    stack_len_after = {"mean": float(len_h.mean()), "max": int(len_h.max())}
     # and the last mask on the device is the oracle's mask of the last timed step's input state
     restore()
     for s in range(K - 1):
@@ -520,6 +524,8 @@ def main():
         "jump_forward": None if args.eager else jump_forward_leg(),
         "fill_mask_byte_by_byte": None if (args.eager or args.no_token_edges) else byte_by_byte_leg(),
         "compile_s": t_compile,
+        "stacks": {"cycle_aware": bool(compact), "reduction_cycles": len(lib.reduction_cycles()),
+                   "len_after_timed_steps": stack_len_after},
         "token_edges": lib.token_edge_stats(),
     }
     print(json.dumps(out))

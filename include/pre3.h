@@ -65,7 +65,9 @@ typedef enum {
                                  /* changes the bound stacks (pre3_advance, pre3_advance_fill_mask,  */
                                  /* pre3_jump_forward) afterwards takes complete traversals of       */
                                  /* reduction cycles out of them, see pre3_n_reduction_cycles.       */
-                                 /* Needs stack_cap <= 4096                                          */
+                                 /* Needs stack_cap <= 4096.  The token-level edges are then built   */
+                                 /* for compacted stacks: pre3_fill_mask stays exact on any valid     */
+                                 /* stack, but one that was never compacted takes the slow walk       */
 
 typedef struct pre3_handle pre3_handle;     /* opaque; owns host and device tables */
 typedef void *pre3_stream;                  /* hipStream_t */
@@ -189,6 +191,7 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream);
  * PRE3_ADVANCE_RESTART_ON_EOS a sequence that takes EOS restarts from data[b*cap] with len 1),
  * bitmask (device, [batch, ceil(n_tokens/32)]) as pre3_fill_mask then writes it for the new
  * stacks.  A sequence whose advance fails keeps its stack and gets the mask of that stack.
+ * (With PRE3_FLAG_COMPACT_CYCLES the stacks are compacted before the mask is looked up.)
  * Errors: BADARG (nothing bound, null pointer, unknown flag). */
 int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,
                            pre3_stream stream);

@@ -350,18 +350,24 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
 // registered reduction cycle that lies right below another v1 carries no information and is taken
 // out.  The stack is rebuilt entry by entry from the bottom; after each entry that is the head of a
 // cycle, the n entries under it are compared with the cycle's states and dropped on a match (then
-// the check repeats).  One wave per sequence, the stack staged in LDS; control flow is uniform over
-// the wave, lanes share the comparisons and the block moves.  A stack without any cycle head, the
-// usual case, costs one pass over its entries and writes nothing.
-__global__ __launch_bounds__(64) void compact_stacks_kernel(const int32_t *__restrict__ cycle_head,
-                                                            const int32_t *__restrict__ cycle_pool, int n_states,
-                                                            int32_t *__restrict__ data, int32_t *__restrict__ len,
-                                                            int cap, int batch) {
-    __shared__ int32_t s[kCompactMaxLen];
-    const int lane = threadIdx.x, b = blockIdx.x;
+// the check repeats).  One wave per sequence, the stack staged in LDS (cap entries per wave) next to
+// a copy of the cycle records (pool_n entries; 0 = read them from global memory); control flow is
+// uniform over the wave, lanes share the comparisons and the block moves.  A stack without any
+// cycle head costs one pass over its entries and writes nothing.
+__global__ __launch_bounds__(256) void compact_stacks_kernel(const int32_t *__restrict__ cycle_head,
+                                                             const int32_t *__restrict__ cycle_pool, int pool_n,
+                                                             int n_states, int32_t *__restrict__ data,
+                                                             int32_t *__restrict__ len, int cap, int batch) {
+    extern __shared__ int32_t compact_lds[];
+    for (int i = threadIdx.x; i < pool_n; i += blockDim.x) compact_lds[i] = cycle_pool[i];
+    __syncthreads();
+    const int32_t *pool = pool_n > 0 ? compact_lds : cycle_pool;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int b = blockIdx.x * (blockDim.x >> 6) + wave;
     if (b >= batch) return;
     const int n = len[b];
-    if (n < 2 || n > cap || n > kCompactMaxLen) return;
+    if (n < 2 || n > cap) return;
+    int32_t *s = compact_lds + pool_n + wave * cap;
     int32_t *row = data + (size_t)b * cap;
     bool any = false;
     for (int i = lane; i < n; i += 64) {
@@ -397,10 +403,10 @@ __global__ __launch_bounds__(64) void compact_stacks_kernel(const int32_t *__res
             const int first = __shfl(hd, j);            // s[w - 1] is the head of these cycles
             int h = first;
             while (h >= 0) {
-                const int k = __builtin_amdgcn_readfirstlane(cycle_pool[h]);
-                const int next = __builtin_amdgcn_readfirstlane(cycle_pool[h + 1]);
+                const int k = __builtin_amdgcn_readfirstlane(pool[h]);
+                const int next = __builtin_amdgcn_readfirstlane(pool[h + 1]);
                 bool match = false;
-                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == cycle_pool[h + 2 + lane]);
+                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == pool[h + 2 + lane]);
                 if (match) {
                     w -= k;                             // the top stays: s[w - 1] held the same state
                     h = first;
@@ -456,11 +462,16 @@ hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *dat
     return hipGetLastError();
 }
 
-hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int n_states, int32_t *data,
-                                 int32_t *len, int cap, int batch, hipStream_t stream) {
+hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int pool_entries, int n_states,
+                                 int32_t *data, int32_t *len, int cap, int batch, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    hipLaunchKernelGGL(compact_stacks_kernel, dim3(batch), dim3(64), 0, stream, cycle_head, cycle_pool, n_states, data, len,
-                       cap, batch);
+    if (cap > kCompactMaxLen) return hipErrorInvalidValue;
+    const int pool_n = pool_entries <= 1024 ? pool_entries : 0;         // small record pools are staged in LDS
+    int waves = 4;                                                      // sequences per block, within 64 KB of LDS
+    while (waves > 1 && (size_t)(pool_n + waves * cap) * sizeof(int32_t) > 65536) waves >>= 1;
+    const size_t lds = (size_t)(pool_n + waves * cap) * sizeof(int32_t);
+    hipLaunchKernelGGL(compact_stacks_kernel, dim3((batch + waves - 1) / waves), dim3(64 * waves), lds, stream, cycle_head,
+                       cycle_pool, pool_n, n_states, data, len, cap, batch);
     return hipGetLastError();
 }
 

@@ -274,8 +274,8 @@ bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 // again (only with PRE3_FLAG_COMPACT_CYCLES and a grammar that has such cycles).
 hipError_t compact_bound_stacks(pre3_handle *h, hipStream_t s) {
     if (!h->compact || h->T.n_cycles == 0) return hipSuccess;
-    return launch_compact_stacks(h->cycle_head, h->cycle_pool, h->T.n_states, h->b_stacks.data, h->b_stacks.len,
-                                 h->b_stacks.cap, h->b_stacks.batch, s);
+    return launch_compact_stacks(h->cycle_head, h->cycle_pool, (int)h->T.cycle_pool.size(), h->T.n_states,
+                                 h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap, h->b_stacks.batch, s);
 }
 
 // (grammar, local state) of a global state id
@@ -335,6 +335,7 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
             TokenEdgeLimits lim;
             if (opt && opt->max_condition_depth > 0) lim.max_known = opt->max_condition_depth;
             if (opt && opt->row_threshold > 0) lim.max_path_ids = opt->row_threshold;
+            lim.compacted_stacks = h->compact;
             lim.n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
             h->E = build_token_edges(h->T, h->V, lim);
         }
@@ -478,11 +479,12 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
     const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (h->use_edges) {
+    // With cycle-aware stacks the mask is looked up after the compaction (the condition trees are
+    // built for compacted stacks only), so the call takes the three launches below.
+    if (h->use_edges && !(h->compact && h->T.n_cycles > 0)) {
         e = launch_advance_fill(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                 h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
                                 h->af_walk_spill, s);
-        if (e == hipSuccess) e = compact_bound_stacks(h, s);       // equivalent stacks: the mask just built stays right
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
     }
     e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
@@ -634,6 +636,21 @@ int pre3_debug_validate_tables(const pre3_handle *h) {
         need(r < (int)T.goto_flat.size());
     }
     for (int32_t t : T.goto_flat) need(t < T.n_states);
+    // reduction cycles: chains of records inside the pool, states in range, every record headed by its chain's state
+    need((int)T.cycle_head.size() == T.n_states);
+    int64_t records = 0;
+    for (int s = 0; s < T.n_states && bad == 0; ++s)
+        for (int at = T.cycle_head[s], guard = 0; at >= 0 && bad == 0; at = T.cycle_pool[at + 1]) {
+            need(at + 2 < (int)T.cycle_pool.size() && ++guard <= T.n_cycles);
+            if (bad) break;
+            const int n = T.cycle_pool[at];
+            need(n >= 1 && n <= kMaxCycleStates && at + 2 + n <= (int)T.cycle_pool.size() && T.cycle_pool[at + 1] < (int)T.cycle_pool.size());
+            if (bad) break;
+            need(T.cycle_pool[at + 2] == s);
+            for (int k = 0; k < n; ++k) need(T.cycle_pool[at + 2 + k] >= 0 && T.cycle_pool[at + 2 + k] < T.n_states);
+            ++records;
+        }
+    need(records == T.n_cycles);
     // merged reduction edges
     const SymbolEdges &S = h->S;
     if (S.enabled) {

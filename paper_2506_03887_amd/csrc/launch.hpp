@@ -40,10 +40,9 @@ hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *dat
                                uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
                                int32_t *lane_spill, hipStream_t stream);
 
-// Stack compaction over registered reduction cycles; handles stacks of at most kCompactMaxLen entries
-// (longer ones are left as they are).
+// Stack compaction over registered reduction cycles; cap (entries per stack) at most kCompactMaxLen.
 constexpr int kCompactMaxLen = 4096;
-hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int n_states, int32_t *data,
-                                 int32_t *len, int cap, int batch, hipStream_t stream);
+hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int pool_entries, int n_states,
+                                 int32_t *data, int32_t *len, int cap, int batch, hipStream_t stream);
 
 }  // namespace pre3

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cstring>
+#include <deque>
 #include <map>
 #include <exception>
 #include <memory>
@@ -103,6 +104,7 @@ struct BuildNode {
     int floor = 0;                              // deepest known state
     std::vector<int32_t> accepted;              // token ids allowed under this node's condition
     std::vector<Pending> pend;
+    std::vector<int32_t> path;                  // known states, top first (kept until the node is expanded)
     std::vector<std::pair<int32_t, std::unique_ptr<BuildNode>>> children;
 };
 
@@ -111,13 +113,12 @@ struct Walker {
     const Trie &trie;
     const std::vector<std::vector<int32_t>> &pred;
     const TokenEdgeLimits &lim;
-    std::atomic<int> &node_budget;
     const int ncol;
     std::vector<std::vector<int32_t>> pool;     // one scratch stack per trie depth
 
     Walker(const EdgeTables &t, const Trie &tr, const std::vector<std::vector<int32_t>> &p,
-           const TokenEdgeLimits &l, std::atomic<int> &budget)
-        : T(t), trie(tr), pred(p), lim(l), node_budget(budget), ncol(t.n_classes + 1), pool(300) {}
+           const TokenEdgeLimits &l)
+        : T(t), trie(tr), pred(p), lim(l), ncol(t.n_classes + 1), pool(300) {}
 
     int goto_of(int state, int nt) const {
         int row = T.goto_row[state];
@@ -186,31 +187,66 @@ struct Walker {
         }
     }
 
-    void expand(BuildNode &nd) {
-        while (!nd.pend.empty()) {
-            const std::vector<int32_t> &ps = pred[nd.floor];
-            if (ps.empty()) { nd.pend.clear(); return; }        // the bottom of a stack is never popped
-            if (nd.known >= lim.max_known) return;              // left to the run-time walk
-            if (ps.size() == 1) {                               // only one stack can lie below: no test needed
-                std::vector<Pending> in;
-                in.swap(nd.pend);
-                resolve(ps[0], in, nd);
-                nd.floor = ps[0];
-                nd.known++;
-                continue;
-            }
-            if (node_budget.fetch_sub((int)ps.size()) < (int)ps.size()) return;
-            for (int X : ps) {
-                std::unique_ptr<BuildNode> ch(new BuildNode());
-                ch->known = nd.known + 1;
-                ch->floor = X;
-                resolve(X, nd.pend, *ch);
-                expand(*ch);
-                nd.children.emplace_back(X, std::move(ch));
-            }
-            nd.pend.clear();
-            return;
+    // With cycle-aware stacks no stack holds a complete traversal v1..vn of a reduction cycle right
+    // below another v1: a condition state X that would complete one under the known entries cannot
+    // occur, so its subtree is not built (a stack that was never compacted finds no child there and
+    // falls back to the walk).  path = the known states, top first.
+    bool excluded_by_compaction(const std::vector<int32_t> &path, int X) const {
+        if (!lim.compacted_stacks) return false;
+        const int size = (int)path.size();
+        for (int at = T.cycle_head[X]; at >= 0; at = T.cycle_pool[at + 1]) {
+            const int n = T.cycle_pool[at];
+            if (size < n || path[size - n] != X) continue;
+            bool same = true;
+            for (int i = 1; i < n && same; ++i) same = path[size - i] == T.cycle_pool[at + 2 + i];
+            if (same) return true;
         }
+        return false;
+    }
+
+    // Expands the nodes waiting in `queue` breadth first until the queue is empty or `budget` nodes
+    // have been created: the tree of one root grows level by level, so when the budget cuts it, it
+    // cuts the deepest conditions (tokens that need them are left to the run-time walk) and never
+    // a shallow one.  Returns the nodes created; a node that did not fit stays at the queue's head.
+    int expand(std::deque<BuildNode *> &queue, int budget) {
+        int used = 0;
+        while (!queue.empty()) {
+            BuildNode &nd = *queue.front();
+            bool wait = false;
+            while (!nd.pend.empty()) {
+                const std::vector<int32_t> &ps = pred[nd.floor];
+                if (ps.empty()) { nd.pend.clear(); break; }        // the bottom of a stack is never popped
+                if (nd.known >= lim.max_known) break;               // left to the run-time walk
+                if (ps.size() == 1) {                               // only one stack can lie below: no test needed
+                    std::vector<Pending> in;
+                    in.swap(nd.pend);
+                    resolve(ps[0], in, nd);
+                    nd.floor = ps[0];
+                    nd.known++;
+                    nd.path.push_back(ps[0]);
+                    continue;
+                }
+                if (used + (int)ps.size() > budget) { wait = true; break; }
+                used += (int)ps.size();
+                for (int X : ps) {
+                    if (excluded_by_compaction(nd.path, X)) continue;
+                    std::unique_ptr<BuildNode> ch(new BuildNode());
+                    ch->known = nd.known + 1;
+                    ch->floor = X;
+                    ch->path = nd.path;
+                    ch->path.push_back(X);
+                    resolve(X, nd.pend, *ch);
+                    queue.push_back(ch.get());
+                    nd.children.emplace_back(X, std::move(ch));
+                }
+                nd.pend.clear();
+                std::vector<int32_t>().swap(nd.path);               // only unexpanded nodes need theirs
+                break;
+            }
+            if (wait) break;
+            queue.pop_front();
+        }
+        return used;
     }
 };
 
@@ -430,33 +466,54 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     }
     E.n_roots = (int64_t)root_state.size();
 
+    // Every root first gets an equal share of the node budget (breadth first, see Walker::expand);
+    // what the finished roots leave over goes, in further rounds, to the roots that were cut.
     std::vector<std::unique_ptr<BuildNode>> roots(root_state.size());
-    std::atomic<int> node_budget(lim.max_nodes);
-    std::atomic<size_t> next(0);
+    std::vector<std::deque<BuildNode *>> queues(root_state.size());
     std::exception_ptr failure;                      // first exception of a worker, rethrown on the caller's thread
     std::mutex failure_lock;
-    auto worker = [&]() {
-        try {
-            Walker w(T, trie, pred, lim, node_budget);
-            for (;;) {
-                size_t i = next.fetch_add(1);
-                if (i >= roots.size()) return;
-                roots[i].reset(new BuildNode());
-                w.walk_root(root_state[i], *roots[i]);
-                w.expand(*roots[i]);
+    int64_t left = lim.max_nodes;
+    std::vector<size_t> todo(roots.size());
+    for (size_t i = 0; i < roots.size(); ++i) todo[i] = i;
+    for (int round = 0; !todo.empty() && left > 0 && !failure; ++round) {
+        const int share = (int)std::max<int64_t>(round == 0 ? 256 : 1, left / (int64_t)todo.size());
+        std::atomic<size_t> next(0);
+        std::atomic<int64_t> used(0);
+        auto worker = [&]() {
+            try {
+                Walker w(T, trie, pred, lim);
+                for (;;) {
+                    const size_t k = next.fetch_add(1);
+                    if (k >= todo.size()) return;
+                    const size_t i = todo[k];
+                    if (!roots[i]) {
+                        roots[i].reset(new BuildNode());
+                        w.walk_root(root_state[i], *roots[i]);
+                        roots[i]->path.assign(1, root_state[i]);
+                        queues[i].push_back(roots[i].get());
+                    }
+                    used += w.expand(queues[i], share);
+                }
+            } catch (...) {
+                std::lock_guard<std::mutex> g(failure_lock);
+                if (!failure) failure = std::current_exception();
+                next.store(todo.size());                 // the other workers stop at their next root
             }
-        } catch (...) {
-            std::lock_guard<std::mutex> g(failure_lock);
-            if (!failure) failure = std::current_exception();
-            next.store(roots.size());                // the other workers stop at their next root
-        }
-    };
-    int n_threads = std::max(1, std::min<int>(lim.n_threads, (int)roots.size()));
-    std::vector<std::thread> pool;
-    for (int i = 1; i < n_threads; ++i) pool.emplace_back(worker);
-    worker();
-    for (auto &t : pool) t.join();
+        };
+        int n_threads = std::max(1, std::min<int>(lim.n_threads, (int)todo.size()));
+        std::vector<std::thread> pool;
+        for (int i = 1; i < n_threads; ++i) pool.emplace_back(worker);
+        worker();
+        for (auto &t : pool) t.join();
+        left -= used.load();
+        std::vector<size_t> cut;
+        for (size_t i : todo)
+            if (!queues[i].empty()) cut.push_back(i);
+        if (used.load() == 0 && round > 0) break;        // the shares no longer buy a level anywhere
+        todo.swap(cut);
+    }
     if (failure) std::rethrow_exception(failure);
+    queues.clear();
 
     Flattener F{trie, lim, E, std::max(1, lim.max_path_ids)};
     std::vector<int> root_node(roots.size());

@@ -61,7 +61,7 @@ struct TokenEdges {
 };
 
 struct TokenEdgeLimits {
-    int max_nodes = 1 << 18;          // condition-tree nodes
+    int max_nodes = 1 << 20;          // condition-tree nodes
     int max_known = 48;               // deepest stack entry a condition may test
     int max_path_ids = 1;             // token ids a descent may collect before a row is materialised
                                       // (1: every node that allows a token of its own has a row; rows
@@ -70,6 +70,7 @@ struct TokenEdgeLimits {
     int max_walk = 2048;              // longest walk list kept per node (longer: whole vocabulary)
     int64_t max_dense_words = (int64_t)1 << 28;   // 1 GiB of dense rows
     int n_threads = 8;
+    bool compacted_stacks = false;    // stacks hold no complete traversal of a reduction cycle (tables.hpp)
 };
 
 TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const TokenEdgeLimits &lim);

@@ -177,13 +177,14 @@ def test_device_calls_refuse_a_host_only_handle(vocab):
     assert lib.pre3_apply_mask_argmax(p._h, null, 0, null, null, null) == binding.E_BADARG
 
 
-@pytest.mark.parametrize("cfg_idx", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cfg_idx", [1, 2, 3, 4, 5, 6, 7])
 def test_compiled_tables_are_internally_consistent(cfg_idx):
     """The kernels follow table contents without range checks: every index in the tables of the
-    five workload configurations must stay inside its table (with each merging level on and off)."""
+    workload configurations must stay inside its table (with each merging level on and off)."""
     from workloads import configs
     cfg = configs.get(cfg_idx)
     v = cfg.vocab
     for kw in (dict(), dict(max_condition_depth=2), dict(merged_reductions=False, token_edges=False)):
-        p = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), host_only=True, **kw)
+        p = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), host_only=True,
+                 compact_cycles=cfg.compact, **kw)
         assert p.validate_tables() == 0

@@ -17,8 +17,9 @@ def _row_bits(row, V):
     return ((row[np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1).astype(bool)
 
 
-def _check_along_trajectory(texts, vocab, steps, batch, seed, nest_cap, grammar_idx=None, **lib_options):
-    o = Oracle(texts)
+def _check_along_trajectory(texts, vocab, steps, batch, seed, nest_cap, grammar_idx=None, compact=False, **lib_options):
+    o = Oracle(texts, compact_cycles=compact)
+    lib_options = dict(lib_options, compact_cycles=compact)
     lib = Pre3(texts, vocab.bytes, vocab.offsets, vocab.eos_id, max_token_len=max(1, vocab.max_len), host_only=True,
                **lib_options)
     assert lib.token_edge_stats()["built"] == 1
@@ -64,6 +65,29 @@ def test_json_rows_equal_oracle_rows(depth_limit):
         assert unresolved == 0 and undecided == 0        # every token became a single edge
     else:
         assert undecided > 0 or unresolved > 0           # shallow limits leave work to the byte-by-byte walk
+
+
+def test_right_recursive_json_rows_on_cycle_aware_stacks():
+    """With cycle-aware stacks the trees leave out conditions that a compacted stack cannot meet:
+    compacted stacks still get exact rows from shallow descents, and a stack that was never
+    compacted gets no answer from the tree (so the kernel walks) rather than a wrong one."""
+    v = bpe_like_vocab(3000, 12, BASE_SEED + 61)
+    resolved, undecided, unresolved, deepest = _check_along_trajectory(
+        [G.JSON_RIGHT_RECURSIVE], v, 40, 6, 5, 6, compact=True)
+    assert resolved > 200 and unresolved == 0 and undecided < resolved     # next to nothing is left to the walk
+    plain = Oracle([G.JSON_RIGHT_RECURSIVE])
+    lib = Pre3([G.JSON_RIGHT_RECURSIVE], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, host_only=True,
+               compact_cycles=True)
+    rc, st = plain.advance(plain.initial_stack(), b'["abcdefgh')
+    assert rc == 0 and len(plain.compact(st)) < len(st)
+    ok, row, walk = lib.debug_resolve_row(np.array(st, dtype=np.int32))
+    want = _row_bits(plain.mask_row(st, v), v.n_tokens)
+    if ok:                                               # whatever the tree does decide must be right
+        left = np.zeros(v.n_tokens, dtype=bool)
+        left[walk] = True
+        assert (_row_bits(row, v.n_tokens)[~left] == want[~left]).all()
+    ok, row, walk = lib.debug_resolve_row(np.array(plain.compact(st), dtype=np.int32))
+    assert ok and len(walk) == 0 and (_row_bits(row, v.n_tokens) == want).all()
 
 
 @pytest.mark.parametrize("threshold", [1, 16, 3000])
