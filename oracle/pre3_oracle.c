@@ -43,8 +43,12 @@
  * jump-forward bytes against the forced bytes read off the brute-force sets of
  * viable prefixes; seeded random grammars against the brute-force recogniser
  * (tests/test_random_grammars.py); the statements of the paper that can be checked
- * mechanically (tests/golden/paper_statements.txt, tests/test_golden.py).  No
- * function here is unpinned.
+ * mechanically (tests/golden/paper_statements.txt, tests/test_golden.py); the
+ * cycle-aware stacks of Sec. 3.2.3 (which cycles are registered: hand-derived cases;
+ * soundness: compacted stacks against the brute-force recogniser on every split of
+ * every short string, curated and seeded random grammars; right-recursive JSON with
+ * compaction against left-recursive JSON: tests/test_oracle_cycles.py).  No function
+ * here is unpinned.
  */
 #include <stdint.h>
 #include <stdio.h>
