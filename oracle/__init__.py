@@ -74,6 +74,8 @@ def _load():
     lib.pre3o_apply_mask.argtypes = [vp, vp, i32, i32, i64]
     lib.pre3o_masked_argmax.restype = None
     lib.pre3o_masked_argmax.argtypes = [vp, vp, i32, i32, i64, vp]
+    lib.pre3o_masked_topk.restype = None
+    lib.pre3o_masked_topk.argtypes = [vp, vp, i32, i32, i64, i32, vp, vp]
     lib.pre3o_jump_forward.restype = i32
     lib.pre3o_jump_forward.argtypes = [vp, vp, vp, i32, i32, vp]
     lib.pre3o_jump_forward_batch.restype = None
@@ -292,3 +294,15 @@ def masked_argmax(logits_u16: np.ndarray, bitmask: np.ndarray, n_tokens: int) ->
     out = np.empty(bm.shape[0], dtype=np.int32)
     _load().pre3o_masked_argmax(_ptr(logits_u16), _ptr(bm), bm.shape[0], int(n_tokens), logits_u16.shape[1], _ptr(out))
     return out
+
+
+def masked_topk(logits_u16: np.ndarray, bitmask: np.ndarray, n_tokens: int, k: int):
+    """Per row the k largest allowed, non-NaN bf16 logits, largest first, equal values by ascending
+    id: (ids [B, k] int32, padded with -1; bf16 patterns [B, k] uint16, padded with 0xFF80)."""
+    assert logits_u16.dtype == np.uint16 and logits_u16.flags.c_contiguous and logits_u16.ndim == 2
+    bm = np.ascontiguousarray(bitmask, dtype=np.uint32)
+    ids = np.empty((bm.shape[0], k), dtype=np.int32)
+    vals = np.empty((bm.shape[0], k), dtype=np.uint16)
+    _load().pre3o_masked_topk(_ptr(logits_u16), _ptr(bm), bm.shape[0], int(n_tokens), logits_u16.shape[1], int(k),
+                              _ptr(ids), _ptr(vals))
+    return ids, vals

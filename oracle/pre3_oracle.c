@@ -965,6 +965,51 @@ void pre3o_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int ba
     }
 }
 
+/* Top-k behind the mask (Sec. 1: invalid tokens are excluded, then a token is sampled; a top-k
+ * sampler draws among the k most probable of what is left): for every row the allowed,
+ * non-NaN tokens ordered by logit as a number, largest first, equal values (+0 = -0) by
+ * ascending id; the first k of them.  out_ids[b][j] = token id, out_vals[b][j] = its bf16
+ * pattern as stored; rows with fewer than k candidates are padded with id -1 and 0xFF80.
+ * Written as the definition: collect the candidates, sort them, cut. */
+typedef struct { float value; int32_t id; } cand_t;
+
+static int cand_cmp(const void *pa, const void *pb) {
+    const cand_t *a = (const cand_t *)pa, *b = (const cand_t *)pb;
+    if (a->value > b->value) return -1;
+    if (a->value < b->value) return 1;
+    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+void pre3o_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int n_tokens,
+                       int64_t row_stride, int k, int32_t *out_ids, uint16_t *out_vals) {
+    int W = (n_tokens + 31) / 32;
+#pragma omp parallel
+    {
+        cand_t *c = (cand_t *)malloc(sizeof(cand_t) * (size_t)(n_tokens > 0 ? n_tokens : 1));
+#pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < batch; b++) {
+            const uint16_t *row = logits + (size_t)b * (size_t)row_stride;
+            int n = 0;
+            for (int t = 0; t < n_tokens; t++) {
+                if (!((bitmask[(size_t)b * W + (t >> 5)] >> (t & 31)) & 1u)) continue;
+                uint32_t bits = (uint32_t)row[t] << 16;
+                float value;
+                memcpy(&value, &bits, sizeof value);
+                if (value != value) continue;     /* NaN */
+                c[n].value = value;
+                c[n].id = t;
+                n++;
+            }
+            qsort(c, (size_t)n, sizeof(cand_t), cand_cmp);
+            for (int j = 0; j < k; j++) {
+                out_ids[(size_t)b * k + j] = j < n ? c[j].id : -1;
+                out_vals[(size_t)b * k + j] = j < n ? row[c[j].id] : 0xFF80;
+            }
+        }
+        free(c);
+    }
+}
+
 /* Jump-forward (Sec. 3.3: runs of edges with a single successor can be merged into one jump):
  * the bytes every continuation of the text must start with.  While the text is not a sentence
  * (the end-of-sequence token is not allowed) and exactly ONE of the 256 bytes keeps it a viable

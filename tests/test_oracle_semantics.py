@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from cfg_brute import languages
-from oracle import Oracle, apply_mask, masked_argmax
+from oracle import Oracle, apply_mask, masked_argmax, masked_topk
 from workloads import grammars as G
 from workloads.vocab import BASE_SEED, arithmetic_vocab, bf16_logits, bpe_like_vocab
 
@@ -413,6 +413,65 @@ def test_masked_argmax_hand_cases():
     assert run({2: ninf, 6: nan}, [6, 2]) == 2
     assert run({2: pinf, 6: two}, [6, 2]) == 2
     assert run({}, []) == -1
+
+
+def test_masked_topk_is_a_stable_numpy_sort_of_the_candidates():
+    # pinned to a library routine: numpy's stable argsort of the negated float32 values over the
+    # allowed, non-NaN entries in id order (stable = equal values keep ascending ids)
+    rng = np.random.default_rng(12)
+    B, V = 10, 3000 + 7
+    logits = bf16_logits(rng, B, V)
+    logits[3] = (np.round(rng.normal(size=V) * 2).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    logits[4, ::3] = 0x0000                                   # zeros of both signs among the largest values
+    logits[4, 1::3] = 0x8000
+    logits[4, 2::3] = 0xBF80
+    logits[5, ::7] = 0x7FC0
+    logits[5, 3::11] = 0xFFC0
+    logits[6, 100] = 0x7F80
+    logits[6, 200:230] = 0xFF80
+    W = (V + 31) // 32
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[7] = 0
+    mask[8] = 0
+    mask[8, 5] = (1 << 9) | (1 << 30)                         # two tokens allowed
+    mask[9] &= rng.integers(0, 2 ** 32, size=W, dtype=np.uint64).astype(np.uint32) & 0x11111111   # sparse
+    bits = _bits_of(mask, V)
+    values = (logits.astype(np.uint32) << 16).view(np.float32)
+    for k in (1, 5, 64):
+        ids, vals = masked_topk(logits, mask, V, k)
+        assert ids.shape == (B, k) and vals.shape == (B, k)
+        for b in range(B):
+            cand = np.flatnonzero(bits[b] & ~np.isnan(values[b]))
+            order = cand[np.argsort(-values[b, cand], kind="stable")][:k]
+            want = np.full(k, -1, dtype=np.int64)
+            want[: len(order)] = order
+            assert ids[b].tolist() == want.tolist(), (k, b)
+            assert vals[b, : len(order)].tolist() == logits[b, order].tolist()
+            assert (vals[b, len(order):] == 0xFF80).all()
+        assert (ids[:, 0] == masked_argmax(logits, mask, V)).all()      # the head of the list is the greedy choice
+    ids, _ = masked_topk(logits, mask, V, 64)
+    assert (ids[7] == -1).all() and ids[8, :2].tolist() == sorted([5 * 32 + 9, 5 * 32 + 30], key=lambda t: (-values[8, t], t))
+    assert (ids[8, 2:] == -1).all()
+
+
+def test_masked_topk_hand_cases():
+    V, W = 40, 2
+    def run(values_u16, allowed, k):
+        logits = np.full((1, V), 0xC000, dtype=np.uint16)     # -2.0 everywhere
+        for t, x in values_u16.items():
+            logits[0, t] = x
+        mask = np.zeros((1, W), dtype=np.uint32)
+        for t in allowed:
+            mask[0, t >> 5] |= np.uint32(1 << (t & 31))
+        ids, vals = masked_topk(logits, mask, V, k)
+        return ids[0].tolist(), vals[0].tolist()
+    one, two, neg0, pos0, nan, ninf, pinf = 0x3F80, 0x4000, 0x8000, 0x0000, 0x7FC1, 0xFF80, 0x7F80
+    assert run({3: one, 9: two, 12: one}, [3, 9, 12, 20], 3) == ([9, 3, 12], [two, one, one])
+    assert run({3: one, 9: two}, [3, 9], 4) == ([9, 3, -1, -1], [two, one, ninf, ninf])
+    assert run({4: neg0, 7: pos0, 9: neg0}, [9, 7, 4], 2) == ([4, 7], [neg0, pos0])     # zeros tie, patterns kept
+    assert run({2: nan, 5: one, 6: ninf}, [2, 5, 6], 3) == ([5, 6, -1], [one, ninf, ninf])
+    assert run({2: pinf, 35: two}, [2, 35, 36], 3) == ([2, 35, 36], [pinf, two, 0xC000])
+    assert run({}, [], 2) == ([-1, -1], [ninf, ninf])
 
 
 def test_arithmetic_workload_vocab_has_the_terminals():
