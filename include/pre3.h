@@ -212,6 +212,21 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
                            int32_t *out_tokens, pre3_stream stream);
 
+#define PRE3_TOPK_MAX 64
+
+/* Top-k behind the mask (Sec. 1: invalid tokens are excluded, then a token is sampled; a top-k or
+ * nucleus sampler only needs the k most probable of what is left).  For every bound sequence b and
+ * j < k:  out_tokens[b*k + j] = the allowed token with the (j+1)-th largest bf16 logit as a number,
+ * equal values (+0 and -0 are equal) in ascending order of id; NaN logits are never listed;
+ * out_logits[b*k + j] (if not null) = that token's bf16 pattern as stored.  Rows with fewer than k
+ * such tokens are padded with -1 and 0xFF80.  out_tokens[b*k] equals the choice of
+ * pre3_apply_mask_argmax.  The logits are read once and not modified (groups of 8 masked tokens
+ * are not read).  1 <= k <= PRE3_TOPK_MAX; layouts and the workspace rule as for
+ * pre3_apply_mask_argmax.  Errors: BADARG (nothing bound, null pointer, row_stride < n_tokens, k out
+ * of range), LIMIT (more than 2,097,152 tokens). */
+int pre3_apply_mask_topk(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
+                         int32_t k, int32_t *out_tokens, uint16_t *out_logits, pre3_stream stream);
+
 /* Jump-forward (Sec. 3.3: runs of edges with a single successor merge into one jump): for every
  * bound, unfinished sequence, the bytes that every continuation of its text must start with.
  * While the end-of-sequence token is not allowed and exactly one of the 256 bytes keeps the text

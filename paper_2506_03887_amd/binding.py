@@ -25,7 +25,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
     "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact",
@@ -80,6 +80,7 @@ def load():
     lib.pre3_advance.argtypes = [vp, vp, vp]
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
+    lib.pre3_apply_mask_topk.argtypes = [vp, vp, c.c_int64, vp, i32, vp, vp, vp]
     lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_reduction_cycle.argtypes = [vp, i32, vp, i32]
     lib.pre3_debug_compact.argtypes = [vp, vp, i32]
@@ -290,6 +291,19 @@ class Pre3:
         assert bitmask.shape[1] == self.words and out_tokens.numel() == logits.shape[0] == bitmask.shape[0]
         self._check(self._lib.pre3_apply_mask_argmax(self._h, _dev(logits, "u16"), logits.stride(0), _dev(bitmask, "u32"),
                                                      _dev(out_tokens, "i32"), _stream_ptr(stream)))
+
+    def apply_mask_topk(self, logits, bitmask, out_tokens, out_logits=None, stream=None):
+        """out_tokens[b, j] = id of the (j+1)-th largest allowed logit of row b (k = out_tokens.shape[1], -1
+        padded), out_logits[b, j] (optional, bf16/int16/uint16) its stored pattern; the logits are only read."""
+        assert logits.dim() == 2 and logits.stride(1) == 1 and bitmask.is_contiguous() and out_tokens.is_contiguous()
+        assert out_tokens.dim() == 2 and out_tokens.shape[0] == logits.shape[0] == bitmask.shape[0]
+        assert bitmask.shape[1] == self.words
+        if out_logits is not None:
+            assert out_logits.is_contiguous() and out_logits.shape == out_tokens.shape
+        self._check(self._lib.pre3_apply_mask_topk(self._h, _dev(logits, "u16"), logits.stride(0), _dev(bitmask, "u32"),
+                                                   out_tokens.shape[1], _dev(out_tokens, "i32"),
+                                                   None if out_logits is None else _dev(out_logits, "u16"),
+                                                   _stream_ptr(stream)))
 
     def jump_forward(self, out_bytes, out_len, stream=None):
         """Forced bytes of every bound sequence into out_bytes [B, max_bytes] (uint8), their counts into

@@ -48,6 +48,8 @@ struct pre3_handle {
     int32_t *af_walk_spill = nullptr;
     unsigned long long *argmax_best = nullptr;   // per-segment partial results of pre3_apply_mask_argmax
     size_t argmax_bytes = 0;
+    unsigned long long *topk_cand = nullptr;     // per-segment candidates of pre3_apply_mask_topk
+    size_t topk_bytes = 0;
     int n_compute_units = 0;
     size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
@@ -396,6 +398,14 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
         h->argmax_best = static_cast<unsigned long long *>(p);
         h->argmax_bytes = need_arg;
     }
+    const size_t need_topk = masked_topk_workspace_bytes(stacks.batch, h->V.n_tokens);
+    if (need_topk > h->topk_bytes) {
+        void *p = nullptr;
+        hipError_t e = device_alloc(h, need_topk, &p, false);
+        if (e != hipSuccess) return hip_fail(h, e, "allocate top-k workspace");
+        h->topk_cand = static_cast<unsigned long long *>(p);
+        h->topk_bytes = need_topk;
+    }
     {   // private stacks of per-lane walks beside an advance (leftover tokens, jump-forward trials)
         size_t need2 = advance_fill_walk_spill_entries(stacks.batch, h->max_depth);
         if (need2 > h->af_walk_spill_entries) {
@@ -505,6 +515,20 @@ int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t 
                                         h->n_compute_units, h->argmax_best, out_tokens,
                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask_argmax");
+}
+
+int pre3_apply_mask_topk(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
+                         int32_t k, int32_t *out_tokens, uint16_t *out_logits, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "apply_mask_topk: no state bound");
+    if (!logits_bf16 || !bitmask || !out_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_topk: null pointer");
+    if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_topk: row stride below vocabulary size");
+    if (k < 1 || k > PRE3_TOPK_MAX) return fail(h, PRE3_E_BADARG, "apply_mask_topk: k outside 1..PRE3_TOPK_MAX");
+    if (h->V.n_tokens > (1 << 21)) return fail(h, PRE3_E_LIMIT, "apply_mask_topk: vocabulary beyond 2,097,152 tokens");
+    hipError_t e = launch_masked_topk(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride, k, h->topk_cand,
+                                      out_tokens, out_logits, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask_topk");
 }
 
 int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int32_t max_bytes, pre3_stream stream) {

@@ -32,6 +32,13 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
 hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                                 int n_compute_units, unsigned long long *workspace, int32_t *out, hipStream_t stream);
 size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);   // per-segment partial results
+// The k largest allowed logits of every row (k <= kTopkMax), ids in out_ids[batch * k] (-1 padded),
+// their bf16 patterns in out_vals (may be null; 0xFF80 padded).
+constexpr int kTopkMax = 64;
+size_t masked_topk_workspace_bytes(int batch, int vocab);
+hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
+                              int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
+                              hipStream_t stream);
 size_t advance_fill_walk_spill_entries(int batch, int max_depth);   // int32 entries
 hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,

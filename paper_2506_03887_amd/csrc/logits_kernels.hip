@@ -230,6 +230,174 @@ __global__ __launch_bounds__(64 * kArgFinishRows) void masked_argmax_finish_kern
     if (lane == 0) out[b] = mine != 0ull ? (int32_t)(0xFFFFFFFFu - (uint32_t)mine) : -1;
 }
 
+
+// ------------------------------------------------------------------- masked top-k
+
+// Order-preserving 16-bit key of a non-NaN bf16 pattern (-0 counts as +0).  Valid values map to
+// 0x007F (-inf) .. 0xFF80 (+inf); 0 is never produced and marks "no candidate".
+__device__ __forceinline__ uint32_t bf16_key(uint32_t h) {
+    if (h == 0x8000u) h = 0u;
+    return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u);
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// The k best candidates of one segment of one row (blockIdx.x = row, blockIdx.y = segment of
+// kTopkSeg tokens): every thread keeps the keys of its 16 tokens in registers (0 = masked, NaN or
+// beyond the vocabulary), so the logits are read once.  The block then finds by bisection on the
+// 16-bit key the largest threshold T that at least kk = min(k, candidates) keys reach, takes every
+// key above T and, of the keys equal to T, the first kk - (number above) in id order (an ordered
+// block scan of the per-thread counts gives each its rank).  The chosen ones are written as
+//   key << 32 | ~id     (distinct words; larger = better value, then smaller id; 0 = empty slot)
+// to out[(row * n_seg + segment) * k ..], in no particular order.
+constexpr int kTopkBlock = 1024;
+constexpr int kTopkSeg = 16 * kTopkBlock;
+__global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
+    const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
+    int n_words, int vec_ok, int k, unsigned long long *__restrict__ out) {
+    __shared__ int s_cnt[kTopkBlock / 64];
+    __shared__ unsigned long long s_out[kTopkMax];
+    __shared__ int s_n;
+    const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
+    const uint16_t *lrow = logits + (size_t)b * row_stride;
+    const int n_mask_bytes = n_words * 4;
+    uint32_t key[16];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int t0 = seg * kTopkSeg + (tid + half * kTopkBlock) * 8;
+        const uint32_t m = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
+        uint32_t h[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = 0x7FC0u;           // NaN: no candidate
+        if (m != 0u) {
+            if (vec_ok && t0 + 8 <= vocab) {
+                const uint4 v = stream_load(lrow + (size_t)t0);
+                const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { h[2 * j] = x[j] & 0xFFFFu; h[2 * j + 1] = x[j] >> 16; }
+            } else {
+                for (int j = 0; j < 8 && t0 + j < vocab; ++j) h[j] = lrow[t0 + j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = ((m >> j) & 1u) && (h[j] & 0x7FFFu) <= 0x7F80u;
+            key[half * 8 + j] = ok ? bf16_key(h[j]) : 0u;
+        }
+    }
+    if (tid == 0) s_n = 0;
+    if (tid < kTopkMax) s_out[tid] = 0ull;
+    auto count_ge = [&](uint32_t T) -> int {                  // keys >= T over the whole block
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c += key[i] >= T ? 1 : 0;
+        c = wave_sum(c);
+        if (lane == 0) s_cnt[wave] = c;
+        __syncthreads();
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < kTopkBlock / 64; ++w) total += s_cnt[w];
+        __syncthreads();
+        return total;
+    };
+    const int candidates = count_ge(1u);
+    const int kk = candidates < k ? candidates : k;
+    unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
+    if (kk == 0) {
+        if (tid < k) dst[tid] = 0ull;
+        return;
+    }
+    uint32_t lo = 1u, hi = 0x10000u;                          // count_ge(lo) >= kk > count_ge(hi) = above
+    int above = 0;
+    while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const int c = count_ge(mid);
+        if (c >= kk) lo = mid;
+        else { hi = mid; above = c; }
+    }
+    const uint32_t T = lo;
+    const int need_equal = kk - above;                        // >= 1, and at least that many keys equal T
+    // rank of every key equal to T in id order: the first halves of all threads come before the second halves
+    int e0 = 0, e1 = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { e0 += key[i] == T ? 1 : 0; e1 += key[8 + i] == T ? 1 : 0; }
+    int packed = e0 | (e1 << 16), incl = packed;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) s_cnt[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkBlock / 64; ++w) {
+        const int c = s_cnt[w];
+        if (w < wave) before += c;
+        all += c;
+    }
+    const int excl = before + incl - packed;
+    int rank0 = excl & 0xFFFF, rank1 = (all & 0xFFFF) + (excl >> 16);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t kv = key[i];
+        bool take = kv > T;
+        if (kv == T) {
+            int &rank = i < 8 ? rank0 : rank1;
+            take = rank < need_equal;
+            ++rank;
+        }
+        if (take) {
+            const uint32_t id = (uint32_t)(seg * kTopkSeg + (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7));
+            const int slot = atomicAdd(&s_n, 1);
+            if (slot < kTopkMax) s_out[slot] = ((unsigned long long)kv << 32) | (0xFFFFFFFFu - id);
+        }
+    }
+    __syncthreads();
+    if (tid < k) dst[tid] = s_out[tid];
+}
+
+// Merges the segments' candidates of one row (n_cand words, 0 = empty) and writes the k best in
+// order: a word's rank is the number of larger words (all non-zero words are distinct).
+__global__ __launch_bounds__(256) void masked_topk_finish_kernel(
+    const unsigned long long *__restrict__ cand, int n_cand, int k, const uint16_t *__restrict__ logits,
+    int64_t row_stride, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
+    extern __shared__ unsigned long long s_cand[];
+    __shared__ int s_valid;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) s_valid = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < n_cand; i += 256) {
+        const unsigned long long c = cand[(size_t)b * n_cand + i];
+        s_cand[i] = c;
+        mine += c != 0ull ? 1 : 0;
+    }
+    if (mine) atomicAdd(&s_valid, mine);
+    __syncthreads();
+    const int n_valid = s_valid;
+    for (int i = tid; i < n_cand; i += 256) {
+        const unsigned long long c = s_cand[i];
+        if (c == 0ull) continue;
+        int rank = 0;
+        for (int j = 0; j < n_cand; ++j) rank += s_cand[j] > c ? 1 : 0;
+        if (rank < k) {
+            const uint32_t id = 0xFFFFFFFFu - (uint32_t)c;
+            out_ids[(size_t)b * k + rank] = (int32_t)id;
+            if (out_vals) out_vals[(size_t)b * k + rank] = logits[(size_t)b * row_stride + id];
+        }
+    }
+    for (int j = (n_valid < k ? n_valid : k) + tid; j < k; j += 256) {
+        out_ids[(size_t)b * k + j] = -1;
+        if (out_vals) out_vals[(size_t)b * k + j] = 0xFF80u;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
@@ -277,6 +445,27 @@ hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask,
     if (n_seg > 1)
         hipLaunchKernelGGL(masked_argmax_finish_kernel, dim3((batch + kArgFinishRows - 1) / kArgFinishRows),
                            dim3(64 * kArgFinishRows), 0, stream, batch, n_seg, workspace, out);
+    return hipGetLastError();
+}
+
+static int masked_topk_segments(int vocab) { return (vocab + kTopkSeg - 1) / kTopkSeg; }
+
+size_t masked_topk_workspace_bytes(int batch, int vocab) {
+    return (size_t)batch * masked_topk_segments(vocab) * kTopkMax * sizeof(unsigned long long);
+}
+
+hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
+                              int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
+                              hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    const int n_words = (vocab + 31) / 32, n_seg = masked_topk_segments(vocab);
+    const int n_cand = n_seg * k;
+    if (k < 1 || k > kTopkMax || n_seg > 65535 || (size_t)n_cand * sizeof(unsigned long long) > 65536) return hipErrorInvalidValue;
+    const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
+    hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
+                       n_words, vec_ok, k, workspace);
+    hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(256), (size_t)n_cand * sizeof(unsigned long long), stream,
+                       workspace, n_cand, k, logits, row_stride, out_ids, out_vals);
     return hipGetLastError();
 }
 

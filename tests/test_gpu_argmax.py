@@ -1,10 +1,10 @@
-"""pre3_apply_mask_argmax through the C ABI against the CPU oracle: value and layout cases of the
+"""pre3_apply_mask_argmax and pre3_apply_mask_topk through the C ABI against the CPU oracle: value and layout cases of the
 greedy choice itself, then a closed decode loop (mask -> choice -> advance) in which the GPU
 and the oracle each pick their own tokens from the same logits and must stay in lockstep."""
 import numpy as np
 import pytest
 
-from oracle import Oracle, masked_argmax as oracle_masked_argmax
+from oracle import Oracle, masked_argmax as oracle_masked_argmax, masked_topk as oracle_masked_topk
 from workloads import configs
 from workloads import grammars as G
 from workloads.vocab import BASE_SEED, Vocab, bf16_logits
@@ -92,6 +92,66 @@ def test_masked_argmax_values_and_layouts(V, B, stride_pad, offset):
     assert torch.equal(flat, before), "the logits are read-only for this call"
     if B > 7:
         assert want[4] == -1 and want[5] == V - 1 and want[7] >= 0
+
+
+@pytest.mark.parametrize("V,B,stride_pad,offset,ks", [
+    (513, 4, 0, 0, (1, 8, 64)), (513, 9, 7, 0, (5,)), (1003, 16, 13, 3, (3, 64)), (32000, 64, 0, 0, (1, 40)),
+    (16384, 5, 0, 0, (64,)), (16385, 5, 0, 0, (64,)), (128256, 256, 0, 0, (50,)), (128256, 3, 0, 8, (64,)), (40, 300, 0, 0, (4, 64))])
+def test_masked_topk_values_and_layouts(V, B, stride_pad, offset, ks):
+    """Same special rows as the arg max test (equal maxima, NaNs, infinities, zeros of both signs, empty
+    and single-token masks); ids and bf16 patterns must equal the oracle's sorted list entry by entry."""
+    torch, dev = _torch()
+    rng = np.random.default_rng(BASE_SEED + 3 * V + B)
+    toks = [bytes([97 + i % 5]) for i in range(V - 1)] + [b""]
+    lib = _bound_lib(Vocab(toks, V - 1), B)
+    logits = _special_logits(rng, B, V)
+    if B > 3:
+        logits[3, ::2] = 0x0000                               # zeros of both signs tie, ids decide
+        logits[3, 1::2] = 0x8000
+    mask = _special_masks(rng, B, V)
+    if B > 8:                                                 # fewer allowed tokens than k in one row
+        mask[8] = 0
+        mask[8, 0] = 0b1011
+    stride = V + stride_pad
+    flat = torch.full((B * stride + offset + 8,), 0x1234, dtype=torch.int16, device=dev)
+    view = flat[offset: offset + B * stride].view(B, stride)[:, :V]
+    view.copy_(torch.from_numpy(logits.view(np.int16)).to(dev))
+    before = flat.clone()
+    m_d = torch.from_numpy(mask.view(np.int32)).to(dev)
+    for k in ks:
+        want_ids, want_vals = oracle_masked_topk(logits, mask, V, k)
+        ids = torch.full((B, k), -7, dtype=torch.int32, device=dev)
+        vals = torch.full((B, k), 0x1111, dtype=torch.int16, device=dev)
+        for _ in range(2):                                    # the second call reuses the workspace
+            ids.fill_(-7)
+            lib.apply_mask_topk(view.view(torch.bfloat16), m_d, ids, vals)
+            got_ids, got_vals = ids.cpu().numpy(), vals.cpu().numpy().view(np.uint16)
+            bad = np.argwhere(got_ids != want_ids)
+            assert len(bad) == 0, (k, bad[:4].tolist(), got_ids[bad[0][0]][:8].tolist(), want_ids[bad[0][0]][:8].tolist())
+            assert (got_vals == want_vals).all(), k
+        ids.fill_(-7)
+        lib.apply_mask_topk(view.view(torch.bfloat16), m_d, ids)          # without the values
+        assert (ids.cpu().numpy() == want_ids).all()
+        first = torch.empty(B, dtype=torch.int32, device=dev)
+        lib.apply_mask_argmax(view.view(torch.bfloat16), m_d, first)
+        assert torch.equal(first, ids[:, 0])
+    assert torch.equal(flat, before), "the logits are read-only for this call"
+
+
+def test_masked_topk_argument_errors():
+    from paper_2506_03887_amd.binding import Pre3Error
+    torch, dev = _torch()
+    V, B = 100, 2
+    toks = [bytes([97 + i % 5]) for i in range(V - 1)] + [b""]
+    lib = _bound_lib(Vocab(toks, V - 1), B)
+    logits = torch.zeros((B, V), dtype=torch.bfloat16, device=dev)
+    mask = torch.zeros((B, (V + 31) // 32), dtype=torch.int32, device=dev)
+    for k in (0, 65):
+        with pytest.raises(Pre3Error):
+            lib.apply_mask_topk(logits, mask, torch.zeros((B, k), dtype=torch.int32, device=dev))
+    with pytest.raises(Pre3Error):
+        lib.apply_mask_topk(torch.zeros((B, 50), dtype=torch.bfloat16, device=dev), mask,
+                            torch.zeros((B, 4), dtype=torch.int32, device=dev))     # rows shorter than the vocabulary
 
 
 @pytest.mark.parametrize("cfg_idx,steps,fused_advance", [(1, 32, False), (2, 48, False), (2, 48, True), (3, 12, True)])
