@@ -79,7 +79,7 @@ def main():
                           "us_per_copy": us, "read_plus_write_GBs": 2.0 * n / (us * 1e-6) / 1e9}))
         return
 
-    from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax
+    from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax, masked_topk as oracle_masked_topk
     from paper_2506_03887_amd import Pre3, apply_mask
     from workloads import configs, trajectory
     from workloads.vocab import bf16_logits
@@ -408,6 +408,17 @@ def main():
             assert (err_d.cpu().numpy() == e).all()
         assert (states_d.cpu().numpy() == s_g).all() and (len_d.cpu().numpy() == l_g).all()
 
+        # top-k behind the mask (k = 50): same read-once traffic as the arg max; one call checked against the oracle
+        topk_k = 50
+        topk_ids = torch.empty((B, topk_k), dtype=torch.int32, device=dev)
+        topk_vals = torch.empty((B, topk_k), dtype=torch.int16, device=dev)
+        lib.apply_mask_topk(logits[0], mask_d, topk_ids, topk_vals)
+        want_ids, want_vals = oracle_masked_topk(host_logits[0], mask_d.cpu().numpy().view(np.uint32), V, topk_k)
+        assert (topk_ids.cpu().numpy() == want_ids).all() and (topk_vals.cpu().numpy().view(np.uint16) == want_vals).all(), \
+            "top-k differs from the oracle's"
+        for s in range(1, 4):
+            lib.apply_mask_topk(logits[s % n_pool], mask_d, topk_ids, topk_vals)
+
         if args.eager:                            # counter collection: the checked eager steps are enough
             return {"checked_steps_against_oracle": n_check}
 
@@ -436,13 +447,17 @@ def main():
 
         argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
         step_us_g = graph_us(greedy_step)
+        topk_us = graph_us(lambda s: lib.apply_mask_topk(logits[s % n_pool], mask_d, topk_ids, topk_vals))
         nbytes = 2.0 * pairs_ + 4.0 * B * W
         return {"step": "pre3_apply_mask_argmax + pre3_advance_fill_mask, K steps in one HIP graph, tokens chosen on the device",
                 "us_per_step": step_us_g, "tokens_per_s": pairs_ / (step_us_g * 1e-6),
                 "argmax_launch_us": argmax_us, "argmax_algorithmic_bytes": nbytes,
                 "argmax_achieved_GBs": nbytes / (argmax_us * 1e-6) / 1e9,
                 "argmax_frac_of_hbm_peak": nbytes / (argmax_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                "checked_steps_against_oracle": n_check}
+                "checked_steps_against_oracle": n_check,
+                "topk": {"k": topk_k, "launch_us": topk_us, "achieved_GBs": nbytes / (topk_us * 1e-6) / 1e9,
+                         "frac_of_hbm_peak": nbytes / (topk_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                         "note": "pre3_apply_mask_topk (both kernels), K calls in one HIP graph; same algorithmic bytes as the arg max"}}
 
     pairs_ = float(B) * V
     greedy = greedy_leg()

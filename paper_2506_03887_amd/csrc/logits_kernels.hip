@@ -234,39 +234,136 @@ __global__ __launch_bounds__(64 * kArgFinishRows) void masked_argmax_finish_kern
 // ------------------------------------------------------------------- masked top-k
 
 // Order-preserving 16-bit key of a non-NaN bf16 pattern (-0 counts as +0).  Valid values map to
-// 0x007F (-inf) .. 0xFF80 (+inf); 0 is never produced and marks "no candidate".
+// 0x007F (-inf) .. 0xFF80 (+inf); 0 is never produced.
 __device__ __forceinline__ uint32_t bf16_key(uint32_t h) {
     if (h == 0x8000u) h = 0u;
     return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u);
 }
 
-__device__ __forceinline__ int wave_sum(int v) {
+// A candidate travels between the stages as the word  key << 21 | (0x1FFFFF - id)  (id < 2^21):
+// distinct words, larger = better value, then smaller id; 0 = no candidate.
+constexpr int kTopkIdBits = 21;
+constexpr int kTopkWordBits = 16 + kTopkIdBits;
+constexpr uint32_t kTopkIdMask = (1u << kTopkIdBits) - 1u;
+__device__ __forceinline__ unsigned long long topk_word(uint32_t key, uint32_t id) {
+    return ((unsigned long long)key << kTopkIdBits) | (unsigned long long)(kTopkIdMask - id);
+}
+
+// Number of (lane, element) pairs for which pred(i) holds, by ballots (scalar population counts: no
+// LDS, no cross-lane data movement).
+template <int kPer, class Pred>
+__device__ __forceinline__ int wave_count(Pred pred) {
+    int c = 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    for (int i = 0; i < kPer; ++i) c += __popcll(__ballot(pred(i)));
+    return c;
+}
+
+// The largest threshold t (16 bits, found bit by bit from the top) that at least `want` of the
+// wave's keys reach; *reached = how many do.  want >= 1 and at least `want` keys are non-zero.
+template <int kPer, class KeyAt>
+__device__ __forceinline__ uint32_t wave_key_threshold(KeyAt key_at, int n_nonzero, int want, int *reached) {
+    uint32_t T = 0u;
+    int at_T = n_nonzero;
+    for (int bit = 15; bit >= 0 && at_T != want; --bit) {
+        const uint32_t t = T | (1u << bit);
+        const int c = wave_count<kPer>([&](int i) { return key_at(i) >= t; });
+        if (c >= want) { T = t; at_T = c; }
+    }
+    *reached = at_T;
+    return T == 0u ? 1u : T;                                  // want == n_nonzero: every candidate
+}
+
+// Selection of the kk = min(k, candidates) best of the elements a wave holds, kPer per lane:
+// key_at(i) (0 = no candidate, else the 16-bit value key) and pref_at(i) (distinct among equal keys,
+// 1 .. 2^pref_bits - 1, larger = preferred, i.e. smaller id).  First the largest key threshold T
+// that at least kk keys reach; then, if more keys equal T than are still needed, the largest
+// preference threshold P that enough of them reach.  Selected: key > T, or key == T and pref >= P.
+// All lanes run in lockstep and obtain the same T, P, kk.
+template <int kPer, class KeyAt, class PrefAt>
+__device__ __forceinline__ void wave_select(KeyAt key_at, PrefAt pref_at, int pref_bits, int k, uint32_t *T_out,
+                                            uint32_t *P_out, int *kk_out) {
+    const int nz = wave_count<kPer>([&](int i) { return key_at(i) != 0u; });
+    const int kk = nz < k ? nz : k;
+    *kk_out = kk;
+    *T_out = 0x10000u;                                        // nothing selected
+    *P_out = 0u;
+    if (kk == 0) return;
+    int at_T;
+    const uint32_t T = wave_key_threshold<kPer>(key_at, nz, kk, &at_T);
+    *T_out = T;
+    if (at_T == kk) return;                                   // every key >= T is selected (P = 0)
+    const int above = wave_count<kPer>([&](int i) { return key_at(i) > T; });
+    const int need = kk - above;                              // of the keys equal to T, the `need` most preferred
+    uint32_t P = 0u;
+    int at_P = at_T - above;                                  // count(key == T && pref >= P)
+    for (int bit = pref_bits - 1; bit >= 0 && at_P != need; --bit) {
+        const uint32_t t = P | (1u << bit);
+        const int c = wave_count<kPer>([&](int i) { return key_at(i) == T && pref_at(i) >= t; });
+        if (c >= need) { P = t; at_P = c; }
+    }
+    *P_out = P;
+}
+
+// The kk-th largest of the S distinct non-zero words of an LDS list (1 <= kk <= S), found bit by bit
+// from the top by one wave; lane l looks at the words l, l + 64, ... (kept in registers when there
+// are at most 256 of them).  Words >= the result are the kk largest.
+__device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned long long *list, int S, int kk, int lane) {
+    if (kk >= S) return 1ull;
+    constexpr int kRegs = 4;
+    unsigned long long r[kRegs];
+#pragma unroll
+    for (int i = 0; i < kRegs; ++i) r[i] = i * 64 + lane < S ? list[i * 64 + lane] : 0ull;
+    const bool in_regs = S <= 64 * kRegs;
+    unsigned long long prefix = 0ull;
+    for (int bit = kTopkWordBits - 1; bit >= 0; --bit) {
+        const unsigned long long t = prefix | (1ull << bit);
+        int c = 0;
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kRegs; ++i)
+                if (i * 64 < S) c += __popcll(__ballot(r[i] >= t));
+        } else {
+            for (int r0 = 0; r0 < S; r0 += 64) c += __popcll(__ballot(r0 + lane < S && list[r0 + lane] >= t));
+        }
+        if (c >= kk) {
+            prefix = t;
+            if (c == kk) break;
+        }
+    }
+    return prefix;
 }
 
 // The k best candidates of one segment of one row (blockIdx.x = row, blockIdx.y = segment of
-// kTopkSeg tokens): every thread keeps the keys of its 16 tokens in registers (0 = masked, NaN or
-// beyond the vocabulary), so the logits are read once.  The block then finds by bisection on the
-// 16-bit key the largest threshold T that at least kk = min(k, candidates) keys reach, takes every
-// key above T and, of the keys equal to T, the first kk - (number above) in id order (an ordered
-// block scan of the per-thread counts gives each its rank).  The chosen ones are written as
-//   key << 32 | ~id     (distinct words; larger = better value, then smaller id; 0 = empty slot)
-// to out[(row * n_seg + segment) * k ..], in no particular order.
-constexpr int kTopkBlock = 1024;
+// kTopkSeg tokens).  Every thread keeps the keys of its 16 tokens in registers (0 = masked, NaN or
+// beyond the vocabulary), so the logits are read once.
+//   Fast path: from the per-thread maxima the block derives a lower bound M of the segment's k-th
+//   largest key (at least k threads hold a key >= M), so only keys >= M can be among the k best:
+//   usually a few times k of them.  They are collected in an LDS list and wave 0 selects the k best.
+//   If the list overflows -- only possible when thousands of keys tie with M -- every wave selects
+//   the k best of its own 1,024 tokens (ties by id) and wave 0 merges the waves' lists.
+// The k words are written, in no particular order, to out[(row * n_seg + segment) * k ..], 0-padded.
+constexpr int kTopkBlock = 512;
+constexpr int kTopkWaves = kTopkBlock / 64;
 constexpr int kTopkSeg = 16 * kTopkBlock;
+constexpr int kTopkList = 2048;
 __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int vec_ok, int k, unsigned long long *__restrict__ out) {
-    __shared__ int s_cnt[kTopkBlock / 64];
-    __shared__ unsigned long long s_out[kTopkMax];
-    __shared__ int s_n;
+    __shared__ unsigned long long s_list[kTopkList];
+    __shared__ unsigned long long s_sel[kTopkWaves][kTopkMax];
+    __shared__ int s_nz[kTopkWaves];
+    __shared__ uint32_t s_wbound[kTopkWaves];
+    __shared__ int s_n[kTopkWaves];
+    __shared__ int s_count;
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     const int n_mask_bytes = n_words * 4;
+    unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
     uint32_t key[16];
+    // element i of a thread is token  seg * kTopkSeg + rel(i),  rel(i) = (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7)
+    auto rel = [&](int i) { return (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7); };
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int t0 = seg * kTopkSeg + (tid + half * kTopkBlock) * 8;
@@ -281,7 +378,9 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { h[2 * j] = x[j] & 0xFFFFu; h[2 * j + 1] = x[j] >> 16; }
             } else {
-                for (int j = 0; j < 8 && t0 + j < vocab; ++j) h[j] = lrow[t0 + j];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + j < vocab) h[j] = lrow[t0 + j];
             }
         }
 #pragma unroll
@@ -290,111 +389,168 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
             key[half * 8 + j] = ok ? bf16_key(h[j]) : 0u;
         }
     }
-    if (tid == 0) s_n = 0;
-    if (tid < kTopkMax) s_out[tid] = 0ull;
-    auto count_ge = [&](uint32_t T) -> int {                  // keys >= T over the whole block
-        int c = 0;
+    uint32_t best = 0u;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) c += key[i] >= T ? 1 : 0;
-        c = wave_sum(c);
-        if (lane == 0) s_cnt[wave] = c;
-        __syncthreads();
-        int total = 0;
+    for (int i = 0; i < 16; ++i) best = key[i] > best ? key[i] : best;
+    // A lower bound of the segment's k-th largest key from the threads' maxima: wave w takes the
+    // q_w-th largest of its 64 maxima, q_w = min(j, threads of w that hold a candidate), with the
+    // smallest j for which the q_w add up to k; the smallest of these is reached by at least k keys.
+    const int nz_wave = __popcll(__ballot(best != 0u));
+    if (lane == 0) s_nz[wave] = nz_wave;
+    if (tid == 0) s_count = 0;
+    if (lane == 0) s_n[wave] = 0;
+    s_sel[wave][lane] = 0ull;
+    __syncthreads();
+    int quota = 0, holders = 0;
 #pragma unroll
-        for (int w = 0; w < kTopkBlock / 64; ++w) total += s_cnt[w];
-        __syncthreads();
-        return total;
-    };
-    const int candidates = count_ge(1u);
-    const int kk = candidates < k ? candidates : k;
-    unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
-    if (kk == 0) {
+    for (int w = 0; w < kTopkWaves; ++w) holders += s_nz[w];
+    if (holders >= k) {
+        for (quota = 1; quota < 64; ++quota) {
+            int sum = 0;
+#pragma unroll
+            for (int w = 0; w < kTopkWaves; ++w) sum += s_nz[w] < quota ? s_nz[w] : quota;
+            if (sum >= k) break;
+        }
+    }
+    {
+        uint32_t mine = 0x10000u;                             // no candidate in this wave
+        if (nz_wave > 0) {
+            mine = 1u;                                        // fewer than k holders in the block: every candidate
+            if (quota > 0) {
+                int reached;
+                mine = wave_key_threshold<1>([&](int) { return best; }, nz_wave, nz_wave < quota ? nz_wave : quota, &reached);
+            }
+        }
+        if (lane == 0) s_wbound[wave] = mine;
+    }
+    __syncthreads();
+    uint32_t bound = 0x10000u;
+#pragma unroll
+    for (int w = 0; w < kTopkWaves; ++w) bound = s_wbound[w] < bound ? s_wbound[w] : bound;
+    if (bound == 0x10000u) {                                  // no candidate in the segment
         if (tid < k) dst[tid] = 0ull;
         return;
     }
-    uint32_t lo = 1u, hi = 0x10000u;                          // count_ge(lo) >= kk > count_ge(hi) = above
-    int above = 0;
-    while (hi - lo > 1u) {
-        const uint32_t mid = (lo + hi) >> 1;
-        const int c = count_ge(mid);
-        if (c >= kk) lo = mid;
-        else { hi = mid; above = c; }
-    }
-    const uint32_t T = lo;
-    const int need_equal = kk - above;                        // >= 1, and at least that many keys equal T
-    // rank of every key equal to T in id order: the first halves of all threads come before the second halves
-    int e0 = 0, e1 = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { e0 += key[i] == T ? 1 : 0; e1 += key[8 + i] == T ? 1 : 0; }
-    int packed = e0 | (e1 << 16), incl = packed;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-    }
-    if (lane == 63) s_cnt[wave] = incl;
-    __syncthreads();
-    int before = 0, all = 0;
-#pragma unroll
-    for (int w = 0; w < kTopkBlock / 64; ++w) {
-        const int c = s_cnt[w];
-        if (w < wave) before += c;
-        all += c;
-    }
-    const int excl = before + incl - packed;
-    int rank0 = excl & 0xFFFF, rank1 = (all & 0xFFFF) + (excl >> 16);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const uint32_t kv = key[i];
-        bool take = kv > T;
-        if (kv == T) {
-            int &rank = i < 8 ? rank0 : rank1;
-            take = rank < need_equal;
-            ++rank;
+    for (int i = 0; i < 16; ++i)
+        if (key[i] >= bound) {
+            const int slot = atomicAdd(&s_count, 1);
+            if (slot < kTopkList) s_list[slot] = topk_word(key[i], (uint32_t)(seg * kTopkSeg + rel(i)));
         }
-        if (take) {
-            const uint32_t id = (uint32_t)(seg * kTopkSeg + (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7));
-            const int slot = atomicAdd(&s_n, 1);
-            if (slot < kTopkMax) s_out[slot] = ((unsigned long long)kv << 32) | (0xFFFFFFFFu - id);
-        }
-    }
     __syncthreads();
-    if (tid < k) dst[tid] = s_out[tid];
+    const int S = s_count;
+    if (S <= kTopkList) {
+        if (wave != 0) return;
+        const int kk = S < k ? S : k;
+        const unsigned long long thr = wave_kth_largest(s_list, S, kk, lane);
+        int base = 0;
+        for (int r0 = 0; r0 < S; r0 += 64) {
+            const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
+            const bool take = w >= thr && w != 0ull;
+            const unsigned long long m = __ballot(take);
+            if (take) dst[base + __popcll(m & ((1ull << lane) - 1ull))] = w;
+            base += __popcll(m);
+        }
+        if (lane >= kk && lane < k) dst[lane] = 0ull;
+        return;
+    }
+    // thousands of ties: exact selection per wave, then a merge by wave 0
+    auto key_at = [&](int i) { return key[i]; };
+    auto pref_at = [&](int i) { return (uint32_t)(kTopkSeg - rel(i)); };     // 1 .. kTopkSeg, larger = smaller id
+    uint32_t T, P;
+    int kk;
+    wave_select<16>(key_at, pref_at, 15, k, &T, &P, &kk);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (key[i] > T || (key[i] == T && pref_at(i) >= P)) {
+            const int slot = atomicAdd(&s_n[wave], 1);
+            if (slot < kTopkMax) s_sel[wave][slot] = topk_word(key[i], (uint32_t)(seg * kTopkSeg + rel(i)));
+        }
+    __syncthreads();
+    if (wave != 0) return;
+    unsigned long long c[kTopkWaves];
+#pragma unroll
+    for (int i = 0; i < kTopkWaves; ++i) c[i] = s_sel[i][lane];      // slot `lane` of every wave (empty slots are 0)
+    auto ckey_at = [&](int i) { return (uint32_t)(c[i] >> kTopkIdBits); };
+    auto cpref_at = [&](int i) { return c[i] != 0ull ? ((uint32_t)c[i] & kTopkIdMask) + 1u : 0u; };
+    wave_select<kTopkWaves>(ckey_at, cpref_at, kTopkIdBits + 1, k, &T, &P, &kk);
+    int base = 0;                                             // compact the selected words into dst[0 .. kk)
+#pragma unroll
+    for (int i = 0; i < kTopkWaves; ++i) {
+        const bool take = c[i] != 0ull && (ckey_at(i) > T || (ckey_at(i) == T && cpref_at(i) >= P));
+        const unsigned long long m = __ballot(take);
+        if (take) dst[base + __popcll(m & ((1ull << lane) - 1ull))] = c[i];
+        base += __popcll(m);
+    }
+    if (lane >= kk && lane < k) dst[lane] = 0ull;
 }
 
-// Merges the segments' candidates of one row (n_cand words, 0 = empty) and writes the k best in
-// order: a word's rank is the number of larger words (all non-zero words are distinct).
-__global__ __launch_bounds__(256) void masked_topk_finish_kernel(
+// Merges the segments' candidates of one row with one wave: n_cand words (0 = empty), at most
+// kTopkFinishPer per lane.  As above, the k-th largest of the 64 per-lane maxima bounds the k-th
+// largest word from below; the words that reach it go to an LDS list, the k best of the list are
+// selected, ranked against each other (a word's rank = number of larger words) and written in order.
+constexpr int kTopkFinishPer = 24;
+__global__ __launch_bounds__(64) void masked_topk_finish_kernel(
     const unsigned long long *__restrict__ cand, int n_cand, int k, const uint16_t *__restrict__ logits,
     int64_t row_stride, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
-    extern __shared__ unsigned long long s_cand[];
-    __shared__ int s_valid;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    if (tid == 0) s_valid = 0;
-    __syncthreads();
-    int mine = 0;
-    for (int i = tid; i < n_cand; i += 256) {
-        const unsigned long long c = cand[(size_t)b * n_cand + i];
-        s_cand[i] = c;
-        mine += c != 0ull ? 1 : 0;
+    __shared__ unsigned long long s_list[64 * kTopkFinishPer];
+    __shared__ unsigned long long s_best[kTopkMax];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    unsigned long long c[kTopkFinishPer], top = 0ull;
+#pragma unroll
+    for (int i = 0; i < kTopkFinishPer; ++i) {
+        const int at = i * 64 + lane;
+        c[i] = at < n_cand ? cand[(size_t)b * n_cand + at] : 0ull;
+        top = c[i] > top ? c[i] : top;
     }
-    if (mine) atomicAdd(&s_valid, mine);
-    __syncthreads();
-    const int n_valid = s_valid;
-    for (int i = tid; i < n_cand; i += 256) {
-        const unsigned long long c = s_cand[i];
-        if (c == 0ull) continue;
-        int rank = 0;
-        for (int j = 0; j < n_cand; ++j) rank += s_cand[j] > c ? 1 : 0;
-        if (rank < k) {
-            const uint32_t id = 0xFFFFFFFFu - (uint32_t)c;
-            out_ids[(size_t)b * k + rank] = (int32_t)id;
-            if (out_vals) out_vals[(size_t)b * k + rank] = logits[(size_t)b * row_stride + id];
+    // lower bound: the min(k, lanes with a candidate)-th largest of the lanes' best words
+    const int nz = __popcll(__ballot(top != 0ull));
+    const int kq = nz < k ? nz : k;
+    unsigned long long bound = 1ull;
+    if (kq < nz) {
+        unsigned long long prefix = 0ull;
+        for (int bit = kTopkWordBits - 1; bit >= 0; --bit) {
+            const unsigned long long t = prefix | (1ull << bit);
+            const int n = __popcll(__ballot(top >= t));
+            if (n >= kq) {
+                prefix = t;
+                if (n == kq) break;
+            }
         }
+        bound = prefix;
     }
-    for (int j = (n_valid < k ? n_valid : k) + tid; j < k; j += 256) {
-        out_ids[(size_t)b * k + j] = -1;
-        if (out_vals) out_vals[(size_t)b * k + j] = 0xFF80u;
+    int S = 0;
+#pragma unroll
+    for (int i = 0; i < kTopkFinishPer; ++i) {
+        const bool keep = c[i] != 0ull && c[i] >= bound;
+        const unsigned long long m = __ballot(keep);
+        if (keep) s_list[S + __popcll(m & ((1ull << lane) - 1ull))] = c[i];
+        S += __popcll(m);
+    }
+    s_best[lane] = 0ull;
+    __builtin_amdgcn_wave_barrier();
+    const int kk = S < k ? S : k;
+    const unsigned long long thr = kk > 0 ? wave_kth_largest(s_list, S, kk, lane) : ~0ull;
+    int base = 0;
+    for (int r0 = 0; r0 < S; r0 += 64) {
+        const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
+        const bool take = w >= thr && w != 0ull;
+        const unsigned long long m = __ballot(take);
+        if (take) s_best[base + __popcll(m & ((1ull << lane) - 1ull))] = w;
+        base += __popcll(m);
+    }
+    __builtin_amdgcn_wave_barrier();
+    const unsigned long long mine = s_best[lane];             // kk <= 64 selected words, one per lane
+    int rank = 0;
+    for (int j = 0; j < kk; ++j) rank += s_best[j] > mine ? 1 : 0;
+    if (mine != 0ull) {
+        const uint32_t id = kTopkIdMask - ((uint32_t)mine & kTopkIdMask);
+        out_ids[(size_t)b * k + rank] = (int32_t)id;
+        if (out_vals) out_vals[(size_t)b * k + rank] = logits[(size_t)b * row_stride + id];
+    }
+    if (lane >= kk && lane < k) {
+        out_ids[(size_t)b * k + lane] = -1;
+        if (out_vals) out_vals[(size_t)b * k + lane] = 0xFF80u;
     }
 }
 
@@ -450,6 +606,11 @@ hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask,
 
 static int masked_topk_segments(int vocab) { return (vocab + kTopkSeg - 1) / kTopkSeg; }
 
+bool masked_topk_fits(int vocab, int k) {
+    return k >= 1 && k <= kTopkMax && vocab >= 1 && vocab <= (1 << kTopkIdBits) &&
+           masked_topk_segments(vocab) * k <= 64 * kTopkFinishPer;
+}
+
 size_t masked_topk_workspace_bytes(int batch, int vocab) {
     return (size_t)batch * masked_topk_segments(vocab) * kTopkMax * sizeof(unsigned long long);
 }
@@ -458,14 +619,13 @@ hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, i
                               int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
                               hipStream_t stream) {
     if (batch == 0) return hipSuccess;
+    if (!masked_topk_fits(vocab, k)) return hipErrorInvalidValue;
     const int n_words = (vocab + 31) / 32, n_seg = masked_topk_segments(vocab);
-    const int n_cand = n_seg * k;
-    if (k < 1 || k > kTopkMax || n_seg > 65535 || (size_t)n_cand * sizeof(unsigned long long) > 65536) return hipErrorInvalidValue;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
     hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
                        n_words, vec_ok, k, workspace);
-    hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(256), (size_t)n_cand * sizeof(unsigned long long), stream,
-                       workspace, n_cand, k, logits, row_stride, out_ids, out_vals);
+    hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(64), 0, stream, workspace, n_seg * k, k, logits, row_stride,
+                       out_ids, out_vals);
     return hipGetLastError();
 }
 
