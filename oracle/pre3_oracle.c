@@ -39,7 +39,8 @@
  * up to length 8 with an independent (non-LR) recogniser, Dyck == counter,
  * right-linear grammar == DFA, JSON grammar == the json module of the Python
  * standard library, and the prefix/concatenation/EOS invariants; the greedy choice
- * (masked arg max) against numpy's argmax over the candidates and hand cases; the
+ * (masked arg max) against numpy's argmax over the candidates and hand cases, the
+ * top-k list against numpy's stable sort of the candidates and hand cases; the
  * jump-forward bytes against the forced bytes read off the brute-force sets of
  * viable prefixes; seeded random grammars against the brute-force recogniser
  * (tests/test_random_grammars.py); the statements of the paper that can be checked
