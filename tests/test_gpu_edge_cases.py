@@ -172,6 +172,52 @@ def test_apply_mask_layouts(V, stride, offset):
     assert int(flat[:offset].abs().sum()) == 0 and int(flat[offset + B * stride:].abs().sum()) == 0
 
 
+def test_batches_beyond_the_grid_limit_of_one_dimension():
+    """More rows than a grid dimension holds (65,535): pre3_apply_mask switches to its flat kernel,
+    the arg max and the top-k put the rows on the x dimension.  Small vocabulary, every row checked."""
+    torch, dev = _torch()
+    from oracle import masked_argmax as oracle_masked_argmax, masked_topk as oracle_masked_topk
+    from paper_2506_03887_amd import Pre3, apply_mask
+    from workloads.vocab import Vocab
+    V, B, cap = 72, 70001, 4
+    W = (V + 31) // 32
+    rng = np.random.default_rng(V + B)
+    logits = bf16_logits(rng, B, V)
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[:, W - 1] &= np.uint32((1 << (V % 32)) - 1)
+    mask[5], mask[B - 1] = 0, 0
+    mask[B - 1, 1] = 1 << 7
+    toks = [bytes([97 + i % 5]) for i in range(V - 1)] + [b""]
+    v = Vocab(toks, V - 1)
+    lib = Pre3(G.ARITHMETIC, v.bytes, v.offsets, v.eos_id, max_token_len=1, stack_cap=cap)
+    s0 = lib.initial_state(0)
+    keep = (torch.full((B,), s0, dtype=torch.int32, device=dev), torch.full((B, cap), s0, dtype=torch.int32, device=dev),
+            torch.ones(B, dtype=torch.int32, device=dev), torch.zeros(B, dtype=torch.int32, device=dev))
+    lib.bind_state(*keep)
+    l_d = torch.from_numpy(logits.view(np.int16)).to(dev)
+    m_d = torch.from_numpy(mask.view(np.int32)).to(dev)
+    tok = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    lib.apply_mask_argmax(l_d.view(torch.bfloat16), m_d, tok)
+    assert (tok.cpu().numpy() == oracle_masked_argmax(logits, mask, V)).all()
+    ids = torch.full((B, 5), -7, dtype=torch.int32, device=dev)
+    vals = torch.zeros((B, 5), dtype=torch.int16, device=dev)
+    lib.apply_mask_topk(l_d.view(torch.bfloat16), m_d, ids, vals)
+    want_ids, want_vals = oracle_masked_topk(logits, mask, V, 5)
+    assert (ids.cpu().numpy() == want_ids).all() and (vals.cpu().numpy().view(np.uint16) == want_vals).all()
+    assert want_ids[B - 1].tolist() == [39, -1, -1, -1, -1] and (want_ids[5] == -1).all()
+    apply_mask(l_d, m_d, V)
+    want = logits.copy()
+    oracle_apply_mask(want, mask, V)
+    assert (l_d.cpu().numpy().view(np.uint16) == want).all()
+    # a stack advance over the same batch: every sequence takes the token "a" (id 0 spells "a")
+    tokens = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.advance(tokens)
+    o = Oracle([G.ARITHMETIC])
+    rc, st = o.advance(o.initial_stack(), b"a")
+    assert rc == 0 and (keep[3].cpu().numpy() == 0).all() and (keep[2].cpu().numpy() == len(st)).all()
+    assert (keep[1].cpu().numpy()[:, : len(st)] == np.array(st, dtype=np.int32)).all()
+
+
 @pytest.mark.parametrize("stride_pad,offset", [(0, 0), (8, 0), (3, 0), (0, 4)])
 def test_fused_call_equals_two_calls_on_any_layout(deep_vocab, stride_pad, offset):
     torch, dev = _torch()
