@@ -339,7 +339,8 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
 // beyond the vocabulary), so the logits are read once.
 //   Fast path: from the per-thread maxima the block derives a lower bound M of the segment's k-th
 //   largest key (at least k threads hold a key >= M), so only keys >= M can be among the k best:
-//   usually a few times k of them.  They are collected in an LDS list and wave 0 selects the k best.
+//   usually a few times k of them.  They are collected in an LDS list; with at most one per thread
+//   every thread ranks its word against the list, otherwise wave 0 selects the k best bit by bit.
 //   If the list overflows -- only possible when thousands of keys tie with M -- every wave selects
 //   the k best of its own 1,024 tokens (ties by id) and wave 0 merges the waves' lists.
 // The k words are written, in no particular order, to out[(row * n_seg + segment) * k ..], 0-padded.
@@ -439,6 +440,19 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
         }
     __syncthreads();
     const int S = s_count;
+    if (S <= kTopkBlock) {
+        // the usual case: one listed word per thread, its rank = number of larger words (every thread
+        // reads the same LDS word at a time: a broadcast), the k best write themselves in order
+        if (tid < S) {
+            const unsigned long long w = s_list[tid];
+            int rank = 0;
+#pragma unroll 8
+            for (int j = 0; j < S; ++j) rank += s_list[j] > w ? 1 : 0;
+            if (rank < k) dst[rank] = w;
+        }
+        if (tid >= S && tid < k) dst[tid] = 0ull;
+        return;
+    }
     if (S <= kTopkList) {
         if (wave != 0) return;
         const int kk = S < k ? S : k;
@@ -487,8 +501,9 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
 
 // Merges the segments' candidates of one row with one wave: n_cand words (0 = empty), at most
 // kTopkFinishPer per lane.  As above, the k-th largest of the 64 per-lane maxima bounds the k-th
-// largest word from below; the words that reach it go to an LDS list, the k best of the list are
-// selected, ranked against each other (a word's rank = number of larger words) and written in order.
+// largest word from below; the words that reach it go to an LDS list.  Up to 256 listed words are
+// ranked directly (a word's rank = number of larger words) and those ranked below k written in
+// order; a longer list is first cut to its k best bit by bit.
 constexpr int kTopkFinishPer = 24;
 __global__ __launch_bounds__(64) void masked_topk_finish_kernel(
     const unsigned long long *__restrict__ cand, int n_cand, int k, const uint16_t *__restrict__ logits,
@@ -527,26 +542,46 @@ __global__ __launch_bounds__(64) void masked_topk_finish_kernel(
         if (keep) s_list[S + __popcll(m & ((1ull << lane) - 1ull))] = c[i];
         S += __popcll(m);
     }
-    s_best[lane] = 0ull;
     __builtin_amdgcn_wave_barrier();
     const int kk = S < k ? S : k;
-    const unsigned long long thr = kk > 0 ? wave_kth_largest(s_list, S, kk, lane) : ~0ull;
-    int base = 0;
-    for (int r0 = 0; r0 < S; r0 += 64) {
-        const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
-        const bool take = w >= thr && w != 0ull;
-        const unsigned long long m = __ballot(take);
-        if (take) s_best[base + __popcll(m & ((1ull << lane) - 1ull))] = w;
-        base += __popcll(m);
-    }
-    __builtin_amdgcn_wave_barrier();
-    const unsigned long long mine = s_best[lane];             // kk <= 64 selected words, one per lane
-    int rank = 0;
-    for (int j = 0; j < kk; ++j) rank += s_best[j] > mine ? 1 : 0;
-    if (mine != 0ull) {
-        const uint32_t id = kTopkIdMask - ((uint32_t)mine & kTopkIdMask);
+    auto emit = [&](unsigned long long w, int rank) {
+        const uint32_t id = kTopkIdMask - ((uint32_t)w & kTopkIdMask);
         out_ids[(size_t)b * k + rank] = (int32_t)id;
         if (out_vals) out_vals[(size_t)b * k + rank] = logits[(size_t)b * row_stride + id];
+    };
+    if (S <= 256) {
+        // the usual case: every listed word is ranked directly (rank = number of larger words; all
+        // lanes read the same LDS word at a time)
+        unsigned long long w[4];
+        int rank[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = i * 64 + lane < S ? s_list[i * 64 + lane] : ~0ull;
+#pragma unroll 8
+        for (int j = 0; j < S; ++j) {
+            const unsigned long long o = s_list[j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rank[i] += o > w[i] ? 1 : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i * 64 + lane < S && rank[i] < k) emit(w[i], rank[i]);
+    } else {
+        s_best[lane] = 0ull;
+        __builtin_amdgcn_wave_barrier();
+        const unsigned long long thr = kk > 0 ? wave_kth_largest(s_list, S, kk, lane) : ~0ull;
+        int base = 0;
+        for (int r0 = 0; r0 < S; r0 += 64) {
+            const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
+            const bool take = w >= thr && w != 0ull;
+            const unsigned long long m = __ballot(take);
+            if (take) s_best[base + __popcll(m & ((1ull << lane) - 1ull))] = w;
+            base += __popcll(m);
+        }
+        __builtin_amdgcn_wave_barrier();
+        const unsigned long long mine = s_best[lane];         // kk <= 64 selected words, one per lane
+        int rank = 0;
+        for (int j = 0; j < kk; ++j) rank += s_best[j] > mine ? 1 : 0;
+        if (mine != 0ull) emit(mine, rank);
     }
     if (lane >= kk && lane < k) {
         out_ids[(size_t)b * k + lane] = -1;
