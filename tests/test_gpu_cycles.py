@@ -28,6 +28,16 @@ def test_right_recursive_json_full_size():
     assert r["full_masks"] == 3
 
 
+@pytest.mark.parametrize("options", [dict(token_edges=False), dict(merged_reductions=False), dict(max_condition_depth=3)])
+def test_cycle_aware_stacks_under_every_merging_level(options):
+    """Compaction does not depend on how masks and walks are computed: byte-by-byte masks, one
+    reduction per step, and shallow condition trees (leftover walks) give the same stacks and masks."""
+    r = replay(7, steps=20, full_mask_steps=[0, 7, 19], check_apply=False, **options)
+    assert r["full_masks"] == 3
+    r = replay_advance_fill(7, steps=16, full_mask_steps=[0, 15], **options)
+    assert r["full_masks"] == 2
+
+
 def _bound(lib, B, cap, s0):
     torch, dev = _torch()
     data = torch.zeros((B, cap), dtype=torch.int32, device=dev)
