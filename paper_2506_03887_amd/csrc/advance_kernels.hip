@@ -60,6 +60,62 @@ __device__ __forceinline__ void commit_overlay(int32_t *row, const PrivateStack 
         for (int i = kLdsDepth; i < d; ++i) row[base + i] = priv.get(i);
 }
 
+// Cycle-aware stack compaction (Sec. 3.2.3; Alg. 1 step 1) of a stack staged in LDS, s[0 .. n): a
+// complete traversal v1..vn of a registered reduction cycle that lies right below another v1 carries
+// no information and is taken out.  The stack is rebuilt entry by entry from the bottom; after each
+// entry that is the head of a cycle, the n entries under it are compared with the cycle's states
+// and dropped on a match (then the check repeats).  Run by the 64 lanes of one wave in lockstep:
+// lanes look up cycle_head for 64 entries at a time, a ballot finds the heads, lane i compares
+// entry i of a traversal, segments between heads are moved down as blocks.  `pool` = the cycle
+// records (in LDS or global memory).  Returns the new length; *first_moved = lowest index whose
+// content changed (= the new length if only the top was cut, n if nothing changed).
+__device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *__restrict__ cycle_head, const int32_t *pool,
+                                           int n_states, int lane, int *first_moved) {
+    int w = 0, moved = n;
+    for (int r0 = 0; r0 < n; r0 += 64) {
+        const int cnt = n - r0 < 64 ? n - r0 : 64;
+        const int x = lane < cnt ? s[r0 + lane] : -1;
+        const int hd = (unsigned)x < (unsigned)n_states ? cycle_head[x] : -1;
+        unsigned long long heads = __ballot(hd >= 0);
+        if (heads == 0 && w == r0) { w += cnt; continue; }
+        int prev = 0;                                   // entries of this chunk already moved
+        for (;;) {
+            const int j = heads ? __ffsll((long long)heads) - 1 : cnt - 1;   // the segment prev..j ends at a head or at the chunk's end
+            const int seg = j - prev + 1;
+            if (seg > 0) {
+                if (w != r0 + prev) {                   // all lanes read, then all lanes write: the ranges may overlap
+                    const int v = lane < seg ? s[r0 + prev + lane] : 0;
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane < seg) s[w + lane] = v;
+                    __builtin_amdgcn_wave_barrier();
+                    moved = w < moved ? w : moved;
+                }
+                w += seg;
+            }
+            if (!heads) break;
+            heads &= heads - 1;
+            prev = j + 1;
+            const int first = __shfl(hd, j);            // s[w - 1] is the head of these cycles
+            int h = first;
+            while (h >= 0) {
+                const int k = __builtin_amdgcn_readfirstlane(pool[h]);
+                const int next = __builtin_amdgcn_readfirstlane(pool[h + 1]);
+                bool match = false;
+                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == pool[h + 2 + lane]);
+                if (match) {
+                    w -= k;                             // the top stays: s[w - 1] held the same state
+                    moved = w < moved ? w : moved;
+                    h = first;
+                } else {
+                    h = next;
+                }
+            }
+        }
+    }
+    *first_moved = moved;
+    return w;
+}
+
 // One wave per sequence: the walk of a single token is a chain of dependent table look-ups, so
 // giving every sequence its own wave keeps control flow uniform (lanes of a shared wave would
 // serialise each other's reduction chains) and lets the chip overlap the chains of all
@@ -141,13 +197,18 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
 // whole block builds the sequence's next mask row (dense row copy, delta lists, leftover walks)
 // and stores it.  The sequence's inputs are loaded once, no kernel boundary separates the two
 // halves, and the long walks of a few sequences overlap the mask building of all others.
+// kCompact (cycle-aware stacks): the new stack is put together in LDS, complete traversals of reduction
+// cycles are taken out of it (fold_cycles) and only then is it written back and looked up, so the call
+// leaves compacted stacks and the mask of exactly those stacks.
 constexpr int kAfBlock = 512;
+template <bool kCompact>
 __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
     int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
     uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
-    size_t walk_spill_stride) {
-    extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4
+    size_t walk_spill_stride, const int32_t *__restrict__ cycle_head, const int32_t *__restrict__ cycle_pool) {
+    extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4;
+                                                       // kCompact: followed by cap stack entries
     __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
     __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
     __shared__ RowPlan plan;
@@ -213,13 +274,40 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                 }
             }
         }
+        // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart)
+        int nl = out_len;
+        if (kCompact && shape_ok) {
+            // put it together in LDS, compact it, write back what changed
+            int32_t *stack = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2));
+            for (int i = lane; i < nl; i += 64)
+                stack[i] = i < base ? StackView{row, s_win, n}.at(i) : priv.get(i - base);
+            __builtin_amdgcn_wave_barrier();
+            int first_moved = nl;
+            if (out_state >= 0 && nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+            const int from = restarted ? nl : (first_moved < base ? first_moved : base);
+            for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
+            if (lane == 0) {
+                err[b] = out_err;
+                if ((out_err == 0 && t >= 0) || nl != n) { states[b] = out_state; len[b] = nl; }
+            }
+            auto new_at = [&](int k) -> int32_t { return k < nl ? stack[nl - 1 - k] : -1; };
+            s_new[lane] = lane < nl ? stack[nl - 1 - lane] : -1;
+            __builtin_amdgcn_wave_barrier();
+            const int top = s_new[0];
+            if (out_state < 0) {
+                if (lane == 0) plan.mode = kRowDone;
+            } else if ((unsigned)top >= (unsigned)T.n_states) {
+                if (lane == 0) plan.mode = kRowEmpty;
+            } else {
+                plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+            }
+            if (lane == 0) { plan.top = top; plan.len = nl; }
+        } else {
         if (lane == 0) {
             err[b] = out_err;
             if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
         }
-        // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart):
         //      stage its top in LDS and commit the private part
-        const int nl = out_len;
         auto new_at = [&](int k) -> int32_t {           // entry k below the new top
             if (restarted) return k == 0 ? row[0] : -1;
             if (k < d) return priv.get(d - 1 - k);
@@ -239,6 +327,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
             plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
         }
         if (lane == 0) { plan.top = top; plan.len = nl; }
+        }
     }
     __syncthreads();
     // ---- the next mask row, by the whole block
@@ -346,14 +435,10 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
 }
 
 
-// Cycle-aware stack compaction (Sec. 3.2.3; Alg. 1 step 1): a complete traversal v1..vn of a
-// registered reduction cycle that lies right below another v1 carries no information and is taken
-// out.  The stack is rebuilt entry by entry from the bottom; after each entry that is the head of a
-// cycle, the n entries under it are compared with the cycle's states and dropped on a match (then
-// the check repeats).  One wave per sequence, the stack staged in LDS (cap entries per wave) next to
-// a copy of the cycle records (pool_n entries; 0 = read them from global memory); control flow is
-// uniform over the wave, lanes share the comparisons and the block moves.  A stack without any
-// cycle head costs one pass over its entries and writes nothing.
+// Stack compaction as a kernel of its own (after advance_kernel and jump_forward_kernel): one wave
+// per sequence, the stack staged in LDS (cap entries per wave) next to a copy of the cycle records
+// (pool_n entries; 0 = read them from global memory).  A stack without any cycle head costs one
+// pass over its entries and writes nothing.
 __global__ __launch_bounds__(256) void compact_stacks_kernel(const int32_t *__restrict__ cycle_head,
                                                              const int32_t *__restrict__ cycle_pool, int pool_n,
                                                              int n_states, int32_t *__restrict__ data,
@@ -377,47 +462,10 @@ __global__ __launch_bounds__(256) void compact_stacks_kernel(const int32_t *__re
     }
     if (!__any(any)) return;
     __builtin_amdgcn_wave_barrier();
-    int w = 0;                                          // entries of the rebuilt stack so far
-    for (int r0 = 0; r0 < n; r0 += 64) {
-        const int cnt = n - r0 < 64 ? n - r0 : 64;
-        const int x = lane < cnt ? s[r0 + lane] : -1;
-        const int hd = (unsigned)x < (unsigned)n_states ? cycle_head[x] : -1;
-        unsigned long long heads = __ballot(hd >= 0);
-        if (heads == 0 && w == r0) { w += cnt; continue; }
-        int prev = 0;                                   // entries of this chunk already moved
-        for (;;) {
-            const int j = heads ? __ffsll((long long)heads) - 1 : cnt - 1;   // the segment prev..j ends at a head or at the chunk's end
-            const int seg = j - prev + 1;
-            if (seg > 0) {
-                if (w != r0 + prev) {                   // all lanes read, then all lanes write: the ranges may overlap
-                    const int v = lane < seg ? s[r0 + prev + lane] : 0;
-                    __builtin_amdgcn_wave_barrier();
-                    if (lane < seg) s[w + lane] = v;
-                    __builtin_amdgcn_wave_barrier();
-                }
-                w += seg;
-            }
-            if (!heads) break;
-            heads &= heads - 1;
-            prev = j + 1;
-            const int first = __shfl(hd, j);            // s[w - 1] is the head of these cycles
-            int h = first;
-            while (h >= 0) {
-                const int k = __builtin_amdgcn_readfirstlane(pool[h]);
-                const int next = __builtin_amdgcn_readfirstlane(pool[h + 1]);
-                bool match = false;
-                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == pool[h + 2 + lane]);
-                if (match) {
-                    w -= k;                             // the top stays: s[w - 1] held the same state
-                    h = first;
-                } else {
-                    h = next;
-                }
-            }
-        }
-    }
+    int first_moved;
+    const int w = fold_cycles(s, n, cycle_head, pool, n_states, lane, &first_moved);
     if (w != n) {
-        for (int i = lane; i < w; i += 64) row[i] = s[i];
+        for (int i = first_moved + lane; i < w; i += 64) row[i] = s[i];
         if (lane == 0) len[b] = w;
     }
 }
@@ -436,12 +484,26 @@ size_t advance_fill_walk_spill_entries(int batch, int max_depth) {
 
 hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
-                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill, hipStream_t stream) {
+                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+                               const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    const size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
-    hipLaunchKernelGGL(advance_fill_kernel, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data, len, cap,
-                       batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64);
+    const size_t row_bytes = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    if (cycle_head) {                                  // cycle-aware stacks: the new stack is staged in LDS too
+        const size_t lds = row_bytes + (size_t)cap * sizeof(int32_t);
+        if (cap > kCompactMaxLen || lds > 65536) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(advance_fill_kernel<true>, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data,
+                           len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
+                           cycle_head, cycle_pool);
+    } else {
+        hipLaunchKernelGGL(advance_fill_kernel<false>, dim3(batch), dim3(kAfBlock), row_bytes, stream, T, E, tokens, states,
+                           data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
+                           nullptr, nullptr);
+    }
     return hipGetLastError();
+}
+
+bool advance_fill_fits_compact(int n_words, int cap) {
+    return cap <= kCompactMaxLen && (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t) + (size_t)cap * sizeof(int32_t) <= 65536;
 }
 
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,

@@ -489,12 +489,14 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
     const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    // With cycle-aware stacks the mask is looked up after the compaction (the condition trees are
-    // built for compacted stacks only), so the call takes the three launches below.
-    if (h->use_edges && !(h->compact && h->T.n_cycles > 0)) {
+    // With cycle-aware stacks the kernel compacts the new stack before it looks the mask up (the
+    // condition trees are built for compacted stacks); if the stack does not fit the kernel's LDS
+    // next to the mask row, the call takes the three launches below.
+    const bool cycles = h->compact && h->T.n_cycles > 0;
+    if (h->use_edges && (!cycles || advance_fill_fits_compact(h->V.n_words, h->b_stacks.cap))) {
         e = launch_advance_fill(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                 h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
-                                h->af_walk_spill, s);
+                                h->af_walk_spill, cycles ? h->cycle_head : nullptr, cycles ? h->cycle_pool : nullptr, s);
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
     }
     e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,

@@ -41,9 +41,13 @@ hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, i
                               int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
                               hipStream_t stream);
 size_t advance_fill_walk_spill_entries(int batch, int max_depth);   // int32 entries
+// cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (the call then needs
+// advance_fill_fits_compact), or null.
 hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
-                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill, hipStream_t stream);
+                               int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+                               const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream);
+bool advance_fill_fits_compact(int n_words, int cap);   // row bitmap + staged stack within 64 KB of LDS
 hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
                                uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
                                int32_t *lane_spill, hipStream_t stream);
