@@ -369,6 +369,16 @@ def main():
         "device state after the timed run differs from the oracle's replay"
     assert int(err_d.abs().sum().item()) == 0
     stack_len_after = {"mean": float(len_h.mean()), "max": int(len_h.max())}
+    # what one mask look-up touches (host evaluation of the same condition trees on the final stacks)
+    tree_nodes = deepest = leftover = 0
+    if not args.no_token_edges and lib.token_edge_stats()["built"]:
+        for b in range(B):
+            if states_h[b] < 0:
+                continue
+            ok, _, walk = lib.debug_resolve_row(data_h[b, : len_h[b]].copy())
+            tree_nodes += lib.last_resolve_info["path_nodes"]
+            deepest = max(deepest, lib.last_resolve_info["deepest_entry"])
+            leftover += len(walk) if ok else V
     # and the last mask on the device is the oracle's mask of the last timed step's input state
     restore()
     for s in range(K - 1):
@@ -537,6 +547,11 @@ def main():
                          "us_per_step": cpu_t / n_cpu * 1e6},
         "greedy": greedy,
         "jump_forward": None if args.eager else jump_forward_leg(),
+        "fill_mask_lookup": {"condition_nodes_visited_per_step": tree_nodes,
+                             "condition_nodes_per_s": tree_nodes / (float(two_call_us["fill_mask"].mean()) * 1e-6),
+                             "deepest_stack_entry_tested": deepest, "tokens_left_to_the_walk_per_step": leftover,
+                             "note": "host evaluation of the device's condition trees on the stacks after the timed steps; "
+                                     "the kernel is latency-bound: a descent of dependent loads per row, then a 16 KB row copy"},
         "fill_mask_byte_by_byte": None if (args.eager or args.no_token_edges) else byte_by_byte_leg(),
         "compile_s": t_compile,
         "stacks": {"cycle_aware": bool(compact), "reduction_cycles": len(lib.reduction_cycles()),
