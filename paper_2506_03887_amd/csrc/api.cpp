@@ -154,7 +154,7 @@ int upload_tables(pre3_handle *h) {
                 const int32_t known = r[0], peak = r[1], np = r[2] & kEffPushMask;
                 if (known < 256 && peak >= -128 && peak < 128 && np >= 1 && np <= 2)
                     c = make_int4(kCellInline | known | ((peak + 128) << 8) | (np << 16) |
-                                      ((r[2] & kEffSameShape) ? kCellSameShape : 0),
+                                      ((r[2] & kEffSameShape) ? kCellSameShape : 0) | ((r[2] & kEffGrow) ? kCellGrow : 0),
                                   r[3], r[4], np == 2 ? r[5] : 0);
             }
             cells[i] = c;

@@ -8,6 +8,7 @@ namespace pre3 {
 
 constexpr int32_t kCellInline = 1 << 30;
 constexpr int32_t kCellSameShape = 1 << 18;
+constexpr int32_t kCellGrow = 1 << 19;
 
 constexpr int kTokInfoBytes = 31;
 
@@ -23,7 +24,7 @@ struct DevTables {
     const int2 *sym_pairs;         // (condition state, child node)
     // [nodes * ncol] one 16-byte cell per (condition node, symbol column).  x < 0: SymbolEffectCode;
     // x with kCellInline: the whole edge (x = known | (peak + 128) << 8 | n_push << 16 | same-shape
-    // flag, y = kind after the edge, z and w = the one or two states pushed); otherwise x is the
+    // and growing flags, y = kind after the edge, z and w = the one or two states pushed); otherwise x is the
     // offset of the edge's record in sym_pool
     const int4 *sym_cell;
     const int32_t *sym_pool;       // effect records, 16-byte aligned

@@ -60,9 +60,15 @@ struct Builder {
                 bool same_shape = st.size() == nd.suffix.size() &&
                                   T.state_kind[st.back()] == T.state_kind[nd.suffix.back()];
                 for (size_t i = 1; same_shape && i + 1 < st.size(); ++i) same_shape = st[i] == nd.suffix[i];
+                // Growing edge (right-recursive lists, one element per symbol): the node knows the top
+                // and the entry x under it; the edge replaces the top by a second x and a new top of
+                // the same kind.  The next symbol meets the same node again, so a run of such symbols
+                // inserts one x each and replaces the top.
+                const bool grow = nd.suffix.size() == 2 && st.size() == 3 && st[1] == st[0] &&
+                                  T.state_kind[st.back()] == T.state_kind[nd.suffix.back()];
                 pool.push_back(nd.known);
                 pool.push_back(peak);
-                pool.push_back(((int32_t)st.size() - 1) | (same_shape ? kEffSameShape : 0));
+                pool.push_back(((int32_t)st.size() - 1) | (same_shape ? kEffSameShape : 0) | (grow ? kEffGrow : 0));
                 pool.push_back(T.state_kind[st.back()]);
                 pool.insert(pool.end(), st.begin() + 1, st.end());
                 deepest = std::max<int64_t>(deepest, nd.known);

@@ -25,9 +25,11 @@ enum SymbolEffectCode : int32_t {
     kEffStepwise = -4     // not precomputed (limits reached): follow the per-step edges
 };
 
-// n_push field of an effect record: low bits = number of pushes, flag = self-similar edge
+// n_push field of an effect record: low bits = number of pushes, flags = self-similar edge (the
+// stack keeps its shape) and growing edge (the stack gains one copy of the entry under the top)
 constexpr int32_t kEffPushMask = 0xFFFF;
 constexpr int32_t kEffSameShape = 1 << 16;
+constexpr int32_t kEffGrow = 1 << 17;
 
 struct SymbolNode {
     int32_t known;        // stack entries (from the top) fixed by this node

@@ -13,6 +13,7 @@ namespace pre3 {
 namespace {
 
 constexpr int kBlock = 256;            // threads per block of the walk kernel
+constexpr int kRunGrows = 1 << 30;      // flag on a run's condition node: the run's edges grow the stack
 constexpr int kLdsDepth = 16;          // private stack entries kept in LDS per lane
 constexpr int kMaxChain = 1 << 20;     // reduction steps per input symbol before a walk gives up
 
@@ -110,13 +111,14 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
             if (code >= 0) {
                 // the edge: truncate to (len - known + 1) entries, push np states (the last one is the
                 // acceptance edge's target); `peak` bounds the height reached on the way
-                int known, peak, np, same, after;
+                int known, peak, np, same, grow, after;
                 int4 push4;
                 if (code & kCellInline) {
                     known = code & 0xFF;
                     peak = ((code >> 8) & 0xFF) - 128;
                     np = (code >> 16) & 3;
                     same = code & kCellSameShape;
+                    grow = code & kCellGrow;
                     after = cell.y;
                     push4 = make_int4(cell.z, cell.w, 0, 0);
                 } else {
@@ -127,6 +129,7 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
                     peak = hdr.y;
                     np = hdr.z & kEffPushMask;
                     same = hdr.z & kEffSameShape;
+                    grow = hdr.z & kEffGrow;
                     after = hdr.w;
                 }
                 const int pops = known - 1;
@@ -147,7 +150,7 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
                     priv.set(d++, v);
                     top = v;
                 }
-                if (run_node) *run_node = (same && after == tree) ? node : -1;
+                if (run_node) *run_node = ((same || grow) && after == tree) ? (node | (grow ? kRunGrows : 0)) : -1;
                 tree = after;
                 return kFed;
             }
@@ -248,33 +251,50 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
 
 // After a self-similar edge found at condition node `node` (the stack kept its shape and the kind
 // of its top), every following symbol whose edge at the same node is again self-similar merely
-// replaces the top of the stack.  Each of the 64 lanes examines one upcoming byte
+// replaces the top of the stack; after a growing edge (`node` carries kRunGrows: the stack gained a
+// second copy of the entry under its top) every following growing edge at the same node inserts one
+// more copy and replaces the top.  Each of the 64 lanes examines one upcoming byte
 // (infos[first + lane], staged in LDS); the run ends at the first byte that is not such an edge.
-// Returns the number of bytes consumed; the last one's target becomes the new top.
+// Returns the number of bytes consumed; the last one's target becomes the new top, and a growing
+// run adds one private entry per byte (d grows).
 template <bool kCheckCap>
 __device__ __forceinline__ int apply_run(const DevTables &T, PrivateStack &priv, const int32_t *infos, int first,
-                                         int n_bytes, int node, int tree, int base, int d, int &top, int cap) {
-    const int i = first + (threadIdx.x & 63);
+                                         int n_bytes, int node, int tree, int base, int &d, int &top, int cap) {
+    const bool grows = (node & kRunGrows) != 0;
+    node &= ~kRunGrows;
+    const int lane = threadIdx.x & 63, i = first + lane;
+    const int gain = grows ? lane : 0;                  // entries added by the run's earlier bytes
     bool ok = i < n_bytes && i < 64;
-    int new_top = 0;
+    int new_top = 0, copy = 0;
     if (ok) {
         const int info = infos[i];
         const int4 cell = T.sym_cell[node * T.ncol + (info & 0xFF)];
         const int code = cell.x;
         ok = code >= 0;
         if (ok && (code & kCellInline)) {
-            ok = (code & kCellSameShape) && cell.y == tree && (!kCheckCap || base + d + ((code >> 8) & 0xFF) - 128 < cap);
+            ok = (code & (grows ? kCellGrow : kCellSameShape)) && cell.y == tree &&
+                 (!kCheckCap || base + d + gain + ((code >> 8) & 0xFF) - 128 < cap);
             new_top = (((code >> 16) & 3) == 1 ? cell.z : cell.w) + (info >> 8);
+            copy = cell.z;
         } else if (ok) {
             const int4 hdr = *reinterpret_cast<const int4 *>(T.sym_pool + code);
-            ok = (hdr.z & kEffSameShape) && hdr.w == tree && (!kCheckCap || base + d + hdr.y < cap);
-            if (ok) new_top = T.sym_pool[code + 4 + (hdr.z & kEffPushMask) - 1] + (info >> 8);
+            ok = (hdr.z & (grows ? kEffGrow : kEffSameShape)) && hdr.w == tree && (!kCheckCap || base + d + gain + hdr.y < cap);
+            if (ok) {
+                new_top = T.sym_pool[code + 4 + (hdr.z & kEffPushMask) - 1] + (info >> 8);
+                copy = T.sym_pool[code + 4];
+            }
         }
     }
     const unsigned long long bad = __ballot(!ok);
-    const int run = bad ? __ffsll((long long)bad) - 1 : 64;
+    int run = bad ? __ffsll((long long)bad) - 1 : 64;
+    if (grows && d + run > T.max_depth) run = T.max_depth > d ? T.max_depth - d : 0;    // cannot happen: see the depth bound
     if (run > 0) {
         top = __builtin_amdgcn_readfirstlane(__shfl(new_top, run - 1));
+        if (grows) {
+            const int x = __builtin_amdgcn_readfirstlane(copy);       // the same entry for every byte of the run
+            for (int j = 0; j < run; ++j) priv.set(d - 1 + j, x);
+            d += run;
+        }
         priv.set(d - 1, top);
     }
     return run;
