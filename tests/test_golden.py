@@ -66,3 +66,16 @@ def test_the_stack_starts_with_the_start_state_only():
     for name in REC["start_state_only_initially"].split():
         o = Oracle(getattr(G, name))
         assert o.initial_stack() == [o.initial_state(0)] == [0]
+
+
+def test_a_complete_cycle_traversal_leaves_no_trace_on_the_stack():
+    o, plain = Oracle(G.RIGHT_LIST, compact_cycles=True), Oracle(G.RIGHT_LIST)
+    for item in REC["cycle_traversal_is_popped"].split():
+        prefix, want = item.rsplit("=", 1)
+        rc, st = o.advance(o.initial_stack(), prefix.encode())
+        rc_p, st_p = plain.advance(plain.initial_stack(), prefix.encode())
+        assert rc == rc_p == 0 and len(st) == int(want), (prefix, st)
+        assert len(st_p) == len(prefix) + 1                         # the plain stack keeps every element
+        for tail in (b"", b",x", b",", b"x", b",x,x", b",,"):       # equivalent state: same continuations
+            a, b = o.advance(st, tail) if tail else (0, st), plain.advance(st_p, tail) if tail else (0, st_p)
+            assert a[0] == b[0] and (a[0] != 0 or o.eos_allowed(a[1]) == plain.eos_allowed(b[1])), (prefix, tail)
