@@ -89,6 +89,59 @@ def test_deep_tokens_spill_the_private_stack(deep_vocab, token_edges):
     assert l_h.max() > 60                                        # a 32-bracket token was committed
 
 
+@pytest.mark.parametrize("grammar,compact,token_edges", [("JSON", False, True), ("JSON", False, False),
+                                                         ("JSON_RIGHT_RECURSIVE", True, True), ("JSON_RIGHT_RECURSIVE", False, True)])
+def test_tokens_of_the_maximum_length(grammar, compact, token_edges):
+    """Tokens of 254 bytes, the longest the library accepts (and of 65..253): strings, digits, white
+    space, escapes, 254 opening brackets, lists -- beyond the bytes a walk stages per token and beyond
+    the length of a run; masks on several stacks and an advance by each of them against the oracle."""
+    torch, dev = _torch()
+    text = getattr(G, grammar)
+    base = bpe_like_vocab(400, 8, BASE_SEED + 79).tokens[:-1]
+    long_tokens = [b'"' + b"x" * 252 + b'"', b"[" * 254, b"1" * 254, b'"' + b"ab" * 100, b"[1," * 84, b" " * 254,
+                   b'"' + b"\\n" * 120 + b'"', b"7" * 65, b'"' + b"y" * 63, b'"' + b"y" * 64 + b'"', b"[" * 100 + b"]" * 100,
+                   b"[[],[[]],{}," * 21, b'{"k":' * 50, b'"' + b"z" * 253 + b'"x']
+    assert max(len(t) for t in long_tokens) == 256 and sum(len(t) == 254 for t in long_tokens) >= 4
+    long_tokens[-1] = long_tokens[-1][:254]              # 254 bytes that end inside the string
+    toks = base + long_tokens + [b""]
+    v = Vocab(toks, len(toks) - 1)
+    assert v.max_len == 254
+    cap = 1024
+    o = Oracle([text], compact_cycles=compact)
+    from paper_2506_03887_amd import Pre3
+    lib = Pre3([text], v.bytes, v.offsets, v.eos_id, max_token_len=254, stack_cap=cap, token_edges=token_edges,
+               compact_cycles=compact)
+    prefixes = [b"", b"[", b'{"a":', b'"abc', b"[1", b"[[[[", b'{"a":[1,', b"12", b'["q",', b"[ ", b'"\\', b"[[[[[[[[[[", b"-", b'{"k":{"k":']
+    states, data, length = _stacks(o, prefixes, cap)
+    if compact:
+        o.compact_batch(data, length)
+    B = len(prefixes)
+    got = _gpu_mask(lib, states, data, length, v.words)
+    want = o.fill_mask(states, data, length, v)
+    assert (got == want).all()
+    first_long = len(base)
+    allowed_long = sum(int((want[b, t >> 5] >> (t & 31)) & 1) for b in range(B) for t in range(first_long, first_long + len(long_tokens)))
+    assert allowed_long >= 25, allowed_long
+    for k in range(len(long_tokens)):                    # every sequence takes long token k (allowed or not)
+        s_h, d_h, l_h = states.copy(), data.copy(), length.copy()
+        s_d, d_d, l_d = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+        e_d = torch.full((B,), -5, dtype=torch.int32, device=dev)
+        m_d = torch.zeros((B, v.words), dtype=torch.int32, device=dev)
+        lib.bind_state(s_d, d_d, l_d, e_d)
+        tok = np.full(B, first_long + k, dtype=np.int32)
+        if k % 2:
+            lib.advance(torch.from_numpy(tok).to(dev))
+        else:
+            lib.advance_fill_mask(torch.from_numpy(tok).to(dev), m_d)
+        err = o.advance_batch(s_h, d_h, l_h, tok, v)
+        assert (e_d.cpu().numpy() == err).all(), (k, long_tokens[k][:12])
+        assert (s_d.cpu().numpy() == s_h).all() and (l_d.cpu().numpy() == l_h).all(), k
+        live = np.arange(cap)[None, :] < l_h[:, None]
+        assert (d_d.cpu().numpy()[live] == d_h[live]).all(), k
+        if k % 2 == 0:
+            assert (m_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_h, d_h, l_h, v)).all(), k
+
+
 def test_advance_error_codes_and_overflow(deep_vocab):
     o = Oracle(G.JSON)
     v = deep_vocab
