@@ -142,6 +142,44 @@ def test_tokens_of_the_maximum_length(grammar, compact, token_edges):
             assert (m_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_h, d_h, l_h, v)).all(), k
 
 
+def test_very_deep_stacks(deep_vocab):
+    """Stacks of tens of thousands of entries (capacity 65,536): 9,000 to 32,750 open brackets, then
+    masks, advances that close many levels at once, and an advance that would pass the capacity."""
+    torch, dev = _torch()
+    o = Oracle(G.JSON)
+    v = deep_vocab
+    cap = 65536
+    lib = _lib(G.JSON, v, stack_cap=cap)
+    prefixes = [b"[" * 9000, b"[" * 30000 + b"1", b'{"a":' * 3000 + b"[", b"[" * 32750, b"[" * 32740 + b'"s"']
+    states, data, length = _stacks(o, prefixes, cap)
+    assert length.max() > 65000 and length.min() > 15000
+    got = _gpu_mask(lib, states, data, length, v.words)
+    assert (got == o.fill_mask(states, data, length, v)).all()
+    s_d, d_d, l_d = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+    e_d = torch.full((len(prefixes),), -5, dtype=torch.int32, device=dev)
+    m_d = torch.zeros((len(prefixes), v.words), dtype=torch.int32, device=dev)
+    lib.bind_state(s_d, d_d, l_d, e_d)
+    s_h, d_h, l_h = states.copy(), data.copy(), length.copy()
+    seq = [[v.tokens.index(b"[" * 32), v.tokens.index(b"]]]]]]]],"), v.tokens.index(b"[1," * 10), v.tokens.index(b"[" * 32),
+            v.tokens.index(b"]" * 20)],
+           [v.tokens.index(b"]" * 20)] * 5]
+    for step in range(5):
+        tok = np.array([seq[0][step], seq[1][step], seq[0][step], seq[0][step], seq[1][step]], dtype=np.int32)
+        if step % 2:
+            lib.advance(torch.from_numpy(tok).to(dev))
+        else:
+            lib.advance_fill_mask(torch.from_numpy(tok).to(dev), m_d)
+        err = o.advance_batch(s_h, d_h, l_h, tok, v)
+        assert (e_d.cpu().numpy() == err).all(), step
+        assert (s_d.cpu().numpy() == s_h).all() and (l_d.cpu().numpy() == l_h).all(), step
+        live = np.arange(cap)[None, :] < l_h[:, None]
+        assert (d_d.cpu().numpy()[live] == d_h[live]).all(), step
+        if step % 2 == 0:
+            assert (m_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_h, d_h, l_h, v)).all(), step
+        if step == 0:
+            assert err[3] == 2 and err[0] == 0               # 32 more brackets do not fit under the capacity
+
+
 def test_advance_error_codes_and_overflow(deep_vocab):
     o = Oracle(G.JSON)
     v = deep_vocab
