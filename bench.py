@@ -47,8 +47,6 @@ def main():
                     help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
     ap.add_argument("--no-token-edges", action="store_true",
                     help="compile without token-level edges: fill_mask walks every (sequence, token) pair")
-    ap.add_argument("--no-compact", action="store_true",
-                    help="a workload that keeps cycle-aware stacks is run without them (stacks then grow with every list)")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
@@ -95,7 +93,7 @@ def main():
     total = K + Wm
 
     # ---- inputs: oracle-driven seeded trajectory (host), then everything uploaded
-    compact = cfg.compact and not args.no_compact
+    compact = cfg.compact
     o = Oracle(cfg.grammars, compact_cycles=compact)
     gi, depths = configs.sequence_setup(cfg)
     traj = trajectory.generate(o, v, B, total, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
