@@ -50,6 +50,7 @@ struct pre3_handle {
     size_t argmax_bytes = 0;
     unsigned long long *topk_cand = nullptr;     // per-segment candidates of pre3_apply_mask_topk
     size_t topk_bytes = 0;
+    bool topk_ready = false;
     int n_compute_units = 0;
     size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
@@ -398,8 +399,11 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
         h->argmax_best = static_cast<unsigned long long *>(p);
         h->argmax_bytes = need_arg;
     }
+    // the top-k candidates: batch x segments x 64 words; a batch so large that this passes 1 GiB goes
+    // without (pre3_apply_mask_topk then reports PRE3_E_LIMIT)
     const size_t need_topk = masked_topk_workspace_bytes(stacks.batch, h->V.n_tokens);
-    if (need_topk > h->topk_bytes) {
+    h->topk_ready = need_topk <= ((size_t)1 << 30);
+    if (h->topk_ready && need_topk > h->topk_bytes) {
         void *p = nullptr;
         hipError_t e = device_alloc(h, need_topk, &p, false);
         if (e != hipSuccess) return hip_fail(h, e, "allocate top-k workspace");
@@ -527,6 +531,7 @@ int pre3_apply_mask_topk(pre3_handle *h, const uint16_t *logits_bf16, int64_t ro
     if (!logits_bf16 || !bitmask || !out_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_topk: null pointer");
     if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "apply_mask_topk: row stride below vocabulary size");
     if (k < 1 || k > PRE3_TOPK_MAX) return fail(h, PRE3_E_BADARG, "apply_mask_topk: k outside 1..PRE3_TOPK_MAX");
+    if (!h->topk_ready) return fail(h, PRE3_E_LIMIT, "apply_mask_topk: batch x vocabulary too large for the candidate workspace (1 GiB)");
     if (!masked_topk_fits(h->V.n_tokens, k))
         return fail(h, PRE3_E_LIMIT, "apply_mask_topk: ceil(n_tokens / 8192) * k must not exceed 1536");
     hipError_t e = launch_masked_topk(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride, k, h->topk_cand,
