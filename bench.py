@@ -519,7 +519,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": t_step / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 bitmask / bf16 logits / i32 states",
+        "dtype": "i32 (integer and bit work: i32 states, u32 bitmask words; the bf16 logits are selected, not computed on)",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": GRAMMAR_LABEL.get(cfg.idx, cfg.name) + ", canonical LR(1)",
                    "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
