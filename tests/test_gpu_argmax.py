@@ -154,7 +154,8 @@ def test_masked_topk_argument_errors():
                             torch.zeros((B, 4), dtype=torch.int32, device=dev))     # rows shorter than the vocabulary
 
 
-@pytest.mark.parametrize("cfg_idx,steps,fused_advance", [(1, 32, False), (2, 48, False), (2, 48, True), (3, 12, True)])
+@pytest.mark.parametrize("cfg_idx,steps,fused_advance", [(1, 32, False), (2, 48, False), (2, 48, True), (3, 12, True),
+                                                         (2, 400, True), (6, 10, True), (7, 10, True)])
 def test_greedy_decode_in_lockstep_with_the_oracle(cfg_idx, steps, fused_advance):
     """Both sides decode greedily from the same seeded logits; tokens, states, stacks, err and
     masks must agree at every step (a sequence that ends restarts, as in the benchmark)."""
@@ -163,14 +164,15 @@ def test_greedy_decode_in_lockstep_with_the_oracle(cfg_idx, steps, fused_advance
     cfg = configs.get(cfg_idx)
     v = cfg.vocab
     B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
-    o = Oracle(cfg.grammars)
+    o = Oracle(cfg.grammars, compact_cycles=cfg.compact)
     gi, _ = configs.sequence_setup(cfg)
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
     data_h = np.zeros((B, cap), dtype=np.int32)
     data_h[:, 0] = s0
     len_h = np.ones(B, dtype=np.int32)
     states_h = s0.copy()
-    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap)
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
+               compact_cycles=cfg.compact)
     data_d, len_d = torch.from_numpy(data_h.copy()).to(dev), torch.from_numpy(len_h.copy()).to(dev)
     states_d, err_d = torch.from_numpy(states_h.copy()).to(dev), torch.zeros(B, dtype=torch.int32, device=dev)
     lib.bind_state(states_d, data_d, len_d, err_d)
