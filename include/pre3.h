@@ -223,8 +223,8 @@ int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t 
  * pre3_apply_mask_argmax.  The logits are read once and not modified (groups of 8 masked tokens
  * are not read).  1 <= k <= PRE3_TOPK_MAX; layouts and the workspace rule as for
  * pre3_apply_mask_argmax.  Errors: BADARG (nothing bound, null pointer, row_stride < n_tokens, k out
- * of range), LIMIT (ceil(n_tokens / 8192) * k above 1536: k = 64 serves up to 196,608 tokens; or a
- * bound batch whose candidate workspace, batch * ceil(n_tokens / 8192) * 512 bytes, would pass 1 GiB). */
+ * of range), LIMIT (ceil(n_tokens / 16384) * k above 1024: k = 64 serves up to 262,144 tokens; or a
+ * bound batch whose candidate workspace, batch * ceil(n_tokens / 16384) * 512 bytes, would pass 1 GiB). */
 int pre3_apply_mask_topk(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
                          int32_t k, int32_t *out_tokens, uint16_t *out_logits, pre3_stream stream);
 

@@ -35,7 +35,7 @@ size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);
 // The k largest allowed logits of every row (k <= kTopkMax), ids in out_ids[batch * k] (-1 padded),
 // their bf16 patterns in out_vals (may be null; 0xFF80 padded).
 constexpr int kTopkMax = 64;
-bool masked_topk_fits(int vocab, int k);      // (segments of 8,192 tokens) x k <= 1,536 candidates per row
+bool masked_topk_fits(int vocab, int k);      // (segments of 16,384 tokens) x k <= 1,024 candidates per row
 size_t masked_topk_workspace_bytes(int batch, int vocab);
 hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                               int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,

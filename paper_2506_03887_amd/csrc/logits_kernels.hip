@@ -335,18 +335,21 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
 }
 
 // The k best candidates of one segment of one row (blockIdx.x = row, blockIdx.y = segment of
-// kTopkSeg tokens).  Every thread keeps the keys of its 16 tokens in registers (0 = masked, NaN or
-// beyond the vocabulary), so the logits are read once.
+// kTopkSeg tokens).  Every thread keeps the 16-bit keys of its 32 tokens in registers, two per
+// register (0 = masked, NaN or beyond the vocabulary), so the logits are read once.
 //   Fast path: from the per-thread maxima the block derives a lower bound M of the segment's k-th
 //   largest key (at least k threads hold a key >= M), so only keys >= M can be among the k best:
 //   usually a few times k of them.  They are collected in an LDS list; with at most one per thread
 //   every thread ranks its word against the list, otherwise wave 0 selects the k best bit by bit.
 //   If the list overflows -- only possible when thousands of keys tie with M -- every wave selects
-//   the k best of its own 1,024 tokens (ties by id) and wave 0 merges the waves' lists.
+//   the k best of its own 2,048 tokens (ties by id) and wave 0 merges the waves' lists.
 // The k words are written, in no particular order, to out[(row * n_seg + segment) * k ..], 0-padded.
+// The phases after the load cost about a microsecond per block whatever its size, so a block covers
+// as many tokens as its registers hold.
 constexpr int kTopkBlock = 512;
 constexpr int kTopkWaves = kTopkBlock / 64;
-constexpr int kTopkSeg = 16 * kTopkBlock;
+constexpr int kTopkPerThread = 32;
+constexpr int kTopkSeg = kTopkPerThread * kTopkBlock;
 constexpr int kTopkList = 2048;
 __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
@@ -362,37 +365,46 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     const int n_mask_bytes = n_words * 4;
     unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
-    uint32_t key[16];
-    // element i of a thread is token  seg * kTopkSeg + rel(i),  rel(i) = (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7)
-    auto rel = [&](int i) { return (tid + (i >> 3) * kTopkBlock) * 8 + (i & 7); };
+    // element e of a thread (0 .. 31) is token  seg * kTopkSeg + rel(e); its key is half (e & 1) of kp[e >> 1]
+    auto rel = [&](int e) { return (tid + (e >> 3) * kTopkBlock) * 8 + (e & 7); };
+    uint32_t kp[kTopkPerThread / 2];
+    auto key_at = [&](int e) { return (kp[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu; };
+    uint32_t m[kTopkPerThread / 8];
+    uint4 v[kTopkPerThread / 8];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int t0 = seg * kTopkSeg + (tid + half * kTopkBlock) * 8;
-        const uint32_t m = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
-        uint32_t h[8];
+    for (int g = 0; g < kTopkPerThread / 8; ++g) {
+        const int t0 = seg * kTopkSeg + (tid + g * kTopkBlock) * 8;
+        m[g] = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
+    }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) h[j] = 0x7FC0u;           // NaN: no candidate
-        if (m != 0u) {
+    for (int g = 0; g < kTopkPerThread / 8; ++g) {
+        const int t0 = seg * kTopkSeg + (tid + g * kTopkBlock) * 8;
+        v[g] = make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);   // NaN: no candidate
+        if (m[g] != 0u) {
             if (vec_ok && t0 + 8 <= vocab) {
-                const uint4 v = stream_load(lrow + (size_t)t0);
-                const uint32_t x[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { h[2 * j] = x[j] & 0xFFFFu; h[2 * j + 1] = x[j] >> 16; }
+                v[g] = stream_load(lrow + (size_t)t0);
             } else {
+                uint32_t h[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t0 + j < vocab) h[j] = lrow[t0 + j];
+                for (int j = 0; j < 8; ++j) h[j] = t0 + j < vocab ? (uint32_t)lrow[t0 + j] : 0x7FC0u;
+                v[g] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
             }
         }
+    }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool ok = ((m >> j) & 1u) && (h[j] & 0x7FFFu) <= 0x7F80u;
-            key[half * 8 + j] = ok ? bf16_key(h[j]) : 0u;
+    for (int g = 0; g < kTopkPerThread / 8; ++g) {
+        const uint32_t x[4] = {v[g].x, v[g].y, v[g].z, v[g].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t lo = x[j] & 0xFFFFu, hi = x[j] >> 16;
+            const bool ok_lo = ((m[g] >> (2 * j)) & 1u) && (lo & 0x7FFFu) <= 0x7F80u;
+            const bool ok_hi = ((m[g] >> (2 * j + 1)) & 1u) && (hi & 0x7FFFu) <= 0x7F80u;
+            kp[g * 4 + j] = (ok_lo ? bf16_key(lo) : 0u) | ((ok_hi ? bf16_key(hi) : 0u) << 16);
         }
     }
     uint32_t best = 0u;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) best = key[i] > best ? key[i] : best;
+    for (int e = 0; e < kTopkPerThread; ++e) best = key_at(e) > best ? key_at(e) : best;
     // A lower bound of the segment's k-th largest key from the threads' maxima: wave w takes the
     // q_w-th largest of its 64 maxima, q_w = min(j, threads of w that hold a candidate), with the
     // smallest j for which the q_w add up to k; the smallest of these is reached by at least k keys.
@@ -432,12 +444,14 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
         if (tid < k) dst[tid] = 0ull;
         return;
     }
+    if (best >= bound) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-        if (key[i] >= bound) {
-            const int slot = atomicAdd(&s_count, 1);
-            if (slot < kTopkList) s_list[slot] = topk_word(key[i], (uint32_t)(seg * kTopkSeg + rel(i)));
-        }
+        for (int e = 0; e < kTopkPerThread; ++e)
+            if (key_at(e) >= bound) {
+                const int slot = atomicAdd(&s_count, 1);
+                if (slot < kTopkList) s_list[slot] = topk_word(key_at(e), (uint32_t)(seg * kTopkSeg + rel(e)));
+            }
+    }
     __syncthreads();
     const int S = s_count;
     if (S <= kTopkBlock) {
@@ -461,24 +475,23 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
         for (int r0 = 0; r0 < S; r0 += 64) {
             const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
             const bool take = w >= thr && w != 0ull;
-            const unsigned long long m = __ballot(take);
-            if (take) dst[base + __popcll(m & ((1ull << lane) - 1ull))] = w;
-            base += __popcll(m);
+            const unsigned long long mm = __ballot(take);
+            if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
+            base += __popcll(mm);
         }
         if (lane >= kk && lane < k) dst[lane] = 0ull;
         return;
     }
     // thousands of ties: exact selection per wave, then a merge by wave 0
-    auto key_at = [&](int i) { return key[i]; };
-    auto pref_at = [&](int i) { return (uint32_t)(kTopkSeg - rel(i)); };     // 1 .. kTopkSeg, larger = smaller id
+    auto pref_at = [&](int e) { return (uint32_t)(kTopkSeg - rel(e)); };     // 1 .. kTopkSeg, larger = smaller id
     uint32_t T, P;
     int kk;
-    wave_select<16>(key_at, pref_at, 15, k, &T, &P, &kk);
+    wave_select<kTopkPerThread>(key_at, pref_at, 15, k, &T, &P, &kk);
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-        if (key[i] > T || (key[i] == T && pref_at(i) >= P)) {
+    for (int e = 0; e < kTopkPerThread; ++e)
+        if (key_at(e) > T || (key_at(e) == T && pref_at(e) >= P)) {
             const int slot = atomicAdd(&s_n[wave], 1);
-            if (slot < kTopkMax) s_sel[wave][slot] = topk_word(key[i], (uint32_t)(seg * kTopkSeg + rel(i)));
+            if (slot < kTopkMax) s_sel[wave][slot] = topk_word(key_at(e), (uint32_t)(seg * kTopkSeg + rel(e)));
         }
     __syncthreads();
     if (wave != 0) return;
@@ -492,9 +505,9 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
 #pragma unroll
     for (int i = 0; i < kTopkWaves; ++i) {
         const bool take = c[i] != 0ull && (ckey_at(i) > T || (ckey_at(i) == T && cpref_at(i) >= P));
-        const unsigned long long m = __ballot(take);
-        if (take) dst[base + __popcll(m & ((1ull << lane) - 1ull))] = c[i];
-        base += __popcll(m);
+        const unsigned long long mm = __ballot(take);
+        if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = c[i];
+        base += __popcll(mm);
     }
     if (lane >= kk && lane < k) dst[lane] = 0ull;
 }
@@ -504,7 +517,7 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
 // largest word from below; the words that reach it go to an LDS list.  Up to 256 listed words are
 // ranked directly (a word's rank = number of larger words) and those ranked below k written in
 // order; a longer list is first cut to its k best bit by bit.
-constexpr int kTopkFinishPer = 24;
+constexpr int kTopkFinishPer = 16;
 __global__ __launch_bounds__(64) void masked_topk_finish_kernel(
     const unsigned long long *__restrict__ cand, int n_cand, int k, const uint16_t *__restrict__ logits,
     int64_t row_stride, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
