@@ -99,3 +99,39 @@ def test_random_grammars_three_ways():
                     rc_l, st_l = lib.debug_advance(st, v.tokens[t], cap=64, merged=merged)
                     assert rc_l == rc_o and (rc_o != 0 or list(st_l) == list(st_o)), (text, p, v.tokens[t], merged)
     assert accepted >= 40 and rejected >= 10, (accepted, rejected, tried)
+
+
+def test_both_sides_read_the_same_grammar_texts():
+    """The grammar text format is specified once and implemented twice: seeded random edits of valid
+    texts (deleted, inserted, replaced characters: quotes, brackets, bars, escapes, comments, line
+    breaks) must be accepted or refused by both, and where accepted give automata of the same size."""
+    from workloads import grammars as G
+    rnd = random.Random(2506_03887 + 9)
+    v = Vocab([bytes([c]) for c in range(256)] + [b""], 256)
+    bases = [G.ARITHMETIC, G.RIGHT_LIST, G.EPSILON_MIX, G.DYCK, 'S ::= [a-c] S | "x" # c\n',
+             'S ::= A\n  | "q"\nA ::= [^a-y] | "\\x41\\n"\n', G.JSON]
+    alphabet = '"[]|:=\\ \n#^-ax1S'
+    accepted = refused = 0
+    for _ in range(2500):
+        t = list(rnd.choice(bases))
+        for _ in range(rnd.randint(1, 3)):
+            kind, pos = rnd.randrange(3), rnd.randrange(len(t) + 1)
+            if kind == 0 and t:
+                del t[min(pos, len(t) - 1)]
+            elif kind == 1:
+                t.insert(pos, rnd.choice(alphabet))
+            elif t:
+                t[min(pos, len(t) - 1)] = rnd.choice(alphabet)
+        text = "".join(t)
+        try:
+            n_oracle = Oracle([text]).n_states(0)
+        except GrammarError:
+            n_oracle = None
+        try:
+            n_lib = Pre3([text], v.bytes, v.offsets, v.eos_id, max_token_len=1, host_only=True, token_edges=False).n_states
+        except Pre3Error:
+            n_lib = None
+        assert n_oracle == n_lib, (text, n_oracle, n_lib)
+        accepted += n_oracle is not None
+        refused += n_oracle is None
+    assert accepted > 150 and refused > 1500, (accepted, refused)
