@@ -180,6 +180,50 @@ def test_very_deep_stacks(deep_vocab):
             assert err[3] == 2 and err[0] == 0               # 32 more brackets do not fit under the capacity
 
 
+@pytest.mark.parametrize("token_edges", [True, False])
+def test_vocabulary_of_arbitrary_bytes(token_edges):
+    """Tokens drawn from all 256 byte values (NUL, control bytes, 0x80..0xFF, quotes and backslashes in
+    any position), duplicates and empty tokens included; masks on stacks inside and outside strings,
+    then every sequence advances by a random token of the vocabulary, allowed or not."""
+    torch, dev = _torch()
+    rng = np.random.default_rng(BASE_SEED + 83)
+    toks = [bytes(rng.integers(0, 256, size=int(rng.integers(1, 7)), dtype=np.uint8).tolist()) for _ in range(5000)]
+    toks += [bytes([c]) for c in range(256)] + [b"", b"", toks[3], toks[3], b"\x00", b"\xff\xfe", b'"\x80"', b"\\\xff"]
+    toks.append(b"")
+    v = Vocab(toks, len(toks) - 1)
+    o = Oracle(G.JSON)
+    lib = _lib(G.JSON, v, token_edges=token_edges)
+    prefixes = [b"", b'"', b'"\x80\xffa', b'"\\', b'["\x7f', b'{"k\xc3\xa9":"', b"[1", b'{"a":', b'"\\u00', b"[[[", b'{"a":"b",', b"tru"]
+    states, data, length = _stacks(o, prefixes, 64)
+    got = _gpu_mask(lib, states, data, length, v.words)
+    want = o.fill_mask(states, data, length, v)
+    assert (got == want).all()
+    assert want[1].view(np.uint8).sum() > want[0].view(np.uint8).sum()     # inside a string far more tokens are allowed
+    s_d, d_d, l_d = (torch.from_numpy(x.copy()).to(dev) for x in (states, data, length))
+    e_d = torch.full((len(prefixes),), -5, dtype=torch.int32, device=dev)
+    lib.bind_state(s_d, d_d, l_d, e_d)
+    s_h, d_h, l_h = states.copy(), data.copy(), length.copy()
+    n_ok = 0
+    for step in range(40):
+        tok = rng.integers(0, v.n_tokens, size=len(prefixes)).astype(np.int32)
+        if step % 2:                                          # every other step: a token that is allowed, if any
+            for b in range(len(prefixes)):
+                row = o.mask_row(d_h[b, : l_h[b]], v, done=s_h[b] < 0)
+                ids = np.flatnonzero((row[np.arange(v.n_tokens) >> 5] >> (np.arange(v.n_tokens) & 31).astype(np.uint32)) & 1)
+                ids = ids[ids != v.eos_id]
+                if len(ids):
+                    tok[b] = ids[rng.integers(len(ids))]
+        lib.advance(torch.from_numpy(tok).to(dev))
+        err = o.advance_batch(s_h, d_h, l_h, tok, v)
+        n_ok += int((err == 0).sum())
+        assert (e_d.cpu().numpy() == err).all(), step
+        assert (s_d.cpu().numpy() == s_h).all() and (l_d.cpu().numpy() == l_h).all(), step
+        live = np.arange(64)[None, :] < l_h[:, None]
+        assert (d_d.cpu().numpy()[live] == d_h[live]).all(), step
+    assert n_ok > 150
+    assert (_gpu_mask(lib, s_h, d_h, l_h, v.words) == o.fill_mask(s_h, d_h, l_h, v)).all()
+
+
 def test_advance_error_codes_and_overflow(deep_vocab):
     o = Oracle(G.JSON)
     v = deep_vocab
