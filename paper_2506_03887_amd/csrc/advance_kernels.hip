@@ -121,10 +121,16 @@ __device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *__r
 // serialise each other's reduction chains) and lets the chip overlap the chains of all
 // sequences.  The walk runs on a private overlay exactly like in the mask kernels; only a walk
 // that succeeds is committed to the sequence's stack.
+// kCompact (cycle-aware stacks): instead of committing the private entries, the wave puts the new
+// stack together in LDS (cap entries per sequence), takes complete traversals of reduction cycles
+// out of it (fold_cycles) and writes back what changed.
 constexpr int kAdvSeqPerBlock = 4;
+template <bool kCompact>
 __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
-    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos) {
+    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos,
+    const int32_t *__restrict__ cycle_head, const int32_t *__restrict__ cycle_pool) {
+    extern __shared__ int32_t adv_stage[];             // kCompact: kAdvSeqPerBlock x cap stack entries
     __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
     __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
     __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
@@ -151,6 +157,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     __builtin_amdgcn_wave_barrier();
     // all lanes hold identical values from here on; lane 0 alone writes the results
     int commit = -1, out_err = 0, out_state = st, out_len = n;
+    int new_base = n, new_d = 0;                        // the new stack is  row[0 .. new_base) ++ priv[0 .. new_d)
     if (t >= 0) {
         int top = live ? __builtin_amdgcn_readfirstlane(s_win[wave][0]) : -1;
         if (!live || (unsigned)top >= (unsigned)T.n_states) {
@@ -175,6 +182,8 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
                     out_len = base + d;
                     out_state = top;
                     s_base[wave] = base;
+                    new_base = base;
+                    new_d = d;
                 }
             }
         }
@@ -184,6 +193,18 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
         }
     } else if (lane == 0) {
         err[b] = 0;
+    }
+    if (kCompact && n >= 1 && n <= cap) {
+        int32_t *stack = adv_stage + wave * cap;
+        int nl = out_len;                               // 1 after a restart: only the bottom entry stays
+        for (int i = lane; i < nl; i += 64) stack[i] = i < new_base ? row[i] : priv.get(i - new_base);
+        __builtin_amdgcn_wave_barrier();
+        int first_moved = nl;
+        if (out_state >= 0 && nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+        const int from = first_moved < new_base ? first_moved : new_base;
+        for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
+        if (lane == 0 && nl != out_len) len[b] = nl;    // the top, hence states[b], is the same
+        return;
     }
     s_depth[wave] = commit;
     __builtin_amdgcn_wave_barrier();
@@ -506,11 +527,23 @@ bool advance_fill_fits_compact(int n_words, int cap) {
     return cap <= kCompactMaxLen && (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t) + (size_t)cap * sizeof(int32_t) <= 65536;
 }
 
+bool advance_fits_compact(int cap) {
+    return cap <= kCompactMaxLen && (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + 4096 <= 65536;
+}
+
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
-                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos, hipStream_t stream) {
+                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
+                          const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    hipLaunchKernelGGL(advance_kernel, dim3((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), dim3(64 * kAdvSeqPerBlock),
-                       0, stream, T, tokens, states, data, len, cap, batch, err, scratch, restart_on_eos);
+    const dim3 grid((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), block(64 * kAdvSeqPerBlock);
+    if (cycle_head) {                                  // cycle-aware stacks: the new stack is staged in LDS
+        if (!advance_fits_compact(cap)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(advance_kernel<true>, grid, block, (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t), stream, T, tokens,
+                           states, data, len, cap, batch, err, scratch, restart_on_eos, cycle_head, cycle_pool);
+    } else {
+        hipLaunchKernelGGL(advance_kernel<false>, grid, block, 0, stream, T, tokens, states, data, len, cap, batch, err,
+                           scratch, restart_on_eos, nullptr, nullptr);
+    }
     return hipGetLastError();
 }
 

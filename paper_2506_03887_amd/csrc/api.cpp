@@ -477,9 +477,12 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
     if (h->bound_empty) return PRE3_OK;
     if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance: no state bound");
     if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
+    // cycle-aware stacks: compacted inside the kernel when four staged stacks fit its LDS, else by a kernel of its own
+    const bool fused = h->compact && h->T.n_cycles > 0 && advance_fits_compact(h->b_stacks.cap);
     hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
-                                  h->b_stacks.batch, h->b_err, h->adv_scratch, 0, static_cast<hipStream_t>(stream));
-    if (e == hipSuccess) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
+                                  h->b_stacks.batch, h->b_err, h->adv_scratch, 0, fused ? h->cycle_head : nullptr,
+                                  fused ? h->cycle_pool : nullptr, static_cast<hipStream_t>(stream));
+    if (e == hipSuccess && !fused) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance");
 }
 
@@ -504,7 +507,7 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
     }
     e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
-                       h->b_stacks.batch, h->b_err, h->adv_scratch, restart, s);
+                       h->b_stacks.batch, h->b_err, h->adv_scratch, restart, nullptr, nullptr, s);
     if (e == hipSuccess) e = compact_bound_stacks(h, s);
     if (e != hipSuccess) return hip_fail(h, e, "launch advance");
     return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);

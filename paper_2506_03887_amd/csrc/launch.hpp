@@ -27,8 +27,11 @@ hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, co
                                   int grid_blocks, hipStream_t stream);
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream);
+// cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (needs advance_fits_compact(cap)), or null
 hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
-                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos, hipStream_t stream);
+                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
+                          const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream);
+bool advance_fits_compact(int cap);                     // four staged stacks within the kernel's LDS
 hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                                 int n_compute_units, unsigned long long *workspace, int32_t *out, hipStream_t stream);
 size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);   // per-segment partial results

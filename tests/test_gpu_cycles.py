@@ -102,6 +102,38 @@ def test_long_lists_keep_bounded_stacks_and_plain_stacks_overflow():
     assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(states_h, data_h, len_h, v)).all()
 
 
+def test_capacity_beyond_the_fused_staging_uses_the_compaction_kernel():
+    """With stack_cap = 4000 four staged stacks no longer fit advance_kernel's LDS, so pre3_advance
+    compacts with the kernel of its own; the stacks must be the same."""
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    v = bpe_like_vocab(2000, 8, BASE_SEED + 83)
+    ids = {tok: t for t, tok in reversed(list(enumerate(v.tokens)))}
+    cap = 4000
+    streams = [list(b'[[1,2,[3,4,5],"ab\\ncd",{"k":[1,2,3],"l":{}}],7,8,9,10]'), list(b'{"a":"xyzw","b":[[],[],[[]]],"c":12345}'),
+               list(b'[' + b'[' * 40 + b'1' + b']' * 40 + b',2,3]')]
+    B = len(streams)
+    o = Oracle([G.JSON_RIGHT_RECURSIVE], compact_cycles=True)
+    lib = Pre3([G.JSON_RIGHT_RECURSIVE], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=cap,
+               compact_cycles=True)
+    s0 = lib.initial_state(0)
+    states_d, data_d, len_d, err_d = _bound(lib, B, cap, s0)
+    data_h = np.zeros((B, cap), dtype=np.int32)
+    data_h[:, 0] = s0
+    len_h = np.ones(B, dtype=np.int32)
+    states_h = np.full(B, s0, dtype=np.int32)
+    for s in range(max(len(st) for st in streams)):
+        tok = np.array([ids[bytes([st[s]])] if s < len(st) else -1 for st in streams], dtype=np.int32)
+        lib.advance(torch.from_numpy(tok).to(dev))
+        assert not o.advance_batch(states_h, data_h, len_h, tok, v).any(), s
+        assert (err_d.cpu().numpy() == 0).all(), s
+        assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), s
+        live = np.arange(cap)[None, :] < len_h[:, None]
+        assert (data_d.cpu().numpy()[live] == data_h[live]).all(), s
+    for b in range(B):
+        assert o.eos_allowed(data_h[b, : len_h[b]])
+
+
 def test_jump_forward_and_whole_tokens_on_lists_of_fixed_keys():
     """A grammar with forced runs inside a right-recursive list: jump-forward crosses whole list
     elements, and the stacks it leaves are compacted like those of an advance."""
