@@ -537,8 +537,8 @@ int pre3_apply_mask_topk(pre3_handle *h, const uint16_t *logits_bf16, int64_t ro
     if (!h->topk_ready) return fail(h, PRE3_E_LIMIT, "apply_mask_topk: batch x vocabulary too large for the candidate workspace (1 GiB)");
     if (!masked_topk_fits(h->V.n_tokens, k))
         return fail(h, PRE3_E_LIMIT, "apply_mask_topk: ceil(n_tokens / 16384) * k must not exceed 1024");
-    hipError_t e = launch_masked_topk(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride, k, h->topk_cand,
-                                      out_tokens, out_logits, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_masked_topk(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride, k, h->n_compute_units,
+                                      h->topk_cand, out_tokens, out_logits, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask_topk");
 }
 

@@ -38,11 +38,11 @@ size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);
 // The k largest allowed logits of every row (k <= kTopkMax), ids in out_ids[batch * k] (-1 padded),
 // their bf16 patterns in out_vals (may be null; 0xFF80 padded).
 constexpr int kTopkMax = 64;
-bool masked_topk_fits(int vocab, int k);      // (segments of 16,384 tokens) x k <= 1,024 candidates per row
+bool masked_topk_fits(int vocab, int k);      // (chunks of 16,384 tokens) x k <= 1,024 candidates per row
 size_t masked_topk_workspace_bytes(int batch, int vocab);
 hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
-                              int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
-                              hipStream_t stream);
+                              int k, int n_compute_units, unsigned long long *workspace, int32_t *out_ids,
+                              uint16_t *out_vals, hipStream_t stream);
 size_t advance_fill_walk_spill_entries(int batch, int max_depth);   // int32 entries
 // cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (the call then needs
 // advance_fill_fits_compact), or null.

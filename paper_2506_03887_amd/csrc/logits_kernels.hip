@@ -233,11 +233,34 @@ __global__ __launch_bounds__(64 * kArgFinishRows) void masked_argmax_finish_kern
 
 // ------------------------------------------------------------------- masked top-k
 
-// Order-preserving 16-bit key of a non-NaN bf16 pattern (-0 counts as +0).  Valid values map to
-// 0x007F (-inf) .. 0xFF80 (+inf); 0 is never produced.
+// Order-preserving 16-bit key of a non-NaN bf16 pattern: a negative value's pattern is negated
+// (two's complement), a non-negative one gets its top bit set (so -0 and +0 share a key), and 0x7F
+// is subtracted with saturation.  Valid values map to 0x0001 (-inf) .. 0xFF01 (+inf); negative NaN
+// patterns map to 0 (no candidate), positive NaN patterns to keys above 0xFF01.
+constexpr uint32_t kTopkKeyMax = 0xFF01u;
 __device__ __forceinline__ uint32_t bf16_key(uint32_t h) {
-    if (h == 0x8000u) h = 0u;
-    return (h & 0x8000u) ? (~h & 0xFFFFu) : (h | 0x8000u);
+    const uint32_t folded = (h & 0x8000u) ? ((0u - h) & 0xFFFFu) : (h | 0x8000u);
+    return folded > 0x7Fu ? folded - 0x7Fu : 0u;
+}
+
+// The same for two patterns in one register, with packed 16-bit arithmetic.
+typedef unsigned short PackedU16 __attribute__((ext_vector_type(2)));
+typedef short PackedI16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t packed_sub_sat_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(PackedU16, a), __builtin_bit_cast(PackedU16, b)));
+}
+__device__ __forceinline__ uint32_t bf16_key_pair(uint32_t x) {
+    const PackedU16 h = __builtin_bit_cast(PackedU16, x);
+    const uint32_t negative = __builtin_bit_cast(uint32_t, __builtin_bit_cast(PackedI16, x) >> 15);   // 0xFFFF per negative half
+    const uint32_t neg = __builtin_bit_cast(uint32_t, (PackedU16)(PackedU16{0, 0} - h));
+    const uint32_t pos = x | 0x80008000u;
+    return packed_sub_sat_u16((neg & negative) | (pos & ~negative), 0x007F007Fu);
+}
+__device__ __forceinline__ uint32_t packed_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(PackedU16, a), __builtin_bit_cast(PackedU16, b)));
+}
+__device__ __forceinline__ uint32_t packed_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(PackedU16, a), __builtin_bit_cast(PackedU16, b)));
 }
 
 // A candidate travels between the stages as the word  key << 21 | (0x1FFFFF - id)  (id < 2^21):
@@ -274,43 +297,12 @@ __device__ __forceinline__ uint32_t wave_key_threshold(KeyAt key_at, int n_nonze
     return T == 0u ? 1u : T;                                  // want == n_nonzero: every candidate
 }
 
-// Selection of the kk = min(k, candidates) best of the elements a wave holds, kPer per lane:
-// key_at(i) (0 = no candidate, else the 16-bit value key) and pref_at(i) (distinct among equal keys,
-// 1 .. 2^pref_bits - 1, larger = preferred, i.e. smaller id).  First the largest key threshold T
-// that at least kk keys reach; then, if more keys equal T than are still needed, the largest
-// preference threshold P that enough of them reach.  Selected: key > T, or key == T and pref >= P.
-// All lanes run in lockstep and obtain the same T, P, kk.
-template <int kPer, class KeyAt, class PrefAt>
-__device__ __forceinline__ void wave_select(KeyAt key_at, PrefAt pref_at, int pref_bits, int k, uint32_t *T_out,
-                                            uint32_t *P_out, int *kk_out) {
-    const int nz = wave_count<kPer>([&](int i) { return key_at(i) != 0u; });
-    const int kk = nz < k ? nz : k;
-    *kk_out = kk;
-    *T_out = 0x10000u;                                        // nothing selected
-    *P_out = 0u;
-    if (kk == 0) return;
-    int at_T;
-    const uint32_t T = wave_key_threshold<kPer>(key_at, nz, kk, &at_T);
-    *T_out = T;
-    if (at_T == kk) return;                                   // every key >= T is selected (P = 0)
-    const int above = wave_count<kPer>([&](int i) { return key_at(i) > T; });
-    const int need = kk - above;                              // of the keys equal to T, the `need` most preferred
-    uint32_t P = 0u;
-    int at_P = at_T - above;                                  // count(key == T && pref >= P)
-    for (int bit = pref_bits - 1; bit >= 0 && at_P != need; --bit) {
-        const uint32_t t = P | (1u << bit);
-        const int c = wave_count<kPer>([&](int i) { return key_at(i) == T && pref_at(i) >= t; });
-        if (c >= need) { P = t; at_P = c; }
-    }
-    *P_out = P;
-}
-
 // The kk-th largest of the S distinct non-zero words of an LDS list (1 <= kk <= S), found bit by bit
 // from the top by one wave; lane l looks at the words l, l + 64, ... (kept in registers when there
-// are at most 256 of them).  Words >= the result are the kk largest.
+// are at most 512 of them).  Words >= the result are the kk largest.
 __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned long long *list, int S, int kk, int lane) {
     if (kk >= S) return 1ull;
-    constexpr int kRegs = 4;
+    constexpr int kRegs = 8;
     unsigned long long r[kRegs];
 #pragma unroll
     for (int i = 0; i < kRegs; ++i) r[i] = i * 64 + lane < S ? list[i * 64 + lane] : 0ull;
@@ -334,179 +326,362 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
     return prefix;
 }
 
-// The k best candidates of one segment of one row (blockIdx.x = row, blockIdx.y = segment of
-// kTopkSeg tokens).  Every thread keeps the 16-bit keys of its 32 tokens in registers, two per
-// register (0 = masked, NaN or beyond the vocabulary), so the logits are read once.
-//   Fast path: from the per-thread maxima the block derives a lower bound M of the segment's k-th
-//   largest key (at least k threads hold a key >= M), so only keys >= M can be among the k best:
-//   usually a few times k of them.  They are collected in an LDS list; with at most one per thread
-//   every thread ranks its word against the list, otherwise wave 0 selects the k best bit by bit.
-//   If the list overflows -- only possible when thousands of keys tie with M -- every wave selects
-//   the k best of its own 2,048 tokens (ties by id) and wave 0 merges the waves' lists.
+// The k best candidates of one segment of one row (blockIdx.x = row, blockIdx.y = segment: a run of
+// chunks_per_seg chunks of kTopkChunk tokens, taken in order).  Of each chunk every thread keeps the
+// 16-bit keys of its 32 tokens in registers, two per register (0 = masked, NaN or beyond the
+// vocabulary), so the logits are read once; the loads of the next chunk are in flight meanwhile.
+//   From the per-thread maxima of the first chunk that holds candidates the block derives a lower
+//   bound M of the k-th largest key (at least k threads hold a key >= M), so only keys >= M can be
+//   among the k best: of every chunk a little more than k.  They are collected in one LDS list.  When
+//   the list passes kTopkRefine words between two chunks it is cut to its k best (every thread ranks
+//   one word) and M rises above the key of the k-th: later chunks hold larger ids, which lose every
+//   tie.  If a single chunk overflows the list -- thousands of keys tie with M -- the chunk's k best
+//   are found exactly, bit by bit over the whole block with the keys read again, and M rises likewise.
+//   At the end every thread ranks its one or two listed words against the list; a longer list is cut
+//   by wave 0 bit by bit.
 // The k words are written, in no particular order, to out[(row * n_seg + segment) * k ..], 0-padded.
-// The phases after the load cost about a microsecond per block whatever its size, so a block covers
-// as many tokens as its registers hold.
+// The kernel is bound by instruction issue and barrier waits, not by HBM: what a block does per chunk
+// after the load costs more than the load, so a segment is as long as still leaves two blocks per
+// compute unit.
 constexpr int kTopkBlock = 512;
 constexpr int kTopkWaves = kTopkBlock / 64;
 constexpr int kTopkPerThread = 32;
-constexpr int kTopkSeg = kTopkPerThread * kTopkBlock;
+constexpr int kTopkChunk = kTopkPerThread * kTopkBlock;
 constexpr int kTopkList = 2048;
+constexpr int kTopkRefine = 256;
+
+// Eight logits from t0 on, one 2-byte load each (rows that are not 16-byte aligned, and the group
+// that straddles the end of the vocabulary); tokens beyond the vocabulary read as NaN.  A loop that
+// is not unrolled: the path is rare and must not cost the kernel registers.
+__device__ __forceinline__ uint4 topk_load_group_unaligned(const uint16_t *__restrict__ lrow, int t0, int vocab) {
+    unsigned long long lo = 0x7FC07FC07FC07FC0ull, hi = lo;
+#pragma unroll 1
+    for (int j = 0; j < 8; ++j) {
+        if (t0 + j >= vocab) break;
+        const unsigned long long h = lrow[t0 + j];
+        const int sh = (j & 3) * 16;
+        if (j < 4) lo = (lo & ~(0xFFFFull << sh)) | (h << sh);
+        else hi = (hi & ~(0xFFFFull << sh)) | (h << sh);
+    }
+    return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
+// Block barrier for data exchanged through LDS: waits for the wave's own LDS operations only, so
+// that global loads issued ahead stay in flight across it (__syncthreads would wait for them).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Every candidate of thread `tid` in `chunk`, read again from memory one token at a time: f(word).
+template <class F>
+__device__ __forceinline__ void topk_each_word(const uint16_t *__restrict__ lrow, const uint8_t *__restrict__ mrow,
+                                               int n_mask_bytes, int vocab, int chunk, int tid, F f) {
+#pragma unroll 1
+    for (int g = 0; g < kTopkPerThread / 8; ++g) {
+        const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
+        const uint32_t m = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
+#pragma unroll 1
+        for (int j = 0; j < 8; ++j) {
+            if (!((m >> j) & 1u) || t0 + j >= vocab) continue;
+            const uint32_t h = lrow[t0 + j];
+            if ((h & 0x7FFFu) > 0x7F80u) continue;
+            f(topk_word(bf16_key(h), (uint32_t)(t0 + j)));
+        }
+    }
+}
+
+// The min(k, candidates) best words of one chunk, exactly: the threshold word is found bit by bit
+// with counts over the whole block (one counter per step in s_cnt), then the words that reach it are
+// appended to the list behind its first S0 entries (S0 + k <= kTopkList).  Called by all threads of
+// the block; returns the new list length, which *s_count holds too.
+__device__ int topk_exact_chunk(const uint16_t *__restrict__ lrow, const uint8_t *__restrict__ mrow, int n_mask_bytes,
+                                int vocab, int chunk, int k, unsigned long long *s_list, int *s_cnt, int *s_count,
+                                int S0, int tid) {
+    const int lane = tid & 63;
+    __syncthreads();                                          // every thread has read the overflowed count
+    for (int i = tid; i <= kTopkWordBits; i += kTopkBlock) s_cnt[i] = 0;
+    if (tid == 0) *s_count = S0;
+    __syncthreads();
+    auto count_ge = [&](unsigned long long t, int slot) {
+        int c = 0;
+        topk_each_word(lrow, mrow, n_mask_bytes, vocab, chunk, tid, [&](unsigned long long w) { c += w >= t ? 1 : 0; });
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
+        if (lane == 0 && c != 0) atomicAdd(&s_cnt[slot], c);
+        __syncthreads();
+        return s_cnt[slot];
+    };
+    const int n_cand = count_ge(1ull, kTopkWordBits);
+    const int kk = n_cand < k ? n_cand : k;
+    unsigned long long thr = 1ull;                            // fewer than k candidates: all of them
+    if (kk < n_cand) {
+        unsigned long long prefix = 0ull;
+        for (int bit = kTopkWordBits - 1; bit >= 0; --bit) {
+            const unsigned long long t = prefix | (1ull << bit);
+            const int c = count_ge(t, bit);
+            if (c >= kk) {
+                prefix = t;
+                if (c == kk) break;
+            }
+        }
+        thr = prefix;                                         // the words are distinct: exactly kk reach it
+    }
+    topk_each_word(lrow, mrow, n_mask_bytes, vocab, chunk, tid, [&](unsigned long long w) {
+        if (w >= thr) {
+            const int slot = atomicAdd(s_count, 1);
+            if (slot < kTopkList) s_list[slot] = w;
+        }
+    });
+    __syncthreads();
+    return S0 + kk;
+}
+
 __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
-    int n_words, int vec_ok, int k, unsigned long long *__restrict__ out) {
+    int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out) {
     __shared__ unsigned long long s_list[kTopkList];
-    __shared__ unsigned long long s_sel[kTopkWaves][kTopkMax];
     __shared__ int s_nz[kTopkWaves];
     __shared__ uint32_t s_wbound[kTopkWaves];
-    __shared__ int s_n[kTopkWaves];
+    __shared__ int s_cnt[kTopkWordBits + 1];
     __shared__ int s_count;
+    __shared__ uint32_t s_bound;
+    __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 256) {
+        uint32_t a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
+        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
+    }
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     const int n_mask_bytes = n_words * 4;
     unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
-    // element e of a thread (0 .. 31) is token  seg * kTopkSeg + rel(e); its key is half (e & 1) of kp[e >> 1]
+    const int n_chunks = (vocab + kTopkChunk - 1) / kTopkChunk;
+    const int c_begin = seg * chunks_per_seg;
+    const int c_end = c_begin + chunks_per_seg < n_chunks ? c_begin + chunks_per_seg : n_chunks;
+    // element e of a thread (0 .. 31) is token  chunk * kTopkChunk + rel(e); its key is half (e & 1) of kp[e >> 1]
     auto rel = [&](int e) { return (tid + (e >> 3) * kTopkBlock) * 8 + (e & 7); };
-    uint32_t kp[kTopkPerThread / 2];
-    auto key_at = [&](int e) { return (kp[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu; };
-    uint32_t m[kTopkPerThread / 8];
-    uint4 v[kTopkPerThread / 8];
-#pragma unroll
-    for (int g = 0; g < kTopkPerThread / 8; ++g) {
-        const int t0 = seg * kTopkSeg + (tid + g * kTopkBlock) * 8;
-        m[g] = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
-    }
-#pragma unroll
-    for (int g = 0; g < kTopkPerThread / 8; ++g) {
-        const int t0 = seg * kTopkSeg + (tid + g * kTopkBlock) * 8;
-        v[g] = make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);   // NaN: no candidate
-        if (m[g] != 0u) {
-            if (vec_ok && t0 + 8 <= vocab) {
-                v[g] = stream_load(lrow + (size_t)t0);
-            } else {
-                uint32_t h[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) h[j] = t0 + j < vocab ? (uint32_t)lrow[t0 + j] : 0x7FC0u;
-                v[g] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-            }
-        }
-    }
-#pragma unroll
-    for (int g = 0; g < kTopkPerThread / 8; ++g) {
-        const uint32_t x[4] = {v[g].x, v[g].y, v[g].z, v[g].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t lo = x[j] & 0xFFFFu, hi = x[j] >> 16;
-            const bool ok_lo = ((m[g] >> (2 * j)) & 1u) && (lo & 0x7FFFu) <= 0x7F80u;
-            const bool ok_hi = ((m[g] >> (2 * j + 1)) & 1u) && (hi & 0x7FFFu) <= 0x7F80u;
-            kp[g * 4 + j] = (ok_lo ? bf16_key(lo) : 0u) | ((ok_hi ? bf16_key(hi) : 0u) << 16);
-        }
-    }
-    uint32_t best = 0u;
-#pragma unroll
-    for (int e = 0; e < kTopkPerThread; ++e) best = key_at(e) > best ? key_at(e) : best;
-    // A lower bound of the segment's k-th largest key from the threads' maxima: wave w takes the
-    // q_w-th largest of its 64 maxima, q_w = min(j, threads of w that hold a candidate), with the
-    // smallest j for which the q_w add up to k; the smallest of these is reached by at least k keys.
-    const int nz_wave = __popcll(__ballot(best != 0u));
-    if (lane == 0) s_nz[wave] = nz_wave;
     if (tid == 0) s_count = 0;
-    if (lane == 0) s_n[wave] = 0;
-    s_sel[wave][lane] = 0ull;
-    __syncthreads();
-    int quota = 0, holders = 0;
+    uint32_t bound = 0u;                                      // 0: no candidate seen yet; 1: every candidate
+    int S = 0;                                                // length of the list (the same in every thread)
+    // The loads run ahead of the selection: while a chunk is worked on, the logits of the next one and
+    // the mask bytes of the one after it are in flight (a group's logits are only read when its mask
+    // byte is not 0, so the mask has to arrive one stage earlier).
+    auto load_mask = [&](int chunk, uint32_t (&m)[kTopkPerThread / 8]) {
 #pragma unroll
-    for (int w = 0; w < kTopkWaves; ++w) holders += s_nz[w];
-    if (holders >= k) {
-        for (quota = 1; quota < 64; ++quota) {
-            int sum = 0;
-#pragma unroll
-            for (int w = 0; w < kTopkWaves; ++w) sum += s_nz[w] < quota ? s_nz[w] : quota;
-            if (sum >= k) break;
+        for (int g = 0; g < kTopkPerThread / 8; ++g) {
+            const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
+            m[g] = (chunk < c_end && t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
         }
-    }
-    {
-        uint32_t mine = 0x10000u;                             // no candidate in this wave
-        if (nz_wave > 0) {
-            mine = 1u;                                        // fewer than k holders in the block: every candidate
-            if (quota > 0) {
-                int reached;
-                mine = wave_key_threshold<1>([&](int) { return best; }, nz_wave, nz_wave < quota ? nz_wave : quota, &reached);
+    };
+    auto load_logits = [&](int chunk, const uint32_t (&m)[kTopkPerThread / 8], uint4 (&v)[kTopkPerThread / 8]) {
+        const uint16_t *p = lrow + (size_t)chunk * kTopkChunk + (size_t)tid * 8;
+        if (vec_ok && (chunk + 1) * kTopkChunk <= vocab) {       // a whole chunk of an aligned row
+#pragma unroll
+            for (int g = 0; g < kTopkPerThread / 8; ++g) {
+                v[g] = make_uint4(0u, 0u, 0u, 0u);               // its mask zeroes the keys anyway
+                if (m[g] != 0u) v[g] = stream_load(p + g * kTopkBlock * 8);
+            }
+            return;
+        }
+#pragma unroll
+        for (int g = 0; g < kTopkPerThread / 8; ++g) {
+            const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
+            v[g] = make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);   // NaN: no candidate
+            if (m[g] != 0u) {
+                if (vec_ok && t0 + 8 <= vocab) v[g] = stream_load(lrow + (size_t)t0);
+                else v[g] = topk_load_group_unaligned(lrow, t0, vocab);
             }
         }
-        if (lane == 0) s_wbound[wave] = mine;
-    }
-    __syncthreads();
-    uint32_t bound = 0x10000u;
+    };
+    uint32_t m[kTopkPerThread / 8], m_ahead[kTopkPerThread / 8];
+    uint4 v[kTopkPerThread / 8];
+    load_mask(c_begin, m);
+    load_mask(c_begin + 1, m_ahead);
+    load_logits(c_begin, m, v);
+    lds_barrier();                                            // s_expand, s_count
+    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+        uint32_t kp[kTopkPerThread / 2];
+        // two keys per register with packed 16-bit arithmetic; the mask byte of a group expands to the
+        // four AND masks of its registers through a table in LDS
+        uint32_t best2 = 0u;
 #pragma unroll
-    for (int w = 0; w < kTopkWaves; ++w) bound = s_wbound[w] < bound ? s_wbound[w] : bound;
-    if (bound == 0x10000u) {                                  // no candidate in the segment
-        if (tid < k) dst[tid] = 0ull;
-        return;
-    }
-    if (best >= bound) {
+        for (int g = 0; g < kTopkPerThread / 8; ++g) {
+            const uint4 allow = s_expand[m[g]];
+            const uint32_t x[4] = {v[g].x, v[g].y, v[g].z, v[g].w}, a[4] = {allow.x, allow.y, allow.z, allow.w};
 #pragma unroll
-        for (int e = 0; e < kTopkPerThread; ++e)
-            if (key_at(e) >= bound) {
-                const int slot = atomicAdd(&s_count, 1);
-                if (slot < kTopkList) s_list[slot] = topk_word(key_at(e), (uint32_t)(seg * kTopkSeg + rel(e)));
+            for (int j = 0; j < 4; ++j) {
+                kp[g * 4 + j] = bf16_key_pair(x[j]) & a[j];
+                best2 = packed_max_u16(best2, kp[g * 4 + j]);
             }
-    }
-    __syncthreads();
-    const int S = s_count;
-    if (S <= kTopkBlock) {
-        // the usual case: one listed word per thread, its rank = number of larger words (every thread
-        // reads the same LDS word at a time: a broadcast), the k best write themselves in order
-        if (tid < S) {
-            const unsigned long long w = s_list[tid];
-            int rank = 0;
+        }
+        if ((best2 & 0xFFFFu) > kTopkKeyMax || (best2 >> 16) > kTopkKeyMax) {      // an allowed NaN: one half at a time
+            best2 = 0u;
+#pragma unroll
+            for (int g = 0; g < kTopkPerThread / 8; ++g) {
+                const uint32_t x[4] = {v[g].x, v[g].y, v[g].z, v[g].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t lo = x[j] & 0xFFFFu, hi = x[j] >> 16;
+                    const bool ok_lo = ((m[g] >> (2 * j)) & 1u) && (lo & 0x7FFFu) <= 0x7F80u;
+                    const bool ok_hi = ((m[g] >> (2 * j + 1)) & 1u) && (hi & 0x7FFFu) <= 0x7F80u;
+                    kp[g * 4 + j] = (ok_lo ? bf16_key(lo) : 0u) | ((ok_hi ? bf16_key(hi) : 0u) << 16);
+                    best2 = packed_max_u16(best2, kp[g * 4 + j]);
+                }
+            }
+        }
+        const uint32_t best = (best2 & 0xFFFFu) > (best2 >> 16) ? (best2 & 0xFFFFu) : (best2 >> 16);
+#pragma unroll
+        for (int g = 0; g < kTopkPerThread / 8; ++g) m[g] = m_ahead[g];
+        if (chunk + 1 < c_end) load_logits(chunk + 1, m, v);
+        load_mask(chunk + 2, m_ahead);
+        lds_barrier();                                        // s_count: set up, or read by every thread after the last chunk
+        if (bound <= 1u) {
+            // A lower bound of the k-th largest key from the threads' maxima: wave w takes the q_w-th
+            // largest of its 64 maxima, q_w = min(j, threads of w that hold a candidate), with the
+            // smallest j for which the q_w add up to k; the smallest of these is reached by at least k keys.
+            const int nz_wave = __popcll(__ballot(best != 0u));
+            if (lane == 0) s_nz[wave] = nz_wave;
+            lds_barrier();
+            int quota = 0, holders = 0;
+#pragma unroll
+            for (int w = 0; w < kTopkWaves; ++w) holders += s_nz[w];
+            if (holders >= k) {
+                for (quota = 1; quota < 64; ++quota) {
+                    int sum = 0;
+#pragma unroll
+                    for (int w = 0; w < kTopkWaves; ++w) sum += s_nz[w] < quota ? s_nz[w] : quota;
+                    if (sum >= k) break;
+                }
+            }
+            uint32_t mine = 0x10000u;                         // no candidate in this wave
+            if (nz_wave > 0) {
+                mine = 1u;                                    // fewer than k holders in the block: every candidate
+                if (quota > 0) {
+                    int reached;
+                    mine = wave_key_threshold<1>([&](int) { return best; }, nz_wave, nz_wave < quota ? nz_wave : quota, &reached);
+                }
+            }
+            if (lane == 0) s_wbound[wave] = mine;
+            lds_barrier();
+            uint32_t cb = 0x10000u;
+#pragma unroll
+            for (int w = 0; w < kTopkWaves; ++w) cb = s_wbound[w] < cb ? s_wbound[w] : cb;
+            if (cb != 0x10000u && cb > bound) bound = cb;
+        }
+        const int S0 = S;
+        if (bound != 0u && __any(best >= bound)) {
+            // The keys that reach the bound (few): every thread counts its own (a saturating packed
+            // subtraction leaves a non-zero half where a key reaches it), reserves that many list
+            // entries and writes them.
+            const uint32_t below = (bound - 1u) * 0x10001u;
+            uint32_t count2 = 0u, where2 = 0u;                // per half: how many reach it, and the sum of their register numbers
+#pragma unroll
+            for (int i = 0; i < kTopkPerThread / 2; ++i) {
+                const uint32_t one = packed_min_u16(packed_sub_sat_u16(kp[i], below), 0x00010001u);
+                count2 += one;
+                where2 += one * (uint32_t)i;
+            }
+            const int mine = (int)((count2 & 0xFFFFu) + (count2 >> 16));      // 0 .. 32
+            int slot = 0;
+            if (mine > 0) slot = atomicAdd(&s_count, mine);                     // the few threads that hold any: one LDS instruction
+            if (mine == 1) {
+                // the usual case: the key is the thread's maximum, and the sum is its register
+                const int e = (count2 & 0xFFFFu) ? 2 * (int)(where2 & 0xFFFFu) : 2 * (int)(where2 >> 16) + 1;
+                if (slot < kTopkList) s_list[slot] = topk_word(best, (uint32_t)(chunk * kTopkChunk + rel(e)));
+            }
+            if (__any(mine > 1)) {
+                if (mine > 1) {
+#pragma unroll
+                    for (int i = 0; i < kTopkPerThread / 2; ++i) {
+                        const uint32_t reach = packed_sub_sat_u16(kp[i], below);
+                        if (reach & 0xFFFFu) {
+                            if (slot < kTopkList) s_list[slot] = topk_word(kp[i] & 0xFFFFu, (uint32_t)(chunk * kTopkChunk + rel(2 * i)));
+                            ++slot;
+                        }
+                        if (reach >> 16) {
+                            if (slot < kTopkList) s_list[slot] = topk_word(kp[i] >> 16, (uint32_t)(chunk * kTopkChunk + rel(2 * i + 1)));
+                            ++slot;
+                        }
+                    }
+                }
+            }
+        }
+        lds_barrier();
+        S = s_count;
+        const bool overflowed = S > kTopkList;
+        if (overflowed) S = topk_exact_chunk(lrow, mrow, n_mask_bytes, vocab, chunk, k, s_list, s_cnt, &s_count, S0, tid);
+        if ((S > kTopkRefine || overflowed) && S > k && chunk + 1 < c_end) {
+            lds_barrier();                                    // every thread has read s_count
+            if (S <= kTopkBlock) {
+                // one listed word per thread: rank it (number of larger words), then the k best move
+                // to the front, in order
+                const unsigned long long w = tid < S ? s_list[tid] : 0ull;
+                int rank = 0;
+                if (wave * 64 < S) {
 #pragma unroll 8
-            for (int j = 0; j < S; ++j) rank += s_list[j] > w ? 1 : 0;
-            if (rank < k) dst[rank] = w;
+                    for (int j = 0; j < S; ++j) rank += s_list[j] > w ? 1 : 0;
+                }
+                lds_barrier();                                // the list has been read
+                if (tid < S && rank < k) s_list[rank] = w;
+                if (tid < S && rank == k - 1) {
+                    s_count = k;
+                    s_bound = (uint32_t)(w >> kTopkIdBits) + 1u;     // later tokens that tie with the k-th lose to it
+                }
+            } else if (wave == 0) {
+                const unsigned long long thr = wave_kth_largest(s_list, S, k, lane);
+                int base = 0;                                 // the k words >= thr move to the front (all lanes read, then write)
+                for (int r0 = 0; r0 < S; r0 += 64) {
+                    const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
+                    const bool take = w >= thr;
+                    const unsigned long long mm = __ballot(take);
+                    __builtin_amdgcn_wave_barrier();
+                    if (take) s_list[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
+                    base += __popcll(mm);
+                }
+                if (lane == 0) {
+                    s_count = k;
+                    s_bound = (uint32_t)(thr >> kTopkIdBits) + 1u;
+                }
+            }
+            lds_barrier();
+            bound = s_bound > bound ? s_bound : bound;
+            S = k;
         }
+    }
+    if (S <= 2 * kTopkBlock) {
+        // the usual case: at most two listed words per thread, a word's rank = number of larger words
+        // (the threads read the same LDS word at a time: a broadcast), the k best write themselves in
+        // order; waves without a word stay out of the way
         if (tid >= S && tid < k) dst[tid] = 0ull;
+        if (wave * 64 >= S) return;
+        const unsigned long long w0 = tid < S ? s_list[tid] : ~0ull, w1 = tid + kTopkBlock < S ? s_list[tid + kTopkBlock] : ~0ull;
+        int rank0 = 0, rank1 = 0;
+        if (S <= kTopkBlock) {
+#pragma unroll 8
+            for (int j = 0; j < S; ++j) rank0 += s_list[j] > w0 ? 1 : 0;
+        } else {
+#pragma unroll 4
+            for (int j = 0; j < S; ++j) {
+                const unsigned long long o = s_list[j];
+                rank0 += o > w0 ? 1 : 0;
+                rank1 += o > w1 ? 1 : 0;
+            }
+        }
+        if (tid < S && rank0 < k) dst[rank0] = w0;
+        if (tid + kTopkBlock < S && rank1 < k) dst[rank1] = w1;
         return;
     }
-    if (S <= kTopkList) {
-        if (wave != 0) return;
-        const int kk = S < k ? S : k;
-        const unsigned long long thr = wave_kth_largest(s_list, S, kk, lane);
-        int base = 0;
-        for (int r0 = 0; r0 < S; r0 += 64) {
-            const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
-            const bool take = w >= thr && w != 0ull;
-            const unsigned long long mm = __ballot(take);
-            if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
-            base += __popcll(mm);
-        }
-        if (lane >= kk && lane < k) dst[lane] = 0ull;
-        return;
-    }
-    // thousands of ties: exact selection per wave, then a merge by wave 0
-    auto pref_at = [&](int e) { return (uint32_t)(kTopkSeg - rel(e)); };     // 1 .. kTopkSeg, larger = smaller id
-    uint32_t T, P;
-    int kk;
-    wave_select<kTopkPerThread>(key_at, pref_at, 15, k, &T, &P, &kk);
-#pragma unroll
-    for (int e = 0; e < kTopkPerThread; ++e)
-        if (key_at(e) > T || (key_at(e) == T && pref_at(e) >= P)) {
-            const int slot = atomicAdd(&s_n[wave], 1);
-            if (slot < kTopkMax) s_sel[wave][slot] = topk_word(key_at(e), (uint32_t)(seg * kTopkSeg + rel(e)));
-        }
-    __syncthreads();
     if (wave != 0) return;
-    unsigned long long c[kTopkWaves];
-#pragma unroll
-    for (int i = 0; i < kTopkWaves; ++i) c[i] = s_sel[i][lane];      // slot `lane` of every wave (empty slots are 0)
-    auto ckey_at = [&](int i) { return (uint32_t)(c[i] >> kTopkIdBits); };
-    auto cpref_at = [&](int i) { return c[i] != 0ull ? ((uint32_t)c[i] & kTopkIdMask) + 1u : 0u; };
-    wave_select<kTopkWaves>(ckey_at, cpref_at, kTopkIdBits + 1, k, &T, &P, &kk);
-    int base = 0;                                             // compact the selected words into dst[0 .. kk)
-#pragma unroll
-    for (int i = 0; i < kTopkWaves; ++i) {
-        const bool take = c[i] != 0ull && (ckey_at(i) > T || (ckey_at(i) == T && cpref_at(i) >= P));
+    const int kk = S < k ? S : k;
+    const unsigned long long thr = wave_kth_largest(s_list, S, kk, lane);
+    int base = 0;
+    for (int r0 = 0; r0 < S; r0 += 64) {
+        const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
+        const bool take = w >= thr && w != 0ull;
         const unsigned long long mm = __ballot(take);
-        if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = c[i];
+        if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
         base += __popcll(mm);
     }
     if (lane >= kk && lane < k) dst[lane] = 0ull;
@@ -652,26 +827,37 @@ hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask,
     return hipGetLastError();
 }
 
-static int masked_topk_segments(int vocab) { return (vocab + kTopkSeg - 1) / kTopkSeg; }
+static int masked_topk_chunks(int vocab) { return (vocab + kTopkChunk - 1) / kTopkChunk; }
+
+// Chunks per block: as many as still leave two blocks per compute unit, so that small batches are
+// spread over the chip and large ones pay the per-block phases once per row.
+static int masked_topk_chunks_per_segment(int batch, int vocab, int n_compute_units) {
+    const int n_chunks = masked_topk_chunks(vocab);
+    int per = 1;
+    while (per < n_chunks && (int64_t)batch * ((n_chunks + 2 * per - 1) / (2 * per)) >= 2 * (int64_t)n_compute_units) per *= 2;
+    return per < n_chunks ? per : n_chunks;
+}
 
 bool masked_topk_fits(int vocab, int k) {
     return k >= 1 && k <= kTopkMax && vocab >= 1 && vocab <= (1 << kTopkIdBits) &&
-           masked_topk_segments(vocab) * k <= 64 * kTopkFinishPer;
+           masked_topk_chunks(vocab) * k <= 64 * kTopkFinishPer;
 }
 
 size_t masked_topk_workspace_bytes(int batch, int vocab) {
-    return (size_t)batch * masked_topk_segments(vocab) * kTopkMax * sizeof(unsigned long long);
+    return (size_t)batch * masked_topk_chunks(vocab) * kTopkMax * sizeof(unsigned long long);
 }
 
 hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
-                              int k, unsigned long long *workspace, int32_t *out_ids, uint16_t *out_vals,
-                              hipStream_t stream) {
+                              int k, int n_compute_units, unsigned long long *workspace, int32_t *out_ids,
+                              uint16_t *out_vals, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
     if (!masked_topk_fits(vocab, k)) return hipErrorInvalidValue;
-    const int n_words = (vocab + 31) / 32, n_seg = masked_topk_segments(vocab);
+    const int n_words = (vocab + 31) / 32;
+    const int per = masked_topk_chunks_per_segment(batch, vocab, n_compute_units);
+    const int n_seg = (masked_topk_chunks(vocab) + per - 1) / per;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
     hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
-                       n_words, vec_ok, k, workspace);
+                       n_words, vec_ok, k, per, workspace);
     hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(64), 0, stream, workspace, n_seg * k, k, logits, row_stride,
                        out_ids, out_vals);
     return hipGetLastError();

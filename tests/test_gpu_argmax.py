@@ -138,6 +138,68 @@ def test_masked_topk_values_and_layouts(V, B, stride_pad, offset, ks):
     assert torch.equal(flat, before), "the logits are read-only for this call"
 
 
+def _bf16(x):
+    return (np.asarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("V,B,stride_pad,ks", [(70001, 300, 7, (50, 64)), (70001, 300, 0, (7,)), (128256, 520, 0, (50,))])
+def test_masked_topk_over_segments_of_several_chunks(V, B, stride_pad, ks):
+    """Batches large enough that a block takes several chunks of 16,384 tokens in a row: rows of equal
+    logits (every chunk overflows the candidate list, ties decided by id), logits rising or falling with
+    the id (the list is cut to its k best between chunks), masks that leave the first chunks empty or
+    nearly empty, a single chunk with thousands of ties under a few larger values, NaN rows."""
+    torch, dev = _torch()
+    rng = np.random.default_rng(BASE_SEED + 5 * V + B)
+    toks = [bytes([97 + i % 5]) for i in range(V - 1)] + [b""]
+    lib = _bound_lib(Vocab(toks, V - 1), B)
+    logits = _special_logits(rng, B, V)
+    mask = _special_masks(rng, B, V)
+    W = mask.shape[1]
+    full = np.full(W, 0xFFFFFFFF, dtype=np.uint32)
+    if V % 32:
+        full[W - 1] = np.uint32((1 << (V % 32)) - 1)
+    base = 8
+    logits[base + 0] = 0x3F80; mask[base + 0] = full                        # all 1.0, all allowed
+    logits[base + 1] = 0xC000                                               # all -2.0, sparse mask
+    logits[base + 2] = _bf16(np.linspace(-3, 3, V)); mask[base + 2] = full  # rising with the id
+    logits[base + 3] = _bf16(np.linspace(3, -3, V)); mask[base + 3] = full  # falling
+    mask[base + 4] = 0; mask[base + 4, (3 * 16384) // 32 + 7:] = full[(3 * 16384) // 32 + 7:]   # the first chunks are empty
+    mask[base + 5] = 0; mask[base + 5, 3] = 0x0FFFFFFF; mask[base + 5, 1024: 1536] = 0xFFFFFFFF  # 28 tokens, then a whole chunk
+    logits[base + 6] = 0x7FC0; logits[base + 6, ::4099] = _bf16(rng.normal(size=len(range(0, V, 4099)))); mask[base + 6] = full
+    logits[base + 7] = _bf16(rng.normal(size=V) - 8); logits[base + 7, 16384 + 100: 16384 + 3300] = 0x4000   # 3,200 ties at 2.0 in one chunk
+    logits[base + 7, [5, 20000, 40000, 69000]] = 0x4040; mask[base + 7] = full
+    logits[base + 8] = 0x8000; logits[base + 8, ::2] = 0x0000; mask[base + 8] = full               # zeros of both signs
+    # 1,280 allowed tokens held by 40 threads of one chunk (fewer holders than k: every one is listed),
+    # once followed by a full chunk, once as the last of its segment
+    few = np.zeros(V, dtype=bool)
+    for g in range(4):
+        for t in range(40):
+            few[(t + g * 512) * 8: (t + g * 512) * 8 + 8] = True
+    for row, chunk, more in ((base + 9, 1, True), (base + 10, 3, False)):
+        allowed = np.zeros(V, dtype=bool)
+        allowed[chunk * 16384: chunk * 16384 + 16384] = few[: min(16384, V - chunk * 16384)]
+        if more:
+            allowed[3 * 16384: 4 * 16384] = True
+        bits = np.zeros(W * 32, dtype=np.uint8)
+        bits[:V] = allowed
+        mask[row] = np.packbits(bits.reshape(W, 32), axis=1, bitorder="little").view(np.uint32)[:, 0]
+    stride = V + stride_pad
+    flat = torch.full((B * stride + 8,), 0x1234, dtype=torch.int16, device=dev)
+    view = flat[: B * stride].view(B, stride)[:, :V]
+    view.copy_(torch.from_numpy(logits.view(np.int16)).to(dev))
+    m_d = torch.from_numpy(mask.view(np.int32)).to(dev)
+    for k in ks:
+        want_ids, want_vals = oracle_masked_topk(logits, mask, V, k)
+        ids = torch.full((B, k), -7, dtype=torch.int32, device=dev)
+        vals = torch.full((B, k), 0x1111, dtype=torch.int16, device=dev)
+        lib.apply_mask_topk(view.view(torch.bfloat16), m_d, ids, vals)
+        got_ids, got_vals = ids.cpu().numpy(), vals.cpu().numpy().view(np.uint16)
+        bad = np.argwhere(got_ids != want_ids)
+        assert len(bad) == 0, (k, bad[:4].tolist(), got_ids[bad[0][0]][:8].tolist(), want_ids[bad[0][0]][:8].tolist())
+        assert (got_vals == want_vals).all(), k
+        assert want_ids[base + 0, :3].tolist() == [0, 1, 2] and want_ids[base + 4, 0] >= 3 * 16384 + 7 * 32
+
+
 def test_masked_topk_argument_errors():
     from paper_2506_03887_amd.binding import Pre3Error
     torch, dev = _torch()
