@@ -332,23 +332,19 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
 // vocabulary), so the logits are read once; the loads of the next chunk are in flight meanwhile.
 //   From the per-thread maxima of the first chunk that holds candidates the block derives a lower
 //   bound M of the k-th largest key (at least k threads hold a key >= M), so only keys >= M can be
-//   among the k best: of every chunk a little more than k.  They are collected in one LDS list.  When
-//   the list passes kTopkRefine words between two chunks it is cut to its k best (every thread ranks
-//   one word) and M rises above the key of the k-th: later chunks hold larger ids, which lose every
-//   tie.  If a single chunk overflows the list -- thousands of keys tie with M -- the chunk's k best
-//   are found exactly, bit by bit over the whole block with the keys read again, and M rises likewise.
-//   At the end every thread ranks its one or two listed words against the list; a longer list is cut
-//   by wave 0 bit by bit.
-// The k words are written, in no particular order, to out[(row * n_seg + segment) * k ..], 0-padded.
-// The kernel is bound by instruction issue and barrier waits, not by HBM: what a block does per chunk
-// after the load costs more than the load, so a segment is as long as still leaves two blocks per
-// compute unit.
+//   among the k best: of every chunk a little more than k.  From then on the waves do not meet again
+//   until the end: each appends its keys >= M to a list of its own (kTopkRegion words of LDS).  A wave
+//   whose list runs full cuts it to its k best and from then on uses the key of its k-th as its bound
+//   (a wave's k-th best is a lower bound of the block's); after a chunk in which that happened the
+//   bound rises by one more, because later chunks hold larger ids, which lose every tie.
+//   At the end every thread ranks the words of its wave's list that fall to it (rank = number of
+//   larger words in all lists) and the k best write themselves in order.
+// The k words are written to out[(row * n_seg + segment) * k ..], best first, 0-padded.
 constexpr int kTopkBlock = 512;
 constexpr int kTopkWaves = kTopkBlock / 64;
 constexpr int kTopkPerThread = 32;
 constexpr int kTopkChunk = kTopkPerThread * kTopkBlock;
-constexpr int kTopkList = 2048;
-constexpr int kTopkRefine = 256;
+constexpr int kTopkRegion = 256;
 
 // Eight logits from t0 on, one 2-byte load each (rows that are not 16-byte aligned, and the group
 // that straddles the end of the vocabulary); tokens beyond the vocabulary read as NaN.  A loop that
@@ -372,80 +368,32 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Every candidate of thread `tid` in `chunk`, read again from memory one token at a time: f(word).
-template <class F>
-__device__ __forceinline__ void topk_each_word(const uint16_t *__restrict__ lrow, const uint8_t *__restrict__ mrow,
-                                               int n_mask_bytes, int vocab, int chunk, int tid, F f) {
-#pragma unroll 1
-    for (int g = 0; g < kTopkPerThread / 8; ++g) {
-        const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
-        const uint32_t m = (t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
-#pragma unroll 1
-        for (int j = 0; j < 8; ++j) {
-            if (!((m >> j) & 1u) || t0 + j >= vocab) continue;
-            const uint32_t h = lrow[t0 + j];
-            if ((h & 0x7FFFu) > 0x7F80u) continue;
-            f(topk_word(bf16_key(h), (uint32_t)(t0 + j)));
-        }
+// Cuts a wave's list (n > k words) to its k best, moved to the front; returns the key of the k-th.
+__device__ __noinline__ uint32_t topk_cut_list(unsigned long long *list, int n, int k, int lane) {
+    const unsigned long long thr = wave_kth_largest(list, n, k, lane);
+    int base = 0;
+    for (int r0 = 0; r0 < n; r0 += 64) {                      // all lanes read, then write: the ranges may overlap
+        const unsigned long long w = r0 + lane < n ? list[r0 + lane] : 0ull;
+        const bool take = w >= thr;
+        const unsigned long long mm = __ballot(take);
+        __builtin_amdgcn_wave_barrier();
+        if (take) list[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
+        base += __popcll(mm);
     }
+    __builtin_amdgcn_wave_barrier();
+    return (uint32_t)(thr >> kTopkIdBits);
 }
 
-// The min(k, candidates) best words of one chunk, exactly: the threshold word is found bit by bit
-// with counts over the whole block (one counter per step in s_cnt), then the words that reach it are
-// appended to the list behind its first S0 entries (S0 + k <= kTopkList).  Called by all threads of
-// the block; returns the new list length, which *s_count holds too.
-__device__ int topk_exact_chunk(const uint16_t *__restrict__ lrow, const uint8_t *__restrict__ mrow, int n_mask_bytes,
-                                int vocab, int chunk, int k, unsigned long long *s_list, int *s_cnt, int *s_count,
-                                int S0, int tid) {
-    const int lane = tid & 63;
-    __syncthreads();                                          // every thread has read the overflowed count
-    for (int i = tid; i <= kTopkWordBits; i += kTopkBlock) s_cnt[i] = 0;
-    if (tid == 0) *s_count = S0;
-    __syncthreads();
-    auto count_ge = [&](unsigned long long t, int slot) {
-        int c = 0;
-        topk_each_word(lrow, mrow, n_mask_bytes, vocab, chunk, tid, [&](unsigned long long w) { c += w >= t ? 1 : 0; });
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
-        if (lane == 0 && c != 0) atomicAdd(&s_cnt[slot], c);
-        __syncthreads();
-        return s_cnt[slot];
-    };
-    const int n_cand = count_ge(1ull, kTopkWordBits);
-    const int kk = n_cand < k ? n_cand : k;
-    unsigned long long thr = 1ull;                            // fewer than k candidates: all of them
-    if (kk < n_cand) {
-        unsigned long long prefix = 0ull;
-        for (int bit = kTopkWordBits - 1; bit >= 0; --bit) {
-            const unsigned long long t = prefix | (1ull << bit);
-            const int c = count_ge(t, bit);
-            if (c >= kk) {
-                prefix = t;
-                if (c == kk) break;
-            }
-        }
-        thr = prefix;                                         // the words are distinct: exactly kk reach it
-    }
-    topk_each_word(lrow, mrow, n_mask_bytes, vocab, chunk, tid, [&](unsigned long long w) {
-        if (w >= thr) {
-            const int slot = atomicAdd(s_count, 1);
-            if (slot < kTopkList) s_list[slot] = w;
-        }
-    });
-    __syncthreads();
-    return S0 + kk;
-}
-
-__global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
+__global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out) {
-    __shared__ unsigned long long s_list[kTopkList];
+    __shared__ unsigned long long s_list[kTopkWaves * kTopkRegion];
     __shared__ int s_nz[kTopkWaves];
     __shared__ uint32_t s_wbound[kTopkWaves];
-    __shared__ int s_cnt[kTopkWordBits + 1];
-    __shared__ int s_count;
-    __shared__ uint32_t s_bound;
+    __shared__ int s_n[kTopkWaves];
     __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
+    __shared__ unsigned long long s_short[kTopkBlock];        // the few words left at the end, one per thread
+    __shared__ int s_total;
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 256) {
         uint32_t a[4];
@@ -462,9 +410,11 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     const int c_end = c_begin + chunks_per_seg < n_chunks ? c_begin + chunks_per_seg : n_chunks;
     // element e of a thread (0 .. 31) is token  chunk * kTopkChunk + rel(e); its key is half (e & 1) of kp[e >> 1]
     auto rel = [&](int e) { return (tid + (e >> 3) * kTopkBlock) * 8 + (e & 7); };
-    if (tid == 0) s_count = 0;
-    uint32_t bound = 0u;                                      // 0: no candidate seen yet; 1: every candidate
-    int S = 0;                                                // length of the list (the same in every thread)
+    unsigned long long *mylist = s_list + wave * kTopkRegion;
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+    int n_mine = 0;                                           // length of the wave's list
+    uint32_t block_bound = 0u;                                // 0: no candidate seen yet; 1: every candidate (same in all waves)
+    uint32_t wave_bound = 0u;                                 // what the wave's own list has proved since
     // The loads run ahead of the selection: while a chunk is worked on, the logits of the next one and
     // the mask bytes of the one after it are in flight (a group's logits are only read when its mask
     // byte is not 0, so the mask has to arrive one stage earlier).
@@ -500,7 +450,7 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
     load_mask(c_begin, m);
     load_mask(c_begin + 1, m_ahead);
     load_logits(c_begin, m, v);
-    lds_barrier();                                            // s_expand, s_count
+    lds_barrier();                                            // s_expand
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         uint32_t kp[kTopkPerThread / 2];
         // two keys per register with packed 16-bit arithmetic; the mask byte of a group expands to the
@@ -536,8 +486,7 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
         for (int g = 0; g < kTopkPerThread / 8; ++g) m[g] = m_ahead[g];
         if (chunk + 1 < c_end) load_logits(chunk + 1, m, v);
         load_mask(chunk + 2, m_ahead);
-        lds_barrier();                                        // s_count: set up, or read by every thread after the last chunk
-        if (bound <= 1u) {
+        if (block_bound <= 1u) {
             // A lower bound of the k-th largest key from the threads' maxima: wave w takes the q_w-th
             // largest of its 64 maxima, q_w = min(j, threads of w that hold a candidate), with the
             // smallest j for which the q_w add up to k; the smallest of these is reached by at least k keys.
@@ -568,123 +517,196 @@ __global__ __launch_bounds__(kTopkBlock) void masked_topk_kernel(
             uint32_t cb = 0x10000u;
 #pragma unroll
             for (int w = 0; w < kTopkWaves; ++w) cb = s_wbound[w] < cb ? s_wbound[w] : cb;
-            if (cb != 0x10000u && cb > bound) bound = cb;
+            if (cb != 0x10000u && cb > block_bound) block_bound = cb;
         }
-        const int S0 = S;
-        if (bound != 0u && __any(best >= bound)) {
-            // The keys that reach the bound (few): every thread counts its own (a saturating packed
-            // subtraction leaves a non-zero half where a key reaches it), reserves that many list
-            // entries and writes them.
-            const uint32_t below = (bound - 1u) * 0x10001u;
-            uint32_t count2 = 0u, where2 = 0u;                // per half: how many reach it, and the sum of their register numbers
+        uint32_t bound = block_bound > wave_bound ? block_bound : wave_bound;
+        if (bound == 0u || !__any(best >= bound)) continue;
+        // The keys that reach the bound (few): every thread counts its own -- a saturating packed
+        // subtraction leaves a non-zero half where a key reaches it -- and notes in which register.
+        const uint32_t below = (bound - 1u) * 0x10001u;
+        uint32_t count2 = 0u, where2 = 0u;                    // per half: how many reach it, and the sum of their register numbers
 #pragma unroll
-            for (int i = 0; i < kTopkPerThread / 2; ++i) {
-                const uint32_t one = packed_min_u16(packed_sub_sat_u16(kp[i], below), 0x00010001u);
-                count2 += one;
-                where2 += one * (uint32_t)i;
+        for (int i = 0; i < kTopkPerThread / 2; ++i) {
+            const uint32_t one = packed_min_u16(packed_sub_sat_u16(kp[i], below), 0x00010001u);
+            count2 += one;
+            where2 += one * (uint32_t)i;
+        }
+        const int mine = (int)((count2 & 0xFFFFu) + (count2 >> 16));      // 0 .. 32
+        const unsigned long long holders = __ballot(mine > 0);
+        int before = __popcll(holders & lanes_below), total = __popcll(holders);   // right when no thread holds several
+        if (__ballot(mine > 1) != 0ull) {
+            before = 0;
+            total = 0;
+#pragma unroll
+            for (int bit = 0; bit < 6; ++bit) {
+                const unsigned long long has = __ballot((mine >> bit) & 1);
+                before += __popcll(has & lanes_below) << bit;
+                total += __popcll(has) << bit;
             }
-            const int mine = (int)((count2 & 0xFFFFu) + (count2 >> 16));      // 0 .. 32
-            int slot = 0;
-            if (mine > 0) slot = atomicAdd(&s_count, mine);                     // the few threads that hold any: one LDS instruction
+        }
+        if (n_mine + total <= kTopkRegion) {
+            int slot = n_mine + before;
             if (mine == 1) {
                 // the usual case: the key is the thread's maximum, and the sum is its register
                 const int e = (count2 & 0xFFFFu) ? 2 * (int)(where2 & 0xFFFFu) : 2 * (int)(where2 >> 16) + 1;
-                if (slot < kTopkList) s_list[slot] = topk_word(best, (uint32_t)(chunk * kTopkChunk + rel(e)));
-            }
-            if (__any(mine > 1)) {
-                if (mine > 1) {
+                mylist[slot] = topk_word(best, (uint32_t)(chunk * kTopkChunk + rel(e)));
+            } else if (mine > 1) {
 #pragma unroll
-                    for (int i = 0; i < kTopkPerThread / 2; ++i) {
-                        const uint32_t reach = packed_sub_sat_u16(kp[i], below);
-                        if (reach & 0xFFFFu) {
-                            if (slot < kTopkList) s_list[slot] = topk_word(kp[i] & 0xFFFFu, (uint32_t)(chunk * kTopkChunk + rel(2 * i)));
-                            ++slot;
-                        }
-                        if (reach >> 16) {
-                            if (slot < kTopkList) s_list[slot] = topk_word(kp[i] >> 16, (uint32_t)(chunk * kTopkChunk + rel(2 * i + 1)));
-                            ++slot;
-                        }
-                    }
+                for (int i = 0; i < kTopkPerThread / 2; ++i) {
+                    const uint32_t reach = packed_sub_sat_u16(kp[i], below);
+                    if (reach & 0xFFFFu) mylist[slot++] = topk_word(kp[i] & 0xFFFFu, (uint32_t)(chunk * kTopkChunk + rel(2 * i)));
+                    if (reach >> 16) mylist[slot++] = topk_word(kp[i] >> 16, (uint32_t)(chunk * kTopkChunk + rel(2 * i + 1)));
                 }
+            }
+            n_mine += total;
+            continue;
+        }
+        // the list may run full: element by element, with room made when it is needed
+        bool cut = false;
+        uint32_t last_kth = 0u;                               // key of the k-th word after the latest cut
+#pragma unroll
+        for (int e = 0; e < kTopkPerThread; ++e) {
+            const uint32_t key = (kp[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+            bool take = key >= bound;
+            unsigned long long mm = __ballot(take);
+            if (mm == 0ull) continue;
+            if (n_mine + __popcll(mm) > kTopkRegion) {        // n_mine > k here: the cut leaves k words
+                last_kth = topk_cut_list(mylist, n_mine, k, lane);
+                n_mine = k;
+                wave_bound = last_kth > wave_bound ? last_kth : wave_bound;
+                bound = block_bound > wave_bound ? block_bound : wave_bound;
+                cut = true;
+                take = key >= bound;
+                mm = __ballot(take);
+            }
+            if (take) mylist[n_mine + __popcll(mm & lanes_below)] = topk_word(key, (uint32_t)(chunk * kTopkChunk + rel(e)));
+            n_mine += __popcll(mm);
+        }
+        if (cut) {                                            // from the next chunk on ties with the k-th can be left out
+            if (n_mine > k) {
+                last_kth = topk_cut_list(mylist, n_mine, k, lane);
+                n_mine = k;
+            }
+            wave_bound = last_kth + 1u > wave_bound ? last_kth + 1u : wave_bound;
+        }
+    }
+    // The lists are complete.  If they hold many words, the same bound as above -- now from the
+    // maxima of the listed words each thread holds -- leaves little more than k of them, and every
+    // wave drops the rest of its list.  Then every thread ranks the words of its wave's list that fall
+    // to it against all lists (rank = number of larger words) and the k best write themselves in order.
+    if (lane == 0) s_n[wave] = n_mine;
+    lds_barrier();
+    int S = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkWaves; ++w) S += s_n[w];
+    if (tid >= S && tid < k) dst[tid] = 0ull;
+    unsigned long long w[kTopkRegion / 64];
+#pragma unroll
+    for (int r = 0; r < kTopkRegion / 64; ++r) w[r] = r * 64 + lane < n_mine ? mylist[r * 64 + lane] : 0ull;
+    uint32_t cb = 1u;                                         // every listed word
+    if (S > 2 * k + 32) {                                     // the same in every thread
+        unsigned long long top = 0ull;
+#pragma unroll
+        for (int r = 0; r < kTopkRegion / 64; ++r) top = w[r] > top ? w[r] : top;
+        const uint32_t best = (uint32_t)(top >> kTopkIdBits);
+        const int nz_wave = __popcll(__ballot(best != 0u));
+        if (lane == 0) s_nz[wave] = nz_wave;
+        lds_barrier();
+        int quota = 0, holders = 0;
+#pragma unroll
+        for (int ww = 0; ww < kTopkWaves; ++ww) holders += s_nz[ww];
+        if (holders >= k) {
+            for (quota = 1; quota < 64; ++quota) {
+                int sum = 0;
+#pragma unroll
+                for (int ww = 0; ww < kTopkWaves; ++ww) sum += s_nz[ww] < quota ? s_nz[ww] : quota;
+                if (sum >= k) break;
             }
         }
+        uint32_t mine = 0x10000u;
+        if (nz_wave > 0) {
+            mine = 1u;
+            if (quota > 0) {
+                int reached;
+                mine = wave_key_threshold<1>([&](int) { return best; }, nz_wave, nz_wave < quota ? nz_wave : quota, &reached);
+            }
+        }
+        if (lane == 0) s_wbound[wave] = mine;
         lds_barrier();
-        S = s_count;
-        const bool overflowed = S > kTopkList;
-        if (overflowed) S = topk_exact_chunk(lrow, mrow, n_mask_bytes, vocab, chunk, k, s_list, s_cnt, &s_count, S0, tid);
-        if ((S > kTopkRefine || overflowed) && S > k && chunk + 1 < c_end) {
-            lds_barrier();                                    // every thread has read s_count
-            if (S <= kTopkBlock) {
-                // one listed word per thread: rank it (number of larger words), then the k best move
-                // to the front, in order
-                const unsigned long long w = tid < S ? s_list[tid] : 0ull;
-                int rank = 0;
-                if (wave * 64 < S) {
-#pragma unroll 8
-                    for (int j = 0; j < S; ++j) rank += s_list[j] > w ? 1 : 0;
-                }
-                lds_barrier();                                // the list has been read
-                if (tid < S && rank < k) s_list[rank] = w;
-                if (tid < S && rank == k - 1) {
-                    s_count = k;
-                    s_bound = (uint32_t)(w >> kTopkIdBits) + 1u;     // later tokens that tie with the k-th lose to it
-                }
-            } else if (wave == 0) {
-                const unsigned long long thr = wave_kth_largest(s_list, S, k, lane);
-                int base = 0;                                 // the k words >= thr move to the front (all lanes read, then write)
-                for (int r0 = 0; r0 < S; r0 += 64) {
-                    const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
-                    const bool take = w >= thr;
-                    const unsigned long long mm = __ballot(take);
-                    __builtin_amdgcn_wave_barrier();
-                    if (take) s_list[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
-                    base += __popcll(mm);
-                }
-                if (lane == 0) {
-                    s_count = k;
-                    s_bound = (uint32_t)(thr >> kTopkIdBits) + 1u;
-                }
+        cb = 0x10000u;
+#pragma unroll
+        for (int ww = 0; ww < kTopkWaves; ++ww) cb = s_wbound[ww] < cb ? s_wbound[ww] : cb;
+    }
+    {
+        // the words that reach it: counted, and if there are few, gathered in one short list, one word per thread
+        bool keep[kTopkRegion / 64];
+        int kept = 0;
+#pragma unroll
+        for (int r = 0; r < kTopkRegion / 64; ++r) {
+            keep[r] = w[r] != 0ull && (uint32_t)(w[r] >> kTopkIdBits) >= cb;
+            kept += __popcll(__ballot(keep[r]));
+        }
+        if (tid == 0) s_total = 0;
+        if (lane == 0) s_nz[wave] = kept;                     // (every wave has read the old values before the last barrier)
+        lds_barrier();
+        int S2 = 0;
+#pragma unroll
+        for (int ww = 0; ww < kTopkWaves; ++ww) S2 += s_nz[ww];
+        if (S2 <= kTopkBlock) {
+            int at = 0;
+            if (lane == 0 && kept > 0) at = atomicAdd(&s_total, kept);
+            at = __builtin_amdgcn_readfirstlane(at);
+#pragma unroll
+            for (int r = 0; r < kTopkRegion / 64; ++r) {
+                const unsigned long long mm = __ballot(keep[r]);
+                if (keep[r]) s_short[at + __popcll(mm & lanes_below)] = w[r];
+                at += __popcll(mm);
             }
             lds_barrier();
-            bound = s_bound > bound ? s_bound : bound;
-            S = k;
-        }
-    }
-    if (S <= 2 * kTopkBlock) {
-        // the usual case: at most two listed words per thread, a word's rank = number of larger words
-        // (the threads read the same LDS word at a time: a broadcast), the k best write themselves in
-        // order; waves without a word stay out of the way
-        if (tid >= S && tid < k) dst[tid] = 0ull;
-        if (wave * 64 >= S) return;
-        const unsigned long long w0 = tid < S ? s_list[tid] : ~0ull, w1 = tid + kTopkBlock < S ? s_list[tid + kTopkBlock] : ~0ull;
-        int rank0 = 0, rank1 = 0;
-        if (S <= kTopkBlock) {
+            if (wave * 64 >= S2) return;
+            const unsigned long long mine = tid < S2 ? s_short[tid] : ~0ull;
+            int rank = 0;
 #pragma unroll 8
-            for (int j = 0; j < S; ++j) rank0 += s_list[j] > w0 ? 1 : 0;
+            for (int j = 0; j < S2; ++j) rank += s_short[j] > mine ? 1 : 0;
+            if (tid < S2 && rank < k) dst[rank] = mine;
+            return;
+        }
+        // many ties with the bound: the words stay where they are, every wave drops the others from its list
+        kept = 0;
+#pragma unroll
+        for (int r = 0; r < kTopkRegion / 64; ++r) {
+            const unsigned long long mm = __ballot(keep[r]);
+            if (keep[r]) mylist[kept + __popcll(mm & lanes_below)] = w[r];   // every word of the list is in a register by now
+            kept += __popcll(mm);
+        }
+        n_mine = kept;
+        if (lane == 0) s_n[wave] = n_mine;
+        lds_barrier();
+#pragma unroll
+        for (int r = 0; r < kTopkRegion / 64; ++r) w[r] = r * 64 + lane < n_mine ? mylist[r * 64 + lane] : 0ull;
+    }
+    if (n_mine == 0) return;
+    int rank[kTopkRegion / 64];
+#pragma unroll
+    for (int r = 0; r < kTopkRegion / 64; ++r) rank[r] = 0;
+    for (int ww = 0; ww < kTopkWaves; ++ww) {
+        const unsigned long long *other = s_list + ww * kTopkRegion;
+        const int n_other = s_n[ww];
+        if (n_mine <= 64) {
+#pragma unroll 8
+            for (int j = 0; j < n_other; ++j) rank[0] += other[j] > w[0] ? 1 : 0;
         } else {
-#pragma unroll 4
-            for (int j = 0; j < S; ++j) {
-                const unsigned long long o = s_list[j];
-                rank0 += o > w0 ? 1 : 0;
-                rank1 += o > w1 ? 1 : 0;
+#pragma unroll 2
+            for (int j = 0; j < n_other; ++j) {
+                const unsigned long long o = other[j];
+#pragma unroll
+                for (int r = 0; r < kTopkRegion / 64; ++r) rank[r] += o > w[r] ? 1 : 0;
             }
         }
-        if (tid < S && rank0 < k) dst[rank0] = w0;
-        if (tid + kTopkBlock < S && rank1 < k) dst[rank1] = w1;
-        return;
     }
-    if (wave != 0) return;
-    const int kk = S < k ? S : k;
-    const unsigned long long thr = wave_kth_largest(s_list, S, kk, lane);
-    int base = 0;
-    for (int r0 = 0; r0 < S; r0 += 64) {
-        const unsigned long long w = r0 + lane < S ? s_list[r0 + lane] : 0ull;
-        const bool take = w >= thr && w != 0ull;
-        const unsigned long long mm = __ballot(take);
-        if (take) dst[base + __popcll(mm & ((1ull << lane) - 1ull))] = w;
-        base += __popcll(mm);
-    }
-    if (lane >= kk && lane < k) dst[lane] = 0ull;
+#pragma unroll
+    for (int r = 0; r < kTopkRegion / 64; ++r)
+        if (r * 64 + lane < n_mine && rank[r] < k) dst[rank[r]] = w[r];
 }
 
 // Merges the segments' candidates of one row with one wave: n_cand words (0 = empty), at most

@@ -183,6 +183,15 @@ def test_masked_topk_over_segments_of_several_chunks(V, B, stride_pad, ks):
         bits = np.zeros(W * 32, dtype=np.uint8)
         bits[:V] = allowed
         mask[row] = np.packbits(bits.reshape(W, 32), axis=1, bitorder="little").view(np.uint32)[:, 0]
+    # a thousand equal logits spread over all chunks and nothing else allowed; the same under a few larger ones
+    for row, extra in ((base + 11, False), (base + 12, True)):
+        bits = np.zeros(W * 32, dtype=np.uint8)
+        bits[np.arange(0, V, 70)] = 1
+        logits[row] = 0x3FC0
+        if extra:
+            bits[[3, 33333, V - 2]] = 1
+            logits[row, [3, 33333, V - 2]] = 0x4100
+        mask[row] = np.packbits(bits.reshape(W, 32), axis=1, bitorder="little").view(np.uint32)[:, 0]
     stride = V + stride_pad
     flat = torch.full((B * stride + 8,), 0x1234, dtype=torch.int16, device=dev)
     view = flat[: B * stride].view(B, stride)[:, :V]
