@@ -465,7 +465,7 @@ def main():
                 "checked_steps_against_oracle": n_check,
                 "topk": {"k": topk_k, "launch_us": topk_us, "achieved_GBs": nbytes / (topk_us * 1e-6) / 1e9,
                          "frac_of_hbm_peak": nbytes / (topk_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                         "note": "pre3_apply_mask_topk (both kernels), K calls in one HIP graph; same algorithmic bytes as the arg max"}}
+                         "note": "pre3_apply_mask_topk, K calls in one HIP graph; same algorithmic bytes as the arg max"}}
 
     pairs_ = float(B) * V
     greedy = greedy_leg()

@@ -339,7 +339,8 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
 //   bound rises by one more, because later chunks hold larger ids, which lose every tie.
 //   At the end every thread ranks the words of its wave's list that fall to it (rank = number of
 //   larger words in all lists) and the k best write themselves in order.
-// The k words are written to out[(row * n_seg + segment) * k ..], best first, 0-padded.
+// The k words are written to out[(row * n_seg + segment) * k ..], best first, 0-padded; with one
+// segment per row the kernel writes the row's ids and bf16 patterns itself (out_ids, out_vals).
 constexpr int kTopkBlock = 512;
 constexpr int kTopkWaves = kTopkBlock / 64;
 constexpr int kTopkPerThread = 32;
@@ -386,7 +387,8 @@ __device__ __noinline__ uint32_t topk_cut_list(unsigned long long *list, int n, 
 
 __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
-    int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out) {
+    int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out,
+    int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
     __shared__ unsigned long long s_list[kTopkWaves * kTopkRegion];
     __shared__ int s_nz[kTopkWaves];
     __shared__ uint32_t s_wbound[kTopkWaves];
@@ -405,6 +407,19 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     const int n_mask_bytes = n_words * 4;
     unsigned long long *dst = out + ((size_t)b * n_seg + seg) * (size_t)k;
+    // with one segment per row (out_ids given) the ranked words are the row's result and go out as ids and patterns
+    auto emit = [&](int rank, unsigned long long word) {
+        if (out_ids == nullptr) {
+            dst[rank] = word;
+        } else if (word != 0ull) {
+            const uint32_t id = kTopkIdMask - ((uint32_t)word & kTopkIdMask);
+            out_ids[(size_t)b * k + rank] = (int32_t)id;
+            if (out_vals) out_vals[(size_t)b * k + rank] = lrow[id];
+        } else {
+            out_ids[(size_t)b * k + rank] = -1;
+            if (out_vals) out_vals[(size_t)b * k + rank] = 0xFF80u;
+        }
+    };
     const int n_chunks = (vocab + kTopkChunk - 1) / kTopkChunk;
     const int c_begin = seg * chunks_per_seg;
     const int c_end = c_begin + chunks_per_seg < n_chunks ? c_begin + chunks_per_seg : n_chunks;
@@ -599,7 +614,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     int S = 0;
 #pragma unroll
     for (int w = 0; w < kTopkWaves; ++w) S += s_n[w];
-    if (tid >= S && tid < k) dst[tid] = 0ull;
+    if (tid >= S && tid < k) emit(tid, 0ull);
     unsigned long long w[kTopkRegion / 64];
 #pragma unroll
     for (int r = 0; r < kTopkRegion / 64; ++r) w[r] = r * 64 + lane < n_mine ? mylist[r * 64 + lane] : 0ull;
@@ -668,7 +683,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
             int rank = 0;
 #pragma unroll 8
             for (int j = 0; j < S2; ++j) rank += s_short[j] > mine ? 1 : 0;
-            if (tid < S2 && rank < k) dst[rank] = mine;
+            if (tid < S2 && rank < k) emit(rank, mine);
             return;
         }
         // many ties with the bound: the words stay where they are, every wave drops the others from its list
@@ -706,7 +721,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     }
 #pragma unroll
     for (int r = 0; r < kTopkRegion / 64; ++r)
-        if (r * 64 + lane < n_mine && rank[r] < k) dst[rank[r]] = w[r];
+        if (r * 64 + lane < n_mine && rank[r] < k) emit(rank[r], w[r]);
 }
 
 // Merges the segments' candidates of one row with one wave: n_cand words (0 = empty), at most
@@ -851,10 +866,12 @@ hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask,
 
 static int masked_topk_chunks(int vocab) { return (vocab + kTopkChunk - 1) / kTopkChunk; }
 
-// Chunks per block: as many as still leave two blocks per compute unit, so that small batches are
-// spread over the chip and large ones pay the per-block phases once per row.
+// Chunks per block: the whole row once there is a row per compute unit (the block then writes the
+// result itself and no second kernel runs); below that as many as still leave two blocks per compute
+// unit, so that small batches are spread over the chip.
 static int masked_topk_chunks_per_segment(int batch, int vocab, int n_compute_units) {
     const int n_chunks = masked_topk_chunks(vocab);
+    if (batch >= n_compute_units) return n_chunks;
     int per = 1;
     while (per < n_chunks && (int64_t)batch * ((n_chunks + 2 * per - 1) / (2 * per)) >= 2 * (int64_t)n_compute_units) per *= 2;
     return per < n_chunks ? per : n_chunks;
@@ -878,8 +895,13 @@ hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, i
     const int per = masked_topk_chunks_per_segment(batch, vocab, n_compute_units);
     const int n_seg = (masked_topk_chunks(vocab) + per - 1) / per;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
+    if (n_seg == 1) {
+        hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, 1), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
+                           n_words, vec_ok, k, per, workspace, out_ids, out_vals);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
-                       n_words, vec_ok, k, per, workspace);
+                       n_words, vec_ok, k, per, workspace, (int32_t *)nullptr, (uint16_t *)nullptr);
     hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(64), 0, stream, workspace, n_seg * k, k, logits, row_stride,
                        out_ids, out_vals);
     return hipGetLastError();

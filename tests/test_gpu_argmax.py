@@ -142,9 +142,11 @@ def _bf16(x):
     return (np.asarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
 
 
-@pytest.mark.parametrize("V,B,stride_pad,ks", [(70001, 300, 7, (50, 64)), (70001, 300, 0, (7,)), (128256, 520, 0, (50,))])
+@pytest.mark.parametrize("V,B,stride_pad,ks", [(70001, 300, 7, (50, 64)), (70001, 300, 0, (7,)), (128256, 520, 0, (50,)),
+                                               (128256, 200, 0, (50, 3))])
 def test_masked_topk_over_segments_of_several_chunks(V, B, stride_pad, ks):
-    """Batches large enough that a block takes several chunks of 16,384 tokens in a row: rows of equal
+    """Batches large enough that a block takes several chunks of 16,384 tokens in a row (a whole row from
+    one row per compute unit on; at B = 200 two chunks, and a second kernel merges the segments): rows of equal
     logits (every chunk overflows the candidate list, ties decided by id), logits rising or falling with
     the id (the list is cut to its k best between chunks), masks that leave the first chunks empty or
     nearly empty, a single chunk with thousands of ties under a few larger values, NaN rows."""
