@@ -367,11 +367,16 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
 // from the current stack on a private overlay of its own -- the walk of a one-byte token --, the
 // wave adds up the BYTES of the viable classes, and if that is one (and '$' is not accepted) the
 // forced byte is walked on the real stack by all lanes together, exactly like in advance_kernel.
+// kCompact (cycle-aware stacks): at the end the wave stages its stack in LDS (cap entries per
+// sequence), takes complete traversals of reduction cycles out of it and writes back what changed.
 constexpr int kJfSeqPerBlock = 4;
+template <bool kCompact>
 __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
     DevTables T, int32_t *__restrict__ states, int32_t *__restrict__ data, int32_t *__restrict__ len, int cap,
     int batch, uint8_t *__restrict__ out_bytes, int32_t *__restrict__ out_len, int max_bytes, int32_t *adv_scratch,
-    int32_t *lane_spill, size_t lane_spill_stride) {
+    int32_t *lane_spill, size_t lane_spill_stride, const int32_t *__restrict__ cycle_head,
+    const int32_t *__restrict__ cycle_pool) {
+    extern __shared__ int32_t jf_stage[];              // kCompact: kJfSeqPerBlock x cap stack entries
     __shared__ int32_t s_trial[kJfSeqPerBlock][kLdsDepth * 64];
     __shared__ int32_t s_adv[kJfSeqPerBlock][kLdsDepth];
     __shared__ int32_t s_win[kJfSeqPerBlock][kWindow], s_new[kJfSeqPerBlock][kWindow];
@@ -453,6 +458,19 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
         }
     }
     if (lane == 0) out_len[b] = count;
+    if (kCompact && n >= 2 && n <= cap) {
+        // n is the current length (the entries committed above are this wave's own stores)
+        __threadfence_block();
+        int32_t *stack = jf_stage + wave * cap;
+        for (int i = lane; i < n; i += 64) stack[i] = row[i];
+        __builtin_amdgcn_wave_barrier();
+        int first_moved = n;
+        const int w = fold_cycles(stack, n, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+        if (w != n) {
+            for (int i = first_moved + lane; i < w; i += 64) row[i] = stack[i];
+            if (lane == 0) len[b] = w;
+        }
+    }
 }
 
 
@@ -547,13 +565,25 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
     return hipGetLastError();
 }
 
+bool jump_forward_fits_compact(int cap) {
+    return cap <= kCompactMaxLen && (size_t)kJfSeqPerBlock * cap * sizeof(int32_t) + 20480 <= 65536;
+}
+
 hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
                                uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
-                               int32_t *lane_spill, hipStream_t stream) {
+                               int32_t *lane_spill, const int32_t *cycle_head, const int32_t *cycle_pool,
+                               hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    hipLaunchKernelGGL(jump_forward_kernel, dim3((batch + kJfSeqPerBlock - 1) / kJfSeqPerBlock), dim3(64 * kJfSeqPerBlock),
-                       0, stream, T, states, data, len, cap, batch, out_bytes, out_len, max_bytes, adv_scratch, lane_spill,
-                       (size_t)batch * 64);
+    const dim3 grid((batch + kJfSeqPerBlock - 1) / kJfSeqPerBlock), block(64 * kJfSeqPerBlock);
+    if (cycle_head) {                                  // cycle-aware stacks: compacted before the kernel ends
+        if (!jump_forward_fits_compact(cap)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(jump_forward_kernel<true>, grid, block, (size_t)kJfSeqPerBlock * cap * sizeof(int32_t), stream, T,
+                           states, data, len, cap, batch, out_bytes, out_len, max_bytes, adv_scratch, lane_spill,
+                           (size_t)batch * 64, cycle_head, cycle_pool);
+    } else {
+        hipLaunchKernelGGL(jump_forward_kernel<false>, grid, block, 0, stream, T, states, data, len, cap, batch, out_bytes,
+                           out_len, max_bytes, adv_scratch, lane_spill, (size_t)batch * 64, nullptr, nullptr);
+    }
     return hipGetLastError();
 }
 

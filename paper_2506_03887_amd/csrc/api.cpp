@@ -548,10 +548,12 @@ int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int3
     if (!h->b_states) return fail(h, PRE3_E_BADARG, "jump_forward: no state bound");
     if (!out_len || max_bytes < 0 || (max_bytes > 0 && !out_bytes))
         return fail(h, PRE3_E_BADARG, "jump_forward: null pointer or negative max_bytes");
+    const bool fused = h->compact && h->T.n_cycles > 0 && jump_forward_fits_compact(h->b_stacks.cap);
     hipError_t e = launch_jump_forward(h->dev, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                                        h->b_stacks.batch, out_bytes, out_len, max_bytes, h->adv_scratch,
-                                       h->af_walk_spill, static_cast<hipStream_t>(stream));
-    if (e == hipSuccess) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
+                                       h->af_walk_spill, fused ? h->cycle_head : nullptr, fused ? h->cycle_pool : nullptr,
+                                       static_cast<hipStream_t>(stream));
+    if (e == hipSuccess && !fused) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch jump_forward");
 }
 

@@ -53,7 +53,9 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
 bool advance_fill_fits_compact(int n_words, int cap);   // row bitmap + staged stack within 64 KB of LDS
 hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
                                uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
-                               int32_t *lane_spill, hipStream_t stream);
+                               int32_t *lane_spill, const int32_t *cycle_head, const int32_t *cycle_pool,
+                               hipStream_t stream);
+bool jump_forward_fits_compact(int cap);                // four staged stacks within the kernel's LDS
 
 // Stack compaction over registered reduction cycles; cap (entries per stack) at most kCompactMaxLen.
 constexpr int kCompactMaxLen = 4096;

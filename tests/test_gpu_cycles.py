@@ -130,6 +130,13 @@ def test_capacity_beyond_the_fused_staging_uses_the_compaction_kernel():
         assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), s
         live = np.arange(cap)[None, :] < len_h[:, None]
         assert (data_d.cpu().numpy()[live] == data_h[live]).all(), s
+        if s % 9 == 4:                                  # jump-forward takes the same fallback at this capacity
+            out = torch.zeros((B, 8), dtype=torch.uint8, device=dev)
+            cnt = torch.zeros(B, dtype=torch.int32, device=dev)
+            lib.jump_forward(out, cnt)
+            want_bytes, want_cnt = o.jump_forward_batch(states_h, data_h, len_h, 8)
+            assert cnt.cpu().numpy().tolist() == want_cnt.tolist() == [0] * B, s      # white space is always allowed
+            assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), s
     for b in range(B):
         assert o.eos_allowed(data_h[b, : len_h[b]])
 
