@@ -278,6 +278,49 @@ def test_greedy_decode_in_lockstep_with_the_oracle(cfg_idx, steps, fused_advance
         assert (data_d.cpu().numpy()[live] == data_h[live]).all()
 
 
+@pytest.mark.parametrize("cfg_idx,steps,k", [(2, 60, 8), (3, 8, 50), (4, 6, 8)])
+def test_topk_sampling_decode_in_lockstep_with_the_oracle(cfg_idx, steps, k):
+    """A top-k sampler on real grammar masks (free-form JSON and a schema whose keys are forced; many
+    groups of 8 tokens fully masked): the k candidates and their logits must equal the oracle's at every step;
+    both sides then take the same seeded choice among them and advance."""
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    cfg = configs.get(cfg_idx)
+    v = cfg.vocab
+    B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
+    o = Oracle(cfg.grammars)
+    s0 = o.initial_state(0)
+    data_h = np.zeros((B, cap), dtype=np.int32)
+    data_h[:, 0] = s0
+    len_h = np.ones(B, dtype=np.int32)
+    states_h = np.full(B, s0, dtype=np.int32)
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap)
+    data_d, len_d = torch.from_numpy(data_h.copy()).to(dev), torch.from_numpy(len_h.copy()).to(dev)
+    states_d, err_d = torch.from_numpy(states_h.copy()).to(dev), torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
+    ids_d = torch.empty((B, k), dtype=torch.int32, device=dev)
+    vals_d = torch.empty((B, k), dtype=torch.int16, device=dev)
+    lib.fill_mask(states_d, data_d, len_d, mask_d)
+    rng = np.random.default_rng(cfg.seed + 11)
+    for s in range(steps):
+        logits = bf16_logits(rng, B, V)
+        mask_h = o.fill_mask(states_h, data_h, len_h, v)
+        want_ids, want_vals = oracle_masked_topk(logits, mask_h, V, k)
+        lib.apply_mask_topk(torch.from_numpy(logits.view(np.int16)).to(dev).view(torch.bfloat16), mask_d, ids_d, vals_d)
+        assert (ids_d.cpu().numpy() == want_ids).all(), f"candidates differ at step {s}"
+        assert (vals_d.cpu().numpy().view(np.uint16) == want_vals).all(), f"candidate logits differ at step {s}"
+        n_valid = (want_ids >= 0).sum(axis=1)
+        assert (n_valid >= 1).all()
+        pick = (rng.integers(0, 1 << 30, size=B) % n_valid).astype(np.int64)
+        tokens = want_ids[np.arange(B), pick].astype(np.int32)
+        assert not o.advance_batch(states_h, data_h, len_h, tokens, v).any()
+        fin = states_h < 0                                    # slot reuse
+        states_h[fin], len_h[fin] = s0, 1
+        lib.advance_fill_mask(torch.from_numpy(tokens).to(dev), mask_d, restart_on_eos=True)
+        assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all()
+
+
 def test_greedy_decode_emits_documents_the_json_module_accepts():
     """No oracle in the loop: the device decodes greedily from seeded logits (EOS favoured a little
     so that documents end), and every finished sequence's text must parse with Python's json."""
