@@ -19,7 +19,8 @@
  *     pre3_bind_state are the calls that allocate device memory (tables; scratch sized by
  *     the bound batch).  Device calls that take the handle share that scratch: enqueue
  *     them so that calls on one handle do not run concurrently (one stream, or ordered
- *     by events); different handles are independent.
+ *     by events); different handles are independent.  A handle's tables live on the
+ *     device that was current in pre3_compile: later calls on it need that device current.
  *   - Terminals are single bytes; a parse stack holds LR(1) state ids only, bottom first
  *     (Sec. 3.2.2: an acceptance edge pushes the target node's state).
  *   - State ids: canonical LR(1) item sets (App. A.2) numbered in breadth-first discovery
