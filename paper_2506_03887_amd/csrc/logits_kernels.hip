@@ -341,10 +341,10 @@ __device__ __forceinline__ unsigned long long wave_kth_largest(const unsigned lo
 //   larger words in all lists) and the k best write themselves in order.
 // The k words are written to out[(row * n_seg + segment) * k ..], best first, 0-padded; with one
 // segment per row the kernel writes the row's ids and bf16 patterns itself (out_ids, out_vals).
-constexpr int kTopkBlock = 512;
-constexpr int kTopkWaves = kTopkBlock / 64;
+constexpr int kTopkBlock = 512;                    // threads per block; kTopkBlockWide when a row has a compute unit to itself
+constexpr int kTopkBlockWide = 1024;
 constexpr int kTopkPerThread = 32;
-constexpr int kTopkChunk = kTopkPerThread * kTopkBlock;
+constexpr int kTopkChunk = kTopkPerThread * kTopkBlock;   // tokens per chunk (twice as many for the wide block)
 constexpr int kTopkRegion = 256;
 
 // Eight logits from t0 on, one 2-byte load each (rows that are not 16-byte aligned, and the group
@@ -385,16 +385,18 @@ __device__ __noinline__ uint32_t topk_cut_list(unsigned long long *list, int n, 
     return (uint32_t)(thr >> kTopkIdBits);
 }
 
-__global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
+template <int kBlock>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out,
     int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
-    __shared__ unsigned long long s_list[kTopkWaves * kTopkRegion];
-    __shared__ int s_nz[kTopkWaves];
-    __shared__ uint32_t s_wbound[kTopkWaves];
-    __shared__ int s_n[kTopkWaves];
+    constexpr int kWaves = kBlock / 64, kChunk = kTopkPerThread * kBlock;
+    __shared__ unsigned long long s_list[kWaves * kTopkRegion];
+    __shared__ int s_nz[kWaves];
+    __shared__ uint32_t s_wbound[kWaves];
+    __shared__ int s_n[kWaves];
     __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
-    __shared__ unsigned long long s_short[kTopkBlock];        // the few words left at the end, one per thread
+    __shared__ unsigned long long s_short[kBlock];        // the few words left at the end, one per thread
     __shared__ int s_total;
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 256) {
@@ -420,11 +422,11 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
             if (out_vals) out_vals[(size_t)b * k + rank] = 0xFF80u;
         }
     };
-    const int n_chunks = (vocab + kTopkChunk - 1) / kTopkChunk;
+    const int n_chunks = (vocab + kChunk - 1) / kChunk;
     const int c_begin = seg * chunks_per_seg;
     const int c_end = c_begin + chunks_per_seg < n_chunks ? c_begin + chunks_per_seg : n_chunks;
-    // element e of a thread (0 .. 31) is token  chunk * kTopkChunk + rel(e); its key is half (e & 1) of kp[e >> 1]
-    auto rel = [&](int e) { return (tid + (e >> 3) * kTopkBlock) * 8 + (e & 7); };
+    // element e of a thread (0 .. 31) is token  chunk * kChunk + rel(e); its key is half (e & 1) of kp[e >> 1]
+    auto rel = [&](int e) { return (tid + (e >> 3) * kBlock) * 8 + (e & 7); };
     unsigned long long *mylist = s_list + wave * kTopkRegion;
     const unsigned long long lanes_below = (1ull << lane) - 1ull;
     int n_mine = 0;                                           // length of the wave's list
@@ -436,23 +438,23 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     auto load_mask = [&](int chunk, uint32_t (&m)[kTopkPerThread / 8]) {
 #pragma unroll
         for (int g = 0; g < kTopkPerThread / 8; ++g) {
-            const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
+            const int t0 = chunk * kChunk + (tid + g * kBlock) * 8;
             m[g] = (chunk < c_end && t0 < vocab && (t0 >> 3) < n_mask_bytes) ? mrow[t0 >> 3] : 0u;
         }
     };
     auto load_logits = [&](int chunk, const uint32_t (&m)[kTopkPerThread / 8], uint4 (&v)[kTopkPerThread / 8]) {
-        const uint16_t *p = lrow + (size_t)chunk * kTopkChunk + (size_t)tid * 8;
-        if (vec_ok && (chunk + 1) * kTopkChunk <= vocab) {       // a whole chunk of an aligned row
+        const uint16_t *p = lrow + (size_t)chunk * kChunk + (size_t)tid * 8;
+        if (vec_ok && (chunk + 1) * kChunk <= vocab) {       // a whole chunk of an aligned row
 #pragma unroll
             for (int g = 0; g < kTopkPerThread / 8; ++g) {
                 v[g] = make_uint4(0u, 0u, 0u, 0u);               // its mask zeroes the keys anyway
-                if (m[g] != 0u) v[g] = stream_load(p + g * kTopkBlock * 8);
+                if (m[g] != 0u) v[g] = stream_load(p + g * kBlock * 8);
             }
             return;
         }
 #pragma unroll
         for (int g = 0; g < kTopkPerThread / 8; ++g) {
-            const int t0 = chunk * kTopkChunk + (tid + g * kTopkBlock) * 8;
+            const int t0 = chunk * kChunk + (tid + g * kBlock) * 8;
             v[g] = make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);   // NaN: no candidate
             if (m[g] != 0u) {
                 if (vec_ok && t0 + 8 <= vocab) v[g] = stream_load(lrow + (size_t)t0);
@@ -510,12 +512,12 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
             lds_barrier();
             int quota = 0, holders = 0;
 #pragma unroll
-            for (int w = 0; w < kTopkWaves; ++w) holders += s_nz[w];
+            for (int w = 0; w < kWaves; ++w) holders += s_nz[w];
             if (holders >= k) {
                 for (quota = 1; quota < 64; ++quota) {
                     int sum = 0;
 #pragma unroll
-                    for (int w = 0; w < kTopkWaves; ++w) sum += s_nz[w] < quota ? s_nz[w] : quota;
+                    for (int w = 0; w < kWaves; ++w) sum += s_nz[w] < quota ? s_nz[w] : quota;
                     if (sum >= k) break;
                 }
             }
@@ -531,7 +533,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
             lds_barrier();
             uint32_t cb = 0x10000u;
 #pragma unroll
-            for (int w = 0; w < kTopkWaves; ++w) cb = s_wbound[w] < cb ? s_wbound[w] : cb;
+            for (int w = 0; w < kWaves; ++w) cb = s_wbound[w] < cb ? s_wbound[w] : cb;
             if (cb != 0x10000u && cb > block_bound) block_bound = cb;
         }
         uint32_t bound = block_bound > wave_bound ? block_bound : wave_bound;
@@ -564,13 +566,13 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
             if (mine == 1) {
                 // the usual case: the key is the thread's maximum, and the sum is its register
                 const int e = (count2 & 0xFFFFu) ? 2 * (int)(where2 & 0xFFFFu) : 2 * (int)(where2 >> 16) + 1;
-                mylist[slot] = topk_word(best, (uint32_t)(chunk * kTopkChunk + rel(e)));
+                mylist[slot] = topk_word(best, (uint32_t)(chunk * kChunk + rel(e)));
             } else if (mine > 1) {
 #pragma unroll
                 for (int i = 0; i < kTopkPerThread / 2; ++i) {
                     const uint32_t reach = packed_sub_sat_u16(kp[i], below);
-                    if (reach & 0xFFFFu) mylist[slot++] = topk_word(kp[i] & 0xFFFFu, (uint32_t)(chunk * kTopkChunk + rel(2 * i)));
-                    if (reach >> 16) mylist[slot++] = topk_word(kp[i] >> 16, (uint32_t)(chunk * kTopkChunk + rel(2 * i + 1)));
+                    if (reach & 0xFFFFu) mylist[slot++] = topk_word(kp[i] & 0xFFFFu, (uint32_t)(chunk * kChunk + rel(2 * i)));
+                    if (reach >> 16) mylist[slot++] = topk_word(kp[i] >> 16, (uint32_t)(chunk * kChunk + rel(2 * i + 1)));
                 }
             }
             n_mine += total;
@@ -594,7 +596,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
                 take = key >= bound;
                 mm = __ballot(take);
             }
-            if (take) mylist[n_mine + __popcll(mm & lanes_below)] = topk_word(key, (uint32_t)(chunk * kTopkChunk + rel(e)));
+            if (take) mylist[n_mine + __popcll(mm & lanes_below)] = topk_word(key, (uint32_t)(chunk * kChunk + rel(e)));
             n_mine += __popcll(mm);
         }
         if (cut) {                                            // from the next chunk on ties with the k-th can be left out
@@ -613,7 +615,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     lds_barrier();
     int S = 0;
 #pragma unroll
-    for (int w = 0; w < kTopkWaves; ++w) S += s_n[w];
+    for (int w = 0; w < kWaves; ++w) S += s_n[w];
     if (tid >= S && tid < k) emit(tid, 0ull);
     unsigned long long w[kTopkRegion / 64];
 #pragma unroll
@@ -629,12 +631,12 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
         lds_barrier();
         int quota = 0, holders = 0;
 #pragma unroll
-        for (int ww = 0; ww < kTopkWaves; ++ww) holders += s_nz[ww];
+        for (int ww = 0; ww < kWaves; ++ww) holders += s_nz[ww];
         if (holders >= k) {
             for (quota = 1; quota < 64; ++quota) {
                 int sum = 0;
 #pragma unroll
-                for (int ww = 0; ww < kTopkWaves; ++ww) sum += s_nz[ww] < quota ? s_nz[ww] : quota;
+                for (int ww = 0; ww < kWaves; ++ww) sum += s_nz[ww] < quota ? s_nz[ww] : quota;
                 if (sum >= k) break;
             }
         }
@@ -650,7 +652,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
         lds_barrier();
         cb = 0x10000u;
 #pragma unroll
-        for (int ww = 0; ww < kTopkWaves; ++ww) cb = s_wbound[ww] < cb ? s_wbound[ww] : cb;
+        for (int ww = 0; ww < kWaves; ++ww) cb = s_wbound[ww] < cb ? s_wbound[ww] : cb;
     }
     {
         // the words that reach it: counted, and if there are few, gathered in one short list, one word per thread
@@ -666,8 +668,8 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
         lds_barrier();
         int S2 = 0;
 #pragma unroll
-        for (int ww = 0; ww < kTopkWaves; ++ww) S2 += s_nz[ww];
-        if (S2 <= kTopkBlock) {
+        for (int ww = 0; ww < kWaves; ++ww) S2 += s_nz[ww];
+        if (S2 <= kBlock) {
             int at = 0;
             if (lane == 0 && kept > 0) at = atomicAdd(&s_total, kept);
             at = __builtin_amdgcn_readfirstlane(at);
@@ -704,7 +706,7 @@ __global__ __launch_bounds__(kTopkBlock) __attribute__((amdgpu_waves_per_eu(4)))
     int rank[kTopkRegion / 64];
 #pragma unroll
     for (int r = 0; r < kTopkRegion / 64; ++r) rank[r] = 0;
-    for (int ww = 0; ww < kTopkWaves; ++ww) {
+    for (int ww = 0; ww < kWaves; ++ww) {
         const unsigned long long *other = s_list + ww * kTopkRegion;
         const int n_other = s_n[ww];
         if (n_mine <= 64) {
@@ -864,7 +866,7 @@ hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask,
     return hipGetLastError();
 }
 
-static int masked_topk_chunks(int vocab) { return (vocab + kTopkChunk - 1) / kTopkChunk; }
+static int masked_topk_chunks(int vocab, int chunk = kTopkChunk) { return (vocab + chunk - 1) / chunk; }
 
 // Chunks per block: the whole row once there is a row per compute unit (the block then writes the
 // result itself and no second kernel runs); below that as many as still leave two blocks per compute
@@ -892,16 +894,23 @@ hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, i
     if (batch == 0) return hipSuccess;
     if (!masked_topk_fits(vocab, k)) return hipErrorInvalidValue;
     const int n_words = (vocab + 31) / 32;
-    const int per = masked_topk_chunks_per_segment(batch, vocab, n_compute_units);
-    const int n_seg = (masked_topk_chunks(vocab) + per - 1) / per;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
-    if (n_seg == 1) {
-        hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, 1), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
-                           n_words, vec_ok, k, per, workspace, out_ids, out_vals);
+    if (batch >= n_compute_units && batch < 2 * n_compute_units) {
+        // a row per compute unit and no second block beside it: sixteen waves take the row
+        hipLaunchKernelGGL(masked_topk_kernel<kTopkBlockWide>, dim3(batch, 1), dim3(kTopkBlockWide), 0, stream, logits, bitmask,
+                           vocab, row_stride, n_words, vec_ok, k, masked_topk_chunks(vocab, kTopkPerThread * kTopkBlockWide),
+                           workspace, out_ids, out_vals);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(masked_topk_kernel, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab, row_stride,
-                       n_words, vec_ok, k, per, workspace, (int32_t *)nullptr, (uint16_t *)nullptr);
+    const int per = masked_topk_chunks_per_segment(batch, vocab, n_compute_units);
+    const int n_seg = (masked_topk_chunks(vocab) + per - 1) / per;
+    if (n_seg == 1) {
+        hipLaunchKernelGGL(masked_topk_kernel<kTopkBlock>, dim3(batch, 1), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab,
+                           row_stride, n_words, vec_ok, k, per, workspace, out_ids, out_vals);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(masked_topk_kernel<kTopkBlock>, dim3(batch, n_seg), dim3(kTopkBlock), 0, stream, logits, bitmask, vocab,
+                       row_stride, n_words, vec_ok, k, per, workspace, (int32_t *)nullptr, (uint16_t *)nullptr);
     hipLaunchKernelGGL(masked_topk_finish_kernel, dim3(batch), dim3(64), 0, stream, workspace, n_seg * k, k, logits, row_stride,
                        out_ids, out_vals);
     return hipGetLastError();
