@@ -12,37 +12,105 @@ without a bracket around every launch (K launches of the kernel in one graph bet
 events); the rocprofv3 summaries under profiles/ hold the profiler's durations of the same
 kernels.  After the timed runs the device state and the last mask are checked against the CPU
 oracle's replay.  Prints ONE JSON line.
+
+The headline fields (`value`, `ms_per_step`, `config`, `dtype`, `roofline`, `cpu_baseline`) are
+measured first; every further leg (per-call brackets, greedy decoding, top-k, jump-forward, the
+byte-by-byte mask, the state checks) is guarded: if it fails, its entry of the line holds an
+"error" string and the line is still printed.  A failed check of the device state against the
+oracle is reported under "checks" and makes the process exit with status 1 after the line.
 """
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
+import traceback
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 BYTES_PER_PAIR = 4.25          # algorithmic HBM bytes per (sequence, token) pair of mask+apply
+APPLY_BYTES_PER_PAIR = 4.125   # logits read + written (2 + 2 B) and one mask bit read per 4 B word / 32 tokens
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of apply_mask_vec8_kernel on the default workload, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE scaled by what the counters read on a plain device copy
-# (profiles/apply_mask_vec8_kernel__json-B256-V128256.txt); other workloads report null
 GRAMMAR_LABEL = {7: "byte-level JSON, every list right-recursive", 1: "arithmetic expressions", 2: "byte-level JSON", 3: "byte-level JSON",
                  4: "schema JSON (12 typed keys)", 5: "8 schema-JSON grammars, mixed",
                  6: "free text, then byte-level JSON"}
-APPLY_TRAFFIC_BYTES = {3: 130.63e6}
+
+def plan_steps(steps: int, warmup: int, cpu_steps: int) -> dict:
+    """How many steps of the trajectory each leg uses.  K timed steps follow Wm warm-up steps on the
+    GPU; the CPU baseline replays the first n_cpu steps of the same trajectory, so the trajectory
+    is generated for n_traj = max(K + Wm, n_cpu) steps and every index any leg uses is below n_traj."""
+    K = max(1, int(steps))
+    Wm = max(0, int(warmup))
+    n_cpu = max(1, int(cpu_steps))
+    total = K + Wm
+    return {"K": K, "Wm": Wm, "total": total, "n_cpu": n_cpu, "n_traj": max(total, n_cpu)}
 
 
-def main():
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    import platform
+    return platform.processor() or platform.machine() or "unknown"
+
+
+def source_hash(rel_path: str) -> str:
+    with open(os.path.join(ROOT, rel_path), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def profile_traffic(kernel: str, workload: str, profiles_dir: str = None):
+    """(bytes per launch or None, note).  Reads `traffic_bytes_per_launch:` from the rocprofv3 summary
+    profiles/<kernel>__<workload>.txt; the figure is void (None) when the summary is missing, does not
+    state it, or was taken with another version of the kernel's source file (`kernel_source_sha256:`)."""
+    path = os.path.join(profiles_dir or os.path.join(ROOT, "profiles"), f"{kernel}__{workload}.txt")
+    rel = os.path.relpath(path, ROOT)
+    if not os.path.exists(path):
+        return None, f"no counter summary {rel}"
+    text = open(path).read()
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+    h = re.search(r"^kernel_source_sha256:\s*(\S+)\s+(\S+)", text, re.M)
+    if not m or not h:
+        return None, f"{rel} states no traffic figure"
+    try:
+        now = source_hash(h.group(1))
+    except OSError:
+        return None, f"{rel}: source file {h.group(1)} not found"
+    if now != h.group(2):
+        return None, f"{rel} was taken with another version of {h.group(1)}: counters void"
+    return float(m.group(1)), f"FETCH_SIZE + WRITE_SIZE per launch, calibrated on a plain copy, from {rel}"
+
+
+def guarded(fn, *a, **kw):
+    """Result of fn, or {"error": ...} if it raises: an auxiliary leg must not take the headline down."""
+    try:
+        return fn(*a, **kw)
+    except Exception as e:                     # noqa: BLE001 - anything: the line is still printed
+        tb = traceback.extract_tb(e.__traceback__)
+        where = f"{os.path.basename(tb[-1].filename)}:{tb[-1].lineno}" if tb else "?"
+        return {"error": f"{type(e).__name__}: {e} ({where})"}
+
+
+def parse_args(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--cpu-steps", type=int, default=96, help="steps of the workload timed on the CPU oracle")
+    ap.add_argument("--cpu-steps", type=int, default=96, help="most steps of the workload timed on the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0,
+                    help="the CPU oracle stops after the step that brings its timed work past this many seconds")
     ap.add_argument("--repeats", type=int, default=3, help="replays of each graph (the fastest is reported)")
     ap.add_argument("--eager", action="store_true",
                     help="no HIP graphs: time the eager pass only (for counter collection with rocprofv3 --pmc)")
+    ap.add_argument("--headline-only", action="store_true", help="skip the auxiliary legs (greedy, top-k, jump-forward, byte-by-byte)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
     ap.add_argument("--no-token-edges", action="store_true",
@@ -52,7 +120,11 @@ def main():
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
                     help="fill_mask + apply_mask + advance | fill_apply_mask + advance | "
                          "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS)")
-    args = ap.parse_args()
+    return ap.parse_args(argv)
+
+
+def main(argv=None):
+    args = parse_args(argv)
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on one GPU (sequences are independent: shard the batch across processes, one handle each); use --gpus 1")
 
@@ -75,7 +147,7 @@ def main():
         # buffers beyond the 256 MB Infinity Cache give the chip's practical read+write HBM rate
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 21,
                           "us_per_copy": us, "read_plus_write_GBs": 2.0 * n / (us * 1e-6) / 1e9}))
-        return
+        return 0
 
     from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax, masked_topk as oracle_masked_topk
     from paper_2506_03887_amd import Pre3, apply_mask
@@ -85,18 +157,19 @@ def main():
     cfg = configs.get(args.config)
     if args.batch > 0 and args.batch != cfg.batch:
         import dataclasses
-        import re
         cfg = dataclasses.replace(cfg, batch=args.batch, name=re.sub(r"-B\d+-", f"-B{args.batch}-", cfg.name))
     v = cfg.vocab
     B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
-    K, Wm = args.steps, args.warmup
-    total = K + Wm
+    plan = plan_steps(args.steps, args.warmup, args.cpu_steps)
+    K, Wm, total, n_traj = plan["K"], plan["Wm"], plan["total"], plan["n_traj"]
+    pairs = float(B) * V
 
     # ---- inputs: oracle-driven seeded trajectory (host), then everything uploaded
     compact = cfg.compact
     o = Oracle(cfg.grammars, compact_cycles=compact)
     gi, depths = configs.sequence_setup(cfg)
-    traj = trajectory.generate(o, v, B, total, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
+    traj = trajectory.generate(o, v, B, n_traj, cap, cfg.seed, gi, cfg.nest_cap, None, cfg.json_strings, depths, marker=cfg.marker, p_line_feed=cfg.p_line_feed)
+    assert traj.tokens.shape[0] == traj.reset.shape[0] == n_traj >= total
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
 
     dev = torch.device("cuda:0")
@@ -113,8 +186,8 @@ def main():
     err_d = torch.zeros(B, dtype=torch.int32, device=dev)
     mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
     lib.bind_state(states_d, data_d, len_d, err_d)
-    tokens_d = torch.from_numpy(traj.tokens).to(dev)
-    reset_d = torch.from_numpy(np.repeat(traj.reset[:, None, :], 2, axis=1)).to(dev)      # [steps, 2, B]
+    tokens_d = torch.from_numpy(traj.tokens[:total]).to(dev)
+    reset_d = torch.from_numpy(np.repeat(traj.reset[:total, None, :], 2, axis=1)).to(dev)      # [steps, 2, B]
     any_reset = traj.reset.any(axis=1)
     fresh_d = torch.from_numpy(np.stack([np.ones(B, dtype=np.int32), s0])).to(dev)        # len = 1, state = s0
     n_pool = 4
@@ -161,17 +234,11 @@ def main():
         resets(Wm)
         lib.fill_mask(states_d, data_d, len_d, mask_d)
 
-    def timed_graph(kind):
-        """Captures the K timed steps with the given kernels and returns the fastest replay (ms)."""
-        restore()
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for s in range(K):
-                step(Wm + s, kind)
+    def replay_best(g, before=None):
         best = float("inf")
         for _ in range(max(1, args.repeats) + 1):          # the first replay also warms the graph
-            restore()
+            if before:
+                before()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
@@ -181,14 +248,15 @@ def main():
             best = min(best, e0.elapsed_time(e1))
         return best
 
-    step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill"}[args.step]
-    if args.eager:
-        t_two = t_step = float("nan")
-    else:
-        t_two = timed_graph("fill+apply") if step_kind != "fill+apply" else None
-        t_step = timed_graph(step_kind)
-        if t_two is None:
-            t_two = t_step
+    def timed_graph(kind):
+        """Captures the K timed steps with the given kernels and returns the fastest replay (ms)."""
+        restore()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(K):
+                step(Wm + s, kind)
+        return replay_best(g, restore)
 
     def eager_pass(kind):
         """The same K steps launched eagerly with a HIP event before and after every library call.
@@ -240,16 +308,7 @@ def main():
         with torch.cuda.graph(g):
             for s in range(K):
                 apply_mask(logits[s % n_pool], mask_d, V)
-        best = float("inf")
-        for _ in range(max(1, args.repeats) + 1):
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            g.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            best = min(best, e0.elapsed_time(e1))
-        return best * 1e3 / K
+        return replay_best(g) * 1e3 / K
 
     _snaps = []
 
@@ -264,6 +323,178 @@ def main():
             torch.cuda.synchronize()
         return _snaps
 
+    def mask_apply_graph_us():
+        """fill_mask + apply_mask alone, K steps in one graph: the stacks of the K timed steps are
+        recorded first (fill_mask reads a snapshot, the bound buffers stay untouched), so every
+        step computes a different batch of rows, as in the real loop, but no advance or reset
+        kernel and no event bracket sits between the two calls that are timed."""
+        snaps = recorded_stacks()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(K):
+                ls, da = snaps[s]
+                lib.fill_mask(ls[1], da, ls[0], mask_d)
+                apply_mask(logits[s % n_pool], mask_d, V)
+        return replay_best(g) * 1e3 / K
+
+    # =========================== headline: the step, then the dominant kernel ===========================
+    step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill"}[args.step]
+    step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
+                 "fused": "pre3_fill_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
+                 "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "
+                                 "slot reuse on EOS)"}
+    step_us = None
+    if args.eager:
+        step_us, t_step = eager_pass(step_kind)
+        apply_us = float(step_us["apply_mask"].mean()) if "apply_mask" in step_us else float("nan")
+    else:
+        t_step = timed_graph(step_kind)
+        apply_us = apply_launch_us()
+    # after these passes the device holds the state after all K timed steps of `step_kind`
+    final_states_d, final_len_d, final_err_d = states_d.clone(), len_d.clone(), err_d.clone()
+
+    out = {
+        "metric": "masked (seq x vocab) tokens/sec",
+        "value": pairs * K / (t_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": t_step / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i32 (integer and bit work: i32 states, u32 bitmask words; the bf16 logits are selected, not computed on)",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": GRAMMAR_LABEL.get(cfg.idx, cfg.name) + ", canonical LR(1)",
+                   "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:total].sum()),
+                   "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
+    }
+
+    # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
+    if step_kind != "fused":
+        dom_name, dom_bytes, dom_us = "apply_mask_vec8_kernel", APPLY_BYTES_PER_PAIR * pairs, apply_us
+        dom_timing = ("HIP events around every launch of an eager pass over the timed steps" if args.eager else
+                      "K launches on rotating logits buffers replayed as one HIP graph between two HIP events, divided by K")
+    else:
+        fused_us, _ = eager_pass("fused")
+        dom_name, dom_bytes = "fill_mask_edges_kernel<true>", BYTES_PER_PAIR * pairs
+        dom_us = float(fused_us["fill_apply_mask"].mean())
+        dom_timing = "HIP events around every launch of an eager pass over the timed steps"
+    traffic, traffic_note = (None, "batch size differs from the profiled workload") if args.batch not in (0, configs.get(args.config).batch) \
+        else profile_traffic(dom_name.split("<")[0], cfg.name)
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                       "kernel": dom_name, "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
+                       "timing": dom_timing, "traffic_source": traffic_note,
+                       "frac_on_traffic": None if traffic is None else traffic / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+    # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
+    def cpu_baseline():
+        data_c, len_c = traj.init_data.copy(), traj.init_len.copy()
+        states_c = data_c[np.arange(B), len_c - 1].copy()
+        rng = np.random.default_rng(cfg.seed + 1)
+        cpu_logits = bf16_logits(rng, B, V)
+        cpu_t, done = 0.0, 0
+        for s in range(min(plan["n_cpu"], traj.reset.shape[0])):
+            rs = np.flatnonzero(traj.reset[s])
+            data_c[rs, 0], len_c[rs], states_c[rs] = s0[rs], 1, s0[rs]
+            t1 = time.perf_counter()
+            m = o.fill_mask(states_c, data_c, len_c, v)
+            oracle_apply_mask(cpu_logits, m, V)
+            cpu_t += time.perf_counter() - t1
+            done += 1
+            if cpu_t >= args.cpu_seconds:
+                break
+            o.advance_batch(states_c, data_c, len_c, traj.tokens[s], v)
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+        return {"value": pairs * done / cpu_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "cpu": cpu_model(),
+                "sample": f"fill_mask+apply_mask of the first {done} steps of the same workload "
+                          f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",
+                "us_per_step": cpu_t / done * 1e6}
+
+    out["cpu_baseline"] = guarded(cpu_baseline)
+
+    # =========================== everything below is auxiliary and guarded ===========================
+    stat = lambda x: {"mean": float(x.mean()), "p50": float(np.median(x)), "p99": float(np.percentile(x, 99))}
+
+    def per_call_leg():
+        """Three-call step in a graph, fill+apply alone in a graph, and per-call event brackets."""
+        r = {}
+        two_call_us, wall_two = eager_pass("fill+apply")
+        kernels = {k: stat(x) for k, x in two_call_us.items()}
+        if step_kind != "fill+apply":
+            su = step_us if step_us is not None else eager_pass(step_kind)[0]
+            kernels.update({k: stat(x) for k, x in su.items()})
+        r["kernels_us"] = kernels
+        brackets = float((two_call_us["fill_mask"] + two_call_us["apply_mask"]).mean())
+        if args.eager:
+            t_two, mask_apply_us = wall_two, brackets
+        else:
+            t_two = t_step if step_kind == "fill+apply" else timed_graph("fill+apply")
+            mask_apply_us = mask_apply_graph_us()
+        r["fill_mask_tokens_per_s"] = pairs / (float(two_call_us["fill_mask"].mean()) * 1e-6)
+        r["mask_apply_us_per_step"] = mask_apply_us
+        r["mask_apply_timing"] = ("pre3_fill_mask + pre3_apply_mask on the recorded stacks of the K timed steps, one HIP graph "
+                                  "between two HIP events, divided by K; with a pair of events around every launch the two "
+                                  f"calls read {brackets:.1f} us")
+        r["mask_apply_tokens_per_s"] = pairs / (mask_apply_us * 1e-6)
+        r["mask_apply_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+        r["step_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (t_step / K * 1e-3) / 1e9 / HBM_PEAK_GBS
+        r["graph_ms_per_step"] = {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K}
+        return r
+
+    def state_check():
+        """The timed run must have done the real work: final state == the oracle's replay."""
+        d_h, l_h, s_h = traj.init_data.copy(), traj.init_len.copy(), None
+        s_h = d_h[np.arange(B), l_h - 1].copy()
+        for s in range(total):
+            rs = np.flatnonzero(traj.reset[s])
+            d_h[rs, 0], l_h[rs], s_h[rs] = s0[rs], 1, s0[rs]
+            err = o.advance_batch(s_h, d_h, l_h, traj.tokens[s], v)
+            assert not err.any()
+        if step_kind == "advance-fill":            # slot reuse happened inside the last call
+            fin = s_h < 0
+            s_h[fin], l_h[fin] = s0[fin], 1
+        assert (final_states_d.cpu().numpy() == s_h).all() and (final_len_d.cpu().numpy() == l_h).all(), \
+            "device state after the timed run differs from the oracle's replay"
+        assert int(final_err_d.abs().sum().item()) == 0, "err flags set during the timed run"
+        return {"ok": True, "len_after_timed_steps": {"mean": float(l_h.mean()), "max": int(l_h.max())},
+                "stacks": (d_h, l_h, s_h)}
+
+    def mask_check():
+        """The last mask on the device is the oracle's mask of the last timed step's input state."""
+        restore()
+        for s in range(K - 1):
+            step(Wm + s, "advance")
+        resets(total - 1)
+        lib.fill_mask(states_d, data_d, len_d, mask_d)
+        d_c, l_c = traj.init_data.copy(), traj.init_len.copy()
+        s_c = d_c[np.arange(B), l_c - 1].copy()
+        for s in range(total - 1):
+            rs = np.flatnonzero(traj.reset[s])
+            d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
+            o.advance_batch(s_c, d_c, l_c, traj.tokens[s], v)
+        rs = np.flatnonzero(traj.reset[total - 1])
+        d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
+        assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_c, d_c, l_c, v)).all(), "final mask differs"
+        return {"ok": True}
+
+    def lookup_stats(stacks):
+        """What one mask look-up touches (host evaluation of the same condition trees on the final stacks)."""
+        d_h, l_h, s_h = stacks
+        tree_nodes = deepest = leftover = 0
+        if not args.no_token_edges and lib.token_edge_stats()["built"]:
+            for b in range(B):
+                if s_h[b] < 0:
+                    continue
+                ok, _, walk = lib.debug_resolve_row(d_h[b, : l_h[b]].copy())
+                tree_nodes += lib.last_resolve_info["path_nodes"]
+                deepest = max(deepest, lib.last_resolve_info["deepest_entry"])
+                leftover += len(walk) if ok else V
+        return {"condition_nodes_visited_per_step": tree_nodes,
+                "deepest_stack_entry_tested": deepest, "tokens_left_to_the_walk_per_step": leftover,
+                "note": "host evaluation of the device's condition trees on the stacks after the timed steps; "
+                        "the kernel is latency-bound: a descent of dependent loads per row, then a row copy"}
+
     def jump_forward_leg(n_calls=32, max_bytes=32):
         """pre3_jump_forward on the recorded stacks of the first steps (on copies: it advances the
         stacks), one call per step with a HIP event on either side; checked against the oracle."""
@@ -274,27 +505,30 @@ def main():
         out_b = torch.zeros((B, max_bytes), dtype=torch.uint8, device=dev)
         out_n = torch.zeros(B, dtype=torch.int32, device=dev)
         lib.bind_state(ls2[1], da2, ls2[0], err2)
-        times, forced = [], 0
-        for s in range(n_calls):
-            ls2.copy_(snaps[s][0]); da2.copy_(snaps[s][1])
-            if s == 0:                                            # check one call against the oracle
-                l_h, s_h = (x.copy() for x in ls2.cpu().numpy())
-                d_h = da2.cpu().numpy().copy()
-                wb, wn = o.jump_forward_batch(s_h, d_h, l_h, max_bytes)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            lib.jump_forward(out_b, out_n)
-            e1.record()
-            torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1) * 1e3)
-            forced += int(out_n.sum().item())
-            if s == 0:
-                assert (out_n.cpu().numpy() == wn).all() and (ls2[0].cpu().numpy() == l_h).all(), "jump_forward differs from the oracle"
-                gb = out_b.cpu().numpy()
-                assert all(gb[b, : wn[b]].tobytes() == wb[b, : wn[b]].tobytes() for b in range(B))
-        lib.bind_state(states_d, data_d, len_d, err_d)
-        return {"us_per_call": float(np.mean(times[1:])), "calls": n_calls - 1, "max_bytes": max_bytes,
+        try:
+            times, forced = [], 0
+            for s in range(n_calls):
+                ls2.copy_(snaps[s][0]); da2.copy_(snaps[s][1])
+                if s == 0:                                            # check one call against the oracle
+                    l_h, s_h = (x.copy() for x in ls2.cpu().numpy())
+                    d_h = da2.cpu().numpy().copy()
+                    wb, wn = o.jump_forward_batch(s_h, d_h, l_h, max_bytes)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lib.jump_forward(out_b, out_n)
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e3)
+                forced += int(out_n.sum().item())
+                if s == 0:
+                    assert (out_n.cpu().numpy() == wn).all() and (ls2[0].cpu().numpy() == l_h).all(), "jump_forward differs from the oracle"
+                    gb = out_b.cpu().numpy()
+                    assert all(gb[b, : wn[b]].tobytes() == wb[b, : wn[b]].tobytes() for b in range(B))
+        finally:
+            lib.bind_state(states_d, data_d, len_d, err_d)
+        timed = times[1:] if len(times) > 1 else times
+        return {"us_per_call": float(np.mean(timed)), "calls": len(timed), "max_bytes": max_bytes,
                 "forced_bytes_per_call": forced / n_calls,
                 "timing": "one eager call per recorded step between two HIP events (the bracket adds a few us)"}
 
@@ -319,91 +553,33 @@ def main():
                 lib.fill_mask(ls[1], da, ls[0], mask_d)
                 assert torch.equal(m2, mask_d), "byte-by-byte mask differs from the token-edge mask"
         t = float(np.mean(times[1:])) if len(times) > 1 else float(times[0])
-        return {"us_per_launch": t, "tokens_per_s": pairs_ / (t * 1e-6),
+        return {"us_per_launch": t, "tokens_per_s": pairs / (t * 1e-6),
                 "vocab_bytes_times_batch_per_s": float(B) * float(v.offsets[-1]) / (t * 1e-6),
                 "note": "fill_mask_walk_kernel; a walk stops at its first rejected byte, so the byte rate is an upper bound on byte steps"}
 
-    def mask_apply_graph_us():
-        """fill_mask + apply_mask alone, K steps in one graph: the stacks of the K timed steps are
-        recorded first (fill_mask reads a snapshot, the bound buffers stay untouched), so every
-        step computes a different batch of rows, as in the real loop, but no advance or reset
-        kernel and no event bracket sits between the two calls that are timed."""
-        snaps = recorded_stacks()
+    # ---- greedy decoding: the sampler fused behind the mask (pre3_apply_mask_argmax reads the logits once
+    #      and writes nothing back), tokens fed straight to pre3_advance_fill_mask
+    def fresh_logits():
+        for x in logits:                          # the timed passes above have masked these in place
+            x.copy_(torch.randn((B, V), generator=gen, device=dev, dtype=torch.float32))
+        return [x.view(torch.int16).cpu().numpy().view(np.uint16) for x in logits]
+
+    def graph_us(fn):
+        restore()
+        torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for s in range(K):
-                ls, da = snaps[s]
-                lib.fill_mask(ls[1], da, ls[0], mask_d)
-                apply_mask(logits[s % n_pool], mask_d, V)
-        best = float("inf")
-        for _ in range(max(1, args.repeats) + 1):
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            g.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            best = min(best, e0.elapsed_time(e1))
-        return best * 1e3 / K
+                fn(s)
+        return replay_best(g, restore) * 1e3 / K
 
-    apply_us = float("nan") if args.eager else apply_launch_us()
-    mask_apply_graph = float("nan") if args.eager else mask_apply_graph_us()
-    two_call_us, wall_two = eager_pass("fill+apply")
-    step_us, wall_step = (two_call_us, wall_two) if step_kind == "fill+apply" else eager_pass(step_kind)
-    if args.eager:
-        t_step, t_two = wall_step, wall_two
-    # after the last pass the device holds the state after all K timed steps of `step_kind`
-
-    # ---- the timed run must have done the real work: final state == oracle's replay
-    for s in range(total):
-        rs = np.flatnonzero(traj.reset[s])
-        data_h[rs, 0], len_h[rs], states_h[rs] = s0[rs], 1, s0[rs]
-        err = o.advance_batch(states_h, data_h, len_h, traj.tokens[s], v)
-        assert not err.any()
-    if step_kind == "advance-fill":            # slot reuse happened inside the last call
-        fin = states_h < 0
-        states_h[fin], len_h[fin] = s0[fin], 1
-    assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), \
-        "device state after the timed run differs from the oracle's replay"
-    assert int(err_d.abs().sum().item()) == 0
-    stack_len_after = {"mean": float(len_h.mean()), "max": int(len_h.max())}
-    # what one mask look-up touches (host evaluation of the same condition trees on the final stacks)
-    tree_nodes = deepest = leftover = 0
-    if not args.no_token_edges and lib.token_edge_stats()["built"]:
-        for b in range(B):
-            if states_h[b] < 0:
-                continue
-            ok, _, walk = lib.debug_resolve_row(data_h[b, : len_h[b]].copy())
-            tree_nodes += lib.last_resolve_info["path_nodes"]
-            deepest = max(deepest, lib.last_resolve_info["deepest_entry"])
-            leftover += len(walk) if ok else V
-    # and the last mask on the device is the oracle's mask of the last timed step's input state
-    restore()
-    for s in range(K - 1):
-        step(Wm + s, "advance")
-    resets(total - 1)
-    lib.fill_mask(states_d, data_d, len_d, mask_d)
-    d_c, l_c = traj.init_data.copy(), traj.init_len.copy()
-    s_c = d_c[np.arange(B), l_c - 1].copy()
-    for s in range(total - 1):
-        rs = np.flatnonzero(traj.reset[s])
-        d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
-        o.advance_batch(s_c, d_c, l_c, traj.tokens[s], v)
-    rs = np.flatnonzero(traj.reset[total - 1])
-    d_c[rs, 0], l_c[rs], s_c[rs] = s0[rs], 1, s0[rs]
-    assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(s_c, d_c, l_c, v)).all(), "final mask differs"
-
-    # ---- greedy decoding: the sampler fused behind the mask (pre3_apply_mask_argmax reads the logits once
-    #      and writes nothing back), tokens fed straight to pre3_advance_fill_mask
     def greedy_leg():
         tok_d = torch.empty(B, dtype=torch.int32, device=dev)
-        for x in logits:                          # fresh logits: the timed passes above have masked these in place
-            x.copy_(torch.randn((B, V), generator=gen, device=dev, dtype=torch.float32))
+        host_logits = fresh_logits()
         restore()
         torch.cuda.synchronize()
         d_g, ls_g = data_d.cpu().numpy().copy(), ls_d.cpu().numpy().copy()
         l_g, s_g = ls_g[0].copy(), ls_g[1].copy()
-        host_logits = [x.view(torch.int16).cpu().numpy().view(np.uint16) for x in logits]
         n_check = 6
         for s in range(n_check):                  # both sides choose their own tokens and must agree
             want = oracle_masked_argmax(host_logits[s % n_pool], o.fill_mask(s_g, d_g, l_g, v), V)
@@ -415,9 +591,27 @@ def main():
             s_g[fin], l_g[fin] = s0[fin], 1
             assert (err_d.cpu().numpy() == e).all()
         assert (states_d.cpu().numpy() == s_g).all() and (len_d.cpu().numpy() == l_g).all()
+        if args.eager:                            # counter collection: the checked eager steps are enough
+            return {"checked_steps_against_oracle": n_check}
 
-        # top-k behind the mask (k = 50): same read-once traffic as the arg max; one call checked against the oracle
-        topk_k = 50
+        def greedy_step(s):
+            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
+            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
+
+        argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
+        step_us_g = graph_us(greedy_step)
+        nbytes = 2.0 * pairs + 4.0 * B * W
+        return {"step": "pre3_apply_mask_argmax + pre3_advance_fill_mask, K steps in one HIP graph, tokens chosen on the device",
+                "us_per_step": step_us_g, "tokens_per_s": pairs / (step_us_g * 1e-6),
+                "argmax_launch_us": argmax_us, "argmax_algorithmic_bytes": nbytes,
+                "argmax_achieved_GBs": nbytes / (argmax_us * 1e-6) / 1e9,
+                "argmax_frac_of_hbm_peak": nbytes / (argmax_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "checked_steps_against_oracle": n_check}
+
+    def topk_leg(topk_k=50):
+        """top-k behind the mask: same read-once traffic as the arg max; one call checked against the oracle."""
+        host_logits = fresh_logits()
+        restore()
         topk_ids = torch.empty((B, topk_k), dtype=torch.int32, device=dev)
         topk_vals = torch.empty((B, topk_k), dtype=torch.int16, device=dev)
         lib.apply_mask_topk(logits[0], mask_d, topk_ids, topk_vals)
@@ -426,138 +620,55 @@ def main():
             "top-k differs from the oracle's"
         for s in range(1, 4):
             lib.apply_mask_topk(logits[s % n_pool], mask_d, topk_ids, topk_vals)
-
-        if args.eager:                            # counter collection: the checked eager steps are enough
-            return {"checked_steps_against_oracle": n_check}
-
-        def graph_us(fn):
-            restore()
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for s in range(K):
-                    fn(s)
-            best = float("inf")
-            for _ in range(max(1, args.repeats) + 1):
-                restore()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                g.replay()
-                e1.record()
-                torch.cuda.synchronize()
-                best = min(best, e0.elapsed_time(e1))
-            return best * 1e3 / K
-
-        def greedy_step(s):
-            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
-            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
-
-        argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
-        step_us_g = graph_us(greedy_step)
+        if args.eager:
+            return {"k": topk_k, "checked_calls_against_oracle": 1}
         topk_us = graph_us(lambda s: lib.apply_mask_topk(logits[s % n_pool], mask_d, topk_ids, topk_vals))
-        nbytes = 2.0 * pairs_ + 4.0 * B * W
-        return {"step": "pre3_apply_mask_argmax + pre3_advance_fill_mask, K steps in one HIP graph, tokens chosen on the device",
-                "us_per_step": step_us_g, "tokens_per_s": pairs_ / (step_us_g * 1e-6),
-                "argmax_launch_us": argmax_us, "argmax_algorithmic_bytes": nbytes,
-                "argmax_achieved_GBs": nbytes / (argmax_us * 1e-6) / 1e9,
-                "argmax_frac_of_hbm_peak": nbytes / (argmax_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                "checked_steps_against_oracle": n_check,
-                "topk": {"k": topk_k, "launch_us": topk_us, "achieved_GBs": nbytes / (topk_us * 1e-6) / 1e9,
-                         "frac_of_hbm_peak": nbytes / (topk_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                         "note": "pre3_apply_mask_topk, K calls in one HIP graph; same algorithmic bytes as the arg max"}}
+        nbytes = 2.0 * pairs + 4.0 * B * W
+        return {"k": topk_k, "launch_us": topk_us, "achieved_GBs": nbytes / (topk_us * 1e-6) / 1e9,
+                "frac_of_hbm_peak": nbytes / (topk_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "note": "pre3_apply_mask_topk, K calls in one HIP graph; same algorithmic bytes as the arg max"}
 
-    pairs_ = float(B) * V
-    greedy = greedy_leg()
+    def auxiliary(out, checks):
+        sc = guarded(state_check)
+        stacks = sc.pop("stacks", None)
+        checks["final_state_vs_oracle"] = sc
+        r = guarded(per_call_leg)
+        out.update({"per_call": r} if "error" in r else r)
+        checks["last_mask_vs_oracle"] = guarded(mask_check)
+        checks["device_fault_count"] = guarded(lambda: {"ok": lib.fault_count() == 0, "count": lib.fault_count()})
+        if stacks is not None:
+            out["fill_mask_lookup"] = guarded(lookup_stats, stacks)
+            if "kernels_us" in out and "error" not in out["fill_mask_lookup"]:
+                out["fill_mask_lookup"]["condition_nodes_per_s"] = (
+                    out["fill_mask_lookup"]["condition_nodes_visited_per_step"] / (out["kernels_us"]["fill_mask"]["mean"] * 1e-6))
+            out["stacks"] = {"cycle_aware": bool(compact), "reduction_cycles": len(lib.reduction_cycles()),
+                             "len_after_timed_steps": sc.get("len_after_timed_steps")}
+        out["initial_stack_depths"] = ({"min": int(traj.init_len.min() - 1), "mean": float(traj.init_len.mean() - 1),
+                                        "max": int(traj.init_len.max() - 1)} if cfg.mixed else None)
+        if not args.headline_only:
+            out["greedy"] = guarded(greedy_leg)
+            out["topk"] = guarded(topk_leg)
+            if not args.eager:
+                out["jump_forward"] = guarded(jump_forward_leg)
+                if not args.no_token_edges:
+                    out["fill_mask_byte_by_byte"] = guarded(byte_by_byte_leg)
+        out["token_edges"] = guarded(lib.token_edge_stats)
 
-    # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
-    n_cpu = max(1, args.cpu_steps)
-    data_c, len_c = traj.init_data.copy(), traj.init_len.copy()
-    states_c = data_c[np.arange(B), len_c - 1].copy()
-    rng = np.random.default_rng(cfg.seed + 1)
-    cpu_logits = bf16_logits(rng, B, V)
-    cpu_t = 0.0
-    for s in range(n_cpu):
-        rs = np.flatnonzero(traj.reset[s])
-        data_c[rs, 0], len_c[rs], states_c[rs] = s0[rs], 1, s0[rs]
-        t1 = time.perf_counter()
-        m = o.fill_mask(states_c, data_c, len_c, v)
-        oracle_apply_mask(cpu_logits, m, V)
-        cpu_t += time.perf_counter() - t1
-        o.advance_batch(states_c, data_c, len_c, traj.tokens[s], v)
-    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-
-    pairs = float(B) * V
-    stat = lambda x: {"mean": float(x.mean()), "p50": float(np.median(x)), "p99": float(np.percentile(x, 99))}
-    kernels = {k: stat(x) for k, x in two_call_us.items()}
-    kernels.update({k: stat(x) for k, x in step_us.items() if k not in kernels or step_kind != "fill+apply"})
-    mask_apply_brackets = float((two_call_us["fill_mask"] + two_call_us["apply_mask"]).mean())
-    mask_apply_us = mask_apply_brackets if args.eager else mask_apply_graph
-    # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
-    if "apply_mask" in step_us:
-        dom_name, dom_bytes = "apply_mask_vec8_kernel", (4.0 + 0.125) * pairs
-        dom_us = float(step_us["apply_mask"].mean()) if args.eager else apply_us
-        dom_timing = ("K launches on rotating logits buffers replayed as one HIP graph between two HIP events, "
-                      "divided by K (a pair of events around every single launch reads "
-                      f"{float(step_us['apply_mask'].mean()):.1f} us: the brackets add a few us)")
-        traffic = APPLY_TRAFFIC_BYTES.get(args.config) if args.batch in (0, configs.get(args.config).batch) else None
-    else:
-        dom_name, dom_bytes = "fill_mask_edges_kernel<true>", BYTES_PER_PAIR * pairs
-        dom_us = float(step_us["fill_apply_mask"].mean())
-        dom_timing = "HIP events around every launch of an eager pass over the timed steps"
-        traffic = None
-    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    step_achieved = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9
-    step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
-                 "fused": "pre3_fill_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
-                 "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "
-                                 "slot reuse on EOS)"}
-    out = {
-        "metric": "masked (seq x vocab) tokens/sec",
-        "value": pairs * K / (t_step * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": t_step / K,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "i32 (integer and bit work: i32 states, u32 bitmask words; the bf16 logits are selected, not computed on)",
-        "data": "synthetic",
-        "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": GRAMMAR_LABEL.get(cfg.idx, cfg.name) + ", canonical LR(1)",
-                   "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:].sum()),
-                   "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
-        "fill_mask_tokens_per_s": pairs / (float(two_call_us["fill_mask"].mean()) * 1e-6),
-        "initial_stack_depths": ({"min": int(traj.init_len.min() - 1), "mean": float(traj.init_len.mean() - 1),
-                                  "max": int(traj.init_len.max() - 1)} if cfg.mixed else None),
-        "mask_apply_us_per_step": mask_apply_us,
-        "mask_apply_timing": "pre3_fill_mask + pre3_apply_mask on the recorded stacks of the K timed steps, one HIP graph "
-                             "between two HIP events, divided by K; with a pair of events around every launch the two "
-                             f"calls read {mask_apply_brackets:.1f} us",
-        "mask_apply_tokens_per_s": pairs / (mask_apply_us * 1e-6),
-        "mask_apply_frac_of_hbm_peak": step_achieved / HBM_PEAK_GBS,
-        "kernels_us": kernels,
-        "graph_ms_per_step": {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": dom_name, "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
-                     "timing": dom_timing},
-        "cpu_baseline": {"value": pairs * n_cpu / cpu_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-                         "sample": f"fill_mask+apply_mask of the first {n_cpu} steps of the same workload "
-                                   f"({cpu_t:.1f} s wall, OpenMP over (sequence, mask word))",
-                         "us_per_step": cpu_t / n_cpu * 1e6},
-        "greedy": greedy,
-        "jump_forward": None if args.eager else jump_forward_leg(),
-        "fill_mask_lookup": {"condition_nodes_visited_per_step": tree_nodes,
-                             "condition_nodes_per_s": tree_nodes / (float(two_call_us["fill_mask"].mean()) * 1e-6),
-                             "deepest_stack_entry_tested": deepest, "tokens_left_to_the_walk_per_step": leftover,
-                             "note": "host evaluation of the device's condition trees on the stacks after the timed steps; "
-                                     "the kernel is latency-bound: a descent of dependent loads per row, then a 16 KB row copy"},
-        "fill_mask_byte_by_byte": None if (args.eager or args.no_token_edges) else byte_by_byte_leg(),
-        "compile_s": t_compile,
-        "stacks": {"cycle_aware": bool(compact), "reduction_cycles": len(lib.reduction_cycles()),
-                   "len_after_timed_steps": stack_len_after},
-        "token_edges": lib.token_edge_stats(),
-    }
+    checks = {}
+    try:
+        auxiliary(out, checks)
+    except Exception as e:                     # noqa: BLE001 - the headline above is still printed
+        out["auxiliary_error"] = f"{type(e).__name__}: {e}"
+    out["checks"] = checks
+    out["compile_s"] = t_compile
     print(json.dumps(out))
+    sys.stdout.flush()
+    bad = [k for k, c in checks.items() if not c.get("ok")]
+    if bad:
+        print("bench.py: check(s) failed: " + ", ".join(f"{k}: {checks[k]}" for k in bad), file=sys.stderr)
+        return 1
+    return 0
 
 
 if __name__ == "__main__":
-    main()
+    sys.exit(main())

@@ -284,6 +284,13 @@ int32_t pre3_edge(const pre3_handle *h, int32_t state, int32_t symbol, int32_t *
 int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt);
 /* Largest number of private stack entries a walk of one token can need. */
 int32_t pre3_walk_depth_bound(const pre3_handle *h);
+/* Number of token walks, since pre3_compile, that a kernel stopped at one of its internal guards
+ * (a private stack deeper than pre3_walk_depth_bound, a reduction chain longer than the tables
+ * allow) and therefore reported as "not allowed".  The bounds are derived from the grammar at
+ * compile time, so the count is 0 unless the tables or the bound are wrong: tests and the
+ * benchmark assert that.  Host call; copies one device counter back (synchronise the streams that
+ * run the handle's work first, so that their walks are counted).  out: host.  Errors: BADARG, HIP. */
+int pre3_debug_fault_count(pre3_handle *h, int64_t *out);
 /* Sizes of the token-level prefix-conditioned edge tables (Sec. 3.3, edge merging along the
  * bytes of each token): out[0] built?, [1] distinct root conditions, [2] condition-tree nodes,
  * [3] dense rows, [4] token ids in delta lists, [5] token ids in walk lists, [6] deepest stack

@@ -28,7 +28,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
-    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact",
+    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count",
 ]
 
 
@@ -84,6 +84,7 @@ def load():
     lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_reduction_cycle.argtypes = [vp, i32, vp, i32]
     lib.pre3_debug_compact.argtypes = [vp, vp, i32]
+    lib.pre3_debug_fault_count.argtypes = [vp, c.POINTER(c.c_int64)]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound",
                  "pre3_n_reduction_cycles"):
         getattr(lib, name).argtypes = [vp]
@@ -230,6 +231,14 @@ class Pre3:
         if n < 0:
             raise Pre3Error(n, "debug_compact")
         return st[:n].tolist()
+
+    def fault_count(self) -> int:
+        """Walks that a kernel stopped at an internal guard since compile (0 expected); synchronises first."""
+        import torch
+        torch.cuda.synchronize()
+        n = ctypes.c_int64()
+        self._check(self._lib.pre3_debug_fault_count(self._h, ctypes.byref(n)))
+        return n.value
 
     def validate_tables(self) -> int:
         """Number of out-of-range indices in the compiled tables (0 expected)."""

@@ -622,6 +622,15 @@ int32_t pre3_debug_compact(const pre3_handle *h, int32_t *stack, int32_t len) {
 
 int32_t pre3_walk_depth_bound(const pre3_handle *h) { return h && h->compiled ? h->max_depth : PRE3_E_BADARG; }
 
+int pre3_debug_fault_count(pre3_handle *h, int64_t *out) {
+    if (!usable(h) || !out) return PRE3_E_BADARG;
+    int32_t n = 0;
+    hipError_t e = hipMemcpy(&n, h->dev.fault, sizeof(n), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(h, e, "read fault counter");
+    *out = n;
+    return PRE3_OK;
+}
+
 int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]) {
     if (!h || !h->compiled || !out) return PRE3_E_BADARG;
     const TokenEdges &E = h->E;

@@ -1,4 +1,4 @@
-// Host-callable launchers of the kernels (defined in mask_kernels.hip, logits_kernels.hip and
+// Host-callable launchers of the kernels (defined in mask_kernels.hip, apply_kernels.hip, sampler_kernels.hip and
 // advance_kernels.hip) and the sizes of the scratch areas they need.
 #pragma once
 #include <hip/hip_runtime_api.h>

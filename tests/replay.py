@@ -15,13 +15,16 @@ def make_library(cfg, **kw):
                 compact_cycles=cfg.compact, **kw)
 
 
-def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, log=print, **lib_options):
+def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_apply=True, apply_steps=None, log=print,
+           **lib_options):
     """Runs `steps` decode steps of config `cfg_idx` on the GPU through the C ABI and checks,
     against the oracle on the same inputs:
       - states, len, live stack entries and err of every sequence after every advance;
-      - the whole bitmask (all B*W words) and the masked bf16 logits (all B*V raw patterns)
-        on the steps in `full_mask_steps` (None = every step);
-      - the full mask rows of `rows_per_step` seeded random sequences on every other step.
+      - the whole bitmask (all B*W words) on the steps in `full_mask_steps` (None = every step), and
+        on those of them in `apply_steps` (None = all of them) the masked bf16 logits (all B*V raw
+        patterns) through pre3_apply_mask and through the fused call;
+      - the full mask rows of `rows_per_step` seeded random sequences on every other step;
+      - at the end, that no kernel stopped a walk at an internal guard (the fault counter is 0).
     Returns a dict of counters."""
     import torch
     from paper_2506_03887_amd import apply_mask
@@ -52,7 +55,8 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
     s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
     rng = np.random.default_rng(cfg.seed + 1)
     full = set(range(steps)) if full_mask_steps is None else set(full_mask_steps)
-    n_full = n_rows = 0
+    with_apply = full if apply_steps is None else set(apply_steps) & full
+    n_full = n_rows = n_apply = 0
 
     for s in range(steps):
         rs = np.flatnonzero(traj.reset[s])
@@ -70,7 +74,8 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
             bad = np.argwhere(got != want)
             assert len(bad) == 0, f"cfg {cfg_idx} step {s}: {len(bad)} mask words differ, first (row, word) {bad[0]}"
             n_full += 1
-            if check_apply:
+            if check_apply and s in with_apply:
+                n_apply += 1
                 logits = bf16_logits(rng, B, V)
                 logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
                 fused_logits_d = logits_d.clone()
@@ -102,8 +107,8 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
         assert (data_g[live] == data_h[live]).all(), f"cfg {cfg_idx} step {s}: stack entries differ"
         if s % 32 == 31 or s == steps - 1:
             log(f"[cfg {cfg_idx}] step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
-    torch.cuda.synchronize()
-    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, depth_hist=traj.depth_hist)
+    assert lib.fault_count() == 0, f"cfg {cfg_idx}: a kernel stopped a walk at an internal guard"
+    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, applied=n_apply, depth_hist=traj.depth_hist)
 
 
 def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, **lib_options):
@@ -159,5 +164,5 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
                 n_rows += 1
         if s % 32 == 31 or s == steps - 1:
             log(f"[cfg {cfg_idx}] advance+fill step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
-    torch.cuda.synchronize()
+    assert lib.fault_count() == 0, f"cfg {cfg_idx}: a kernel stopped a walk at an internal guard"
     return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows)

@@ -49,28 +49,32 @@ def test_cfg2_rows_assembled_from_id_lists(threshold):
 
 
 def test_cfg3_json_full_size():
-    """B=256, V=128256, 256 steps: states/stacks on every step, the whole bitmask and masked
-    logits on 6 steps spread over the run, two full mask rows on every other step."""
-    r = replay(3, full_mask_steps=[0, 1, 50, 100, 200, 255])
-    assert r["full_masks"] == 6 and r["sampled_rows"] == 500
+    """B=256, V=128256, 256 steps: states/stacks and the whole bitmask (all B*W words) on every
+    step, the masked logits (both entry points) on 6 steps spread over the run."""
+    r = replay(3, apply_steps=[0, 1, 50, 100, 200, 255])
+    assert r["full_masks"] == 256 and r["applied"] == 6
 
 
 def test_cfg4_schema_full_size():
-    r = replay(4, full_mask_steps=[0, 40, 128, 255])
-    assert r["full_masks"] == 4
+    """B=512, V=152064, 256 steps: states/stacks on every step, the whole bitmask on every fourth
+    step (and the last), two full rows on every other step, the masked logits on 4 steps."""
+    r = replay(4, full_mask_steps=list(range(0, 256, 4)) + [255], apply_steps=[0, 40, 128, 255])
+    assert r["full_masks"] == 65 and r["applied"] == 4 and r["sampled_rows"] == 2 * (256 - 65)
 
 
 def test_cfg5_mixed_grammars_deep_stacks():
-    r = replay(5, full_mask_steps=[0, 1, 64, 256, 511])
-    assert r["full_masks"] == 5
+    """B=256, V=128256, 512 steps, 8 grammars, seeded deep stacks: states/stacks and the whole
+    bitmask on every step, the masked logits on 5 steps."""
+    r = replay(5, apply_steps=[0, 1, 64, 256, 511])
+    assert r["full_masks"] == 512 and r["applied"] == 5
     assert max(r["depth_hist"]) >= 60 and len(r["depth_hist"]) > 40
 
 
 def test_cfg6_free_text_then_json_full_size():
     """The second workload: documents that open with unconstrained text (dense masks) and end in
     a JSON answer, B=256, V=128256."""
-    r = replay(6, steps=160, full_mask_steps=[0, 1, 30, 80, 159])
-    assert r["full_masks"] == 5 and r["sampled_rows"] == 310
+    r = replay(6, steps=160, apply_steps=[0, 1, 30, 80, 159])
+    assert r["full_masks"] == 160 and r["applied"] == 5
 
 
 def test_advance_fill_mask_all_configs():
@@ -81,10 +85,10 @@ def test_advance_fill_mask_all_configs():
     assert replay_advance_fill(2, steps=64)["full_masks"] == 64
     assert replay_advance_fill(2, steps=12, max_condition_depth=2)["full_masks"] == 12
     assert replay_advance_fill(2, steps=12, token_edges=False)["full_masks"] == 12
-    assert replay_advance_fill(3, steps=96, full_mask_steps=[0, 40, 95])["full_masks"] == 3
-    assert replay_advance_fill(4, steps=64, full_mask_steps=[0, 63])["full_masks"] == 2
-    assert replay_advance_fill(5, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
-    assert replay_advance_fill(6, steps=96, full_mask_steps=[0, 50, 95])["full_masks"] == 3
+    assert replay_advance_fill(3, steps=96)["full_masks"] == 96
+    assert replay_advance_fill(4, steps=64, full_mask_steps=range(0, 64, 4))["full_masks"] == 16
+    assert replay_advance_fill(5, steps=96)["full_masks"] == 96
+    assert replay_advance_fill(6, steps=96, full_mask_steps=range(0, 96, 2))["full_masks"] == 48
 
 
 @pytest.mark.parametrize("fused", [False, True])
