@@ -182,6 +182,22 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
  * top.  Errors: BADARG (nothing bound, null tokens). */
 int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream);
 
+/* pre3_advance for callers that cannot allocate device memory at all: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same results as pre3_advance, but on the
+ * buffers passed in (nothing needs to be bound, so pre3_bind_state, which allocates the per-batch
+ * workspaces, is never needed), and the spill area of the walks' private stacks is a fixed array
+ * of 2^20 int32 (4 MiB) inside the library's own device code instead of an allocation.  The call
+ * allocates nothing on the device and frees nothing; it only enqueues kernels on `stream`.
+ * tokens [batch], states [batch], stacks, err [batch]: device, as for pre3_bind_state / pre3_advance.
+ * Limit: batch * max(0, pre3_walk_depth_bound(h) - 16) <= 2^20, else PRE3_E_LIMIT (text in
+ * pre3_last_error) and nothing is enqueued.  Every call on one GPU, from any handle or stream, uses
+ * that GPU's one array: calls that overlap in time on one GPU race and must be ordered by the
+ * caller (one stream, or events).  The array keeps the last call's contents; a walk writes each
+ * spilled entry before it reads it, so nothing has to be cleared between calls.
+ * Errors: BADARG (null pointer, cap > stack_cap, batch < 0), LIMIT, HIP. */
+int pre3_advance_static(pre3_handle *h, const int32_t *tokens, int32_t *states, pre3_stacks stacks, int32_t *err,
+                        pre3_stream stream);
+
 #define PRE3_ADVANCE_RESTART_ON_EOS 1  /* slot reuse: a sequence that takes the EOS token (where allowed) */
                                       /* goes back to its initial state (len = 1) instead of DONE         */
 

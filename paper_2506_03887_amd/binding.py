@@ -28,7 +28,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
-    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count",
+    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_advance_static",
 ]
 
 
@@ -79,6 +79,7 @@ def load():
     lib.pre3_fill_apply_mask.argtypes = [vp, vp, _Stacks, vp, vp, c.c_int64, vp]
     lib.pre3_advance.argtypes = [vp, vp, vp]
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
+    lib.pre3_advance_static.argtypes = [vp, vp, vp, _Stacks, vp, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
     lib.pre3_apply_mask_topk.argtypes = [vp, vp, c.c_int64, vp, i32, vp, vp, vp]
     lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
@@ -287,6 +288,12 @@ class Pre3:
     def advance(self, tokens, stream=None):
         assert tokens.is_contiguous()
         self._check(self._lib.pre3_advance(self._h, _dev(tokens, "i32"), _stream_ptr(stream)))
+
+    def advance_static(self, tokens, states, data, length, err, stream=None):
+        """pre3_advance on the buffers passed in, with the library's static spill area (no allocation)."""
+        assert tokens.is_contiguous() and tokens.numel() == data.shape[0] == states.numel() == err.numel()
+        self._check(self._lib.pre3_advance_static(self._h, _dev(tokens, "i32"), _dev(states, "i32"),
+                                                  self._stacks(data, length), _dev(err, "i32"), _stream_ptr(stream)))
 
     def advance_fill_mask(self, tokens, bitmask, restart_on_eos=False, stream=None):
         assert tokens.is_contiguous() and bitmask.is_contiguous() and bitmask.shape[1] == self.words

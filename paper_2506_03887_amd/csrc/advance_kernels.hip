@@ -2,8 +2,16 @@
 // own stack, alone or followed by the next step's mask row in the same launch.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "launch.hpp"
 #include "row_plan.hpp"
+
+// Spill area of the private stacks for pre3_advance_static, the entry point that allocates
+// nothing: device memory that belongs to the loaded library itself (every GPU the library runs
+// on holds its own copy until the process ends).  Host code never passes this name to a kernel:
+// the device address is taken once per device with hipGetSymbolAddress (static_advance_scratch).
+static __device__ __align__(256) int32_t pre3_static_scratch[pre3::kStaticScratchEntries];
 
 namespace pre3 {
 
@@ -510,6 +518,26 @@ __global__ __launch_bounds__(256) void compact_stacks_kernel(const int32_t *__re
 }
 
 }  // namespace
+
+hipError_t static_advance_scratch(int32_t **out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static int32_t *address[kMaxDevices] = {};
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[device]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(pre3_static_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        address[device] = static_cast<int32_t *>(p);
+    }
+    *out = address[device];
+    return hipSuccess;
+}
 
 size_t advance_scratch_entries(int batch, int max_depth) {
     const int deep = max_depth > kLdsDepth ? max_depth - kLdsDepth : 0;

@@ -233,6 +233,10 @@ int upload_tables(pre3_handle *h) {
     if ((e = hipGetDevice(&device)) != hipSuccess) return hip_fail(h, e, "hipGetDevice");
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return hip_fail(h, e, "hipGetDeviceProperties");
     h->n_compute_units = prop.multiProcessorCount;
+    {   // the spill area of pre3_advance_static: its address on this device is looked up here, once
+        int32_t *unused = nullptr;
+        if ((e = static_advance_scratch(&unused)) != hipSuccess) return hip_fail(h, e, "address of the static scratch");
+    }
     h->grid_blocks = walk_grid_blocks(prop.multiProcessorCount);
     void *p = nullptr;
     if ((e = device_alloc(h, walk_spill_entries(h->grid_blocks, h->max_depth) * sizeof(int32_t), &p, false)) != hipSuccess)
@@ -275,11 +279,12 @@ bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 
 // After a call that changed the bound stacks: take complete traversals of reduction cycles out
 // again (only with PRE3_FLAG_COMPACT_CYCLES and a grammar that has such cycles).
-hipError_t compact_bound_stacks(pre3_handle *h, hipStream_t s) {
+hipError_t compact_stacks(pre3_handle *h, const pre3_stacks &st, hipStream_t s) {
     if (!h->compact || h->T.n_cycles == 0) return hipSuccess;
     return launch_compact_stacks(h->cycle_head, h->cycle_pool, (int)h->T.cycle_pool.size(), h->T.n_states,
-                                 h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap, h->b_stacks.batch, s);
+                                 st.data, st.len, st.cap, st.batch, s);
 }
+hipError_t compact_bound_stacks(pre3_handle *h, hipStream_t s) { return compact_stacks(h, h->b_stacks, s); }
 
 // (grammar, local state) of a global state id
 bool locate(const pre3_handle *h, int state, int *g, int *local) {
@@ -484,6 +489,29 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
                                   fused ? h->cycle_pool : nullptr, static_cast<hipStream_t>(stream));
     if (e == hipSuccess && !fused) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance");
+}
+
+int pre3_advance_static(pre3_handle *h, const int32_t *tokens, int32_t *states, pre3_stacks stacks, int32_t *err,
+                        pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (stacks.batch == 0) return PRE3_OK;
+    if (!tokens || !states || !err || !stacks.data || !stacks.len || stacks.batch < 0 || stacks.cap < 1 ||
+        stacks.cap > h->stack_cap)
+        return fail(h, PRE3_E_BADARG, "advance_static: null buffer, negative batch or cap outside 1..stack_cap");
+    const size_t need = advance_scratch_entries(stacks.batch, h->max_depth);
+    if (need > kStaticScratchEntries)
+        return fail(h, PRE3_E_LIMIT, "advance_static: batch " + std::to_string(stacks.batch) + " x " +
+                                         std::to_string(need / (size_t)stacks.batch) + " spill entries per sequence exceeds the static scratch of " +
+                                         std::to_string(kStaticScratchEntries) + " entries: use pre3_bind_state + pre3_advance");
+    int32_t *scratch = nullptr;
+    hipError_t e = static_advance_scratch(&scratch);
+    if (e != hipSuccess) return hip_fail(h, e, "advance_static: address of the static scratch");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool fused = h->compact && h->T.n_cycles > 0 && advance_fits_compact(stacks.cap);
+    e = launch_advance(h->dev, tokens, states, stacks.data, stacks.len, stacks.cap, stacks.batch, err, scratch, 0,
+                       fused ? h->cycle_head : nullptr, fused ? h->cycle_pool : nullptr, s);
+    if (e == hipSuccess && !fused) e = compact_stacks(h, stacks, s);
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_static");
 }
 
 int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,

@@ -32,6 +32,11 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
                           int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
                           const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream);
 bool advance_fits_compact(int cap);                     // four staged stacks within the kernel's LDS
+// The library's own spill area (a device array of kStaticScratchEntries int32 that is part of the
+// loaded code object, 4 MiB per GPU): its address on the current device.  The first call on a
+// device looks the address up; no call allocates.
+constexpr size_t kStaticScratchEntries = (size_t)1 << 20;
+hipError_t static_advance_scratch(int32_t **out);
 hipError_t launch_masked_argmax(const uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                                 int n_compute_units, unsigned long long *workspace, int32_t *out, hipStream_t stream);
 size_t masked_argmax_workspace_bytes(int batch, int vocab, int n_compute_units);   // per-segment partial results
