@@ -139,7 +139,14 @@ int32_t pre3_initial_state(const pre3_handle *h, int32_t grammar_idx);
 
 /* Binds the per-sequence buffers that pre3_advance mutates (all device memory, caller-owned,
  * must outlive the binding): states [batch] (top state of each stack, or PRE3_STATE_DONE),
- * the stacks, and err [batch].  Rebinding replaces the previous binding. */
+ * the stacks, and err [batch].  Rebinding replaces the previous binding.
+ * This is the call that allocates the per-batch workspaces (private-stack spill areas, partial
+ * results of the arg max and the top-k): one allocation of each kind per handle, sized for the
+ * largest batch bound so far.  Binding a batch that needs no more reuses them; binding a larger
+ * one frees the superseded workspace (hipFree: waits for the device to go idle) and allocates the
+ * larger one, so a server that resizes its batch does not accumulate device memory.  Work that was
+ * recorded into a HIP graph before such a growing rebind points at the freed workspace and must be
+ * recorded again.  Errors: BADARG, HIP (allocation failed). */
 int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t *err);
 
 /* Token mask of one decode step (Sec. 1: every token whose bytes leave the language of

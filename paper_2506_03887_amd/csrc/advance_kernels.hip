@@ -230,6 +230,11 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
 // cycles are taken out of it (fold_cycles) and only then is it written back and looked up, so the call
 // leaves compacted stacks and the mask of exactly those stacks.
 constexpr int kAfBlock = 512;
+// LDS the kernel declares statically (stack windows, token bytes, private stacks, the row plan),
+// rounded up: what is left of the 64 KB for the dynamic part (mask row, staged stack)
+constexpr size_t kAfStaticLdsBytes =
+    ((sizeof(int32_t) * (2 * kWindow + 64 + kLdsDepth + kLdsDepth * 64) + sizeof(RowPlan)) + 1023) & ~(size_t)1023;
+constexpr size_t kAfDynamicLdsMax = 65536 - kAfStaticLdsBytes;
 template <bool kCompact>
 __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
@@ -250,9 +255,9 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         // The waves that wait for the walk pull the small tables it reads into this XCD's L2 (a
         // streaming kernel that ran in between has evicted them): one 128-byte line per lane,
         // the lines dealt out over the blocks of the XCD (blocks go round-robin to the 8 XCDs).
-        const int per_xcd = (gridDim.x + 7) >> 3, idle = kAfBlock - 64;
+        const int64_t per_xcd = (gridDim.x + 7) >> 3, idle = kAfBlock - 64;
         int acc = 0;
-        for (int off = ((blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
+        for (int64_t off = ((int64_t)(blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
             acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
         if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
     }
@@ -557,11 +562,12 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
     const size_t row_bytes = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
     if (cycle_head) {                                  // cycle-aware stacks: the new stack is staged in LDS too
         const size_t lds = row_bytes + (size_t)cap * sizeof(int32_t);
-        if (cap > kCompactMaxLen || lds > 65536) return hipErrorInvalidValue;
+        if (cap > kCompactMaxLen || lds > kAfDynamicLdsMax) return hipErrorInvalidValue;
         hipLaunchKernelGGL(advance_fill_kernel<true>, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data,
                            len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
                            cycle_head, cycle_pool);
     } else {
+        if (row_bytes > kAfDynamicLdsMax) return hipErrorInvalidValue;
         hipLaunchKernelGGL(advance_fill_kernel<false>, dim3(batch), dim3(kAfBlock), row_bytes, stream, T, E, tokens, states,
                            data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
                            nullptr, nullptr);
@@ -570,7 +576,8 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
 }
 
 bool advance_fill_fits_compact(int n_words, int cap) {
-    return cap <= kCompactMaxLen && (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t) + (size_t)cap * sizeof(int32_t) <= 65536;
+    return cap <= kCompactMaxLen &&
+           (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t) + (size_t)cap * sizeof(int32_t) <= kAfDynamicLdsMax;
 }
 
 bool advance_fits_compact(int cap) {

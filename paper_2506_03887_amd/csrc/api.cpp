@@ -44,17 +44,16 @@ struct pre3_handle {
     // binding used by pre3_advance
     int32_t *b_states = nullptr, *b_err = nullptr;
     pre3_stacks b_stacks{};
-    int32_t *adv_scratch = nullptr;
-    int32_t *af_walk_spill = nullptr;
+    // per-batch workspaces (pre3_bind_state): device allocations of their own, outside the arena
+    struct Workspace { void *p = nullptr; size_t bytes = 0; };
+    Workspace ws_adv, ws_argmax, ws_topk, ws_af_spill;
+    int32_t *adv_scratch = nullptr;              // private-stack spill of the advance
+    int32_t *af_walk_spill = nullptr;            // ... of per-lane walks beside an advance
     unsigned long long *argmax_best = nullptr;   // per-segment partial results of pre3_apply_mask_argmax
-    size_t argmax_bytes = 0;
     unsigned long long *topk_cand = nullptr;     // per-segment candidates of pre3_apply_mask_topk
-    size_t topk_bytes = 0;
     bool topk_ready = false;
     int n_compute_units = 0;
-    size_t af_walk_spill_entries = 0;
     bool bound_empty = false;
-    size_t adv_scratch_entries = 0;
     // stack compaction over reduction cycles (PRE3_FLAG_COMPACT_CYCLES)
     bool compact = false;
     const int32_t *cycle_head = nullptr, *cycle_pool = nullptr;
@@ -112,6 +111,20 @@ hipError_t device_alloc(pre3_handle *h, size_t bytes, void **out, bool zero) {
     if (e != hipSuccess) return e;
     if (zero) e = hipMemset(*out, 0, bytes ? bytes : 16);
     return e;
+}
+
+// Makes `w` hold at least `need` bytes: kept if large enough, else freed and allocated anew, so a
+// handle holds one workspace of each kind, sized for the largest batch bound so far.
+hipError_t grow_workspace(pre3_handle::Workspace &w, size_t need, void **out) {
+    if (need > w.bytes || !w.p) {
+        if (w.p) { (void)hipFree(w.p); w.p = nullptr; w.bytes = 0; }
+        const size_t bytes = need < 256 ? 256 : need;
+        hipError_t e = hipMalloc(&w.p, bytes);
+        if (e != hipSuccess) { w.p = nullptr; return e; }
+        w.bytes = bytes;
+    }
+    *out = w.p;
+    return hipSuccess;
 }
 
 constexpr ptrdiff_t kHotBytesMax = 2 << 20;   // half of one XCD's L2
@@ -367,6 +380,8 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
 int pre3_free(pre3_handle *h) {
     if (!h) return PRE3_OK;
     for (void *p : h->allocations) (void)hipFree(p);
+    for (pre3_handle::Workspace *w : {&h->ws_adv, &h->ws_argmax, &h->ws_topk, &h->ws_af_spill})
+        if (w->p) (void)hipFree(w->p);
     delete h;
     return PRE3_OK;
 }
@@ -388,43 +403,28 @@ int pre3_bind_state(pre3_handle *h, int32_t *states, pre3_stacks stacks, int32_t
     if (!states || !err || !stacks.data || !stacks.len || stacks.batch < 0 || stacks.cap < 1 ||
         stacks.cap > h->stack_cap)
         return fail(h, PRE3_E_BADARG, "bind_state: null buffer, negative batch or cap outside 1..stack_cap");
-    size_t need = advance_scratch_entries(stacks.batch, h->max_depth);
-    if (need > h->adv_scratch_entries) {
-        void *p = nullptr;
-        hipError_t e = device_alloc(h, need * sizeof(int32_t), &p, false);
-        if (e != hipSuccess) return hip_fail(h, e, "allocate advance scratch");
-        h->adv_scratch = static_cast<int32_t *>(p);
-        h->adv_scratch_entries = need;
-    }
-    const size_t need_arg = masked_argmax_workspace_bytes(stacks.batch, h->V.n_tokens, h->n_compute_units);
-    if (need_arg > h->argmax_bytes) {
-        void *p = nullptr;
-        hipError_t e = device_alloc(h, need_arg, &p, false);
-        if (e != hipSuccess) return hip_fail(h, e, "allocate argmax workspace");
-        h->argmax_best = static_cast<unsigned long long *>(p);
-        h->argmax_bytes = need_arg;
-    }
+    // per-batch workspaces: each is an allocation of its own that grows with the largest batch bound
+    // so far; a superseded one is freed (hipFree waits until the device no longer uses it)
+    hipError_t e;
+    void *p = nullptr;
+    if ((e = grow_workspace(h->ws_adv, advance_scratch_entries(stacks.batch, h->max_depth) * sizeof(int32_t), &p)) != hipSuccess)
+        return hip_fail(h, e, "allocate advance scratch");
+    h->adv_scratch = static_cast<int32_t *>(p);
+    if ((e = grow_workspace(h->ws_argmax, masked_argmax_workspace_bytes(stacks.batch, h->V.n_tokens, h->n_compute_units), &p)) != hipSuccess)
+        return hip_fail(h, e, "allocate argmax workspace");
+    h->argmax_best = static_cast<unsigned long long *>(p);
     // the top-k candidates: batch x segments x 64 words; a batch so large that this passes 1 GiB goes
     // without (pre3_apply_mask_topk then reports PRE3_E_LIMIT)
     const size_t need_topk = masked_topk_workspace_bytes(stacks.batch, h->V.n_tokens);
     h->topk_ready = need_topk <= ((size_t)1 << 30);
-    if (h->topk_ready && need_topk > h->topk_bytes) {
-        void *p = nullptr;
-        hipError_t e = device_alloc(h, need_topk, &p, false);
-        if (e != hipSuccess) return hip_fail(h, e, "allocate top-k workspace");
+    if (h->topk_ready) {
+        if ((e = grow_workspace(h->ws_topk, need_topk, &p)) != hipSuccess) return hip_fail(h, e, "allocate top-k workspace");
         h->topk_cand = static_cast<unsigned long long *>(p);
-        h->topk_bytes = need_topk;
     }
-    {   // private stacks of per-lane walks beside an advance (leftover tokens, jump-forward trials)
-        size_t need2 = advance_fill_walk_spill_entries(stacks.batch, h->max_depth);
-        if (need2 > h->af_walk_spill_entries) {
-            void *p = nullptr;
-            hipError_t e = device_alloc(h, need2 * sizeof(int32_t), &p, false);
-            if (e != hipSuccess) return hip_fail(h, e, "allocate advance+fill spill area");
-            h->af_walk_spill = static_cast<int32_t *>(p);
-            h->af_walk_spill_entries = need2;
-        }
-    }
+    // private stacks of per-lane walks beside an advance (leftover tokens, jump-forward trials)
+    if ((e = grow_workspace(h->ws_af_spill, advance_fill_walk_spill_entries(stacks.batch, h->max_depth) * sizeof(int32_t), &p)) != hipSuccess)
+        return hip_fail(h, e, "allocate advance+fill spill area");
+    h->af_walk_spill = static_cast<int32_t *>(p);
     h->b_states = states;
     h->b_stacks = stacks;
     h->b_err = err;

@@ -191,3 +191,38 @@ digit ::= [0-9]
             len_d[idx] = 1
             states_d[idx] = int(drv.data[fin[0], 0])
     assert forced > 300, forced
+
+
+def test_row_plus_staged_stack_beyond_the_lds_takes_three_launches():
+    """400,000 tokens (a mask row of 50,000 bytes) and a capacity of 3,000 entries (12,000 bytes): together
+    with the kernel's own LDS they pass 64 KB, so pre3_advance_fill_mask must fall back to advance,
+    compaction and mask as separate launches -- and leave the same stacks and masks."""
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    v = bpe_like_vocab(400000, 12, BASE_SEED + 84)
+    ids = {tok: t for t, tok in reversed(list(enumerate(v.tokens)))}
+    cap = 3000
+    streams = [list(b'[[1,2,[3,4,5],"ab\\ncd",{"k":[1,2,3]}],7,8]'), list(b'{"a":"xyzw","b":[[],[],[[]]],"c":12345}'),
+               list(b'[1,2,3,4,5,6,7,8,9,10,11,12,13]')]
+    B = len(streams)
+    o = Oracle([G.JSON_RIGHT_RECURSIVE], compact_cycles=True)
+    lib = Pre3([G.JSON_RIGHT_RECURSIVE], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=cap,
+               compact_cycles=True)
+    assert lib.token_edge_stats()["built"] == 1 and v.words * 4 + cap * 4 > 65536 - 8192
+    s0 = lib.initial_state(0)
+    states_d, data_d, len_d, err_d = _bound(lib, B, cap, s0)
+    mask_d = torch.zeros((B, v.words), dtype=torch.int32, device=dev)
+    data_h = np.zeros((B, cap), dtype=np.int32)
+    data_h[:, 0] = s0
+    len_h = np.ones(B, dtype=np.int32)
+    states_h = np.full(B, s0, dtype=np.int32)
+    for s in range(max(len(st) for st in streams)):
+        tok = np.array([ids[bytes([st[s]])] if s < len(st) else -1 for st in streams], dtype=np.int32)
+        lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d)
+        assert not o.advance_batch(states_h, data_h, len_h, tok, v).any(), s
+        assert (err_d.cpu().numpy() == 0).all(), s
+        assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), s
+        live = np.arange(cap)[None, :] < len_h[:, None]
+        assert (data_d.cpu().numpy()[live] == data_h[live]).all(), s
+        if s % 6 == 0:
+            assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(states_h, data_h, len_h, v)).all(), s

@@ -539,3 +539,44 @@ def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
     lib.advance_fill_mask(torch.from_numpy(picks).to(dev), m)
     assert (err.cpu().numpy() == e_h).all() and (st.cpu().numpy() == states).all() and (ln.cpu().numpy() == length).all()
     assert (m.cpu().numpy().view(np.uint32) == o.fill_mask(states, data, length, v)).all()
+
+
+def test_rebinding_other_batch_sizes_does_not_accumulate_device_memory():
+    """A server that resizes its batch rebinds again and again: the per-batch workspaces are reused or
+    replaced, never abandoned (free device memory stays level), and every binding advances correctly."""
+    torch, dev = _torch()
+    o = Oracle(G.JSON)
+    v = bpe_like_vocab(3000, 16, BASE_SEED + 90)
+    lib = _lib(G.JSON, v, stack_cap=64)
+    s0 = lib.initial_state(0)
+    tok = v.tokens.index(b"[")
+    rc, want = o.advance([s0], b"[")
+    assert rc == 0
+
+    def bind_and_advance(B):
+        data = torch.zeros((B, 64), dtype=torch.int32, device=dev)
+        data[:, 0] = s0
+        length = torch.ones(B, dtype=torch.int32, device=dev)
+        states = torch.full((B,), s0, dtype=torch.int32, device=dev)
+        err = torch.full((B,), -3, dtype=torch.int32, device=dev)
+        lib.bind_state(states, data, length, err)
+        lib.advance(torch.full((B,), tok, dtype=torch.int32, device=dev))
+        out = torch.empty(B, dtype=torch.int32, device=dev)
+        mask = torch.empty((B, v.words), dtype=torch.int32, device=dev)
+        lib.fill_mask(states, data, length, mask)
+        lib.apply_mask_argmax(torch.zeros((B, v.n_tokens), dtype=torch.bfloat16, device=dev), mask, out)
+        torch.cuda.synchronize()
+        assert int(err.abs().sum().item()) == 0 and int((length != len(want)).sum().item()) == 0
+        assert (data[:, : len(want)].cpu().numpy() == np.array(want, dtype=np.int32)[None, :]).all()
+
+    sizes = [8, 4096, 64, 20000, 1, 512]
+    for B in sizes:                       # every size once: the workspaces reach their largest extent
+        bind_and_advance(B)
+    torch.cuda.empty_cache()
+    free_before = torch.cuda.mem_get_info()[0]
+    for _ in range(6):
+        for B in sizes:
+            bind_and_advance(B)
+    torch.cuda.empty_cache()
+    free_after = torch.cuda.mem_get_info()[0]
+    assert free_before - free_after < (8 << 20), (free_before, free_after)
