@@ -270,10 +270,10 @@ int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int3
 
 /* Reduction cycles (Sec. 3.2.3: cycles with the reduction problem; Alg. 1 step 1).  A cycle is
  * registered for a right-recursive production  A -> X1..Xn A  (1 <= n <= 64) and states
- * v1 = GOTO(vn, X1), v2 = GOTO(v1, X2), .., vn = GOTO(v(n-1), Xn) when
- *   - every kernel item of v1 is an item of A with the dot after its first symbol,
- *   - the kernel of r = GOTO(vn, A) holds only the finished item  A -> X1..Xn A . , and
- *   - r reduces on every lookahead that a kernel item of v1 carries.
+ * v1 = GOTO(vn, X1), v2 = GOTO(v1, X2), .., vn = GOTO(v(n-1), Xn) when every kernel item of v1 is
+ * an item of A with the dot after its first symbol.  (In a conflict-free canonical automaton the
+ * kernel of r = GOTO(vn, A) then holds only the finished item  A -> X1..Xn A .  and r reduces on
+ * every lookahead that a kernel item of v1 carries.)
  * Then a stack  .. v1 .. vn v1 rest  accepts exactly the continuations of  .. v1 rest : whatever
  * looks below the upper v1 goes to r, pops the traversal and repeats one traversal lower before
  * the next byte is consumed.  With PRE3_FLAG_COMPACT_CYCLES the stacks are kept in the normal

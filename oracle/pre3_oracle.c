@@ -546,21 +546,21 @@ static int set_action(grammar_t *G, int s, int a, int kind, int arg, char *err, 
  * problem" that "corresponds to recursive reduction of a nonterminal A".  The reading taken
  * here (the paper does not define the terms): a production  A -> X1 .. Xn A  and item sets
  * v1 .. vn with  GOTO(vn, X1) = v1, GOTO(v1, X2) = v2, .., GOTO(v(n-1), Xn) = vn,  such that
- *   (a) every kernel item (dot not at the left end) of v1 is [A -> Y . delta, a]: an item of A
- *       with the dot after one symbol;
- *   (b) every kernel item of r = GOTO(vn, A) is [A -> X1 .. Xn A ., a];
- *   (c) for every kernel item [.., a] of v1 the item [A -> X1 .. Xn A ., a] is in r.
+ * every kernel item (dot not at the left end) of v1 is [A -> Y . delta, a]: an item of A with
+ * the dot after one symbol.
+ * In a conflict-free canonical LR(1) automaton two more facts follow, with r = GOTO(vn, A):
+ *   (i)  every kernel item of r is the finished [A -> X1 .. Xn A ., a];
+ *   (ii) for every kernel item [.., a] of v1 the item [A -> X1 .. Xn A ., a] is in r.
+ * (The kernel of v1 stems from closure items [A -> . X1 delta, a] of vn; the closure gives all
+ * productions of A the same lookaheads L, the union of FIRST(beta b) over the items
+ * [C -> alpha . A beta, b] of vn; the item of the cycle's own production carries L from v1 along
+ * the path to vn, which gives (ii); an item of vn with A after the dot other than that one
+ * would put FIRST(beta b), a part of L, on a second action of r: a conflict, hence (i).)
  * Why a stack  .. v1 .. vn v1 rest  then accepts the same continuations as  .. v1 rest : the
- * parser looks below the upper v1 only by finishing a kernel item of it, which by (a) pops
- * down to the entry under v1 and goes to A from there: from vn that is r, where by (b) and
- * (c) the same lookahead reduces A -> X1..Xn A, pops r and the traversal v1..vn and goes to A
- * again from the entry below -- the very configuration the shorter stack reached directly. */
-static int set_has(const itemset_t *S, int prod, int dot, int la) {
-    for (int k = 0; k < S->n; k++)
-        if (S->it[k].prod == prod && S->it[k].dot == dot && S->it[k].la == la) return 1;
-    return 0;
-}
-
+ * parser looks below the upper v1 only by finishing a kernel item of it, which pops down to the
+ * entry under v1 and goes to A from there: from vn that is r, where by (i) and (ii) the same
+ * lookahead reduces A -> X1..Xn A, pops r and the traversal v1..vn and goes to A again from the
+ * entry below -- the very configuration the shorter stack reached directly. */
 static int cycle_cmp(const int *a, int na, const int *b, int nb) {
     if (a[0] != b[0]) return a[0] < b[0] ? -1 : 1;
     if (na != nb) return na < nb ? -1 : 1;
@@ -590,18 +590,13 @@ static void find_cycles(grammar_t *G, const itemset_t *states, int n_states, con
             for (int i = 0; i < n && v >= 0; i++) { v = delta[(size_t)v * n_sym + P->rhs[i]]; path[i] = v; }
             if (v != vn) continue;
             const itemset_t *V1 = &states[path[0]];
-            int r = delta[(size_t)vn * n_sym + NT_BASE + P->lhs];
-            if (r < 0) continue;
-            const itemset_t *R = &states[r];
+            if (delta[(size_t)vn * n_sym + NT_BASE + P->lhs] < 0) continue;
             int ok = 1;
             for (int k = 0; k < V1->n && ok; k++) {
                 item_t x = V1->it[k];
                 if (x.dot == 0) continue;                              /* closure item */
-                ok = G->prod[x.prod].lhs == P->lhs && x.dot == 1       /* (a) */
-                     && set_has(R, p, n + 1, x.la);                    /* (c) */
+                ok = G->prod[x.prod].lhs == P->lhs && x.dot == 1;
             }
-            for (int k = 0; k < R->n && ok; k++)
-                if (R->it[k].dot > 0) ok = R->it[k].prod == p && R->it[k].dot == n + 1;   /* (b) */
             if (!ok) continue;
             /* insert in order, skipping a duplicate */
             int at = 0, dup = 0;
