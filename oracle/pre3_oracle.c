@@ -196,10 +196,11 @@ static int tokenize(const char *s, toklist_t *L, char *err, int errlen) {
             while (s[i] != '"') {
                 if (s[i] == 0 || s[i] == '\n') {
                     set_err(err, errlen, "line %d: unterminated string", line);
+                    free(tk.text);
                     return -1;
                 }
                 int b = read_escaped(s, &i);
-                if (b < 0) { set_err(err, errlen, "line %d: bad escape in string", line); return -1; }
+                if (b < 0) { set_err(err, errlen, "line %d: bad escape in string", line); free(tk.text); return -1; }
                 tk.text[tk.len++] = (char)b;
             }
             i++;
@@ -254,10 +255,8 @@ static int find_nt(const grammar_t *G, const char *name) {
     return -1;
 }
 
-static int parse_grammar(const char *text, grammar_t *G, char *err, int errlen) {
-    toklist_t L = {0, 0, 0};
-    if (tokenize(text, &L, err, errlen) != 0) return -1;
-
+/* The rules of a tokenised grammar text; `buf` has room for every symbol of the text. */
+static int parse_rules(toklist_t L, int *buf, grammar_t *G, char *err, int errlen) {
     /* pass 1: left-hand sides in order of first appearance */
     for (int k = 0; k + 1 < L.n; k++) {
         if (L.t[k].kind == TK_IDENT && L.t[k + 1].kind == TK_ASSIGN) {
@@ -278,7 +277,6 @@ static int parse_grammar(const char *text, grammar_t *G, char *err, int errlen) 
 
     /* pass 2: rules */
     int k = 0;
-    int *buf = (int *)malloc(sizeof(int) * (strlen(text) + 4));
     while (L.t[k].kind != TK_EOF) {
         if (L.t[k].kind == TK_NEWLINE) { k++; continue; }
         if (L.t[k].kind != TK_IDENT || L.t[k + 1].kind != TK_ASSIGN) {
@@ -344,10 +342,20 @@ static int parse_grammar(const char *text, grammar_t *G, char *err, int errlen) 
             return -1;
         }
     }
-    free(buf);
+    return 0;
+}
+
+static int parse_grammar(const char *text, grammar_t *G, char *err, int errlen) {
+    toklist_t L = {0, 0, 0};
+    int rc = tokenize(text, &L, err, errlen);
+    if (rc == 0) {
+        int *buf = (int *)malloc(sizeof(int) * (strlen(text) + 4));
+        rc = parse_rules(L, buf, G, err, errlen);
+        free(buf);
+    }
     for (int i = 0; i < L.n; i++) free(L.t[i].text);
     free(L.t);
-    return 0;
+    return rc;
 }
 
 /* -------------------------------------------- useless symbols (must be none) */
