@@ -558,6 +558,47 @@ def main(argv=None):
                 "vocab_bytes_times_batch_per_s": float(B) * float(v.offsets[-1]) / (t * 1e-6),
                 "note": "fill_mask_walk_kernel; a walk stops at its first rejected byte, so the byte rate is an upper bound on byte steps"}
 
+    def row_latency_leg(max_rows=256, launches=16):
+        """pre3_fill_mask on ONE sequence at a time (the stacks of the first timed step): per row, `launches`
+        calls in one HIP graph between two events.  Shows what the rows that leave tokens to the run-time
+        walk cost next to the rows that are a pure look-up (the launch itself is part of every figure)."""
+        ls, da = recorded_stacks()[0]
+        l_h, s_h = ls.cpu().numpy()
+        d_h = da.cpu().numpy()
+        rows = list(range(min(B, max_rows)))
+        us, walked = [], []
+        for b in rows:
+            n_walk = 0
+            if not args.no_token_edges and s_h[b] >= 0:
+                ok, _, walk = lib.debug_resolve_row(d_h[b, : l_h[b]].copy())
+                n_walk = len(walk) if ok else V
+            walked.append(n_walk)
+            st1, da1, ln1, m1 = ls[1][b:b + 1], da[b:b + 1], ls[0][b:b + 1], mask_d[b:b + 1]
+            lib.fill_mask(st1, da1, ln1, m1)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(launches):
+                    lib.fill_mask(st1, da1, ln1, m1)
+            best = float("inf")
+            for _ in range(2):
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            us.append(best * 1e3 / launches)
+        us, walked = np.array(us), np.array(walked)
+        r = {"rows": len(rows), "us_per_row_launch": stat(us), "max": float(us.max()),
+             "rows_with_tokens_left_to_the_walk": int((walked > 0).sum()), "most_tokens_walked_in_a_row": int(walked.max()),
+             "timing": f"per row: {launches} one-row pre3_fill_mask launches in one HIP graph between two events, divided by {launches}"}
+        if (walked > 0).any() and (walked == 0).any():
+            r["us_rows_pure_lookup_mean"] = float(us[walked == 0].mean())
+            r["us_rows_with_walk_mean"] = float(us[walked > 0].mean())
+        return r
+
     # ---- greedy decoding: the sampler fused behind the mask (pre3_apply_mask_argmax reads the logits once
     #      and writes nothing back), tokens fed straight to pre3_advance_fill_mask
     def fresh_logits():
@@ -650,7 +691,8 @@ def main(argv=None):
             out["greedy"] = guarded(greedy_leg)
             out["topk"] = guarded(topk_leg)
             if not args.eager:
-                out["jump_forward"] = guarded(jump_forward_leg)
+                out["fill_mask_row_latency"] = guarded(row_latency_leg)
+            out["jump_forward"] = guarded(jump_forward_leg)
                 if not args.no_token_edges:
                     out["fill_mask_byte_by_byte"] = guarded(byte_by_byte_leg)
         out["token_edges"] = guarded(lib.token_edge_stats)
