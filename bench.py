@@ -692,7 +692,7 @@ def main(argv=None):
             out["topk"] = guarded(topk_leg)
             if not args.eager:
                 out["fill_mask_row_latency"] = guarded(row_latency_leg)
-            out["jump_forward"] = guarded(jump_forward_leg)
+                out["jump_forward"] = guarded(jump_forward_leg)
                 if not args.no_token_edges:
                     out["fill_mask_byte_by_byte"] = guarded(byte_by_byte_leg)
         out["token_edges"] = guarded(lib.token_edge_stats)
