@@ -115,6 +115,9 @@ def parse_args(argv=None):
                     help="only run 20 plain device copies of MIB mebibytes (known traffic, to scale HBM counters)")
     ap.add_argument("--no-token-edges", action="store_true",
                     help="compile without token-level edges: fill_mask walks every (sequence, token) pair")
+    ap.add_argument("--max-condition-depth", type=int, default=0,
+                    help="limit the token-level conditions to this many stack entries (0 = the library's default of 48): "
+                         "a probe that leaves tokens to the run-time walk")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
@@ -175,7 +178,7 @@ def main(argv=None):
     dev = torch.device("cuda:0")
     t_compile = time.perf_counter()
     lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
-               token_edges=not args.no_token_edges, compact_cycles=compact)
+               token_edges=not args.no_token_edges, compact_cycles=compact, max_condition_depth=args.max_condition_depth)
     t_compile = time.perf_counter() - t_compile
     data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
     states_h = data_h[np.arange(B), len_h - 1].copy()
@@ -364,7 +367,8 @@ def main(argv=None):
         "dtype": "i32 (integer and bit work: i32 states, u32 bitmask words; the bf16 logits are selected, not computed on)",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "vocab": V, "grammar": GRAMMAR_LABEL.get(cfg.idx, cfg.name) + ", canonical LR(1)",
-                   "stack_cap": cap, "sequences_restarted_in_timed_steps": int(traj.reset[Wm:total].sum()),
+                   "stack_cap": cap, **({"max_condition_depth": args.max_condition_depth} if args.max_condition_depth else {}),
+                   "sequences_restarted_in_timed_steps": int(traj.reset[Wm:total].sum()),
                    "step": step_text[step_kind] + (", K eager steps" if args.eager else ", K steps in one HIP graph")},
     }
 
@@ -559,19 +563,28 @@ def main(argv=None):
                 "note": "fill_mask_walk_kernel; a walk stops at its first rejected byte, so the byte rate is an upper bound on byte steps"}
 
     def row_latency_leg(max_rows=256, launches=16):
-        """pre3_fill_mask on ONE sequence at a time (the stacks of the first timed step): per row, `launches`
-        calls in one HIP graph between two events.  Shows what the rows that leave tokens to the run-time
+        """pre3_fill_mask on ONE sequence at a time (the stacks of the first timed step, and rows of the first 32
+        steps whose look-up leaves tokens to the run-time walk): per row, `launches` calls in one HIP graph
+        between two events.  Shows what the rows that leave tokens to the run-time
         walk cost next to the rows that are a pure look-up (the launch itself is part of every figure)."""
-        ls, da = recorded_stacks()[0]
-        l_h, s_h = ls.cpu().numpy()
-        d_h = da.cpu().numpy()
-        rows = list(range(min(B, max_rows)))
+        snaps = recorded_stacks()
+        # every row of the first timed step, plus up to 128 rows of the other steps that leave tokens to the walk
+        todo = []
+        for si, (ls, da) in enumerate(snaps):
+            l_h, s_h = ls.cpu().numpy()
+            d_h = da.cpu().numpy()
+            for b in range(B):
+                n_walk = 0
+                if not args.no_token_edges and s_h[b] >= 0:
+                    ok, _, walk = lib.debug_resolve_row(d_h[b, : l_h[b]].copy())
+                    n_walk = len(walk) if ok else V
+                if (si == 0 and b < max_rows) or (si > 0 and n_walk > 0 and len(todo) < max_rows + 128):
+                    todo.append((si, b, n_walk))
+            if si >= 31:
+                break
         us, walked = [], []
-        for b in rows:
-            n_walk = 0
-            if not args.no_token_edges and s_h[b] >= 0:
-                ok, _, walk = lib.debug_resolve_row(d_h[b, : l_h[b]].copy())
-                n_walk = len(walk) if ok else V
+        for si, b, n_walk in todo:
+            ls, da = snaps[si]
             walked.append(n_walk)
             st1, da1, ln1, m1 = ls[1][b:b + 1], da[b:b + 1], ls[0][b:b + 1], mask_d[b:b + 1]
             lib.fill_mask(st1, da1, ln1, m1)
@@ -590,6 +603,7 @@ def main(argv=None):
                 torch.cuda.synchronize()
                 best = min(best, e0.elapsed_time(e1))
             us.append(best * 1e3 / launches)
+        rows = todo
         us, walked = np.array(us), np.array(walked)
         r = {"rows": len(rows), "us_per_row_launch": stat(us), "max": float(us.max()),
              "rows_with_tokens_left_to_the_walk": int((walked > 0).sum()), "most_tokens_walked_in_a_row": int(walked.max()),
