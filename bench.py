@@ -118,6 +118,8 @@ def parse_args(argv=None):
     ap.add_argument("--max-condition-depth", type=int, default=0,
                     help="limit the token-level conditions to this many stack entries (0 = the library's default of 48): "
                          "a probe that leaves tokens to the run-time walk")
+    ap.add_argument("--effect-min-len", type=int, default=0,
+                    help="shortest token that gets a stack-effect record (0 = the library's default; -1 = no records)")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
     ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
@@ -178,7 +180,8 @@ def main(argv=None):
     dev = torch.device("cuda:0")
     t_compile = time.perf_counter()
     lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
-               token_edges=not args.no_token_edges, compact_cycles=compact, max_condition_depth=args.max_condition_depth)
+               token_edges=not args.no_token_edges, compact_cycles=compact, max_condition_depth=args.max_condition_depth,
+               token_effects=args.effect_min_len >= 0, effect_min_len=max(0, args.effect_min_len))
     t_compile = time.perf_counter() - t_compile
     data_h, len_h = traj.init_data.copy(), traj.init_len.copy()
     states_h = data_h[np.arange(B), len_h - 1].copy()

@@ -62,6 +62,8 @@ typedef enum {
                                  /* edges: walks follow one reduction step at a time             */
 #define PRE3_FLAG_NO_TOKEN_EDGES 2 /* do not precompute token-level edges: pre3_fill_mask then     */
                                  /* walks every (sequence, token) pair byte by byte              */
+#define PRE3_FLAG_NO_TOKEN_EFFECTS 16 /* do not record the stack operations of the token-level edges:     */
+                                 /* pre3_advance_fill_mask then walks every sampled token byte by byte   */
 #define PRE3_FLAG_COMPACT_CYCLES 8 /* cycle-aware stacks (Sec. 3.2.3; Alg. 1 step 1): every call that */
                                  /* changes the bound stacks (pre3_advance, pre3_advance_fill_mask,  */
                                  /* pre3_jump_forward) afterwards takes complete traversals of       */
@@ -95,6 +97,8 @@ typedef struct {
                                  /* such row on its path (identical rows are stored once); below the     */
                                  /* threshold the node lists the ids and the kernel ORs them in.  Larger */
                                  /* values trade table size for work at run time                         */
+    int32_t effect_min_len;      /* 0 = default 5: tokens of at least this many bytes get a stack-effect     */
+                                 /* record (see pre3_token_effect_stats); shorter ones are always walked     */
 } pre3_options;
 
 /* Parse stacks of a batch, device memory, caller-owned.
@@ -319,6 +323,22 @@ int pre3_debug_fault_count(pre3_handle *h, int64_t *out);
  * [3] dense rows, [4] token ids in delta lists, [5] token ids in walk lists, [6] deepest stack
  * entry tested, [7] bytes of device memory they take. */
 int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]);
+/* Stack operations of the token-level edges (Sec. 3.1: an edge carries its accepted symbols, its
+ * stack-matching condition and its stack operations): for every token of at least 5 bytes that a
+ * node of a condition tree allows, what the token's walk does to any stack matching the node's
+ * condition (how many entries it replaces, the states it pushes, the highest the stack gets on
+ * the way).  pre3_advance_fill_mask applies such a token with one look-up instead of a walk; tokens
+ * without a record (short ones, records that found their two hash buckets full, grammars whose
+ * records would pass 12 Mi) are walked.  out[0] records, [1] records in the look-up table, [2] records
+ * left out of it, [3] bytes of device memory. */
+int pre3_token_effect_stats(const pre3_handle *h, int64_t out[4]);
+/* Host mirror of that look-up (tests and tools): stack[0..len) (host, global state ids, bottom
+ * first) and a token id.  On a hit writes the stack after the token to out[0..return value) and,
+ * if info is not NULL, k (entries from the top that the record covers), peak (the walk overflows a
+ * capacity cap iff len + peak >= cap) and the number of states pushed; returns the new length, 0 if
+ * no record covers (stack, token), or PRE3_E_BADARG (also when out_cap is too small). */
+int32_t pre3_debug_token_effect(const pre3_handle *h, const int32_t *stack, int32_t len, int32_t token, int32_t *out,
+                                int32_t out_cap, int32_t *info);
 /* Sizes of the merged reduction edges (Sec. 3.2.2; Alg. 1 step 3): out[0] built?, [1] condition
  * nodes, [2] deepest stack entry tested, [3] bytes of device memory. */
 int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]);

@@ -20,6 +20,7 @@ FLAG_HOST_ONLY = 1
 FLAG_NO_TOKEN_EDGES = 2
 FLAG_STEPWISE_REDUCTIONS = 4
 FLAG_COMPACT_CYCLES = 8
+FLAG_NO_TOKEN_EFFECTS = 16
 ADVANCE_RESTART_ON_EOS = 1
 STATE_DONE = -1
 
@@ -28,7 +29,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
-    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_advance_static",
+    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
 ]
 
 
@@ -45,7 +46,8 @@ class _Vocab(ctypes.Structure):
 
 class _Options(ctypes.Structure):
     _fields_ = [("max_token_len", ctypes.c_int32), ("stack_cap", ctypes.c_int32), ("flags", ctypes.c_int32),
-                ("max_condition_depth", ctypes.c_int32), ("row_threshold", ctypes.c_int32)]
+                ("max_condition_depth", ctypes.c_int32), ("row_threshold", ctypes.c_int32),
+                ("effect_min_len", ctypes.c_int32)]
 
 
 class _Stacks(ctypes.Structure):
@@ -95,6 +97,8 @@ def load():
     lib.pre3_goto_target.argtypes = [vp, i32, i32]
     lib.pre3_token_edge_stats.argtypes = [vp, vp]
     lib.pre3_symbol_edge_stats.argtypes = [vp, vp]
+    lib.pre3_token_effect_stats.argtypes = [vp, vp]
+    lib.pre3_debug_token_effect.argtypes = [vp, vp, i32, i32, vp, i32, vp]
     lib.pre3_debug_advance.argtypes = [vp, vp, vp, i32, vp, i32, i32]
     lib.pre3_debug_resolve_row.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp]
     for name in EXPORTS:
@@ -128,7 +132,8 @@ class Pre3:
     def __init__(self, grammars, vocab_bytes: np.ndarray, vocab_offsets: np.ndarray, eos_id: int,
                  max_token_len: int = 64, stack_cap: int = 1024, host_only: bool = False,
                  token_edges: bool = True, max_condition_depth: int = 0, merged_reductions: bool = True,
-                 row_threshold: int = 0, compact_cycles: bool = False):
+                 row_threshold: int = 0, compact_cycles: bool = False, token_effects: bool = True,
+                 effect_min_len: int = 0):
         lib = load()
         if isinstance(grammars, str):
             grammars = [grammars]
@@ -139,8 +144,8 @@ class Pre3:
         opt = _Options(max_token_len, stack_cap,
                        (FLAG_HOST_ONLY if host_only else 0) | (0 if token_edges else FLAG_NO_TOKEN_EDGES)
                        | (0 if merged_reductions else FLAG_STEPWISE_REDUCTIONS)
-                       | (FLAG_COMPACT_CYCLES if compact_cycles else 0),
-                       max_condition_depth, row_threshold)
+                       | (FLAG_COMPACT_CYCLES if compact_cycles else 0) | (0 if token_effects else FLAG_NO_TOKEN_EFFECTS),
+                       max_condition_depth, row_threshold, effect_min_len)
         h = ctypes.c_void_p()
         rc = lib.pre3_compile(texts, len(grammars), ctypes.byref(voc), ctypes.byref(opt), ctypes.byref(h))
         self._lib, self._h = lib, h
@@ -194,6 +199,21 @@ class Pre3:
         self._check(self._lib.pre3_token_edge_stats(self._h, out))
         keys = ["built", "roots", "nodes", "dense_rows", "delta_ids", "walk_ids", "max_known", "device_bytes"]
         return dict(zip(keys, list(out)))
+
+    def token_effect_stats(self):
+        out = (ctypes.c_int64 * 4)()
+        self._check(self._lib.pre3_token_effect_stats(self._h, out))
+        return dict(zip(["records", "stored", "dropped", "device_bytes"], list(out)))
+
+    def debug_token_effect(self, stack, token: int):
+        """Host mirror of the effect look-up: (new stack list, k, peak, n_push) or None if no record covers it."""
+        st = np.ascontiguousarray(stack, dtype=np.int32)
+        out = np.zeros(len(st) + 256, dtype=np.int32)
+        info = np.zeros(3, dtype=np.int32)
+        n = self._lib.pre3_debug_token_effect(self._h, st.ctypes.data, len(st), int(token), out.ctypes.data, len(out), info.ctypes.data)
+        if n < 0:
+            raise Pre3Error(n, "debug_token_effect")
+        return None if n == 0 else (out[:n].tolist(), int(info[0]), int(info[1]), int(info[2]))
 
     def symbol_edge_stats(self):
         out = (ctypes.c_int64 * 4)()

@@ -273,6 +273,14 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         const bool shape_ok = n >= 1 && n <= cap;
         const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
         StagedToken tok{0, 0};
+        // the root of the condition tree of the stack's top (states[b] names it) is fetched together
+        // with the stack window and the token's bytes: the effect look-up starts from it
+        int fx_root = -1;
+        DevConditionNode fx_nd{};
+        if (E.fx_slots && live && t != T.eos_id && (unsigned)st < (unsigned)T.n_states) {
+            fx_root = E.root_id[st];
+            fx_nd = E.root_nodes[st];
+        }
         s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
         if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
         __builtin_amdgcn_wave_barrier();
@@ -296,7 +304,34 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                     base = n;
                     d = 0;                               // the '$' walk never changes the stack
                 } else {
-                    const int rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
+                    // a longer token whose merged edge carries its stack operations is applied in one
+                    // step (look-up, truncate, push); every other token is walked byte by byte
+                    EffectHit fx{0, 0, 0, 0, 0, 0, 0};
+                    if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
+                        fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
+                                         [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                    int rc;
+                    if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
+                        if (n + fx.peak >= cap) {
+                            rc = kOverflow;
+                        } else {
+                            base = n - fx.k + 1;
+                            if (fx.inline_count > 0) {
+                                priv.set(0, fx.x0);
+                                top = fx.x0;
+                                if (fx.inline_count == 2) { priv.set(1, fx.x1); top = fx.x1; }
+                            } else {
+                                for (int i = 0; i < fx.np; ++i) {
+                                    top = table<true>(E.fx_pool, fx.x0 + i);
+                                    priv.set(i, top);
+                                }
+                            }
+                            d = fx.np;
+                            rc = kFed;
+                        }
+                    } else {
+                        rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
+                    }
                     if (rc != kFed) {
                         out_err = rc == kOverflow ? 2 : 1;
                         base = n;

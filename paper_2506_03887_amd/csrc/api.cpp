@@ -27,6 +27,7 @@ struct pre3_handle {
     EdgeTables T;
     VocabLayout V;
     TokenEdges E;
+    EffectTable X;                       // (condition node, token) -> stack effect, built from E
     SymbolEdges S;
     int max_depth = 0;
 
@@ -205,6 +206,7 @@ int upload_tables(pre3_handle *h) {
         if ((e = upload(h, h->E.child_state, &h->dev_edges.child_state)) != hipSuccess)
             return hip_fail(h, e, "upload child_state");
         if ((e = upload(h, nodes, &h->dev_edges.nodes)) != hipSuccess) return hip_fail(h, e, "upload nodes");
+        if ((e = upload(h, h->E.root_of_state, &h->dev_edges.root_id)) != hipSuccess) return hip_fail(h, e, "upload root_id");
     }
     {
         const ptrdiff_t span = h->arena - reinterpret_cast<const char *>(D.byte_info);
@@ -273,6 +275,17 @@ int upload_tables(pre3_handle *h) {
         PRE3_UPE(h->E.delta_ids, delta_ids);
         PRE3_UPE(h->E.walk_ids, walk_ids);
 #undef PRE3_UPE
+        X.fx_slots = nullptr; X.fx_pool = nullptr; X.fx_mask = 0; X.fx_min_len = 0;   // X = h->dev_edges
+        if (!h->X.slots.empty()) {
+            const int32_t *slots = nullptr;
+            if ((e = upload(h, h->X.slots, &slots)) != hipSuccess) return hip_fail(h, e, "upload effect slots");
+            std::vector<int32_t> pool = h->X.pool;
+            if (pool.empty()) pool.push_back(0);
+            if ((e = upload(h, pool, &X.fx_pool)) != hipSuccess) return hip_fail(h, e, "upload effect pool");
+            X.fx_slots = reinterpret_cast<const int4 *>(slots);
+            X.fx_mask = h->X.bucket_mask;
+            X.fx_min_len = h->E.effect_min_len;
+        }
         h->edge_blocks = edge_grid_blocks(prop.multiProcessorCount);
         if ((e = device_alloc(h, edge_spill_entries(h->edge_blocks, h->max_depth) * sizeof(int32_t), &p, false)) != hipSuccess)
             return hip_fail(h, e, "allocate edge-kernel spill area");
@@ -327,7 +340,7 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
     h->host_only = opt && (opt->flags & PRE3_FLAG_HOST_ONLY);
     h->compact = opt && (opt->flags & PRE3_FLAG_COMPACT_CYCLES);
     if (opt && (opt->flags & ~(PRE3_FLAG_HOST_ONLY | PRE3_FLAG_NO_TOKEN_EDGES | PRE3_FLAG_STEPWISE_REDUCTIONS |
-                               PRE3_FLAG_COMPACT_CYCLES)))
+                               PRE3_FLAG_COMPACT_CYCLES | PRE3_FLAG_NO_TOKEN_EFFECTS)))
         return fail(h, PRE3_E_BADARG, "unknown flag in options");
     if (h->compact && h->stack_cap > kCompactMaxLen)
         return fail(h, PRE3_E_BADARG, "stack compaction handles stacks of at most " + std::to_string(kCompactMaxLen) +
@@ -358,7 +371,10 @@ int pre3_compile(const char *const *grammars, int32_t n_grammars, const pre3_voc
             if (opt && opt->row_threshold > 0) lim.max_path_ids = opt->row_threshold;
             lim.compacted_stacks = h->compact;
             lim.n_threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+            if (opt && opt->effect_min_len > 0) lim.effect_min_len = opt->effect_min_len;
+            if (opt && (opt->flags & PRE3_FLAG_NO_TOKEN_EFFECTS)) lim.effect_min_len = 0;
             h->E = build_token_edges(h->T, h->V, lim);
+            h->X = build_effect_table(h->E);
         }
     } catch (const CompileError &e) {
         return fail(h, e.status, e.text);
@@ -674,6 +690,30 @@ int pre3_token_edge_stats(const pre3_handle *h, int64_t out[8]) {
     return PRE3_OK;
 }
 
+int pre3_token_effect_stats(const pre3_handle *h, int64_t out[4]) {
+    if (!h || !h->compiled || !out) return PRE3_E_BADARG;
+    out[0] = h->E.n_effect_records;
+    out[1] = h->X.stored;
+    out[2] = h->X.dropped;
+    out[3] = (int64_t)((h->X.slots.size() + h->X.pool.size()) * sizeof(int32_t));
+    return PRE3_OK;
+}
+
+int32_t pre3_debug_token_effect(const pre3_handle *h, const int32_t *stack, int32_t len, int32_t token, int32_t *out,
+                                int32_t out_cap, int32_t *info) {
+    if (!h || !h->compiled || !stack || len < 1 || !out || token < 0 || token >= h->V.n_tokens) return PRE3_E_BADARG;
+    int k = 0, peak = 0;
+    std::vector<int32_t> pushes;
+    if (h->E.effect_min_len <= 0 || h->V.offsets[token + 1] - h->V.offsets[token] < h->E.effect_min_len) return 0;
+    if (!find_effect(h->E, h->X, stack, len, token, &k, &peak, &pushes) || k > len) return 0;
+    const int new_len = len - k + 1 + (int)pushes.size();
+    if (new_len > out_cap) return PRE3_E_BADARG;
+    std::copy(stack, stack + (len - k + 1), out);
+    std::copy(pushes.begin(), pushes.end(), out + (len - k + 1));
+    if (info) { info[0] = k; info[1] = peak; info[2] = (int32_t)pushes.size(); }
+    return new_len;
+}
+
 int pre3_symbol_edge_stats(const pre3_handle *h, int64_t out[4]) {
     if (!h || !h->compiled || !out) return PRE3_E_BADARG;
     out[0] = h->S.enabled;
@@ -772,6 +812,32 @@ int pre3_debug_validate_tables(const pre3_handle *h) {
             need(n.walk_count >= -1 && n.walk_begin >= 0 &&
                  (n.walk_count < 0 || (size_t)n.walk_begin + n.walk_count <= E.walk_ids.size()));
         }
+        // stack-effect records and their look-up table
+        for (const ConditionNode &n : E.nodes) {
+            need(n.effect_words >= 0 && n.effect_begin >= 0 && (size_t)n.effect_begin + n.effect_words <= E.effects.size());
+            if (bad) break;
+            for (int32_t at = n.effect_begin; at < n.effect_begin + n.effect_words;) {
+                need(at + 4 <= n.effect_begin + n.effect_words);
+                if (bad) break;
+                const int32_t np = E.effects[at + 3];
+                need(E.effects[at] >= 0 && E.effects[at] < h->V.n_tokens && E.effects[at + 1] >= 1 && E.effects[at + 1] <= 255 && np >= 1 &&
+                     np <= 255 && at + 4 + np <= n.effect_begin + n.effect_words);
+                if (bad) break;
+                for (int i = 0; i < np; ++i) need(E.effects[at + 4 + i] >= 0 && E.effects[at + 4 + i] < T.n_states);
+                at += 4 + np;
+            }
+        }
+        const EffectTable &X = h->X;
+        need(X.slots.size() == (X.slots.empty() ? 0 : ((size_t)X.bucket_mask + 1) * kEffectBucketSlots * 4));
+        for (size_t i = 0; i + 3 < X.slots.size() && bad == 0; i += 4) {
+            if (X.slots[i] < 0) continue;
+            const EffectFields f = effect_unpack((uint32_t)X.slots[i + 1], (uint32_t)X.slots[i + 2], (uint32_t)X.slots[i + 3]);
+            const int32_t tok = X.slots[i + 1] & 0x1FFFFF;
+            need(X.slots[i] < (int)E.nodes.size() && tok < h->V.n_tokens && f.np >= 1 && f.k >= 1);
+            if (f.inline_count > 0) need(f.inline_count == f.np && f.x0 < T.n_states && (f.np == 1 || f.x1 < T.n_states));
+            else need(f.x0 >= 0 && (size_t)f.x0 + f.np <= X.pool.size());
+        }
+        for (int32_t v : X.pool) need(v >= 0 && v < T.n_states);
         for (int32_t t : E.delta_ids) need(t >= 0 && t < h->V.n_tokens);
         for (int32_t t : E.walk_ids) need(t >= 0 && t < h->V.n_tokens);
     }

@@ -62,6 +62,12 @@ struct DevTokenEdges {
     const int32_t *child_state;            // condition states, sorted per node
     const uint32_t *dense_rows;            // [n_dense * stride], stride = n_words rounded up to 4
     const int32_t *delta_ids, *walk_ids;
+    // stack effects of the longer tokens (token_edges.hpp): (node, token) -> record, null = none
+    const int32_t *root_id;                // [n_states] index of each state's root in nodes[]
+    const int4 *fx_slots;                  // buckets of kEffectBucketSlots slots
+    const int32_t *fx_pool;                // pushes of records with more than one
+    uint32_t fx_mask;
+    int32_t fx_min_len;                    // tokens shorter than this have no record
 };
 
 }  // namespace pre3

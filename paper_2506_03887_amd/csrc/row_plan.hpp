@@ -1,6 +1,7 @@
 // Descent of the condition tree of the token-level edges and the assembly of one sequence's mask
 // row from what the descent found.  Shared by the mask kernel and the advance+mask kernel.
 #pragma once
+#include "effect_hash.hpp"
 #include "walk.hpp"
 
 namespace pre3 {
@@ -77,6 +78,78 @@ __device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNod
         plan->walk_begin = walk_begin;
         plan->walk_count = walk_count;
     }
+}
+
+// What the merged edge of a token does to the stack (the stack operations that every prefix-conditioned
+// edge carries, Sec. 3.1): the top k - 1 entries are replaced by np states; peak = highest the stack
+// gets just before a push, relative to its height before the token.
+struct EffectHit {
+    int found, k, peak, np, inline_count, x0, x1;   // x0, x1: the states pushed when inline_count > 0, else x0 = their offset in fx_pool
+};
+
+// Looks the effect of token `tok` up for the stack whose top state has the root `node` (its record:
+// `nd`): descends the condition tree like plan_row and probes every node on the way.  One round of
+// loads per level: lanes 0..7 fetch the eight slots of the key's two buckets, lanes 8..63 the
+// condition states and records of the node's first 56 children (more children take further rounds);
+// a ballot finds the record, another the child.  Run by all 64 lanes of a wave with identical
+// values; a miss means "walk the token".
+template <typename Deeper>
+__device__ __forceinline__ EffectHit find_effect(const DevTokenEdges &E, int node, DevConditionNode nd, const int32_t *win,
+                                                 int n, Deeper deeper, int tok, int lane) {
+    EffectHit r{0, 0, 0, 0, 0, 0, 0};
+    for (int level = 0; level < 256; ++level) {
+        uint32_t b1, b2;
+        effect_buckets((uint32_t)node, (uint32_t)tok, E.fx_mask, &b1, &b2);
+        int4 slot = make_int4(-1, 0, 0, 0);
+        if (lane < 2 * kEffectBucketSlots)
+            slot = E.fx_slots[(size_t)(lane < kEffectBucketSlots ? b1 : b2) * kEffectBucketSlots + (lane & (kEffectBucketSlots - 1))];
+        const bool inner = nd.child_count > 0 && nd.known < n;
+        int x = -3;
+        if (inner) x = nd.known < kWindow ? win[nd.known] : deeper(nd.known);
+        int cstate = -2;
+        DevConditionNode c{};
+        int j = lane - 2 * kEffectBucketSlots;
+        if (inner && j >= 0 && j < nd.child_count) {
+            cstate = E.child_state[nd.a + j];
+            c = E.nodes[nd.b + j];
+        }
+        const unsigned long long hit = __ballot(lane < 2 * kEffectBucketSlots && slot.x >= 0 &&
+                                                effect_slot_matches((uint32_t)slot.x, (uint32_t)slot.y, (uint32_t)node, (uint32_t)tok));
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            const EffectFields f = effect_unpack((uint32_t)__shfl(slot.y, src), (uint32_t)__shfl(slot.z, src), (uint32_t)__shfl(slot.w, src));
+            r.found = 1;
+            r.k = f.k;
+            r.peak = f.peak;
+            r.np = f.np;
+            r.inline_count = f.inline_count;
+            r.x0 = f.x0;
+            r.x1 = f.x1;
+            return r;
+        }
+        if (!inner) return r;
+        unsigned long long m = __ballot(cstate == x);
+        int child = -1;
+        if (m) child = __ffsll((long long)m) - 1 - 2 * kEffectBucketSlots;
+        for (int c0 = 64 - 2 * kEffectBucketSlots; !m && c0 < nd.child_count; c0 += 64) {
+            j = c0 + lane;
+            cstate = -2;
+            if (j < nd.child_count) {
+                cstate = E.child_state[nd.a + j];
+                c = E.nodes[nd.b + j];
+            }
+            m = __ballot(cstate == x);
+            if (m) child = c0 + __ffsll((long long)m) - 1;
+        }
+        if (!m) return r;
+        const int src = __ffsll((long long)m) - 1;
+        node = nd.b + child;
+        nd.known = __shfl(c.known, src);
+        nd.child_count = __shfl(c.child_count, src);
+        nd.a = __shfl(c.a, src);
+        nd.b = __shfl(c.b, src);
+    }
+    return r;
 }
 
 // Assembles mask words [4 * v_lo, 4 * (v_lo + v_cnt)) of the row that `plan` describes in the LDS

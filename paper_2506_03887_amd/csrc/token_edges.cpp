@@ -97,12 +97,20 @@ struct Pending {    // a trie subtree whose verdict depends on stack entries not
     int32_t trie_node;
     int32_t need;
     int32_t nt;
+    int32_t peak;   // highest the stack has been before a push so far in this token's walk (kNoPeak: no push yet)
+};
+constexpr int kNoPeak = -(1 << 24);
+
+struct EffectBudget {   // shared by the workers: records written so far, and the switch that ends recording
+    std::atomic<int64_t> records{0};
+    std::atomic<bool> exceeded{false};
 };
 
 struct BuildNode {
     int known = 1;
     int floor = 0;                              // deepest known state
     std::vector<int32_t> accepted;              // token ids allowed under this node's condition
+    std::vector<int32_t> eff;                   // their stack effects: token, k, peak, n_push, pushes (longer tokens only)
     std::vector<Pending> pend;
     std::vector<int32_t> path;                  // known states, top first (kept until the node is expanded)
     std::vector<std::pair<int32_t, std::unique_ptr<BuildNode>>> children;
@@ -115,24 +123,31 @@ struct Walker {
     const TokenEdgeLimits &lim;
     const int ncol;
     std::vector<std::vector<int32_t>> pool;     // one scratch stack per trie depth
+    const std::vector<int32_t> &tok_len;        // bytes of each token
+    EffectBudget &budget;
 
     Walker(const EdgeTables &t, const Trie &tr, const std::vector<std::vector<int32_t>> &p,
-           const TokenEdgeLimits &l)
-        : T(t), trie(tr), pred(p), lim(l), ncol(t.n_classes + 1), pool(300) {}
+           const TokenEdgeLimits &l, const std::vector<int32_t> &tl, EffectBudget &bud)
+        : T(t), trie(tr), pred(p), lim(l), ncol(t.n_classes + 1), pool(300), tok_len(tl), budget(bud) {}
 
     int goto_of(int state, int nt) const {
         int row = T.goto_row[state];
         return row < 0 ? -1 : T.goto_flat[row + nt];
     }
 
-    // st[0] is the deepest known state; consumes one symbol
-    FeedOut feed(std::vector<int32_t> &st, int col, int delta) const {
+    // st[0] is the deepest known state, the entry k - 1 below the top of the stack the walk started
+    // from; consumes one symbol.  peak follows the height of the stack just before each push,
+    // relative to the height before the token: st holds the entries from st[0] up, so that is |st| - k.
+    FeedOut feed(std::vector<int32_t> &st, int col, int delta, int k, int &peak) const {
         for (;;) {
             uint32_t e = T.edge[(size_t)st.back() * ncol + col];
             switch (e & kKindMask) {
                 case kError: return {kRejectedH, 0, 0};
                 case kAccept: return {kAcceptedH, 0, 0};
-                case kShift: st.push_back((int32_t)(e >> 2) + delta); return {kFedH, 0, 0};
+                case kShift:
+                    peak = std::max(peak, (int)st.size() - k);
+                    st.push_back((int32_t)(e >> 2) + delta);
+                    return {kFedH, 0, 0};
                 default: break;
             }
             int n = (int)((e >> 2) & kMaxPop), nt = (int)(e >> kNtShift);
@@ -140,23 +155,44 @@ struct Walker {
             st.resize(st.size() - n);
             int t = goto_of(st.back(), nt);
             if (t < 0) return {kRejectedH, 0, 0};
+            peak = std::max(peak, (int)st.size() - k);
             st.push_back(t);
         }
     }
 
+    // The stack operations of the merged edge of token `tok`, whose walk has just ended on `st`.
+    void record_effect(BuildNode &out, int32_t tok, const std::vector<int32_t> &st, int k, int peak) {
+        const int np = (int)st.size() - 1;
+        if (lim.effect_min_len <= 0 || tok_len[tok] < lim.effect_min_len || budget.exceeded.load(std::memory_order_relaxed)) return;
+        if (np < 1 || np > 255 || k > 255 || peak < -32768 || peak > 32767 || tok >= (1 << 21)) return;    // such a token keeps its byte-by-byte walk
+        if (budget.records.fetch_add(1, std::memory_order_relaxed) >= lim.max_effect_records) {
+            budget.exceeded.store(true, std::memory_order_relaxed);
+            return;
+        }
+        out.eff.push_back(tok);
+        out.eff.push_back(k);
+        out.eff.push_back(peak);
+        out.eff.push_back(np);
+        out.eff.insert(out.eff.end(), st.begin() + 1, st.end());
+    }
+
     // The edge into trie node `c` is fed from `st`; on success the subtree below is explored.
-    void enter(int c, std::vector<int32_t> &st, int depth, BuildNode &out) {
+    void enter(int c, std::vector<int32_t> &st, int depth, BuildNode &out, int k, int peak) {
         const Trie::Node &N = trie.nodes[c];
-        FeedOut r = feed(st, N.col, N.delta);
-        if (r.kind == kUnderflowH) { out.pend.push_back({c, r.need, r.nt}); return; }
+        FeedOut r = feed(st, N.col, N.delta, k, peak);
+        if (r.kind == kUnderflowH) { out.pend.push_back({c, r.need, r.nt, peak}); return; }
         if (r.kind == kRejectedH) return;
         // shifted (or, for the end-of-input pseudo token, accepted)
-        for (int i = 0; i < N.tok_count; ++i) out.accepted.push_back(trie.tok_ids[N.tok_begin + i]);
+        for (int i = 0; i < N.tok_count; ++i) {
+            const int32_t tok = trie.tok_ids[N.tok_begin + i];
+            out.accepted.push_back(tok);
+            if (r.kind == kFedH) record_effect(out, tok, st, k, peak);
+        }
         if (r.kind == kAcceptedH) return;
         for (int i = 0; i < N.n_children; ++i) {
             std::vector<int32_t> &st2 = pool[depth + 1];
             st2 = st;
-            enter(N.first_child + i, st2, depth + 1, out);
+            enter(N.first_child + i, st2, depth + 1, out, k, peak);
         }
     }
 
@@ -166,24 +202,24 @@ struct Walker {
         const Trie::Node &R = trie.nodes[0];
         std::vector<int32_t> &st = pool[0];
         st.assign(1, state);
-        enter(1, st, 0, out);                                   // '$'
+        enter(1, st, 0, out, 1, kNoPeak);                       // '$'
         for (int i = 0; i < R.n_children; ++i) {
             st.assign(1, state);
-            enter(R.first_child + i, st, 0, out);
+            enter(R.first_child + i, st, 0, out, 1, kNoPeak);
         }
     }
 
-    // One more stack entry X becomes known below the node that owned `in`.
-    void resolve(int X, const std::vector<Pending> &in, BuildNode &out) {
+    // One more stack entry X becomes known below the node that owned `in`: X is the entry k - 1 below the top.
+    void resolve(int X, const std::vector<Pending> &in, BuildNode &out, int k) {
         for (const Pending &u : in) {
-            if (u.need > 1) { out.pend.push_back({u.trie_node, u.need - 1, u.nt}); continue; }
+            if (u.need > 1) { out.pend.push_back({u.trie_node, u.need - 1, u.nt, u.peak}); continue; }
             int t = goto_of(X, u.nt);
             if (t < 0) continue;
             std::vector<int32_t> &st = pool[0];
             st.clear();
             st.push_back(X);
-            st.push_back(t);
-            enter(u.trie_node, st, 0, out);
+            st.push_back(t);                                    // pushed onto a stack cut down to X: height 1 - k before
+            enter(u.trie_node, st, 0, out, k, std::max(u.peak, 1 - k));
         }
     }
 
@@ -220,7 +256,7 @@ struct Walker {
                 if (ps.size() == 1) {                               // only one stack can lie below: no test needed
                     std::vector<Pending> in;
                     in.swap(nd.pend);
-                    resolve(ps[0], in, nd);
+                    resolve(ps[0], in, nd, nd.known + 1);
                     nd.floor = ps[0];
                     nd.known++;
                     nd.path.push_back(ps[0]);
@@ -235,7 +271,7 @@ struct Walker {
                     ch->floor = X;
                     ch->path = nd.path;
                     ch->path.push_back(X);
-                    resolve(X, nd.pend, *ch);
+                    resolve(X, nd.pend, *ch, ch->known);
                     queue.push_back(ch.get());
                     nd.children.emplace_back(X, std::move(ch));
                 }
@@ -256,6 +292,7 @@ struct Flattener {
     const TokenEdgeLimits &lim;
     TokenEdges &E;
     int dense_threshold;
+    bool record_effects;
 
     void subtree_tokens(int c, std::vector<int32_t> &out) const {
         const Trie::Node &N = trie.nodes[c];
@@ -356,7 +393,7 @@ struct Flattener {
         return begin;
     }
 
-    std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> delta_index, walk_index;
+    std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> delta_index, walk_index, effect_index;
     // hash of a group of sibling records (with their condition states) -> (child_begin, count)
     std::unordered_multimap<uint64_t, std::pair<int32_t, int32_t>> group_index;
 
@@ -407,6 +444,10 @@ struct Flattener {
             n.delta_begin = intern_list(E.delta_ids, delta_index, b.accepted);
             since.insert(since.end(), b.accepted.begin(), b.accepted.end());
         }
+        if (record_effects && !b.eff.empty()) {
+            n.effect_words = (int)b.eff.size();
+            n.effect_begin = intern_list(E.effects, effect_index, b.eff);
+        }
         // tokens left undetermined when the tree ends here
         if (b.children.empty() && !b.pend.empty()) {
             int64_t total = 0;
@@ -453,6 +494,9 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     const int ncol = T.n_classes + 1;
 
     const std::vector<std::vector<int32_t>> pred = predecessors(T);
+    std::vector<int32_t> tok_len(V.n_tokens);
+    for (int t = 0; t < V.n_tokens; ++t) tok_len[t] = V.offsets[t + 1] - V.offsets[t];
+    EffectBudget budget;
 
     // states with identical edges, goto row and predecessors share one root
     std::map<std::tuple<std::vector<uint32_t>, int32_t, std::vector<int32_t>>, int> root_ids;
@@ -481,7 +525,7 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
         std::atomic<int64_t> used(0);
         auto worker = [&]() {
             try {
-                Walker w(T, trie, pred, lim);
+                Walker w(T, trie, pred, lim, tok_len, budget);
                 for (;;) {
                     const size_t k = next.fetch_add(1);
                     if (k >= todo.size()) return;
@@ -515,7 +559,10 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     if (failure) std::rethrow_exception(failure);
     queues.clear();
 
-    Flattener F{trie, lim, E, std::max(1, lim.max_path_ids)};
+    // effect records are kept only if all of them fitted the budget (a partial set would make the speed
+    // of an advance depend on which worker happened to write first)
+    const bool keep_effects = lim.effect_min_len > 0 && !budget.exceeded.load();
+    Flattener F{trie, lim, E, std::max(1, lim.max_path_ids), keep_effects};
     std::vector<int> root_node(roots.size());
     for (size_t i = 0; i < roots.size(); ++i) {
         std::vector<int32_t> since;
@@ -526,7 +573,81 @@ TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const To
     }
     E.root_of_state.resize(T.n_states);
     for (int s = 0; s < T.n_states; ++s) E.root_of_state[s] = root_node[root_index[s]];
+    if (keep_effects && !E.effects.empty()) {
+        E.effect_min_len = lim.effect_min_len;
+        for (size_t i = 0; i < E.effects.size(); i += 4 + (size_t)E.effects[i + 3]) E.n_effect_records++;
+    }
     return E;
+}
+
+EffectTable build_effect_table(const TokenEdges &E) {
+    EffectTable X;
+    if (E.effect_min_len <= 0) return X;
+    // records per node (a list shared by several nodes is entered once per node)
+    int64_t total = 0;
+    for (const ConditionNode &n : E.nodes)
+        for (int32_t at = n.effect_begin; at < n.effect_begin + n.effect_words; at += 4 + E.effects[at + 3]) ++total;
+    uint64_t buckets = 1;
+    while (buckets * 2 < (uint64_t)std::max<int64_t>(total, 1)) buckets <<= 1;       // about half full
+    X.bucket_mask = (uint32_t)(buckets - 1);
+    X.slots.assign((size_t)buckets * kEffectBucketSlots * 4, -1);
+    std::vector<uint8_t> fill((size_t)buckets, 0);
+    for (size_t node = 0; node < E.nodes.size(); ++node) {
+        const ConditionNode &n = E.nodes[node];
+        for (int32_t at = n.effect_begin; at < n.effect_begin + n.effect_words; at += 4 + E.effects[at + 3]) {
+            const int32_t tok = E.effects[at], k = E.effects[at + 1], peak = E.effects[at + 2], np = E.effects[at + 3];
+            uint32_t b1, b2;
+            effect_buckets((uint32_t)node, (uint32_t)tok, X.bucket_mask, &b1, &b2);
+            const uint32_t b = fill[b2] < fill[b1] ? b2 : b1;
+            if (fill[b] >= kEffectBucketSlots) { ++X.dropped; continue; }
+            int32_t *slot = &X.slots[((size_t)b * kEffectBucketSlots + fill[b]++) * 4];
+            const bool inl = np <= 2 && E.effects[at + 4] < (1 << kEffectInlineStateBits) &&
+                             (np == 1 || E.effects[at + 5] < (1 << kEffectInlineStateBits));
+            const uint32_t s0 = (uint32_t)E.effects[at + 4], s1 = np == 2 ? (uint32_t)E.effects[at + 5] : 0u;
+            slot[0] = (int32_t)node;
+            slot[1] = (int32_t)((uint32_t)tok | ((uint32_t)k << 21) | ((inl ? (uint32_t)np : 0u) << 29));
+            slot[2] = (int32_t)(((uint32_t)(peak + 32768) << 16) | (inl ? ((s1 >> 12) << 8) : 0u) | (uint32_t)np);
+            if (inl) {
+                slot[3] = (int32_t)(s0 | ((s1 & 0xFFFu) << 20));
+            } else {
+                slot[3] = (int32_t)X.pool.size();
+                X.pool.insert(X.pool.end(), E.effects.begin() + at + 4, E.effects.begin() + at + 4 + np);
+            }
+            ++X.stored;
+        }
+    }
+    return X;
+}
+
+bool find_effect(const TokenEdges &E, const EffectTable &X, const int32_t *stack, int len, int32_t token, int *k,
+                 int *peak, std::vector<int32_t> *pushes) {
+    if (X.slots.empty() || len < 1 || stack[len - 1] < 0 || stack[len - 1] >= (int)E.root_of_state.size()) return false;
+    int node = E.root_of_state[stack[len - 1]];
+    for (;;) {
+        uint32_t b[2];
+        effect_buckets((uint32_t)node, (uint32_t)token, X.bucket_mask, &b[0], &b[1]);
+        for (int c = 0; c < 2; ++c)
+            for (int s = 0; s < kEffectBucketSlots; ++s) {
+                const int32_t *slot = &X.slots[((size_t)b[c] * kEffectBucketSlots + s) * 4];
+                if (slot[0] < 0 || !effect_slot_matches((uint32_t)slot[0], (uint32_t)slot[1], (uint32_t)node, (uint32_t)token)) continue;
+                const EffectFields f = effect_unpack((uint32_t)slot[1], (uint32_t)slot[2], (uint32_t)slot[3]);
+                *k = f.k;
+                *peak = f.peak;
+                pushes->clear();
+                if (f.inline_count >= 1) pushes->push_back(f.x0);
+                if (f.inline_count == 2) pushes->push_back(f.x1);
+                if (f.inline_count == 0) pushes->insert(pushes->end(), X.pool.begin() + f.x0, X.pool.begin() + f.x0 + f.np);
+                return true;
+            }
+        const ConditionNode &n = E.nodes[node];
+        if (n.child_count == 0 || n.known >= len) return false;
+        const int x = stack[len - 1 - n.known];
+        int next = -1;
+        for (int i = 0; i < n.child_count; ++i)
+            if (E.child_state[n.child_begin + i] == x) next = E.child_node[n.child_begin + i];
+        if (next < 0) return false;
+        node = next;
+    }
 }
 
 bool resolve_row(const TokenEdges &E, const int32_t *stack, int len, uint32_t *row, std::vector<int32_t> &walk,

@@ -31,6 +31,7 @@
 #include <cstdint>
 #include <vector>
 
+#include "effect_hash.hpp"
 #include "tables.hpp"
 
 namespace pre3 {
@@ -46,6 +47,8 @@ struct ConditionNode {
     int32_t delta_count;
     int32_t walk_begin;     // token ids left undetermined if the descent ends here;
     int32_t walk_count;     // -1: too many, walk the whole vocabulary
+    int32_t effect_begin;   // stack effects of the longer tokens allowed here (records in TokenEdges::effects)
+    int32_t effect_words;
 };
 
 struct TokenEdges {
@@ -56,9 +59,37 @@ struct TokenEdges {
     std::vector<int32_t> child_state, child_node;
     std::vector<uint32_t> dense_rows;
     std::vector<int32_t> delta_ids, walk_ids;
+    // Stack effects (the merged edge's stack operations, Sec. 3.1: every edge carries its accepted
+    // symbols, its stack-matching condition AND its stack operations).  For a token of at least
+    // effect_min_len bytes that a node allows, one record
+    //     token id, k, peak, n_push, push[0 .. n_push)
+    // says what the token's walk does to ANY stack matching the node's condition: the top k - 1
+    // entries are replaced by the n_push states (so the entry k - 1 below the top is the deepest one
+    // the walk exposes, and it stays); peak = largest stack height just before a push, relative to the
+    // height before the token (the walk overflows a capacity `cap` iff len + peak >= cap).
+    // A node's records are effects[effect_begin .. effect_begin + effect_words).
+    std::vector<int32_t> effects;
+    int64_t n_effect_records = 0;
+    int effect_min_len = 0;               // 0: no effects were recorded
     // statistics
     int64_t n_roots = 0, max_known = 0, n_dense = 0;
 };
+
+// (node, token) -> effect record: buckets of four 16-byte slots, two candidate buckets per key; a
+// record that finds both full is left out (its token is then walked byte by byte, like every token
+// without a record).  The slot layout is in effect_hash.hpp: one or two pushed states travel inside
+// the slot, longer push lists in `pool`.
+struct EffectTable {
+    std::vector<int32_t> slots;           // 4 ints per slot, 4 slots per bucket; node = -1: empty
+    std::vector<int32_t> pool;            // the pushes of records with more than one
+    uint32_t bucket_mask = 0;
+    int64_t stored = 0, dropped = 0;
+};
+EffectTable build_effect_table(const TokenEdges &E);
+// Host mirror of the kernels' look-up (tests and tools): descends the condition tree for the stack,
+// probes every node on the way for `token`.  Returns true and fills k, peak and the pushes on a hit.
+bool find_effect(const TokenEdges &E, const EffectTable &X, const int32_t *stack, int len, int32_t token, int *k,
+                 int *peak, std::vector<int32_t> *pushes);
 
 struct TokenEdgeLimits {
     int max_nodes = 1 << 20;          // condition-tree nodes
@@ -71,6 +102,9 @@ struct TokenEdgeLimits {
     int64_t max_dense_words = (int64_t)1 << 28;   // 1 GiB of dense rows
     int n_threads = 8;
     bool compacted_stacks = false;    // stacks hold no complete traversal of a reduction cycle (tables.hpp)
+    int effect_min_len = 3;           // tokens of at least this many bytes get stack-effect records (0: none);
+                                      // shorter ones are walked as fast as a record is found
+    int64_t max_effect_records = (int64_t)12 << 20;   // beyond this no records are kept at all
 };
 
 TokenEdges build_token_edges(const EdgeTables &T, const VocabLayout &V, const TokenEdgeLimits &lim);

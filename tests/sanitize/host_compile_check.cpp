@@ -80,8 +80,9 @@ int main(int argc, char **argv) {
         if (!stepwise) S = build_symbol_edges(T);
         TokenEdges E;
         if (token_edges) E = build_token_edges(T, V, lim);
-        std::printf("tables states %d classes %d kinds %d cycles %d sym_nodes %zu tree_nodes %zu rows %lld\n", T.n_states,
-                    T.n_classes, T.n_kinds, T.n_cycles, S.nodes.size(), E.nodes.size(), (long long)E.n_dense);
+        const EffectTable X = build_effect_table(E);
+        std::printf("tables states %d classes %d kinds %d cycles %d sym_nodes %zu tree_nodes %zu rows %lld effects %lld\n", T.n_states,
+                    T.n_classes, T.n_kinds, T.n_cycles, S.nodes.size(), E.nodes.size(), (long long)E.n_dense, (long long)X.stored);
 
         const std::string sb = slurp(dir + "/stacks.bin", &ok);
         if (!ok) return 2;
@@ -115,6 +116,14 @@ int main(int argc, char **argv) {
                 if (walk(st, t, 1 << 30, nullptr) == 0) row[t >> 5] |= 1u << (t & 31);
             std::vector<int32_t> after = st;
             int rc = token >= 0 && token < n_tokens && token != eos ? walk(st, token, 1 << 30, &after) : -1;
+            // the recorded stack operations of the token, where there are any, must give the walk's stack
+            int fk = 0, fpeak = 0;
+            std::vector<int32_t> pushes;
+            if (rc == 0 && token_edges && find_effect(E, X, st.data(), len, token, &fk, &fpeak, &pushes) && fk <= len) {
+                std::vector<int32_t> by_effect(st.begin(), st.begin() + (len - fk + 1));
+                by_effect.insert(by_effect.end(), pushes.begin(), pushes.end());
+                if (by_effect != after) std::printf("MISMATCH effect of token %d on stack %d\n", token, k);
+            }
             std::printf("stack %d row %016llx resolved %d advance %d %016llx\n", k, (unsigned long long)fnv(row.data(), row.size() * 4),
                         (int)resolved, rc, (unsigned long long)fnv(after.data(), after.size() * 4));
         }

@@ -84,6 +84,10 @@ def test_advance_fill_mask_all_configs():
     assert replay_advance_fill(1)["full_masks"] == 32
     assert replay_advance_fill(2, steps=64)["full_masks"] == 64
     assert replay_advance_fill(2, steps=12, max_condition_depth=2)["full_masks"] == 12
+    # the stack operations of the token-level edges: off (every token walked), and for every token of 2+ bytes
+    assert replay_advance_fill(2, steps=64, token_effects=False)["full_masks"] == 64
+    assert replay_advance_fill(2, steps=64, effect_min_len=2)["full_masks"] == 64
+    assert replay_advance_fill(3, steps=24, effect_min_len=12, full_mask_steps=[0, 23])["full_masks"] == 2
     assert replay_advance_fill(2, steps=12, token_edges=False)["full_masks"] == 12
     assert replay_advance_fill(3, steps=96)["full_masks"] == 96
     assert replay_advance_fill(4, steps=64, full_mask_steps=range(0, 64, 4))["full_masks"] == 16

@@ -63,6 +63,7 @@ def _run(exe, case, *options):
     report = r.stderr + r.stdout
     assert r.returncode == 0 and "runtime error" not in report and "Sanitizer" not in report, \
         f"{os.path.basename(exe)} {options}: exit {r.returncode}\n{report[-3000:]}"
+    assert "MISMATCH" not in r.stdout, r.stdout[-2000:]
     return r.stdout.splitlines()
 
 
