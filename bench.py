@@ -118,6 +118,8 @@ def parse_args(argv=None):
     ap.add_argument("--max-condition-depth", type=int, default=0,
                     help="limit the token-level conditions to this many stack entries (0 = the library's default of 48): "
                          "a probe that leaves tokens to the run-time walk")
+    ap.add_argument("--row-latency", action="store_true",
+                    help="also time pre3_fill_mask one sequence at a time (hundreds of one-row launches)")
     ap.add_argument("--effect-min-len", type=int, default=0,
                     help="shortest token that gets a stack-effect record (0 = the library's default; -1 = no records)")
     ap.add_argument("--batch", type=int, default=0,
@@ -708,7 +710,8 @@ def main(argv=None):
             out["greedy"] = guarded(greedy_leg)
             out["topk"] = guarded(topk_leg)
             if not args.eager:
-                out["fill_mask_row_latency"] = guarded(row_latency_leg)
+                if args.row_latency:
+                    out["fill_mask_row_latency"] = guarded(row_latency_leg)
                 out["jump_forward"] = guarded(jump_forward_leg)
                 if not args.no_token_edges:
                     out["fill_mask_byte_by_byte"] = guarded(byte_by_byte_leg)
