@@ -75,12 +75,33 @@ __device__ __forceinline__ void commit_overlay(int32_t *row, const PrivateStack 
 // and dropped on a match (then the check repeats).  Run by the 64 lanes of one wave in lockstep:
 // lanes look up cycle_head for 64 entries at a time, a ballot finds the heads, lane i compares
 // entry i of a traversal, segments between heads are moved down as blocks.  `pool` = the cycle
-// records (in LDS or global memory).  Returns the new length; *first_moved = lowest index whose
+// records in their device layout (states last first, kCyclePoolPad entries of padding at the end),
+// in LDS or global memory.  Returns the new length; *first_moved = lowest index whose
 // content changed (= the new length if only the top was cut, n if nothing changed).
-__device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *__restrict__ cycle_head, const int32_t *pool,
+__device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *cycle_head, const int32_t *pool,
                                            int n_states, int lane, int *first_moved) {
-    int w = 0, moved = n;
-    for (int r0 = 0; r0 < n; r0 += 64) {
+    // Where can the first traversal end?  Until one is dropped the stack has its original layout, and
+    // a traversal of length k under the entry at position p needs s[p - k] == s[p] (both are the
+    // cycle's first state): every lane tests that for one position and the cycles of its state, and
+    // the rebuilding starts at the lowest position that passes -- in a stack that was compacted
+    // before the call, that is inside the entries the call added.
+    int start = n;
+    for (int r0 = 0; r0 < n && start == n; r0 += 64) {
+        const int p = r0 + lane;
+        bool candidate = false;
+        if (p < n) {
+            const int x = s[p];
+            for (int at = (unsigned)x < (unsigned)n_states ? cycle_head[x] : -1; at >= 0 && !candidate; at = pool[at + 1]) {
+                const int k = pool[at];
+                candidate = p - k >= 0 && s[p - k] == x;
+            }
+        }
+        const unsigned long long c = __ballot(candidate);
+        if (c) start = r0 + __ffsll((long long)c) - 1;
+    }
+    if (start == n) { *first_moved = n; return n; }
+    int w = start, moved = n;
+    for (int r0 = start; r0 < n; r0 += 64) {
         const int cnt = n - r0 < 64 ? n - r0 : 64;
         const int x = lane < cnt ? s[r0 + lane] : -1;
         const int hd = (unsigned)x < (unsigned)n_states ? cycle_head[x] : -1;
@@ -103,17 +124,33 @@ __device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *__r
             if (!heads) break;
             heads &= heads - 1;
             prev = j + 1;
-            const int first = __shfl(hd, j);            // s[w - 1] is the head of these cycles
+            const int first = __builtin_amdgcn_readlane(hd, j);   // s[w - 1] is the head of these cycles
             int h = first;
             while (h >= 0) {
-                const int k = __builtin_amdgcn_readfirstlane(pool[h]);
-                const int next = __builtin_amdgcn_readfirstlane(pool[h + 1]);
-                bool match = false;
-                if (w - 1 - k >= 0) match = __all(lane >= k || s[w - 1 - k + lane] == pool[h + 2 + lane]);
+                // one round of loads per record: its header, its states (stored last first and
+                // padded, so no address depends on the length) and the entries under the head
+                const int header = pool[h + (lane & 1)];
+                const int want = pool[h + 2 + lane];
+                const int have = w - 2 - lane >= 0 ? s[w - 2 - lane] : -1;
+                const int k = __builtin_amdgcn_readlane(header, 0), next = __builtin_amdgcn_readlane(header, 1);
+                const bool match = __all(lane >= k || have == want);   // an entry below the bottom (-1) matches no state
                 if (match) {
                     w -= k;                             // the top stays: s[w - 1] held the same state
                     moved = w < moved ? w : moved;
-                    h = first;
+                    // The new top failed every check when it was put there, over the same entries:
+                    // no need to try its records again.  And the k entries just dropped, s[w .. w + k),
+                    // took the stack from this very content back to it without any drop on the way, so
+                    // every further copy of them that follows in the input does the same: skip those
+                    // copies (as far as they lie in this chunk) at once.
+                    const int left = cnt - prev;
+                    if (left >= k) {
+                        const bool same = lane < left && s[r0 + prev + lane] == s[w + lane % k];
+                        const unsigned long long differs = ~__ballot(same);
+                        const int run = differs ? __ffsll((long long)differs) - 1 : 64;
+                        prev += run / k * k;
+                        heads = prev >= 64 ? 0ull : heads & (~0ull << prev);
+                    }
+                    h = -1;
                 } else {
                     h = next;
                 }
@@ -122,6 +159,20 @@ __device__ __forceinline__ int fold_cycles(int32_t *s, int n, const int32_t *__r
     }
     *first_moved = moved;
     return w;
+}
+
+// The cycle tables (cycle_head[n_states], then the records) are small for most grammars: the threads
+// given here copy them into LDS (`lds`, n_states + pool_n entries) so that fold_cycles, whose look-ups
+// depend on one another, does not go to global memory for each.  The caller puts a block barrier
+// between this copy and the first use.
+constexpr int kStageCycleStates = 4096, kStageCyclePool = 1024;
+__host__ __device__ inline bool cycles_fit_lds(int n_states, int pool_n) {
+    return n_states <= kStageCycleStates && pool_n <= kStageCyclePool;
+}
+__device__ __forceinline__ void copy_cycle_tables(int32_t *lds, int n_states, int pool_n, const int32_t *head,
+                                                  const int32_t *pool, int first, int step) {
+    for (int i = first; i < n_states; i += step) lds[i] = head[i];
+    for (int i = first; i < pool_n; i += step) lds[n_states + i] = pool[i];
 }
 
 // One wave per sequence: the walk of a single token is a chain of dependent table look-ups, so
@@ -137,14 +188,26 @@ template <bool kCompact>
 __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
     int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos,
-    const int32_t *__restrict__ cycle_head, const int32_t *__restrict__ cycle_pool) {
-    extern __shared__ int32_t adv_stage[];             // kCompact: kAdvSeqPerBlock x cap stack entries
+    const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles) {
+    extern __shared__ int32_t adv_stage[];             // kCompact: kAdvSeqPerBlock x (cap stack entries [+ cycle tables])
     __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
     __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
     __shared__ int32_t s_base[kAdvSeqPerBlock], s_depth[kAdvSeqPerBlock];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int b = blockIdx.x * kAdvSeqPerBlock + wave;
-    if (b >= batch) return;
+    // kCompact with small cycle tables: the block copies them into LDS behind the staged stacks; every
+    // wave passes exactly one block barrier (a wave without a sequence right here, the others once
+    // their own input loads are under way)
+    int32_t *cycle_lds = adv_stage + kAdvSeqPerBlock * cap;
+    if (kCompact && stage_cycles) {
+        copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, threadIdx.x, 64 * kAdvSeqPerBlock);
+        cycle_head = cycle_lds;
+        cycle_pool = cycle_lds + T.n_states;
+    }
+    if (b >= batch) {
+        if (kCompact && stage_cycles) __syncthreads();
+        return;
+    }
     int32_t *row = data + (size_t)b * cap;
     PrivateStack priv;
     priv.lds = lds_stack + wave;
@@ -162,6 +225,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
         s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
         if (t != T.eos_id) tok = stage_token(T, t, lane, s_info[wave]);
     }
+    if (kCompact && stage_cycles) __syncthreads();
     __builtin_amdgcn_wave_barrier();
     // all lanes hold identical values from here on; lane 0 alone writes the results
     int commit = -1, out_err = 0, out_state = st, out_len = n;
@@ -240,9 +304,9 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
     int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
     uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
-    size_t walk_spill_stride, const int32_t *__restrict__ cycle_head, const int32_t *__restrict__ cycle_pool) {
+    size_t walk_spill_stride, const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles) {
     extern __shared__ uint4 bits4[];                   // whole row: n_words rounded up to a multiple of 4;
-                                                       // kCompact: followed by cap stack entries
+                                                       // kCompact: followed by cap stack entries [+ cycle tables]
     __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
     __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
     __shared__ RowPlan plan;
@@ -260,6 +324,11 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         for (int64_t off = ((int64_t)(blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
             acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
         if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
+        if (kCompact && stage_cycles) {                 // ... and copy the cycle tables into LDS for wave 0
+            int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2)) + cap;
+            copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, tid - 64, kAfBlock - 64);
+            __syncthreads();
+        }
     }
     if (tid < 64) {
         PrivateStack priv;
@@ -283,6 +352,12 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         }
         s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
         if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
+        if (kCompact && stage_cycles) {                 // the other waves have copied the cycle tables meanwhile
+            __syncthreads();
+            int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2)) + cap;
+            cycle_head = cycle_lds;
+            cycle_pool = cycle_lds + T.n_states;
+        }
         __builtin_amdgcn_wave_barrier();
         // ---- advance (all lanes hold identical values)
         int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
@@ -422,14 +497,21 @@ template <bool kCompact>
 __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
     DevTables T, int32_t *__restrict__ states, int32_t *__restrict__ data, int32_t *__restrict__ len, int cap,
     int batch, uint8_t *__restrict__ out_bytes, int32_t *__restrict__ out_len, int max_bytes, int32_t *adv_scratch,
-    int32_t *lane_spill, size_t lane_spill_stride, const int32_t *__restrict__ cycle_head,
-    const int32_t *__restrict__ cycle_pool) {
-    extern __shared__ int32_t jf_stage[];              // kCompact: kJfSeqPerBlock x cap stack entries
+    int32_t *lane_spill, size_t lane_spill_stride, const int32_t *cycle_head, const int32_t *cycle_pool,
+    int stage_cycles) {
+    extern __shared__ int32_t jf_stage[];              // kCompact: kJfSeqPerBlock x (cap stack entries [+ cycle tables])
     __shared__ int32_t s_trial[kJfSeqPerBlock][kLdsDepth * 64];
     __shared__ int32_t s_adv[kJfSeqPerBlock][kLdsDepth];
     __shared__ int32_t s_win[kJfSeqPerBlock][kWindow], s_new[kJfSeqPerBlock][kWindow];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int b = blockIdx.x * kJfSeqPerBlock + wave;
+    if (kCompact && stage_cycles) {                     // small cycle tables: copied into LDS by the whole block
+        int32_t *cycle_lds = jf_stage + kJfSeqPerBlock * cap;
+        copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, threadIdx.x, 64 * kJfSeqPerBlock);
+        cycle_head = cycle_lds;
+        cycle_pool = cycle_lds + T.n_states;
+        __syncthreads();
+    }
     if (b >= batch) return;
     int32_t *row = data + (size_t)b * cap;
     int n = len[b];
@@ -596,16 +678,19 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
     if (batch == 0) return hipSuccess;
     const size_t row_bytes = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
     if (cycle_head) {                                  // cycle-aware stacks: the new stack is staged in LDS too
-        const size_t lds = row_bytes + (size_t)cap * sizeof(int32_t);
+        size_t lds = row_bytes + (size_t)cap * sizeof(int32_t);
         if (cap > kCompactMaxLen || lds > kAfDynamicLdsMax) return hipErrorInvalidValue;
+        const size_t tables = (size_t)(T.n_states + T.cycle_pool_n) * sizeof(int32_t);
+        const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) && lds + tables <= kAfDynamicLdsMax;
+        if (stage) lds += tables;
         hipLaunchKernelGGL(advance_fill_kernel<true>, dim3(batch), dim3(kAfBlock), lds, stream, T, E, tokens, states, data,
                            len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
-                           cycle_head, cycle_pool);
+                           cycle_head, cycle_pool, stage);
     } else {
         if (row_bytes > kAfDynamicLdsMax) return hipErrorInvalidValue;
         hipLaunchKernelGGL(advance_fill_kernel<false>, dim3(batch), dim3(kAfBlock), row_bytes, stream, T, E, tokens, states,
                            data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
-                           nullptr, nullptr);
+                           nullptr, nullptr, 0);
     }
     return hipGetLastError();
 }
@@ -626,11 +711,15 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
     const dim3 grid((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), block(64 * kAdvSeqPerBlock);
     if (cycle_head) {                                  // cycle-aware stacks: the new stack is staged in LDS
         if (!advance_fits_compact(cap)) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(advance_kernel<true>, grid, block, (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t), stream, T, tokens,
-                           states, data, len, cap, batch, err, scratch, restart_on_eos, cycle_head, cycle_pool);
+        const size_t tables = (size_t)(T.n_states + T.cycle_pool_n) * sizeof(int32_t);
+        const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) &&
+                          (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + tables + 4096 <= 65536;
+        const size_t lds = (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + (stage ? tables : 0);
+        hipLaunchKernelGGL(advance_kernel<true>, grid, block, lds, stream, T, tokens, states, data, len, cap, batch, err,
+                           scratch, restart_on_eos, cycle_head, cycle_pool, stage);
     } else {
         hipLaunchKernelGGL(advance_kernel<false>, grid, block, 0, stream, T, tokens, states, data, len, cap, batch, err,
-                           scratch, restart_on_eos, nullptr, nullptr);
+                           scratch, restart_on_eos, nullptr, nullptr, 0);
     }
     return hipGetLastError();
 }
@@ -647,12 +736,15 @@ hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *dat
     const dim3 grid((batch + kJfSeqPerBlock - 1) / kJfSeqPerBlock), block(64 * kJfSeqPerBlock);
     if (cycle_head) {                                  // cycle-aware stacks: compacted before the kernel ends
         if (!jump_forward_fits_compact(cap)) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(jump_forward_kernel<true>, grid, block, (size_t)kJfSeqPerBlock * cap * sizeof(int32_t), stream, T,
-                           states, data, len, cap, batch, out_bytes, out_len, max_bytes, adv_scratch, lane_spill,
-                           (size_t)batch * 64, cycle_head, cycle_pool);
+        const size_t tables = (size_t)(T.n_states + T.cycle_pool_n) * sizeof(int32_t);
+        const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) &&
+                          (size_t)kJfSeqPerBlock * cap * sizeof(int32_t) + tables + 20480 <= 65536;
+        const size_t lds = (size_t)kJfSeqPerBlock * cap * sizeof(int32_t) + (stage ? tables : 0);
+        hipLaunchKernelGGL(jump_forward_kernel<true>, grid, block, lds, stream, T, states, data, len, cap, batch, out_bytes,
+                           out_len, max_bytes, adv_scratch, lane_spill, (size_t)batch * 64, cycle_head, cycle_pool, stage);
     } else {
         hipLaunchKernelGGL(jump_forward_kernel<false>, grid, block, 0, stream, T, states, data, len, cap, batch, out_bytes,
-                           out_len, max_bytes, adv_scratch, lane_spill, (size_t)batch * 64, nullptr, nullptr);
+                           out_len, max_bytes, adv_scratch, lane_spill, (size_t)batch * 64, nullptr, nullptr, 0);
     }
     return hipGetLastError();
 }

@@ -93,6 +93,19 @@ hipError_t arena_alloc(pre3_handle *h, size_t bytes, void **out) {
     return hipSuccess;
 }
 
+// The reduction-cycle records as the kernels read them: same offsets as in EdgeTables::cycle_pool
+// ([length, next record of the same head, states]), but every record's states last first, so that
+// the lane that looks at the entry i below a head compares it with entry 2 + i of the record
+// whatever the record's length; kCyclePoolPad entries that match no state follow the last record,
+// so that all 64 lanes can load.
+std::vector<int32_t> device_cycle_pool(const EdgeTables &T) {
+    std::vector<int32_t> pool = T.cycle_pool;
+    for (size_t at = 0; at + 2 <= pool.size(); at += 2 + (size_t)pool[at])
+        std::reverse(pool.begin() + at + 2, pool.begin() + at + 2 + pool[at]);
+    pool.insert(pool.end(), kCyclePoolPad, -2);
+    return pool;
+}
+
 template <typename T>
 hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
     void *p = nullptr;
@@ -242,6 +255,7 @@ int upload_tables(pre3_handle *h) {
     D.n_tokens = h->V.n_tokens;
     D.eos_id = h->V.eos_id;
     D.max_depth = h->max_depth;
+    D.cycle_pool_n = h->compact ? (int)h->T.cycle_pool.size() + kCyclePoolPad : 0;
 
     int device = 0;
     hipDeviceProp_t prop;
@@ -294,9 +308,7 @@ int upload_tables(pre3_handle *h) {
     }
     if (h->compact) {
         if ((e = upload(h, h->T.cycle_head, &h->cycle_head)) != hipSuccess) return hip_fail(h, e, "upload cycle_head");
-        std::vector<int32_t> pool = h->T.cycle_pool;
-        if (pool.empty()) pool.push_back(0);
-        if ((e = upload(h, pool, &h->cycle_pool)) != hipSuccess) return hip_fail(h, e, "upload cycle_pool");
+        if ((e = upload(h, device_cycle_pool(h->T), &h->cycle_pool)) != hipSuccess) return hip_fail(h, e, "upload cycle_pool");
     }
     return PRE3_OK;
 }
@@ -307,7 +319,7 @@ bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 // again (only with PRE3_FLAG_COMPACT_CYCLES and a grammar that has such cycles).
 hipError_t compact_stacks(pre3_handle *h, const pre3_stacks &st, hipStream_t s) {
     if (!h->compact || h->T.n_cycles == 0) return hipSuccess;
-    return launch_compact_stacks(h->cycle_head, h->cycle_pool, (int)h->T.cycle_pool.size(), h->T.n_states,
+    return launch_compact_stacks(h->cycle_head, h->cycle_pool, h->dev.cycle_pool_n, h->T.n_states,
                                  st.data, st.len, st.cap, st.batch, s);
 }
 hipError_t compact_bound_stacks(pre3_handle *h, hipStream_t s) { return compact_stacks(h, h->b_stacks, s); }

@@ -42,6 +42,7 @@ struct DevTables {
     // [1 + i] = byte_info of byte i -- everything a walk needs to know about the token in one access
     const int32_t *tok_info;       // [n_tokens * 32]
     int max_depth;                 // private stack entries a walk can need
+    int cycle_pool_n;              // entries of the reduction-cycle records (cycle-aware stacks), 0 = none
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
     // the small tables every advance touches lie next to each other: idle waves pull them into L2
     const char *hot_begin;

@@ -62,6 +62,9 @@ hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *dat
                                hipStream_t stream);
 bool jump_forward_fits_compact(int cap);                // four staged stacks within the kernel's LDS
 
+// The cycle records in device memory end with this many entries that match no state.
+constexpr int kCyclePoolPad = 64;
+
 // Stack compaction over registered reduction cycles; cap (entries per stack) at most kCompactMaxLen.
 constexpr int kCompactMaxLen = 4096;
 hipError_t launch_compact_stacks(const int32_t *cycle_head, const int32_t *cycle_pool, int pool_entries, int n_states,

@@ -2,6 +2,7 @@
 #include "symbol_edges.hpp"
 
 #include <algorithm>
+#include <deque>
 #include <memory>
 
 namespace pre3 {
@@ -111,39 +112,45 @@ struct Builder {
         nd.pend.clear();
     }
 
-    void expand(BuildNode &nd) {
-        while (!nd.pend.empty()) {
-            const std::vector<int32_t> &ps = pred[nd.floor];
-            if (ps.empty()) {                                   // the bottom of a stack is never popped
-                for (const Pending &u : nd.pend) nd.eff[u.col] = kEffNone;
+    // Grows the tree under `root` breadth first: the node budget then cuts the deepest conditions
+    // (right-recursive lists unroll without end) and never a shallow one that many stacks meet.
+    void expand(BuildNode &root) {
+        std::deque<BuildNode *> queue(1, &root);
+        while (!queue.empty()) {
+            BuildNode &nd = *queue.front();
+            queue.pop_front();
+            while (!nd.pend.empty()) {
+                const std::vector<int32_t> &ps = pred[nd.floor];
+                if (ps.empty()) {                               // the bottom of a stack is never popped
+                    for (const Pending &u : nd.pend) nd.eff[u.col] = kEffNone;
+                    nd.pend.clear();
+                    break;
+                }
+                if (nd.known >= max_known) { give_up(nd); break; }
+                if (ps.size() == 1) {                           // only one state can lie below: no test needed
+                    std::vector<Pending> in;
+                    in.swap(nd.pend);
+                    nd.floor = ps[0];
+                    nd.known++;
+                    nd.suffix.insert(nd.suffix.begin(), ps[0]);
+                    resolve(ps[0], in, nd);
+                    continue;
+                }
+                if (node_budget < (int)ps.size()) { give_up(nd); break; }
+                node_budget -= (int)ps.size();
+                for (int X : ps) {
+                    std::unique_ptr<BuildNode> ch(new BuildNode());
+                    ch->known = nd.known + 1;
+                    ch->floor = X;
+                    ch->suffix = nd.suffix;
+                    ch->suffix.insert(ch->suffix.begin(), X);
+                    ch->eff.assign(ncol, kEffNone);
+                    resolve(X, nd.pend, *ch);
+                    queue.push_back(ch.get());
+                    nd.children.emplace_back(X, std::move(ch));
+                }
                 nd.pend.clear();
-                return;
             }
-            if (nd.known >= max_known) { give_up(nd); return; }
-            if (ps.size() == 1) {                               // only one state can lie below: no test needed
-                std::vector<Pending> in;
-                in.swap(nd.pend);
-                nd.floor = ps[0];
-                nd.known++;
-                nd.suffix.insert(nd.suffix.begin(), ps[0]);
-                resolve(ps[0], in, nd);
-                continue;
-            }
-            if (node_budget < (int)ps.size()) { give_up(nd); return; }
-            node_budget -= (int)ps.size();
-            for (int X : ps) {
-                std::unique_ptr<BuildNode> ch(new BuildNode());
-                ch->known = nd.known + 1;
-                ch->floor = X;
-                ch->suffix = nd.suffix;
-                ch->suffix.insert(ch->suffix.begin(), X);
-                ch->eff.assign(ncol, kEffNone);
-                resolve(X, nd.pend, *ch);
-                expand(*ch);
-                nd.children.emplace_back(X, std::move(ch));
-            }
-            nd.pend.clear();
-            return;
         }
     }
 };
