@@ -226,3 +226,63 @@ def test_row_plus_staged_stack_beyond_the_lds_takes_three_launches():
         assert (data_d.cpu().numpy()[live] == data_h[live]).all(), s
         if s % 6 == 0:
             assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(states_h, data_h, len_h, v)).all(), s
+
+
+@pytest.mark.parametrize("call", ["advance", "advance_fill_mask", "jump_forward"])
+def test_stacks_that_were_never_compacted_are_compacted_whole(call):
+    """The caller binds stacks that a parser without the option has built: hundreds of entries that
+    hold long runs of traversals (several 64-entry chunks each, runs that cross chunk borders, runs
+    of different cycles one after the other).  The next call that changes them must leave what the
+    oracle leaves when it advances and then compacts the whole stack."""
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    v = bpe_like_vocab(2000, 8, BASE_SEED + 85)
+    ids = {tok: t for t, tok in reversed(list(enumerate(v.tokens)))}
+    cap = 1024
+    prefixes = [                                        # (document so far, the byte that comes next)
+        (b'["' + b"abcd" * 70, b"e"), (b"[1" + b"2345" * 60, b"6"), (b"[" + b"7," * 150, b"8"),
+        (b'{"k":1' + b',"k":2' * 60, b","), (b"[" + b" \n\t " * 60, b"1"), (b"[[" + b'"x",' * 90, b"0"),
+        (b"[" + b"[]," * 100, b"["), (b"[" + b"1," * 31 + b'"' + b"ab" * 40, b'"'),
+        (b"[" + b"1," * 40 + b"[" + b"2," * 50 + b'{"a":3' + b',"a":4' * 30, b"}"),
+        (b'["' + b"\\n" * 50 + b'",' + b"9," * 45 + b"10", b"]"), (b"[1,2,3", b","), (b"[", b"]"),
+    ]
+    B = len(prefixes)
+    plain = Oracle([G.JSON_RIGHT_RECURSIVE])
+    o = Oracle([G.JSON_RIGHT_RECURSIVE], compact_cycles=True)
+    lib = Pre3([G.JSON_RIGHT_RECURSIVE], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=cap,
+               compact_cycles=True)
+    data_h = np.zeros((B, cap), dtype=np.int32)
+    len_h = np.zeros(B, dtype=np.int32)
+    for b, (text, _) in enumerate(prefixes):
+        rc, st = plain.advance(plain.initial_stack(0), text)
+        assert rc == 0 and len(st) <= cap - 8
+        data_h[b, : len(st)], len_h[b] = st, len(st)
+    assert (len_h > 192).sum() >= 5 and int(len_h.max()) > 300          # several chunks of 64 entries
+    folded = [len(o.compact(list(data_h[b, : len_h[b]]))) for b in range(B)]
+    assert max(folded) <= 24, folded
+    states_h = data_h[np.arange(B), len_h - 1].copy()
+    states_d, data_d, len_d = (torch.from_numpy(a.copy()).to(dev) for a in (states_h, data_h, len_h))
+    err_d = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    tok = np.array([ids[nxt] for _, nxt in prefixes], dtype=np.int32)
+    if call == "jump_forward":
+        out = torch.zeros((B, 8), dtype=torch.uint8, device=dev)
+        cnt = torch.zeros(B, dtype=torch.int32, device=dev)
+        lib.jump_forward(out, cnt)
+        want_bytes, want_cnt = o.jump_forward_batch(states_h, data_h, len_h, 8)
+        assert cnt.cpu().numpy().tolist() == want_cnt.tolist()
+        assert (out.cpu().numpy() == want_bytes).all()
+    else:
+        if call == "advance":
+            lib.advance(torch.from_numpy(tok).to(dev))
+        else:
+            mask_d = torch.zeros((B, v.words), dtype=torch.int32, device=dev)
+            lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d)
+        assert not o.advance_batch(states_h, data_h, len_h, tok, v).any()
+        assert (err_d.cpu().numpy() == 0).all()
+        if call == "advance_fill_mask":
+            assert (mask_d.cpu().numpy().view(np.uint32) == o.fill_mask(states_h, data_h, len_h, v)).all()
+    assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), (len_d.cpu().numpy(), len_h)
+    live = np.arange(cap)[None, :] < len_h[:, None]
+    assert (data_d.cpu().numpy()[live] == data_h[live]).all()
+    assert lib.fault_count() == 0
