@@ -13,13 +13,6 @@ namespace {
 
 // ------------------------------------------------------------------- masked argmax
 
-// Order-preserving map of a non-NaN binary32 pattern to an unsigned key (-0 counts as +0).
-__device__ __forceinline__ uint32_t float_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0;
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
     const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
     return ((unsigned long long)hi << 32) | lo;
@@ -34,39 +27,116 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     return v;
 }
 
-// Greedy choice among the allowed tokens without writing the masked logits back: a row's logits
-// are read once (groups of 8 whose mask byte is zero are not read at all).  blockIdx.x = row,
-// blockIdx.y = segment of the row.  A lane keeps the largest value it has seen among allowed
-// entries and its id (ids ascend within a lane, so `>` keeps the first of equal values; a NaN
-// never compares greater; an allowed -inf, which can only win if nothing else is allowed, is
-// remembered separately by lanes that have seen nothing larger); lanes and waves are then
-// combined through the packed word
-//   key(value) << 32 | ~id,
-// whose maximum is the largest value and, among equal values, the smallest id; 0 = no candidate.  With one segment
-// per row the block writes out[b] itself; otherwise it stores its word in partial[b][segment]
-// and masked_argmax_finish_kernel combines the segments.  (Combining them inside this kernel
-// with device-scope atomics and a last-arrival counter was measured: rows that finish early
-// then cost tens of microseconds per launch.)  The mask bytes of the next pass are fetched
-// while the logits of the current one are in flight.
+// Signed order key of a bf16 pattern: for non-NaN patterns a larger key is a larger value.  Valid
+// values map to kOrderNegInf .. kOrderPosInf (-0 to -1, +0 to 0), negative NaN patterns below
+// kOrderNegInf, positive NaN patterns above kOrderPosInf.
+constexpr int kOrderNegInf = -32641, kOrderPosInf = 32640;
+__device__ __forceinline__ int bf16_order(uint32_t h) {
+    const int v = (int)(int16_t)h;
+    return v ^ ((v >> 15) & 0x7FFF);
+}
+typedef short PackedS16 __attribute__((ext_vector_type(2)));
+// The same for the two patterns of one register; halves the AND mask `allow` clears get the lowest key.
+__device__ __forceinline__ uint32_t bf16_order_pair(uint32_t x, uint32_t allow) {
+    const uint32_t negative = __builtin_bit_cast(uint32_t, __builtin_bit_cast(PackedS16, x) >> 15);
+    const uint32_t key = x ^ (negative & 0x7FFF7FFFu);
+    return (key & allow) | (~allow & 0x80008000u);
+}
+__device__ __forceinline__ uint32_t packed_max_s16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(PackedS16, a), __builtin_bit_cast(PackedS16, b)));
+}
+// A lane's or a block's candidate: order key (with -0 counted as +0) above the complement of the id,
+// so that the largest word is the largest value and, among equal values, the smallest id; 0 = none.
+__device__ __forceinline__ unsigned long long argmax_word(int order, int id) {
+    if (order == -1) order = 0;
+    return ((unsigned long long)(uint32_t)(order + 32768) << 32) | (0xFFFFFFFFu - (uint32_t)id);
+}
+
 constexpr int kArgBlock = 1024;
 constexpr int kArgUnroll = 4;
+
+__device__ __forceinline__ unsigned long long argmax_block_max(unsigned long long mine, unsigned long long *s_part, int tid) {
+    mine = wave_max_u64(mine);
+    __syncthreads();                                    // s_part may still be read from an earlier round
+    if ((tid & 63) == 0) s_part[tid >> 6] = mine;
+    __syncthreads();
+    if (tid < 64) {
+        mine = wave_max_u64(tid < kArgBlock / 64 ? s_part[tid] : 0ull);
+        if (tid == 0) s_part[kArgBlock / 64] = mine;
+    }
+    __syncthreads();
+    return s_part[kArgBlock / 64];
+}
+
+// The segment's candidate with one float compare per token: a lane keeps the largest value it has
+// seen among allowed entries and its id (ids ascend within a lane, so `>` keeps the first of equal
+// values, -0 and +0 are equal, a NaN never compares greater); an allowed -inf, which can only win if
+// nothing else is allowed, is remembered separately by lanes that have seen nothing larger.  Used
+// for the rare rows on which the packed keys of masked_argmax_kernel cannot decide.
+__device__ __noinline__ unsigned long long argmax_segment_by_compare(const uint16_t *__restrict__ lrow,
+                                                                     const uint8_t *__restrict__ mrow, int g_lo, int g_hi,
+                                                                     int vocab, int tid) {
+    float best_v = -INFINITY;
+    int best_t = -1, ninf_t = -1;
+    for (int g = g_lo + tid; g < g_hi; g += kArgBlock) {
+        const uint32_t mu = mrow[g];
+        if (mu == 0u) continue;
+        for (int k = 0; k < 8 && g * 8 + k < vocab; ++k) {
+            if (!((mu >> k) & 1u)) continue;
+            const uint32_t h = lrow[g * 8 + k];
+            const float f = __uint_as_float(h << 16);
+            if (f > best_v) { best_v = f; best_t = g * 8 + k; }
+            if (best_t < 0 && ninf_t < 0 && h == 0xFF80u) ninf_t = g * 8 + k;
+        }
+    }
+    if (best_t >= 0) return argmax_word(bf16_order(__float_as_uint(best_v) >> 16), best_t);
+    if (ninf_t >= 0) return argmax_word(kOrderNegInf, ninf_t);
+    return 0ull;
+}
+
+// Greedy choice among the allowed tokens without writing the masked logits back: a row's logits
+// are read once (groups of 8 whose mask byte is zero are not read at all).  blockIdx.x = row,
+// blockIdx.y = segment of the row.  The stream is bound by instruction issue as much as by HBM, so
+// the inner loop does as little as it can per token: the two bf16 patterns of a register become
+// two signed 16-bit order keys with packed arithmetic (masked halves get the lowest key; the mask
+// byte of a group expands to its four AND masks through a 4 KB table in LDS), packed maxima fold a
+// group of 8 into its largest key, and only when that beats the lane's best so far (strictly: the
+// first of equal values stays) the lane keeps the key, the group's index, registers and mask byte.
+// At the end a lane finds its winner's position inside the kept group; lanes, waves and segments
+// are combined through argmax_word.  Two cases the keys cannot decide are left to
+// argmax_segment_by_compare, for the whole segment: a positive NaN pattern has a key above +inf's
+// (the block's best key shows it), and -0 and +0 have different keys but are equal values (the
+// block's best value is zero).  With one segment per row the block writes out[b] itself; otherwise
+// it stores its word in partial[b][segment] and masked_argmax_finish_kernel combines the segments.
+// (Combining them inside this kernel with device-scope atomics and a last-arrival counter was
+// measured: rows that finish early then cost tens of microseconds per launch.)  The mask bytes of
+// the next pass are fetched while the logits of the current one are in flight.
 __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int groups_per_seg, int vec_ok, unsigned long long *__restrict__ partial, int32_t *__restrict__ out) {
-    __shared__ unsigned long long s_part[kArgBlock / 64];
+    __shared__ unsigned long long s_part[kArgBlock / 64 + 1];
+    __shared__ uint4 s_expand[256];                     // mask byte -> AND masks of the group's four registers
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x;
     const int groups = (vocab + 7) >> 3;
     const int g_lo = seg * groups_per_seg, g_hi = min(groups, g_lo + groups_per_seg);
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
-    float best_v = -INFINITY;
-    int best_t = -1, ninf_t = -1;                       // ninf_t: first allowed entry that is exactly -inf
+    if (tid < 256) {
+        uint32_t a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
+        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
+    }
+    int best = kOrderNegInf - 1, best_g = -1;           // only a valid value (or a positive NaN pattern) beats the start
+    uint4 best_x = make_uint4(0, 0, 0, 0);
+    uint32_t best_m = 0u;
     uint32_t m[kArgUnroll], m_next[kArgUnroll];
 #pragma unroll
     for (int u = 0; u < kArgUnroll; ++u) {
         const int g = g_lo + tid + u * kArgBlock;
         m[u] = g < g_hi ? mrow[g] : 0u;
     }
+    __syncthreads();                                    // s_expand
     for (int g0 = g_lo + tid; g0 < g_hi; g0 += kArgBlock * kArgUnroll) {
         uint4 v[kArgUnroll];
 #pragma unroll
@@ -81,49 +151,46 @@ __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
         }
 #pragma unroll
         for (int u = 0; u < kArgUnroll; ++u) {
-            const uint32_t mu = m[u];
+            uint32_t mu = m[u];
             if (mu == 0u) continue;
-            const int t0 = (g0 + u * kArgBlock) * 8;
-            if (vec_ok && t0 + 8 <= vocab) {
-                const uint32_t x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float f0 = (mu >> (2 * k)) & 1u ? __uint_as_float(x[k] << 16) : -INFINITY;
-                    const float f1 = (mu >> (2 * k + 1)) & 1u ? __uint_as_float(x[k] & 0xFFFF0000u) : -INFINITY;
-                    if (f0 > best_v) { best_v = f0; best_t = t0 + 2 * k; }
-                    if (f1 > best_v) { best_v = f1; best_t = t0 + 2 * k + 1; }
-                }
-                if (best_t < 0 && ninf_t < 0) {
-#pragma unroll
-                    for (int k = 7; k >= 0; --k) {     // descending: the smallest k is assigned last
-                        const uint32_t h = (k & 1) ? (x[k >> 1] >> 16) : (x[k >> 1] & 0xFFFFu);
-                        if (((mu >> k) & 1u) && h == 0xFF80u) ninf_t = t0 + k;
-                    }
-                }
-            } else {                                   // ragged tail or unaligned rows: one logit at a time
-                for (int k = 0; k < 8 && t0 + k < vocab; ++k) {
-                    const uint32_t h = lrow[t0 + k];
-                    const float f = (mu >> k) & 1u ? __uint_as_float(h << 16) : -INFINITY;
-                    if (f > best_v) { best_v = f; best_t = t0 + k; }
-                    if (best_t < 0 && ninf_t < 0 && ((mu >> k) & 1u) && h == 0xFF80u) ninf_t = t0 + k;
-                }
+            const int g = g0 + u * kArgBlock, t0 = g * 8;
+            if (!(vec_ok && t0 + 8 <= vocab)) {        // ragged tail or unaligned rows: one logit at a time
+                uint32_t x[4] = {0u, 0u, 0u, 0u};
+                if (t0 + 8 > vocab) mu &= (1u << (vocab - t0)) - 1u;
+                for (int k = 0; k < 8 && t0 + k < vocab; ++k) x[k >> 1] |= (uint32_t)lrow[t0 + k] << (16 * (k & 1));
+                v[u] = make_uint4(x[0], x[1], x[2], x[3]);
+                if (mu == 0u) continue;
+            }
+            const uint4 allow = s_expand[mu];
+            const uint32_t k01 = packed_max_s16(bf16_order_pair(v[u].x, allow.x), bf16_order_pair(v[u].y, allow.y));
+            const uint32_t k23 = packed_max_s16(bf16_order_pair(v[u].z, allow.z), bf16_order_pair(v[u].w, allow.w));
+            const uint32_t k = packed_max_s16(k01, k23);
+            const int group_best = max((int)(int16_t)(k & 0xFFFFu), (int)k >> 16);
+            if (group_best > best) {
+                best = group_best;
+                best_g = g;
+                best_x = v[u];
+                best_m = mu;
             }
         }
 #pragma unroll
         for (int u = 0; u < kArgUnroll; ++u) m[u] = m_next[u];
     }
     unsigned long long mine = 0ull;
-    if (best_t >= 0) mine = ((unsigned long long)float_key(best_v) << 32) | (0xFFFFFFFFu - (uint32_t)best_t);
-    else if (ninf_t >= 0) mine = ((unsigned long long)float_key(-INFINITY) << 32) | (0xFFFFFFFFu - (uint32_t)ninf_t);
-    mine = wave_max_u64(mine);
-    if ((tid & 63) == 0) s_part[tid >> 6] = mine;
-    __syncthreads();
-    if (tid < 64) {
-        mine = wave_max_u64(tid < kArgBlock / 64 ? s_part[tid] : 0ull);
-        if (tid == 0) s_part[0] = mine;
+    if (best_g >= 0) {
+        const uint32_t x[4] = {best_x.x, best_x.y, best_x.z, best_x.w};
+        int first = 0;
+#pragma unroll
+        for (int k = 7; k >= 0; --k) {                  // descending: the smallest k is assigned last
+            const uint32_t h = (k & 1) ? (x[k >> 1] >> 16) : (x[k >> 1] & 0xFFFFu);
+            if (((best_m >> k) & 1u) && bf16_order(h) == best) first = k;
+        }
+        mine = argmax_word(best, best_g * 8 + first);
     }
-    __syncthreads();
-    mine = s_part[0];
+    mine = argmax_block_max(mine, s_part, tid);
+    const int order = (int)(uint32_t)(mine >> 32) - 32768;
+    if (mine != 0ull && (order > kOrderPosInf || order == 0))
+        mine = argmax_block_max(argmax_segment_by_compare(lrow, mrow, g_lo, g_hi, vocab, tid), s_part, tid);
     if (n_seg > 1) {
         if (tid == 0) partial[(size_t)b * n_seg + seg] = mine;
         return;
@@ -302,10 +369,10 @@ __device__ __noinline__ uint32_t topk_cut_list(unsigned long long *list, int n, 
 }
 
 template <int kBlock>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
+__device__ __forceinline__ void masked_topk_chunked(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out,
-    int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
+    int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals, int b, int seg, int n_seg) {
     constexpr int kWaves = kBlock / 64, kChunk = kTopkPerThread * kBlock;
     __shared__ unsigned long long s_list[kWaves * kTopkRegion];
     __shared__ int s_nz[kWaves];
@@ -314,7 +381,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
     __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
     __shared__ unsigned long long s_short[kBlock];        // the few words left at the end, one per thread
     __shared__ int s_total;
-    const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 256) {
         uint32_t a[4];
 #pragma unroll
@@ -642,6 +709,188 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
         if (r * 64 + lane < n_mine && rank[r] < k) emit(rank[r], w[r]);
 }
 
+template <int kBlock>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_kernel(
+    const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
+    int n_words, int vec_ok, int k, int chunks_per_seg, unsigned long long *__restrict__ out,
+    int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_vals) {
+    masked_topk_chunked<kBlock>(logits, bitmask, vocab, row_stride, n_words, vec_ok, k, chunks_per_seg, out, out_ids, out_vals,
+                                blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// The stored bf16 pattern behind a key of bf16_key, or -1 for the key of zero, which -0 and +0 share.
+__device__ __forceinline__ int bf16_pattern_of_key(uint32_t key) {
+    const uint32_t folded = key + 0x7Fu;
+    if (folded == 0x8000u) return -1;
+    return (folded & 0x8000u) ? (int)(folded & 0x7FFFu) : (int)((0x10000u - folded) & 0xFFFFu);
+}
+
+// The k best of a whole row by one block of 1,024 threads that keeps the row in registers: rows of at
+// most kTopkRowGroups * 1,024 groups of 8 tokens (131,072 tokens), 16-byte aligned.  Every thread
+// issues the loads of its mask bytes and of its up to 16 groups of logits at once (a group is read
+// whatever its mask byte says: no load waits for another one) and turns them into 64 registers of
+// packed 16-bit keys (0 = masked, NaN or beyond the vocabulary), with the packed maximum of every
+// group and the thread's maximum.  What follows the stream is short:
+//   (1) a lower bound M of the k-th largest key: every wave takes the q-th largest of its 64 thread
+//       maxima (q = ceil(k / 16); a wave with fewer holders its smallest); if these quotas add up to
+//       k, at least k keys reach the smallest of the waves' values (one barrier);
+//   (2) the few threads whose maximum reaches M look through the groups whose maximum does and
+//       append those keys, as words, to one list in LDS;
+//   (3) the list (little more than k words) is ranked by all threads together -- a word's rank is the
+//       number of larger words, counted in slices by several threads and added up in LDS -- and the
+//       k best write their id and pattern (rebuilt from the key, read back only for a zero) in order.
+// A list that would pass kTopkRowList words (thousands of ties with the bound, or quotas that do not
+// add up to k on a dense row) is given up: the block then takes the row chunk by chunk with
+// masked_topk_chunked, which has no such limit.
+// (Measured and dropped: taking the bound from half of the row while the other half is still in
+// flight, with the second half filtered as it arrives -- the waves of a block finish their halves
+// microseconds apart, so the barrier gains nothing, and the looser bound doubles the list.)
+constexpr int kTopkRowGroups = 16;
+constexpr int kTopkRowList = 512;
+__global__ __launch_bounds__(kTopkBlockWide) __attribute__((amdgpu_waves_per_eu(4))) void masked_topk_row_kernel(
+    const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
+    int n_words, int k, unsigned long long *__restrict__ workspace, int32_t *__restrict__ out_ids,
+    uint16_t *__restrict__ out_vals) {
+    constexpr int kBlock = kTopkBlockWide, kWaves = kBlock / 64, kG = kTopkRowGroups;
+    __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
+    __shared__ unsigned long long s_cand[kTopkRowList];
+    __shared__ int s_rank[kTopkRowList];
+    __shared__ int s_nz[kWaves];
+    __shared__ uint32_t s_wbound[kWaves];
+    __shared__ int s_count;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 256) {
+        uint32_t a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
+        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
+    }
+    s_rank[tid] = 0;
+    if (tid == 0) s_count = 0;
+    const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
+    const uint16_t *lrow = logits + (size_t)b * row_stride;
+    const int groups = (vocab + 7) >> 3, n_mask_bytes = n_words * 4;
+    uint32_t m[kG];
+    uint4 v[kG];
+#pragma unroll
+    for (int u = 0; u < kG; ++u) {
+        const int g = tid + u * kBlock;
+        m[u] = (g < groups && g < n_mask_bytes) ? mrow[g] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < kG; ++u) {
+        const int g = tid + u * kBlock;
+        v[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (g * 8 + 8 <= vocab) v[u] = stream_load(lrow + (size_t)g * 8);
+        else if (g < groups) v[u] = topk_load_group_unaligned(lrow, g * 8, vocab);   // the group the vocabulary ends in
+    }
+    lds_barrier();                                            // s_expand, s_rank, s_count
+    uint32_t kp[kG * 4], gmax2[kG];
+    uint32_t best2 = 0u;
+#pragma unroll
+    for (int u = 0; u < kG; ++u) {
+        const uint4 allow = s_expand[m[u]];
+        const uint32_t x[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, a[4] = {allow.x, allow.y, allow.z, allow.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kp[u * 4 + j] = bf16_key_pair(x[j]) & a[j];
+        gmax2[u] = packed_max_u16(packed_max_u16(kp[u * 4], kp[u * 4 + 1]), packed_max_u16(kp[u * 4 + 2], kp[u * 4 + 3]));
+        best2 = packed_max_u16(best2, gmax2[u]);
+    }
+    if ((best2 & 0xFFFFu) > kTopkKeyMax || (best2 >> 16) > kTopkKeyMax) {          // an allowed NaN: its key goes
+        best2 = 0u;
+#pragma unroll
+        for (int u = 0; u < kG; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = kp[u * 4 + j] & 0xFFFFu, hi = kp[u * 4 + j] >> 16;
+                kp[u * 4 + j] = (lo > kTopkKeyMax ? 0u : lo) | ((hi > kTopkKeyMax ? 0u : hi) << 16);
+            }
+            gmax2[u] = packed_max_u16(packed_max_u16(kp[u * 4], kp[u * 4 + 1]), packed_max_u16(kp[u * 4 + 2], kp[u * 4 + 3]));
+            best2 = packed_max_u16(best2, gmax2[u]);
+        }
+    }
+    const uint32_t best = (best2 & 0xFFFFu) > (best2 >> 16) ? (best2 & 0xFFFFu) : (best2 >> 16);
+    // (1) the bound
+    const int quota = (k + kWaves - 1) / kWaves;
+    const int nz_wave = __popcll(__ballot(best != 0u));
+    uint32_t wave_m = 0x10000u;                                // no candidate in this wave
+    if (nz_wave > 0) {
+        int reached;
+        wave_m = wave_key_threshold<1>([&](int) { return best; }, nz_wave, nz_wave < quota ? nz_wave : quota, &reached);
+    }
+    if (lane == 0) { s_nz[wave] = nz_wave; s_wbound[wave] = wave_m; }
+    lds_barrier();
+    uint32_t bound = 0x10000u;
+    int reach_bound = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        bound = s_wbound[w] < bound ? s_wbound[w] : bound;
+        reach_bound += s_nz[w] < quota ? s_nz[w] : quota;
+    }
+    auto emit = [&](int rank, unsigned long long word) {
+        if (word != 0ull) {
+            const uint32_t id = kTopkIdMask - ((uint32_t)word & kTopkIdMask);
+            out_ids[(size_t)b * k + rank] = (int32_t)id;
+            if (out_vals) {
+                const int pattern = bf16_pattern_of_key((uint32_t)(word >> kTopkIdBits));
+                out_vals[(size_t)b * k + rank] = pattern >= 0 ? (uint16_t)pattern : lrow[id];
+            }
+        } else {
+            out_ids[(size_t)b * k + rank] = -1;
+            if (out_vals) out_vals[(size_t)b * k + rank] = 0xFF80u;
+        }
+    };
+    if (bound == 0x10000u) {                                  // nothing is allowed (or only NaN)
+        if (tid < k) emit(tid, 0ull);
+        return;
+    }
+    if (reach_bound < k) bound = 1u;                          // the quotas do not add up: every candidate
+    // (2) the list
+    if (__any(best >= bound)) {
+        const uint32_t below = (bound - 1u) * 0x10001u;
+#pragma unroll
+        for (int u = 0; u < kG; ++u) {
+            if (packed_sub_sat_u16(gmax2[u], below) == 0u) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t reach = packed_sub_sat_u16(kp[u * 4 + j], below);
+                const uint32_t t0 = (uint32_t)(tid + u * kBlock) * 8u + (uint32_t)j * 2u;
+                if (reach & 0xFFFFu) {
+                    const int slot = atomicAdd(&s_count, 1);
+                    if (slot < kTopkRowList) s_cand[slot] = topk_word(kp[u * 4 + j] & 0xFFFFu, t0);
+                }
+                if (reach >> 16) {
+                    const int slot = atomicAdd(&s_count, 1);
+                    if (slot < kTopkRowList) s_cand[slot] = topk_word(kp[u * 4 + j] >> 16, t0 + 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int n = s_count;
+    if (n > kTopkRowList) {                                   // same in every thread
+        masked_topk_chunked<kBlock>(logits, bitmask, vocab, row_stride, n_words, 1, k,
+                                    (vocab + kTopkPerThread * kBlock - 1) / (kTopkPerThread * kBlock), workspace, out_ids, out_vals,
+                                    b, 0, 1);
+        return;
+    }
+    // (3) ranks: thread (slice, word) counts the larger words of its slice of the list
+    if (tid >= n && tid < k) emit(tid, 0ull);
+    if (n == 0) return;
+    const int slices = kBlock / n > 0 ? kBlock / n : 1, per = (n + slices - 1) / slices;
+    const int word_at = tid % n, slice = tid / n;
+    if (slice < slices) {
+        const unsigned long long mine = s_cand[word_at];
+        const int j_end = (slice + 1) * per < n ? (slice + 1) * per : n;
+        int larger = 0;
+#pragma unroll 4
+        for (int j = slice * per; j < j_end; ++j) larger += s_cand[j] > mine ? 1 : 0;
+        if (larger) atomicAdd(&s_rank[word_at], larger);
+    }
+    __syncthreads();
+    if (tid < n && s_rank[tid] < k) emit(s_rank[tid], s_cand[tid]);
+}
+
 // Merges the segments' candidates of one row with one wave: n_cand words (0 = empty), at most
 // kTopkFinishPer per lane.  As above, the k-th largest of the 64 per-lane maxima bounds the k-th
 // largest word from below; the words that reach it go to an LDS list.  Up to 256 listed words are
@@ -792,6 +1041,12 @@ hipError_t launch_masked_topk(const uint16_t *logits, const uint32_t *bitmask, i
     if (!masked_topk_fits(vocab, k)) return hipErrorInvalidValue;
     const int n_words = (vocab + 31) / 32;
     const int vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
+    if (batch >= n_compute_units && vec_ok && (vocab + 7) / 8 <= kTopkRowGroups * kTopkBlockWide) {
+        // a block per row that keeps the whole row in registers
+        hipLaunchKernelGGL(masked_topk_row_kernel, dim3(batch), dim3(kTopkBlockWide), 0, stream, logits, bitmask, vocab,
+                           row_stride, n_words, k, workspace, out_ids, out_vals);
+        return hipGetLastError();
+    }
     if (batch >= n_compute_units && batch < 2 * n_compute_units) {
         // a row per compute unit and no second block beside it: sixteen waves take the row
         hipLaunchKernelGGL(masked_topk_kernel<kTopkBlockWide>, dim3(batch, 1), dim3(kTopkBlockWide), 0, stream, logits, bitmask,

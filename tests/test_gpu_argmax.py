@@ -77,6 +77,15 @@ def test_masked_argmax_values_and_layouts(V, B, stride_pad, offset):
         allowed = ((mask[7][np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1).astype(bool)
         logits[7, allowed] = 0xFF80
         logits[7, np.flatnonzero(allowed)[:3]] = 0x7FC0
+    if B > 8:                                                 # the largest value is zero, of both signs, -0 first
+        logits[8] |= 0x8000
+        logits[8, 5::11] = 0x8000
+        logits[8, 9::13] = 0x0000
+        mask[8] = _special_masks(rng, 1, V)[0]
+    if B > 12:                                                # the same with few tokens allowed, and only -0
+        logits[12] |= 0x8000
+        logits[12, 3::7] = 0x8000
+        mask[12, 1:] &= mask[11, 1:]
     want = oracle_masked_argmax(logits, mask, V)
     stride = V + stride_pad
     flat = torch.full((B * stride + offset + 8,), 0x1234, dtype=torch.int16, device=dev)
