@@ -2,6 +2,7 @@
 // row from what the descent found.  Shared by the mask kernel and the advance+mask kernel.
 #pragma once
 #include "effect_hash.hpp"
+#include "stream_access.hpp"
 #include "walk.hpp"
 
 namespace pre3 {
@@ -174,7 +175,7 @@ __device__ __forceinline__ void build_and_store_row(const DevTables &T, const De
         // the row is exactly a materialised row: copy it without staging it in LDS
         const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec + v_lo;
         uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row) + v_lo;
-        for (int w = tid; w < v_cnt; w += kThreads) dst4[w] = src[w];
+        for (int w = tid; w < v_cnt; w += kThreads) stream_store(src[w], dst4 + w);
         return;
     }
     if (mode == kRowFast && plan.dense >= 0) {
@@ -217,7 +218,7 @@ __device__ __forceinline__ void build_and_store_row(const DevTables &T, const De
     __syncthreads();
     if (dst_vector_ok) {
         uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row) + v_lo;
-        for (int w = tid; w < v_cnt; w += kThreads) dst4[w] = bits4[w];
+        for (int w = tid; w < v_cnt; w += kThreads) stream_store(bits4[w], dst4 + w);
     } else {
         for (int w = w_lo + tid; w < min(w_hi, T.n_words); w += kThreads) dst_row[w] = bits[w - w_lo];
     }
