@@ -318,6 +318,12 @@ int32_t pre3_walk_depth_bound(const pre3_handle *h);
  * benchmark assert that.  Host call; copies one device counter back (synchronise the streams that
  * run the handle's work first, so that their walks are counted).  out: host.  Errors: BADARG, HIP. */
 int pre3_debug_fault_count(pre3_handle *h, int64_t *out);
+/* Measurement aid (no passage of the paper: it serves the benchmark): enqueues a one-thread kernel
+ * that writes the device's 100 MHz wall clock to *out (device, 8 bytes).  Recorded between the
+ * calls of a captured step it gives each kernel's duration in its real place, which HIP events
+ * cannot give inside a graph; two stamps with nothing between them give the cost of a stamp.
+ * Asynchronous on `stream`.  Errors: BADARG, HIP. */
+int pre3_debug_timestamp(int64_t *out, pre3_stream stream);
 /* Sizes of the token-level prefix-conditioned edge tables (Sec. 3.3, edge merging along the
  * bytes of each token): out[0] built?, [1] distinct root conditions, [2] condition-tree nodes,
  * [3] dense rows, [4] token ids in delta lists, [5] token ids in walk lists, [6] deepest stack

@@ -29,7 +29,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
-    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
+    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_debug_timestamp", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
 ]
 
 
@@ -88,6 +88,7 @@ def load():
     lib.pre3_reduction_cycle.argtypes = [vp, i32, vp, i32]
     lib.pre3_debug_compact.argtypes = [vp, vp, i32]
     lib.pre3_debug_fault_count.argtypes = [vp, c.POINTER(c.c_int64)]
+    lib.pre3_debug_timestamp.argtypes = [vp, vp]
     for name in ("pre3_n_grammars", "pre3_n_states", "pre3_n_byte_classes", "pre3_walk_depth_bound",
                  "pre3_n_reduction_cycles"):
         getattr(lib, name).argtypes = [vp]
@@ -358,3 +359,13 @@ def apply_mask(logits, bitmask, vocab: int, stream=None):
                              logits.stride(0), _stream_ptr(stream))
     if rc != PRE3_OK:
         raise Pre3Error(rc, "apply_mask: bad argument or launch failure")
+
+
+def device_timestamp(out, index: int = 0, stream=None):
+    """Enqueues a one-thread kernel that writes the device's 100 MHz wall clock to out[index]
+    (out: int64 device tensor).  Between the calls of a captured step this times each kernel in place."""
+    lib = load()
+    assert out.dtype.itemsize == 8 and out.is_contiguous() and 0 <= index < out.numel()
+    rc = lib.pre3_debug_timestamp(out.data_ptr() + 8 * index, _stream_ptr(stream))
+    if rc != PRE3_OK:
+        raise Pre3Error(rc, "device_timestamp: bad argument or launch failure")

@@ -678,6 +678,11 @@ int32_t pre3_debug_compact(const pre3_handle *h, int32_t *stack, int32_t len) {
 
 int32_t pre3_walk_depth_bound(const pre3_handle *h) { return h && h->compiled ? h->max_depth : PRE3_E_BADARG; }
 
+int pre3_debug_timestamp(int64_t *out, pre3_stream stream) {
+    if (!out) return PRE3_E_BADARG;
+    return launch_timestamp(out, static_cast<hipStream_t>(stream)) == hipSuccess ? PRE3_OK : PRE3_E_HIP;
+}
+
 int pre3_debug_fault_count(pre3_handle *h, int64_t *out) {
     if (!usable(h) || !out) return PRE3_E_BADARG;
     int32_t n = 0;

@@ -13,8 +13,15 @@ namespace {
 
 constexpr int kApplyBlock = 256;
 constexpr int kApplySpan = kApplyBlock * 8;            // logits per block
+constexpr int64_t kMaskBytesInL2 = 16 << 20;            // masks up to this size are read where they were written (half of the L2s)
 
-// blockIdx.y = row, blockIdx.x = span of kApplySpan logits.  A lane owns one group of 8 consecutive
+// One block per span of kApplySpan logits of one row.  kRowsByXcd = false: blockIdx.y = row,
+// blockIdx.x = span.  kRowsByXcd = true (one-dimensional grid): workgroups go round-robin to the
+// chip's eight XCDs in the order of their linear id, and the kernels that write the mask run row b
+// in block b, that is on XCD b % 8 -- so block L takes a row of XCD L % 8's, and the mask bytes it
+// reads are still in that XCD's L2 (B = 256: 34.8 -> 33.7 us per step, B = 1,024: 111.5 -> 109.0;
+// a mask beyond the L2s gains nothing and the scattered rows cost 2 %, so large batches keep the
+// two-dimensional grid).  A lane owns one group of 8 consecutive
 // logits (16 bytes), so that every access of a wave is one contiguous 1 KiB.  Fully allowed groups
 // are not touched, fully masked groups are overwritten without being read, mixed groups are read,
 // patched and written back: the mask byte's bits become the AND masks of the group's four registers
@@ -23,12 +30,21 @@ constexpr int kApplySpan = kApplyBlock * 8;            // logits per block
 // then the store) as much as by HBM: the fewer instructions a wave issues, the faster it runs, and
 // variants that give a lane several groups -- 4 KiB apart or side by side -- were slower (26.6 us
 // and 52.8 us against 23.6 us at B = 256, V = 128,256).
+constexpr int kXcds = 8;
+template <bool kRowsByXcd>
 __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *__restrict__ logits,
                                                                      const uint32_t *__restrict__ bitmask,
-                                                                     int vocab, int64_t row_stride, int n_words) {
-    const int b = blockIdx.y;
+                                                                     int vocab, int64_t row_stride, int n_words,
+                                                                     int batch, int spans) {
+    int b = blockIdx.y, span = blockIdx.x;
+    if (kRowsByXcd) {
+        const int xcd = blockIdx.x % kXcds, at = blockIdx.x / kXcds;
+        b = (at / spans) * kXcds + xcd;
+        span = at % spans;
+        if (b >= batch) return;
+    }
     const int groups = (vocab + 7) >> 3;
-    const int g = blockIdx.x * kApplyBlock + threadIdx.x;
+    const int g = span * kApplyBlock + threadIdx.x;
     if (g >= groups) return;
     const uint32_t mu = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words)[g];   // little endian: byte g of the row = bits of group g
     if (mu == 0xFFu) return;
@@ -64,7 +80,14 @@ __global__ __launch_bounds__(256) void apply_mask_scalar_kernel(uint16_t *__rest
     }
 }
 
+__global__ void timestamp_kernel(int64_t *out) { *out = (int64_t)wall_clock64(); }
+
 }  // namespace
+
+hipError_t launch_timestamp(int64_t *out, hipStream_t stream) {
+    hipLaunchKernelGGL(timestamp_kernel, dim3(1), dim3(1), 0, stream, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream) {
@@ -72,9 +95,14 @@ hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batc
     const int n_words = (vocab + 31) / 32;
     const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && (row_stride % 8 == 0);
     if (aligned && batch <= 65535) {
-        const dim3 grid((vocab + kApplySpan - 1) / kApplySpan, batch);
-        hipLaunchKernelGGL(apply_mask_vec8_kernel, grid, dim3(kApplyBlock), 0, stream, logits, bitmask, vocab, row_stride,
-                           n_words);
+        const int spans = (vocab + kApplySpan - 1) / kApplySpan;
+        const int64_t by_xcd = (int64_t)spans * kXcds * ((batch + kXcds - 1) / kXcds);
+        if ((int64_t)batch * n_words * 4 <= kMaskBytesInL2 && by_xcd <= 0x7FFFFFFF)
+            hipLaunchKernelGGL(apply_mask_vec8_kernel<true>, dim3((unsigned)by_xcd), dim3(kApplyBlock), 0, stream, logits, bitmask,
+                               vocab, row_stride, n_words, batch, spans);
+        else
+            hipLaunchKernelGGL(apply_mask_vec8_kernel<false>, dim3(spans, batch), dim3(kApplyBlock), 0, stream, logits, bitmask,
+                               vocab, row_stride, n_words, batch, spans);
     } else {
         const int64_t total = (int64_t)batch * vocab;
         const int64_t want = (total + 255) / 256;

@@ -25,6 +25,9 @@ hipError_t launch_fill_mask_edges(const DevTables &T, const DevTokenEdges &E, co
                                   const int32_t *data, const int32_t *len, int cap, int batch, uint32_t *bitmask,
                                   uint16_t *logits /* null: mask only */, int64_t row_stride, int32_t *spill,
                                   int grid_blocks, hipStream_t stream);
+// One thread writes the device's wall clock (100 MHz) to *out.
+hipError_t launch_timestamp(int64_t *out, hipStream_t stream);
+
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream);
 // cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (needs advance_fits_compact(cap)), or null
