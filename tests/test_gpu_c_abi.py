@@ -59,3 +59,37 @@ def test_plain_c_program_matches_the_oracle(tmp_path):
     proc = subprocess.run([BINARY, str(path)], capture_output=True, text=True, timeout=120)
     assert proc.returncode == 0 and "C ABI OK" in proc.stdout, (proc.returncode, proc.stdout, proc.stderr)
     assert int(jn.sum()) > 0 and (err != 0).any() and (err == 0).any()
+
+
+def test_device_timestamps_follow_stream_order_and_time_a_kernel():
+    """pre3_debug_timestamp: stamps recorded around a masking launch, eagerly and inside a captured graph,
+    increase in stream order, and the launch they bracket takes a plausible time (the clock runs at 100 MHz)."""
+    import torch
+    from paper_2506_03887_amd import apply_mask
+    from paper_2506_03887_amd.binding import Pre3Error, device_timestamp, load
+    dev = torch.device("cuda:0")
+    B, V = 64, 32000
+    W = (V + 31) // 32
+    logits = torch.randn((B, V), device=dev).to(torch.bfloat16)
+    mask = torch.full((B, W), 0x55555555, dtype=torch.int32, device=dev)
+    stamps = torch.zeros(6, dtype=torch.int64, device=dev)
+
+    def bracket(first):
+        device_timestamp(stamps, first)
+        device_timestamp(stamps, first + 1)
+        apply_mask(logits, mask, V)
+        device_timestamp(stamps, first + 2)
+
+    bracket(0)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        bracket(3)
+    g.replay()
+    torch.cuda.synchronize()
+    t = stamps.cpu().numpy()
+    assert (np.diff(t[:3]) > 0).all() and (np.diff(t[3:]) > 0).all() and t[3] > t[2], t
+    for first in (0, 3):
+        launch_us = ((t[first + 2] - t[first + 1]) - (t[first + 1] - t[first])) * 0.01
+        assert -2.0 < launch_us < 200.0, (first, launch_us, t)
+    assert load().pre3_debug_timestamp(None, None) < 0          # a null pointer is refused, nothing is launched
