@@ -307,6 +307,31 @@ def test_apply_mask_layouts(V, stride, offset):
     assert int(flat[:offset].abs().sum()) == 0 and int(flat[offset + B * stride:].abs().sum()) == 0
 
 
+@pytest.mark.parametrize("B", [1003, 1100])
+def test_apply_mask_on_both_sides_of_the_grid_switch(B):
+    """pre3_apply_mask orders its blocks by the XCD that wrote a row's mask while the mask fits the L2s
+    (16 MB) and falls back to the (span, row) grid beyond: at V = 128,256 the switch lies between 1,046 and
+    1,047 rows.  Batches that are no multiple of 8 on both sides, every logit compared."""
+    torch, dev = _torch()
+    from paper_2506_03887_amd import apply_mask
+    V = 128256
+    W = (V + 31) // 32
+    assert (B * W * 4 <= 16 << 20) == (B == 1003)
+    rng = np.random.default_rng(B)
+    host = bf16_logits(rng, B, V)
+    mask = rng.integers(0, 2 ** 32, size=(B, W), dtype=np.uint64).astype(np.uint32)
+    mask[1::5] &= rng.integers(0, 2 ** 32, size=mask[1::5].shape, dtype=np.uint64).astype(np.uint32)
+    mask[2::7] = 0
+    mask[3::11] = 0xFFFFFFFF
+    mask[B - 1, ::3] = 0
+    logits = torch.from_numpy(host.view(np.int16)).to(dev)
+    apply_mask(logits.view(torch.bfloat16), torch.from_numpy(mask.view(np.int32)).to(dev), V)
+    want = host.copy()
+    oracle_apply_mask(want, mask, V)
+    got = logits.cpu().numpy().view(np.uint16)
+    assert (got == want).all(), np.argwhere(got != want)[:4].tolist()
+
+
 def test_batches_beyond_the_grid_limit_of_one_dimension():
     """More rows than a grid dimension holds (65,535): pre3_apply_mask switches to its flat kernel,
     the arg max and the top-k put the rows on the x dimension.  Small vocabulary, every row checked."""
