@@ -272,7 +272,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
         for (int i = lane; i < nl; i += 64) stack[i] = i < new_base ? row[i] : priv.get(i - new_base);
         __builtin_amdgcn_wave_barrier();
         int first_moved = nl;
-        if (out_state >= 0 && nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+        if (nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
         const int from = first_moved < new_base ? first_moved : new_base;
         for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
         if (lane == 0 && nl != out_len) len[b] = nl;    // the top, hence states[b], is the same
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
                 stack[i] = i < base ? StackView{row, s_win, n}.at(i) : priv.get(i - base);
             __builtin_amdgcn_wave_barrier();
             int first_moved = nl;
-            if (out_state >= 0 && nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+            if (nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
             const int from = restarted ? nl : (first_moved < base ? first_moved : base);
             for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
             if (lane == 0) {

@@ -245,6 +245,7 @@ def test_stacks_that_were_never_compacted_are_compacted_whole(call):
         (b"[" + b"[]," * 100, b"["), (b"[" + b"1," * 31 + b'"' + b"ab" * 40, b'"'),
         (b"[" + b"1," * 40 + b"[" + b"2," * 50 + b'{"a":3' + b',"a":4' * 30, b"}"),
         (b'["' + b"\\n" * 50 + b'",' + b"9," * 45 + b"10", b"]"), (b"[1,2,3", b","), (b"[", b"]"),
+        (b"[1]" + b" \n" * 50, None), (b'{"k":[]}' + b"\t" * 90, None),      # a sentence, then white space: ends here (None = the end-of-sequence token)
     ]
     B = len(prefixes)
     plain = Oracle([G.JSON_RIGHT_RECURSIVE])
@@ -264,7 +265,7 @@ def test_stacks_that_were_never_compacted_are_compacted_whole(call):
     states_d, data_d, len_d = (torch.from_numpy(a.copy()).to(dev) for a in (states_h, data_h, len_h))
     err_d = torch.zeros(B, dtype=torch.int32, device=dev)
     lib.bind_state(states_d, data_d, len_d, err_d)
-    tok = np.array([ids[nxt] for _, nxt in prefixes], dtype=np.int32)
+    tok = np.array([v.eos_id if nxt is None else ids[nxt] for _, nxt in prefixes], dtype=np.int32)
     if call == "jump_forward":
         out = torch.zeros((B, 8), dtype=torch.uint8, device=dev)
         cnt = torch.zeros(B, dtype=torch.int32, device=dev)
