@@ -535,6 +535,32 @@ __global__ __launch_bounds__(64 * kJfSeqPerBlock) void jump_forward_kernel(
             adv.spill_stride = (size_t)batch;
             int new_top = top;
             while (count < max_bytes) {
+                // a state whose only edge shifts one byte starts a run of forced bytes known since the
+                // tables were compiled: emitted and pushed in one step (the byte-by-byte search below
+                // would find the same bytes one at a time)
+                const int run = T.run_off ? table<true>(T.run_off, top) : -1;
+                if (run >= 0) {
+                    int take = table<true>(T.run_pool, run);
+                    take = take < max_bytes - count ? take : max_bytes - count;
+                    take = take < cap - n ? take : cap - n;
+                    if (take <= 0) break;                  // the stack is full
+                    const int word = lane < take ? T.run_pool[run + 1 + lane] : 0;
+                    if (lane < take) {
+                        row[n + lane] = word >> 8;
+                        out_bytes[(size_t)b * max_bytes + count + lane] = (uint8_t)(word & 0xFF);
+                    }
+                    // the new top of the stack: the run's states, then what was the top before
+                    const int from_run = __shfl(word, take - 1 - lane < 0 ? 0 : take - 1 - lane) >> 8;
+                    const int below = lane >= take ? s_win[wave][lane - take] : -1;
+                    __builtin_amdgcn_wave_barrier();
+                    s_win[wave][lane] = lane < take ? from_run : below;
+                    __builtin_amdgcn_wave_barrier();
+                    n += take;
+                    top = __builtin_amdgcn_readfirstlane(s_win[wave][0]);
+                    kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
+                    count += take;
+                    continue;
+                }
                 const StackView view{row, s_win[wave], n};
                 int viable_bytes = 0, only = -1;
                 bool at_end = false;

@@ -41,6 +41,10 @@ struct DevTables {
     // one 128-byte line per token: [0] = length in bytes (-1: longer than kTokInfoBytes, use vbytes),
     // [1 + i] = byte_info of byte i -- everything a walk needs to know about the token in one access
     const int32_t *tok_info;       // [n_tokens * 32]
+    // runs of forced bytes (multi-symbol edges): run_off[s] = offset in run_pool of the run that starts at
+    // state s, or -1; a run is its length L (1..64) followed by L words  target state << 8 | byte
+    const int32_t *run_off;        // [n_states], null = none
+    const int32_t *run_pool;
     int max_depth;                 // private stack entries a walk can need
     int cycle_pool_n;              // entries of the reduction-cycle records (cycle-aware stacks), 0 = none
     int32_t *fault;                // device counter: walks stopped by an internal guard (must stay 0)
