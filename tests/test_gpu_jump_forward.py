@@ -160,3 +160,38 @@ def test_decode_loop_with_jump_forward_emits_valid_documents():
     assert len(done) >= 4 and forced_total > 200, (len(done), forced_total)
     for t in done:
         json.loads(t.decode("latin-1"))
+
+
+def test_runs_of_forced_bytes_longer_than_a_wave():
+    """A literal of 100 bytes, a choice, a literal of 70 bytes: the forced runs are cut at max_bytes, at the
+    64 bytes one step can take, at the choice, at the end of the sentence and at the stack capacity, always where
+    the oracle's byte-by-byte search stops."""
+    from paper_2506_03887_amd import Pre3
+    v = bpe_like_vocab(500, 6, BASE_SEED + 73)
+    lit1 = bytes(97 + (7 * i) % 26 for i in range(100))
+    lit2 = bytes(48 + (3 * i) % 10 for i in range(70))
+    text = 'S ::= "%s" T "%s"\nT ::= "x" | "y"' % (lit1.decode(), lit2.decode())
+    o = Oracle([text])
+    cap = 256
+    lib = Pre3([text], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=cap)
+    prefixes = [b"", lit1[:1], lit1[:36], lit1[:99], lit1, lit1 + b"x", lit1 + b"y" + lit2[:69], lit1 + b"x" + lit2]
+    B = len(prefixes)
+    data = np.zeros((B, cap), dtype=np.int32)
+    length = np.ones(B, dtype=np.int32)
+    for b, p in enumerate(prefixes):
+        st = o.initial_stack() if not p else o.advance(o.initial_stack(), p)[1]
+        data[b, : len(st)], length[b] = st, len(st)
+    states = data[np.arange(B), length - 1].copy()
+    for max_bytes in (1, 31, 63, 64, 65, 100, 101, 128, 200):
+        forced = _compare(o, lib, states, data, length, max_bytes)
+        assert forced > 0
+    got_bytes, got_cnt, _, _, _ = _jump(lib, states, data, length, 200)
+    assert got_bytes[0, : got_cnt[0]].tobytes() == lit1 and got_bytes[5, : got_cnt[5]].tobytes() == lit2 and got_cnt[7] == 0
+    # the capacity ends a run in its middle: 1 .. 70 entries of room above the stack after the first literal and "x"
+    deep = o.advance(o.initial_stack(), lit1 + b"x")[1]
+    for room in (0, 1, 5, 63, 64, 65, 69, 70, 71):
+        c = len(deep) + room
+        lib2 = Pre3([text], v.bytes, v.offsets, v.eos_id, max_token_len=v.max_len, stack_cap=c)
+        d2 = np.zeros((1, c), dtype=np.int32)
+        d2[0, : len(deep)] = deep
+        _compare(o, lib2, np.array([deep[-1]], dtype=np.int32), d2, np.array([len(deep)], dtype=np.int32), 200)
