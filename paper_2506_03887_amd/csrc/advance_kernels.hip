@@ -186,9 +186,9 @@ __device__ __forceinline__ void copy_cycle_tables(int32_t *lds, int n_states, in
 constexpr int kAdvSeqPerBlock = 4;
 template <bool kCompact>
 __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
-    DevTables T, const int32_t *__restrict__ tokens, int32_t *__restrict__ states, int32_t *__restrict__ data,
-    int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch, int restart_on_eos,
-    const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles) {
+    DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
+    int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err, int32_t *scratch,
+    int restart_on_eos, const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles) {
     extern __shared__ int32_t adv_stage[];             // kCompact: kAdvSeqPerBlock x (cap stack entries [+ cycle tables])
     __shared__ int32_t lds_stack[kLdsDepth * kAdvSeqPerBlock];
     __shared__ int32_t s_win[kAdvSeqPerBlock][kWindow], s_info[kAdvSeqPerBlock][64];
@@ -221,6 +221,14 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     const int st = states[b];
     const bool live = t >= 0 && t < T.n_tokens && st >= 0 && n >= 1 && n <= cap;
     StagedToken tok{0, 0};
+    // the root of the condition tree of the stack's top (states[b] names it) is fetched together with
+    // the stack window and the token's bytes: the look-up of the token's stack operations starts from it
+    int fx_root = -1;
+    DevConditionNode fx_nd{};
+    if (E.fx_slots && live && t != T.eos_id && (unsigned)st < (unsigned)T.n_states) {
+        fx_root = E.root_id[st];
+        fx_nd = E.root_nodes[st];
+    }
     if (live) {
         s_win[wave][lane] = n - 1 - lane >= 0 ? row[n - 1 - lane] : -1;
         if (t != T.eos_id) tok = stage_token(T, t, lane, s_info[wave]);
@@ -246,7 +254,34 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
                     out_err = 1;
                 }
             } else {
-                const int rc = walk_staged_token(T, priv, s_info[wave], tok, view, cap, base, d, top, kind);
+                // a longer token whose merged edge carries its stack operations is applied in one step
+                // (look-up, truncate, push), as in advance_fill_kernel; every other token is walked
+                EffectHit fx{0, 0, 0, 0, 0, 0, 0};
+                if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
+                    fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win[wave], n,
+                                     [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                int rc;
+                if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
+                    if (n + fx.peak >= cap) {
+                        rc = kOverflow;
+                    } else {
+                        base = n - fx.k + 1;
+                        if (fx.inline_count > 0) {
+                            priv.set(0, fx.x0);
+                            top = fx.x0;
+                            if (fx.inline_count == 2) { priv.set(1, fx.x1); top = fx.x1; }
+                        } else {
+                            for (int i = 0; i < fx.np; ++i) {
+                                top = table<true>(E.fx_pool, fx.x0 + i);
+                                priv.set(i, top);
+                            }
+                        }
+                        d = fx.np;
+                        rc = kFed;
+                    }
+                } else {
+                    rc = walk_staged_token(T, priv, s_info[wave], tok, view, cap, base, d, top, kind);
+                }
                 if (rc != kFed) {
                     out_err = rc == kOverflow ? 2 : 1;
                 } else {
@@ -730,8 +765,8 @@ bool advance_fits_compact(int cap) {
     return cap <= kCompactMaxLen && (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + 4096 <= 65536;
 }
 
-hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
-                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
+hipError_t launch_advance(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states, int32_t *data,
+                          int32_t *len, int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
                           const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
     const dim3 grid((batch + kAdvSeqPerBlock - 1) / kAdvSeqPerBlock), block(64 * kAdvSeqPerBlock);
@@ -741,10 +776,10 @@ hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *st
         const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) &&
                           (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + tables + 4096 <= 65536;
         const size_t lds = (size_t)kAdvSeqPerBlock * cap * sizeof(int32_t) + (stage ? tables : 0);
-        hipLaunchKernelGGL(advance_kernel<true>, grid, block, lds, stream, T, tokens, states, data, len, cap, batch, err,
+        hipLaunchKernelGGL(advance_kernel<true>, grid, block, lds, stream, T, E, tokens, states, data, len, cap, batch, err,
                            scratch, restart_on_eos, cycle_head, cycle_pool, stage);
     } else {
-        hipLaunchKernelGGL(advance_kernel<false>, grid, block, 0, stream, T, tokens, states, data, len, cap, batch, err,
+        hipLaunchKernelGGL(advance_kernel<false>, grid, block, 0, stream, T, E, tokens, states, data, len, cap, batch, err,
                            scratch, restart_on_eos, nullptr, nullptr, 0);
     }
     return hipGetLastError();

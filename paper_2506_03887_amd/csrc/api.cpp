@@ -359,6 +359,9 @@ int upload_tables(pre3_handle *h) {
 
 bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 
+// The token-level edges for pre3_advance: only their stack-effect records are used there.
+DevTokenEdges effect_edges(const pre3_handle *h) { return h->use_edges ? h->dev_edges : DevTokenEdges{}; }
+
 // After a call that changed the bound stacks: take complete traversals of reduction cycles out
 // again (only with PRE3_FLAG_COMPACT_CYCLES and a grammar that has such cycles).
 hipError_t compact_stacks(pre3_handle *h, const pre3_stacks &st, hipStream_t s) {
@@ -556,7 +559,7 @@ int pre3_advance(pre3_handle *h, const int32_t *tokens, pre3_stream stream) {
     if (!tokens) return fail(h, PRE3_E_BADARG, "advance: null tokens");
     // cycle-aware stacks: compacted inside the kernel when four staged stacks fit its LDS, else by a kernel of its own
     const bool fused = h->compact && h->T.n_cycles > 0 && advance_fits_compact(h->b_stacks.cap);
-    hipError_t e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
+    hipError_t e = launch_advance(h->dev, effect_edges(h), tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                                   h->b_stacks.batch, h->b_err, h->adv_scratch, 0, fused ? h->cycle_head : nullptr,
                                   fused ? h->cycle_pool : nullptr, static_cast<hipStream_t>(stream));
     if (e == hipSuccess && !fused) e = compact_bound_stacks(h, static_cast<hipStream_t>(stream));
@@ -580,7 +583,7 @@ int pre3_advance_static(pre3_handle *h, const int32_t *tokens, int32_t *states, 
     if (e != hipSuccess) return hip_fail(h, e, "advance_static: address of the static scratch");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool fused = h->compact && h->T.n_cycles > 0 && advance_fits_compact(stacks.cap);
-    e = launch_advance(h->dev, tokens, states, stacks.data, stacks.len, stacks.cap, stacks.batch, err, scratch, 0,
+    e = launch_advance(h->dev, effect_edges(h), tokens, states, stacks.data, stacks.len, stacks.cap, stacks.batch, err, scratch, 0,
                        fused ? h->cycle_head : nullptr, fused ? h->cycle_pool : nullptr, s);
     if (e == hipSuccess && !fused) e = compact_stacks(h, stacks, s);
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_static");
@@ -606,7 +609,7 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
                                 h->af_walk_spill, cycles ? h->cycle_head : nullptr, cycles ? h->cycle_pool : nullptr, s);
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_mask");
     }
-    e = launch_advance(h->dev, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
+    e = launch_advance(h->dev, effect_edges(h), tokens, h->b_states, h->b_stacks.data, h->b_stacks.len, h->b_stacks.cap,
                        h->b_stacks.batch, h->b_err, h->adv_scratch, restart, nullptr, nullptr, s);
     if (e == hipSuccess) e = compact_bound_stacks(h, s);
     if (e != hipSuccess) return hip_fail(h, e, "launch advance");

@@ -30,9 +30,10 @@ hipError_t launch_timestamp(int64_t *out, hipStream_t stream);
 
 hipError_t launch_apply_mask(uint16_t *logits, const uint32_t *bitmask, int batch, int vocab, int64_t row_stride,
                              hipStream_t stream);
-// cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (needs advance_fits_compact(cap)), or null
-hipError_t launch_advance(const DevTables &T, const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len,
-                          int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
+// cycle_head / cycle_pool: the cycle tables for cycle-aware stacks (needs advance_fits_compact(cap)), or null;
+// E: the token-level edges, whose stack-effect records apply longer tokens in one step (E.fx_slots null: every token is walked)
+hipError_t launch_advance(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states, int32_t *data,
+                          int32_t *len, int cap, int batch, int32_t *err, int32_t *scratch, int restart_on_eos,
                           const int32_t *cycle_head, const int32_t *cycle_pool, hipStream_t stream);
 bool advance_fits_compact(int cap);                     // four staged stacks within the kernel's LDS
 // The library's own spill area (a device array of kStaticScratchEntries int32 that is part of the
