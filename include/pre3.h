@@ -293,6 +293,14 @@ int pre3_jump_forward(pre3_handle *h, uint8_t *out_bytes, int32_t *out_len, int3
  * then as tried) to out_states[0..out_cap) and returns n; BADARG if n > out_cap. */
 int32_t pre3_n_reduction_cycles(const pre3_handle *h);
 int32_t pre3_reduction_cycle(const pre3_handle *h, int32_t index, int32_t *out_states, int32_t out_cap);
+
+/* Multi-symbol edges for jump-forward (Sec. 3.3, merging of deterministic single-successor runs):
+ * the run of forced bytes that starts at `state`, i.e. while a state's only edge is an acceptance
+ * edge on one byte.  out_bytes[i] / out_states[i] (host, out_cap entries each) = the i-th forced
+ * byte and the state it is shifted to; at most 64 per entry (a longer run continues with the run of
+ * its last state).  Returns the length, 0 if the state forces nothing; BADARG if out_cap is too small. */
+int32_t pre3_forced_run(const pre3_handle *h, int32_t state, uint8_t *out_bytes, int32_t *out_states, int32_t out_cap);
+
 /* Host evaluation of the normal form on the uploaded cycle tables: compacts stack[0..len) in place
  * and returns the new length (tests check the tables with it; the device path is the kernel). */
 int32_t pre3_debug_compact(const pre3_handle *h, int32_t *stack, int32_t len);

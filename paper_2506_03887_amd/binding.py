@@ -29,7 +29,7 @@ EXPORTS = [
     "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
-    "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_debug_timestamp", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
+    "pre3_forced_run", "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_debug_timestamp", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
 ]
 
 
@@ -86,6 +86,7 @@ def load():
     lib.pre3_apply_mask_topk.argtypes = [vp, vp, c.c_int64, vp, i32, vp, vp, vp]
     lib.pre3_jump_forward.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_reduction_cycle.argtypes = [vp, i32, vp, i32]
+    lib.pre3_forced_run.argtypes = [vp, i32, vp, vp, i32]
     lib.pre3_debug_compact.argtypes = [vp, vp, i32]
     lib.pre3_debug_fault_count.argtypes = [vp, c.POINTER(c.c_int64)]
     lib.pre3_debug_timestamp.argtypes = [vp, vp]
@@ -253,6 +254,15 @@ class Pre3:
         if n < 0:
             raise Pre3Error(n, "debug_compact")
         return st[:n].tolist()
+
+    def forced_run(self, state: int):
+        """(bytes, states) of the run of forced bytes that starts at `state` (empty if it forces nothing)."""
+        out_b = (ctypes.c_uint8 * 64)()
+        out_s = (ctypes.c_int32 * 64)()
+        n = self._lib.pre3_forced_run(self._h, int(state), out_b, out_s, 64)
+        if n < 0:
+            raise Pre3Error(n, "forced_run")
+        return bytes(out_b[:n]), list(out_s[:n])
 
     def fault_count(self) -> int:
         """Walks that a kernel stopped at an internal guard since compile (0 expected); synchronises first."""

@@ -106,44 +106,6 @@ std::vector<int32_t> device_cycle_pool(const EdgeTables &T) {
     return pool;
 }
 
-// Multi-symbol edges for jump-forward (Sec. 3.3, merging of deterministic single-successor runs): a
-// state whose ONLY edge is an acceptance edge on a byte class of one byte -- no reduction step on
-// any class, nothing on '$' -- forces that byte whatever lies under it on the stack, and so does the
-// state it leads to, and so on.  run_off[s] = offset of the run that starts at s (or -1), a run =
-// its length (at most kMaxRun; a longer one continues with the run of the state it ends in), then
-// per forced byte the word  target state << 8 | byte.
-constexpr int kMaxRun = 64;
-void build_forced_runs(const EdgeTables &T, std::vector<int32_t> *run_off, std::vector<int32_t> *run_pool) {
-    const int ncol = T.n_classes + 1;
-    std::vector<int> class_bytes(T.n_classes, 0), class_first(T.n_classes, -1);
-    for (int b = 255; b >= 0; --b) {
-        class_bytes[T.byte_class[b]]++;
-        class_first[T.byte_class[b]] = b;
-    }
-    std::vector<int32_t> step(T.n_states, -1);             // target << 8 | byte of a state's forced byte, or -1
-    for (int s = 0; s < T.n_states; ++s) {
-        int edges = 0, col = -1;
-        for (int c = 0; c < ncol; ++c)
-            if ((T.edge[(size_t)s * ncol + c] & kKindMask) != kError) { ++edges; col = c; }
-        if (edges != 1 || col >= T.n_classes || class_bytes[col] != 1) continue;
-        const uint32_t e = T.edge[(size_t)s * ncol + col];
-        if ((e & kKindMask) != kShift) continue;
-        const int byte = class_first[col];
-        step[s] = (int32_t)((((e >> 2) + (uint32_t)T.byte_delta[byte]) << 8) | (uint32_t)byte);
-    }
-    run_off->assign(T.n_states, -1);
-    run_pool->clear();
-    for (int s = 0; s < T.n_states; ++s) {
-        if (step[s] < 0) continue;
-        (*run_off)[s] = (int32_t)run_pool->size();
-        run_pool->push_back(0);
-        int len = 0;
-        for (int at = s; len < kMaxRun && step[at] >= 0; at = step[at] >> 8, ++len) run_pool->push_back(step[at]);
-        (*run_pool)[(*run_off)[s]] = len;
-    }
-    if (run_pool->empty()) run_pool->push_back(0);
-}
-
 template <typename T>
 hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
     void *p = nullptr;
@@ -268,12 +230,8 @@ int upload_tables(pre3_handle *h) {
     PRE3_UP(h->T.edge, edge);
     PRE3_UP(h->T.goto_row, goto_row);
     PRE3_UP(h->T.goto_flat, goto_flat);
-    {
-        std::vector<int32_t> run_off, run_pool;
-        build_forced_runs(h->T, &run_off, &run_pool);
-        PRE3_UP(run_off, run_off);
-        PRE3_UP(run_pool, run_pool);
-    }
+    PRE3_UP(h->T.run_off, run_off);
+    PRE3_UP(h->T.run_pool, run_pool);
     PRE3_UP(h->V.tok_len, tok_len);
     PRE3_UP(h->V.tok_bit, tok_bit);
     PRE3_UP(h->V.tok_words, tok_words);
@@ -687,6 +645,19 @@ int32_t pre3_goto_target(const pre3_handle *h, int32_t state, int32_t nt) {
     if (!locate(h, state, &g, &local) || nt < 0 || nt >= h->T.automata[g].n_nt) return PRE3_E_BADARG;
     int row = h->T.goto_row[state];
     return row < 0 ? -1 : h->T.goto_flat[row + nt];
+}
+
+int32_t pre3_forced_run(const pre3_handle *h, int32_t state, uint8_t *out_bytes, int32_t *out_states, int32_t out_cap) {
+    if (!h || !h->compiled || state < 0 || state >= h->T.n_states || !out_bytes || !out_states) return PRE3_E_BADARG;
+    const int at = h->T.run_off[state];
+    if (at < 0) return 0;
+    const int n = h->T.run_pool[at];
+    if (n > out_cap) return PRE3_E_BADARG;
+    for (int i = 0; i < n; ++i) {
+        out_bytes[i] = (uint8_t)(h->T.run_pool[at + 1 + i] & 0xFF);
+        out_states[i] = h->T.run_pool[at + 1 + i] >> 8;
+    }
+    return n;
 }
 
 int32_t pre3_n_reduction_cycles(const pre3_handle *h) { return h && h->compiled ? h->T.n_cycles : PRE3_E_BADARG; }

@@ -62,6 +62,44 @@ int height_per_symbol(const EdgeTables &T) {
 
 }  // namespace
 
+// Multi-symbol edges for jump-forward (Sec. 3.3, merging of deterministic single-successor runs): a
+// state whose ONLY edge is an acceptance edge on a byte class of one byte -- no reduction step on
+// any class, nothing on '$' -- forces that byte whatever lies under it on the stack, and so does the
+// state it leads to, and so on.  run_off[s] = offset of the run that starts at s (or -1), a run =
+// its length (at most kMaxRun; a longer one continues with the run of the state it ends in), then
+// per forced byte the word  target state << 8 | byte.
+void build_forced_runs(EdgeTables &T) {
+    std::vector<int32_t> *run_off = &T.run_off, *run_pool = &T.run_pool;
+    const int ncol = T.n_classes + 1;
+    std::vector<int> class_bytes(T.n_classes, 0), class_first(T.n_classes, -1);
+    for (int b = 255; b >= 0; --b) {
+        class_bytes[T.byte_class[b]]++;
+        class_first[T.byte_class[b]] = b;
+    }
+    std::vector<int32_t> step(T.n_states, -1);             // target << 8 | byte of a state's forced byte, or -1
+    for (int s = 0; s < T.n_states; ++s) {
+        int edges = 0, col = -1;
+        for (int c = 0; c < ncol; ++c)
+            if ((T.edge[(size_t)s * ncol + c] & kKindMask) != kError) { ++edges; col = c; }
+        if (edges != 1 || col >= T.n_classes || class_bytes[col] != 1) continue;
+        const uint32_t e = T.edge[(size_t)s * ncol + col];
+        if ((e & kKindMask) != kShift) continue;
+        const int byte = class_first[col];
+        step[s] = (int32_t)((((e >> 2) + (uint32_t)T.byte_delta[byte]) << 8) | (uint32_t)byte);
+    }
+    run_off->assign(T.n_states, -1);
+    run_pool->clear();
+    for (int s = 0; s < T.n_states; ++s) {
+        if (step[s] < 0) continue;
+        (*run_off)[s] = (int32_t)run_pool->size();
+        run_pool->push_back(0);
+        int len = 0;
+        for (int at = s; len < kMaxRun && step[at] >= 0; at = step[at] >> 8, ++len) run_pool->push_back(step[at]);
+        (*run_pool)[(*run_off)[s]] = len;
+    }
+    if (run_pool->empty()) run_pool->push_back(0);
+}
+
 EdgeTables build_edge_tables(const std::vector<Grammar> &grammars) {
     EdgeTables T;
     T.n_grammars = (int)grammars.size();
@@ -186,6 +224,7 @@ EdgeTables build_edge_tables(const std::vector<Grammar> &grammars) {
             ++T.n_cycles;
         }
     }
+    build_forced_runs(T);
     return T;
 }
 

@@ -45,7 +45,13 @@ struct EdgeTables {
     std::vector<int32_t> cycle_head;       // [n_states]
     std::vector<int32_t> cycle_pool;
     int n_cycles = 0;
+    // Runs of forced bytes (multi-symbol edges for jump-forward): run_off[s] = offset in run_pool of the
+    // run that starts at state s, or -1; a run is its length (1 .. kMaxRun) followed by one word per
+    // forced byte,  target state << 8 | byte.
+    std::vector<int32_t> run_off;          // [n_states]
+    std::vector<int32_t> run_pool;
 };
+constexpr int kMaxRun = 64;
 
 struct VocabLayout {
     int n_tokens = 0, eos_id = 0;

@@ -34,6 +34,41 @@ def test_header_symbols_are_exported():
 
 
 @pytest.mark.parametrize("texts", [
+    [G.JSON], [G.schema_grammar(11, 6, 2, 4).text, G.JSON], [G.JSON_RIGHT_RECURSIVE, G.schema_grammar(13, 8, 1, 5).text],
+    ['S ::= "%s" T "%s"\nT ::= "x" | "y"' % ("abcdefghij" * 10, "0123456789" * 7)],
+])
+def test_forced_runs_are_the_shift_only_chains_of_the_oracle_tables(texts, vocab):
+    """The multi-symbol edges of jump-forward (Sec. 3.3) against the oracle's ACTION table: a state starts a
+    run exactly if its only action, over all 256 bytes and the end of input, is one shift; the run follows
+    such shifts byte by byte and target by target, for at most 64 steps, and ends where the next state has
+    another action (or the limit is reached)."""
+    o = Oracle(texts)
+    p = host_compile(texts, vocab)
+
+    def only_shift(g, s):
+        acts = [(a,) + o.action(s, a, g) for a in range(257)]
+        live = [x for x in acts if x[1] != A_ERROR]
+        return (live[0][0], live[0][2]) if len(live) == 1 and live[0][1] == A_SHIFT else None
+
+    with_run = longest = 0
+    for g in range(len(texts)):
+        off = o.initial_state(g)
+        for s in range(o.n_states(g)):
+            want_bytes, want_states, at = [], [], s
+            while len(want_bytes) < 64 and only_shift(g, at) is not None:
+                a, at = only_shift(g, at)
+                want_bytes.append(a)
+                want_states.append(at + off)
+            got_bytes, got_states = p.forced_run(off + s)
+            assert list(got_bytes) == want_bytes and got_states == want_states, (g, s)
+            with_run += bool(want_bytes)
+            longest = max(longest, len(want_bytes))
+    assert with_run > 0
+    if len(texts) == 1 and texts[0].startswith("S ::="):
+        assert longest == 64 and p.forced_run(p.initial_state(0))[0] == ("abcdefghij" * 10)[:64].encode()
+
+
+@pytest.mark.parametrize("texts", [
     [G.ARITHMETIC], [G.JSON], [G.EPSILON_MIX, G.DYCK, G.ARITHMETIC],
     [G.schema_grammar(11, 6, 2, 4).text, G.JSON],
 ])
