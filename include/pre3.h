@@ -224,6 +224,20 @@ int pre3_advance_static(pre3_handle *h, const int32_t *tokens, int32_t *states, 
 int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, int32_t flags,
                            pre3_stream stream);
 
+/* One whole decode step as one call (Alg. 1 per step: advance by the sampled token, compute the
+ * mask of the new stacks, mask the logits): pre3_advance_fill_mask followed by pre3_apply_mask of
+ * the new rows on logits_bf16 (device, [batch, >= n_tokens] bf16 patterns, row_stride elements
+ * between rows, masked in place).  Results are exactly those of the two calls in sequence --
+ * states, stacks, err and bitmask as pre3_advance_fill_mask leaves them, logits as pre3_apply_mask
+ * then leaves them.  Where the sizes allow (logits aligned to 16 bytes, row_stride a multiple of 8,
+ * at most 153,600 tokens, token-level edges in use, the mask row and -- with cycle-aware stacks --
+ * the stack within the kernel's LDS) the step is ONE kernel in which every sequence's logits are
+ * fetched while its token is still being walked; otherwise the call is the two calls.
+ * flags: as for pre3_advance_fill_mask.  Errors: BADARG (nothing bound, null pointer, unknown
+ * flag, row_stride < n_tokens, logits not 2-byte aligned), HIP. */
+int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
+                                 int64_t row_stride, int32_t flags, pre3_stream stream);
+
 /* Greedy sampling fused behind the mask (Sec. 1: invalid tokens are excluded, then a token is
  * sampled; here the sampler is the arg max).  For every bound sequence b:
  *   out_tokens[b] = the token t with bit t of bitmask row b set whose bf16 logit is the largest

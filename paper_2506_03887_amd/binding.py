@@ -26,7 +26,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_advance_fill_apply_mask", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
     "pre3_forced_run", "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_debug_timestamp", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
@@ -81,6 +81,7 @@ def load():
     lib.pre3_fill_apply_mask.argtypes = [vp, vp, _Stacks, vp, vp, c.c_int64, vp]
     lib.pre3_advance.argtypes = [vp, vp, vp]
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
+    lib.pre3_advance_fill_apply_mask.argtypes = [vp, vp, vp, vp, c.c_int64, i32, vp]
     lib.pre3_advance_static.argtypes = [vp, vp, vp, _Stacks, vp, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
     lib.pre3_apply_mask_topk.argtypes = [vp, vp, c.c_int64, vp, i32, vp, vp, vp]
@@ -331,6 +332,15 @@ class Pre3:
         self._check(self._lib.pre3_advance_fill_mask(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
                                                      ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
                                                      _stream_ptr(stream)))
+
+    def advance_fill_apply_mask(self, tokens, bitmask, logits, restart_on_eos=False, stream=None):
+        """The whole decode step: advance, next mask rows, and those rows applied to `logits` in place."""
+        assert tokens.is_contiguous() and bitmask.is_contiguous() and bitmask.shape[1] == self.words
+        assert logits.dim() == 2 and logits.stride(1) == 1 and logits.shape[0] == bitmask.shape[0]
+        self._check(self._lib.pre3_advance_fill_apply_mask(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
+                                                           _dev(logits, "u16"), logits.stride(0),
+                                                           ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
+                                                           _stream_ptr(stream)))
 
     def apply_mask_argmax(self, logits, bitmask, out_tokens, stream=None):
         """out_tokens[b] = id of the largest allowed logit of row b (bound batch); the logits are only read."""

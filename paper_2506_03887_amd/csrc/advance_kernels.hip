@@ -319,6 +319,162 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
     if (d > 0) commit_overlay(row, priv, s_base[wave], d, lane);
 }
 
+// The work of the wave that advances one sequence (all 64 lanes with identical values): walks the
+// sampled token (or applies its stack-effect record), commits the new stack, stages the new top of
+// the stack in s_new and descends the condition tree of the token-level edges with it; the result is
+// `plan`.  kCompact: the new stack is put together at after_row (LDS, cap entries), folded and only
+// then written back and looked up; stage_cycles: the block's other waves copy the cycle tables to
+// after_row + cap meanwhile and meet this wave at one block barrier.
+template <bool kCompact>
+__device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTokenEdges &E, const int32_t *__restrict__ tokens,
+                                                 int32_t *__restrict__ states, int32_t *row, int32_t *__restrict__ len,
+                                                 int cap, int batch, int32_t *__restrict__ err, int restart_on_eos,
+                                                 int32_t *adv_scratch, const int32_t *cycle_head, const int32_t *cycle_pool,
+                                                 int stage_cycles, int32_t *after_row, int32_t *s_win, int32_t *s_new,
+                                                 int32_t *s_info, int32_t *s_adv_stack, RowPlan &plan, int b, int lane) {
+    PrivateStack priv;
+    priv.lds = s_adv_stack;
+    priv.lds_stride = 1;
+    priv.spill = adv_scratch + b;
+    priv.spill_stride = (size_t)batch;
+    const int t = tokens[b];
+    const int n = len[b];
+    const int st = states[b];
+    const bool shape_ok = n >= 1 && n <= cap;
+    const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
+    StagedToken tok{0, 0};
+    // the root of the condition tree of the stack's top (states[b] names it) is fetched together
+    // with the stack window and the token's bytes: the effect look-up starts from it
+    int fx_root = -1;
+    DevConditionNode fx_nd{};
+    if (E.fx_slots && live && t != T.eos_id && (unsigned)st < (unsigned)T.n_states) {
+        fx_root = E.root_id[st];
+        fx_nd = E.root_nodes[st];
+    }
+    s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
+    if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
+    if (kCompact && stage_cycles) {                 // the other waves have copied the cycle tables meanwhile
+        __syncthreads();
+        int32_t *cycle_lds = after_row + cap;
+        cycle_head = cycle_lds;
+        cycle_pool = cycle_lds + T.n_states;
+    }
+    __builtin_amdgcn_wave_barrier();
+    // ---- advance (all lanes hold identical values)
+    int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
+    bool restarted = false;
+    if (t >= 0) {
+        int top = live ? __builtin_amdgcn_readfirstlane(s_win[0]) : -1;
+        if (!live || (unsigned)top >= (unsigned)T.n_states) {
+            out_err = 1;
+        } else {
+            const StackView view{row, s_win, n};
+            int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
+            if (t == T.eos_id) {
+                if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
+                    out_state = -1;
+                    if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
+                } else {
+                    out_err = 1;
+                }
+                base = n;
+                d = 0;                               // the '$' walk never changes the stack
+            } else {
+                // a longer token whose merged edge carries its stack operations is applied in one
+                // step (look-up, truncate, push); every other token is walked byte by byte
+                EffectHit fx{0, 0, 0, 0, 0, 0, 0};
+                if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
+                    fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
+                                     [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                int rc;
+                if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
+                    if (n + fx.peak >= cap) {
+                        rc = kOverflow;
+                    } else {
+                        base = n - fx.k + 1;
+                        if (fx.inline_count > 0) {
+                            priv.set(0, fx.x0);
+                            top = fx.x0;
+                            if (fx.inline_count == 2) { priv.set(1, fx.x1); top = fx.x1; }
+                        } else {
+                            for (int i = 0; i < fx.np; ++i) {
+                                top = table<true>(E.fx_pool, fx.x0 + i);
+                                priv.set(i, top);
+                            }
+                        }
+                        d = fx.np;
+                        rc = kFed;
+                    }
+                } else {
+                    rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
+                }
+                if (rc != kFed) {
+                    out_err = rc == kOverflow ? 2 : 1;
+                    base = n;
+                    d = 0;
+                } else {
+                    out_len = base + d;
+                    out_state = top;
+                }
+            }
+        }
+    }
+    // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart)
+    int nl = out_len;
+    if (kCompact && shape_ok) {
+        // put it together in LDS, compact it, write back what changed
+        int32_t *stack = after_row;
+        for (int i = lane; i < nl; i += 64)
+            stack[i] = i < base ? StackView{row, s_win, n}.at(i) : priv.get(i - base);
+        __builtin_amdgcn_wave_barrier();
+        int first_moved = nl;
+        if (nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
+        const int from = restarted ? nl : (first_moved < base ? first_moved : base);
+        for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
+        if (lane == 0) {
+            err[b] = out_err;
+            if ((out_err == 0 && t >= 0) || nl != n) { states[b] = out_state; len[b] = nl; }
+        }
+        auto new_at = [&](int k) -> int32_t { return k < nl ? stack[nl - 1 - k] : -1; };
+        s_new[lane] = lane < nl ? stack[nl - 1 - lane] : -1;
+        __builtin_amdgcn_wave_barrier();
+        const int top = s_new[0];
+        if (out_state < 0) {
+            if (lane == 0) plan.mode = kRowDone;
+        } else if ((unsigned)top >= (unsigned)T.n_states) {
+            if (lane == 0) plan.mode = kRowEmpty;
+        } else {
+            plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+        }
+        if (lane == 0) { plan.top = top; plan.len = nl; }
+    } else {
+    if (lane == 0) {
+        err[b] = out_err;
+        if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
+    }
+    //      stage its top in LDS and commit the private part
+    auto new_at = [&](int k) -> int32_t {           // entry k below the new top
+        if (restarted) return k == 0 ? row[0] : -1;
+        if (k < d) return priv.get(d - 1 - k);
+        const int idx = base - 1 - (k - d);
+        return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
+    };
+    s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
+    commit_overlay(row, priv, base, d, lane);
+    __builtin_amdgcn_wave_barrier();
+    // ---- descent of the condition tree with the new stack
+    const int top = s_new[0];
+    if (out_state < 0) {
+        if (lane == 0) plan.mode = kRowDone;
+    } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
+        if (lane == 0) plan.mode = kRowEmpty;
+    } else {
+        plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+    }
+    if (lane == 0) { plan.top = top; plan.len = nl; }
+    }
+}
+
 // Advance and next mask in one launch: one block per sequence.  Wave 0 walks the sampled token
 // exactly like advance_kernel (scalar table loads), commits the new stack, stages the NEW top
 // of the stack in LDS and descends the condition tree of the token-level edges with it; then the
@@ -366,147 +522,9 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         }
     }
     if (tid < 64) {
-        PrivateStack priv;
-        priv.lds = s_adv_stack;
-        priv.lds_stride = 1;
-        priv.spill = adv_scratch + b;
-        priv.spill_stride = (size_t)batch;
-        const int t = tokens[b];
-        const int n = len[b];
-        const int st = states[b];
-        const bool shape_ok = n >= 1 && n <= cap;
-        const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
-        StagedToken tok{0, 0};
-        // the root of the condition tree of the stack's top (states[b] names it) is fetched together
-        // with the stack window and the token's bytes: the effect look-up starts from it
-        int fx_root = -1;
-        DevConditionNode fx_nd{};
-        if (E.fx_slots && live && t != T.eos_id && (unsigned)st < (unsigned)T.n_states) {
-            fx_root = E.root_id[st];
-            fx_nd = E.root_nodes[st];
-        }
-        s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
-        if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
-        if (kCompact && stage_cycles) {                 // the other waves have copied the cycle tables meanwhile
-            __syncthreads();
-            int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2)) + cap;
-            cycle_head = cycle_lds;
-            cycle_pool = cycle_lds + T.n_states;
-        }
-        __builtin_amdgcn_wave_barrier();
-        // ---- advance (all lanes hold identical values)
-        int out_err = 0, out_state = st, out_len = n, base = n, d = 0;
-        bool restarted = false;
-        if (t >= 0) {
-            int top = live ? __builtin_amdgcn_readfirstlane(s_win[0]) : -1;
-            if (!live || (unsigned)top >= (unsigned)T.n_states) {
-                out_err = 1;
-            } else {
-                const StackView view{row, s_win, n};
-                int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
-                if (t == T.eos_id) {
-                    if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
-                        out_state = -1;
-                        if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
-                    } else {
-                        out_err = 1;
-                    }
-                    base = n;
-                    d = 0;                               // the '$' walk never changes the stack
-                } else {
-                    // a longer token whose merged edge carries its stack operations is applied in one
-                    // step (look-up, truncate, push); every other token is walked byte by byte
-                    EffectHit fx{0, 0, 0, 0, 0, 0, 0};
-                    if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
-                        fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
-                                         [&](int k2) { return row[n - 1 - k2]; }, t, lane);
-                    int rc;
-                    if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
-                        if (n + fx.peak >= cap) {
-                            rc = kOverflow;
-                        } else {
-                            base = n - fx.k + 1;
-                            if (fx.inline_count > 0) {
-                                priv.set(0, fx.x0);
-                                top = fx.x0;
-                                if (fx.inline_count == 2) { priv.set(1, fx.x1); top = fx.x1; }
-                            } else {
-                                for (int i = 0; i < fx.np; ++i) {
-                                    top = table<true>(E.fx_pool, fx.x0 + i);
-                                    priv.set(i, top);
-                                }
-                            }
-                            d = fx.np;
-                            rc = kFed;
-                        }
-                    } else {
-                        rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
-                    }
-                    if (rc != kFed) {
-                        out_err = rc == kOverflow ? 2 : 1;
-                        base = n;
-                        d = 0;
-                    } else {
-                        out_len = base + d;
-                        out_state = top;
-                    }
-                }
-            }
-        }
-        // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart)
-        int nl = out_len;
-        if (kCompact && shape_ok) {
-            // put it together in LDS, compact it, write back what changed
-            int32_t *stack = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2));
-            for (int i = lane; i < nl; i += 64)
-                stack[i] = i < base ? StackView{row, s_win, n}.at(i) : priv.get(i - base);
-            __builtin_amdgcn_wave_barrier();
-            int first_moved = nl;
-            if (nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
-            const int from = restarted ? nl : (first_moved < base ? first_moved : base);
-            for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
-            if (lane == 0) {
-                err[b] = out_err;
-                if ((out_err == 0 && t >= 0) || nl != n) { states[b] = out_state; len[b] = nl; }
-            }
-            auto new_at = [&](int k) -> int32_t { return k < nl ? stack[nl - 1 - k] : -1; };
-            s_new[lane] = lane < nl ? stack[nl - 1 - lane] : -1;
-            __builtin_amdgcn_wave_barrier();
-            const int top = s_new[0];
-            if (out_state < 0) {
-                if (lane == 0) plan.mode = kRowDone;
-            } else if ((unsigned)top >= (unsigned)T.n_states) {
-                if (lane == 0) plan.mode = kRowEmpty;
-            } else {
-                plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
-            }
-            if (lane == 0) { plan.top = top; plan.len = nl; }
-        } else {
-        if (lane == 0) {
-            err[b] = out_err;
-            if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
-        }
-        //      stage its top in LDS and commit the private part
-        auto new_at = [&](int k) -> int32_t {           // entry k below the new top
-            if (restarted) return k == 0 ? row[0] : -1;
-            if (k < d) return priv.get(d - 1 - k);
-            const int idx = base - 1 - (k - d);
-            return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
-        };
-        s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
-        commit_overlay(row, priv, base, d, lane);
-        __builtin_amdgcn_wave_barrier();
-        // ---- descent of the condition tree with the new stack
-        const int top = s_new[0];
-        if (out_state < 0) {
-            if (lane == 0) plan.mode = kRowDone;
-        } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
-            if (lane == 0) plan.mode = kRowEmpty;
-        } else {
-            plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
-        }
-        if (lane == 0) { plan.top = top; plan.len = nl; }
-        }
+        advance_and_plan<kCompact>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch, cycle_head,
+                                   cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2)), s_win,
+                                   s_new, s_info, s_adv_stack, plan, b, lane);
     }
     __syncthreads();
     // ---- the next mask row, by the whole block
@@ -517,6 +535,143 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     wp.spill_stride = walk_spill_stride;
     const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
     build_and_store_row<kAfBlock, true, true>(T, E, plan, bits4, 0, n_vec, row, wp, bitmask + (size_t)b * T.n_words, vector_ok, tid);
+}
+
+// The whole decode step in one launch: advance, next mask row, and that row applied to the
+// sequence's logits.  One 1,024-thread block per sequence.  Wave 0 advances and descends the
+// condition tree exactly as in advance_fill_kernel.  The other fifteen waves meanwhile fetch the
+// sequence's whole row of logits -- the fetch does not depend on the mask -- into registers (kHeld
+// groups of 8 bf16 per lane, lane j of the 960 holding groups j, j + 960, ...), so the read half of
+// the masking pass runs under the advance instead of after it; once the plan is there they put the
+// mask row together in LDS (materialised row, id lists; wave 0 walks what the tree left open),
+// store it, and patch and store the logits they hold.  The two halves are separate branches of the
+// kernel with the same number of block barriers, so the registers that hold the logits are not live
+// in wave 0's code.  Masked logits are exactly those of apply_mask_vec8_kernel: fully allowed
+// groups are not written, every other group is written with -inf where a bit is clear.
+constexpr int kStepBlock = 1024, kStepData = kStepBlock - 64;
+template <bool kCompact, int kHeld>
+__global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
+    DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
+    int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
+    uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+    size_t walk_spill_stride, const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles,
+    uint16_t *__restrict__ logits, int64_t row_stride) {
+    extern __shared__ uint4 bits4[];                   // the mask row; kCompact: then cap stack entries [+ cycle tables]
+    __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
+    __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
+    __shared__ RowPlan plan;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int b = blockIdx.x;
+    const int n_vec = (T.n_words + 3) >> 2;
+    int32_t *row = data + (size_t)b * cap;
+    uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
+    uint32_t *dst_row = bitmask + (size_t)b * T.n_words;
+    const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
+
+    if (tid < 64) {
+        advance_and_plan<kCompact>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch, cycle_head,
+                                   cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec), s_win, s_new, s_info,
+                                   s_adv_stack, plan, b, lane);
+        __syncthreads();                               // the plan is there
+        __syncthreads();                               // the materialised row (or zeros) is in LDS
+        // tokens the tree leaves undetermined are walked on the committed stack, one lane per token
+        PrivateStack wp;
+        wp.lds = s_walk_stack + lane;
+        wp.lds_stride = 64;
+        wp.spill = walk_spill + (size_t)b * 64 + lane;
+        wp.spill_stride = walk_spill_stride;
+        const int mode = plan.mode, n = plan.len, top0 = plan.top;
+        if (mode == kRowFast) {
+            const int wc = plan.walk_count;
+            for (int k = lane; k < wc; k += 64) {
+                const int t = E.walk_ids[plan.walk_begin + k];
+                if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+            }
+        } else if (mode == kRowWalkAll) {
+            for (int t = lane; t < T.n_tokens; t += 64)
+                if (walk_token_id(T, wp, t, row, n, top0)) atomicOr(&bits[t >> 5], 1u << (t & 31));
+        } else if (mode == kRowDone && lane == 0) {
+            bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
+        }
+        __syncthreads();                               // the row is complete
+    } else {
+        const int j = tid - 64;
+        {   // pull the small tables of the walk into this XCD's L2, as in advance_fill_kernel
+            const int64_t per_xcd = (gridDim.x + 7) >> 3;
+            int acc = 0;
+            for (int64_t off = ((int64_t)(blockIdx.x >> 3) * kStepData + j) * 128; off < T.hot_bytes; off += per_xcd * kStepData * 128)
+                acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
+            if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
+        }
+        if (kCompact && stage_cycles) {
+            int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + n_vec) + cap;
+            copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, j, kStepData);
+            __syncthreads();
+        }
+        // the row of logits: every group of 8 that lies wholly inside the vocabulary
+        uint16_t *lrow = logits + (size_t)b * row_stride;
+        const int whole = T.n_tokens >> 3;
+        uint4 held[kHeld];
+#pragma unroll
+        for (int i = 0; i < kHeld; ++i) {
+            const int g = i * kStepData + j;
+            held[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (g < whole) held[i] = stream_load(lrow + (size_t)g * 8);
+        }
+        __syncthreads();                               // the plan is there (and the logits have arrived)
+        const int mode = plan.mode;
+        if (mode == kRowFast && plan.dense >= 0) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec;
+            for (int w = j; w < n_vec; w += kStepData) bits4[w] = src[w];
+        } else {
+            for (int w = j; w < n_vec; w += kStepData) bits4[w] = make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();                               // the materialised row (or zeros) is in LDS
+        if (mode == kRowFast) {
+            const int nseg = plan.nseg;
+            for (int i = 0; i < nseg; ++i) {
+                const int32_t *ids = E.delta_ids + plan.seg_begin[i];
+                const int cnt = plan.seg_count[i];
+                for (int k = j; k < cnt; k += kStepData) {
+                    const int t = ids[k];
+                    atomicOr(&bits[t >> 5], 1u << (t & 31));
+                }
+            }
+        }
+        __syncthreads();                               // the row is complete
+        if (vector_ok) {
+            uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row);
+            for (int w = j; w < n_vec; w += kStepData) stream_store(bits4[w], dst4 + w);
+        } else {
+            for (int w = j; w < T.n_words; w += kStepData) dst_row[w] = bits[w];
+        }
+        const uint8_t *mask_bytes = reinterpret_cast<const uint8_t *>(bits4);     // byte g = bits of group g
+#pragma unroll
+        for (int i = 0; i < kHeld; ++i) {
+            const int g = i * kStepData + j;
+            if (g < whole) {
+                const uint32_t mu = mask_bytes[g];
+                if (mu != 0xFFu) {
+                    uint4 v = held[i];
+                    uint32_t *x = reinterpret_cast<uint32_t *>(&v);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)mu, 2 * k, 1);
+                        const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)mu, 2 * k + 1, 1);
+                        const uint32_t allow = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                        x[k] = (x[k] & allow) | (~allow & kNegInfPair);
+                    }
+                    stream_store(v, lrow + (size_t)g * 8);
+                }
+            }
+        }
+        // the last, partial group of a vocabulary that is not a multiple of 8
+        const int tail = T.n_tokens & 7;
+        if (j < tail) {
+            const int t = whole * 8 + j;
+            if (!((bits[t >> 5] >> (t & 31)) & 1u)) lrow[t] = 0xFF80;
+        }
+    }
 }
 
 // Jump-forward: while a sequence's text is not a sentence and exactly one byte keeps it a viable
@@ -752,6 +907,56 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
         hipLaunchKernelGGL(advance_fill_kernel<false>, dim3(batch), dim3(kAfBlock), row_bytes, stream, T, E, tokens, states,
                            data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,
                            nullptr, nullptr, 0);
+    }
+    return hipGetLastError();
+}
+
+// Largest vocabulary the fused step kernel can hold in registers, and the choice of its variant.
+constexpr int kStepHeldMax = 20;
+bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles) {
+    const size_t row_bytes = (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t);
+    if ((n_tokens >> 3) > kStepHeldMax * kStepData) return false;
+    if (cycles) return cap <= kCompactMaxLen && row_bytes + (size_t)cap * sizeof(int32_t) <= kAfDynamicLdsMax;
+    return row_bytes <= kAfDynamicLdsMax;
+}
+
+template <bool kCompact>
+static void launch_step_variant(int held, dim3 grid, size_t lds, hipStream_t stream, const DevTables &T, const DevTokenEdges &E,
+                                const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
+                                int32_t *err, uint32_t *bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+                                const int32_t *cycle_head, const int32_t *cycle_pool, int stage, uint16_t *logits,
+                                int64_t row_stride) {
+#define PRE3_STEP(H)                                                                                                        \
+    hipLaunchKernelGGL((advance_fill_apply_kernel<kCompact, H>), grid, dim3(kStepBlock), lds, stream, T, E, tokens, states,   \
+                       data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,     \
+                       cycle_head, cycle_pool, stage, logits, row_stride)
+    if (held <= 9) PRE3_STEP(9);
+    else if (held <= 17) PRE3_STEP(17);
+    else PRE3_STEP(20);
+#undef PRE3_STEP
+}
+
+hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
+                                     int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
+                                     int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
+                                     const int32_t *cycle_head, const int32_t *cycle_pool, uint16_t *logits,
+                                     int64_t row_stride, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, cycle_head != nullptr)) return hipErrorInvalidValue;
+    if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
+        return hipErrorInvalidValue;
+    const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;
+    size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    if (cycle_head) {
+        lds += (size_t)cap * sizeof(int32_t);
+        const size_t tables = (size_t)(T.n_states + T.cycle_pool_n) * sizeof(int32_t);
+        const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) && lds + tables <= kAfDynamicLdsMax;
+        if (stage) lds += tables;
+        launch_step_variant<true>(held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask,
+                                  restart_on_eos, adv_scratch, walk_spill, cycle_head, cycle_pool, stage, logits, row_stride);
+    } else {
+        launch_step_variant<false>(held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask,
+                                   restart_on_eos, adv_scratch, walk_spill, nullptr, nullptr, 0, logits, row_stride);
     }
     return hipGetLastError();
 }

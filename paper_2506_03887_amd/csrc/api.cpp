@@ -574,6 +574,34 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
     return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);
 }
 
+int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
+                                 int64_t row_stride, int32_t flags, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: no state bound");
+    if (!tokens || !bitmask || !logits_bf16) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: null pointer");
+    if (flags & ~PRE3_ADVANCE_RESTART_ON_EOS) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: unknown flag");
+    if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: row stride below vocabulary size");
+    if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: misaligned logits");
+    const bool cycles = h->compact && h->T.n_cycles > 0;
+    const bool one_kernel = h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
+                            advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles);
+    if (one_kernel) {
+        const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
+        hipError_t e = launch_advance_fill_apply(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
+                                                 h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
+                                                 h->af_walk_spill, cycles ? h->cycle_head : nullptr,
+                                                 cycles ? h->cycle_pool : nullptr, logits_bf16, row_stride,
+                                                 static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_apply_mask");
+    }
+    const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags, stream);
+    if (rc != PRE3_OK) return rc;
+    hipError_t e = launch_apply_mask(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask");
+}
+
 int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,
                            int32_t *out_tokens, pre3_stream stream) {
     if (!usable(h)) return PRE3_E_BADARG;

@@ -111,10 +111,15 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
     return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, applied=n_apply, depth_hist=traj.depth_hist)
 
 
-def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, **lib_options):
+def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, step_call_every=0,
+                        logits_pad=0, **lib_options):
     """Same trajectory, driven through pre3_advance_fill_mask with slot reuse on EOS: after every
     call the device's states/len/live stack/err and the next mask must equal the oracle's
-    advance followed by its fill (whole bitmask on `full_mask_steps`, sampled rows otherwise)."""
+    advance followed by its fill (whole bitmask on `full_mask_steps`, sampled rows otherwise).
+    step_call_every = k > 0: every k-th step goes through pre3_advance_fill_apply_mask (the whole step
+    as one call) on fresh seeded logits whose rows are `logits_pad` elements longer than the vocabulary;
+    on those steps the whole bitmask is checked, and all B * (V + pad) logit patterns against the
+    oracle's apply_mask on the oracle's mask (the padding must come back untouched)."""
     import torch
 
     cfg = configs.get(cfg_idx)
@@ -140,9 +145,19 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
     rng = np.random.default_rng(cfg.seed + 2)
     full = set(range(steps)) if full_mask_steps is None else set(full_mask_steps)
     n_full = n_rows = 0
+    n_step_calls = 0
+    V = v.n_tokens
     for s in range(steps):
         tok = traj.tokens[s]
-        lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d, restart_on_eos=True)
+        one_call = step_call_every > 0 and s % step_call_every == 0
+        if one_call:
+            logits = np.full((B, V + logits_pad), 0x1234, dtype=np.uint16)
+            logits[:, :V] = bf16_logits(rng, B, V)
+            logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
+            mask_d.fill_(0x5A5A5A5A)
+            lib.advance_fill_apply_mask(torch.from_numpy(tok).to(dev), mask_d, logits_d, restart_on_eos=True)
+        else:
+            lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d, restart_on_eos=True)
         err_h = o.advance_batch(states_h, data_h, len_h, tok, v)
         done = states_h < 0
         states_h[done], len_h[done] = data_h[done, 0], 1                   # restart on EOS
@@ -152,11 +167,17 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
         live = np.arange(cap)[None, :] < len_h[:, None]
         assert (data_d.cpu().numpy()[live] == data_h[live]).all(), f"cfg {cfg_idx} step {s}: stack entries differ"
         got = mask_d.cpu().numpy().view(np.uint32)
-        if s in full:
+        if s in full or one_call:
             want = o.fill_mask(states_h, data_h, len_h, v)
             bad = np.argwhere(got != want)
             assert len(bad) == 0, f"cfg {cfg_idx} step {s}: {len(bad)} mask words differ, first (row, word) {bad[0]}"
             n_full += 1
+            if one_call:
+                oracle_apply_mask(logits, want, V)
+                out = logits_d.cpu().numpy().view(np.uint16)
+                bad = np.argwhere(out != logits)
+                assert len(bad) == 0, f"cfg {cfg_idx} step {s}: {len(bad)} logits differ after the one-call step, first (row, column) {bad[0]}"
+                n_step_calls += 1
         else:
             for b in rng.integers(0, B, size=rows_per_step):
                 want = o.mask_row(data_h[b, : len_h[b]], v, done=states_h[b] < 0)
@@ -165,4 +186,4 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
         if s % 32 == 31 or s == steps - 1:
             log(f"[cfg {cfg_idx}] advance+fill step {s + 1}/{steps} ok ({n_full} full masks, {n_rows} sampled rows)", flush=True)
     assert lib.fault_count() == 0, f"cfg {cfg_idx}: a kernel stopped a walk at an internal guard"
-    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows)
+    return dict(steps=steps, full_masks=n_full, sampled_rows=n_rows, step_calls=n_step_calls)

@@ -95,6 +95,29 @@ def test_advance_fill_mask_all_configs():
     assert replay_advance_fill(6, steps=96, full_mask_steps=range(0, 96, 2))["full_masks"] == 48
 
 
+def test_whole_step_as_one_call_all_configs():
+    """pre3_advance_fill_apply_mask (advance, next mask and masked logits in one call) against the oracle's
+    advance, fill and apply: states, stacks, err, the whole bitmask and every logit pattern, padding included.
+    Config 1 has a ragged vocabulary (513 tokens, 17 mask words): with 7 elements of padding per row the one
+    kernel runs with its partial last group and word-wise mask stores, without padding the rows are not
+    16-byte aligned and the call takes its two-call form.  Config 2 also with leftover walks inside the kernel
+    (shallow conditions), rows put together from id lists, every token walked, and without token-level edges
+    (two-call form); configs 3-6 at full size, 7 with cycle-aware stacks."""
+    assert replay_advance_fill(1, step_call_every=1, logits_pad=7)["step_calls"] == 32
+    assert replay_advance_fill(1, step_call_every=1)["step_calls"] == 32
+    assert replay_advance_fill(2, steps=64, step_call_every=1)["step_calls"] == 64
+    assert replay_advance_fill(2, steps=64, step_call_every=2, logits_pad=24)["step_calls"] == 32
+    assert replay_advance_fill(2, steps=12, step_call_every=1, max_condition_depth=2)["step_calls"] == 12
+    assert replay_advance_fill(2, steps=40, step_call_every=1, row_threshold=64)["step_calls"] == 40
+    assert replay_advance_fill(2, steps=40, step_call_every=1, token_effects=False)["step_calls"] == 40
+    assert replay_advance_fill(2, steps=12, step_call_every=1, token_edges=False)["step_calls"] == 12
+    assert replay_advance_fill(3, steps=64, step_call_every=4)["step_calls"] == 16
+    assert replay_advance_fill(4, steps=32, step_call_every=8, full_mask_steps=[])["step_calls"] == 4
+    assert replay_advance_fill(5, steps=64, step_call_every=8)["step_calls"] == 8
+    assert replay_advance_fill(6, steps=48, step_call_every=8, full_mask_steps=[])["step_calls"] == 6
+    assert replay_advance_fill(7, steps=64, step_call_every=4)["step_calls"] == 16
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
     """Sequences of config 2 fed, per step and sequence, one of: an allowed token, an arbitrary
