@@ -41,9 +41,12 @@ __device__ __forceinline__ StagedToken stage_token(const DevTables &T, int t, in
     return tok;
 }
 
+constexpr int kScalarRunMin = 8;       // bytes left in a token before a scalar-only walk looks for a run
+
 // Walks a staged token from the configuration  view ++ priv[0..d)  with capacity checks.  Runs on
 // all 64 lanes with identical values (scalar table loads, LDS broadcast reads); a run of
 // self-similar edges is applied in one step.  Returns kFed, kRejected or kOverflow.
+template <bool kScalar = false>
 __device__ __forceinline__ int walk_staged_token(const DevTables &T, PrivateStack &priv, const int32_t *s_info,
                                                  StagedToken tok, const StackView &view, int cap, int &base, int &d,
                                                  int &top, int &kind) {
@@ -52,8 +55,9 @@ __device__ __forceinline__ int walk_staged_token(const DevTables &T, PrivateStac
     for (int i = 0; i < n_bytes && rc == kFed; ++i) {
         const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[tok.lo + i]]);
         int run_node = -1;
-        rc = feed<true, true>(T, priv, info, base, d, top, kind, view, cap, &run_node);
-        if (rc == kFed && run_node >= 0 && i + 1 < n_bytes)
+        rc = feed<true, true, kScalar>(T, priv, info, base, d, top, kind, view, cap, &run_node);
+        // (a run is examined with one vector load per lane: a wave that keeps to scalar loads takes short tails byte by byte)
+        if (rc == kFed && run_node >= 0 && i + 1 < n_bytes && (!kScalar || n_bytes - (i + 1) >= kScalarRunMin))
             i += apply_run<true>(T, priv, s_info, i + 1, n_bytes, run_node, kind, base, d, top, cap);
     }
     return rc;
@@ -325,7 +329,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
 // `plan`.  kCompact: the new stack is put together at after_row (LDS, cap entries), folded and only
 // then written back and looked up; stage_cycles: the block's other waves copy the cycle tables to
 // after_row + cap meanwhile and meet this wave at one block barrier.
-template <bool kCompact>
+template <bool kCompact, bool kScalar = false>
 __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTokenEdges &E, const int32_t *__restrict__ tokens,
                                                  int32_t *__restrict__ states, int32_t *row, int32_t *__restrict__ len,
                                                  int cap, int batch, int32_t *__restrict__ err, int restart_on_eos,
@@ -337,9 +341,9 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
     priv.lds_stride = 1;
     priv.spill = adv_scratch + b;
     priv.spill_stride = (size_t)batch;
-    const int t = tokens[b];
-    const int n = len[b];
-    const int st = states[b];
+    const int t = kScalar ? table<true>(tokens, b) : tokens[b];
+    const int n = kScalar ? table<true>(const_cast<const int32_t *>(len), b) : len[b];
+    const int st = kScalar ? table<true>(const_cast<const int32_t *>(states), b) : states[b];
     const bool shape_ok = n >= 1 && n <= cap;
     const bool live = t >= 0 && t < T.n_tokens && st >= 0 && shape_ok;
     StagedToken tok{0, 0};
@@ -348,8 +352,8 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
     int fx_root = -1;
     DevConditionNode fx_nd{};
     if (E.fx_slots && live && t != T.eos_id && (unsigned)st < (unsigned)T.n_states) {
-        fx_root = E.root_id[st];
-        fx_nd = E.root_nodes[st];
+        fx_root = kScalar ? table<true>(E.root_id, st) : E.root_id[st];
+        fx_nd = kScalar ? scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(st)) : E.root_nodes[st];
     }
     s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
     if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
@@ -358,6 +362,10 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
         int32_t *cycle_lds = after_row + cap;
         cycle_head = cycle_lds;
         cycle_pool = cycle_lds + T.n_states;
+    } else if (kScalar) {
+        // this wave's vector loads (stack window, token bytes) are on their way: only now do the block's
+        // other waves queue theirs, so that these are not held up behind them
+        __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_wave_barrier();
     // ---- advance (all lanes hold identical values)
@@ -371,7 +379,7 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
             const StackView view{row, s_win, n};
             int kind = T.state_kind ? table<true>(T.state_kind, top) : 0;
             if (t == T.eos_id) {
-                if (feed<false, true>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
+                if (feed<false, true, kScalar>(T, priv, T.end_col, base, d, top, kind, view, 0) == kAccepted) {
                     out_state = -1;
                     if (restart_on_eos) { out_state = row[0]; out_len = 1; restarted = true; }   // slot reuse
                 } else {
@@ -383,9 +391,14 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
                 // a longer token whose merged edge carries its stack operations is applied in one
                 // step (look-up, truncate, push); every other token is walked byte by byte
                 EffectHit fx{0, 0, 0, 0, 0, 0, 0};
-                if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
-                    fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
-                                     [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len) {
+                    if (kScalar)
+                        fx = find_effect_scalar(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
+                                                [&](int k2) { return row[n - 1 - k2]; }, __builtin_amdgcn_readfirstlane(t));
+                    else
+                        fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
+                                         [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                }
                 int rc;
                 if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
                     if (n + fx.peak >= cap) {
@@ -406,7 +419,7 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
                         rc = kFed;
                     }
                 } else {
-                    rc = walk_staged_token(T, priv, s_info, tok, view, cap, base, d, top, kind);
+                    rc = walk_staged_token<kScalar>(T, priv, s_info, tok, view, cap, base, d, top, kind);
                 }
                 if (rc != kFed) {
                     out_err = rc == kOverflow ? 2 : 1;
@@ -444,7 +457,8 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
         } else if ((unsigned)top >= (unsigned)T.n_states) {
             if (lane == 0) plan.mode = kRowEmpty;
         } else {
-            plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+            if (kScalar) plan_row_scalar(E, scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(top)), s_new, nl, new_at, &plan, lane);
+            else plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
         }
         if (lane == 0) { plan.top = top; plan.len = nl; }
     } else {
@@ -469,7 +483,8 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
     } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
         if (lane == 0) plan.mode = kRowEmpty;
     } else {
-        plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
+        if (kScalar) plan_row_scalar(E, scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(top)), s_new, nl, new_at, &plan, lane);
+            else plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
     }
     if (lane == 0) { plan.top = top; plan.len = nl; }
     }
@@ -569,9 +584,9 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
     const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
 
     if (tid < 64) {
-        advance_and_plan<kCompact>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch, cycle_head,
-                                   cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec), s_win, s_new, s_info,
-                                   s_adv_stack, plan, b, lane);
+        advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
+                                         cycle_head, cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec), s_win,
+                                         s_new, s_info, s_adv_stack, plan, b, lane);
         __syncthreads();                               // the plan is there
         __syncthreads();                               // the materialised row (or zeros) is in LDS
         // tokens the tree leaves undetermined are walked on the committed stack, one lane per token
@@ -607,6 +622,8 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + n_vec) + cap;
             copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, j, kStepData);
             __syncthreads();
+        } else {
+            __builtin_amdgcn_s_barrier();              // wave 0 has queued its own vector loads
         }
         // the row of logits: every group of 8 that lies wholly inside the vocabulary
         uint16_t *lrow = logits + (size_t)b * row_stride;
@@ -616,6 +633,9 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         for (int i = 0; i < kHeld; ++i) {
             const int g = i * kStepData + j;
             held[i] = make_uint4(0u, 0u, 0u, 0u);
+#ifdef PRE3_STEP_IN_FLIGHT
+            if (i >= PRE3_STEP_IN_FLIGHT) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRE3_STEP_IN_FLIGHT - 1));
+#endif
             if (g < whole) held[i] = stream_load(lrow + (size_t)g * 8);
         }
         __syncthreads();                               // the plan is there (and the logits have arrived)
@@ -649,9 +669,12 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
 #pragma unroll
         for (int i = 0; i < kHeld; ++i) {
             const int g = i * kStepData + j;
+            // a group that needs no change is still written if one of the eight groups of its 128-byte line
+            // does: lines written in part cost the memory system far more than the bytes saved
+            const uint32_t mu = g < whole ? mask_bytes[g] : 0xFFu;
+            const unsigned long long changed = __ballot(mu != 0xFFu);
             if (g < whole) {
-                const uint32_t mu = mask_bytes[g];
-                if (mu != 0xFFu) {
+                if ((changed >> (lane & 56)) & 0xFFull) {
                     uint4 v = held[i];
                     uint32_t *x = reinterpret_cast<uint32_t *>(&v);
 #pragma unroll

@@ -110,7 +110,7 @@ template <typename T>
 hipError_t upload(pre3_handle *h, const std::vector<T> &src, const T **dst) {
     void *p = nullptr;
     size_t bytes = src.size() * sizeof(T);
-    hipError_t e = arena_alloc(h, bytes, &p);
+    hipError_t e = arena_alloc(h, bytes + 64, &p);        // the scalar 16-word loads of the kernels may reach 60 bytes past a table
     if (e != hipSuccess) return e;
     if (bytes) {
         e = hipMemcpy(p, src.data(), bytes, hipMemcpyHostToDevice);

@@ -45,9 +45,12 @@ __global__ __launch_bounds__(kApplyBlock) void apply_mask_vec8_kernel(uint16_t *
     }
     const int groups = (vocab + 7) >> 3;
     const int g = span * kApplyBlock + threadIdx.x;
-    if (g >= groups) return;
-    const uint32_t mu = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words)[g];   // little endian: byte g of the row = bits of group g
-    if (mu == 0xFFu) return;
+    uint32_t mu = 0xFFu;
+    if (g < groups) mu = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words)[g];   // little endian: byte g of the row = bits of group g
+    // a 128-byte line (the groups of eight consecutive lanes) is written whole or not at all: lines
+    // written in part cost the memory system far more than the bytes saved
+    const unsigned long long changed = __ballot(mu != 0xFFu);
+    if (g >= groups || !((changed >> (threadIdx.x & 56)) & 0xFFull)) return;
     uint16_t *p = logits + (size_t)b * row_stride + (size_t)g * 8;
     if (g * 8 + 8 <= vocab) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);

@@ -81,6 +81,50 @@ __device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNod
     }
 }
 
+// A node record of the condition tree through the scalar cache (all lanes get the same record).
+__device__ __forceinline__ DevConditionNode scalar_node(const DevConditionNode *p) {
+    const NativeInt8 v = scalar_load8(p);
+    DevConditionNode nd;
+    nd.known = v[0]; nd.child_count = v[1]; nd.a = v[2]; nd.b = v[3];
+    nd.dense_row = v[4]; nd.delta_begin = v[5]; nd.delta_count = v[6]; nd.pad = v[7];
+    return nd;
+}
+
+// plan_row with scalar loads only (see scalar_load16): per level one round for the condition states,
+// one for the child's record.
+template <typename Deeper>
+__device__ __forceinline__ void plan_row_scalar(const DevTokenEdges &E, DevConditionNode nd, const int32_t *win, int n,
+                                                Deeper deeper, RowPlan *plan, int lane) {
+    int mode = kRowFast, nseg = 0, dense = -1, walk_begin = 0, walk_count = 0;
+    for (;;) {
+        if (nd.dense_row >= 0) {
+            dense = nd.dense_row;
+            nseg = 0;
+        } else if (nd.delta_count > 0) {
+            if (lane == 0) { plan->seg_begin[nseg] = nd.delta_begin; plan->seg_count[nseg] = nd.delta_count; }
+            ++nseg;
+        }
+        if (nd.child_count == 0) {
+            walk_begin = nd.a;
+            walk_count = nd.b;
+            if (walk_count < 0) mode = kRowWalkAll;
+            break;
+        }
+        if (nd.known >= n || nseg >= kMaxPath) { mode = kRowWalkAll; break; }
+        const int x = __builtin_amdgcn_readfirstlane(nd.known < kWindow ? win[nd.known] : deeper(nd.known));
+        const int j = scalar_find<1>(E.child_state + nd.a, nd.child_count, x);
+        if (j < 0) { mode = kRowWalkAll; break; }
+        nd = scalar_node(E.nodes + nd.b + j);
+    }
+    if (lane == 0) {
+        plan->nseg = nseg;
+        plan->dense = dense;
+        plan->mode = mode;
+        plan->walk_begin = walk_begin;
+        plan->walk_count = walk_count;
+    }
+}
+
 // What the merged edge of a token does to the stack (the stack operations that every prefix-conditioned
 // edge carries, Sec. 3.1): the top k - 1 entries are replaced by np states; peak = highest the stack
 // gets just before a push, relative to its height before the token.
@@ -149,6 +193,60 @@ __device__ __forceinline__ EffectHit find_effect(const DevTokenEdges &E, int nod
         nd.child_count = __shfl(c.child_count, src);
         nd.a = __shfl(c.a, src);
         nd.b = __shfl(c.b, src);
+    }
+    return r;
+}
+
+// find_effect with scalar loads only (see scalar_load16): per level one round for the two buckets and
+// the node's first sixteen condition states, one for the child's record.
+template <typename Deeper>
+__device__ __forceinline__ EffectHit find_effect_scalar(const DevTokenEdges &E, int node, DevConditionNode nd, const int32_t *win,
+                                                        int n, Deeper deeper, int tok) {
+    EffectHit r{0, 0, 0, 0, 0, 0, 0};
+    for (int level = 0; level < 256; ++level) {
+        uint32_t b1, b2;
+        effect_buckets((uint32_t)node, (uint32_t)tok, E.fx_mask, &b1, &b2);
+        const bool inner = nd.child_count > 0 && nd.known < n;
+        const NativeInt16 s1 = scalar_load16(E.fx_slots + (size_t)b1 * kEffectBucketSlots);
+        const NativeInt16 s2 = scalar_load16(E.fx_slots + (size_t)b2 * kEffectBucketSlots);
+        const int32_t *kids = E.child_state + (inner ? nd.a : 0);
+        const NativeInt16 first = scalar_load16(kids);
+        int x = -3;
+        if (inner) x = __builtin_amdgcn_readfirstlane(nd.known < kWindow ? win[nd.known] : deeper(nd.known));
+        bool hit = false;
+        uint32_t w1 = 0, w2 = 0, w3 = 0;
+#pragma unroll
+        for (int k = 0; k < 2 * kEffectBucketSlots; ++k) {
+            const NativeInt16 &s = k < kEffectBucketSlots ? s1 : s2;
+            const int o = (k & (kEffectBucketSlots - 1)) * 4;
+            if (!hit && s[o] >= 0 && effect_slot_matches((uint32_t)s[o], (uint32_t)s[o + 1], (uint32_t)node, (uint32_t)tok)) {
+                hit = true;
+                w1 = (uint32_t)s[o + 1]; w2 = (uint32_t)s[o + 2]; w3 = (uint32_t)s[o + 3];
+            }
+        }
+        if (hit) {
+            const EffectFields f = effect_unpack(w1, w2, w3);
+            r.found = 1;
+            r.k = f.k;
+            r.peak = f.peak;
+            r.np = f.np;
+            r.inline_count = f.inline_count;
+            r.x0 = f.x0;
+            r.x1 = f.x1;
+            return r;
+        }
+        if (!inner) return r;
+        int j = -1;
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < nd.child_count && first[k] == x) j = k;
+        if (j < 0 && nd.child_count > 16) {
+            j = scalar_find<1>(kids + 16, nd.child_count - 16, x);
+            if (j >= 0) j += 16;
+        }
+        if (j < 0) return r;
+        node = nd.b + j;
+        nd = scalar_node(E.nodes + node);
     }
     return r;
 }

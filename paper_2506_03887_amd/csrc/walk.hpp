@@ -74,6 +74,35 @@ __device__ __forceinline__ int uni(int v) {
     return kUniform ? __builtin_amdgcn_readfirstlane(v) : v;
 }
 
+// Wider scalar loads for a wave that must stay off the vector-memory path (its block's other waves
+// have a long queue of loads in flight there, and vector loads return in order): 8 or 16 consecutive
+// 32-bit words at a wave-uniform, 4-byte aligned address of a read-only table.  A 16-word load may
+// reach up to 60 bytes past the entries the caller wants: every uploaded table ends with that much
+// padding.
+typedef int NativeInt8 __attribute__((ext_vector_type(8)));
+typedef int NativeInt16 __attribute__((ext_vector_type(16)));
+typedef NativeInt8 __attribute__((aligned(4))) NativeInt8U;
+typedef NativeInt16 __attribute__((aligned(4))) NativeInt16U;
+__device__ __forceinline__ NativeInt8 scalar_load8(const void *p) { return *(ConstPtr<NativeInt8U>)p; }
+__device__ __forceinline__ NativeInt16 scalar_load16(const void *p) { return *(ConstPtr<NativeInt16U>)p; }
+
+// Position of `x` among the `count` ascending values that start at list[0], or -1; values at a stride
+// of kStride words (1: plain list, 2: the first halves of pairs).  All arguments wave-uniform.
+template <int kStride>
+__device__ __forceinline__ int scalar_find(const int32_t *list, int count, int x) {
+    constexpr int kPer = 16 / kStride;
+    for (int c0 = 0; c0 < count; c0 += kPer) {
+        const NativeInt16 v = scalar_load16(list + (size_t)c0 * kStride);
+        int found = -1;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k)
+            if (c0 + k < count && v[k * kStride] == x) found = c0 + k;
+        if (found >= 0) return found;
+        if (v[(kPer - 1) * kStride] > x && c0 + kPer <= count) return -1;      // ascending: x cannot follow
+    }
+    return -1;
+}
+
 // The sequence's stack as the walk sees it: row[0..n), optionally with its top `kWindow` entries
 // staged in LDS (win[k] = entry k below the top).
 constexpr int kWindow = 64;
@@ -96,7 +125,7 @@ struct StackView {
 // the exposed state (its stack-matching condition) and pushes the goto target, until an
 // acceptance edge shifts the symbol.
 // With kCheckCap the walk reports kOverflow exactly when a push would exceed `cap` entries.
-template <bool kCheckCap, bool kUniform = false>
+template <bool kCheckCap, bool kUniform = false, bool kScalarOnly = false>
 __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int info, int &base, int &d,
                                     int &top, int &tree, const StackView &row, int cap, int *run_node = nullptr) {
     const int col = info & 0xFF, delta = info >> 8;    // byte class and per-byte target offset
@@ -167,7 +196,15 @@ __device__ __forceinline__ int feed(const DevTables &T, PrivateStack &priv, int 
             }
             x = uni<kUniform>(x);
             int next = -1;
-            if (kUniform) {
+            if (kUniform && kScalarOnly) {
+                // the same search through the scalar cache: the condition states first, then the child's record and cell
+                const int j = scalar_find<2>(reinterpret_cast<const int32_t *>(T.sym_pairs + nd.y), nd.z, x);
+                if (j < 0) break;
+                next = nd.w + j;
+                node = next;
+                nd = table<true>(T.sym_nodes, node);
+                cell = table<true>(T.sym_cell, node * T.ncol + col);
+            } else if (kUniform) {
                 // all lanes run this walk: lane j fetches condition j together with child j's node
                 // record and cell, so one round of loads both picks the child and enters it
                 const int lane = threadIdx.x & 63;
