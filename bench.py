@@ -124,9 +124,10 @@ def parse_args(argv=None):
                     help="shortest token that gets a stack-effect record (0 = the library's default; -1 = no records)")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (a scaling probe: the JSON line names the workload with the new size)")
-    ap.add_argument("--step", choices=["two-call", "fused", "advance-fill"], default="advance-fill",
+    ap.add_argument("--step", choices=["two-call", "fused", "advance-fill", "one-call"], default="one-call",
                     help="fill_mask + apply_mask + advance | fill_apply_mask + advance | "
-                         "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS)")
+                         "apply_mask + advance_fill_mask (advance and next mask in one launch, slot reuse on EOS) | "
+                         "advance_fill_apply_mask (the whole step in one launch)")
     return ap.parse_args(argv)
 
 
@@ -209,6 +210,9 @@ def main(argv=None):
             torch.where(reset_d[s], fresh_d, ls_d, out=ls_d)
 
     def step(s, kind):
+        if kind == "one-call":         # advance by this step's tokens, next mask, and that mask on the next logits
+            lib.advance_fill_apply_mask(tokens_d[s], mask_d, logits[(s + 1) % n_pool], restart_on_eos=True)
+            return
         if kind == "advance-fill":     # mask_d already holds this step's mask (from the previous call)
             apply_mask(logits[s % n_pool], mask_d, V)
             lib.advance_fill_mask(tokens_d[s], mask_d, restart_on_eos=True)
@@ -231,6 +235,7 @@ def main(argv=None):
     apply_mask(logits[0], mask_d, V)
     lib.advance(skip_d)
     lib.advance_fill_mask(skip_d, mask_d, restart_on_eos=True)
+    lib.advance_fill_apply_mask(skip_d, mask_d, logits[0], restart_on_eos=True)
     for s in range(Wm):
         step(s, "fused" if s % 2 else "fill+apply")
     torch.cuda.synchronize()
@@ -279,6 +284,11 @@ def main(argv=None):
         t0 = time.perf_counter()
         for s in range(K):
             lg = logits[(Wm + s) % n_pool]
+            if kind == "one-call":
+                ev[s][0].record()
+                lib.advance_fill_apply_mask(tokens_d[Wm + s], mask_d, logits[(Wm + s + 1) % n_pool], restart_on_eos=True)
+                ev[s][1].record()
+                continue
             if kind == "advance-fill":
                 ev[s][0].record()
                 apply_mask(lg, mask_d, V)
@@ -301,6 +311,8 @@ def main(argv=None):
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
         d = lambda i, j: np.array([e[i].elapsed_time(e[j]) for e in ev]) * 1e3
+        if kind == "one-call":
+            return {"advance_fill_apply_mask": d(0, 1)}, wall
         if kind == "advance-fill":
             return {"apply_mask": d(0, 1), "advance_fill_mask": d(1, 2)}, wall
         if kind == "fused":
@@ -318,8 +330,8 @@ def main(argv=None):
                 apply_mask(logits[s % n_pool], mask_d, V)
         return replay_best(g) * 1e3 / K
 
-    def in_step_us():
-        """Durations of the two kernels of the advance-fill step where they run: the K timed steps are
+    def in_step_us(kind):
+        """Durations of the kernels of the step (advance-fill: two, one-call: one) where they run: the K timed steps are
         captured once more with a one-thread kernel between the calls that writes the device's
         100 MHz clock (HIP events cannot be recorded inside a graph here).  A stamp kernel sits between
         every two kernels, so a difference of two stamps is one kernel plus one stamp launch; that
@@ -333,6 +345,10 @@ def main(argv=None):
             for s in range(K):
                 device_timestamp(stamps, 4 * s)
                 device_timestamp(stamps, 4 * s + 1)
+                if kind == "one-call":
+                    lib.advance_fill_apply_mask(tokens_d[Wm + s], mask_d, logits[(s + 1) % n_pool], restart_on_eos=True)
+                    device_timestamp(stamps, 4 * s + 2)
+                    continue
                 apply_mask(logits[s % n_pool], mask_d, V)
                 device_timestamp(stamps, 4 * s + 2)
                 lib.advance_fill_mask(tokens_d[Wm + s], mask_d, restart_on_eos=True)
@@ -345,9 +361,13 @@ def main(argv=None):
             torch.cuda.synchronize()
             t = stamps.cpu().numpy().reshape(K, 4).astype(np.float64) * 0.01        # microseconds
             cost = np.median(t[:, 1] - t[:, 0])
-            cur = {"apply_mask": float(np.mean(t[:, 2] - t[:, 1]) - cost), "advance_fill_mask": float(np.mean(t[:, 3] - t[:, 2]) - cost),
-                   "stamp_cost": float(cost)}
-            if best is None or cur["apply_mask"] + cur["advance_fill_mask"] < best["apply_mask"] + best["advance_fill_mask"]:
+            if kind == "one-call":
+                cur = {"advance_fill_apply_mask": float(np.mean(t[:, 2] - t[:, 1]) - cost), "stamp_cost": float(cost)}
+            else:
+                cur = {"apply_mask": float(np.mean(t[:, 2] - t[:, 1]) - cost),
+                       "advance_fill_mask": float(np.mean(t[:, 3] - t[:, 2]) - cost), "stamp_cost": float(cost)}
+            total_us = lambda r: sum(x for k_, x in r.items() if k_ != "stamp_cost")
+            if best is None or total_us(cur) < total_us(best):
                 best = cur
         return best
 
@@ -379,15 +399,19 @@ def main(argv=None):
         return replay_best(g) * 1e3 / K
 
     # =========================== headline: the step, then the dominant kernel ===========================
-    step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill"}[args.step]
+    step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill", "one-call": "one-call"}[args.step]
     step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
                  "fused": "pre3_fill_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
                  "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "
-                                 "slot reuse on EOS)"}
+                                 "slot reuse on EOS)",
+                 "one-call": "pre3_advance_fill_apply_mask (advance, next mask and masked logits in one launch, "
+                             "slot reuse on EOS)"}
     step_us = None
     if args.eager:
         step_us, t_step = eager_pass(step_kind)
         apply_us = float(step_us["apply_mask"].mean()) if "apply_mask" in step_us else float("nan")
+        if step_kind == "one-call":
+            apply_us = float(step_us["advance_fill_apply_mask"].mean())
     else:
         t_step = timed_graph(step_kind)
     # the device now holds the state after all K timed steps of `step_kind`: kept for the check below
@@ -397,8 +421,11 @@ def main(argv=None):
         apply_alone_us = apply_launch_us()
         apply_us = apply_alone_us
         if step_kind == "advance-fill":
-            in_step = in_step_us()
+            in_step = in_step_us(step_kind)
             apply_us = in_step["apply_mask"]
+        if step_kind == "one-call":
+            in_step = in_step_us(step_kind)
+            apply_us = in_step["advance_fill_apply_mask"]
 
     out = {
         "metric": "masked (seq x vocab) tokens/sec",
@@ -416,7 +443,13 @@ def main(argv=None):
     }
 
     # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
-    if step_kind != "fused":
+    if step_kind == "one-call":
+        # the one kernel of the step reads and writes the logits (4 B/pair) and writes the mask (one bit per pair)
+        dom_name, dom_bytes, dom_us = "advance_fill_apply_kernel", APPLY_BYTES_PER_PAIR * pairs, apply_us
+        dom_timing = ("HIP events around every launch of an eager pass over the timed steps" if args.eager else
+                      "inside the K timed steps replayed as one HIP graph: device clock stamps (one-thread kernels) before and "
+                      "after every launch, minus the cost of a stamp")
+    elif step_kind != "fused":
         dom_name, dom_bytes, dom_us = "apply_mask_vec8_kernel", APPLY_BYTES_PER_PAIR * pairs, apply_us
         dom_timing = ("HIP events around every launch of an eager pass over the timed steps" if args.eager else
                       "inside the K timed steps replayed as one HIP graph: device clock stamps (one-thread kernels) before and "
@@ -435,11 +468,14 @@ def main(argv=None):
                        "kernel": dom_name, "algorithmic_bytes_per_launch": dom_bytes, "launch_us": dom_us,
                        "timing": dom_timing, "traffic_source": traffic_note,
                        "frac_on_traffic": None if traffic is None else traffic / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
-    if in_step:
+    if in_step and step_kind == "advance-fill":
         # the same kernel launched K times back to back finds its mask bytes in L2 and runs faster than in the step
         out["roofline"]["launch_us_back_to_back"] = apply_alone_us
         out["roofline"]["frac_back_to_back"] = dom_bytes / (apply_alone_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    if in_step:
         out["in_step_kernel_us"] = in_step
+    if step_kind == "one-call":
+        out["apply_mask_alone_us"] = apply_alone_us
 
     # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
     def cpu_baseline():
@@ -495,6 +531,8 @@ def main(argv=None):
         r["mask_apply_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9 / HBM_PEAK_GBS
         r["step_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (t_step / K * 1e-3) / 1e9 / HBM_PEAK_GBS
         r["graph_ms_per_step"] = {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K}
+        if step_kind == "one-call" and not args.eager:
+            r["graph_ms_per_step"][step_text["advance-fill"]] = timed_graph("advance-fill") / K
         return r
 
     def state_check():
@@ -506,7 +544,7 @@ def main(argv=None):
             d_h[rs, 0], l_h[rs], s_h[rs] = s0[rs], 1, s0[rs]
             err = o.advance_batch(s_h, d_h, l_h, traj.tokens[s], v)
             assert not err.any()
-        if step_kind == "advance-fill":            # slot reuse happened inside the last call
+        if step_kind in ("advance-fill", "one-call"):            # slot reuse happened inside the last call
             fin = s_h < 0
             s_h[fin], l_h[fin] = s0[fin], 1
         assert (final_states_d.cpu().numpy() == s_h).all() and (final_len_d.cpu().numpy() == l_h).all(), \

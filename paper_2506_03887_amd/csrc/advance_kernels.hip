@@ -53,7 +53,9 @@ __device__ __forceinline__ int walk_staged_token(const DevTables &T, PrivateStac
     const int n_bytes = tok.hi - tok.lo;
     int rc = n_bytes > 0 ? kFed : kRejected;
     for (int i = 0; i < n_bytes && rc == kFed; ++i) {
-        const int info = __builtin_amdgcn_readfirstlane(i < 64 ? s_info[i] : T.byte_info[T.vbytes[tok.lo + i]]);
+        int info = lds_read(s_info + (i < 64 ? i : 63));
+        if (i >= 64) info = T.byte_info[T.vbytes[tok.lo + i]];
+        info = __builtin_amdgcn_readfirstlane(info);
         int run_node = -1;
         rc = feed<true, true, kScalar>(T, priv, info, base, d, top, kind, view, cap, &run_node);
         // (a run is examined with one vector load per lane: a wave that keeps to scalar loads takes short tails byte by byte)
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(64 * kAdvSeqPerBlock) void advance_kernel(
                 EffectHit fx{0, 0, 0, 0, 0, 0, 0};
                 if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len)
                     fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win[wave], n,
-                                     [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                                     [&](int k2) { return global_read(row + (n - 1 - k2)); }, t, lane);
                 int rc;
                 if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
                     if (n + fx.peak >= cap) {
@@ -394,10 +396,10 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
                 if (fx_root >= 0 && top == st && tok.hi - tok.lo >= E.fx_min_len) {
                     if (kScalar)
                         fx = find_effect_scalar(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
-                                                [&](int k2) { return row[n - 1 - k2]; }, __builtin_amdgcn_readfirstlane(t));
+                                                [&](int k2) { return global_read(row + (n - 1 - k2)); }, __builtin_amdgcn_readfirstlane(t));
                     else
                         fx = find_effect(E, __builtin_amdgcn_readfirstlane(fx_root), fx_nd, s_win, n,
-                                         [&](int k2) { return row[n - 1 - k2]; }, t, lane);
+                                         [&](int k2) { return global_read(row + (n - 1 - k2)); }, t, lane);
                 }
                 int rc;
                 if (fx.found && fx.k <= n && fx.np <= T.max_depth) {
@@ -432,7 +434,10 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
             }
         }
     }
-    // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart)
+    // ---- the new stack is  row[0 .. base) ++ priv[0 .. d)  (or just its bottom after a restart).
+    // Its top is staged and the condition tree descended BEFORE anything is stored: a wave that has
+    // stores in flight waits for them wherever it next waits for a load, and in the one-launch step
+    // kernel they complete only behind the row loads of the block's other waves.
     int nl = out_len;
     if (kCompact && shape_ok) {
         // put it together in LDS, compact it, write back what changed
@@ -442,12 +447,6 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
         __builtin_amdgcn_wave_barrier();
         int first_moved = nl;
         if (nl >= 2) nl = fold_cycles(stack, nl, cycle_head, cycle_pool, T.n_states, lane, &first_moved);
-        const int from = restarted ? nl : (first_moved < base ? first_moved : base);
-        for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
-        if (lane == 0) {
-            err[b] = out_err;
-            if ((out_err == 0 && t >= 0) || nl != n) { states[b] = out_state; len[b] = nl; }
-        }
         auto new_at = [&](int k) -> int32_t { return k < nl ? stack[nl - 1 - k] : -1; };
         s_new[lane] = lane < nl ? stack[nl - 1 - lane] : -1;
         __builtin_amdgcn_wave_barrier();
@@ -461,32 +460,38 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
             else plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
         }
         if (lane == 0) { plan.top = top; plan.len = nl; }
+        const int from = restarted ? nl : (first_moved < base ? first_moved : base);
+        for (int i = from + lane; i < nl; i += 64) row[i] = stack[i];
+        if (lane == 0) {
+            err[b] = out_err;
+            if ((out_err == 0 && t >= 0) || nl != n) { states[b] = out_state; len[b] = nl; }
+        }
     } else {
-    if (lane == 0) {
-        err[b] = out_err;
-        if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
-    }
-    //      stage its top in LDS and commit the private part
-    auto new_at = [&](int k) -> int32_t {           // entry k below the new top
-        if (restarted) return k == 0 ? row[0] : -1;
-        if (k < d) return priv.get(d - 1 - k);
-        const int idx = base - 1 - (k - d);
-        return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
-    };
-    s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
-    commit_overlay(row, priv, base, d, lane);
-    __builtin_amdgcn_wave_barrier();
-    // ---- descent of the condition tree with the new stack
-    const int top = s_new[0];
-    if (out_state < 0) {
-        if (lane == 0) plan.mode = kRowDone;
-    } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
-        if (lane == 0) plan.mode = kRowEmpty;
-    } else {
-        if (kScalar) plan_row_scalar(E, scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(top)), s_new, nl, new_at, &plan, lane);
+        auto new_at = [&](int k) -> int32_t {           // entry k below the new top
+            if (restarted) return k == 0 ? (kScalar ? table<true>(const_cast<const int32_t *>(row), 0) : row[0]) : -1;
+            if (k < d) return priv.get(d - 1 - k);
+            const int idx = base - 1 - (k - d);
+            return idx >= 0 ? StackView{row, s_win, n}.at(idx) : -1;
+        };
+        s_new[lane] = (shape_ok && lane < nl) ? new_at(lane) : -1;
+        __builtin_amdgcn_wave_barrier();
+        // ---- descent of the condition tree with the new stack
+        const int top = s_new[0];
+        if (out_state < 0) {
+            if (lane == 0) plan.mode = kRowDone;
+        } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
+            if (lane == 0) plan.mode = kRowEmpty;
+        } else {
+            if (kScalar) plan_row_scalar(E, scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(top)), s_new, nl, new_at, &plan, lane);
             else plan_row(E, E.root_nodes[top], s_new, nl, new_at, &plan, lane);
-    }
-    if (lane == 0) { plan.top = top; plan.len = nl; }
+        }
+        if (lane == 0) { plan.top = top; plan.len = nl; }
+        // ---- commit the private part
+        commit_overlay(row, priv, base, d, lane);
+        if (lane == 0) {
+            err[b] = out_err;
+            if (out_err == 0 && t >= 0) { states[b] = out_state; len[b] = out_len; }
+        }
     }
 }
 
@@ -528,7 +533,7 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
         const int64_t per_xcd = (gridDim.x + 7) >> 3, idle = kAfBlock - 64;
         int acc = 0;
         for (int64_t off = ((int64_t)(blockIdx.x >> 3) * idle + (tid - 64)) * 128; off < T.hot_bytes; off += per_xcd * idle * 128)
-            acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
+            acc |= *(const volatile __attribute__((address_space(1))) int *)(T.hot_begin + off);
         if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
         if (kCompact && stage_cycles) {                 // ... and copy the cycle tables into LDS for wave 0
             int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + ((T.n_words + 3) >> 2)) + cap;
@@ -587,8 +592,10 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
                                          cycle_head, cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec), s_win,
                                          s_new, s_info, s_adv_stack, plan, b, lane);
-        __syncthreads();                               // the plan is there
-        __syncthreads();                               // the materialised row (or zeros) is in LDS
+        // (barriers that order LDS only: this wave's stores of the new stack are still on their way, and
+        // nothing in this block reads them before the launch ends -- except the walks below, which wait)
+        lds_barrier();                                 // the plan is there
+        lds_barrier();                                 // the materialised row (or zeros) is in LDS
         // tokens the tree leaves undetermined are walked on the committed stack, one lane per token
         PrivateStack wp;
         wp.lds = s_walk_stack + lane;
@@ -596,6 +603,8 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         wp.spill = walk_spill + (size_t)b * 64 + lane;
         wp.spill_stride = walk_spill_stride;
         const int mode = plan.mode, n = plan.len, top0 = plan.top;
+        if (mode == kRowWalkAll || (mode == kRowFast && plan.walk_count > 0))
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // the walks read the committed stack
         if (mode == kRowFast) {
             const int wc = plan.walk_count;
             for (int k = lane; k < wc; k += 64) {
@@ -608,14 +617,14 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         } else if (mode == kRowDone && lane == 0) {
             bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
         }
-        __syncthreads();                               // the row is complete
+        lds_barrier();                                 // the row is complete
     } else {
         const int j = tid - 64;
         {   // pull the small tables of the walk into this XCD's L2, as in advance_fill_kernel
             const int64_t per_xcd = (gridDim.x + 7) >> 3;
             int acc = 0;
             for (int64_t off = ((int64_t)(blockIdx.x >> 3) * kStepData + j) * 128; off < T.hot_bytes; off += per_xcd * kStepData * 128)
-                acc |= *reinterpret_cast<const volatile int *>(T.hot_begin + off);
+                acc |= *(const volatile __attribute__((address_space(1))) int *)(T.hot_begin + off);
             if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
         }
         if (kCompact && stage_cycles) {
@@ -638,7 +647,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
 #endif
             if (g < whole) held[i] = stream_load(lrow + (size_t)g * 8);
         }
-        __syncthreads();                               // the plan is there (and the logits have arrived)
+        lds_barrier();                                 // the plan is there
         const int mode = plan.mode;
         if (mode == kRowFast && plan.dense >= 0) {
             const uint4 *src = reinterpret_cast<const uint4 *>(E.dense_rows) + (size_t)plan.dense * n_vec;
@@ -646,7 +655,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         } else {
             for (int w = j; w < n_vec; w += kStepData) bits4[w] = make_uint4(0, 0, 0, 0);
         }
-        __syncthreads();                               // the materialised row (or zeros) is in LDS
+        lds_barrier();                                 // the materialised row (or zeros) is in LDS
         if (mode == kRowFast) {
             const int nseg = plan.nseg;
             for (int i = 0; i < nseg; ++i) {
@@ -658,7 +667,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
                 }
             }
         }
-        __syncthreads();                               // the row is complete
+        lds_barrier();                                 // the row is complete
         if (vector_ok) {
             uint4 *dst4 = reinterpret_cast<uint4 *>(dst_row);
             for (int w = j; w < n_vec; w += kStepData) stream_store(bits4[w], dst4 + w);

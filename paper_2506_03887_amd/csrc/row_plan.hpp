@@ -47,7 +47,8 @@ __device__ __forceinline__ void plan_row(const DevTokenEdges &E, DevConditionNod
             break;
         }
         if (nd.known >= n || nseg >= kMaxPath) { mode = kRowWalkAll; break; }
-        const int x = nd.known < kWindow ? win[nd.known] : deeper(nd.known);
+        int x = lds_read(win + (nd.known < kWindow ? nd.known : kWindow - 1));
+        if (nd.known >= kWindow) x = deeper(nd.known);
         bool found = false;
         for (int c0 = 0; c0 < nd.child_count && !found; c0 += 64) {
             const int j = c0 + lane;
@@ -111,7 +112,9 @@ __device__ __forceinline__ void plan_row_scalar(const DevTokenEdges &E, DevCondi
             break;
         }
         if (nd.known >= n || nseg >= kMaxPath) { mode = kRowWalkAll; break; }
-        const int x = __builtin_amdgcn_readfirstlane(nd.known < kWindow ? win[nd.known] : deeper(nd.known));
+        int x = lds_read(win + (nd.known < kWindow ? nd.known : kWindow - 1));
+        if (nd.known >= kWindow) x = deeper(nd.known);
+        x = __builtin_amdgcn_readfirstlane(x);
         const int j = scalar_find<1>(E.child_state + nd.a, nd.child_count, x);
         if (j < 0) { mode = kRowWalkAll; break; }
         nd = scalar_node(E.nodes + nd.b + j);
@@ -150,7 +153,10 @@ __device__ __forceinline__ EffectHit find_effect(const DevTokenEdges &E, int nod
             slot = E.fx_slots[(size_t)(lane < kEffectBucketSlots ? b1 : b2) * kEffectBucketSlots + (lane & (kEffectBucketSlots - 1))];
         const bool inner = nd.child_count > 0 && nd.known < n;
         int x = -3;
-        if (inner) x = nd.known < kWindow ? win[nd.known] : deeper(nd.known);
+        if (inner) {
+            x = lds_read(win + (nd.known < kWindow ? nd.known : kWindow - 1));
+            if (nd.known >= kWindow) x = deeper(nd.known);
+        }
         int cstate = -2;
         DevConditionNode c{};
         int j = lane - 2 * kEffectBucketSlots;
@@ -212,7 +218,11 @@ __device__ __forceinline__ EffectHit find_effect_scalar(const DevTokenEdges &E, 
         const int32_t *kids = E.child_state + (inner ? nd.a : 0);
         const NativeInt16 first = scalar_load16(kids);
         int x = -3;
-        if (inner) x = __builtin_amdgcn_readfirstlane(nd.known < kWindow ? win[nd.known] : deeper(nd.known));
+        if (inner) {
+            x = lds_read(win + (nd.known < kWindow ? nd.known : kWindow - 1));
+            if (nd.known >= kWindow) x = deeper(nd.known);
+            x = __builtin_amdgcn_readfirstlane(x);
+        }
         bool hit = false;
         uint32_t w1 = 0, w2 = 0, w3 = 0;
 #pragma unroll

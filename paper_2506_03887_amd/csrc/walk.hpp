@@ -17,6 +17,25 @@ constexpr int kRunGrows = 1 << 30;      // flag on a run's condition node: the r
 constexpr int kLdsDepth = 16;          // private stack entries kept in LDS per lane
 constexpr int kMaxChain = 1 << 20;     // reduction steps per input symbol before a walk gives up
 
+// Reads that name their address space.  Where the source chooses between an LDS and a global address
+// the compiler otherwise forms ONE load from the chosen generic address, a flat load, and a wave
+// waits for a flat load as for a vector-memory load -- in order behind whatever its compute unit
+// has in flight there -- even when the address turns out to be in LDS.
+__device__ __forceinline__ int32_t lds_read(const int32_t *p) {
+    return *(const __attribute__((address_space(3))) int32_t *)p;
+}
+__device__ __forceinline__ int32_t global_read(const int32_t *p) {
+    return *(const __attribute__((address_space(1))) int32_t *)p;
+}
+
+// Block barrier that orders the block's LDS accesses only.  __syncthreads also makes a wave wait until
+// its global stores are acknowledged, which takes microseconds while the memory system is saturated.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Private stack of one walk: the states pushed above the part of the sequence's stack that
 // is still untouched.  The first kLdsDepth entries live in LDS (one column per lane), deeper
 // ones in a global spill area (one column per resident lane), both indexed [depth][lane] so
@@ -27,7 +46,9 @@ struct PrivateStack {
     int lds_stride;
     size_t spill_stride;
     __device__ int32_t get(int i) const {
-        return i < kLdsDepth ? lds[i * lds_stride] : spill[(size_t)(i - kLdsDepth) * spill_stride];
+        int32_t v = lds_read(lds + (i < kLdsDepth ? i : kLdsDepth - 1) * lds_stride);
+        if (i >= kLdsDepth) v = global_read(spill + (size_t)(i - kLdsDepth) * spill_stride);
+        return v;
     }
     __device__ void set(int i, int32_t v) {
         if (i < kLdsDepth) lds[i * lds_stride] = v;
@@ -111,8 +132,11 @@ struct StackView {
     const int32_t *win;
     int n;
     __device__ int32_t at(int idx) const {
+        if (!win) return row[idx];
         const int k = n - 1 - idx;
-        return (win && k < kWindow) ? win[k] : row[idx];
+        int32_t v = lds_read(win + (k < kWindow ? k : kWindow - 1));
+        if (k >= kWindow) v = global_read(row + idx);
+        return v;
     }
 };
 
