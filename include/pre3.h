@@ -229,12 +229,19 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
  * the new rows on logits_bf16 (device, [batch, >= n_tokens] bf16 patterns, row_stride elements
  * between rows, masked in place).  Results are exactly those of the two calls in sequence --
  * states, stacks, err and bitmask as pre3_advance_fill_mask leaves them, logits as pre3_apply_mask
- * then leaves them.  Where the sizes allow (logits aligned to 16 bytes, row_stride a multiple of 8,
- * at most 153,600 tokens, token-level edges in use, the mask row and -- with cycle-aware stacks --
- * the stack within the kernel's LDS) the step is ONE kernel in which every sequence's logits are
- * fetched while its token is still being walked; otherwise the call is the two calls.
- * flags: as for pre3_advance_fill_mask.  Errors: BADARG (nothing bound, null pointer, unknown
- * flag, row_stride < n_tokens, logits not 2-byte aligned), HIP. */
+ * then leaves them.
+ * The step can run as ONE kernel in which every sequence's logits are fetched while its token is
+ * still being walked.  That form needs: logits aligned to 16 bytes, row_stride a multiple of 8, at
+ * most 153,600 tokens, token-level edges in use, and the mask row and -- with cycle-aware stacks --
+ * the stack within the kernel's LDS.  It holds one sequence's logits in the registers of one compute
+ * unit, so it pays when the batch is between a quarter of the GPU's compute units and all of them
+ * (64..256 sequences on 256 units: 23.9 against 30.5 us per step at 256 x 128,256); the call chooses
+ * it for such batches and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks for the one kernel
+ * at any batch size where the conditions above hold (the call is still the two calls where not).
+ * flags: PRE3_ADVANCE_RESTART_ON_EOS as for pre3_advance_fill_mask, PRE3_STEP_ONE_KERNEL.
+ * Errors: BADARG (nothing bound, null pointer, unknown flag, row_stride < n_tokens, logits not
+ * 2-byte aligned), HIP. */
+#define PRE3_STEP_ONE_KERNEL 2
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
                                  int64_t row_stride, int32_t flags, pre3_stream stream);
 

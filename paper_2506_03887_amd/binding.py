@@ -22,6 +22,7 @@ FLAG_STEPWISE_REDUCTIONS = 4
 FLAG_COMPACT_CYCLES = 8
 FLAG_NO_TOKEN_EFFECTS = 16
 ADVANCE_RESTART_ON_EOS = 1
+STEP_ONE_KERNEL = 2
 STATE_DONE = -1
 
 EXPORTS = [
@@ -333,13 +334,15 @@ class Pre3:
                                                      ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
                                                      _stream_ptr(stream)))
 
-    def advance_fill_apply_mask(self, tokens, bitmask, logits, restart_on_eos=False, stream=None):
-        """The whole decode step: advance, next mask rows, and those rows applied to `logits` in place."""
+    def advance_fill_apply_mask(self, tokens, bitmask, logits, restart_on_eos=False, one_kernel=False, stream=None):
+        """The whole decode step: advance, next mask rows, and those rows applied to `logits` in place.
+        one_kernel: ask for the one-kernel form at any batch size (the library chooses by itself otherwise)."""
         assert tokens.is_contiguous() and bitmask.is_contiguous() and bitmask.shape[1] == self.words
         assert logits.dim() == 2 and logits.stride(1) == 1 and logits.shape[0] == bitmask.shape[0]
         self._check(self._lib.pre3_advance_fill_apply_mask(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
                                                            _dev(logits, "u16"), logits.stride(0),
-                                                           ADVANCE_RESTART_ON_EOS if restart_on_eos else 0,
+                                                           (ADVANCE_RESTART_ON_EOS if restart_on_eos else 0) |
+                                                           (STEP_ONE_KERNEL if one_kernel else 0),
                                                            _stream_ptr(stream)))
 
     def apply_mask_argmax(self, logits, bitmask, out_tokens, stream=None):

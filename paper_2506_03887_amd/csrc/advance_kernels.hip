@@ -364,10 +364,6 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
         int32_t *cycle_lds = after_row + cap;
         cycle_head = cycle_lds;
         cycle_pool = cycle_lds + T.n_states;
-    } else if (kScalar) {
-        // this wave's vector loads (stack window, token bytes) are on their way: only now do the block's
-        // other waves queue theirs, so that these are not held up behind them
-        __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_wave_barrier();
     // ---- advance (all lanes hold identical values)
@@ -620,19 +616,18 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         lds_barrier();                                 // the row is complete
     } else {
         const int j = tid - 64;
-        {   // pull the small tables of the walk into this XCD's L2, as in advance_fill_kernel
+        // pull the small tables of the walk into this XCD's L2, as in advance_fill_kernel (the loaded
+        // words are looked at only at the very end, so nothing here waits for them)
+        int prefetched = 0;
+        {
             const int64_t per_xcd = (gridDim.x + 7) >> 3;
-            int acc = 0;
             for (int64_t off = ((int64_t)(blockIdx.x >> 3) * kStepData + j) * 128; off < T.hot_bytes; off += per_xcd * kStepData * 128)
-                acc |= *(const volatile __attribute__((address_space(1))) int *)(T.hot_begin + off);
-            if (acc == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the loads alive; no effect
+                prefetched |= *(const volatile __attribute__((address_space(1))) int *)(T.hot_begin + off);
         }
         if (kCompact && stage_cycles) {
             int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + n_vec) + cap;
             copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, j, kStepData);
             __syncthreads();
-        } else {
-            __builtin_amdgcn_s_barrier();              // wave 0 has queued its own vector loads
         }
         // the row of logits: every group of 8 that lies wholly inside the vocabulary
         uint16_t *lrow = logits + (size_t)b * row_stride;
@@ -703,6 +698,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             const int t = whole * 8 + j;
             if (!((bits[t >> 5] >> (t & 31)) & 1u)) lrow[t] = 0xFF80;
         }
+        if (prefetched == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the prefetch loads alive; no effect
     }
 }
 

@@ -580,11 +580,15 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
     if (h->bound_empty) return PRE3_OK;
     if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: no state bound");
     if (!tokens || !bitmask || !logits_bf16) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: null pointer");
-    if (flags & ~PRE3_ADVANCE_RESTART_ON_EOS) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: unknown flag");
+    if (flags & ~(PRE3_ADVANCE_RESTART_ON_EOS | PRE3_STEP_ONE_KERNEL)) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: unknown flag");
     if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: row stride below vocabulary size");
     if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: misaligned logits");
     const bool cycles = h->compact && h->T.n_cycles > 0;
-    const bool one_kernel = h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
+    // the one kernel keeps a sequence's logits in the registers of one compute unit: it pays while the batch
+    // fills a good part of the chip and no compute unit has to take a second sequence
+    const int batch = h->b_stacks.batch;
+    const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || (batch * 4 >= h->n_compute_units && batch <= h->n_compute_units);
+    const bool one_kernel = wanted && h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
                             advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles);
     if (one_kernel) {
         const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
@@ -595,7 +599,7 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
                                                  static_cast<hipStream_t>(stream));
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_apply_mask");
     }
-    const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags, stream);
+    const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags & PRE3_ADVANCE_RESTART_ON_EOS, stream);
     if (rc != PRE3_OK) return rc;
     hipError_t e = launch_apply_mask(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride,
                                      static_cast<hipStream_t>(stream));

@@ -112,14 +112,15 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
 
 
 def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, step_call_every=0,
-                        logits_pad=0, **lib_options):
+                        logits_pad=0, one_kernel=True, **lib_options):
     """Same trajectory, driven through pre3_advance_fill_mask with slot reuse on EOS: after every
     call the device's states/len/live stack/err and the next mask must equal the oracle's
     advance followed by its fill (whole bitmask on `full_mask_steps`, sampled rows otherwise).
     step_call_every = k > 0: every k-th step goes through pre3_advance_fill_apply_mask (the whole step
     as one call) on fresh seeded logits whose rows are `logits_pad` elements longer than the vocabulary;
     on those steps the whole bitmask is checked, and all B * (V + pad) logit patterns against the
-    oracle's apply_mask on the oracle's mask (the padding must come back untouched)."""
+    oracle's apply_mask on the oracle's mask (the padding must come back untouched).  one_kernel: ask for
+    the one-kernel form whatever the batch size (False: the library chooses by the batch size)."""
     import torch
 
     cfg = configs.get(cfg_idx)
@@ -155,7 +156,7 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
             logits[:, :V] = bf16_logits(rng, B, V)
             logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
             mask_d.fill_(0x5A5A5A5A)
-            lib.advance_fill_apply_mask(torch.from_numpy(tok).to(dev), mask_d, logits_d, restart_on_eos=True)
+            lib.advance_fill_apply_mask(torch.from_numpy(tok).to(dev), mask_d, logits_d, restart_on_eos=True, one_kernel=one_kernel)
         else:
             lib.advance_fill_mask(torch.from_numpy(tok).to(dev), mask_d, restart_on_eos=True)
         err_h = o.advance_batch(states_h, data_h, len_h, tok, v)

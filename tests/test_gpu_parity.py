@@ -102,7 +102,8 @@ def test_whole_step_as_one_call_all_configs():
     kernel runs with its partial last group and word-wise mask stores, without padding the rows are not
     16-byte aligned and the call takes its two-call form.  Config 2 also with leftover walks inside the kernel
     (shallow conditions), rows put together from id lists, every token walked, and without token-level edges
-    (two-call form); configs 3-6 at full size, 7 with cycle-aware stacks."""
+    (two-call form); configs 3-6 at full size, 7 with cycle-aware stacks.  All of these ask for the one-kernel
+    form whatever the batch size; the last three leave the choice to the library."""
     assert replay_advance_fill(1, step_call_every=1, logits_pad=7)["step_calls"] == 32
     assert replay_advance_fill(1, step_call_every=1)["step_calls"] == 32
     assert replay_advance_fill(2, steps=64, step_call_every=1)["step_calls"] == 64
@@ -116,13 +117,18 @@ def test_whole_step_as_one_call_all_configs():
     assert replay_advance_fill(5, steps=64, step_call_every=8)["step_calls"] == 8
     assert replay_advance_fill(6, steps=48, step_call_every=8, full_mask_steps=[])["step_calls"] == 6
     assert replay_advance_fill(7, steps=64, step_call_every=4)["step_calls"] == 16
+    # the form the library chooses by itself: one kernel at 256 sequences, the two calls at 4 and at 512
+    assert replay_advance_fill(3, steps=16, step_call_every=4, one_kernel=False)["step_calls"] == 4
+    assert replay_advance_fill(1, step_call_every=1, logits_pad=7, one_kernel=False)["step_calls"] == 32
+    assert replay_advance_fill(4, steps=8, step_call_every=4, full_mask_steps=[], one_kernel=False)["step_calls"] == 2
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "step"])
 def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
     """Sequences of config 2 fed, per step and sequence, one of: an allowed token, an arbitrary
     token (mostly not allowed), EOS (allowed or not), or no token; finished sequences keep
-    receiving tokens.  err, states, stacks and the next masks must follow the oracle exactly."""
+    receiving tokens.  err, states, stacks and the next masks must follow the oracle exactly
+    ("step": through the one kernel of pre3_advance_fill_apply_mask, whose masked logits are checked too)."""
     import torch
     from oracle import Oracle
     from paper_2506_03887_amd import Pre3
@@ -166,7 +172,15 @@ def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
         for code in (0, 1, 2):
             seen[code] += int((e_h == code).sum())
         t_d = torch.from_numpy(toks).to(dev)
-        if fused:
+        if fused == "step":
+            from oracle import apply_mask as oracle_apply_mask
+            from workloads.vocab import bf16_logits
+            logits = bf16_logits(rng, B, V)
+            logits_d = torch.from_numpy(logits.view(np.int16)).to(dev)
+            lib.advance_fill_apply_mask(t_d, mask, logits_d, one_kernel=True)
+            oracle_apply_mask(logits, o.fill_mask(states, data, length, v), V)
+            assert (logits_d.cpu().numpy().view(np.uint16) == logits).all(), step
+        elif fused:
             lib.advance_fill_mask(t_d, mask)
         else:
             lib.advance(t_d)
