@@ -400,6 +400,10 @@ def main(argv=None):
 
     # =========================== headline: the step, then the dominant kernel ===========================
     step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill", "one-call": "one-call"}[args.step]
+    if step_kind == "one-call" and not lib.step_is_one_kernel(logits[0]):
+        # outside the batch sizes (or vocabulary) of the one kernel the call is pre3_advance_fill_mask + pre3_apply_mask:
+        # time and label those
+        step_kind = "advance-fill"
     step_text = {"fill+apply": "pre3_fill_mask + pre3_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
                  "fused": "pre3_fill_apply_mask + pre3_advance (+ slot-reuse resets by the caller)",
                  "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "

@@ -244,6 +244,9 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 #define PRE3_STEP_ONE_KERNEL 2
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
                                  int64_t row_stride, int32_t flags, pre3_stream stream);
+/* Which form the call above takes for the bound batch and these logits: 1 = the one kernel,
+ * 0 = the two calls; BADARG if nothing is bound.  Host call, launches nothing. */
+int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags);
 
 /* Greedy sampling fused behind the mask (Sec. 1: invalid tokens are excluded, then a token is
  * sampled; here the sampler is the arg max).  For every bound sequence b:

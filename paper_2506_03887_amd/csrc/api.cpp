@@ -574,6 +574,23 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
     return pre3_fill_mask(h, h->b_states, h->b_stacks, bitmask, stream);
 }
 
+namespace {
+// The one kernel keeps a sequence's logits in the registers of one compute unit: it pays while the batch
+// fills a good part of the chip and no compute unit has to take a second sequence.
+bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
+    const int batch = h->b_stacks.batch;
+    const bool cycles = h->compact && h->T.n_cycles > 0;
+    const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || (batch * 4 >= h->n_compute_units && batch <= h->n_compute_units);
+    return wanted && h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
+           row_stride >= h->V.n_tokens && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles);
+}
+}  // namespace
+
+int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
+    if (!usable(h) || (!h->b_states && !h->bound_empty)) return PRE3_E_BADARG;
+    return !h->bound_empty && step_takes_one_kernel(h, logits_bf16, row_stride, flags) ? 1 : 0;
+}
+
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
                                  int64_t row_stride, int32_t flags, pre3_stream stream) {
     if (!usable(h)) return PRE3_E_BADARG;
@@ -584,13 +601,7 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
     if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: row stride below vocabulary size");
     if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: misaligned logits");
     const bool cycles = h->compact && h->T.n_cycles > 0;
-    // the one kernel keeps a sequence's logits in the registers of one compute unit: it pays while the batch
-    // fills a good part of the chip and no compute unit has to take a second sequence
-    const int batch = h->b_stacks.batch;
-    const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || (batch * 4 >= h->n_compute_units && batch <= h->n_compute_units);
-    const bool one_kernel = wanted && h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
-                            advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles);
-    if (one_kernel) {
+    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags)) {
         const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
         hipError_t e = launch_advance_fill_apply(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                                  h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,

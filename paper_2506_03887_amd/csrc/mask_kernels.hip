@@ -143,6 +143,7 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
             const int g_lo = w_lo * 4, g_cnt = max(v_cnt, 0) * 16;
             for (int g0 = tid; g0 < g_cnt; g0 += kEdgeBlock * 4) {
                 uint32_t m[4];
+                bool line[4];
                 uint4 v[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -150,13 +151,17 @@ __global__ __launch_bounds__(kEdgeBlock) void fill_mask_edges_kernel(
                     m[u] = gl < g_cnt ? mbytes[gl] : 0xFFu;
                     const int t0 = (g_lo + gl) * 8;
                     if (t0 >= T.n_tokens) m[u] = 0xFFu;                   // padding beyond the vocabulary
-                    if (m[u] != 0xFFu && m[u] != 0u && t0 + 8 <= T.n_tokens)
+                    // a 128-byte line (the groups of eight consecutive lanes) is written whole or not at all:
+                    // lines written in part cost the memory system far more than the bytes saved
+                    const unsigned long long changed = __ballot(m[u] != 0xFFu);
+                    line[u] = ((changed >> (tid & 56)) & 0xFFull) != 0 && t0 < T.n_tokens && gl < g_cnt;
+                    if (line[u] && m[u] != 0u && t0 + 8 <= T.n_tokens)
                         v[u] = *reinterpret_cast<const uint4 *>(lrow + t0);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const uint32_t mu = m[u];
-                    if (mu == 0xFFu) continue;
+                    if (!line[u]) continue;
                     const int t0 = (g_lo + g0 + u * kEdgeBlock) * 8;
                     uint16_t *p = lrow + t0;
                     if (t0 + 8 <= T.n_tokens) {
