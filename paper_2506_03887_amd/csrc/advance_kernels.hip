@@ -41,6 +41,75 @@ __device__ __forceinline__ StagedToken stage_token(const DevTables &T, int t, in
     return tok;
 }
 
+// Lanes kLane0 .. kLane0 + kCount of `w` replaced by the wave-uniform words v[kSrc0 ..] (one v_writelane
+// each; the lane is an immediate, the instruction takes one scalar register only).
+template <int kLane0, int kSrc0, int kCount, int kI = 0>
+__device__ __forceinline__ int32_t deal_to_lanes(int32_t w, const NativeInt16 &v) {
+    if constexpr (kI < kCount) {
+        asm("v_writelane_b32 %0, %1, %2" : "+v"(w) : "s"(v[kSrc0 + kI]), "n"(kLane0 + kI));
+        return deal_to_lanes<kLane0, kSrc0, kCount, kI + 1>(w, v);
+    } else {
+        return w;
+    }
+}
+
+// stage_token through the scalar cache: the token's 128-byte line comes as two 16-word loads, whose words
+// are dealt out to the lanes (lane i gets byte i's word) and stored with one LDS write.  Tokens longer
+// than the line holds take the vector path.
+__device__ __forceinline__ StagedToken stage_token_scalar(const DevTables &T, int t, int lane, int32_t *s_info) {
+    const int32_t *rec = T.tok_info + (size_t)t * 32;
+    const NativeInt16 a = scalar_load16(rec), b = scalar_load16(rec + 16);
+    const int n_bytes = a[0];
+    if (n_bytes < 0) return stage_token(T, t, lane, s_info);
+    static_assert(kTokInfoBytes == 31, "two 16-word loads hold the length and 31 bytes");
+    int32_t w = 0;
+    w = deal_to_lanes<0, 1, 15>(w, a);
+    w = deal_to_lanes<15, 0, 16>(w, b);
+    if (lane < n_bytes) s_info[lane] = w;
+    return StagedToken{0, n_bytes};
+}
+
+// The top 64 entries of a stack (win[k] = entry k below the top, -1 beyond the bottom) through the scalar
+// cache: four 16-entry loads that end at the top -- each moved to where it lies wholly inside the row's
+// cap entries, cap >= 16 --, dealt out to the lanes and stored with one LDS write.
+__device__ __forceinline__ void stage_window_scalar(const int32_t *row, int n, int cap, bool shape_ok, int lane, int32_t *win) {
+    win[lane] = -1;
+    if (!shape_ok) return;
+    int32_t w = 0;
+    int my_lo = 0;
+    auto chunk_begin = [&](int c) {
+        int lo = n - 16 * (c + 1);
+        lo = lo < 0 ? 0 : lo;
+        return lo > cap - 16 ? cap - 16 : lo;
+    };
+    // one chunk at a time, and only the chunks the stack reaches (few scalar registers live; the later loads
+    // find their cache lines where the first one brought them)
+    const int lo0 = chunk_begin(0);
+    w = deal_to_lanes<0, 0, 16>(w, scalar_load16(row + lo0));
+    my_lo = lo0;
+    int dealt = 16;                                     // lanes that hold an entry
+    if (n > 16) {
+        const int lo1 = chunk_begin(1);
+        w = deal_to_lanes<16, 0, 16>(w, scalar_load16(row + lo1));
+        if (lane >= 16) my_lo = lo1;
+        dealt = 32;
+        if (n > 32) {
+            const int lo2 = chunk_begin(2);
+            w = deal_to_lanes<32, 0, 16>(w, scalar_load16(row + lo2));
+            if (lane >= 32) my_lo = lo2;
+            dealt = 48;
+            if (n > 48) {
+                const int lo3 = chunk_begin(3);
+                w = deal_to_lanes<48, 0, 16>(w, scalar_load16(row + lo3));
+                if (lane >= 48) my_lo = lo3;
+                dealt = 64;
+            }
+        }
+    }
+    const int idx = my_lo + (lane & 15), k = n - 1 - idx;
+    if (lane < dealt && idx < n && k >= 0 && k < kWindow) win[k] = w;
+}
+
 constexpr int kScalarRunMin = 8;       // bytes left in a token before a scalar-only walk looks for a run
 
 // Walks a staged token from the configuration  view ++ priv[0..d)  with capacity checks.  Runs on
@@ -357,8 +426,13 @@ __device__ __forceinline__ void advance_and_plan(const DevTables &T, const DevTo
         fx_root = kScalar ? table<true>(E.root_id, st) : E.root_id[st];
         fx_nd = kScalar ? scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(st)) : E.root_nodes[st];
     }
-    s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
-    if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
+    if (kScalar && cap >= 16) {
+        stage_window_scalar(row, n, cap, shape_ok, lane, s_win);
+        if (live && t != T.eos_id) tok = stage_token_scalar(T, __builtin_amdgcn_readfirstlane(t), lane, s_info);
+    } else {
+        s_win[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
+        if (live && t != T.eos_id) tok = stage_token(T, t, lane, s_info);
+    }
     if (kCompact && stage_cycles) {                 // the other waves have copied the cycle tables meanwhile
         __syncthreads();
         int32_t *cycle_lds = after_row + cap;
@@ -616,14 +690,6 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         lds_barrier();                                 // the row is complete
     } else {
         const int j = tid - 64;
-        // pull the small tables of the walk into this XCD's L2, as in advance_fill_kernel (the loaded
-        // words are looked at only at the very end, so nothing here waits for them)
-        int prefetched = 0;
-        {
-            const int64_t per_xcd = (gridDim.x + 7) >> 3;
-            for (int64_t off = ((int64_t)(blockIdx.x >> 3) * kStepData + j) * 128; off < T.hot_bytes; off += per_xcd * kStepData * 128)
-                prefetched |= *(const volatile __attribute__((address_space(1))) int *)(T.hot_begin + off);
-        }
         if (kCompact && stage_cycles) {
             int32_t *cycle_lds = reinterpret_cast<int32_t *>(bits4 + n_vec) + cap;
             copy_cycle_tables(cycle_lds, T.n_states, T.cycle_pool_n, cycle_head, cycle_pool, j, kStepData);
@@ -640,7 +706,8 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
 #ifdef PRE3_STEP_IN_FLIGHT
             if (i >= PRE3_STEP_IN_FLIGHT) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRE3_STEP_IN_FLIGHT - 1));
 #endif
-            if (g < whole) held[i] = stream_load(lrow + (size_t)g * 8);
+            // (a wave-uniform base per i plus one 32-bit lane offset: no 64-bit address register per group)
+            if (g < whole) held[i] = stream_load(lrow + (size_t)i * (kStepData * 8) + (uint32_t)(j * 8));
         }
         lds_barrier();                                 // the plan is there
         const int mode = plan.mode;
@@ -688,7 +755,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
                         const uint32_t allow = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                         x[k] = (x[k] & allow) | (~allow & kNegInfPair);
                     }
-                    stream_store(v, lrow + (size_t)g * 8);
+                    stream_store(v, lrow + (size_t)i * (kStepData * 8) + (uint32_t)(j * 8));
                 }
             }
         }
@@ -698,7 +765,6 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             const int t = whole * 8 + j;
             if (!((bits[t >> 5] >> (t & 31)) & 1u)) lrow[t] = 0xFF80;
         }
-        if (prefetched == 0x7ff1234f && T.fault) atomicAdd(T.fault, 0);   // keeps the prefetch loads alive; no effect
     }
 }
 
