@@ -244,6 +244,20 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 #define PRE3_STEP_ONE_KERNEL 2
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
                                  int64_t row_stride, int32_t flags, pre3_stream stream);
+/* One whole greedy decode step as one call: pre3_advance_fill_mask followed by
+ * pre3_apply_mask_argmax of the new rows on logits_bf16 (device, [batch, >= n_tokens], row_stride
+ * elements between rows; only read).  Results are exactly those of the two calls in sequence:
+ * states, stacks, err and bitmask as pre3_advance_fill_mask leaves them, out_tokens[b] (device,
+ * [batch]) the arg max of the allowed logits of row b under the rules of pre3_apply_mask_argmax.
+ * out_tokens may be the tokens buffer itself (a greedy loop then needs no copy between steps).
+ * The call takes its one-kernel form -- the logits are fetched while the token is walked and the
+ * arg max is taken from the registers that hold them -- under the conditions and for the batch
+ * sizes of pre3_advance_fill_apply_mask, and is the two calls otherwise; flags as there.
+ * Errors: BADARG (nothing bound, null pointer, unknown flag, row_stride < n_tokens, logits not
+ * 2-byte aligned), HIP. */
+int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, const uint16_t *logits_bf16,
+                             int64_t row_stride, int32_t *out_tokens, int32_t flags, pre3_stream stream);
+
 /* Which form the call above takes for the bound batch and these logits: 1 = the one kernel,
  * 0 = the two calls; BADARG if nothing is bound.  Host call, launches nothing. */
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags);

@@ -27,7 +27,7 @@ STATE_DONE = -1
 
 EXPORTS = [
     "pre3_compile", "pre3_free", "pre3_last_error", "pre3_initial_state", "pre3_bind_state",
-    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_advance_fill_apply_mask", "pre3_step_is_one_kernel", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
+    "pre3_fill_mask", "pre3_apply_mask", "pre3_fill_apply_mask", "pre3_advance", "pre3_advance_fill_mask", "pre3_advance_fill_apply_mask", "pre3_advance_fill_argmax", "pre3_step_is_one_kernel", "pre3_apply_mask_argmax", "pre3_apply_mask_topk", "pre3_jump_forward", "pre3_n_grammars", "pre3_n_states",
     "pre3_n_byte_classes", "pre3_byte_class", "pre3_edge", "pre3_goto_target", "pre3_walk_depth_bound",
     "pre3_token_edge_stats", "pre3_debug_resolve_row", "pre3_symbol_edge_stats", "pre3_debug_advance", "pre3_debug_validate_tables",
     "pre3_forced_run", "pre3_n_reduction_cycles", "pre3_reduction_cycle", "pre3_debug_compact", "pre3_debug_fault_count", "pre3_debug_timestamp", "pre3_advance_static", "pre3_token_effect_stats", "pre3_debug_token_effect",
@@ -84,6 +84,7 @@ def load():
     lib.pre3_advance_fill_mask.argtypes = [vp, vp, vp, i32, vp]
     lib.pre3_advance_fill_apply_mask.argtypes = [vp, vp, vp, vp, c.c_int64, i32, vp]
     lib.pre3_step_is_one_kernel.argtypes = [vp, vp, c.c_int64, i32]
+    lib.pre3_advance_fill_argmax.argtypes = [vp, vp, vp, vp, c.c_int64, vp, i32, vp]
     lib.pre3_advance_static.argtypes = [vp, vp, vp, _Stacks, vp, vp]
     lib.pre3_apply_mask_argmax.argtypes = [vp, vp, c.c_int64, vp, vp, vp]
     lib.pre3_apply_mask_topk.argtypes = [vp, vp, c.c_int64, vp, i32, vp, vp, vp]
@@ -345,6 +346,16 @@ class Pre3:
                                                            (ADVANCE_RESTART_ON_EOS if restart_on_eos else 0) |
                                                            (STEP_ONE_KERNEL if one_kernel else 0),
                                                            _stream_ptr(stream)))
+
+    def advance_fill_argmax(self, tokens, bitmask, logits, out_tokens, restart_on_eos=False, one_kernel=False, stream=None):
+        """The whole greedy step: advance, next mask rows, and out_tokens[b] = arg max of the allowed logits of
+        row b (the logits are only read; out_tokens may be `tokens`)."""
+        assert tokens.is_contiguous() and bitmask.is_contiguous() and bitmask.shape[1] == self.words and out_tokens.is_contiguous()
+        assert logits.dim() == 2 and logits.stride(1) == 1 and logits.shape[0] == bitmask.shape[0] == out_tokens.numel()
+        self._check(self._lib.pre3_advance_fill_argmax(self._h, _dev(tokens, "i32"), _dev(bitmask, "u32"),
+                                                       _dev(logits, "u16"), logits.stride(0), _dev(out_tokens, "i32"),
+                                                       (ADVANCE_RESTART_ON_EOS if restart_on_eos else 0) |
+                                                       (STEP_ONE_KERNEL if one_kernel else 0), _stream_ptr(stream)))
 
     def step_is_one_kernel(self, logits, one_kernel=False):
         """Whether advance_fill_apply_mask runs as one kernel for the bound batch and these logits."""

@@ -4,6 +4,7 @@
 
 #include <mutex>
 
+#include "argmax.hpp"
 #include "launch.hpp"
 #include "row_plan.hpp"
 
@@ -638,14 +639,20 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
 // kernel with the same number of block barriers, so the registers that hold the logits are not live
 // in wave 0's code.  Masked logits are exactly those of apply_mask_vec8_kernel: fully allowed
 // groups are not written, every other group is written with -inf where a bit is clear.
+// kArgmax: the greedy decode step.  The logits are not written back; instead every lane takes the arg max
+// of the allowed logits among the groups it holds (the order keys of masked_argmax_kernel, the same rules:
+// largest value, first of equal values, +0 = -0, NaN never), the block combines the lanes, and out_tokens[b]
+// is the sequence's next token (-1 if nothing is allowed).  out_tokens may be the tokens buffer: block b
+// reads tokens[b] before anything else and writes out_tokens[b] last.
 constexpr int kStepBlock = 1024, kStepData = kStepBlock - 64;
-template <bool kCompact, int kHeld>
+static_assert(kStepBlock == kArgBlock, "the step kernel combines its lanes with argmax_block_max");
+template <bool kCompact, int kHeld, bool kArgmax>
 __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
-    DevTables T, DevTokenEdges E, const int32_t *__restrict__ tokens, int32_t *__restrict__ states,
+    DevTables T, DevTokenEdges E, const int32_t *tokens, int32_t *__restrict__ states,
     int32_t *__restrict__ data, int32_t *__restrict__ len, int cap, int batch, int32_t *__restrict__ err,
     uint32_t *__restrict__ bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
     size_t walk_spill_stride, const int32_t *cycle_head, const int32_t *cycle_pool, int stage_cycles,
-    uint16_t *__restrict__ logits, int64_t row_stride) {
+    uint16_t *__restrict__ logits, int64_t row_stride, int32_t *out_tokens) {
     extern __shared__ uint4 bits4[];                   // the mask row; kCompact: then cap stack entries [+ cycle tables]
     __shared__ int32_t s_win[kWindow], s_new[kWindow], s_info[64];
     __shared__ int32_t s_adv_stack[kLdsDepth], s_walk_stack[kLdsDepth * 64];
@@ -657,6 +664,12 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
     uint32_t *bits = reinterpret_cast<uint32_t *>(bits4);
     uint32_t *dst_row = bitmask + (size_t)b * T.n_words;
     const bool vector_ok = (T.n_words & 3) == 0 && (reinterpret_cast<uintptr_t>(bitmask) & 15) == 0;
+    uint16_t *lrow = logits + (size_t)b * row_stride;
+    unsigned long long mine = 0ull;                    // kArgmax: this lane's candidate
+    // kArgmax: half a mask byte -> AND masks of two registers.  Sixteen entries: lanes that read the same entry are
+    // served together and different entries lie in different banks (a 256-entry table of whole bytes cost 4-way
+    // bank conflicts on every read: 5.1 us for the arg max of a block instead of the 3.3 us it takes now)
+    __shared__ uint2 s_expand[kArgmax ? 16 : 1];
 
     if (tid < 64) {
         advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
@@ -696,7 +709,6 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             __syncthreads();
         }
         // the row of logits: every group of 8 that lies wholly inside the vocabulary
-        uint16_t *lrow = logits + (size_t)b * row_stride;
         const int whole = T.n_tokens >> 3;
         uint4 held[kHeld];
 #pragma unroll
@@ -708,6 +720,19 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
 #endif
             // (a wave-uniform base per i plus one 32-bit lane offset: no 64-bit address register per group)
             if (g < whole) held[i] = stream_load(lrow + (size_t)i * (kStepData * 8) + (uint32_t)(j * 8));
+        }
+        if (kArgmax) {
+            if (j < 16) {
+                uint32_t am[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) am[q] = (((j >> (2 * q)) & 1) ? 0x0000FFFFu : 0u) | (((j >> (2 * q + 1)) & 1) ? 0xFFFF0000u : 0u);
+                s_expand[j] = make_uint2(am[0], am[1]);
+            }
+            // the patterns become order keys as the groups arrive, under the loads still in flight
+#pragma unroll
+            for (int i = 0; i < kHeld; ++i)
+                held[i] = make_uint4(bf16_order_keys(held[i].x), bf16_order_keys(held[i].y), bf16_order_keys(held[i].z),
+                                     bf16_order_keys(held[i].w));
         }
         lds_barrier();                                 // the plan is there
         const int mode = plan.mode;
@@ -737,6 +762,59 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             for (int w = j; w < T.n_words; w += kStepData) dst_row[w] = bits[w];
         }
         const uint8_t *mask_bytes = reinterpret_cast<const uint8_t *>(bits4);     // byte g = bits of group g
+        if (kArgmax) {
+            // Per group: the mask byte's four AND masks come from the LDS table, masked halves get the lowest
+            // key, three packed maxima fold the group, and only the best key and the slot of its group are
+            // kept (a lane's groups ascend, so `>` keeps the first of equal values); the group itself is
+            // picked out of the registers once, at the end.
+            int best = kOrderNegInf - 1, best_i = -1;   // only a valid value (or a positive NaN pattern) beats the start
+            auto group_best = [&](uint4 v, uint32_t mu) {        // v: the group's order keys
+                const uint2 lo = s_expand[mu & 15u], hi = s_expand[mu >> 4];
+                const uint32_t k01 = packed_max_s16(mask_order_keys(v.x, lo.x), mask_order_keys(v.y, lo.y));
+                const uint32_t k23 = packed_max_s16(mask_order_keys(v.z, hi.x), mask_order_keys(v.w, hi.y));
+                const uint32_t kk = packed_max_s16(k01, k23);
+                return max((int)(int16_t)(kk & 0xFFFFu), (int)kk >> 16);
+            };
+#pragma unroll
+            for (int i = 0; i < kHeld; ++i) {
+                // no branches: a group outside the row or without an allowed token gets the lowest key in every
+                // half, which is below the start value, and the LDS reads of the groups can overlap
+                const int g = i * kStepData + j;
+                const uint32_t mu = mask_bytes[g < whole ? g : 0];
+                const int gb = group_best(held[i], g < whole ? mu : 0u);
+                best_i = gb > best ? i : best_i;
+                best = max(gb, best);
+            }
+            uint4 best_x = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < kHeld; ++i)
+                if (best_i == i) best_x = held[i];
+            int best_g = best_i >= 0 ? best_i * kStepData + j : -1;
+            uint32_t best_m = best_i >= 0 ? mask_bytes[best_g] : 0u;
+            const int tail = T.n_tokens & 7;
+            if (tail > 0 && j == 0) {                   // the last, partial group: its logits one at a time
+                uint32_t x[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int k = 0; k < 7; ++k)
+                    if (k < tail) x[k >> 1] |= (uint32_t)lrow[whole * 8 + k] << (16 * (k & 1));
+                const uint32_t mu = mask_bytes[whole] & ((1u << tail) - 1u);
+                if (mu != 0u) {
+                    const uint4 v = make_uint4(bf16_order_keys(x[0]), bf16_order_keys(x[1]), bf16_order_keys(x[2]), bf16_order_keys(x[3]));
+                    const int gb = group_best(v, mu);
+                    if (gb > best) { best = gb; best_g = whole; best_x = v; best_m = mu; }
+                }
+            }
+            if (best_g >= 0) {
+                const uint32_t x[4] = {best_x.x, best_x.y, best_x.z, best_x.w};
+                int first = 0;
+#pragma unroll
+                for (int k = 7; k >= 0; --k) {          // descending: the smallest k is assigned last
+                    const int key = (k & 1) ? ((int)x[k >> 1] >> 16) : (int)(int16_t)(x[k >> 1] & 0xFFFFu);
+                    if (((best_m >> k) & 1u) && key == best) first = k;
+                }
+                mine = argmax_word(best, best_g * 8 + first);
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < kHeld; ++i) {
             const int g = i * kStepData + j;
@@ -765,6 +843,16 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             const int t = whole * 8 + j;
             if (!((bits[t >> 5] >> (t & 31)) & 1u)) lrow[t] = 0xFF80;
         }
+        }
+    }
+    if (kArgmax) {
+        __shared__ unsigned long long s_part[kStepBlock / 64 + 1];
+        mine = argmax_block_max(mine, s_part, tid);
+        const int order = (int)(uint32_t)(mine >> 32) - 32768;
+        if (mine != 0ull && (order > kOrderPosInf || order == 0))      // a positive NaN pattern or a zero on top: compare as numbers
+            mine = argmax_block_max(argmax_segment_by_compare_inline(lrow, reinterpret_cast<const uint8_t *>(bits4), 0,
+                                                                     (T.n_tokens + 7) >> 3, T.n_tokens, tid), s_part, tid);
+        if (tid == 0) out_tokens[b] = mine != 0ull ? (int32_t)(0xFFFFFFFFu - (uint32_t)mine) : -1;
     }
 }
 
@@ -1014,16 +1102,16 @@ bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles) {
     return row_bytes <= kAfDynamicLdsMax;
 }
 
-template <bool kCompact>
+template <bool kCompact, bool kArgmax>
 static void launch_step_variant(int held, dim3 grid, size_t lds, hipStream_t stream, const DevTables &T, const DevTokenEdges &E,
                                 const int32_t *tokens, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
                                 int32_t *err, uint32_t *bitmask, int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
                                 const int32_t *cycle_head, const int32_t *cycle_pool, int stage, uint16_t *logits,
-                                int64_t row_stride) {
+                                int64_t row_stride, int32_t *out_tokens) {
 #define PRE3_STEP(H)                                                                                                        \
-    hipLaunchKernelGGL((advance_fill_apply_kernel<kCompact, H>), grid, dim3(kStepBlock), lds, stream, T, E, tokens, states,   \
-                       data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill, (size_t)batch * 64,     \
-                       cycle_head, cycle_pool, stage, logits, row_stride)
+    hipLaunchKernelGGL((advance_fill_apply_kernel<kCompact, H, kArgmax>), grid, dim3(kStepBlock), lds, stream, T, E, tokens,  \
+                       states, data, len, cap, batch, err, bitmask, restart_on_eos, adv_scratch, walk_spill,                 \
+                       (size_t)batch * 64, cycle_head, cycle_pool, stage, logits, row_stride, out_tokens)
     if (held <= 9) PRE3_STEP(9);
     else if (held <= 17) PRE3_STEP(17);
     else PRE3_STEP(20);
@@ -1034,24 +1122,30 @@ hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E,
                                      int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
                                      int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
                                      const int32_t *cycle_head, const int32_t *cycle_pool, uint16_t *logits,
-                                     int64_t row_stride, hipStream_t stream) {
+                                     int64_t row_stride, int32_t *out_tokens, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
     if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, cycle_head != nullptr)) return hipErrorInvalidValue;
     if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
         return hipErrorInvalidValue;
     const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;
     size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    int stage = 0;
     if (cycle_head) {
         lds += (size_t)cap * sizeof(int32_t);
         const size_t tables = (size_t)(T.n_states + T.cycle_pool_n) * sizeof(int32_t);
-        const int stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) && lds + tables <= kAfDynamicLdsMax;
+        stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) && lds + tables <= kAfDynamicLdsMax;
         if (stage) lds += tables;
-        launch_step_variant<true>(held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask,
-                                  restart_on_eos, adv_scratch, walk_spill, cycle_head, cycle_pool, stage, logits, row_stride);
-    } else {
-        launch_step_variant<false>(held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask,
-                                   restart_on_eos, adv_scratch, walk_spill, nullptr, nullptr, 0, logits, row_stride);
     }
+#define PRE3_STEP_ARGS held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask, restart_on_eos, \
+                       adv_scratch, walk_spill, cycle_head, cycle_pool, stage, logits, row_stride, out_tokens
+    if (cycle_head) {
+        if (out_tokens) launch_step_variant<true, true>(PRE3_STEP_ARGS);
+        else launch_step_variant<true, false>(PRE3_STEP_ARGS);
+    } else {
+        if (out_tokens) launch_step_variant<false, true>(PRE3_STEP_ARGS);
+        else launch_step_variant<false, false>(PRE3_STEP_ARGS);
+    }
+#undef PRE3_STEP_ARGS
     return hipGetLastError();
 }
 

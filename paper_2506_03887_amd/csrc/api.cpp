@@ -606,7 +606,7 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
         hipError_t e = launch_advance_fill_apply(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                                  h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
                                                  h->af_walk_spill, cycles ? h->cycle_head : nullptr,
-                                                 cycles ? h->cycle_pool : nullptr, logits_bf16, row_stride,
+                                                 cycles ? h->cycle_pool : nullptr, logits_bf16, row_stride, nullptr,
                                                  static_cast<hipStream_t>(stream));
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_apply_mask");
     }
@@ -615,6 +615,31 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
     hipError_t e = launch_apply_mask(logits_bf16, bitmask, h->b_stacks.batch, h->V.n_tokens, row_stride,
                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch apply_mask");
+}
+
+int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, const uint16_t *logits_bf16,
+                             int64_t row_stride, int32_t *out_tokens, int32_t flags, pre3_stream stream) {
+    if (!usable(h)) return PRE3_E_BADARG;
+    if (h->bound_empty) return PRE3_OK;
+    if (!h->b_states) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: no state bound");
+    if (!tokens || !bitmask || !logits_bf16 || !out_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: null pointer");
+    if (flags & ~(PRE3_ADVANCE_RESTART_ON_EOS | PRE3_STEP_ONE_KERNEL)) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: unknown flag");
+    if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: row stride below vocabulary size");
+    if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: misaligned logits");
+    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags)) {
+        const bool cycles = h->compact && h->T.n_cycles > 0;
+        const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
+        // the kernel only reads the logits in this form
+        hipError_t e = launch_advance_fill_apply(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
+                                                 h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
+                                                 h->af_walk_spill, cycles ? h->cycle_head : nullptr,
+                                                 cycles ? h->cycle_pool : nullptr, const_cast<uint16_t *>(logits_bf16), row_stride,
+                                                 out_tokens, static_cast<hipStream_t>(stream));
+        return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_argmax");
+    }
+    const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags & PRE3_ADVANCE_RESTART_ON_EOS, stream);
+    if (rc != PRE3_OK) return rc;
+    return pre3_apply_mask_argmax(h, logits_bf16, row_stride, bitmask, out_tokens, stream);
 }
 
 int pre3_apply_mask_argmax(pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, const uint32_t *bitmask,

@@ -287,6 +287,93 @@ def test_greedy_decode_in_lockstep_with_the_oracle(cfg_idx, steps, fused_advance
         assert (data_d.cpu().numpy()[live] == data_h[live]).all()
 
 
+def _special_rows_under_a_mask(rng, B, V, mask_h):
+    """Seeded logits whose first rows hold the cases the order keys cannot decide by themselves or must not get
+    wrong: zeros of both signs only, NaN patterns only, -inf only, positive NaN patterns around one finite
+    value, +inf twice, a negative NaN below everything, and -0 before +0 among the allowed tokens."""
+    logits = bf16_logits(rng, B, V)
+    allowed = [np.flatnonzero((mask_h[b][np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1) for b in range(B)]
+    if B >= 8:
+        logits[0] = np.where(rng.random(V) < 0.5, 0x8000, 0x0000)            # -0 / +0 everywhere: the first allowed id wins
+        logits[1] = np.where(rng.random(V) < 0.5, 0x7FC1, 0xFFC0)            # NaN everywhere: -1
+        logits[2] = 0xFF80                                                   # -inf everywhere: the first allowed id
+        logits[3] = 0x7FC1                                                   # positive NaN patterns ...
+        if len(allowed[3]) > 2:
+            logits[3, allowed[3][len(allowed[3]) // 2]] = 0xC000             # ... and one finite (negative) value
+        if len(allowed[4]) > 3:
+            logits[4, allowed[4][-1]] = logits[4, allowed[4][1]] = 0x7F80    # +inf twice: the smaller id
+        logits[5] = 0xFFC1                                                   # negative NaN patterns and one -inf
+        if len(allowed[5]) > 1:
+            logits[5, allowed[5][-1]] = 0xFF80
+        logits[6] = 0xBF80                                                   # -1 everywhere, then -0 before +0
+        if len(allowed[6]) > 2:
+            logits[6, allowed[6][0]], logits[6, allowed[6][-1]] = 0x8000, 0x0000
+    return logits
+
+
+@pytest.mark.parametrize("cfg_idx,steps,pad,one_kernel", [(1, 32, 7, True), (1, 32, 0, True), (2, 120, 0, True), (2, 40, 16, True),
+                                                          (3, 12, 0, False), (5, 8, 0, True), (6, 8, 0, True), (7, 10, 0, True),
+                                                          (4, 4, 0, True), (4, 3, 0, False)])
+def test_greedy_decode_through_the_one_call_step_in_lockstep_with_the_oracle(cfg_idx, steps, pad, one_kernel):
+    """pre3_advance_fill_argmax (advance, next mask and next greedy token in one call, the token buffer updated in
+    place) against the oracle's advance, fill and arg max: tokens, states, stacks, err and the whole mask at every
+    step, the logits untouched.  The first rows of every step's logits hold the value cases of _special_rows_under_a_mask.
+    Config 1 has a ragged vocabulary (partial last group; without padding its rows are misaligned and the call
+    takes its two-call form); config 4 at 512 sequences runs the one kernel only because it is asked for; config 7
+    has cycle-aware stacks."""
+    from paper_2506_03887_amd import Pre3
+    torch, dev = _torch()
+    cfg = configs.get(cfg_idx)
+    v = cfg.vocab
+    B, V, W, cap = cfg.batch, v.n_tokens, v.words, cfg.cap
+    o = Oracle(cfg.grammars, compact_cycles=cfg.compact)
+    gi, _ = configs.sequence_setup(cfg)
+    s0 = np.array([o.initial_state(int(g)) for g in gi], dtype=np.int32)
+    data_h = np.zeros((B, cap), dtype=np.int32)
+    data_h[:, 0] = s0
+    len_h = np.ones(B, dtype=np.int32)
+    states_h = s0.copy()
+    lib = Pre3(cfg.grammars, v.bytes, v.offsets, v.eos_id, max_token_len=max(1, v.max_len), stack_cap=cap,
+               compact_cycles=cfg.compact)
+    data_d, len_d = torch.from_numpy(data_h.copy()).to(dev), torch.from_numpy(len_h.copy()).to(dev)
+    states_d, err_d = torch.from_numpy(states_h.copy()).to(dev), torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states_d, data_d, len_d, err_d)
+    mask_d = torch.empty((B, W), dtype=torch.int32, device=dev)
+    tok_d = torch.empty(B, dtype=torch.int32, device=dev)
+    lib.fill_mask(states_d, data_d, len_d, mask_d)
+    rng = np.random.default_rng(cfg.seed + 6)
+    mask_h = o.fill_mask(states_h, data_h, len_h, v)
+    logits = _special_rows_under_a_mask(rng, B, V, mask_h)
+    want_tok = oracle_masked_argmax(logits, mask_h, V)
+    lib.apply_mask_argmax(torch.from_numpy(logits.view(np.int16)).to(dev).view(torch.bfloat16), mask_d, tok_d)
+    assert tok_d.cpu().numpy().tolist() == want_tok.tolist()
+    n_none = 0
+    for s in range(steps):
+        # rows with no choice (all NaN) carry -1: no token, the sequence stays where it is
+        n_none += int((want_tok < 0).sum())
+        err_h = o.advance_batch(states_h, data_h, len_h, want_tok, v)
+        fin = states_h < 0                                    # slot reuse
+        states_h[fin], len_h[fin] = s0[fin], 1
+        mask_h = o.fill_mask(states_h, data_h, len_h, v)
+        logits = _special_rows_under_a_mask(rng, B, V, mask_h)
+        host = np.full((B, V + pad), 0x1234, dtype=np.uint16)
+        host[:, :V] = logits
+        logits_d = torch.from_numpy(host.view(np.int16)).to(dev)
+        want_tok = oracle_masked_argmax(logits, mask_h, V)
+        mask_d.fill_(0x5A5A5A5A)
+        lib.advance_fill_argmax(tok_d, mask_d, logits_d, tok_d, restart_on_eos=True, one_kernel=one_kernel)
+        assert (err_d.cpu().numpy() == err_h).all() and not err_h.any(), f"err differs at step {s}"
+        assert (states_d.cpu().numpy() == states_h).all() and (len_d.cpu().numpy() == len_h).all(), f"states differ at step {s}"
+        live = np.arange(cap)[None, :] < len_h[:, None]
+        assert (data_d.cpu().numpy()[live] == data_h[live]).all(), f"stacks differ at step {s}"
+        assert (mask_d.cpu().numpy().view(np.uint32) == mask_h).all(), f"mask differs at step {s}"
+        assert tok_d.cpu().numpy().tolist() == want_tok.tolist(), f"greedy tokens differ at step {s}"
+        assert (logits_d.cpu().numpy().view(np.uint16) == host).all(), f"logits were written at step {s}"
+    assert lib.fault_count() == 0
+    if B >= 8:
+        assert n_none >= steps                                # the all-NaN row had no choice at every step
+
+
 @pytest.mark.parametrize("cfg_idx,steps,k", [(2, 60, 8), (3, 8, 50), (4, 6, 8)])
 def test_topk_sampling_decode_in_lockstep_with_the_oracle(cfg_idx, steps, k):
     """A top-k sampler on real grammar masks (free-form JSON and a schema whose keys are forced; many
