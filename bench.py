@@ -739,16 +739,6 @@ def main(argv=None):
             s_g[fin], l_g[fin] = s0[fin], 1
             assert (err_d.cpu().numpy() == e).all()
         assert (states_d.cpu().numpy() == s_g).all() and (len_d.cpu().numpy() == l_g).all()
-        if args.eager:                            # counter collection: the checked eager steps are enough
-            return {"checked_steps_against_oracle": n_check}
-
-        def greedy_step(s):
-            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
-            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
-
-        argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
-        step_us_g = graph_us(greedy_step)
-        nbytes = 2.0 * pairs + 4.0 * B * W
 
         # the same loop with one call per step: pre3_advance_fill_argmax takes the token buffer in and out
         def first_token():
@@ -766,6 +756,17 @@ def main(argv=None):
             s_g[fin], l_g[fin] = s0[fin], 1
             want = oracle_masked_argmax(host_logits[(s + 1) % n_pool], o.fill_mask(s_g, d_g, l_g, v), V)
             assert (err_d.cpu().numpy() == e).all() and (tok_d.cpu().numpy() == want).all(), "one-call greedy step differs from the oracle's"
+        if args.eager:                            # counter collection: the checked eager steps are enough
+            return {"checked_steps_against_oracle": n_check}
+
+        def greedy_step(s):
+            lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d)
+            lib.advance_fill_mask(tok_d, mask_d, restart_on_eos=True)
+
+        argmax_us = graph_us(lambda s: lib.apply_mask_argmax(logits[s % n_pool], mask_d, tok_d))
+        step_us_g = graph_us(greedy_step)
+        nbytes = 2.0 * pairs + 4.0 * B * W
+
         first_token()
         torch.cuda.synchronize()
         g1 = torch.cuda.CUDAGraph()
