@@ -123,7 +123,7 @@ def test_whole_step_as_one_call_all_configs():
     assert replay_advance_fill(4, steps=8, step_call_every=4, full_mask_steps=[], one_kernel=False)["step_calls"] == 2
 
 
-@pytest.mark.parametrize("fused", [False, True, "step"])
+@pytest.mark.parametrize("fused", [False, True, "step", "step, 12 entries"])
 def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
     """Sequences of config 2 fed, per step and sequence, one of: an allowed token, an arbitrary
     token (mostly not allowed), EOS (allowed or not), or no token; finished sequences keep
@@ -137,6 +137,8 @@ def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
     cfg = configs.get(2)
     v = cfg.vocab
     B, V, W, cap = cfg.batch, v.n_tokens, v.words, 20            # a small capacity: overflows do happen
+    if fused == "step, 12 entries":                              # below 16 entries the step kernel stages the stack
+        fused, cap = "step", 12                                  # window with vector loads
     o = Oracle(cfg.grammars)
     s0 = o.initial_state(0)
     data = np.zeros((B, cap), dtype=np.int32)
@@ -196,4 +198,4 @@ def test_mixed_token_stream_valid_invalid_skipped_and_eos(fused):
             st[torch.from_numpy(again).to(dev)] = s0
             ln[torch.from_numpy(again).to(dev)] = 1
             lib.fill_mask(st, da, ln, mask)
-    assert seen[0] > 1000 and seen[1] > 300 and seen[2] > 0, seen
+    assert seen[0] > (1000 if cap >= 20 else 300) and seen[1] > 300 and seen[2] > 0, seen
