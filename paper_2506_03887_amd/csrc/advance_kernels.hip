@@ -630,15 +630,17 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
 
 // The whole decode step in one launch: advance, next mask row, and that row applied to the
 // sequence's logits.  One 1,024-thread block per sequence.  Wave 0 advances and descends the
-// condition tree exactly as in advance_fill_kernel.  The other fifteen waves meanwhile fetch the
+// condition tree as in advance_fill_kernel, but through scalar loads only (vector loads return in order
+// per compute unit: behind the row loads of this block each of them would wait microseconds).  The
+// other fifteen waves meanwhile fetch the
 // sequence's whole row of logits -- the fetch does not depend on the mask -- into registers (kHeld
 // groups of 8 bf16 per lane, lane j of the 960 holding groups j, j + 960, ...), so the read half of
 // the masking pass runs under the advance instead of after it; once the plan is there they put the
 // mask row together in LDS (materialised row, id lists; wave 0 walks what the tree left open),
 // store it, and patch and store the logits they hold.  The two halves are separate branches of the
 // kernel with the same number of block barriers, so the registers that hold the logits are not live
-// in wave 0's code.  Masked logits are exactly those of apply_mask_vec8_kernel: fully allowed
-// groups are not written, every other group is written with -inf where a bit is clear.
+// in wave 0's code.  Masked logits are exactly those of apply_mask_vec8_kernel (-inf where a bit is
+// clear, 128-byte lines written whole or not at all).
 // kArgmax: the greedy decode step.  The logits are not written back; instead every lane takes the arg max
 // of the allowed logits among the groups it holds (the order keys of masked_argmax_kernel, the same rules:
 // largest value, first of equal values, +0 = -0, NaN never), the block combines the lanes, and out_tokens[b]
@@ -670,6 +672,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
     // served together and different entries lie in different banks (a 256-entry table of whole bytes cost 4-way
     // bank conflicts on every read: 5.1 us for the arg max of a block instead of the 3.3 us it takes now)
     __shared__ uint2 s_expand[kArgmax ? 16 : 1];
+    __shared__ unsigned long long s_part[kArgmax ? kStepBlock / 64 + 1 : 1];
 
     if (tid < 64) {
         advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
@@ -701,6 +704,7 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
             bits[T.eos_id >> 5] = 1u << (T.eos_id & 31);
         }
         lds_barrier();                                 // the row is complete
+        if (kArgmax) mine = argmax_block_max(0ull, s_part, tid);
     } else {
         const int j = tid - 64;
         if (kCompact && stage_cycles) {
@@ -763,10 +767,12 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         }
         const uint8_t *mask_bytes = reinterpret_cast<const uint8_t *>(bits4);     // byte g = bits of group g
         if (kArgmax) {
-            // Per group: the mask byte's four AND masks come from the LDS table, masked halves get the lowest
-            // key, three packed maxima fold the group, and only the best key and the slot of its group are
-            // kept (a lane's groups ascend, so `>` keeps the first of equal values); the group itself is
-            // picked out of the registers once, at the end.
+            // Per group: the AND masks of the two halves of the mask byte come from the LDS table, masked halves
+            // get the lowest key, three packed maxima fold the group, and only the best key and the slot of its
+            // group are kept (a lane's groups ascend, so `>` keeps the first of equal values).  The block is
+            // combined on (key, group): groups are disjoint runs of ascending ids, so the first of equal values
+            // lies in the smallest group.  Only the one lane that holds the winning group then picks that
+            // group out of its registers and finds the token inside it.
             int best = kOrderNegInf - 1, best_i = -1;   // only a valid value (or a positive NaN pattern) beats the start
             auto group_best = [&](uint4 v, uint32_t mu) {        // v: the group's order keys
                 const uint2 lo = s_expand[mu & 15u], hi = s_expand[mu >> 4];
@@ -778,19 +784,17 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
 #pragma unroll
             for (int i = 0; i < kHeld; ++i) {
                 // no branches: a group outside the row or without an allowed token gets the lowest key in every
-                // half, which is below the start value, and the LDS reads of the groups can overlap
+                // half, which is below the start value, and the LDS reads of the groups can overlap (the row's
+                // LDS area is at least kHeld * kStepData bytes, so the byte is read at a fixed offset)
                 const int g = i * kStepData + j;
-                const uint32_t mu = mask_bytes[g < whole ? g : 0];
+                const uint32_t mu = mask_bytes[g];
                 const int gb = group_best(held[i], g < whole ? mu : 0u);
                 best_i = gb > best ? i : best_i;
                 best = max(gb, best);
             }
-            uint4 best_x = make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < kHeld; ++i)
-                if (best_i == i) best_x = held[i];
             int best_g = best_i >= 0 ? best_i * kStepData + j : -1;
-            uint32_t best_m = best_i >= 0 ? mask_bytes[best_g] : 0u;
+            uint4 tail_keys = make_uint4(0, 0, 0, 0);
+            uint32_t tail_m = 0u;
             const int tail = T.n_tokens & 7;
             if (tail > 0 && j == 0) {                   // the last, partial group: its logits one at a time
                 uint32_t x[4] = {0u, 0u, 0u, 0u};
@@ -801,18 +805,29 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
                 if (mu != 0u) {
                     const uint4 v = make_uint4(bf16_order_keys(x[0]), bf16_order_keys(x[1]), bf16_order_keys(x[2]), bf16_order_keys(x[3]));
                     const int gb = group_best(v, mu);
-                    if (gb > best) { best = gb; best_g = whole; best_x = v; best_m = mu; }
+                    if (gb > best) { best = gb; best_g = whole; tail_keys = v; tail_m = mu; }
                 }
             }
-            if (best_g >= 0) {
-                const uint32_t x[4] = {best_x.x, best_x.y, best_x.z, best_x.w};
+            const unsigned long long word = best_g >= 0 ? argmax_word(best, best_g) : 0ull;
+            mine = argmax_block_max(word, s_part, tid);
+            const int top = (int)(uint32_t)(mine >> 32) - 32768;
+            if (word != 0ull && word == mine && !(top > kOrderPosInf || top == 0)) {
+                uint4 keys = tail_keys;                 // the winning lane: its group's keys and mask byte
+                uint32_t m = tail_m;
+                if (best_g != whole || tail_m == 0u) {
+#pragma unroll
+                    for (int i = 0; i < kHeld; ++i)
+                        if (best_i == i) keys = held[i];
+                    m = mask_bytes[best_g];
+                }
+                const uint32_t x[4] = {keys.x, keys.y, keys.z, keys.w};
                 int first = 0;
 #pragma unroll
                 for (int k = 7; k >= 0; --k) {          // descending: the smallest k is assigned last
                     const int key = (k & 1) ? ((int)x[k >> 1] >> 16) : (int)(int16_t)(x[k >> 1] & 0xFFFFu);
-                    if (((best_m >> k) & 1u) && key == best) first = k;
+                    if (((m >> k) & 1u) && key == best) first = k;
                 }
-                mine = argmax_word(best, best_g * 8 + first);
+                out_tokens[b] = best_g * 8 + first;
             }
         } else {
 #pragma unroll
@@ -846,13 +861,16 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         }
     }
     if (kArgmax) {
-        __shared__ unsigned long long s_part[kStepBlock / 64 + 1];
-        mine = argmax_block_max(mine, s_part, tid);
-        const int order = (int)(uint32_t)(mine >> 32) - 32768;
-        if (mine != 0ull && (order > kOrderPosInf || order == 0))      // a positive NaN pattern or a zero on top: compare as numbers
+        // `mine` is the block's best (key, group) word in every thread.  The lane that holds it has written the
+        // token unless the keys cannot decide: a positive NaN pattern or a zero on top are compared as numbers.
+        const int top = (int)(uint32_t)(mine >> 32) - 32768;
+        if (mine == 0ull) {
+            if (tid == 0) out_tokens[b] = -1;
+        } else if (top > kOrderPosInf || top == 0) {
             mine = argmax_block_max(argmax_segment_by_compare_inline(lrow, reinterpret_cast<const uint8_t *>(bits4), 0,
                                                                      (T.n_tokens + 7) >> 3, T.n_tokens, tid), s_part, tid);
-        if (tid == 0) out_tokens[b] = mine != 0ull ? (int32_t)(0xFFFFFFFFu - (uint32_t)mine) : -1;
+            if (tid == 0) out_tokens[b] = mine != 0ull ? (int32_t)(0xFFFFFFFFu - (uint32_t)mine) : -1;
+        }
     }
 }
 
@@ -1128,6 +1146,7 @@ hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E,
     if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
         return hipErrorInvalidValue;
     const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;
+    const int held_variant = held <= 9 ? 9 : held <= 17 ? 17 : kStepHeldMax;
     size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
     int stage = 0;
     if (cycle_head) {
@@ -1136,6 +1155,8 @@ hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E,
         stage = cycles_fit_lds(T.n_states, T.cycle_pool_n) && lds + tables <= kAfDynamicLdsMax;
         if (stage) lds += tables;
     }
+    // the greedy fold reads a mask byte for every group slot of a lane, also those past the row's end
+    if (out_tokens && lds < (size_t)held_variant * kStepData + 16) lds = (size_t)held_variant * kStepData + 16;
 #define PRE3_STEP_ARGS held, dim3(batch), lds, stream, T, E, tokens, states, data, len, cap, batch, err, bitmask, restart_on_eos, \
                        adv_scratch, walk_spill, cycle_head, cycle_pool, stage, logits, row_stride, out_tokens
     if (cycle_head) {
