@@ -607,6 +607,71 @@ def test_hip_graph_of_the_greedy_loop_replays_like_eager():
             assert torch.equal(got, want), f"replay {s} differs from the eager step"
 
 
+@pytest.mark.parametrize("greedy", [False, True])
+def test_hip_graph_of_the_one_kernel_step_replays_like_eager(greedy):
+    """The one-kernel step (pre3_advance_fill_apply_mask; greedy: pre3_advance_fill_argmax with the token buffer
+    updated in place) captured once and replayed: each replay, with fresh logits and -- for the masking form -- fresh
+    tokens uploaded eagerly in between, must leave what the eager call leaves."""
+    torch, dev = _torch()
+    from workloads import configs
+    cfg = configs.get(2)
+    v = cfg.vocab
+    lib = _lib(cfg.grammars, v, stack_cap=256)
+    B, V, W, cap, steps = 32, v.n_tokens, v.words, 256, 8
+    s0 = lib.initial_state(0)
+    data = torch.zeros((B, cap), dtype=torch.int32, device=dev)
+    length = torch.ones(B, dtype=torch.int32, device=dev)
+    states = torch.full((B,), s0, dtype=torch.int32, device=dev)
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(states, data, length, err)
+    mask = torch.zeros((B, W), dtype=torch.int32, device=dev)
+    tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    rng = np.random.default_rng(9)
+    all_logits = [torch.from_numpy(bf16_logits(rng, B, V).view(np.int16)).to(dev) for _ in range(steps + 1)]
+    logits = all_logits[0].clone()
+
+    def start():
+        data.zero_(); data[:, 0] = s0; length.fill_(1); states.fill_(s0)
+        lib.fill_mask(states, data, length, mask)
+        lib.apply_mask_argmax(all_logits[steps].view(torch.bfloat16), mask, tok)     # a first token that is allowed
+
+    def one_step():
+        if greedy:
+            lib.advance_fill_argmax(tok, mask, logits, tok, restart_on_eos=True, one_kernel=True)
+        else:
+            lib.advance_fill_apply_mask(tok, mask, logits, restart_on_eos=True, one_kernel=True)
+
+    def next_token():                                         # the masking form: the caller samples; here the arg max
+        if not greedy:
+            lib.apply_mask_argmax(logits.view(torch.bfloat16), mask, tok)
+
+    assert lib.step_is_one_kernel(logits, one_kernel=True)
+    start(); one_step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    start()
+    with torch.cuda.graph(g):
+        one_step()
+    ref = []
+    start()
+    for s in range(steps):
+        logits.copy_(all_logits[s])
+        one_step()
+        torch.cuda.synchronize()
+        ref.append(tuple(x.clone() for x in (tok, mask, states, length, data, err, logits)))
+        next_token()
+    assert len({int(r[2][0]) for r in ref}) > 2              # the sequences did move
+    start()
+    for s in range(steps):
+        logits.copy_(all_logits[s])                           # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((tok, mask, states, length, data, err, logits), ref[s]):
+            assert torch.equal(got, want), f"replay {s} differs from the eager step"
+        next_token()
+
+
 def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
     """A mask row of more than 56 KiB does not fit the token-edge kernels' LDS bitmap: every call
     must then give the same results through the byte-by-byte kernel."""
