@@ -719,9 +719,6 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
         for (int i = 0; i < kHeld; ++i) {
             const int g = i * kStepData + j;
             held[i] = make_uint4(0u, 0u, 0u, 0u);
-#ifdef PRE3_STEP_IN_FLIGHT
-            if (i >= PRE3_STEP_IN_FLIGHT) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PRE3_STEP_IN_FLIGHT - 1));
-#endif
             // (a wave-uniform base per i plus one 32-bit lane offset: no 64-bit address register per group)
             if (g < whole) held[i] = stream_load(lrow + (size_t)i * (kStepData * 8) + (uint32_t)(j * 8));
         }
