@@ -672,6 +672,32 @@ def test_hip_graph_of_the_one_kernel_step_replays_like_eager(greedy):
         next_token()
 
 
+def test_which_form_the_step_call_takes(deep_vocab):
+    """pre3_step_is_one_kernel: the one kernel for batches between a quarter of the compute units and all of them
+    (64..256 on the 256 units of an MI355X), at any batch size when asked for, and never for logits whose rows are
+    not 16-byte aligned or shorter than the vocabulary."""
+    torch, dev = _torch()
+    v = deep_vocab
+    lib = _lib(G.JSON, v)
+    units = torch.cuda.get_device_properties(0).multi_processor_count
+    V = v.n_tokens
+    stride = (V + 7) // 8 * 8
+    z32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=dev)
+    for B in (4, units // 4 - 1, units // 4, units, units + 1):
+        states = torch.full((B,), lib.initial_state(0), dtype=torch.int32, device=dev)
+        data = torch.zeros((B, 32), dtype=torch.int32, device=dev)
+        data[:, 0] = states
+        lib.bind_state(states, data, torch.ones(B, dtype=torch.int32, device=dev), z32(B))
+        flat = torch.zeros(B * stride + 16, dtype=torch.int16, device=dev)
+        aligned = flat[: B * stride].view(B, stride)
+        assert lib.step_is_one_kernel(aligned) == (units // 4 <= B <= units), B
+        assert lib.step_is_one_kernel(aligned, one_kernel=True), B
+        assert not lib.step_is_one_kernel(flat[4: 4 + B * stride].view(B, stride), one_kernel=True)          # rows at 8 bytes
+        if B > 1:
+            assert not lib.step_is_one_kernel(torch.zeros((B, stride + 4), dtype=torch.int16, device=dev), one_kernel=True)
+    torch.cuda.synchronize()
+
+
 def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
     """A mask row of more than 56 KiB does not fit the token-edge kernels' LDS bitmap: every call
     must then give the same results through the byte-by-byte kernel."""
