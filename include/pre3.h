@@ -167,7 +167,8 @@ int pre3_fill_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, ui
 
 /* Applies a token mask to bf16 logits in place (Sec. 1: the mask removes the sampling
  * probability of excluded tokens): logits[b*row_stride + t] becomes -inf (bit pattern
- * 0xFF80) where the token's bit is 0 and is left untouched, bit for bit, where it is 1.
+ * 0xFF80) where the token's bit is 0 and keeps its value, bit for bit, where it is 1 (the kernel
+ * writes 128-byte lines whole: an allowed logit next to a masked one is stored back unchanged).
  * logits_bf16: device, [batch, >= vocab] with row_stride elements between rows;
  * bitmask: device [batch, ceil(vocab/32)].  Needs no handle.  Errors: BADARG. */
 int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batch, int32_t vocab,
