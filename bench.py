@@ -1,16 +1,18 @@
 """Benchmark of the batched token-mask path on one MI355X.
 
-One step = logits masking + stack advance + token mask of the next step over one batch (B=256
+One step = stack advance + token mask of the new stacks + logits masking over one batch (B=256
 sequences, V=128,256 tokens, byte-level JSON grammar: workload "json-B256-V128256"), replaying
-a seeded trajectory; all inputs are resident in HBM before the timed region.  The K timed steps
-are captured into one HIP graph (kernel launches only) and replayed between two HIP events, so
-the GPU runs the kernels back to back as a serving loop would: that replay gives `value`.
+a seeded trajectory; all inputs are resident in HBM before the timed region.  By default the step
+is one call, pre3_advance_fill_apply_mask (one kernel launch where the batch size allows, else
+pre3_apply_mask + pre3_advance_fill_mask).  The K timed steps are captured into one HIP graph
+(kernel launches only) and replayed between two HIP events, so the GPU runs the kernels back to
+back as a serving loop would: that replay gives `value`.
 Per-call durations (`kernels_us`) come from a second, eager pass over the same K steps with a
 HIP event before and after every launch; the pass is queued behind a device-side delay so the
 events are processed back to back on the GPU.  The launch duration behind `roofline` is taken
-without a bracket around every launch (K launches of the kernel in one graph between two
-events); the rocprofv3 summaries under profiles/ hold the profiler's durations of the same
-kernels.  After the timed runs the device state and the last mask are checked against the CPU
+inside the timed steps: they are captured once more with one-thread kernels that write the
+device clock before and after every launch; the rocprofv3 summaries under profiles/ hold the
+profiler's durations of the same kernels.  After the timed runs the device state and the last mask are checked against the CPU
 oracle's replay.  Prints ONE JSON line.
 
 The headline fields (`value`, `ms_per_step`, `config`, `dtype`, `roofline`, `cpu_baseline`) are
