@@ -400,6 +400,17 @@ def main(argv=None):
                 apply_mask(logits[s % n_pool], mask_d, V)
         return replay_best(g) * 1e3 / K
 
+    def fill_apply_graph_us():
+        """pre3_fill_apply_mask (mask + masking as one call; one launch where the batch size allows) on the recorded
+        stacks of the K timed steps, one graph between two events."""
+        snaps = recorded_stacks()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in range(K):
+                ls, da = snaps[s]
+                lib.fill_apply_mask(ls[1], da, ls[0], mask_d, logits[s % n_pool])
+        return replay_best(g) * 1e3 / K
+
     # =========================== headline: the step, then the dominant kernel ===========================
     step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill", "one-call": "one-call"}[args.step]
     if step_kind == "one-call" and not lib.step_is_one_kernel(logits[0]):
@@ -534,6 +545,10 @@ def main(argv=None):
                                   "between two HIP events, divided by K; with a pair of events around every launch the two "
                                   f"calls read {brackets:.1f} us")
         r["mask_apply_tokens_per_s"] = pairs / (mask_apply_us * 1e-6)
+        if not args.eager:
+            fa_us = fill_apply_graph_us()
+            r["fill_apply_one_call_us_per_step"] = fa_us
+            r["fill_apply_one_call_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (fa_us * 1e-6) / 1e9 / HBM_PEAK_GBS
         r["mask_apply_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (mask_apply_us * 1e-6) / 1e9 / HBM_PEAK_GBS
         r["step_frac_of_hbm_peak"] = BYTES_PER_PAIR * pairs / (t_step / K * 1e-3) / 1e9 / HBM_PEAK_GBS
         r["graph_ms_per_step"] = {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K}

@@ -179,7 +179,10 @@ int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batc
  * back from memory (Sec. 1: mask computation and masking belong to the same decode step).
  * Results are exactly those of the two calls in sequence: bitmask as pre3_fill_mask writes it,
  * logits (device, [batch, >= n_tokens], row_stride elements between rows) as pre3_apply_mask
- * leaves them.  Errors: BADARG. */
+ * leaves them.  A batch between a quarter of the GPU's compute units and all of them, no larger
+ * than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
+ * runs through that kernel without the advance: each sequence's logits are fetched while its
+ * mask row is looked up.  Errors: BADARG. */
 int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
                          uint16_t *logits_bf16, int64_t row_stride, pre3_stream stream);
 

@@ -628,6 +628,30 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
     build_and_store_row<kAfBlock, true, true>(T, E, plan, bits4, 0, n_vec, row, wp, bitmask + (size_t)b * T.n_words, vector_ok, tid);
 }
 
+// The part of advance_and_plan that is left when there is no token: the top of the stack as it stands is
+// staged in s_new and the condition tree descended with it, through scalar loads (the step kernel's
+// wave 0 when the kernel is asked for mask + masking only).
+__device__ __forceinline__ void plan_only_scalar(const DevTables &T, const DevTokenEdges &E, const int32_t *states,
+                                                 const int32_t *row, const int32_t *len, int cap, int32_t *s_new,
+                                                 RowPlan &plan, int b, int lane) {
+    const int n = table<true>(len, b);
+    const int st = table<true>(states, b);
+    const bool shape_ok = n >= 1 && n <= cap;
+    if (cap >= 16) stage_window_scalar(row, n, cap, shape_ok, lane, s_new);
+    else s_new[lane] = (shape_ok && n - 1 - lane >= 0) ? row[n - 1 - lane] : -1;
+    __builtin_amdgcn_wave_barrier();
+    const int top = s_new[0];
+    if (st < 0) {
+        if (lane == 0) plan.mode = kRowDone;
+    } else if (!shape_ok || (unsigned)top >= (unsigned)T.n_states) {
+        if (lane == 0) plan.mode = kRowEmpty;
+    } else {
+        plan_row_scalar(E, scalar_node(E.root_nodes + __builtin_amdgcn_readfirstlane(top)), s_new, n,
+                        [&](int k) { return global_read(row + (n - 1 - k)); }, &plan, lane);
+    }
+    if (lane == 0) { plan.top = top; plan.len = n; }
+}
+
 // The whole decode step in one launch: advance, next mask row, and that row applied to the
 // sequence's logits.  One 1,024-thread block per sequence.  Wave 0 advances and descends the
 // condition tree as in advance_fill_kernel, but through scalar loads only (vector loads return in order
@@ -646,6 +670,8 @@ __global__ __launch_bounds__(kAfBlock) void advance_fill_kernel(
 // largest value, first of equal values, +0 = -0, NaN never), the block combines the lanes, and out_tokens[b]
 // is the sequence's next token (-1 if nothing is allowed).  out_tokens may be the tokens buffer: block b
 // reads tokens[b] before anything else and writes out_tokens[b] last.
+// tokens == nullptr: no advance -- the mask of the stacks as they are, and the masking (states, data and
+// len are then only read).
 constexpr int kStepBlock = 1024, kStepData = kStepBlock - 64;
 static_assert(kStepBlock == kArgBlock, "the step kernel combines its lanes with argmax_block_max");
 template <bool kCompact, int kHeld, bool kArgmax>
@@ -675,9 +701,12 @@ __global__ __launch_bounds__(kStepBlock) void advance_fill_apply_kernel(
     __shared__ unsigned long long s_part[kArgmax ? kStepBlock / 64 + 1 : 1];
 
     if (tid < 64) {
-        advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
-                                         cycle_head, cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec), s_win,
-                                         s_new, s_info, s_adv_stack, plan, b, lane);
+        if (tokens)
+            advance_and_plan<kCompact, true>(T, E, tokens, states, row, len, cap, batch, err, restart_on_eos, adv_scratch,
+                                             cycle_head, cycle_pool, stage_cycles, reinterpret_cast<int32_t *>(bits4 + n_vec),
+                                             s_win, s_new, s_info, s_adv_stack, plan, b, lane);
+        else
+            plan_only_scalar(T, E, states, row, len, cap, s_new, plan, b, lane);
         // (barriers that order LDS only: this wave's stores of the new stack are still on their way, and
         // nothing in this block reads them before the launch ends -- except the walks below, which wait)
         lds_barrier();                                 // the plan is there
@@ -1164,6 +1193,22 @@ hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E,
         else launch_step_variant<false, false>(PRE3_STEP_ARGS);
     }
 #undef PRE3_STEP_ARGS
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_apply_rows(const DevTables &T, const DevTokenEdges &E, const int32_t *states, const int32_t *data,
+                                  const int32_t *len, int cap, int batch, uint32_t *bitmask, int32_t *walk_spill,
+                                  uint16_t *logits, int64_t row_stride, hipStream_t stream) {
+    if (batch == 0) return hipSuccess;
+    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, false)) return hipErrorInvalidValue;
+    if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
+        return hipErrorInvalidValue;
+    const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;
+    const size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
+    // no tokens: the kernel only reads the states and the stacks
+    launch_step_variant<false, false>(held, dim3(batch), lds, stream, T, E, nullptr, const_cast<int32_t *>(states),
+                                      const_cast<int32_t *>(data), const_cast<int32_t *>(len), cap, batch, nullptr, bitmask, 0,
+                                      nullptr, walk_spill, nullptr, nullptr, 0, logits, row_stride, nullptr);
     return hipGetLastError();
 }
 

@@ -490,6 +490,14 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
     if (reinterpret_cast<uintptr_t>(logits) % 2 != 0) return fail(h, PRE3_E_BADARG, "fill_apply_mask: misaligned logits");
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool fused = h->use_edges && reinterpret_cast<uintptr_t>(logits) % 16 == 0 && row_stride % 8 == 0;
+    // A batch that suits the one-launch step kernel (a row of logits per compute unit, fetched while the mask is
+    // looked up) runs through it, without the advance; its walks spill into the workspace of the bound batch.
+    if (fused && h->af_walk_spill && stacks.batch <= h->b_stacks.batch && stacks.batch * 4 >= h->n_compute_units &&
+        stacks.batch <= h->n_compute_units && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, stacks.cap, false)) {
+        hipError_t e = launch_fill_apply_rows(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap, stacks.batch,
+                                              bitmask, h->af_walk_spill, logits, row_stride, s);
+        return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_apply_mask");
+    }
     if (fused) {
         hipError_t e = launch_fill_mask_edges(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap,
                                               stacks.batch, bitmask, logits, row_stride, h->edge_spill, h->edge_blocks, s);

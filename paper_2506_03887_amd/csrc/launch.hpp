@@ -66,6 +66,11 @@ bool advance_fill_fits_compact(int n_words, int cap);   // row bitmap + staged s
 // out_tokens null: the logits are masked in place; else they are only read and out_tokens[b] becomes
 // the arg max of the allowed logits of row b (the greedy step).
 bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles);
+// The same kernel without the advance: mask rows of the stacks as they are, applied to the logits
+// (walk_spill: advance_fill_walk_spill_entries(batch, ...) entries; same conditions on the logits).
+hipError_t launch_fill_apply_rows(const DevTables &T, const DevTokenEdges &E, const int32_t *states, const int32_t *data,
+                                  const int32_t *len, int cap, int batch, uint32_t *bitmask, int32_t *walk_spill,
+                                  uint16_t *logits, int64_t row_stride, hipStream_t stream);
 hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                      int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
                                      int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
