@@ -57,6 +57,7 @@ int main(int argc, char **argv) {
     const void *data1 = take(&p, nD), *mask1 = take(&p, nM);
     const void *jump_bytes = take(&p, (size_t)B * max_jump), *jump_len = take(&p, nB);
     const void *states2 = take(&p, nB), *len2 = take(&p, nB);
+    const void *masked1 = take(&p, nL), *argmax1 = take(&p, nB);      /* the step's logits under the NEXT mask */
     if (p - buf != size) { fprintf(stderr, "fixture size mismatch\n"); return 1; }
 
     pre3_handle *h = NULL;
@@ -116,6 +117,29 @@ int main(int argc, char **argv) {
                    (size_t)((const int32_t *)jump_len)[b]);
     CHECK_HIP(hipMemcpy(got, d_states, nB, hipMemcpyDeviceToHost)); ok &= same("states after jump", got, states2, nB);
     CHECK_HIP(hipMemcpy(got, d_len, nB, hipMemcpyDeviceToHost)); ok &= same("len after jump", got, len2, nB);
+
+    /* the whole step as one call, from the first state again: advance, next mask, and that mask on the logits
+     * (asked for as one kernel: 48 sequences are fewer than the library would choose it for), then the greedy form */
+    for (int greedy = 0; greedy < 2; greedy++) {
+        CHECK_HIP(hipMemcpy(d_states, states0, nB, hipMemcpyHostToDevice));
+        CHECK_HIP(hipMemcpy(d_data, data0, nD, hipMemcpyHostToDevice));
+        CHECK_HIP(hipMemcpy(d_len, len0, nB, hipMemcpyHostToDevice));
+        CHECK_HIP(hipMemcpy(d_logits, logits, nL, hipMemcpyHostToDevice));
+        CHECK_HIP(hipMemset(d_mask, 0x5A, nM));
+        if (pre3_step_is_one_kernel(h, d_logits, V, PRE3_STEP_ONE_KERNEL) != 1) { fprintf(stderr, "one-kernel form refused\n"); ok = 0; }
+        if (greedy)
+            CHECK_PRE3(pre3_advance_fill_argmax(h, d_tokens, d_mask, d_logits, V, d_arg, PRE3_STEP_ONE_KERNEL, stream));
+        else
+            CHECK_PRE3(pre3_advance_fill_apply_mask(h, d_tokens, d_mask, d_logits, V, PRE3_STEP_ONE_KERNEL, stream));
+        CHECK_HIP(hipStreamSynchronize(stream));
+        CHECK_HIP(hipMemcpy(got, d_err, nB, hipMemcpyDeviceToHost)); ok &= same("err (one call)", got, err1, nB);
+        CHECK_HIP(hipMemcpy(got, d_states, nB, hipMemcpyDeviceToHost)); ok &= same("states (one call)", got, states1, nB);
+        CHECK_HIP(hipMemcpy(got, d_len, nB, hipMemcpyDeviceToHost)); ok &= same("len (one call)", got, len1, nB);
+        CHECK_HIP(hipMemcpy(got, d_mask, nM, hipMemcpyDeviceToHost)); ok &= same("next mask (one call)", got, mask1, nM);
+        CHECK_HIP(hipMemcpy(got, d_logits, nL, hipMemcpyDeviceToHost));
+        ok &= same(greedy ? "logits left alone (greedy call)" : "masked logits (one call)", got, greedy ? logits : masked1, nL);
+        if (greedy) { CHECK_HIP(hipMemcpy(got, d_arg, nB, hipMemcpyDeviceToHost)); ok &= same("argmax (one call)", got, argmax1, nB); }
+    }
 
     /* the separate advance call on an empty batch and argument errors */
     pre3_stacks none = {NULL, NULL, cap, 0};

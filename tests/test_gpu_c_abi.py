@@ -1,6 +1,7 @@
 """The C ABI without Python in the loop: tests/c_abi/check (plain C, gcc-built, HIP runtime for
 device memory only) replays one step of a seeded JSON workload from a fixture holding the inputs
-and the oracle's expected outputs, and must match bit for bit."""
+and the oracle's expected outputs -- call by call, then as the one-call step and the one-call greedy
+step -- and must match bit for bit."""
 import os
 import subprocess
 
@@ -46,12 +47,15 @@ def test_plain_c_program_matches_the_oracle(tmp_path):
     mask1 = o.fill_mask(s1, d1, l1, v)
     s2, d2, l2 = s1.copy(), d1.copy(), l1.copy()
     jb, jn = o.jump_forward_batch(s2, d2, l2, max_jump)
+    masked1 = logits.copy()
+    oracle_apply_mask(masked1, mask1, V)
+    argmax1 = oracle_masked_argmax(logits, mask1, V)
     gram = text.encode("latin-1")
     header = np.array([len(gram), len(v.bytes), V, v.eos_id, B, cap, max_jump, 0], dtype=np.int32)
     parts = [header, np.frombuffer(gram, dtype=np.uint8), np.asarray(v.bytes, dtype=np.uint8),
              np.asarray(v.offsets, dtype=np.int64), states, data, length, mask, logits, masked, argmax,
              tokens.astype(np.int32), err.astype(np.int32), s1, l1, d1, mask1,
-             np.ascontiguousarray(jb, dtype=np.uint8), jn.astype(np.int32), s2, l2]
+             np.ascontiguousarray(jb, dtype=np.uint8), jn.astype(np.int32), s2, l2, masked1, argmax1]
     path = tmp_path / "fixture.bin"
     with open(path, "wb") as f:
         for a in parts:
