@@ -236,8 +236,8 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
  * then leaves them.
  * The step can run as ONE kernel in which every sequence's logits are fetched while its token is
  * still being walked.  That form needs: logits aligned to 16 bytes, row_stride a multiple of 8, at
- * most 153,600 tokens, token-level edges in use, and the mask row and -- with cycle-aware stacks --
- * the stack within the kernel's LDS.  It holds one sequence's logits in the registers of one compute
+ * most 207,360 tokens (a row has to fit the registers of one compute unit), token-level edges in
+ * use, and the mask row and -- with cycle-aware stacks -- the stack within the kernel's LDS.  It holds one sequence's logits in the registers of one compute
  * unit, so it pays when the batch is between a quarter of the GPU's compute units and all of them
  * (64..256 sequences on 256 units: 23.9 against 30.5 us per step at 256 x 128,256); the call chooses
  * it for such batches and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks for the one kernel
@@ -256,14 +256,16 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
  * out_tokens may be the tokens buffer itself (a greedy loop then needs no copy between steps).
  * The call takes its one-kernel form -- the logits are fetched while the token is walked and the
  * arg max is taken from the registers that hold them -- under the conditions and for the batch
- * sizes of pre3_advance_fill_apply_mask, and is the two calls otherwise; flags as there.
+ * sizes of pre3_advance_fill_apply_mask, except that the vocabulary may have at most 153,600 tokens
+ * (the fold needs registers of its own), and is the two calls otherwise; flags as there.
  * Errors: BADARG (nothing bound, null pointer, unknown flag, row_stride < n_tokens, logits not
  * 2-byte aligned), HIP. */
 int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, const uint16_t *logits_bf16,
                              int64_t row_stride, int32_t *out_tokens, int32_t flags, pre3_stream stream);
 
-/* Which form the call above takes for the bound batch and these logits: 1 = the one kernel,
- * 0 = the two calls; BADARG if nothing is bound.  Host call, launches nothing. */
+/* Which form pre3_advance_fill_apply_mask takes for the bound batch and these logits: 1 = the one
+ * kernel, 0 = the two calls; BADARG if nothing is bound.  pre3_advance_fill_argmax takes the same
+ * form for vocabularies of at most 153,600 tokens.  Host call, launches nothing. */
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags);
 
 /* Greedy sampling fused behind the mask (Sec. 1: invalid tokens are excluded, then a token is

@@ -1137,11 +1137,13 @@ hipError_t launch_advance_fill(const DevTables &T, const DevTokenEdges &E, const
     return hipGetLastError();
 }
 
+// (27 groups per lane, 207,360 tokens, is what fits the 128 vector registers of a 1,024-thread block beside the
+// masking code; the greedy fold needs more registers and stops at 20 groups, 153,600 tokens)
+constexpr int kStepHeldMax = 27, kStepHeldMaxGreedy = 20;
 // Largest vocabulary the fused step kernel can hold in registers, and the choice of its variant.
-constexpr int kStepHeldMax = 20;
-bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles) {
+bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles, bool greedy) {
     const size_t row_bytes = (size_t)edge_row_stride_words(n_words) * sizeof(uint32_t);
-    if ((n_tokens >> 3) > kStepHeldMax * kStepData) return false;
+    if ((n_tokens >> 3) > (greedy ? kStepHeldMaxGreedy : kStepHeldMax) * kStepData) return false;
     if (cycles) return cap <= kCompactMaxLen && row_bytes + (size_t)cap * sizeof(int32_t) <= kAfDynamicLdsMax;
     return row_bytes <= kAfDynamicLdsMax;
 }
@@ -1158,7 +1160,8 @@ static void launch_step_variant(int held, dim3 grid, size_t lds, hipStream_t str
                        (size_t)batch * 64, cycle_head, cycle_pool, stage, logits, row_stride, out_tokens)
     if (held <= 9) PRE3_STEP(9);
     else if (held <= 17) PRE3_STEP(17);
-    else PRE3_STEP(20);
+    else if (held <= kStepHeldMaxGreedy || kArgmax) PRE3_STEP(20);
+    else if constexpr (!kArgmax) PRE3_STEP(27);
 #undef PRE3_STEP
 }
 
@@ -1168,11 +1171,11 @@ hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E,
                                      const int32_t *cycle_head, const int32_t *cycle_pool, uint16_t *logits,
                                      int64_t row_stride, int32_t *out_tokens, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, cycle_head != nullptr)) return hipErrorInvalidValue;
+    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, cycle_head != nullptr, out_tokens != nullptr)) return hipErrorInvalidValue;
     if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
         return hipErrorInvalidValue;
     const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;
-    const int held_variant = held <= 9 ? 9 : held <= 17 ? 17 : kStepHeldMax;
+    const int held_variant = held <= 9 ? 9 : held <= 17 ? 17 : kStepHeldMaxGreedy;
     size_t lds = (size_t)edge_row_stride_words(T.n_words) * sizeof(uint32_t);
     int stage = 0;
     if (cycle_head) {
@@ -1200,7 +1203,7 @@ hipError_t launch_fill_apply_rows(const DevTables &T, const DevTokenEdges &E, co
                                   const int32_t *len, int cap, int batch, uint32_t *bitmask, int32_t *walk_spill,
                                   uint16_t *logits, int64_t row_stride, hipStream_t stream) {
     if (batch == 0) return hipSuccess;
-    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, false)) return hipErrorInvalidValue;
+    if (!advance_fill_apply_fits(T.n_tokens, T.n_words, cap, false, false)) return hipErrorInvalidValue;
     if ((reinterpret_cast<uintptr_t>(logits) & 15) != 0 || (row_stride & 7) != 0 || row_stride < T.n_tokens)
         return hipErrorInvalidValue;
     const int held = ((T.n_tokens >> 3) + kStepData - 1) / kStepData;

@@ -493,7 +493,7 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
     // A batch that suits the one-launch step kernel (a row of logits per compute unit, fetched while the mask is
     // looked up) runs through it, without the advance; its walks spill into the workspace of the bound batch.
     if (fused && h->af_walk_spill && stacks.batch <= h->b_stacks.batch && stacks.batch * 4 >= h->n_compute_units &&
-        stacks.batch <= h->n_compute_units && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, stacks.cap, false)) {
+        stacks.batch <= h->n_compute_units && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, stacks.cap, false, false)) {
         hipError_t e = launch_fill_apply_rows(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap, stacks.batch,
                                               bitmask, h->af_walk_spill, logits, row_stride, s);
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_apply_mask");
@@ -585,18 +585,18 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 namespace {
 // The one kernel keeps a sequence's logits in the registers of one compute unit: it pays while the batch
 // fills a good part of the chip and no compute unit has to take a second sequence.
-bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
+bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags, bool greedy) {
     const int batch = h->b_stacks.batch;
     const bool cycles = h->compact && h->T.n_cycles > 0;
     const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || (batch * 4 >= h->n_compute_units && batch <= h->n_compute_units);
     return wanted && h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
-           row_stride >= h->V.n_tokens && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles);
+           row_stride >= h->V.n_tokens && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles, greedy);
 }
 }  // namespace
 
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
     if (!usable(h) || (!h->b_states && !h->bound_empty)) return PRE3_E_BADARG;
-    return !h->bound_empty && step_takes_one_kernel(h, logits_bf16, row_stride, flags) ? 1 : 0;
+    return !h->bound_empty && step_takes_one_kernel(h, logits_bf16, row_stride, flags, false) ? 1 : 0;
 }
 
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
@@ -609,7 +609,7 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
     if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: row stride below vocabulary size");
     if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_apply_mask: misaligned logits");
     const bool cycles = h->compact && h->T.n_cycles > 0;
-    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags)) {
+    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags, false)) {
         const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
         hipError_t e = launch_advance_fill_apply(h->dev, h->dev_edges, tokens, h->b_states, h->b_stacks.data, h->b_stacks.len,
                                                  h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
@@ -634,7 +634,7 @@ int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bi
     if (flags & ~(PRE3_ADVANCE_RESTART_ON_EOS | PRE3_STEP_ONE_KERNEL)) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: unknown flag");
     if (row_stride < h->V.n_tokens) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: row stride below vocabulary size");
     if (reinterpret_cast<uintptr_t>(logits_bf16) % 2 != 0) return fail(h, PRE3_E_BADARG, "advance_fill_argmax: misaligned logits");
-    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags)) {
+    if (step_takes_one_kernel(h, logits_bf16, row_stride, flags, true)) {
         const bool cycles = h->compact && h->T.n_cycles > 0;
         const int restart = (flags & PRE3_ADVANCE_RESTART_ON_EOS) ? 1 : 0;
         // the kernel only reads the logits in this form

@@ -65,7 +65,7 @@ bool advance_fill_fits_compact(int n_words, int cap);   // row bitmap + staged s
 // aligned to 16 bytes and a row stride that is a multiple of 8 and at least the vocabulary size.
 // out_tokens null: the logits are masked in place; else they are only read and out_tokens[b] becomes
 // the arg max of the allowed logits of row b (the greedy step).
-bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles);
+bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles, bool greedy);   // greedy: the arg-max form
 // The same kernel without the advance: mask rows of the stacks as they are, applied to the logits
 // (walk_spill: advance_fill_walk_spill_entries(batch, ...) entries; same conditions on the logits).
 hipError_t launch_fill_apply_rows(const DevTables &T, const DevTokenEdges &E, const int32_t *states, const int32_t *data,

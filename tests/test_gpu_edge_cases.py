@@ -4,7 +4,7 @@ rows, tokens deep enough to spill the private stack, snapshots, HIP-graph replay
 import numpy as np
 import pytest
 
-from oracle import Oracle, apply_mask as oracle_apply_mask
+from oracle import Oracle, apply_mask as oracle_apply_mask, masked_argmax as oracle_masked_argmax
 from workloads import grammars as G
 from workloads.vocab import BASE_SEED, Vocab, bf16_logits, bpe_like_vocab
 
@@ -696,6 +696,83 @@ def test_which_form_the_step_call_takes(deep_vocab):
         if B > 1:
             assert not lib.step_is_one_kernel(torch.zeros((B, stride + 4), dtype=torch.int16, device=dev), one_kernel=True)
     torch.cuda.synchronize()
+
+
+def _short_token_vocab(rng, V):
+    """V - 1 tokens of one to four bytes over the arithmetic grammar's alphabet, then the end-of-sequence token."""
+    alphabet = np.frombuffer(b"a+*()b- ", dtype=np.uint8)
+    lens = rng.integers(1, 5, size=V - 1)
+    flat = alphabet[rng.integers(0, len(alphabet), size=int(lens.sum()))].tobytes()
+    offs = np.concatenate([[0], np.cumsum(lens)])
+    return Vocab([flat[offs[i]: offs[i + 1]] for i in range(V - 1)] + [b""], V - 1)
+
+
+def _allowed(row, V):
+    return np.flatnonzero((row[np.arange(V) >> 5] >> (np.arange(V) & 31).astype(np.uint32)) & 1)
+
+
+@pytest.mark.parametrize("V", [200_003, 207_360, 207_368])
+def test_whole_step_as_one_call_on_a_vocabulary_of_two_hundred_thousand(V):
+    """The one-kernel step keeps up to 27 groups of eight logits per lane (207,360 tokens) when it masks and
+    20 (153,600) when it takes the arg max: a vocabulary of about 200,000 tokens takes the one kernel for the
+    masking call and two launches for the greedy call, one of 207,368 takes two launches for both, and every
+    form gives the oracle's stacks, mask rows, masked logits and picks."""
+    torch, dev = _torch()
+    rng = np.random.default_rng(BASE_SEED + 93 + V)
+    v = _short_token_vocab(rng, V)
+    o = Oracle(G.ARITHMETIC)
+    lib = _lib(G.ARITHMETIC, v, stack_cap=64)
+    assert lib.token_edge_stats()["built"] > 0
+    kinds = [b"", b"(a+", b"a*(a", b"((a)", b"a", b"(", b"a+", b"((a*a)+"]
+    reps = 8                                                       # 64 rows: the mask + masking call takes the step kernel too
+    s1, d1, l1 = _stacks(o, kinds, 64)
+    states, data, length = np.tile(s1, reps), np.tile(d1, (reps, 1)), np.tile(l1, reps)
+    B, W = len(states), v.words
+    stride = (V + 7) // 8 * 8 + 8
+    st, da, ln = torch.from_numpy(states).to(dev), torch.from_numpy(data).to(dev), torch.from_numpy(length).to(dev)
+    err = torch.zeros(B, dtype=torch.int32, device=dev)
+    lib.bind_state(st, da, ln, err)
+    lg = torch.zeros((B, stride), dtype=torch.int16, device=dev)
+    assert lib.step_is_one_kernel(lg, one_kernel=True) == (V <= 207_360)
+
+    def masked(logits, rows):
+        expect = logits.copy()
+        oracle_apply_mask(expect, rows, V)
+        return expect
+
+    # mask rows of the stacks as they are, applied in the same call
+    want = np.tile(o.fill_mask(s1, d1, l1, v), (reps, 1))
+    logits = bf16_logits(rng, B, V)
+    lg[:, :V] = torch.from_numpy(logits.view(np.int16)).to(dev)
+    m = torch.full((B, W), 0x55555555, dtype=torch.int32, device=dev)
+    lib.fill_apply_mask(st, da, ln, m, lg.view(torch.bfloat16)[:, :V])
+    assert (m.cpu().numpy().view(np.uint32) == want).all()
+    assert (lg[:, :V].cpu().numpy().view(np.uint16) == masked(logits, want)).all()
+    assert int(lg[:, V:].abs().sum().item()) == 0                  # nothing written past a row's end
+
+    # three whole steps in one call each, then a greedy one
+    for step in range(4):
+        picks1 = np.array([_allowed(want[b], V)[(5 + 3 * step + b) % 11] for b in range(len(kinds))], dtype=np.int32)
+        picks = np.tile(picks1, reps)
+        e1 = o.advance_batch(s1, d1, l1, picks1, v)
+        assert (e1 == 0).all()
+        want = np.tile(o.fill_mask(s1, d1, l1, v), (reps, 1))
+        logits = bf16_logits(rng, B, V)
+        lg[:, :V] = torch.from_numpy(logits.view(np.int16)).to(dev)
+        m.fill_(0x55555555)
+        toks = torch.from_numpy(picks).to(dev)
+        if step < 3:
+            lib.advance_fill_apply_mask(toks, m, lg.view(torch.bfloat16)[:, :V], one_kernel=True)
+            assert (lg[:, :V].cpu().numpy().view(np.uint16) == masked(logits, want)).all(), step
+        else:
+            out = torch.full((B,), -7, dtype=torch.int32, device=dev)
+            lib.advance_fill_argmax(toks, m, lg.view(torch.bfloat16)[:, :V], out, one_kernel=True)
+            assert (lg[:, :V].cpu().numpy().view(np.uint16) == logits).all()
+            assert (out.cpu().numpy() == oracle_masked_argmax(logits, want, V)).all()
+        assert (err.cpu().numpy() == 0).all() and (st.cpu().numpy() == np.tile(s1, reps)).all()
+        assert (ln.cpu().numpy() == np.tile(l1, reps)).all()
+        assert (m.cpu().numpy().view(np.uint32) == want).all(), step
+        assert int(lg[:, V:].abs().sum().item()) == 0
 
 
 def test_vocabulary_larger_than_the_lds_bitmap_takes_the_walk_path():
