@@ -413,7 +413,8 @@ def main(argv=None):
 
     # =========================== headline: the step, then the dominant kernel ===========================
     step_kind = {"two-call": "fill+apply", "fused": "fused", "advance-fill": "advance-fill", "one-call": "one-call"}[args.step]
-    if step_kind == "one-call" and not lib.step_is_one_kernel(logits[0]):
+    step_launches = lib.step_kernel_launches(logits[0]) if step_kind == "one-call" else 0
+    if step_kind == "one-call" and step_launches == 0:
         # outside the batch sizes (or vocabulary) of the one kernel the call is pre3_advance_fill_mask + pre3_apply_mask:
         # time and label those
         step_kind = "advance-fill"
@@ -422,7 +423,9 @@ def main(argv=None):
                  "advance-fill": "pre3_apply_mask + pre3_advance_fill_mask (advance and next mask in one launch, "
                                  "slot reuse on EOS)",
                  "one-call": "pre3_advance_fill_apply_mask (advance, next mask and masked logits in one launch, "
-                             "slot reuse on EOS)"}
+                             "slot reuse on EOS)" if step_launches <= 1 else
+                             f"pre3_advance_fill_apply_mask (advance, next mask and masked logits in one kernel, {step_launches} "
+                             "launches on equal shares of the batch, slot reuse on EOS)"}
     step_us = None
     if args.eager:
         step_us, t_step = eager_pass(step_kind)
@@ -462,7 +465,8 @@ def main(argv=None):
     # the logits-masking kernel dominates: it reads and writes the bf16 logits (4 B/pair) and reads the mask
     if step_kind == "one-call":
         # the one kernel of the step reads and writes the logits (4 B/pair) and writes the mask (one bit per pair)
-        dom_name, dom_bytes, dom_us = "advance_fill_apply_kernel", APPLY_BYTES_PER_PAIR * pairs, apply_us
+        # (a batch beyond one sequence per compute unit goes as several launches of equal shares: the figures are per launch)
+        dom_name, dom_bytes, dom_us = "advance_fill_apply_kernel", APPLY_BYTES_PER_PAIR * pairs / step_launches, apply_us / step_launches
         dom_timing = ("HIP events around every launch of an eager pass over the timed steps" if args.eager else
                       "inside the K timed steps replayed as one HIP graph: device clock stamps (one-thread kernels) before and "
                       "after every launch, minus the cost of a stamp")
@@ -493,6 +497,7 @@ def main(argv=None):
         out["in_step_kernel_us"] = in_step
     if step_kind == "one-call":
         out["apply_mask_alone_us"] = apply_alone_us
+        out["roofline"]["launches_per_step"] = step_launches
 
     # ---- CPU baseline: the oracle's fill + apply on the first steps of the same workload
     def cpu_baseline():
@@ -794,7 +799,7 @@ def main(argv=None):
         return {"step": "pre3_apply_mask_argmax + pre3_advance_fill_mask, K steps in one HIP graph, tokens chosen on the device",
                 "one_call_step": "pre3_advance_fill_argmax (one launch per step where the batch size allows), K steps in one HIP graph",
                 "one_call_us_per_step": one_call_us, "one_call_tokens_per_s": pairs / (one_call_us * 1e-6),
-                "one_call_is_one_kernel": lib.step_is_one_kernel(logits[0]),
+                "one_call_kernel_launches": lib.step_kernel_launches(logits[0]),
                 "us_per_step": step_us_g, "tokens_per_s": pairs / (step_us_g * 1e-6),
                 "argmax_launch_us": argmax_us, "argmax_algorithmic_bytes": nbytes,
                 "argmax_achieved_GBs": nbytes / (argmax_us * 1e-6) / 1e9,

@@ -179,8 +179,8 @@ int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batc
  * back from memory (Sec. 1: mask computation and masking belong to the same decode step).
  * Results are exactly those of the two calls in sequence: bitmask as pre3_fill_mask writes it,
  * logits (device, [batch, >= n_tokens], row_stride elements between rows) as pre3_apply_mask
- * leaves them.  A batch between a quarter of the GPU's compute units and all of them, no larger
- * than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
+ * leaves them.  A batch between a quarter of the GPU's compute units and four times their number,
+ * no larger than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
  * runs through that kernel without the advance: each sequence's logits are fetched while its
  * mask row is looked up.  Errors: BADARG. */
 int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
@@ -237,11 +237,14 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
  * The step can run as ONE kernel in which every sequence's logits are fetched while its token is
  * still being walked.  That form needs: logits aligned to 16 bytes, row_stride a multiple of 8, at
  * most 207,360 tokens (a row has to fit the registers of one compute unit), token-level edges in
- * use, and the mask row and -- with cycle-aware stacks -- the stack within the kernel's LDS.  It holds one sequence's logits in the registers of one compute
- * unit, so it pays when the batch is between a quarter of the GPU's compute units and all of them
- * (64..256 sequences on 256 units: 23.9 against 30.5 us per step at 256 x 128,256); the call chooses
- * it for such batches and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks for the one kernel
- * at any batch size where the conditions above hold (the call is still the two calls where not).
+ * use, and the mask row and -- with cycle-aware stacks -- the stack within the kernel's LDS.
+ * It holds one sequence's logits in the registers of one compute unit; a batch larger than the
+ * number of compute units goes as several launches of that kernel, each an equal share of the
+ * batch of at most one sequence per unit.  It pays when the batch is between a quarter of the
+ * GPU's compute units and four times their number (64..1,024 sequences on 256 units: 23.5 against
+ * 30.7 us per step at 256 x 128,256, 47.2 against 51.6 us at 512); the call chooses it for such
+ * batches and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks for the one kernel at any
+ * batch size where the conditions above hold (the call is still the two calls where not).
  * flags: PRE3_ADVANCE_RESTART_ON_EOS as for pre3_advance_fill_mask, PRE3_STEP_ONE_KERNEL.
  * Errors: BADARG (nothing bound, null pointer, unknown flag, row_stride < n_tokens, logits not
  * 2-byte aligned), HIP. */
@@ -263,8 +266,9 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
 int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, const uint16_t *logits_bf16,
                              int64_t row_stride, int32_t *out_tokens, int32_t flags, pre3_stream stream);
 
-/* Which form pre3_advance_fill_apply_mask takes for the bound batch and these logits: 1 = the one
- * kernel, 0 = the two calls; BADARG if nothing is bound.  pre3_advance_fill_argmax takes the same
+/* Which form pre3_advance_fill_apply_mask takes for the bound batch and these logits: 0 = the two
+ * calls, n >= 1 = the one kernel, launched n times on equal shares of the batch (n = 1 up to one
+ * sequence per compute unit); BADARG if nothing is bound.  pre3_advance_fill_argmax takes the same
  * form for vocabularies of at most 153,600 tokens.  Host call, launches nothing. */
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags);
 

@@ -357,12 +357,17 @@ class Pre3:
                                                        (ADVANCE_RESTART_ON_EOS if restart_on_eos else 0) |
                                                        (STEP_ONE_KERNEL if one_kernel else 0), _stream_ptr(stream)))
 
-    def step_is_one_kernel(self, logits, one_kernel=False):
-        """Whether advance_fill_apply_mask runs as one kernel for the bound batch and these logits."""
+    def step_kernel_launches(self, logits, one_kernel=False):
+        """0 if advance_fill_apply_mask is two calls for the bound batch and these logits, else the number of launches
+        of its one kernel (1 up to one sequence per compute unit, equal shares of the batch beyond)."""
         rc = self._lib.pre3_step_is_one_kernel(self._h, _dev(logits, "u16"), logits.stride(0), STEP_ONE_KERNEL if one_kernel else 0)
         if rc < 0:
             raise Pre3Error(rc, "step_is_one_kernel")
-        return bool(rc)
+        return rc
+
+    def step_is_one_kernel(self, logits, one_kernel=False):
+        """Whether advance_fill_apply_mask runs as one kernel for the bound batch and these logits."""
+        return self.step_kernel_launches(logits, one_kernel) > 0
 
     def apply_mask_argmax(self, logits, bitmask, out_tokens, stream=None):
         """out_tokens[b] = id of the largest allowed logit of row b (bound batch); the logits are only read."""

@@ -317,6 +317,14 @@ int upload_tables(pre3_handle *h) {
 
 bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 
+// Batch sizes at which the one-kernel step pays.  It keeps a sequence's logits in the registers of one compute
+// unit while the token is walked: below a quarter of the units too much of the chip idles, and a batch larger
+// than the chip goes as equal launches of at most one row per unit, whose gain over the two launches shrinks
+// with every further one (10 % at 320 rows on 256 units, 8 % at 512, 3 % at 1,024, none at 2,048).
+bool step_kernel_batch(const pre3_handle *h, int batch) {
+    return batch * 4 >= h->n_compute_units && batch <= 4 * h->n_compute_units;
+}
+
 // The token-level edges for pre3_advance: only their stack-effect records are used there.
 DevTokenEdges effect_edges(const pre3_handle *h) { return h->use_edges ? h->dev_edges : DevTokenEdges{}; }
 
@@ -492,10 +500,10 @@ int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stac
     const bool fused = h->use_edges && reinterpret_cast<uintptr_t>(logits) % 16 == 0 && row_stride % 8 == 0;
     // A batch that suits the one-launch step kernel (a row of logits per compute unit, fetched while the mask is
     // looked up) runs through it, without the advance; its walks spill into the workspace of the bound batch.
-    if (fused && h->af_walk_spill && stacks.batch <= h->b_stacks.batch && stacks.batch * 4 >= h->n_compute_units &&
-        stacks.batch <= h->n_compute_units && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, stacks.cap, false, false)) {
+    if (fused && h->af_walk_spill && stacks.batch <= h->b_stacks.batch && step_kernel_batch(h, stacks.batch) &&
+        advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, stacks.cap, false, false)) {
         hipError_t e = launch_fill_apply_rows(h->dev, h->dev_edges, states, stacks.data, stacks.len, stacks.cap, stacks.batch,
-                                              bitmask, h->af_walk_spill, logits, row_stride, s);
+                                              bitmask, h->af_walk_spill, logits, row_stride, h->n_compute_units, s);
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch fill_apply_mask");
     }
     if (fused) {
@@ -583,12 +591,11 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
 }
 
 namespace {
-// The one kernel keeps a sequence's logits in the registers of one compute unit: it pays while the batch
-// fills a good part of the chip and no compute unit has to take a second sequence.
+// Whether the step call takes its one-kernel form: asked for or a suitable batch size, and the kernel's conditions.
 bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags, bool greedy) {
     const int batch = h->b_stacks.batch;
     const bool cycles = h->compact && h->T.n_cycles > 0;
-    const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || (batch * 4 >= h->n_compute_units && batch <= h->n_compute_units);
+    const bool wanted = (flags & PRE3_STEP_ONE_KERNEL) || step_kernel_batch(h, batch);
     return wanted && h->use_edges && reinterpret_cast<uintptr_t>(logits_bf16) % 16 == 0 && row_stride % 8 == 0 &&
            row_stride >= h->V.n_tokens && advance_fill_apply_fits(h->V.n_tokens, h->V.n_words, h->b_stacks.cap, cycles, greedy);
 }
@@ -596,7 +603,8 @@ bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, in
 
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
     if (!usable(h) || (!h->b_states && !h->bound_empty)) return PRE3_E_BADARG;
-    return !h->bound_empty && step_takes_one_kernel(h, logits_bf16, row_stride, flags, false) ? 1 : 0;
+    if (h->bound_empty || !step_takes_one_kernel(h, logits_bf16, row_stride, flags, false)) return 0;
+    return (h->b_stacks.batch + h->n_compute_units - 1) / h->n_compute_units;      // launches of equal shares
 }
 
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
@@ -615,7 +623,7 @@ int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t
                                                  h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
                                                  h->af_walk_spill, cycles ? h->cycle_head : nullptr,
                                                  cycles ? h->cycle_pool : nullptr, logits_bf16, row_stride, nullptr,
-                                                 static_cast<hipStream_t>(stream));
+                                                 h->n_compute_units, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_apply_mask");
     }
     const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags & PRE3_ADVANCE_RESTART_ON_EOS, stream);
@@ -642,7 +650,7 @@ int pre3_advance_fill_argmax(pre3_handle *h, const int32_t *tokens, uint32_t *bi
                                                  h->b_stacks.cap, h->b_stacks.batch, h->b_err, bitmask, restart, h->adv_scratch,
                                                  h->af_walk_spill, cycles ? h->cycle_head : nullptr,
                                                  cycles ? h->cycle_pool : nullptr, const_cast<uint16_t *>(logits_bf16), row_stride,
-                                                 out_tokens, static_cast<hipStream_t>(stream));
+                                                 out_tokens, h->n_compute_units, static_cast<hipStream_t>(stream));
         return e == hipSuccess ? PRE3_OK : hip_fail(h, e, "launch advance_fill_argmax");
     }
     const int rc = pre3_advance_fill_mask(h, tokens, bitmask, flags & PRE3_ADVANCE_RESTART_ON_EOS, stream);

@@ -65,17 +65,19 @@ bool advance_fill_fits_compact(int n_words, int cap);   // row bitmap + staged s
 // aligned to 16 bytes and a row stride that is a multiple of 8 and at least the vocabulary size.
 // out_tokens null: the logits are masked in place; else they are only read and out_tokens[b] becomes
 // the arg max of the allowed logits of row b (the greedy step).
+// rows_per_launch: a batch of more rows goes as several launches of equal shares of at most that many
+// (the number of compute units: a block fills one); 0: one launch.
 bool advance_fill_apply_fits(int n_tokens, int n_words, int cap, bool cycles, bool greedy);   // greedy: the arg-max form
 // The same kernel without the advance: mask rows of the stacks as they are, applied to the logits
 // (walk_spill: advance_fill_walk_spill_entries(batch, ...) entries; same conditions on the logits).
 hipError_t launch_fill_apply_rows(const DevTables &T, const DevTokenEdges &E, const int32_t *states, const int32_t *data,
                                   const int32_t *len, int cap, int batch, uint32_t *bitmask, int32_t *walk_spill,
-                                  uint16_t *logits, int64_t row_stride, hipStream_t stream);
+                                  uint16_t *logits, int64_t row_stride, int rows_per_launch, hipStream_t stream);
 hipError_t launch_advance_fill_apply(const DevTables &T, const DevTokenEdges &E, const int32_t *tokens, int32_t *states,
                                      int32_t *data, int32_t *len, int cap, int batch, int32_t *err, uint32_t *bitmask,
                                      int restart_on_eos, int32_t *adv_scratch, int32_t *walk_spill,
                                      const int32_t *cycle_head, const int32_t *cycle_pool, uint16_t *logits,
-                                     int64_t row_stride, int32_t *out_tokens, hipStream_t stream);
+                                     int64_t row_stride, int32_t *out_tokens, int rows_per_launch, hipStream_t stream);
 hipError_t launch_jump_forward(const DevTables &T, int32_t *states, int32_t *data, int32_t *len, int cap, int batch,
                                uint8_t *out_bytes, int32_t *out_len, int max_bytes, int32_t *adv_scratch,
                                int32_t *lane_spill, const int32_t *cycle_head, const int32_t *cycle_pool,

@@ -112,7 +112,7 @@ def replay(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, check_app
 
 
 def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step=2, log=print, step_call_every=0,
-                        logits_pad=0, one_kernel=True, **lib_options):
+                        logits_pad=0, one_kernel=True, batch=None, **lib_options):
     """Same trajectory, driven through pre3_advance_fill_mask with slot reuse on EOS: after every
     call the device's states/len/live stack/err and the next mask must equal the oracle's
     advance followed by its fill (whole bitmask on `full_mask_steps`, sampled rows otherwise).
@@ -120,10 +120,14 @@ def replay_advance_fill(cfg_idx, steps=None, full_mask_steps=None, rows_per_step
     as one call) on fresh seeded logits whose rows are `logits_pad` elements longer than the vocabulary;
     on those steps the whole bitmask is checked, and all B * (V + pad) logit patterns against the
     oracle's apply_mask on the oracle's mask (the padding must come back untouched).  one_kernel: ask for
-    the one-kernel form whatever the batch size (False: the library chooses by the batch size)."""
+    the one-kernel form whatever the batch size (False: the library chooses by the batch size).
+    batch: another number of sequences than the configuration's."""
+    import dataclasses
     import torch
 
     cfg = configs.get(cfg_idx)
+    if batch is not None:
+        cfg = dataclasses.replace(cfg, batch=batch)
     v = cfg.vocab
     steps = cfg.steps if steps is None else steps
     o = Oracle(cfg.grammars, compact_cycles=cfg.compact)
