@@ -215,6 +215,9 @@ def main(argv=None):
         if kind == "one-call":         # advance by this step's tokens, next mask, and that mask on the next logits
             lib.advance_fill_apply_mask(tokens_d[s], mask_d, logits[(s + 1) % n_pool], restart_on_eos=True)
             return
+        if kind == "one-call-asked":   # the same call asked for its one-kernel form whatever the batch size
+            lib.advance_fill_apply_mask(tokens_d[s], mask_d, logits[(s + 1) % n_pool], restart_on_eos=True, one_kernel=True)
+            return
         if kind == "advance-fill":     # mask_d already holds this step's mask (from the previous call)
             apply_mask(logits[s % n_pool], mask_d, V)
             lib.advance_fill_mask(tokens_d[s], mask_d, restart_on_eos=True)
@@ -559,6 +562,11 @@ def main(argv=None):
         r["graph_ms_per_step"] = {step_text[step_kind]: t_step / K, step_text["fill+apply"]: t_two / K}
         if step_kind == "one-call" and not args.eager:
             r["graph_ms_per_step"][step_text["advance-fill"]] = timed_graph("advance-fill") / K
+        asked = lib.step_kernel_launches(logits[0], one_kernel=True)
+        if step_kind == "advance-fill" and args.step == "one-call" and asked > 0 and not args.eager:
+            # a batch beyond one sequence per compute unit: the one kernel only runs on request (PRE3_STEP_ONE_KERNEL)
+            r["graph_ms_per_step"][f"pre3_advance_fill_apply_mask asked for its one-kernel form ({asked} launches on equal shares "
+                                   "of the batch)"] = timed_graph("one-call-asked") / K
         return r
 
     def state_check():

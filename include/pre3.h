@@ -179,8 +179,8 @@ int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batc
  * back from memory (Sec. 1: mask computation and masking belong to the same decode step).
  * Results are exactly those of the two calls in sequence: bitmask as pre3_fill_mask writes it,
  * logits (device, [batch, >= n_tokens], row_stride elements between rows) as pre3_apply_mask
- * leaves them.  A batch between a quarter of the GPU's compute units and four times their number,
- * no larger than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
+ * leaves them.  A batch between a quarter of the GPU's compute units and all of them, no larger
+ * than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
  * runs through that kernel without the advance: each sequence's logits are fetched while its
  * mask row is looked up.  Errors: BADARG. */
 int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
@@ -240,11 +240,14 @@ int pre3_advance_fill_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitm
  * use, and the mask row and -- with cycle-aware stacks -- the stack within the kernel's LDS.
  * It holds one sequence's logits in the registers of one compute unit; a batch larger than the
  * number of compute units goes as several launches of that kernel, each an equal share of the
- * batch of at most one sequence per unit.  It pays when the batch is between a quarter of the
- * GPU's compute units and four times their number (64..1,024 sequences on 256 units: 23.5 against
- * 30.7 us per step at 256 x 128,256, 47.2 against 51.6 us at 512); the call chooses it for such
- * batches and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks for the one kernel at any
- * batch size where the conditions above hold (the call is still the two calls where not).
+ * batch of at most one sequence per unit.  The call chooses that form when the batch is between a
+ * quarter of the GPU's compute units and all of them (64..256 sequences on 256 units: 23.5 against
+ * 30.7 us per step at 256 x 128,256) and is the two calls otherwise.  PRE3_STEP_ONE_KERNEL asks
+ * for the one kernel at any batch size where the conditions above hold (the call is still the two
+ * calls where not): on larger batches it wins where the masks leave most lines of the logits to
+ * be read (JSON, 512 x 128,256: 47.2 against 51.6 us) and loses where they are sparse (a fixed
+ * schema, 512 x 152,064: 55.4 against 53.7 us), since it fetches a row before its mask is known
+ * and pre3_apply_mask does not read what is masked as a whole.
  * flags: PRE3_ADVANCE_RESTART_ON_EOS as for pre3_advance_fill_mask, PRE3_STEP_ONE_KERNEL.
  * Errors: BADARG (nothing bound, null pointer, unknown flag, row_stride < n_tokens, logits not
  * 2-byte aligned), HIP. */

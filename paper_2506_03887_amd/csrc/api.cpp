@@ -317,12 +317,15 @@ int upload_tables(pre3_handle *h) {
 
 bool usable(const pre3_handle *h) { return h && h->compiled && !h->host_only; }
 
-// Batch sizes at which the one-kernel step pays.  It keeps a sequence's logits in the registers of one compute
-// unit while the token is walked: below a quarter of the units too much of the chip idles, and a batch larger
-// than the chip goes as equal launches of at most one row per unit, whose gain over the two launches shrinks
-// with every further one (10 % at 320 rows on 256 units, 8 % at 512, 3 % at 1,024, none at 2,048).
+// Batch sizes at which the one-kernel step is chosen unasked.  It keeps a sequence's logits in the registers of one
+// compute unit while the token is walked: below a quarter of the units too much of the chip idles.  A batch larger
+// than the chip goes as equal launches of at most one row per unit; against the two launches that wins where most
+// of the logits have to be read anyway (JSON at 128,256 tokens: 10 % at 320 rows on 256 units, 8 % at 512, 3 % at
+// 1,024, none at 2,048) and loses where the masks are sparse (a fixed schema at 512 x 152,064: 55.4 against 53.7 us),
+// because the masking kernel does not read lines that are masked as a whole and this kernel fetches the row before
+// it knows the mask.  The library cannot tell which it will be, so beyond the chip the caller asks for it.
 bool step_kernel_batch(const pre3_handle *h, int batch) {
-    return batch * 4 >= h->n_compute_units && batch <= 4 * h->n_compute_units;
+    return batch * 4 >= h->n_compute_units && batch <= h->n_compute_units;
 }
 
 // The token-level edges for pre3_advance: only their stack-effect records are used there.

@@ -314,14 +314,14 @@ def _special_rows_under_a_mask(rng, B, V, mask_h):
 @pytest.mark.parametrize("cfg_idx,steps,pad,one_kernel,batch", [
     (1, 32, 7, True, None), (1, 32, 0, True, None), (2, 120, 0, True, None), (2, 40, 16, True, None), (3, 12, 0, False, None),
     (5, 8, 0, True, None), (6, 8, 0, True, None), (7, 10, 0, True, None), (4, 4, 0, True, None), (4, 3, 0, False, None),
-    (2, 30, 0, True, 333), (7, 6, 0, False, 300)])
+    (2, 30, 0, True, 333), (7, 6, 0, True, 300)])
 def test_greedy_decode_through_the_one_call_step_in_lockstep_with_the_oracle(cfg_idx, steps, pad, one_kernel, batch):
     """pre3_advance_fill_argmax (advance, next mask and next greedy token in one call, the token buffer updated in
     place) against the oracle's advance, fill and arg max: tokens, states, stacks, err and the whole mask at every
     step, the logits untouched.  The first rows of every step's logits hold the value cases of _special_rows_under_a_mask.
     Config 1 has a ragged vocabulary (partial last group; without padding its rows are misaligned and the call
-    takes its two-call form); config 4 at 512 sequences runs the one kernel in two launches, asked for or not; config
-    7 has cycle-aware stacks; 333 and 300 sequences go as launches of 167 + 166 and 150 + 150."""
+    takes its two-call form); config 4 at 512 sequences runs the one kernel, in two launches, only because it is asked
+    for; config 7 has cycle-aware stacks; 333 and 300 sequences go as launches of 167 + 166 and 150 + 150."""
     import dataclasses
     from paper_2506_03887_amd import Pre3
     torch, dev = _torch()

@@ -673,10 +673,9 @@ def test_hip_graph_of_the_one_kernel_step_replays_like_eager(greedy):
 
 
 def test_which_form_the_step_call_takes(deep_vocab):
-    """pre3_step_is_one_kernel: the one kernel for batches between a quarter of the compute units and four times
-    their number (64..1,024 on the 256 units of an MI355X; beyond one sequence per unit in several launches), at
-    any batch size when asked for, and never for logits whose rows are not 16-byte aligned or shorter than the
-    vocabulary."""
+    """pre3_step_is_one_kernel: the one kernel for batches between a quarter of the compute units and all of them
+    (64..256 on the 256 units of an MI355X), at any batch size when asked for (beyond one sequence per unit in
+    several launches), and never for logits whose rows are not 16-byte aligned or shorter than the vocabulary."""
     torch, dev = _torch()
     v = deep_vocab
     lib = _lib(G.JSON, v)
@@ -691,7 +690,7 @@ def test_which_form_the_step_call_takes(deep_vocab):
         lib.bind_state(states, data, torch.ones(B, dtype=torch.int32, device=dev), z32(B))
         flat = torch.zeros(B * stride + 16, dtype=torch.int16, device=dev)
         aligned = flat[: B * stride].view(B, stride)
-        assert lib.step_is_one_kernel(aligned) == (units // 4 <= B <= 4 * units), B
+        assert lib.step_is_one_kernel(aligned) == (units // 4 <= B <= units), B
         assert lib.step_kernel_launches(aligned, one_kernel=True) == (B + units - 1) // units, B
         assert not lib.step_is_one_kernel(flat[4: 4 + B * stride].view(B, stride), one_kernel=True)          # rows at 8 bytes
         if B > 1:

@@ -117,8 +117,7 @@ def test_whole_step_as_one_call_all_configs():
     assert replay_advance_fill(5, steps=64, step_call_every=8)["step_calls"] == 8
     assert replay_advance_fill(6, steps=48, step_call_every=8, full_mask_steps=[])["step_calls"] == 6
     assert replay_advance_fill(7, steps=64, step_call_every=4)["step_calls"] == 16
-    # the form the library chooses by itself: one kernel at 256 sequences, the two calls at 4, two launches of the
-    # one kernel at 512
+    # the form the library chooses by itself: one kernel at 256 sequences, the two calls at 4 and at 512
     assert replay_advance_fill(3, steps=16, step_call_every=4, one_kernel=False)["step_calls"] == 4
     assert replay_advance_fill(1, step_call_every=1, logits_pad=7, one_kernel=False)["step_calls"] == 32
     assert replay_advance_fill(4, steps=8, step_call_every=4, full_mask_steps=[], one_kernel=False)["step_calls"] == 2
@@ -128,12 +127,11 @@ def test_whole_step_on_batches_larger_than_the_chip():
     """A batch of more sequences than compute units goes through the one kernel in several launches of equal shares
     (333 sequences on 256 units: 167 + 166; 1,031: four launches of 207 and one of 203): every sequence
     must be advanced, masked and applied exactly once, whatever launch it falls in -- config 2 at 333 and 1,031
-    sequences and config 7 (cycle-aware stacks) at 300 ask for that form, config 3 at 300 gets it from the
-    library's own choice."""
+    sequences, config 7 (cycle-aware stacks) and config 3 at 300."""
     assert replay_advance_fill(2, steps=24, step_call_every=1, batch=333, logits_pad=8)["step_calls"] == 24
     assert replay_advance_fill(2, steps=8, step_call_every=1, batch=1031)["step_calls"] == 8
     assert replay_advance_fill(7, steps=16, step_call_every=2, batch=300, full_mask_steps=[])["step_calls"] == 8
-    assert replay_advance_fill(3, steps=12, step_call_every=3, batch=300, full_mask_steps=[], one_kernel=False)["step_calls"] == 4
+    assert replay_advance_fill(3, steps=12, step_call_every=3, batch=300, full_mask_steps=[])["step_calls"] == 4
 
 
 @pytest.mark.parametrize("fused", [False, True, "step", "step, 12 entries"])
