@@ -182,7 +182,8 @@ int pre3_apply_mask(uint16_t *logits_bf16, const uint32_t *bitmask, int32_t batc
  * leaves them.  A batch between a quarter of the GPU's compute units and all of them, no larger
  * than the bound batch, with logits as pre3_advance_fill_apply_mask's one-kernel form needs them,
  * runs through that kernel without the advance: each sequence's logits are fetched while its
- * mask row is looked up.  Errors: BADARG. */
+ * mask row is looked up; a batch of more sequences than compute units runs as the two calls,
+ * which are then the faster form.  Errors: BADARG. */
 int pre3_fill_apply_mask(pre3_handle *h, const int32_t *states, pre3_stacks stacks, uint32_t *bitmask,
                          uint16_t *logits_bf16, int64_t row_stride, pre3_stream stream);
 
