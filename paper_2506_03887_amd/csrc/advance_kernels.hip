@@ -1166,7 +1166,7 @@ static void launch_step_variant(int held, dim3 grid, size_t lds, hipStream_t str
 }
 
 // A block holds its row in the registers of a whole compute unit, so a grid of more blocks than units runs in
-// rounds whose blocks start as others end, out of step with each other (62.5 us per step at 512 x 128,256).  A
+// rounds whose blocks start as others end, out of step with each other (62.5 us per step at 512 x 152,064).  A
 // large batch goes as several launches of at most rows_per_launch rows instead, in equal shares (320 rows on
 // 256 units as 160 + 160: 32.2 us against 36.7 us as 256 + 64), each launch a front of its own (47.2 us at 512).
 static int step_rows_per_launch(int batch, int rows_per_launch) {
