@@ -481,11 +481,15 @@ def main(argv=None):
                       "K launches on rotating logits buffers replayed as one HIP graph between two HIP events, divided by K")
     else:
         fused_us, _ = eager_pass("fused")
-        dom_name, dom_bytes = "fill_mask_edges_kernel<true>", BYTES_PER_PAIR * pairs
+        # the call takes one of three forms by the batch size (the figures below are those of the whole call)
+        units = torch.cuda.get_device_properties(0).multi_processor_count
+        dom_name = ("advance_fill_apply_kernel (without the advance)" if lib.step_kernel_launches(logits[0]) == 1 else
+                    "fill_mask_edges_kernel<false> + apply_mask_vec8_kernel" if B > units else "fill_mask_edges_kernel<true>")
+        dom_bytes = BYTES_PER_PAIR * pairs
         dom_us = float(fused_us["fill_apply_mask"].mean())
         dom_timing = "HIP events around every launch of an eager pass over the timed steps"
     traffic, traffic_note = (None, "batch size differs from the profiled workload") if args.batch not in (0, configs.get(args.config).batch) \
-        else profile_traffic(dom_name.split("<")[0], cfg.name)
+        else profile_traffic(dom_name.split("<")[0].split(" ")[0], cfg.name) if step_kind != "fused" else (None, "no counters for this form")
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
