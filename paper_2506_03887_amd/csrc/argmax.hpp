@@ -54,6 +54,23 @@ __device__ __forceinline__ unsigned long long argmax_word(int order, int id) {
     return ((unsigned long long)(uint32_t)(order + 32768) << 32) | (0xFFFFFFFFu - (uint32_t)id);
 }
 
+// Half a mask byte -> the AND masks of two registers of packed 16-bit pairs (bit i of the nibble allows half i).
+// Sixteen entries of 8 bytes: lanes that read the same entry are served together and different entries lie in
+// different LDS banks, where a table of whole bytes (256 entries of 16 bytes) puts every sixteenth entry on the
+// same banks.  mask_nibble_table_init: by the first sixteen threads, followed by a barrier of the caller.
+__device__ __forceinline__ void mask_nibble_table_init(uint2 *table, int tid) {
+    if (tid < 16) {
+        uint32_t a[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) a[q] = (((tid >> (2 * q)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * q + 1)) & 1) ? 0xFFFF0000u : 0u);
+        table[tid] = make_uint2(a[0], a[1]);
+    }
+}
+__device__ __forceinline__ uint4 expand_mask_byte(const uint2 *table, uint32_t mask_byte) {
+    const uint2 lo = table[mask_byte & 15u], hi = table[mask_byte >> 4];
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+
 constexpr int kArgBlock = 1024;
 
 __device__ __forceinline__ unsigned long long argmax_block_max(unsigned long long mine, unsigned long long *s_part, int tid) {

@@ -37,18 +37,13 @@ __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
     const uint16_t *__restrict__ logits, const uint32_t *__restrict__ bitmask, int vocab, int64_t row_stride,
     int n_words, int groups_per_seg, int vec_ok, unsigned long long *__restrict__ partial, int32_t *__restrict__ out) {
     __shared__ unsigned long long s_part[kArgBlock / 64 + 1];
-    __shared__ uint4 s_expand[256];                     // mask byte -> AND masks of the group's four registers
+    __shared__ uint2 s_expand[16];                      // half a mask byte -> AND masks of two of the group's registers
     const int b = blockIdx.x, seg = blockIdx.y, n_seg = gridDim.y, tid = threadIdx.x;
     const int groups = (vocab + 7) >> 3;
     const int g_lo = seg * groups_per_seg, g_hi = min(groups, g_lo + groups_per_seg);
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
-    if (tid < 256) {
-        uint32_t a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
-        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
-    }
+    mask_nibble_table_init(s_expand, tid);
     int best = kOrderNegInf - 1, best_g = -1;           // only a valid value (or a positive NaN pattern) beats the start
     uint4 best_x = make_uint4(0, 0, 0, 0);
     uint32_t best_m = 0u;
@@ -83,7 +78,7 @@ __global__ __launch_bounds__(kArgBlock) void masked_argmax_kernel(
                 v[u] = make_uint4(x[0], x[1], x[2], x[3]);
                 if (mu == 0u) continue;
             }
-            const uint4 allow = s_expand[mu];
+            const uint4 allow = expand_mask_byte(s_expand, mu);
             const uint32_t k01 = packed_max_s16(bf16_order_pair(v[u].x, allow.x), bf16_order_pair(v[u].y, allow.y));
             const uint32_t k23 = packed_max_s16(bf16_order_pair(v[u].z, allow.z), bf16_order_pair(v[u].w, allow.w));
             const uint32_t k = packed_max_s16(k01, k23);
@@ -300,16 +295,11 @@ __device__ __forceinline__ void masked_topk_chunked(
     __shared__ int s_nz[kWaves];
     __shared__ uint32_t s_wbound[kWaves];
     __shared__ int s_n[kWaves];
-    __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
+    __shared__ uint2 s_expand[16];                            // half a mask byte -> AND masks of two of the group's registers
     __shared__ unsigned long long s_short[kBlock];        // the few words left at the end, one per thread
     __shared__ int s_total;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 256) {
-        uint32_t a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
-        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
-    }
+    mask_nibble_table_init(s_expand, tid);
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
     const int n_mask_bytes = n_words * 4;
@@ -380,7 +370,7 @@ __device__ __forceinline__ void masked_topk_chunked(
         uint32_t best2 = 0u;
 #pragma unroll
         for (int g = 0; g < kTopkPerThread / 8; ++g) {
-            const uint4 allow = s_expand[m[g]];
+            const uint4 allow = expand_mask_byte(s_expand, m[g]);
             const uint32_t x[4] = {v[g].x, v[g].y, v[g].z, v[g].w}, a[4] = {allow.x, allow.y, allow.z, allow.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -674,20 +664,15 @@ __global__ __launch_bounds__(kTopkBlockWide) __attribute__((amdgpu_waves_per_eu(
     int n_words, int k, unsigned long long *__restrict__ workspace, int32_t *__restrict__ out_ids,
     uint16_t *__restrict__ out_vals) {
     constexpr int kBlock = kTopkBlockWide, kWaves = kBlock / 64, kG = kTopkRowGroups;
-    __shared__ uint4 s_expand[256];                           // mask byte -> AND masks of the group's four registers
+    __shared__ uint2 s_expand[16];                            // half a mask byte -> AND masks of two of the group's registers
     __shared__ unsigned long long s_cand[kTopkRowList];
     __shared__ int s_rank[kTopkRowList];
     __shared__ int s_nz[kWaves];
     __shared__ uint32_t s_wbound[kWaves];
     __shared__ int s_count;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 256) {
-        uint32_t a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = (((tid >> (2 * j)) & 1) ? 0x0000FFFFu : 0u) | (((tid >> (2 * j + 1)) & 1) ? 0xFFFF0000u : 0u);
-        s_expand[tid] = make_uint4(a[0], a[1], a[2], a[3]);
-    }
-    s_rank[tid] = 0;
+    mask_nibble_table_init(s_expand, tid);
+    if (tid < kTopkRowList) s_rank[tid] = 0;                  // (the list has fewer entries than the block has threads)
     if (tid == 0) s_count = 0;
     const uint8_t *mrow = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * n_words);
     const uint16_t *lrow = logits + (size_t)b * row_stride;
@@ -711,7 +696,7 @@ __global__ __launch_bounds__(kTopkBlockWide) __attribute__((amdgpu_waves_per_eu(
     uint32_t best2 = 0u;
 #pragma unroll
     for (int u = 0; u < kG; ++u) {
-        const uint4 allow = s_expand[m[u]];
+        const uint4 allow = expand_mask_byte(s_expand, m[u]);
         const uint32_t x[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, a[4] = {allow.x, allow.y, allow.z, allow.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) kp[u * 4 + j] = bf16_key_pair(x[j]) & a[j];
