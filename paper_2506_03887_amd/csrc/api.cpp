@@ -610,7 +610,10 @@ bool step_takes_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, in
 int32_t pre3_step_is_one_kernel(const pre3_handle *h, const uint16_t *logits_bf16, int64_t row_stride, int32_t flags) {
     if (!usable(h) || (!h->b_states && !h->bound_empty)) return PRE3_E_BADARG;
     if (h->bound_empty || !step_takes_one_kernel(h, logits_bf16, row_stride, flags, false)) return 0;
-    return (h->b_stacks.batch + h->n_compute_units - 1) / h->n_compute_units;      // launches of equal shares
+    // launches of equal shares, counted as the launcher deals them out
+    const int batch = h->b_stacks.batch, most = (batch + h->n_compute_units - 1) / h->n_compute_units;
+    const int share = (batch + most - 1) / most;
+    return (batch + share - 1) / share;
 }
 
 int pre3_advance_fill_apply_mask(pre3_handle *h, const int32_t *tokens, uint32_t *bitmask, uint16_t *logits_bf16,
